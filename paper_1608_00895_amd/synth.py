@@ -1,0 +1,119 @@
+"""Seeded synthetic inputs for the LSTM / BLSTM hot path.
+
+This module only draws random numbers and shapes them; it contains none of
+the LSTM arithmetic.  It is the one module that both the CPU oracle's tests
+and the HIP path's tests / benchmark may share, so that both sides see the
+same arrays.
+
+The workloads stand in for the speech features the paper trains on
+(Sec. 6: ~40-dimensional acoustic frames, utterances of several hundred
+frames, zero-padded into time-major batches): x ~ N(0,1) per feature,
+uniform weights, sequence lengths uniform in a range, frames past a
+sequence's length set to zero.
+
+Draw order (one numpy Philox stream per workload, seeded by ``seed``):
+seq_lens, x, then for every layer and direction (forward first) W, R, b,
+then the loss weights G of the top layer.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional, Tuple
+
+import numpy as np
+
+
+@dataclass
+class Workload:
+    name: str
+    L: int                 # stacked layers
+    T: int                 # padded length (= max seq_lens)
+    B: int                 # sequences per minibatch
+    D: int                 # input feature width of layer 0
+    H: int                 # units per direction
+    bidirectional: bool
+    operand_dtype: int     # 0: fp32 operands, 1: bf16 GEMM operands (fp32 accumulate / cell)
+    seq_lens: np.ndarray   # int32 [B]
+    x: np.ndarray          # float32 [T, B, D], zero past each sequence's length
+    # params[l][d] = (W [D_l, 4H], R [H, 4H], b [4H]) float32; d = 0 forward, 1 backward
+    params: List[List[Tuple[np.ndarray, np.ndarray, np.ndarray]]] = field(default_factory=list)
+    G: Optional[np.ndarray] = None  # float32 [T, B, ndir*H]: loss = sum(y_top * G)
+
+    @property
+    def ndir(self) -> int:
+        return 2 if self.bidirectional else 1
+
+    @property
+    def frames(self) -> int:
+        return int(self.seq_lens.sum())
+
+
+def make_workload(name: str, *, L: int, B: int, D: int, H: int, len_lo: int, len_hi: int,
+                  wscale: float, seed: int, bidirectional: bool = True,
+                  operand_dtype: int = 0, loss: str = "random", T: Optional[int] = None,
+                  bias_scale: float = 0.0) -> Workload:
+    """Draw one workload.  Lengths are uniform integers in [len_lo, len_hi]
+    (both ends included); sequence 0 is forced to len_hi so that the padded
+    length T = len_hi is the same for every seed.  ``loss`` = "ones" gives
+    G = 1 (loss = sum of outputs), "random" gives G ~ N(0,1)."""
+    rng = np.random.Generator(np.random.Philox(seed))
+    seq_lens = rng.integers(len_lo, len_hi + 1, size=B).astype(np.int32)
+    if B > 0:
+        seq_lens[0] = len_hi
+    Tp = int(len_hi if T is None else T)
+    assert Tp >= len_hi
+    x = rng.standard_normal((Tp, B, D)).astype(np.float32)
+    tt = np.arange(Tp, dtype=np.int32)[:, None]
+    x *= (tt < seq_lens[None, :])[:, :, None]
+    ndir = 2 if bidirectional else 1
+    params = []
+    for l in range(L):
+        Dl = D if l == 0 else ndir * H
+        layer = []
+        for _d in range(ndir):
+            W = rng.uniform(-wscale, wscale, size=(Dl, 4 * H)).astype(np.float32)
+            R = rng.uniform(-wscale, wscale, size=(H, 4 * H)).astype(np.float32)
+            if bias_scale > 0.0:
+                b = rng.uniform(-bias_scale, bias_scale, size=(4 * H,)).astype(np.float32)
+            else:
+                b = np.zeros((4 * H,), dtype=np.float32)
+            layer.append((W, R, b))
+        params.append(layer)
+    if loss == "ones":
+        G = np.ones((Tp, B, ndir * H), dtype=np.float32)
+    else:
+        G = rng.standard_normal((Tp, B, ndir * H)).astype(np.float32)
+    return Workload(name=name, L=L, T=Tp, B=B, D=D, H=H, bidirectional=bidirectional,
+                    operand_dtype=operand_dtype, seq_lens=seq_lens, x=x, params=params, G=G)
+
+
+def config1() -> Workload:
+    """1-layer unidirectional LSTM, T=20, B=2, D=8, H=16, all lengths 20, loss = sum(y), seed 0."""
+    return make_workload("config1_lstm_T20_B2_D8_H16", L=1, B=2, D=8, H=16, len_lo=20, len_hi=20,
+                         wscale=0.1, seed=0, bidirectional=False, loss="ones")
+
+
+def config2() -> Workload:
+    """1-layer BLSTM, D=40, H=256 per direction, B=16, lengths uniform in [100, 500]."""
+    return make_workload("config2_blstm1x256_B16", L=1, B=16, D=40, H=256, len_lo=100, len_hi=500,
+                         wscale=0.08, seed=2)
+
+
+def config3() -> Workload:
+    """4-layer BLSTM, D=40, H=500 per direction, B=32, lengths uniform in [300, 1000] (headline)."""
+    return make_workload("config3_blstm4x500_B32", L=4, B=32, D=40, H=500, len_lo=300, len_hi=1000,
+                         wscale=0.05, seed=3)
+
+
+def config4() -> Workload:
+    """6-layer BLSTM, D=40, H=1000 per direction, B=64, lengths in [500, 1500], bf16 GEMM operands."""
+    return make_workload("config4_blstm6x1000_B64_bf16", L=6, B=64, D=40, H=1000, len_lo=500,
+                         len_hi=1500, wscale=0.03, seed=4, operand_dtype=1)
+
+
+def small_blstm(seed: int = 11, *, L: int = 2, B: int = 5, D: int = 12, H: int = 20,
+                len_lo: int = 3, len_hi: int = 37, wscale: float = 0.3,
+                bias_scale: float = 0.2, T: Optional[int] = None) -> Workload:
+    """A ragged multi-layer BLSTM small enough for the oracle to finish in well under a second."""
+    return make_workload(f"small_blstm_s{seed}", L=L, B=B, D=D, H=H, len_lo=len_lo, len_hi=len_hi,
+                         wscale=wscale, seed=seed, bias_scale=bias_scale, T=T)
