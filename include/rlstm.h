@@ -1,0 +1,224 @@
+/*
+ * rlstm.h - C ABI of the MI355X (gfx950) LSTM / deep BLSTM training kernels.
+ *
+ * The library implements the LSTM layer of RETURNN (arXiv 1608.00895) as the
+ * paper's Sec. 4.2 describes it: the non-recurrent part of the forward pass is
+ * one matrix product over all frames of the minibatch, the recurrent part runs
+ * through time with a fused gating step, back-propagation first runs back
+ * through time and then forms the weight and input gradients as whole-minibatch
+ * matrix products, and buffers are reused in place.  Tensors are time-major
+ * [time, batch, feature] with a per-(time, batch) validity mask (Sec. 5),
+ * given here as seq_lens[B]: frame t of sequence n is valid iff t < seq_lens[n].
+ * A layer has a direction (+1 scans t = 0..T-1, -1 scans t = T-1..0) and a
+ * bidirectional layer feeds [y_forward | y_backward] to the next layer (Fig. 1).
+ * Gradients are plain sums over frames and sequences (Sec. 4.3).
+ *
+ * Cell (the paper cites the LSTM without printing equations; this is the
+ * reading fixed for the whole library).  With a = b + x_t W + h_prev R, a 4H
+ * wide row whose column blocks are  i | f | o | g  in that order:
+ *     i = s(a_i)  f = s(a_f)  o = s(a_o)  g = tanh(a_g)     s(u) = 1/(1+exp(-u))
+ *     c~ = f*c_prev + i*g        h~ = o*tanh(c~)
+ *     valid frame:   (h, c) <- (h~, c~),  y_t = h~
+ *     invalid frame: (h, c) unchanged,    y_t = 0
+ * "prev" is the previously processed frame in the layer's direction; the state
+ * before the first processed frame is (h0, c0).  c[t] returns the carried cell
+ * state after frame t.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers (HIP, fp32 unless said otherwise,
+ *     16-byte aligned recommended) owned by the caller.  Descriptors are HOST
+ *     structs.  The library allocates and frees no device memory, never
+ *     synchronises the device and only enqueues work on the streams passed in
+ *     (a null stream handle is HIP's default stream).
+ *   - Inputs are read-only.  Outputs are overwritten, never accumulated into.
+ *   - workspace must hold rlstm_workspace_bytes() (resp. rblstm_workspace_bytes())
+ *     bytes; its contents need no initialisation and are undefined afterwards.
+ *     Calls that share a workspace must not overlap in time.
+ *   - Return value: 0 on success, a negative RLSTM_E* code otherwise; nothing
+ *     is enqueued when an argument check fails.  rlstm_strerror() names a code.
+ *   - seq_lens values are clamped on the device to [0, T].
+ *   - The recurrent kernels are persistent: all of their workgroups must be
+ *     resident at once, so they are launched cooperatively and the call fails
+ *     with RLSTM_ERESIDENT when the device cannot hold them.  Their
+ *     per-step device-wide wait is bounded; if it ever expires the kernel
+ *     stops stepping and sets a flag that rlstm_last_timeout() reports.
+ */
+#ifndef RLSTM_H
+#define RLSTM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#if defined(__GNUC__)
+#define RLSTM_API __attribute__((visibility("default")))
+#else
+#define RLSTM_API
+#endif
+
+#define RLSTM_OK          0
+#define RLSTM_ENULL      -1   /* a required pointer is null */
+#define RLSTM_EDIM       -2   /* a dimension is <= 0 or a leading dimension is too small */
+#define RLSTM_EMODE      -3   /* bad direction / operand_dtype / engine */
+#define RLSTM_ESIZE      -4   /* reserved */
+#define RLSTM_ERESIDENT  -5   /* persistent kernel cannot be made co-resident / shape unsupported by the engine */
+#define RLSTM_EHIP       -6   /* a HIP runtime call failed */
+
+#define RLSTM_ENGINE_AUTO        0  /* persistent kernels where the shape fits on chip, else stepwise */
+#define RLSTM_ENGINE_PERSISTENT  1  /* one launch runs all T steps; fails if the shape does not fit */
+#define RLSTM_ENGINE_STEPWISE    2  /* one launch per time step (plain kernels; any shape) */
+
+/* One LSTM layer, one direction.  Host struct, all int32. */
+typedef struct rlstm_desc {
+  int32_t T;              /* padded length (frames)                                   */
+  int32_t B;              /* sequences in the minibatch                               */
+  int32_t D;              /* input feature width                                      */
+  int32_t H;              /* units                                                    */
+  int32_t direction;      /* +1 or -1 (Fig. 1)                                        */
+  int32_t operand_dtype;  /* 0: fp32; 1: matrix-product operands rounded to bf16,
+                             fp32 accumulation, fp32 cell state and outputs          */
+  int32_t ldx;            /* row stride (floats) of x and dx, >= D; 0 means D         */
+  int32_t ldy;            /* row stride (floats) of y and dy, >= H; 0 means H         */
+  int32_t engine;         /* RLSTM_ENGINE_*                                           */
+} rlstm_desc;
+
+/* Deep bidirectional stack: L layers, each a forward and a backward LSTM of H
+ * units on the same input; layer 0 reads D features, layers >= 1 read 2H. */
+typedef struct rblstm_desc {
+  int32_t L, T, B, D, H;
+  int32_t operand_dtype;  /* as in rlstm_desc */
+  int32_t engine;         /* RLSTM_ENGINE_* */
+} rblstm_desc;
+
+/* Bytes of the opaque forward-to-backward buffer of lstm_fwd / lstm_bwd (it
+ * holds the activated gates [T,B,4H]); 0 if the descriptor is invalid. */
+RLSTM_API size_t rlstm_reserve_bytes(const rlstm_desc* desc);
+/* Bytes of scratch for lstm_fwd / lstm_bwd; 0 if the descriptor is invalid. */
+RLSTM_API size_t rlstm_workspace_bytes(const rlstm_desc* desc);
+/* Same for blstm_stack_fwd_bwd (reserve: per layer and direction the gate
+ * buffer [T,B,4H] and cell buffer [T,B,H], plus the hidden layers' outputs). */
+RLSTM_API size_t rblstm_reserve_bytes(const rblstm_desc* desc);
+RLSTM_API size_t rblstm_workspace_bytes(const rblstm_desc* desc);
+
+/*
+ * lstm_fwd - forward pass of one layer in one direction (Sec. 4.2: one matrix
+ * product x W for all T*B frames, then the recurrence with fused gating;
+ * Sec. 5 mask; Fig. 1 direction).
+ *   x   [T,B,ldx]  in     W [D,4H] in    R [H,4H] in    b [4H] in
+ *   h0, c0 [B,H]   in, may be null (= zeros)
+ *   seq_lens [B]   in, int32
+ *   y   [T,B,ldy]  out (only the first H floats of each row are written)
+ *   c   [T,B,H]    out, carried cell state after each frame
+ *   hT, cT [B,H]   out, may be null: state after the last processed frame
+ *   reserve        out, rlstm_reserve_bytes(): needed by lstm_bwd
+ */
+RLSTM_API int lstm_fwd(const rlstm_desc* desc, const float* x, const float* W, const float* R, const float* b,
+             const float* h0, const float* c0, const int32_t* seq_lens,
+             float* y, float* c, float* hT, float* cT,
+             void* reserve, void* workspace, void* hip_stream);
+
+/*
+ * lstm_bwd - back-propagation through time for the pass lstm_fwd recorded
+ * (Sec. 4.2: the recurrent part is propagated back through time first, then
+ * the gradients w.r.t. weights and inputs are whole-minibatch matrix
+ * products; Sec. 4.3: unscaled sums).
+ *   x, W, R, seq_lens, h0, c0  as given to lstm_fwd
+ *   y, c                       as written by lstm_fwd
+ *   reserve                    in/out: consumed (holds d loss / d a afterwards)
+ *   dy  [T,B,ldy]  in, gradient w.r.t. y (rows beyond a sequence's length are ignored)
+ *   dhT, dcT [B,H] in, may be null (= zeros): gradient w.r.t. hT, cT
+ *   dx  [T,B,ldx]  out, may be null (skipped); 0 at invalid frames
+ *   dW [D,4H], dR [H,4H], db [4H]  out
+ *   dh0, dc0 [B,H] out, may be null
+ */
+RLSTM_API int lstm_bwd(const rlstm_desc* desc, const float* x, const float* W, const float* R,
+             const int32_t* seq_lens, const float* h0, const float* c0,
+             const float* y, const float* c, void* reserve,
+             const float* dy, const float* dhT, const float* dcT,
+             float* dx, float* dW, float* dR, float* db, float* dh0, float* dc0,
+             void* workspace, void* hip_stream);
+
+/*
+ * blstm_stack_fwd_bwd - one training pass (forward, then backward) of an
+ * L-layer bidirectional LSTM stack with zero initial states (Fig. 1 stacking,
+ * Sec. 4.2 kernels).  The two directions of a layer run concurrently.
+ *   x [T,B,D] in;  seq_lens [B] in
+ *   params: HOST array of 6*L DEVICE pointers, for layer l and direction d
+ *           (0 forward, 1 backward): params[6l+3d+0] = W [D_l,4H],
+ *           +1 = R [H,4H], +2 = b [4H];  D_0 = D, D_l = 2H otherwise
+ *   dy_top [T,B,2H] in: gradient of the loss w.r.t. the top layer's output
+ *   y_top  [T,B,2H] out
+ *   grads:  HOST array of 6*L DEVICE pointers laid out like params (dW, dR, db), out
+ *   dx [T,B,D] out, may be null (the bottom layer's input gradient is skipped)
+ *   stream_a carries the dependent chain; stream_b, if not null and different,
+ *   is used to overlap independent weight-gradient products with the next
+ *   layer's pass back through time.  On return all work has been enqueued and
+ *   stream_a waits for everything placed on stream_b.
+ */
+RLSTM_API int blstm_stack_fwd_bwd(const rblstm_desc* desc, const float* x, const float* const* params,
+                        const int32_t* seq_lens, const float* dy_top,
+                        float* y_top, float* const* grads, float* dx,
+                        void* reserve, void* workspace, void* hip_stream_a, void* hip_stream_b);
+
+/* Forward half only of the stack (inference / parity of hidden layers):
+ * same arguments as above without gradients. */
+RLSTM_API int blstm_stack_fwd(const rblstm_desc* desc, const float* x, const float* const* params,
+                    const int32_t* seq_lens, float* y_top,
+                    void* reserve, void* workspace, void* hip_stream_a);
+
+/*
+ * rlstm_gemm_f32 - the whole-minibatch matrix product the layer is built on
+ * (Sec. 4.2: "a single matrix multiplication for the whole mini-batch"), exposed
+ * for measurement and testing:  C[M,N] = op(A) op(B) (+ bias[n] on every row).
+ *   trans_a == 0: A is [M,K] with row stride lda;  != 0: A is stored [K,M]
+ *   trans_b == 0: B is [K,N] with row stride ldb;  != 0: B is stored [N,K]
+ *   C [M,N] out, row stride ldc; bias [N] or null
+ *   splitk_ws: scratch of splitk_ws_bytes (may be null / 0): lets products with
+ *   K much larger than M, N split K into slices that are summed in a fixed order.
+ */
+RLSTM_API int rlstm_gemm_f32(int trans_a, int trans_b, int M, int N, int K,
+                   const float* A, int lda, const float* B, int ldb, float* C, int ldc,
+                   const float* bias, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream);
+
+/*
+ * Optional per-kernel timing for measurement (not part of the method).  While
+ * enabled, every kernel group the library enqueues is bracketed by a pair of
+ * HIP events on the stream it is launched on.  rlstm_profile_read() waits for
+ * the recorded events, writes up to max_entries entries (in launch order) and
+ * clears the record; it returns the number of entries recorded (which may
+ * exceed max_entries) or a negative code.  Not thread-safe.
+ *   kind: 0 input projection X W + b        1 recurrent forward pass (all T steps)
+ *         2 pass back through time          3 input gradient dZ W^T
+ *         4 weight gradient X^T dZ          5 recurrent weight gradient Hprev^T dZ
+ *   layer: stack layer (0 for the single-layer entry points); ndir: directions covered
+ */
+typedef struct rlstm_profile_entry {
+  int32_t kind, layer, ndir, reserved;
+  float ms;
+} rlstm_profile_entry;
+RLSTM_API int rlstm_profile_enable(int on);
+RLSTM_API int rlstm_profile_read(rlstm_profile_entry* out, int max_entries);
+
+/* Reads (with a blocking device-to-host copy) the timeout flag that the
+ * persistent kernels keep at the start of `workspace`: 0 = no bounded wait
+ * expired since the last call that used this workspace, 1 = one did and the
+ * results are invalid, negative = RLSTM_E* code.  Synchronises the device. */
+RLSTM_API int rlstm_last_timeout(const void* workspace);
+
+/* Which engine RLSTM_ENGINE_AUTO resolves to for this shape on the current
+ * device: RLSTM_ENGINE_PERSISTENT or RLSTM_ENGINE_STEPWISE (negative: error). */
+RLSTM_API int rlstm_resolve_engine(const rlstm_desc* desc);
+
+/* Static string for an RLSTM_* code. */
+RLSTM_API const char* rlstm_strerror(int code);
+
+/* Library version, "major.minor". */
+RLSTM_API const char* rlstm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RLSTM_H */

@@ -1,0 +1,215 @@
+"""Thin ctypes binding of librlstm.so: argument marshalling only.
+
+Every function has the name and argument order of its C entry point in
+include/rlstm.h.  Tensors are torch CUDA (ROCm) tensors used purely as device
+memory; streams are torch streams or None (the current stream).  Nothing is
+computed here, and there is no fallback: if the library is missing, loading
+raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librlstm.so")
+
+RLSTM_ENGINE_AUTO = 0
+RLSTM_ENGINE_PERSISTENT = 1
+RLSTM_ENGINE_STEPWISE = 2
+
+EXPORTS = [
+    "rlstm_reserve_bytes", "rlstm_workspace_bytes", "rblstm_reserve_bytes", "rblstm_workspace_bytes",
+    "lstm_fwd", "lstm_bwd", "blstm_stack_fwd_bwd", "blstm_stack_fwd",
+    "rlstm_gemm_f32", "rlstm_profile_enable", "rlstm_profile_read", "rlstm_last_timeout", "rlstm_resolve_engine", "rlstm_strerror", "rlstm_version",
+]
+
+
+class rlstm_desc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("T", "B", "D", "H", "direction", "operand_dtype", "ldx", "ldy", "engine")]
+
+
+class rblstm_desc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("L", "T", "B", "D", "H", "operand_dtype", "engine")]
+
+
+class rlstm_profile_entry(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("layer", ctypes.c_int32), ("ndir", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("ms", ctypes.c_float)]
+
+
+PROFILE_KINDS = {0: "input_projection", 1: "recurrent_forward", 2: "recurrent_backward",
+                 3: "input_gradient", 4: "weight_gradient", 5: "recurrent_weight_gradient"}
+
+
+class RlstmError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where} failed: {code} ({strerror(code)})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads librlstm.so (built in-tree by paper_1608_00895_amd/build.py)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python paper_1608_00895_amd/build.py` "
+                               "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, ip = ctypes.c_void_p, ctypes.c_int
+        for name in ("rlstm_reserve_bytes", "rlstm_workspace_bytes"):
+            getattr(L, name).restype = ctypes.c_size_t
+            getattr(L, name).argtypes = [ctypes.POINTER(rlstm_desc)]
+        for name in ("rblstm_reserve_bytes", "rblstm_workspace_bytes"):
+            getattr(L, name).restype = ctypes.c_size_t
+            getattr(L, name).argtypes = [ctypes.POINTER(rblstm_desc)]
+        L.lstm_fwd.restype = ip
+        L.lstm_fwd.argtypes = [ctypes.POINTER(rlstm_desc)] + [vp] * 14
+        L.lstm_bwd.restype = ip
+        L.lstm_bwd.argtypes = [ctypes.POINTER(rlstm_desc)] + [vp] * 20
+        L.blstm_stack_fwd_bwd.restype = ip
+        L.blstm_stack_fwd_bwd.argtypes = [ctypes.POINTER(rblstm_desc), vp, ctypes.POINTER(vp), vp, vp, vp,
+                                          ctypes.POINTER(vp), vp, vp, vp, vp, vp]
+        L.blstm_stack_fwd.restype = ip
+        L.blstm_stack_fwd.argtypes = [ctypes.POINTER(rblstm_desc), vp, ctypes.POINTER(vp), vp, vp, vp, vp, vp]
+        L.rlstm_gemm_f32.restype = ip
+        L.rlstm_gemm_f32.argtypes = [ip, ip, ip, ip, ip, vp, ip, vp, ip, vp, ip, vp, vp, ctypes.c_size_t, vp]
+        L.rlstm_profile_enable.restype = ip
+        L.rlstm_profile_enable.argtypes = [ip]
+        L.rlstm_profile_read.restype = ip
+        L.rlstm_profile_read.argtypes = [ctypes.POINTER(rlstm_profile_entry), ip]
+        L.rlstm_last_timeout.restype = ip
+        L.rlstm_last_timeout.argtypes = [vp]
+        L.rlstm_resolve_engine.restype = ip
+        L.rlstm_resolve_engine.argtypes = [ctypes.POINTER(rlstm_desc)]
+        L.rlstm_strerror.restype = ctypes.c_char_p
+        L.rlstm_strerror.argtypes = [ip]
+        L.rlstm_version.restype = ctypes.c_char_p
+        L.rlstm_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().rlstm_strerror(int(code)).decode()
+
+
+def version() -> str:
+    return lib().rlstm_version().decode()
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("librlstm takes device pointers: pass a tensor on the GPU")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(s) -> ctypes.c_void_p:
+    if s is None:
+        s = torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _ptr_array(ts: Sequence[torch.Tensor]):
+    arr = (ctypes.c_void_p * len(ts))()
+    for i, t in enumerate(ts):
+        if not t.is_cuda:
+            raise ValueError("librlstm takes device pointers: pass tensors on the GPU")
+        arr[i] = t.data_ptr()
+    return arr
+
+
+def rlstm_reserve_bytes(desc: rlstm_desc) -> int:
+    return int(lib().rlstm_reserve_bytes(ctypes.byref(desc)))
+
+
+def rlstm_workspace_bytes(desc: rlstm_desc) -> int:
+    return int(lib().rlstm_workspace_bytes(ctypes.byref(desc)))
+
+
+def rblstm_reserve_bytes(desc: rblstm_desc) -> int:
+    return int(lib().rblstm_reserve_bytes(ctypes.byref(desc)))
+
+
+def rblstm_workspace_bytes(desc: rblstm_desc) -> int:
+    return int(lib().rblstm_workspace_bytes(ctypes.byref(desc)))
+
+
+def rlstm_resolve_engine(desc: rlstm_desc) -> int:
+    return int(lib().rlstm_resolve_engine(ctypes.byref(desc)))
+
+
+def rlstm_last_timeout(workspace: torch.Tensor) -> int:
+    return int(lib().rlstm_last_timeout(_ptr(workspace)))
+
+
+def lstm_fwd(desc, x, W, R, b, h0, c0, seq_lens, y, c, hT, cT, reserve, workspace, stream=None, check=True) -> int:
+    rc = lib().lstm_fwd(ctypes.byref(desc), _ptr(x), _ptr(W), _ptr(R), _ptr(b), _ptr(h0), _ptr(c0), _ptr(seq_lens),
+                        _ptr(y), _ptr(c), _ptr(hT), _ptr(cT), _ptr(reserve), _ptr(workspace), _stream(stream))
+    if check and rc != 0:
+        raise RlstmError(rc, "lstm_fwd")
+    return rc
+
+
+def lstm_bwd(desc, x, W, R, seq_lens, h0, c0, y, c, reserve, dy, dhT, dcT, dx, dW, dR, db, dh0, dc0,
+             workspace, stream=None, check=True) -> int:
+    rc = lib().lstm_bwd(ctypes.byref(desc), _ptr(x), _ptr(W), _ptr(R), _ptr(seq_lens), _ptr(h0), _ptr(c0),
+                        _ptr(y), _ptr(c), _ptr(reserve), _ptr(dy), _ptr(dhT), _ptr(dcT),
+                        _ptr(dx), _ptr(dW), _ptr(dR), _ptr(db), _ptr(dh0), _ptr(dc0),
+                        _ptr(workspace), _stream(stream))
+    if check and rc != 0:
+        raise RlstmError(rc, "lstm_bwd")
+    return rc
+
+
+def blstm_stack_fwd_bwd(desc, x, params, seq_lens, dy_top, y_top, grads, dx, reserve, workspace,
+                        stream_a=None, stream_b=None, check=True) -> int:
+    """params / grads: flat sequences of 6*L tensors (layer-major, forward direction first: W, R, b)."""
+    pa, ga = _ptr_array(params), _ptr_array(grads)
+    sb = ctypes.c_void_p(stream_b.cuda_stream) if stream_b is not None else None
+    rc = lib().blstm_stack_fwd_bwd(ctypes.byref(desc), _ptr(x), pa, _ptr(seq_lens), _ptr(dy_top), _ptr(y_top),
+                                   ga, _ptr(dx), _ptr(reserve), _ptr(workspace), _stream(stream_a), sb)
+    if check and rc != 0:
+        raise RlstmError(rc, "blstm_stack_fwd_bwd")
+    return rc
+
+
+def blstm_stack_fwd(desc, x, params, seq_lens, y_top, reserve, workspace, stream_a=None, check=True) -> int:
+    pa = _ptr_array(params)
+    rc = lib().blstm_stack_fwd(ctypes.byref(desc), _ptr(x), pa, _ptr(seq_lens), _ptr(y_top),
+                               _ptr(reserve), _ptr(workspace), _stream(stream_a))
+    if check and rc != 0:
+        raise RlstmError(rc, "blstm_stack_fwd")
+    return rc
+
+
+def rlstm_gemm_f32(trans_a, trans_b, M, N, K, A, lda, B, ldb, C, ldc, bias=None, splitk_ws=None,
+                   stream=None, check=True) -> int:
+    nbytes = 0 if splitk_ws is None else splitk_ws.numel() * splitk_ws.element_size()
+    rc = lib().rlstm_gemm_f32(int(trans_a), int(trans_b), M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc,
+                              _ptr(bias), _ptr(splitk_ws), nbytes, _stream(stream))
+    if check and rc != 0:
+        raise RlstmError(rc, "rlstm_gemm_f32")
+    return rc
+
+
+def rlstm_profile_enable(on: bool) -> int:
+    return int(lib().rlstm_profile_enable(1 if on else 0))
+
+
+def rlstm_profile_read(max_entries: int = 4096):
+    """Returns the recorded (kind, layer, ndir, ms) entries in launch order and clears the record."""
+    buf = (rlstm_profile_entry * max_entries)()
+    n = int(lib().rlstm_profile_read(buf, max_entries))
+    if n < 0:
+        raise RlstmError(n, "rlstm_profile_read")
+    return [(buf[i].kind, buf[i].layer, buf[i].ndir, float(buf[i].ms)) for i in range(min(n, max_entries))]

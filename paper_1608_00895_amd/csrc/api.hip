@@ -1,0 +1,465 @@
+// C ABI of librlstm (declared in include/rlstm.h): argument checks, the
+// layout of the reserve / workspace buffers, and the order in which the
+// matrix products and the recurrent passes of one layer, and of the stacked
+// bidirectional network, are enqueued (Sec. 4.2 and Fig. 1 of the RETURNN paper).
+#include "../../include/rlstm.h"
+#include "rlstm_internal.h"
+
+#include <vector>
+
+using namespace rlstm;
+
+namespace {
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+constexpr size_t kFlagBytes = 256;
+
+int check_desc(const rlstm_desc* d) {
+  if (!d) return RLSTM_ENULL;
+  if (d->T <= 0 || d->B <= 0 || d->D <= 0 || d->H <= 0) return RLSTM_EDIM;
+  if (d->ldx != 0 && d->ldx < d->D) return RLSTM_EDIM;
+  if (d->ldy != 0 && d->ldy < d->H) return RLSTM_EDIM;
+  if ((long long)d->T * d->B > (1ll << 30) || (long long)d->H * 4 > (1ll << 24)) return RLSTM_EDIM;
+  if (d->direction != 1 && d->direction != -1) return RLSTM_EMODE;
+  if (d->operand_dtype != 0) return RLSTM_EMODE;
+  if (d->engine < RLSTM_ENGINE_AUTO || d->engine > RLSTM_ENGINE_STEPWISE) return RLSTM_EMODE;
+  return RLSTM_OK;
+}
+int check_stack_desc(const rblstm_desc* d) {
+  if (!d) return RLSTM_ENULL;
+  if (d->L <= 0 || d->T <= 0 || d->B <= 0 || d->D <= 0 || d->H <= 0) return RLSTM_EDIM;
+  if ((long long)d->T * d->B > (1ll << 30) || (long long)d->H * 4 > (1ll << 24)) return RLSTM_EDIM;
+  if (d->operand_dtype != 0) return RLSTM_EMODE;
+  if (d->engine < RLSTM_ENGINE_AUTO || d->engine > RLSTM_ENGINE_STEPWISE) return RLSTM_EMODE;
+  return RLSTM_OK;
+}
+
+size_t splitk_floats(int max_m, int H) {
+  // room for 16 partial [max_m, 4H] results
+  return align_up((size_t)16 * max_m * 4 * H, 64);
+}
+
+// resolves the engine; returns RLSTM_ENGINE_PERSISTENT / _STEPWISE or a negative code
+int resolve_engine(int engine, const RecShape& s) {
+  if (engine == RLSTM_ENGINE_STEPWISE) return RLSTM_ENGINE_STEPWISE;
+  DeviceInfo di;
+  if (device_info(&di) != hipSuccess) { (void)hipGetLastError(); return RLSTM_EHIP; }
+  const bool ok = rec_persistent_supported(s, di.num_cus, di.max_lds);
+  if (engine == RLSTM_ENGINE_PERSISTENT) return ok ? RLSTM_ENGINE_PERSISTENT : RLSTM_ERESIDENT;
+  return ok ? RLSTM_ENGINE_PERSISTENT : RLSTM_ENGINE_STEPWISE;
+}
+
+// ---- optional event timing of the enqueued kernel groups ---------------------
+struct ProfRec { int kind, layer, ndir; hipEvent_t a, b; };
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof;
+std::vector<hipEvent_t> g_prof_pool;
+
+hipEvent_t prof_event() {
+  hipEvent_t e = nullptr;
+  if (!g_prof_pool.empty()) { e = g_prof_pool.back(); g_prof_pool.pop_back(); return e; }
+  if (hipEventCreate(&e) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+  return e;
+}
+struct ProfScope {
+  hipStream_t st; hipEvent_t b = nullptr; bool on;
+  ProfScope(hipStream_t s, int kind, int layer, int ndir) : st(s), on(g_prof_on) {
+    if (!on) return;
+    hipEvent_t a = prof_event(); b = prof_event();
+    if (!a || !b) { on = false; return; }
+    (void)hipEventRecord(a, st);
+    g_prof.push_back(ProfRec{kind, layer, ndir, a, b});
+  }
+  ~ProfScope() { if (on) (void)hipEventRecord(b, st); }
+};
+
+int hip_to_code(hipError_t e, int resident_err) {
+  if (e == hipSuccess) return RLSTM_OK;
+  (void)hipGetLastError();
+  return resident_err ? RLSTM_ERESIDENT : RLSTM_EHIP;
+}
+
+#define RLSTM_TRY(expr)                                   \
+  do {                                                    \
+    hipError_t e_ = (expr);                               \
+    if (e_ != hipSuccess) return hip_to_code(e_, resident_err); \
+  } while (0)
+
+// weight gradients of one direction: dW = X^T dZ, dR = Hprev^T dZ (Hprev = y shifted by one
+// processed frame; the h0 term is added separately by the single-layer entry point)
+int weight_grads(hipStream_t st, int layer, int T, int B, int Din, int H, int direction,
+                 const float* x, int ldx, const float* y, int ldy, const float* dz,
+                 float* dW, float* dR, float* skws, size_t skfloats, bool naive) {
+  int resident_err = 0;
+  GemmCall g;
+  g.transA = true; g.transB = false;
+  g.M = Din; g.N = 4 * H; g.K = T * B;
+  g.A = x; g.lda = ldx; g.B = dz; g.ldb = 4 * H; g.C = dW; g.ldc = 4 * H;
+  g.splitk_ws = skws; g.splitk_floats = skfloats; g.naive = naive;
+  {
+    ProfScope ps(st, 4, layer, 1);
+    RLSTM_TRY(gemm(st, g));
+  }
+  GemmCall r = g;
+  r.M = H; r.K = (T - 1) * B;
+  r.lda = ldy; r.C = dR;
+  if (direction > 0) { r.A = y; r.B = dz + (size_t)B * 4 * H; }
+  else               { r.A = y + (size_t)B * ldy; r.B = dz; }
+  {
+    ProfScope ps(st, 5, layer, 1);
+    RLSTM_TRY(gemm(st, r));
+  }
+  return RLSTM_OK;
+}
+
+struct StackLayout {
+  size_t zg[2], c[2], y;     // offsets (floats) inside one layer's block of the reserve
+  size_t per_layer;
+};
+StackLayout stack_layout(const rblstm_desc* d) {
+  StackLayout s;
+  const size_t tb = (size_t)d->T * d->B;
+  size_t off = 0;
+  for (int k = 0; k < 2; ++k) { s.zg[k] = off; off += align_up(tb * 4 * d->H, 64); }
+  for (int k = 0; k < 2; ++k) { s.c[k] = off; off += align_up(tb * d->H, 64); }
+  s.y = off; off += align_up(tb * 2 * d->H, 64);
+  s.per_layer = off;
+  return s;
+}
+
+RecShape stack_rec_shape(const rblstm_desc* d) {
+  RecShape s;
+  s.T = d->T; s.B = d->B; s.H = d->H; s.ldy = 2 * d->H; s.ndir = 2; s.operand_dtype = d->operand_dtype;
+  return s;
+}
+
+int stack_forward(const rblstm_desc* d, const float* x, const float* const* params, const int32_t* seq_lens,
+                  float* y_top, float* res, char* ws, hipStream_t sa, bool persistent) {
+  int resident_err = 0;
+  const StackLayout lay = stack_layout(d);
+  const RecShape rs = stack_rec_shape(d);
+  unsigned* flag = reinterpret_cast<unsigned*>(ws);
+  void* recws = ws + kFlagBytes;
+  const int T = d->T, B = d->B, H = d->H;
+  RLSTM_TRY(clear_flag(sa, flag));
+  const float* in = x;
+  int din = d->D;
+  for (int l = 0; l < d->L; ++l) {
+    float* base = res + (size_t)l * lay.per_layer;
+    float* yl = (l == d->L - 1) ? y_top : base + lay.y;
+    RecFwdDir dirs[2];
+    for (int k = 0; k < 2; ++k) {
+      const float* W = params[6 * l + 3 * k + 0];
+      const float* R = params[6 * l + 3 * k + 1];
+      const float* b = params[6 * l + 3 * k + 2];
+      GemmCall g;
+      g.M = T * B; g.N = 4 * H; g.K = din;
+      g.A = in; g.lda = din; g.B = W; g.ldb = 4 * H; g.C = base + lay.zg[k]; g.ldc = 4 * H; g.bias = b;
+      g.naive = !persistent;
+      {
+        ProfScope ps(sa, 0, l, 1);
+        RLSTM_TRY(gemm(sa, g));
+      }
+      dirs[k] = RecFwdDir{base + lay.zg[k], R, nullptr, nullptr, yl + (size_t)k * H, base + lay.c[k],
+                          nullptr, nullptr, k == 0 ? 1 : -1};
+    }
+    {
+      ProfScope ps(sa, 1, l, 2);
+      RLSTM_TRY(rec_forward(sa, rs, dirs, seq_lens, recws, flag, persistent, &resident_err));
+    }
+    in = yl;
+    din = 2 * H;
+  }
+  return RLSTM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* rlstm_version(void) { return "0.1"; }
+
+const char* rlstm_strerror(int code) {
+  switch (code) {
+    case RLSTM_OK: return "success";
+    case RLSTM_ENULL: return "a required pointer is null";
+    case RLSTM_EDIM: return "a dimension is not positive or a leading dimension is too small";
+    case RLSTM_EMODE: return "unsupported direction, operand_dtype or engine";
+    case RLSTM_ESIZE: return "buffer too small";
+    case RLSTM_ERESIDENT: return "the persistent recurrent kernel cannot hold this shape on this device";
+    case RLSTM_EHIP: return "a HIP runtime call failed";
+    default: return "unknown rlstm error code";
+  }
+}
+
+size_t rlstm_reserve_bytes(const rlstm_desc* d) {
+  if (check_desc(d) != RLSTM_OK) return 0;
+  return align_up((size_t)d->T * d->B * 4 * d->H * sizeof(float), 256);
+}
+
+size_t rlstm_workspace_bytes(const rlstm_desc* d) {
+  if (check_desc(d) != RLSTM_OK) return 0;
+  RecShape s{d->T, d->B, d->H, d->ldy ? d->ldy : d->H, 1, d->operand_dtype};
+  const int mm = d->D > d->H ? d->D : d->H;
+  return kFlagBytes + align_up(rec_workspace_bytes(s), 256) + splitk_floats(mm, d->H) * sizeof(float);
+}
+
+size_t rblstm_reserve_bytes(const rblstm_desc* d) {
+  if (check_stack_desc(d) != RLSTM_OK) return 0;
+  return stack_layout(d).per_layer * (size_t)d->L * sizeof(float);
+}
+
+size_t rblstm_workspace_bytes(const rblstm_desc* d) {
+  if (check_stack_desc(d) != RLSTM_OK) return 0;
+  const RecShape s = stack_rec_shape(d);
+  const int mm = d->D > 2 * d->H ? d->D : 2 * d->H;
+  const size_t dy = align_up((size_t)d->T * d->B * 2 * d->H, 64);
+  return kFlagBytes + align_up(rec_workspace_bytes(s), 256) + (splitk_floats(mm, d->H) + 2 * dy) * sizeof(float);
+}
+
+int rlstm_resolve_engine(const rlstm_desc* d) {
+  int rc = check_desc(d);
+  if (rc != RLSTM_OK) return rc;
+  RecShape s{d->T, d->B, d->H, d->ldy ? d->ldy : d->H, 1, d->operand_dtype};
+  return resolve_engine(d->engine, s);
+}
+
+int rlstm_last_timeout(const void* workspace) {
+  if (!workspace) return RLSTM_ENULL;
+  if (hipDeviceSynchronize() != hipSuccess) { (void)hipGetLastError(); return RLSTM_EHIP; }
+  unsigned v = 0;
+  if (hipMemcpy(&v, workspace, sizeof(v), hipMemcpyDeviceToHost) != hipSuccess) { (void)hipGetLastError(); return RLSTM_EHIP; }
+  return v != 0 ? 1 : 0;
+}
+
+int rlstm_profile_enable(int on) {
+  g_prof_on = on != 0;
+  return RLSTM_OK;
+}
+
+int rlstm_profile_read(rlstm_profile_entry* out, int max_entries) {
+  const int n = (int)g_prof.size();
+  int rc = n;
+  for (int i = 0; i < n; ++i) {
+    ProfRec& r = g_prof[i];
+    float ms = 0.f;
+    if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) {
+      (void)hipGetLastError();
+      rc = RLSTM_EHIP;
+    }
+    if (out && i < max_entries) out[i] = rlstm_profile_entry{r.kind, r.layer, r.ndir, 0, ms};
+    g_prof_pool.push_back(r.a);
+    g_prof_pool.push_back(r.b);
+  }
+  g_prof.clear();
+  return rc;
+}
+
+int rlstm_gemm_f32(int trans_a, int trans_b, int M, int N, int K,
+                   const float* A, int lda, const float* B, int ldb, float* C, int ldc,
+                   const float* bias, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream) {
+  if (!A || !B || !C) return RLSTM_ENULL;
+  if (M <= 0 || N <= 0 || K < 0) return RLSTM_EDIM;
+  if (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N) || ldc < N) return RLSTM_EDIM;
+  int resident_err = 0;
+  GemmCall g;
+  g.transA = trans_a != 0; g.transB = trans_b != 0;
+  g.M = M; g.N = N; g.K = K; g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.bias = bias;
+  g.splitk_ws = static_cast<float*>(splitk_ws); g.splitk_floats = splitk_ws ? splitk_ws_bytes / sizeof(float) : 0;
+  RLSTM_TRY(gemm(static_cast<hipStream_t>(hip_stream), g));
+  return RLSTM_OK;
+}
+
+int lstm_fwd(const rlstm_desc* d, const float* x, const float* W, const float* R, const float* b,
+             const float* h0, const float* c0, const int32_t* seq_lens,
+             float* y, float* c, float* hT, float* cT, void* reserve, void* workspace, void* hip_stream) {
+  int rc = check_desc(d);
+  if (rc != RLSTM_OK) return rc;
+  if (!x || !W || !R || !b || !seq_lens || !y || !c || !reserve || !workspace) return RLSTM_ENULL;
+  const int ldx = d->ldx ? d->ldx : d->D, ldy = d->ldy ? d->ldy : d->H;
+  RecShape s{d->T, d->B, d->H, ldy, 1, d->operand_dtype};
+  const int eng = resolve_engine(d->engine, s);
+  if (eng < 0) return eng;
+  const bool persistent = eng == RLSTM_ENGINE_PERSISTENT;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  int resident_err = 0;
+  char* ws = static_cast<char*>(workspace);
+  unsigned* flag = reinterpret_cast<unsigned*>(ws);
+  float* zg = static_cast<float*>(reserve);
+
+  RLSTM_TRY(clear_flag(st, flag));
+  GemmCall g;
+  g.M = d->T * d->B; g.N = 4 * d->H; g.K = d->D;
+  g.A = x; g.lda = ldx; g.B = W; g.ldb = 4 * d->H; g.C = zg; g.ldc = 4 * d->H; g.bias = b;
+  g.naive = !persistent;
+  {
+    ProfScope ps(st, 0, 0, 1);
+    RLSTM_TRY(gemm(st, g));
+  }
+  RecFwdDir dir{zg, R, h0, c0, y, c, hT, cT, d->direction};
+  {
+    ProfScope ps(st, 1, 0, 1);
+    RLSTM_TRY(rec_forward(st, s, &dir, seq_lens, ws + kFlagBytes, flag, persistent, &resident_err));
+  }
+  return RLSTM_OK;
+}
+
+int lstm_bwd(const rlstm_desc* d, const float* x, const float* W, const float* R,
+             const int32_t* seq_lens, const float* h0, const float* c0,
+             const float* y, const float* c, void* reserve,
+             const float* dy, const float* dhT, const float* dcT,
+             float* dx, float* dW, float* dR, float* db, float* dh0, float* dc0,
+             void* workspace, void* hip_stream) {
+  int rc = check_desc(d);
+  if (rc != RLSTM_OK) return rc;
+  if (!x || !W || !R || !seq_lens || !y || !c || !reserve || !dy || !dW || !dR || !db || !workspace) return RLSTM_ENULL;
+  const int ldx = d->ldx ? d->ldx : d->D, ldy = d->ldy ? d->ldy : d->H;
+  const int T = d->T, B = d->B, D = d->D, H = d->H;
+  RecShape s{T, B, H, ldy, 1, d->operand_dtype};
+  const int eng = resolve_engine(d->engine, s);
+  if (eng < 0) return eng;
+  const bool persistent = eng == RLSTM_ENGINE_PERSISTENT;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  int resident_err = 0;
+  char* ws = static_cast<char*>(workspace);
+  unsigned* flag = reinterpret_cast<unsigned*>(ws);
+  float* zg = static_cast<float*>(reserve);
+  char* recws = ws + kFlagBytes;
+  float* skws = reinterpret_cast<float*>(recws + align_up(rec_workspace_bytes(s), 256));
+  const size_t skfloats = splitk_floats(D > H ? D : H, H);
+
+  RLSTM_TRY(clear_flag(st, flag));
+  RecBwdDir dir{zg, R, c, c0, dy, dhT, dcT, dh0, dc0, db, d->direction};
+  {
+    ProfScope ps(st, 2, 0, 1);
+    RLSTM_TRY(rec_backward(st, s, &dir, seq_lens, recws, flag, persistent, &resident_err));
+  }
+  rc = weight_grads(st, 0, T, B, D, H, d->direction, x, ldx, y, ldy, zg, dW, dR, skws, skfloats, !persistent);
+  if (rc != RLSTM_OK) return rc;
+  if (h0) RLSTM_TRY(add_h0_outer(st, T, B, H, d->direction, h0, zg, seq_lens, dR));
+  if (dx) {
+    GemmCall g;
+    g.transB = true;
+    g.M = T * B; g.N = D; g.K = 4 * H;
+    g.A = zg; g.lda = 4 * H; g.B = W; g.ldb = 4 * H; g.C = dx; g.ldc = ldx;
+    g.naive = !persistent;
+    ProfScope ps(st, 3, 0, 1);
+    RLSTM_TRY(gemm(st, g));
+  }
+  return RLSTM_OK;
+}
+
+int blstm_stack_fwd(const rblstm_desc* d, const float* x, const float* const* params,
+                    const int32_t* seq_lens, float* y_top, void* reserve, void* workspace, void* hip_stream_a) {
+  int rc = check_stack_desc(d);
+  if (rc != RLSTM_OK) return rc;
+  if (!x || !params || !seq_lens || !y_top || !reserve || !workspace) return RLSTM_ENULL;
+  for (int i = 0; i < 6 * d->L; ++i) if (!params[i]) return RLSTM_ENULL;
+  const int eng = resolve_engine(d->engine, stack_rec_shape(d));
+  if (eng < 0) return eng;
+  return stack_forward(d, x, params, seq_lens, y_top, static_cast<float*>(reserve), static_cast<char*>(workspace),
+                       static_cast<hipStream_t>(hip_stream_a), eng == RLSTM_ENGINE_PERSISTENT);
+}
+
+int blstm_stack_fwd_bwd(const rblstm_desc* d, const float* x, const float* const* params,
+                        const int32_t* seq_lens, const float* dy_top,
+                        float* y_top, float* const* grads, float* dx,
+                        void* reserve, void* workspace, void* hip_stream_a, void* hip_stream_b) {
+  int rc = check_stack_desc(d);
+  if (rc != RLSTM_OK) return rc;
+  if (!x || !params || !seq_lens || !dy_top || !y_top || !grads || !reserve || !workspace) return RLSTM_ENULL;
+  for (int i = 0; i < 6 * d->L; ++i) if (!params[i] || !grads[i]) return RLSTM_ENULL;
+  const RecShape rs = stack_rec_shape(d);
+  const int eng = resolve_engine(d->engine, rs);
+  if (eng < 0) return eng;
+  const bool persistent = eng == RLSTM_ENGINE_PERSISTENT;
+  hipStream_t sa = static_cast<hipStream_t>(hip_stream_a);
+  hipStream_t sb = static_cast<hipStream_t>(hip_stream_b);
+  const bool overlap = sb != nullptr && sb != sa;
+  if (!overlap) sb = sa;
+
+  float* res = static_cast<float*>(reserve);
+  char* ws = static_cast<char*>(workspace);
+  rc = stack_forward(d, x, params, seq_lens, y_top, res, ws, sa, persistent);
+  if (rc != RLSTM_OK) return rc;
+
+  int resident_err = 0;
+  const StackLayout lay = stack_layout(d);
+  const int T = d->T, B = d->B, H = d->H, L = d->L;
+  unsigned* flag = reinterpret_cast<unsigned*>(ws);
+  char* recws = ws + kFlagBytes;
+  float* skws = reinterpret_cast<float*>(recws + align_up(rec_workspace_bytes(rs), 256));
+  const int mm = d->D > 2 * H ? d->D : 2 * H;
+  const size_t skfloats = splitk_floats(mm, H);
+  const size_t dyfloats = align_up((size_t)T * B * 2 * H, 64);
+  float* dybuf[2] = {skws + skfloats, skws + skfloats + dyfloats};
+
+  std::vector<hipEvent_t> events;
+  auto new_event = [&](hipEvent_t* ev) -> hipError_t {
+    hipError_t e = hipEventCreateWithFlags(ev, hipEventDisableTiming);
+    if (e == hipSuccess) events.push_back(*ev);
+    return e;
+  };
+  auto cleanup = [&]() { for (hipEvent_t ev : events) (void)hipEventDestroy(ev); };
+#define RLSTM_TRY_C(expr)                                                         \
+  do {                                                                            \
+    hipError_t e_ = (expr);                                                       \
+    if (e_ != hipSuccess) { cleanup(); return hip_to_code(e_, resident_err); }    \
+  } while (0)
+
+  const float* dy = dy_top;
+  for (int l = L - 1; l >= 0; --l) {
+    float* base = res + (size_t)l * lay.per_layer;
+    const float* yl = (l == L - 1) ? y_top : base + lay.y;
+    const float* xin = (l == 0) ? x : res + (size_t)(l - 1) * lay.per_layer + lay.y;
+    const int din = (l == 0) ? d->D : 2 * H;
+    RecBwdDir dirs[2];
+    for (int k = 0; k < 2; ++k) {
+      dirs[k] = RecBwdDir{base + lay.zg[k], params[6 * l + 3 * k + 1], base + lay.c[k], nullptr,
+                          dy + (size_t)k * H, nullptr, nullptr, nullptr, nullptr, grads[6 * l + 3 * k + 2],
+                          k == 0 ? 1 : -1};
+    }
+    {
+      ProfScope ps(sa, 2, l, 2);
+      RLSTM_TRY_C(rec_backward(sa, rs, dirs, seq_lens, recws, flag, persistent, &resident_err));
+    }
+    if (overlap) {
+      hipEvent_t ev;
+      RLSTM_TRY_C(new_event(&ev));
+      RLSTM_TRY_C(hipEventRecord(ev, sa));
+      RLSTM_TRY_C(hipStreamWaitEvent(sb, ev, 0));
+    }
+    // input gradient = next lower layer's dy (chain on stream a)
+    float* dxl = (l == 0) ? dx : dybuf[l & 1];
+    if (dxl) {
+      for (int k = 0; k < 2; ++k) {
+        GemmCall g;
+        g.transB = true;
+        g.M = T * B; g.N = din; g.K = 4 * H;
+        g.A = base + lay.zg[k]; g.lda = 4 * H; g.B = params[6 * l + 3 * k + 0]; g.ldb = 4 * H;
+        g.C = dxl; g.ldc = din; g.accumulate = (k == 1);
+        g.naive = !persistent;
+        ProfScope ps(sa, 3, l, 1);
+        RLSTM_TRY_C(gemm(sa, g));
+      }
+    }
+    // weight gradients (independent of the chain: stream b)
+    for (int k = 0; k < 2; ++k) {
+      rc = weight_grads(sb, l, T, B, din, H, k == 0 ? 1 : -1, xin, din, yl + (size_t)k * H, 2 * H,
+                        base + lay.zg[k], grads[6 * l + 3 * k + 0], grads[6 * l + 3 * k + 1], skws, skfloats,
+                        !persistent);
+      if (rc != RLSTM_OK) { cleanup(); return rc; }
+    }
+    dy = dxl;
+  }
+  if (overlap) {
+    hipEvent_t ev;
+    RLSTM_TRY_C(new_event(&ev));
+    RLSTM_TRY_C(hipEventRecord(ev, sb));
+    RLSTM_TRY_C(hipStreamWaitEvent(sa, ev, 0));
+  }
+  cleanup();
+  return RLSTM_OK;
+}
+
+}  // extern "C"

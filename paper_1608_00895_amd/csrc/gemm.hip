@@ -1,0 +1,321 @@
+// Dense fp32 products on the CDNA4 matrix cores (v_mfma_f32_32x32x2_f32).
+//
+// These serve the whole-minibatch products of the LSTM layer (Sec. 4.2 of the
+// RETURNN paper): the input projection Z = X W + b over all T*B frames, and
+// after the pass back through time dX = dZ W^T, dW = X^T dZ, dR = Hprev^T dZ.
+//
+// Tiling: a 256-thread workgroup (4 wavefronts of 64 lanes, 2 x 2) owns a
+// 128 x 128 tile of C; every wavefront owns 64 x 64 of it as 2 x 2 MFMA tiles
+// of 32 x 32 (64 accumulator registers per lane).  K is consumed in slabs of
+// BK; both operand slabs are staged in LDS k-major ([BK][128+pad]) so that the
+// MFMA operand fetch (lane l reads element [k + l/32][l%32]) is a conflict-free
+// ds_read_b32, and double-buffered so global loads of slab i+1 overlap the
+// MFMAs of slab i.  Operands that are k-contiguous in memory are transposed on
+// their way into LDS.
+//
+// Split-K (for the weight gradients, whose K = T*B is 32x larger than M or N)
+// writes per-slice partial tiles to scratch and sums them in slice order in a
+// second kernel, so results are bit-reproducible run to run.
+#include "rlstm_internal.h"
+
+namespace rlstm {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+namespace {
+
+constexpr int TM = 128;       // C tile rows per workgroup
+constexpr int TN = 128;       // C tile cols per workgroup
+constexpr int LDS_PAD = 4;    // floats; keeps float4 rows 16-byte aligned
+constexpr int LDT = TM + LDS_PAD;
+
+struct GemmP {
+  int M, N, K;
+  const float* A; int lda;
+  const float* B; int ldb;
+  float* C; int ldc;
+  const float* bias;
+  int accumulate;
+  int tiles_n;
+  int kchunk;          // K range per blockIdx.z slice (multiple of BK)
+  float* partial;      // split-K scratch [slices][M][N] or null
+};
+
+// ---- slab loaders: global -> registers -> LDS ------------------------------
+
+// "natural": element (k, mn) at ptr[k*ld + mn]; slab is BK rows of 128 floats.
+template <int BK, bool VEC>
+__device__ __forceinline__ void load_natural(const float* __restrict__ ptr, int ld, int k0, int kend,
+                                             int mn0, int MN, float4 (&r)[BK / 8]) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < BK / 8; ++i) {
+    const int idx = tid + i * 256;
+    const int row = idx >> 5, c4 = idx & 31;
+    const int k = k0 + row, mn = mn0 + c4 * 4;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (k < kend) {
+      const float* q = ptr + (size_t)k * ld + mn;
+      if (VEC) {
+        if (mn < MN) v = *reinterpret_cast<const float4*>(q);
+      } else {
+        if (mn + 0 < MN) v.x = q[0];
+        if (mn + 1 < MN) v.y = q[1];
+        if (mn + 2 < MN) v.z = q[2];
+        if (mn + 3 < MN) v.w = q[3];
+      }
+    }
+    r[i] = v;
+  }
+}
+template <int BK>
+__device__ __forceinline__ void store_natural(float* __restrict__ s, const float4 (&r)[BK / 8]) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < BK / 8; ++i) {
+    const int idx = tid + i * 256;
+    const int row = idx >> 5, c4 = idx & 31;
+    *reinterpret_cast<float4*>(s + row * LDT + c4 * 4) = r[i];
+  }
+}
+
+// "transposing": element (mn, k) at ptr[mn*ld + k]; slab is 128 rows of BK floats.
+template <int BK, bool VEC>
+__device__ __forceinline__ void load_transposing(const float* __restrict__ ptr, int ld, int k0, int kend,
+                                                 int mn0, int MN, float4 (&r)[BK / 8]) {
+  constexpr int QPR = BK / 4;   // float4 per row
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < BK / 8; ++i) {
+    const int idx = tid + i * 256;
+    const int mn = mn0 + idx / QPR, k = k0 + (idx % QPR) * 4;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (mn < MN) {
+      const float* q = ptr + (size_t)mn * ld + k;
+      if (VEC) {
+        if (k < kend) v = *reinterpret_cast<const float4*>(q);
+      } else {
+        if (k + 0 < kend) v.x = q[0];
+        if (k + 1 < kend) v.y = q[1];
+        if (k + 2 < kend) v.z = q[2];
+        if (k + 3 < kend) v.w = q[3];
+      }
+    }
+    r[i] = v;
+  }
+}
+template <int BK>
+__device__ __forceinline__ void store_transposing(float* __restrict__ s, const float4 (&r)[BK / 8]) {
+  constexpr int QPR = BK / 4;
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < BK / 8; ++i) {
+    const int idx = tid + i * 256;
+    const int mn = idx / QPR, kq = (idx % QPR) * 4;
+    s[(kq + 0) * LDT + mn] = r[i].x;
+    s[(kq + 1) * LDT + mn] = r[i].y;
+    s[(kq + 2) * LDT + mn] = r[i].z;
+    s[(kq + 3) * LDT + mn] = r[i].w;
+  }
+}
+
+// TA: A stored [K,M] (natural loader); !TA: A stored [M,K] (transposing loader)
+// TB: B stored [N,K] (transposing loader); !TB: B stored [K,N] (natural loader)
+template <int BK, bool TA, bool TB, bool VEC>
+__global__ __launch_bounds__(256) void gemm_mfma_f32_kernel(GemmP p) {
+  extern __shared__ __align__(16) float smem[];
+  float* As = smem;                       // [2][BK][LDT]
+  float* Bs = smem + 2 * BK * LDT;        // [2][BK][LDT]
+
+  const int tile = blockIdx.x;
+  const int tn = tile % p.tiles_n, tm = tile / p.tiles_n;
+  const int m0 = tm * TM, n0 = tn * TN;
+  const int kbeg = blockIdx.z * p.kchunk;
+  const int kend = min(p.K, kbeg + p.kchunk);
+  const int nslab = (kend - kbeg + BK - 1) / BK;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, lh = lane >> 5;
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  float4 ra[BK / 8], rb[BK / 8];
+  auto loadA = [&](int k0) {
+    if (TA) load_natural<BK, VEC>(p.A, p.lda, k0, kend, m0, p.M, ra);
+    else    load_transposing<BK, VEC>(p.A, p.lda, k0, kend, m0, p.M, ra);
+  };
+  auto loadB = [&](int k0) {
+    if (TB) load_transposing<BK, VEC>(p.B, p.ldb, k0, kend, n0, p.N, rb);
+    else    load_natural<BK, VEC>(p.B, p.ldb, k0, kend, n0, p.N, rb);
+  };
+  auto storeAB = [&](int buf) {
+    if (TA) store_natural<BK>(As + buf * BK * LDT, ra); else store_transposing<BK>(As + buf * BK * LDT, ra);
+    if (TB) store_transposing<BK>(Bs + buf * BK * LDT, rb); else store_natural<BK>(Bs + buf * BK * LDT, rb);
+  };
+
+  if (nslab > 0) {
+    loadA(kbeg); loadB(kbeg);
+    storeAB(0);
+  }
+  __syncthreads();
+
+  for (int s = 0; s < nslab; ++s) {
+    const int buf = s & 1;
+    if (s + 1 < nslab) { loadA(kbeg + (s + 1) * BK); loadB(kbeg + (s + 1) * BK); }
+    const float* as = As + buf * BK * LDT + wm * 64 + l32;
+    const float* bs = Bs + buf * BK * LDT + wn * 64 + l32;
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 2) {
+      const float a0 = as[(kk + lh) * LDT];
+      const float a1 = as[(kk + lh) * LDT + 32];
+      const float b0 = bs[(kk + lh) * LDT];
+      const float b1 = bs[(kk + lh) * LDT + 32];
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+    }
+    if (s + 1 < nslab) storeAB(buf ^ 1);
+    __syncthreads();
+  }
+
+  // Epilogue.  Accumulator register r of lane l holds
+  // C[(r/4)*8 + (l/32)*4 + r%4][l%32] of its 32 x 32 tile.
+  float* Cout = p.C;
+  int ldc = p.ldc;
+  const bool partial = p.partial != nullptr;
+  if (partial) { Cout = p.partial + (size_t)blockIdx.z * p.M * p.N; ldc = p.N; }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int col = n0 + wn * 64 + j * 32 + l32;
+      if (col >= p.N) continue;
+      const float bv = (!partial && p.bias) ? p.bias[col] : 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wm * 64 + i * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
+        if (row < p.M) {
+          float* dst = Cout + (size_t)row * ldc + col;
+          float v = acc[i][j][r] + bv;
+          if (!partial && p.accumulate) v += *dst;
+          *dst = v;
+        }
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int slices,
+                                                             int M, int N, float* __restrict__ C, int ldc,
+                                                             const float* __restrict__ bias, int accumulate) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t mn = (size_t)M * N;
+  if (idx >= mn) return;
+  float s = 0.f;
+  for (int z = 0; z < slices; ++z) s += partial[(size_t)z * mn + idx];
+  const int m = (int)(idx / N), n = (int)(idx % N);
+  if (bias) s += bias[n];
+  float* dst = C + (size_t)m * ldc + n;
+  if (accumulate) s += *dst;
+  *dst = s;
+}
+
+// Plain product for the stepwise engine: one thread per element of C.
+__global__ __launch_bounds__(256) void gemm_naive_kernel(GemmP p, int transA, int transB) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (size_t)p.M * p.N) return;
+  const int m = (int)(idx / p.N), n = (int)(idx % p.N);
+  float s = 0.f;
+  for (int k = 0; k < p.K; ++k) {
+    const float a = transA ? p.A[(size_t)k * p.lda + m] : p.A[(size_t)m * p.lda + k];
+    const float b = transB ? p.B[(size_t)n * p.ldb + k] : p.B[(size_t)k * p.ldb + n];
+    s = fmaf(a, b, s);
+  }
+  if (p.bias) s += p.bias[n];
+  float* dst = p.C + (size_t)m * p.ldc + n;
+  if (p.accumulate) s += *dst;
+  *dst = s;
+}
+
+inline bool aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
+
+template <int BK, bool TA, bool TB>
+hipError_t launch_mfma(hipStream_t stream, const GemmP& p, dim3 grid, bool vec) {
+  const size_t lds = (size_t)4 * BK * LDT * sizeof(float);
+  if (vec) {
+    hipLaunchKernelGGL((gemm_mfma_f32_kernel<BK, TA, TB, true>), grid, dim3(256), lds, stream, p);
+  } else {
+    hipLaunchKernelGGL((gemm_mfma_f32_kernel<BK, TA, TB, false>), grid, dim3(256), lds, stream, p);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t gemm(hipStream_t stream, const GemmCall& g) {
+  if (g.M <= 0 || g.N <= 0) return hipSuccess;
+  GemmP p;
+  p.M = g.M; p.N = g.N; p.K = g.K;
+  p.A = g.A; p.lda = g.lda; p.B = g.B; p.ldb = g.ldb; p.C = g.C; p.ldc = g.ldc;
+  p.bias = g.bias; p.accumulate = g.accumulate ? 1 : 0;
+  p.tiles_n = (g.N + TN - 1) / TN;
+  p.kchunk = g.K; p.partial = nullptr;
+
+  if (g.naive) {
+    const size_t total = (size_t)g.M * g.N;
+    hipLaunchKernelGGL(gemm_naive_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, p,
+                       g.transA ? 1 : 0, g.transB ? 1 : 0);
+    return hipGetLastError();
+  }
+
+  constexpr int BK = 16;
+  // float4 global loads need 16-byte aligned rows and whole float4s inside the matrix
+  bool vec = aligned16(g.A) && aligned16(g.B) && (g.lda % 4 == 0) && (g.ldb % 4 == 0) && (g.K % 4 == 0);
+  if (g.transA) vec = vec && (g.M % 4 == 0);
+  if (!g.transB) vec = vec && (g.N % 4 == 0);
+
+  const int tiles_m = (g.M + TM - 1) / TM;
+  const int tiles = tiles_m * p.tiles_n;
+  int slices = 1;
+  if (g.splitk_ws && g.K >= 4 * 1024 && tiles < 512) {
+    slices = (1024 + tiles - 1) / tiles;
+    const int max_by_k = g.K / 512;
+    if (slices > max_by_k) slices = max_by_k;
+    const size_t per = (size_t)g.M * g.N;
+    const size_t max_by_ws = g.splitk_floats / per;
+    if ((size_t)slices > max_by_ws) slices = (int)max_by_ws;
+    if (slices > 64) slices = 64;
+    if (slices < 1) slices = 1;
+  }
+  if (slices > 1) {
+    int kchunk = (g.K + slices - 1) / slices;
+    kchunk = (kchunk + BK - 1) / BK * BK;
+    slices = (g.K + kchunk - 1) / kchunk;
+    p.kchunk = kchunk;
+    p.partial = g.splitk_ws;
+  }
+  dim3 grid((unsigned)tiles, 1, (unsigned)slices);
+  hipError_t e;
+  if (!g.transA && !g.transB)      e = launch_mfma<BK, false, false>(stream, p, grid, vec);
+  else if (!g.transA && g.transB)  e = launch_mfma<BK, false, true>(stream, p, grid, vec);
+  else if (g.transA && !g.transB)  e = launch_mfma<BK, true, false>(stream, p, grid, vec);
+  else                             e = launch_mfma<BK, true, true>(stream, p, grid, vec);
+  if (e != hipSuccess) return e;
+  if (slices > 1) {
+    const size_t total = (size_t)g.M * g.N;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+                       g.splitk_ws, slices, g.M, g.N, g.C, g.ldc, g.bias, g.accumulate ? 1 : 0);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+}  // namespace rlstm

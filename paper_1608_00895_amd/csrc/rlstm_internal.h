@@ -1,0 +1,89 @@
+// Internal declarations shared by the translation units of librlstm.
+// Nothing here is part of the C ABI (see include/rlstm.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace rlstm {
+
+// ---------------------------------------------------------------------------
+// Dense products on the matrix cores.
+//   C[M,N] (row stride ldc) = op(A) * op(B) (+ bias[n]) (+ C if accumulate)
+//   transA == false: A is [M,K], row stride lda (k contiguous)
+//   transA == true : A is stored [K,M], row stride lda (m contiguous)
+//   transB == false: B is [K,N], row stride ldb (n contiguous)
+//   transB == true : B is stored [N,K], row stride ldb (k contiguous)
+// splitk_ws / splitk_floats: scratch for deterministic split-K partial sums
+// (may be null: no split).  naive selects the plain one-thread-per-output
+// kernel of the stepwise engine.
+// ---------------------------------------------------------------------------
+struct GemmCall {
+  bool transA = false, transB = false;
+  int M = 0, N = 0, K = 0;
+  const float* A = nullptr; int lda = 0;
+  const float* B = nullptr; int ldb = 0;
+  float* C = nullptr; int ldc = 0;
+  const float* bias = nullptr;
+  bool accumulate = false;
+  float* splitk_ws = nullptr; size_t splitk_floats = 0;
+  int operand_dtype = 0;
+  bool naive = false;
+};
+hipError_t gemm(hipStream_t stream, const GemmCall& g);
+
+// ---------------------------------------------------------------------------
+// Recurrent passes.  One call handles ndir (1 or 2) independent directions of
+// the same shape in a single launch.
+// ---------------------------------------------------------------------------
+struct RecFwdDir {
+  float* zg;          // [T,B,4H] in: b + x W ; out: activated gates i|f|o|g
+  const float* R;     // [H,4H]
+  const float* h0;    // [B,H] or null
+  const float* c0;    // [B,H] or null
+  float* y;           // [T,B,ldy], already offset to this direction's columns
+  float* c;           // [T,B,H]
+  float* hT;          // [B,H] or null
+  float* cT;          // [B,H] or null
+  int direction;      // +1 / -1
+};
+struct RecBwdDir {
+  float* zg;          // [T,B,4H] in: gates ; out: d loss / d a
+  const float* R;     // [H,4H]
+  const float* c;     // [T,B,H]
+  const float* c0;    // [B,H] or null
+  const float* dy;    // [T,B,ldy], offset to this direction's columns
+  const float* dhT;   // [B,H] or null
+  const float* dcT;   // [B,H] or null
+  float* dh0;         // [B,H] or null
+  float* dc0;         // [B,H] or null
+  float* db;          // [4H]
+  int direction;
+};
+struct RecShape {
+  int T, B, H, ldy, ndir, operand_dtype;
+};
+
+// Scratch bytes the recurrent passes need (max over both engines, fwd and bwd).
+size_t rec_workspace_bytes(const RecShape& s);
+// true if the persistent kernels can hold this shape (LDS, grid <= CUs).
+bool rec_persistent_supported(const RecShape& s, int num_cus, size_t max_lds);
+
+hipError_t rec_forward(hipStream_t stream, const RecShape& s, const RecFwdDir* dirs,
+                       const int32_t* seq_lens, void* ws, unsigned* flag, bool persistent, int* resident_err);
+hipError_t rec_backward(hipStream_t stream, const RecShape& s, const RecBwdDir* dirs,
+                        const int32_t* seq_lens, void* ws, unsigned* flag, bool persistent, int* resident_err);
+
+// dR += h0^T * dz(first processed valid frame of each sequence); no-op layout helper
+hipError_t add_h0_outer(hipStream_t stream, int T, int B, int H, int direction, const float* h0,
+                        const float* dz, const int32_t* seq_lens, float* dR);
+// column sums of a [rows, cols] matrix (stepwise engine's bias gradient)
+hipError_t column_sum(hipStream_t stream, const float* a, size_t rows, int cols, int lda, float* out);
+// zero the timeout flag
+hipError_t clear_flag(hipStream_t stream, unsigned* flag);
+
+struct DeviceInfo { int num_cus; size_t max_lds; };
+hipError_t device_info(DeviceInfo* out);
+
+}  // namespace rlstm
