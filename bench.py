@@ -1,0 +1,181 @@
+#!/usr/bin/env python3
+"""Benchmark of the deep BLSTM training pass (forward + back-propagation through time).
+
+One "step" = one blstm_stack_fwd_bwd call on one minibatch of synthetic,
+speech-shaped input that is already resident in HBM: all layers, both
+directions, gradients of every parameter.  Prints ONE JSON line:
+frames/s over valid (unpadded) frames, plus a roofline object for the
+dominant kernel (timed live with HIP events on its launch stream by the
+library's profiling hooks) and the CPU oracle timed on a bounded sample.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config3|config2]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X dense fp32 matrix peak
+PEAK_HBM_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def gemm_flops(kind, layer, wl):
+    """Algorithmic FLOP of one launch group of the given kind (2*M*N*K)."""
+    tb = wl.T * wl.B
+    din = wl.D if layer == 0 else 2 * wl.H
+    if kind == 0:
+        return 2.0 * tb * din * 4 * wl.H
+    if kind == 3:
+        return 2.0 * tb * din * 4 * wl.H
+    if kind == 4:
+        return 2.0 * tb * din * 4 * wl.H
+    if kind == 5:
+        return 2.0 * (wl.T - 1) * wl.B * wl.H * 4 * wl.H
+    if kind in (1, 2):
+        return 2.0 * 2 * tb * wl.H * 4 * wl.H      # both directions, h R (or dz R^T) over all steps
+    raise ValueError(kind)
+
+
+def rec_bytes(kind, wl):
+    """Algorithmic HBM bytes of one recurrent launch (both directions), fp32:
+    forward reads Z and writes gates, y, c; backward reads gates, c (twice), dy and writes dz."""
+    per_slot_dir = 4 * ((4 + 4 + 1 + 1) * wl.H) if kind == 1 else 4 * ((4 + 2 + 1 + 4) * wl.H)
+    return 2.0 * wl.T * wl.B * per_slot_dir + 2 * 4.0 * wl.H * 4 * wl.H
+
+
+def cpu_baseline(wl_full, seconds_budget=20.0):
+    """Times the oracle (as it is, numpy fp64) on a bounded sample of the same workload:
+    the same network on the first Ts frames of the minibatch."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import blstm_stack_backward, blstm_stack_forward
+    from paper_1608_00895_amd import synth
+
+    Ts = 512 if wl_full.H >= 400 else 500
+    Ts = min(Ts, wl_full.T)
+    lens = np.minimum(wl_full.seq_lens, Ts).astype(np.int32)
+    params = [[tuple(a.astype(np.float64) for a in p) for p in layer] for layer in wl_full.params]
+    x = wl_full.x[:Ts].astype(np.float64)
+    G = wl_full.G[:Ts].astype(np.float64)
+    t0 = time.perf_counter()
+    y, caches = blstm_stack_forward(x, params, lens)
+    blstm_stack_backward(caches, G)
+    dt = time.perf_counter() - t0
+    threads = max([i.get("num_threads", 1) for i in threadpool_info() if i.get("user_api") == "blas"] or [1])
+    frames = int(lens.sum())
+    return {"value": frames / dt, "unit": "frames/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{wl_full.name}: same {wl_full.L}-layer network, first {Ts} frames of all {wl_full.B} "
+                      f"sequences ({frames} frames), numpy fp64 forward+backward, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="config3", choices=["config2", "config3"])
+    ap.add_argument("--engine", type=int, default=0)
+    ap.add_argument("--one-stream", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_1608_00895_amd import binding as rl
+    from paper_1608_00895_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    wl = synth.config3() if args.workload == "config3" else synth.config2()
+    log(f"workload {wl.name}: L={wl.L} T={wl.T} B={wl.B} D={wl.D} H={wl.H} frames={wl.frames} slots={wl.T * wl.B}")
+
+    desc = rl.rblstm_desc(L=wl.L, T=wl.T, B=wl.B, D=wl.D, H=wl.H, operand_dtype=0, engine=args.engine)
+    x = torch.from_numpy(wl.x).to(dev)
+    sl = torch.from_numpy(wl.seq_lens).to(dev)
+    params = [torch.from_numpy(a).to(dev) for layer in wl.params for p in layer for a in p]
+    grads = [torch.empty_like(p) for p in params]
+    G = torch.from_numpy(wl.G).to(dev)
+    y_top = torch.empty((wl.T, wl.B, 2 * wl.H), device=dev)
+    reserve = torch.empty(rl.rblstm_reserve_bytes(desc), dtype=torch.uint8, device=dev)
+    ws = torch.empty(rl.rblstm_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+    sa = torch.cuda.current_stream()
+    sb = None if args.one_stream else torch.cuda.Stream()
+
+    def step():
+        # the bottom layer's input gradient is not needed for training and is skipped (dx = null)
+        rl.blstm_stack_fwd_bwd(desc, x, params, sl, G, y_top, grads, None, reserve, ws, sa, sb)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    assert rl.rlstm_last_timeout(ws) == 0
+    rl.rlstm_profile_read()
+    rl.rlstm_profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    rl.rlstm_profile_enable(False)
+    prof = rl.rlstm_profile_read(1 << 16)
+    assert rl.rlstm_last_timeout(ws) == 0
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    frames_per_s = wl.frames / (ms_per_step * 1e-3)
+
+    # per-kernel-group summary from the HIP events recorded inside the timed region
+    by_kind = {}
+    for kind, layer, ndir, ms in prof:
+        d = by_kind.setdefault(kind, {"ms": 0.0, "launches": 0, "flop": 0.0})
+        d["ms"] += ms
+        d["launches"] += 1
+        d["flop"] += gemm_flops(kind, layer, wl)
+    kernels = []
+    for kind, d in sorted(by_kind.items()):
+        e = {"kernel": rl.PROFILE_KINDS[kind], "launches_per_step": d["launches"] / args.steps,
+             "avg_ms": d["ms"] / d["launches"], "ms_per_step": d["ms"] / args.steps,
+             "tflops": d["flop"] / (d["ms"] * 1e-3) / 1e12}
+        if kind in (1, 2):
+            e["step_us"] = 1e3 * e["avg_ms"] / wl.T
+            e["hbm_gbs"] = rec_bytes(kind, wl) / (e["avg_ms"] * 1e-3) / 1e9
+        kernels.append(e)
+        log(e)
+    dom = max(kernels, key=lambda e: e["ms_per_step"])
+    roofline = {"kernel": dom["kernel"], "bound": "mfma", "achieved": dom["tflops"], "peak": PEAK_FP32_MFMA_TFLOPS,
+                "unit": "TFLOP/s", "frac": dom["tflops"] / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                "avg_launch_ms": dom["avg_ms"]}
+
+    out = {
+        "metric": "BLSTM train frames/sec (fwd+bwd)", "value": frames_per_s, "unit": "frames/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "layers": wl.L, "units_per_direction": wl.H, "batch": wl.B,
+                   "T_padded": wl.T, "valid_frames": wl.frames, "padded_slots": wl.T * wl.B,
+                   "padded_slots_per_s": wl.T * wl.B / (ms_per_step * 1e-3),
+                   "engine": "persistent" if args.engine in (0, 1) else "stepwise",
+                   "streams": 1 if args.one_stream else 2},
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

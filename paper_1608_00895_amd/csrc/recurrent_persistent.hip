@@ -1,0 +1,744 @@
+// Persistent engine of the recurrent part of the LSTM layer (Sec. 4.2 of the
+// RETURNN paper): the forward time loop h_{t-1} R + gating, and the pass back
+// through time, each as ONE cooperative launch that runs all T steps of up to
+// two independent directions.
+//
+// Forward.  The H units of a direction are dealt out to Gf workgroups, U units
+// each (U = 4 or 8).  A workgroup keeps the i, f, o, g columns of its units of
+// R in LDS for the whole kernel, keeps c and h of its (sequence, unit) pairs in
+// registers, and per step computes h_{t-1}[B x H] * R[:, its 4U columns] on the
+// matrix cores (v_mfma_f32_16x16x4_f32; K split over the 4 wavefronts, partial
+// tiles summed through LDS in a fixed order), then applies sigmoid / tanh, the
+// cell update and the validity mask (Sec. 5) and stores gates, y and c.
+//
+// Backward.  d h_{t-1} = d a_t R^T has K = 4H.  The workgroups form a PG x 4
+// grid: workgroup (p, q) multiplies the q-th quarter of the rows of d a_t with
+// the matching rows of R^T (kept in LDS) for the p-th group of 4U units, and
+// hands the partial tile to the four workgroups that own those units; each
+// owner adds the four partials in a fixed order.  Gate derivatives, d c and
+// d b stay in the owner's registers.
+//
+// Exchange between workgroups (h_t forwards; d a_t and the partial tiles
+// backwards) goes through global memory with device-scope (sc1) stores and
+// loads only, never through plain cached accesses:
+//   * h_t and d a_t: the producer stores its values, waits until the stores
+//     are acknowledged (s_waitcnt vmcnt(0)), then raises its own step flag;
+//     a consumer wavefront polls only the flags of the producers whose rows it
+//     multiplies, then fetches those rows with 16-byte device-scope buffer
+//     loads, all issued before the first MFMA.  The exchange arrays are laid
+//     out in MFMA operand order so each such load is a contiguous 1 KiB per
+//     wavefront.  Buffers are double-buffered by step parity.
+//   * partial tiles: every value travels as one 64-bit word (value, step tag),
+//     so the consumer polls the data itself and no flag round trip is needed.
+// There is no device-wide barrier and no cache write-back / invalidate in the
+// step loop.  All waits are bounded: on expiry the kernel raises the timeout
+// flag and every workgroup leaves its loop.
+#include "rlstm_internal.h"
+
+namespace rlstm {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef int intx4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr unsigned long long kWaitTimeoutTicks = 400000000ull;   // 4 s of the 100 MHz wall clock
+constexpr int CG = 16;                  // 16-byte loads in flight per lane
+constexpr int kAuxSc1 = 16;             // buffer-load cache policy: device scope
+
+// ---- bounded spinning --------------------------------------------------------
+struct Spin {
+  unsigned n = 0;
+  unsigned long long t0 = 0;
+  // call once per unsuccessful poll; true = give up
+  __device__ __forceinline__ bool expired(unsigned* err) {
+    if ((++n & 1023u) != 0) return false;
+    const unsigned long long now = wall_clock64();
+    if (t0 == 0) { t0 = now; return false; }
+    if (now - t0 > kWaitTimeoutTicks) return true;
+    return __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
+  }
+};
+
+__device__ __forceinline__ void st_dev(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev(unsigned* p, unsigned v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned ld_dev(const unsigned* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void wait_stores_acked() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ void compiler_fence() { __atomic_signal_fence(__ATOMIC_SEQ_CST); }
+
+// A wavefront waits until flags[first .. first+count) (clipped to limit) have all reached `want`.
+__device__ __forceinline__ bool wave_wait_flags(const unsigned* flags, int first, int count, int limit,
+                                                unsigned want, unsigned* err) {
+  const int lane = threadIdx.x & 63;
+  const bool mine = lane < count && first + lane < limit;
+  Spin sp;
+  bool ok = true;
+  for (;;) {
+    const bool ready = !mine || ld_dev(flags + first + lane) >= want;
+    if (__all(ready)) break;
+    if (sp.expired(err)) { ok = false; break; }
+  }
+  compiler_fence();
+  return ok;
+}
+
+// fast gate functions: v_exp_f32 / v_rcp_f32 (about 1e-6 absolute error)
+__device__ __forceinline__ float fsigmoid(float u) { return __builtin_amdgcn_rcpf(1.0f + __expf(-u)); }
+__device__ __forceinline__ float ftanh(float u) { return 2.0f * __builtin_amdgcn_rcpf(1.0f + __expf(-2.0f * u)) - 1.0f; }
+
+// position of element (row k of a wavefront's K range, sequence b) inside that wavefront's
+// operand-ordered block: [chunk][lane][4], L = (k/4)*MT + b/16, chunk = L/4, lane = (k%4)*16 + b%16
+template <int MT>
+__device__ __forceinline__ int operand_slot(int k, int b) {
+  const int L = (k >> 2) * MT + (b >> 4);
+  return ((L >> 2) * 64 + (k & 3) * 16 + (b & 15)) * 4 + (L & 3);
+}
+
+// One wavefront's share of a [B x K] * [K x 16*NT] product.  A rows come from the exchange
+// array (device-scope 16-byte loads, operand order), B rows from LDS (row stride ldb floats).
+template <int MT, int NT>
+__device__ __forceinline__ void wave_product(const float* xblock, int xblock_bytes, int nch, const float* bs, int ldb,
+                                             floatx4 (&acc)[MT][NT]) {
+  const int lane = threadIdx.x & 63, l16 = lane & 15, lq = lane >> 4;
+  __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(xblock), 0, xblock_bytes, 0x00020000);
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+  for (int c0 = 0; c0 < nch; c0 += CG) {
+    floatx4 v[CG];
+#pragma unroll
+    for (int q = 0; q < CG; ++q)
+      v[q] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, ((c0 + q) * 64 + lane) * 16, 0, kAuxSc1));
+    // chunks past nch read beyond the buffer resource's size and return zeros; their MFMAs are skipped
+#pragma unroll
+    for (int q = 0; q < CG; ++q) {
+      if (c0 + q < nch) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          constexpr int KPC = 4 / MT;                 // k-steps per chunk
+          const int ks = (c0 + q) * KPC + w / MT;
+          const int mt = w % MT;
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            const float bf = bs[(ks * 4 + lq) * ldb + nt * 16 + l16];
+            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(v[q][w], bf, acc[mt][nt], 0, 0, 0);
+          }
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// forward
+// ---------------------------------------------------------------------------
+struct PFwdDir {
+  float* zg; const float* R; const float* h0; const float* c0;
+  float* y; float* c; float* hT; float* cT;
+  float* hx;            // 2 x [4 wavefronts][nch][64][4]
+  unsigned* flags;      // [Gf]
+  int direction;
+};
+struct PFwdParams {
+  PFwdDir d[2];
+  const int32_t* seq_lens;
+  unsigned* err;
+  int T, B, H, ldy, Gf, Hp, nch;
+};
+
+template <int MT, int NT>
+__global__ __launch_bounds__(256) void lstm_fwd_persistent_kernel(PFwdParams p) {
+  constexpr int U = 4 * NT, NC = 16 * NT;
+  constexpr int EPT = (MT * 16 * U + 255) / 256;
+  extern __shared__ __align__(16) float lds[];
+  const int dir = blockIdx.x / p.Gf, wg = blockIdx.x % p.Gf;
+  const PFwdDir& D = p.d[dir];
+  const int T = p.T, B = p.B, H = p.H, Hp = p.Hp, nch = p.nch;
+  const int u0 = wg * U;
+  float* Rs = lds;                               // [Hp][NC]
+  float* Red = lds + (size_t)Hp * NC;            // [4][MT][NT][256]
+
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // wavefront-uniform, kept in a scalar register
+
+  // resident slice of R: slice column g*U + uu is column g*H + u0 + uu of R
+  for (int idx = tid; idx < Hp * NC; idx += 256) {
+    const int k = idx / NC, col = idx % NC;
+    const int g = col / U, u = u0 + col % U;
+    Rs[idx] = (k < H && u < H) ? D.R[(size_t)k * 4 * H + g * H + u] : 0.f;
+  }
+
+  const int KW = Hp / 4;                         // rows of h per wavefront
+  const int wblock = nch * 256;                  // floats of one wavefront's operand block
+  const size_t hxsz = (size_t)4 * wblock;
+
+  // carried state of the (sequence, unit) pairs this thread owns
+  float hreg[EPT], creg[EPT];
+  int eb[EPT], eu[EPT], elen[EPT], eslot[EPT];
+  bool ev[EPT];
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    const int j = tid + e * 256;
+    eb[e] = j / U; eu[e] = u0 + j % U;
+    ev[e] = (j < MT * 16 * U) && eb[e] < B && eu[e] < H;
+    hreg[e] = 0.f; creg[e] = 0.f; elen[e] = 0; eslot[e] = 0;
+    if (ev[e]) {
+      if (D.h0) hreg[e] = D.h0[(size_t)eb[e] * H + eu[e]];
+      if (D.c0) creg[e] = D.c0[(size_t)eb[e] * H + eu[e]];
+      elen[e] = min(max(p.seq_lens[eb[e]], 0), T);
+      eslot[e] = (eu[e] / KW) * wblock + operand_slot<MT>(eu[e] % KW, eb[e]);
+    }
+  }
+  __syncthreads();
+
+  const int prod_first = wave * KW / U, prod_count = KW / U;
+
+  float za[EPT][4];
+  {
+    const int t0 = D.direction > 0 ? 0 : T - 1;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e)
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        za[e][g] = ev[e] ? D.zg[((size_t)t0 * B + eb[e]) * 4 * H + g * H + eu[e]] : 0.f;
+  }
+
+  for (int s = 0; s < T; ++s) {
+    const int t = D.direction > 0 ? s : T - 1 - s;
+    const float* hprev = D.hx + (size_t)((s + 1) & 1) * hxsz;
+    float* hcur = D.hx + (size_t)(s & 1) * hxsz;
+
+    // h of the previous step: wait for the producers of this wavefront's rows, then h_prev * R
+    int fail = 0;
+    if (s > 0 && !wave_wait_flags(D.flags, prod_first, prod_count, p.Gf, (unsigned)s, p.err)) fail = 1;
+    floatx4 acc[MT][NT];
+    wave_product<MT, NT>(hprev + (size_t)wave * wblock, wblock * 4, nch, Rs + (size_t)wave * KW * NC, NC, acc);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+        *reinterpret_cast<floatx4*>(Red + ((wave * MT + mt) * NT + nt) * 256 + (tid & 63) * 4) = acc[mt][nt];
+    if (__syncthreads_or(fail)) {
+      if (tid == 0) st_dev(p.err, 1u);
+      return;
+    }
+
+    // gating, cell update, mask
+    float gate[EPT][4], yv[EPT];
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      if (!ev[e]) continue;
+      const int b = eb[e], uu = eu[e] - u0;
+      const int mt = b >> 4, r = b & 15;
+      float a[4];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int col = g * U + uu;
+        const int nt = col >> 4, n = col & 15;
+        const int src = ((r >> 2) * 16 + n) * 4 + (r & 3);    // accumulator (row r, col n) of a 16x16 tile
+        float sum = za[e][g];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) sum += Red[((w * MT + mt) * NT + nt) * 256 + src];
+        a[g] = sum;
+      }
+      const float gi = fsigmoid(a[0]), gf = fsigmoid(a[1]), go = fsigmoid(a[2]), gg = ftanh(a[3]);
+      const float cn = gf * creg[e] + gi * gg;
+      const float hn = go * ftanh(cn);
+      const bool valid = t < elen[e];
+      if (valid) { creg[e] = cn; hreg[e] = hn; }
+      gate[e][0] = gi; gate[e][1] = gf; gate[e][2] = go; gate[e][3] = gg;
+      yv[e] = valid ? hn : 0.f;
+      st_dev(hcur + eslot[e], hreg[e]);          // publish the carried h
+    }
+    wait_stores_acked();
+    __syncthreads();
+    if (tid == 0) st_dev(D.flags + wg, (unsigned)(s + 1));
+
+    // outputs of this frame (off the critical path), then the next frame's input part
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      if (!ev[e]) continue;
+      const size_t row = (size_t)t * B + eb[e];
+      float* zrow = D.zg + row * 4 * H + eu[e];
+      zrow[0] = gate[e][0]; zrow[H] = gate[e][1]; zrow[2 * H] = gate[e][2]; zrow[3 * H] = gate[e][3];
+      D.y[row * p.ldy + eu[e]] = yv[e];
+      D.c[row * H + eu[e]] = creg[e];
+    }
+    if (s + 1 < T) {
+      const int tn = D.direction > 0 ? s + 1 : T - 2 - s;
+#pragma unroll
+      for (int e = 0; e < EPT; ++e)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          za[e][g] = ev[e] ? D.zg[((size_t)tn * B + eb[e]) * 4 * H + g * H + eu[e]] : 0.f;
+    }
+  }
+
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    if (!ev[e]) continue;
+    if (D.hT) D.hT[(size_t)eb[e] * H + eu[e]] = hreg[e];
+    if (D.cT) D.cT[(size_t)eb[e] * H + eu[e]] = creg[e];
+  }
+}
+
+// ---------------------------------------------------------------------------
+// backward
+// ---------------------------------------------------------------------------
+struct PBwdDir {
+  float* zg; const float* R; const float* c; const float* c0; const float* dy;
+  const float* dhT; const float* dcT; float* dh0; float* dc0; float* db;
+  float* dzx;                   // 2 x [4 quarters][4 wavefronts][nch][64][4]
+  unsigned long long* part;     // 2 x [PG][4][Bp][UG] (value, tag)
+  unsigned* flags;              // [Gb]
+  int direction;
+};
+struct PBwdParams {
+  PBwdDir d[2];
+  const int32_t* seq_lens;
+  unsigned* err;
+  int T, B, H, ldy, PG, Hq, nch;
+};
+
+template <int MT, int NT>
+__global__ __launch_bounds__(256) void lstm_bwd_persistent_kernel(PBwdParams p) {
+  constexpr int U = 4 * NT, UG = 16 * NT, Bp = 16 * MT;
+  constexpr int EPT = (MT * 16 * U + 255) / 256;
+  extern __shared__ __align__(16) float lds[];
+  const int Gb = 4 * p.PG;
+  const int dir = blockIdx.x / Gb, wg = blockIdx.x % Gb;
+  const int pg = wg >> 2, qq = wg & 3;           // unit group, K quarter (also: which quarter of the group it owns)
+  const PBwdDir& D = p.d[dir];
+  const int T = p.T, B = p.B, H = p.H, Hq = p.Hq, nch = p.nch;
+  const int u0 = wg * U;                         // owned units
+  float* RTs = lds;                              // [4*Hq][UG]
+  float* Red = lds + (size_t)4 * Hq * UG;        // [4][MT][NT][256]
+
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // wavefront-uniform, kept in a scalar register
+  const int UW = Hq / 4;                         // units per wavefront of a quarter
+  // Quarters that hold no unit (small H) contribute nothing: their workgroups publish no partial
+  // tile and owners do not wait for one.  Every workgroup that does publish is paced by the flags
+  // of real producers, so no tile is overwritten before its owners have read it.
+  const int nq = (H + Hq - 1) / Hq;
+
+  // resident rows of R^T: row r = (wavefront w, unit ur of it, gate g) -> unit uk = qq*Hq + w*UW + ur;
+  // RTs[r][n] = R[pg*UG + n][g*H + uk]
+  for (int idx = tid; idx < 4 * Hq * UG; idx += 256) {
+    const int r = idx / UG, n = idx % UG;
+    const int w = r / Hq, rr = r % Hq;
+    const int uk = qq * Hq + w * UW + (rr >> 2), g = rr & 3;
+    const int un = pg * UG + n;
+    RTs[idx] = (uk < H && un < H) ? D.R[(size_t)un * 4 * H + g * H + uk] : 0.f;
+  }
+
+  const int wblock = nch * 256;                  // floats per (quarter, wavefront) operand block
+  const size_t xsz = (size_t)16 * wblock;
+  const size_t psz = (size_t)p.PG * 4 * Bp * UG;
+
+  float Dh[EPT], Dc[EPT], dbacc[EPT][4];
+  int eb[EPT], eu[EPT], elen[EPT], eslot[EPT];
+  bool ev[EPT];
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    const int j = tid + e * 256;
+    eb[e] = j / U; eu[e] = u0 + j % U;
+    ev[e] = (j < MT * 16 * U) && eb[e] < B && eu[e] < H;
+    Dh[e] = 0.f; Dc[e] = 0.f; elen[e] = 0; eslot[e] = 0;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) dbacc[e][g] = 0.f;
+    if (ev[e]) {
+      if (D.dhT) Dh[e] = D.dhT[(size_t)eb[e] * H + eu[e]];
+      if (D.dcT) Dc[e] = D.dcT[(size_t)eb[e] * H + eu[e]];
+      elen[e] = min(max(p.seq_lens[eb[e]], 0), T);
+      // d a of unit u, gate g sits in quarter u/Hq, wavefront (u%Hq)/UW, row ((u%Hq)%UW)*4 + g
+      const int ul = eu[e] % Hq;
+      eslot[e] = ((eu[e] / Hq) * 4 + ul / UW) * wblock + operand_slot<MT>((ul % UW) * 4, eb[e]);
+    }
+  }
+  __syncthreads();
+
+  // producers of this wavefront's rows: owners of units [qq*Hq + wave*UW, +UW)
+  const int prod_first = (qq * Hq + wave * UW) / U, prod_count = UW / U;
+
+  // inputs of the first visited frame
+  float gin[EPT][4], cti[EPT], cpi[EPT], dyi[EPT];
+  auto load_inputs = [&](int t, int tprev, bool first) {
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      if (!ev[e]) continue;
+      const size_t row = (size_t)t * B + eb[e];
+      const float* zrow = D.zg + row * 4 * H + eu[e];
+      gin[e][0] = zrow[0]; gin[e][1] = zrow[H]; gin[e][2] = zrow[2 * H]; gin[e][3] = zrow[3 * H];
+      cti[e] = first ? D.c[row * H + eu[e]] : cpi[e];      // c of this frame = c_prev of the frame visited before
+      if (tprev >= 0 && tprev < T) cpi[e] = D.c[((size_t)tprev * B + eb[e]) * H + eu[e]];
+      else cpi[e] = D.c0 ? D.c0[(size_t)eb[e] * H + eu[e]] : 0.f;
+      dyi[e] = D.dy[row * p.ldy + eu[e]];
+    }
+  };
+  {
+    const int t = D.direction > 0 ? T - 1 : 0;
+    load_inputs(t, D.direction > 0 ? t - 1 : t + 1, true);
+  }
+
+  bool vprev[EPT];
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) vprev[e] = false;
+
+  // sums the four partial tiles of step `step` for the owned pairs (tag = step + 1)
+  auto collect = [&](int step, float (&out)[EPT]) -> int {
+    int fail = 0;
+    const unsigned long long* pbuf = D.part + (size_t)(step & 1) * psz;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      out[e] = 0.f;
+      if (!ev[e]) continue;
+      const int n = qq * U + (eu[e] - u0);
+      const unsigned long long* src = pbuf + ((size_t)(pg * 4) * Bp + eb[e]) * UG + n;
+      unsigned long long v[4];
+      Spin sp;
+      for (;;) {
+        bool ok = true;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          v[k] = 0ull;
+          if (k < nq) {
+            v[k] = __hip_atomic_load(src + (size_t)k * Bp * UG, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            ok = ok && (unsigned)(v[k] >> 32) == (unsigned)(step + 1);
+          }
+        }
+        if (ok) break;
+        if (sp.expired(p.err)) { fail = 1; break; }
+      }
+      float sum = 0.f;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) sum += __uint_as_float((unsigned)v[k]);
+      out[e] = sum;
+    }
+    return fail;
+  };
+
+  for (int s = 0; s < T; ++s) {
+    // frames are visited in the reverse of the forward processing order
+    const int t = D.direction > 0 ? T - 1 - s : s;
+    float* dzcur = D.dzx + (size_t)(s & 1) * xsz;
+    int fail = 0;
+
+    // d h carried into this frame: product of the previous step (+ carried d h where that frame was invalid)
+    if (s > 0) {
+      float g[EPT];
+      fail = collect(s - 1, g);
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) Dh[e] = vprev[e] ? g[e] : g[e] + Dh[e];
+    }
+
+    // gate derivatives
+    float dz[EPT][4];
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) dz[e][g] = 0.f;
+      vprev[e] = false;
+      if (!ev[e]) continue;
+      const bool m = t < elen[e];
+      vprev[e] = m;
+      if (m) {
+        const float gi = gin[e][0], gf = gin[e][1], go = gin[e][2], gg = gin[e][3];
+        const float tc = ftanh(cti[e]);
+        const float dh = dyi[e] + Dh[e];
+        const float d_o = dh * tc;
+        const float dc = Dc[e] + dh * go * (1.0f - tc * tc);
+        dz[e][0] = dc * gg * gi * (1.0f - gi);
+        dz[e][1] = dc * cpi[e] * gf * (1.0f - gf);
+        dz[e][2] = d_o * go * (1.0f - go);
+        dz[e][3] = dc * gi * (1.0f - gg * gg);
+        Dc[e] = dc * gf;
+      }
+      // rows (unit, gate 0..3) are lanes 0, 16, 32, 48 apart in operand order
+#pragma unroll
+      for (int g = 0; g < 4; ++g) st_dev(dzcur + eslot[e] + g * 64, dz[e][g]);
+    }
+    wait_stores_acked();
+    if (__syncthreads_or(fail)) {
+      if (tid == 0) st_dev(p.err, 1u);
+      return;
+    }
+    if (tid == 0) st_dev(D.flags + wg, (unsigned)(s + 1));
+
+    // d a of this frame in place over the gates; bias gradient; next frame's inputs
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      if (!ev[e]) continue;
+      float* zrow = D.zg + ((size_t)t * B + eb[e]) * 4 * H + eu[e];
+      zrow[0] = dz[e][0]; zrow[H] = dz[e][1]; zrow[2 * H] = dz[e][2]; zrow[3 * H] = dz[e][3];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) dbacc[e][g] += dz[e][g];
+    }
+    if (s + 1 < T) {
+      const int tn = D.direction > 0 ? T - 2 - s : s + 1;
+      load_inputs(tn, D.direction > 0 ? tn - 1 : tn + 1, false);
+    }
+
+    // this workgroup's quarter of d a_t R^T for its unit group
+    if (qq >= nq) continue;
+    fail = 0;
+    if (!wave_wait_flags(D.flags, prod_first, prod_count, Gb, (unsigned)(s + 1), p.err)) fail = 1;
+    floatx4 acc[MT][NT];
+    wave_product<MT, NT>(dzcur + (size_t)(qq * 4 + wave) * wblock, wblock * 4, nch, RTs + (size_t)wave * Hq * UG, UG, acc);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+        *reinterpret_cast<floatx4*>(Red + ((wave * MT + mt) * NT + nt) * 256 + (tid & 63) * 4) = acc[mt][nt];
+    if (__syncthreads_or(fail)) {
+      if (tid == 0) st_dev(p.err, 1u);
+      return;
+    }
+    // sum the four wavefronts' tiles in order and hand (value, tag) to the owners
+    {
+      unsigned long long* pbuf = D.part + (size_t)(s & 1) * psz + (size_t)(pg * 4 + qq) * Bp * UG;
+      const int ln = tid >> 2, reg = tid & 3;
+      const int row = 4 * (ln >> 4) + reg, col = ln & 15;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          float sum = 0.f;
+#pragma unroll
+          for (int w = 0; w < 4; ++w) sum += Red[((w * MT + mt) * NT + nt) * 256 + tid];
+          const unsigned long long word = ((unsigned long long)(unsigned)(s + 1) << 32) | __float_as_uint(sum);
+          __hip_atomic_store(pbuf + (size_t)(mt * 16 + row) * UG + nt * 16 + col, word, __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    // Red is rewritten only after the next step's workgroup barrier
+  }
+
+  // gradient w.r.t. the initial state, and the bias gradient of the owned columns
+  {
+    float g[EPT];
+    const int fail = collect(T - 1, g);
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) Dh[e] = vprev[e] ? g[e] : g[e] + Dh[e];
+    if (__syncthreads_or(fail)) {
+      if (tid == 0) st_dev(p.err, 1u);
+      return;
+    }
+  }
+  float* stage = Red;                            // [Bp][4U]
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    const int j = tid + e * 256;
+    if (j < MT * 16 * U) {
+      const int b = j / U, uu = j % U;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) stage[b * 4 * U + g * U + uu] = ev[e] ? dbacc[e][g] : 0.f;
+    }
+    if (!ev[e]) continue;
+    if (D.dh0) D.dh0[(size_t)eb[e] * H + eu[e]] = Dh[e];
+    if (D.dc0) D.dc0[(size_t)eb[e] * H + eu[e]] = Dc[e];
+  }
+  __syncthreads();
+  if (tid < 4 * U) {
+    const int g = tid / U, u = u0 + tid % U;
+    if (u < H) {
+      float sum = 0.f;
+      for (int b = 0; b < B; ++b) sum += stage[b * 4 * U + tid];
+      D.db[g * H + u] = sum;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// set-up kernel: clears flags, exchange arrays and tags; seeds h0 in operand order
+// ---------------------------------------------------------------------------
+struct PrepParams {
+  unsigned* zero_words[2]; size_t nzero[2];       // per direction: words to clear (flags + exchange [+ partial tiles])
+  float* hx1[2]; const float* h0[2];              // forward only: buffer 1 of the h exchange, h0 or null
+  int ndir, B, H, KW, wblock, MT;
+};
+__global__ __launch_bounds__(256) void prep_kernel(PrepParams p) {
+  const size_t gtid = (size_t)blockIdx.x * 256 + threadIdx.x, gsz = (size_t)gridDim.x * 256;
+  for (int d = 0; d < p.ndir; ++d) {
+    for (size_t i = gtid; i < p.nzero[d]; i += gsz) p.zero_words[d][i] = 0u;
+  }
+  // h0 lands in words this same thread grid has just cleared; order the two phases per thread
+  // by letting each thread write only h0 elements, after all clears, in a second kernel launch.
+}
+__global__ __launch_bounds__(256) void seed_h0_kernel(PrepParams p) {
+  const size_t gtid = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (gtid >= (size_t)p.B * p.H) return;
+  const int b = (int)(gtid / p.H), u = (int)(gtid % p.H);
+  for (int d = 0; d < p.ndir; ++d) {
+    if (!p.h0[d]) continue;
+    const int k = u % p.KW;
+    int slot;
+    if (p.MT == 1) slot = operand_slot<1>(k, b);
+    else if (p.MT == 2) slot = operand_slot<2>(k, b);
+    else slot = operand_slot<4>(k, b);
+    p.hx1[d][(size_t)(u / p.KW) * p.wblock + slot] = p.h0[d][gtid];
+  }
+}
+
+// ---- host side ----------------------------------------------------------------
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Plan {
+  bool ok;
+  int MT, NT, U, UG, Bp;
+  int Gf, Hp, nchF;
+  int PG, Gb, Hq, nchB;
+  size_t ldsF, ldsB;
+};
+
+Plan make_plan(const RecShape& s, int num_cus, size_t max_lds) {
+  Plan pl{};
+  pl.ok = false;
+  if (s.operand_dtype != 0) return pl;
+  if (s.B < 1 || s.B > 64 || s.H < 1) return pl;
+  pl.MT = s.B <= 16 ? 1 : (s.B <= 32 ? 2 : 4);
+  pl.Bp = pl.MT * 16;
+  const int per_dir = num_cus / s.ndir;
+  for (int NT = 1; NT <= 2; ++NT) {
+    const int U = 4 * NT, UG = 16 * NT;
+    const int Gf = (s.H + U - 1) / U;
+    const int PG = (s.H + UG - 1) / UG;
+    const int Gb = 4 * PG;
+    if (Gf > per_dir || Gb > per_dir) continue;
+    const int Hp = (int)align_up((size_t)s.H, 64);
+    const int Hq = (int)align_up((size_t)PG * U, 32);
+    // a wavefront polls at most 64 producers
+    if (Hp / 4 / U > 64 || Hq / 4 / U > 64) continue;
+    const size_t red = (size_t)4 * pl.MT * NT * 256;
+    const size_t lf = ((size_t)Hp * 16 * NT + red) * sizeof(float);
+    const size_t lb = ((size_t)4 * Hq * UG + red) * sizeof(float);
+    if (lf > max_lds || lb > max_lds) continue;
+    pl.ok = true; pl.NT = NT; pl.U = U; pl.UG = UG;
+    pl.Gf = Gf; pl.Hp = Hp; pl.nchF = (Hp / 16) * pl.MT / 4;
+    pl.PG = PG; pl.Gb = Gb; pl.Hq = Hq; pl.nchB = (Hq / 4) * pl.MT / 4;
+    pl.ldsF = lf; pl.ldsB = lb;
+    return pl;
+  }
+  return pl;
+}
+
+template <typename K>
+hipError_t coop_launch(K kernel, int grid, size_t lds, hipStream_t stream, void* params, int* resident_err) {
+  hipError_t e = hipSuccess;
+  if (lds > 48 * 1024) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  void* args[] = {params};
+  e = hipLaunchCooperativeKernel(reinterpret_cast<const void*>(kernel), dim3((unsigned)grid), dim3(256), args,
+                                 (unsigned)lds, stream);
+  if (e == hipErrorCooperativeLaunchTooLarge) { *resident_err = 1; (void)hipGetLastError(); }
+  return e;
+}
+
+}  // namespace
+
+bool persistent_supported(const RecShape& s, int num_cus, size_t max_lds) {
+  return make_plan(s, num_cus, max_lds).ok;
+}
+
+// Upper bound (independent of the device) of the per-direction scratch, in bytes:
+// [flags 1 KiB][exchange arrays][partial tiles].
+size_t persistent_scratch_bytes_per_dir(const RecShape& s) {
+  const size_t Bp = s.B <= 16 ? 16 : (s.B <= 32 ? 32 : 64);
+  const size_t Hp = align_up((size_t)s.H, 64);
+  const size_t Hq = align_up((size_t)s.H / 4 + 8, 32);
+  const size_t exch = 2 * (Hp > 16 * Hq ? Hp : 16 * Hq) * Bp * sizeof(float);
+  const size_t part = 2 * 4 * Bp * ((size_t)s.H + 32) * sizeof(unsigned long long);
+  return 1024 + align_up(exch, 256) + align_up(part, 256);
+}
+
+hipError_t persistent_forward(hipStream_t stream, const RecShape& s, const RecFwdDir* dirs, const int32_t* seq_lens,
+                              char* const* scratch, unsigned* err, int* resident_err) {
+  DeviceInfo di;
+  hipError_t e = device_info(&di);
+  if (e != hipSuccess) return e;
+  const Plan pl = make_plan(s, di.num_cus, di.max_lds);
+  if (!pl.ok) { *resident_err = 1; return hipErrorInvalidValue; }
+  const int wblock = pl.nchF * 256;
+  PrepParams pp{};
+  PFwdParams kp{};
+  for (int d = 0; d < s.ndir; ++d) {
+    unsigned* flags = reinterpret_cast<unsigned*>(scratch[d]);
+    float* hx = reinterpret_cast<float*>(scratch[d] + 1024);
+    pp.zero_words[d] = flags;
+    pp.nzero[d] = 256 + (size_t)2 * 4 * wblock;
+    pp.hx1[d] = hx + (size_t)4 * wblock;
+    pp.h0[d] = dirs[d].h0;
+    PFwdDir& k = kp.d[d];
+    k.zg = dirs[d].zg; k.R = dirs[d].R; k.h0 = dirs[d].h0; k.c0 = dirs[d].c0;
+    k.y = dirs[d].y; k.c = dirs[d].c; k.hT = dirs[d].hT; k.cT = dirs[d].cT;
+    k.hx = hx; k.flags = flags; k.direction = dirs[d].direction;
+  }
+  pp.ndir = s.ndir; pp.B = s.B; pp.H = s.H; pp.KW = pl.Hp / 4; pp.wblock = wblock; pp.MT = pl.MT;
+  kp.seq_lens = seq_lens; kp.err = err;
+  kp.T = s.T; kp.B = s.B; kp.H = s.H; kp.ldy = s.ldy; kp.Gf = pl.Gf; kp.Hp = pl.Hp; kp.nch = pl.nchF;
+  hipLaunchKernelGGL(prep_kernel, dim3(64), dim3(256), 0, stream, pp);
+  if (pp.h0[0] || (s.ndir > 1 && pp.h0[1])) {
+    const size_t bh = (size_t)s.B * s.H;
+    hipLaunchKernelGGL(seed_h0_kernel, dim3((unsigned)((bh + 255) / 256)), dim3(256), 0, stream, pp);
+  }
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int grid = pl.Gf * s.ndir;
+#define RLSTM_FWD_CASE(MT_, NT_)                                                                      \
+  if (pl.MT == MT_ && pl.NT == NT_)                                                                   \
+    return coop_launch(lstm_fwd_persistent_kernel<MT_, NT_>, grid, pl.ldsF, stream, &kp, resident_err);
+  RLSTM_FWD_CASE(1, 1) RLSTM_FWD_CASE(2, 1) RLSTM_FWD_CASE(4, 1)
+  RLSTM_FWD_CASE(1, 2) RLSTM_FWD_CASE(2, 2) RLSTM_FWD_CASE(4, 2)
+#undef RLSTM_FWD_CASE
+  return hipErrorInvalidValue;
+}
+
+hipError_t persistent_backward(hipStream_t stream, const RecShape& s, const RecBwdDir* dirs, const int32_t* seq_lens,
+                               char* const* scratch, unsigned* err, int* resident_err) {
+  DeviceInfo di;
+  hipError_t e = device_info(&di);
+  if (e != hipSuccess) return e;
+  const Plan pl = make_plan(s, di.num_cus, di.max_lds);
+  if (!pl.ok) { *resident_err = 1; return hipErrorInvalidValue; }
+  const int wblock = pl.nchB * 256;
+  const size_t exch_floats = (size_t)2 * 16 * wblock;
+  const size_t part_words = (size_t)2 * pl.PG * 4 * pl.Bp * pl.UG;
+  PrepParams pp{};
+  PBwdParams kp{};
+  for (int d = 0; d < s.ndir; ++d) {
+    unsigned* flags = reinterpret_cast<unsigned*>(scratch[d]);
+    float* dzx = reinterpret_cast<float*>(scratch[d] + 1024);
+    unsigned long long* part = reinterpret_cast<unsigned long long*>(dzx + align_up(exch_floats, 64));
+    pp.zero_words[d] = flags;
+    pp.nzero[d] = 256 + align_up(exch_floats, 64) + 2 * part_words;
+    PBwdDir& k = kp.d[d];
+    k.zg = dirs[d].zg; k.R = dirs[d].R; k.c = dirs[d].c; k.c0 = dirs[d].c0; k.dy = dirs[d].dy;
+    k.dhT = dirs[d].dhT; k.dcT = dirs[d].dcT; k.dh0 = dirs[d].dh0; k.dc0 = dirs[d].dc0; k.db = dirs[d].db;
+    k.dzx = dzx; k.part = part; k.flags = flags; k.direction = dirs[d].direction;
+  }
+  pp.ndir = s.ndir;
+  kp.seq_lens = seq_lens; kp.err = err;
+  kp.T = s.T; kp.B = s.B; kp.H = s.H; kp.ldy = s.ldy; kp.PG = pl.PG; kp.Hq = pl.Hq; kp.nch = pl.nchB;
+  hipLaunchKernelGGL(prep_kernel, dim3(128), dim3(256), 0, stream, pp);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int grid = pl.Gb * s.ndir;
+#define RLSTM_BWD_CASE(MT_, NT_)                                                                      \
+  if (pl.MT == MT_ && pl.NT == NT_)                                                                   \
+    return coop_launch(lstm_bwd_persistent_kernel<MT_, NT_>, grid, pl.ldsB, stream, &kp, resident_err);
+  RLSTM_BWD_CASE(1, 1) RLSTM_BWD_CASE(2, 1) RLSTM_BWD_CASE(4, 1)
+  RLSTM_BWD_CASE(1, 2) RLSTM_BWD_CASE(2, 2) RLSTM_BWD_CASE(4, 2)
+#undef RLSTM_BWD_CASE
+  return hipErrorInvalidValue;
+}
+
+}  // namespace rlstm

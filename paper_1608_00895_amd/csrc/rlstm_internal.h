@@ -75,7 +75,20 @@ hipError_t rec_forward(hipStream_t stream, const RecShape& s, const RecFwdDir* d
 hipError_t rec_backward(hipStream_t stream, const RecShape& s, const RecBwdDir* dirs,
                         const int32_t* seq_lens, void* ws, unsigned* flag, bool persistent, int* resident_err);
 
-// dR += h0^T * dz(first processed valid frame of each sequence); no-op layout helper
+// the two engines behind rec_forward / rec_backward
+bool persistent_supported(const RecShape& s, int num_cus, size_t max_lds);
+size_t persistent_scratch_bytes_per_dir(const RecShape& s);
+hipError_t persistent_forward(hipStream_t stream, const RecShape& s, const RecFwdDir* dirs, const int32_t* seq_lens,
+                              char* const* scratch, unsigned* err, int* resident_err);
+hipError_t persistent_backward(hipStream_t stream, const RecShape& s, const RecBwdDir* dirs, const int32_t* seq_lens,
+                               char* const* scratch, unsigned* err, int* resident_err);
+size_t stepwise_scratch_floats_per_dir(const RecShape& s);
+hipError_t stepwise_forward(hipStream_t stream, const RecShape& s, const RecFwdDir* dirs, const int32_t* seq_lens,
+                            float* const* buf);
+hipError_t stepwise_backward(hipStream_t stream, const RecShape& s, const RecBwdDir* dirs, const int32_t* seq_lens,
+                             float* const* buf);
+
+// dR += h0^T * dz(first processed valid frame of each sequence)
 hipError_t add_h0_outer(hipStream_t stream, int T, int B, int H, int direction, const float* h0,
                         const float* dz, const int32_t* seq_lens, float* dR);
 // column sums of a [rows, cols] matrix (stepwise engine's bias gradient)
