@@ -38,10 +38,10 @@
  *     is enqueued when an argument check fails.  rlstm_strerror() names a code.
  *   - seq_lens values are clamped on the device to [0, T].
  *   - The recurrent kernels are persistent: all of their workgroups must be
- *     resident at once, so they are launched cooperatively and the call fails
- *     with RLSTM_ERESIDENT when the device cannot hold them.  Their
- *     per-step device-wide wait is bounded; if it ever expires the kernel
- *     stops stepping and sets a flag that rlstm_last_timeout() reports.
+ *     resident at once, so the call fails with RLSTM_ERESIDENT when the device
+ *     cannot hold them.  Their waits on each other are bounded; if one ever
+ *     expires the kernel stops stepping and sets a flag that
+ *     rlstm_last_timeout() reports.
  */
 #ifndef RLSTM_H
 #define RLSTM_H
@@ -189,7 +189,8 @@ RLSTM_API int rlstm_gemm_f32(int trans_a, int trans_b, int M, int N, int K,
  * HIP events on the stream it is launched on.  rlstm_profile_read() waits for
  * the recorded events, writes up to max_entries entries (in launch order) and
  * clears the record; it returns the number of entries recorded (which may
- * exceed max_entries) or a negative code.  Not thread-safe.
+ * exceed max_entries) or a negative code; when timing has been switched off it
+ * also destroys the events it had created.  Not thread-safe.
  *   kind: 0 input projection X W + b        1 recurrent forward pass (all T steps)
  *         2 pass back through time          3 input gradient dZ W^T
  *         4 weight gradient X^T dZ          5 recurrent weight gradient Hprev^T dZ

@@ -252,6 +252,11 @@ int rlstm_profile_read(rlstm_profile_entry* out, int max_entries) {
     g_prof_pool.push_back(r.b);
   }
   g_prof.clear();
+  if (!g_prof_on) {
+    // timing is off: give the events back to the runtime so that none outlives the caller's use of the library
+    for (hipEvent_t ev : g_prof_pool) (void)hipEventDestroy(ev);
+    g_prof_pool.clear();
+  }
   return rc;
 }
 

@@ -1,6 +1,6 @@
 // Persistent engine of the recurrent part of the LSTM layer (Sec. 4.2 of the
 // RETURNN paper): the forward time loop h_{t-1} R + gating, and the pass back
-// through time, each as ONE cooperative launch that runs all T steps of up to
+// through time, each as ONE launch that runs all T steps of up to
 // two independent directions.
 //
 // Forward.  The H units of a direction are dealt out to Gf workgroups, U units
@@ -629,18 +629,25 @@ Plan make_plan(const RecShape& s, int num_cus, size_t max_lds) {
   return pl;
 }
 
+// Launches a kernel whose workgroups wait on each other.  All of them must be resident at
+// once: the grid may not exceed what the device can hold of this kernel (checked here).
+// A plain launch is used; other work on the device can delay residency but not prevent it,
+// and the kernels' own waits are bounded.
 template <typename K>
-hipError_t coop_launch(K kernel, int grid, size_t lds, hipStream_t stream, void* params, int* resident_err) {
+hipError_t resident_launch(K kernel, int grid, size_t lds, int num_cus, hipStream_t stream, void* params,
+                           int* resident_err) {
   hipError_t e = hipSuccess;
+  const void* fn = reinterpret_cast<const void*>(kernel);
   if (lds > 48 * 1024) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
   }
+  int per_cu = 0;
+  e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 256, lds);
+  if (e != hipSuccess) return e;
+  if ((long long)per_cu * num_cus < grid) { *resident_err = 1; return hipErrorCooperativeLaunchTooLarge; }
   void* args[] = {params};
-  e = hipLaunchCooperativeKernel(reinterpret_cast<const void*>(kernel), dim3((unsigned)grid), dim3(256), args,
-                                 (unsigned)lds, stream);
-  if (e == hipErrorCooperativeLaunchTooLarge) { *resident_err = 1; (void)hipGetLastError(); }
-  return e;
+  return hipLaunchKernel(fn, dim3((unsigned)grid), dim3(256), args, lds, stream);
 }
 
 }  // namespace
@@ -695,7 +702,7 @@ hipError_t persistent_forward(hipStream_t stream, const RecShape& s, const RecFw
   const int grid = pl.Gf * s.ndir;
 #define RLSTM_FWD_CASE(MT_, NT_)                                                                      \
   if (pl.MT == MT_ && pl.NT == NT_)                                                                   \
-    return coop_launch(lstm_fwd_persistent_kernel<MT_, NT_>, grid, pl.ldsF, stream, &kp, resident_err);
+    return resident_launch(lstm_fwd_persistent_kernel<MT_, NT_>, grid, pl.ldsF, di.num_cus, stream, &kp, resident_err);
   RLSTM_FWD_CASE(1, 1) RLSTM_FWD_CASE(2, 1) RLSTM_FWD_CASE(4, 1)
   RLSTM_FWD_CASE(1, 2) RLSTM_FWD_CASE(2, 2) RLSTM_FWD_CASE(4, 2)
 #undef RLSTM_FWD_CASE
@@ -734,7 +741,7 @@ hipError_t persistent_backward(hipStream_t stream, const RecShape& s, const RecB
   const int grid = pl.Gb * s.ndir;
 #define RLSTM_BWD_CASE(MT_, NT_)                                                                      \
   if (pl.MT == MT_ && pl.NT == NT_)                                                                   \
-    return coop_launch(lstm_bwd_persistent_kernel<MT_, NT_>, grid, pl.ldsB, stream, &kp, resident_err);
+    return resident_launch(lstm_bwd_persistent_kernel<MT_, NT_>, grid, pl.ldsB, di.num_cus, stream, &kp, resident_err);
   RLSTM_BWD_CASE(1, 1) RLSTM_BWD_CASE(2, 1) RLSTM_BWD_CASE(4, 1)
   RLSTM_BWD_CASE(1, 2) RLSTM_BWD_CASE(2, 2) RLSTM_BWD_CASE(4, 2)
 #undef RLSTM_BWD_CASE
