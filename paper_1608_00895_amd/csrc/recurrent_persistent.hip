@@ -72,15 +72,27 @@ __device__ __forceinline__ unsigned ld_dev(const unsigned* p) {
 __device__ __forceinline__ void wait_stores_acked() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 __device__ __forceinline__ void compiler_fence() { __atomic_signal_fence(__ATOMIC_SEQ_CST); }
 
+// Step flags.  Every producer keeps kFlagCopies copies of its flag, each copy set in its own
+// 4 KiB block, and a consumer workgroup polls copy (its index mod kFlagCopies): polls of one
+// memory line by many wavefronts are served one after the other, so with a single copy the
+// ~125 pollers of each line would queue behind each other for microseconds.
+constexpr int kFlagCopies = 64;
+constexpr int kFlagCopyStride = 1024;            // unsigned words between copies
+
+__device__ __forceinline__ void publish_flag(unsigned* flags, int wg, unsigned value) {
+  if (threadIdx.x < kFlagCopies) st_dev(flags + threadIdx.x * kFlagCopyStride + wg, value);
+}
+
 // A wavefront waits until flags[first .. first+count) (clipped to limit) have all reached `want`.
 __device__ __forceinline__ bool wave_wait_flags(const unsigned* flags, int first, int count, int limit,
                                                 unsigned want, unsigned* err) {
   const int lane = threadIdx.x & 63;
   const bool mine = lane < count && first + lane < limit;
+  const unsigned* src = flags + (mine ? first + lane : first);
   Spin sp;
   bool ok = true;
   for (;;) {
-    const bool ready = !mine || ld_dev(flags + first + lane) >= want;
+    const bool ready = !mine || ld_dev(src) >= want;
     if (__all(ready)) break;
     if (sp.expired(err)) { ok = false; break; }
   }
@@ -153,23 +165,36 @@ struct PFwdParams {
   int T, B, H, ldy, Gf, Hp, nch;
 };
 
+// Workgroup = 4 compute wavefronts (threads 0..255) + 1 I/O wavefront (threads 256..319).
+// The compute wavefronts touch global memory only through the device-scope exchange; the I/O
+// wavefront moves the frame's input part from HBM into LDS one step ahead and the frame's
+// outputs (gates, y, c) from LDS to HBM one step behind, so HBM latency and store
+// acknowledgements never sit in the step's dependency chain.
+constexpr int kBlockThreads = 320;
+
 template <int MT, int NT>
-__global__ __launch_bounds__(256) void lstm_fwd_persistent_kernel(PFwdParams p) {
+__global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwdParams p) {
   constexpr int U = 4 * NT, NC = 16 * NT;
-  constexpr int EPT = (MT * 16 * U + 255) / 256;
+  constexpr int NE = MT * 16 * U;                // (sequence, unit) pairs of this workgroup (multiple of 64)
+  constexpr int EPT = (NE + 255) / 256;          // pairs per compute thread
+  constexpr int EPL = NE / 64;                   // pairs per I/O lane
   extern __shared__ __align__(16) float lds[];
   const int dir = blockIdx.x / p.Gf, wg = blockIdx.x % p.Gf;
   const PFwdDir& D = p.d[dir];
   const int T = p.T, B = p.B, H = p.H, Hp = p.Hp, nch = p.nch;
   const int u0 = wg * U;
   float* Rs = lds;                               // [Hp][NC]
-  float* Red = lds + (size_t)Hp * NC;            // [4][MT][NT][256]
+  float* Red = Rs + (size_t)Hp * NC;             // [4][MT][NT][256]
+  float* zin = Red + 4 * MT * NT * 256;          // [2][4][NE]  input part of the frame, per gate
+  float* gout = zin + 2 * 4 * NE;                // [2][6][NE]  gates i,f,o,g, y, c of the frame
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // wavefront-uniform, kept in a scalar register
+  const bool is_io = wave == 4;
+  const int lane = tid & 63;
 
   // resident slice of R: slice column g*U + uu is column g*H + u0 + uu of R
-  for (int idx = tid; idx < Hp * NC; idx += 256) {
+  for (int idx = tid; idx < Hp * NC; idx += kBlockThreads) {
     const int k = idx / NC, col = idx % NC;
     const int g = col / U, u = u0 + col % U;
     Rs[idx] = (k < H && u < H) ? D.R[(size_t)k * 4 * H + g * H + u] : 0.f;
@@ -179,7 +204,7 @@ __global__ __launch_bounds__(256) void lstm_fwd_persistent_kernel(PFwdParams p) 
   const int wblock = nch * 256;                  // floats of one wavefront's operand block
   const size_t hxsz = (size_t)4 * wblock;
 
-  // carried state of the (sequence, unit) pairs this thread owns
+  // compute threads: carried state of the pairs they own
   float hreg[EPT], creg[EPT];
   int eb[EPT], eu[EPT], elen[EPT], eslot[EPT];
   bool ev[EPT];
@@ -187,7 +212,7 @@ __global__ __launch_bounds__(256) void lstm_fwd_persistent_kernel(PFwdParams p) 
   for (int e = 0; e < EPT; ++e) {
     const int j = tid + e * 256;
     eb[e] = j / U; eu[e] = u0 + j % U;
-    ev[e] = (j < MT * 16 * U) && eb[e] < B && eu[e] < H;
+    ev[e] = !is_io && (j < NE) && eb[e] < B && eu[e] < H;
     hreg[e] = 0.f; creg[e] = 0.f; elen[e] = 0; eslot[e] = 0;
     if (ev[e]) {
       if (D.h0) hreg[e] = D.h0[(size_t)eb[e] * H + eu[e]];
@@ -196,90 +221,122 @@ __global__ __launch_bounds__(256) void lstm_fwd_persistent_kernel(PFwdParams p) 
       eslot[e] = (eu[e] / KW) * wblock + operand_slot<MT>(eu[e] % KW, eb[e]);
     }
   }
+  // I/O lanes: the pairs they move
+  int ib[EPL], iu[EPL];
+  bool iv[EPL];
+  float zr[EPL][4];
+#pragma unroll
+  for (int i = 0; i < EPL; ++i) {
+    const int j = lane + i * 64;
+    ib[i] = j / U; iu[i] = u0 + j % U;
+    iv[i] = is_io && ib[i] < B && iu[i] < H;
+  }
+  auto io_load = [&](int step) {                 // input part of the frame of `step` -> registers
+    const int t = D.direction > 0 ? step : T - 1 - step;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i)
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        zr[i][g] = iv[i] ? D.zg[((size_t)t * B + ib[i]) * 4 * H + g * H + iu[i]] : 0.f;
+  };
+  auto io_stage = [&](int step) {                // registers -> LDS buffer of `step`
+    float* dst = zin + (step & 1) * 4 * NE;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) dst[g * NE + lane + i * 64] = zr[i][g];
+  };
+  auto io_store = [&](int step) {                // outputs of the frame of `step`: LDS -> HBM
+    const int t = D.direction > 0 ? step : T - 1 - step;
+    const float* src = gout + (step & 1) * 6 * NE;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+      if (!iv[i]) continue;
+      const int j = lane + i * 64;
+      const size_t row = (size_t)t * B + ib[i];
+      float* zrow = D.zg + row * 4 * H + iu[i];
+      zrow[0] = src[0 * NE + j]; zrow[H] = src[1 * NE + j]; zrow[2 * H] = src[2 * NE + j]; zrow[3 * H] = src[3 * NE + j];
+      D.y[row * p.ldy + iu[i]] = src[4 * NE + j];
+      D.c[row * H + iu[i]] = src[5 * NE + j];
+    }
+  };
+  if (is_io) {
+    io_load(0);
+    io_stage(0);
+    if (T > 1) io_load(1);
+  }
   __syncthreads();
 
   const int prod_first = wave * KW / U, prod_count = KW / U;
-
-  float za[EPT][4];
-  {
-    const int t0 = D.direction > 0 ? 0 : T - 1;
-#pragma unroll
-    for (int e = 0; e < EPT; ++e)
-#pragma unroll
-      for (int g = 0; g < 4; ++g)
-        za[e][g] = ev[e] ? D.zg[((size_t)t0 * B + eb[e]) * 4 * H + g * H + eu[e]] : 0.f;
-  }
+  const unsigned* myflags = D.flags + (wg % kFlagCopies) * kFlagCopyStride;
 
   for (int s = 0; s < T; ++s) {
     const int t = D.direction > 0 ? s : T - 1 - s;
     const float* hprev = D.hx + (size_t)((s + 1) & 1) * hxsz;
     float* hcur = D.hx + (size_t)(s & 1) * hxsz;
-
-    // h of the previous step: wait for the producers of this wavefront's rows, then h_prev * R
     int fail = 0;
-    if (s > 0 && !wave_wait_flags(D.flags, prod_first, prod_count, p.Gf, (unsigned)s, p.err)) fail = 1;
-    floatx4 acc[MT][NT];
-    wave_product<MT, NT>(hprev + (size_t)wave * wblock, wblock * 4, nch, Rs + (size_t)wave * KW * NC, NC, acc);
+
+    if (!is_io) {
+      // h of the previous step: wait for the producers of this wavefront's rows, then h_prev * R
+      if (s > 0 && !wave_wait_flags(myflags, prod_first, prod_count, p.Gf, (unsigned)s, p.err)) fail = 1;
+      floatx4 acc[MT][NT];
+      wave_product<MT, NT>(hprev + (size_t)wave * wblock, wblock * 4, nch, Rs + (size_t)wave * KW * NC, NC, acc);
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+      for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
-        *reinterpret_cast<floatx4*>(Red + ((wave * MT + mt) * NT + nt) * 256 + (tid & 63) * 4) = acc[mt][nt];
+        for (int nt = 0; nt < NT; ++nt)
+          *reinterpret_cast<floatx4*>(Red + ((wave * MT + mt) * NT + nt) * 256 + lane * 4) = acc[mt][nt];
+    } else {
+      // stage the next frame's input part (loaded a step ago), write out the previous frame's
+      // outputs, start loading the frame after next: every wait here is on work issued a step ago
+      if (s + 1 < T) io_stage(s + 1);
+      if (s > 0) io_store(s - 1);
+      if (s + 2 < T) io_load(s + 2);
+    }
     if (__syncthreads_or(fail)) {
       if (tid == 0) st_dev(p.err, 1u);
       return;
     }
 
-    // gating, cell update, mask
-    float gate[EPT][4], yv[EPT];
+    if (!is_io) {
+      // gating, cell update, mask; publish the carried h; leave the frame's outputs in LDS
+      const float* zcur = zin + (s & 1) * 4 * NE;
+      float* ocur = gout + (s & 1) * 6 * NE;
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) {
-      if (!ev[e]) continue;
-      const int b = eb[e], uu = eu[e] - u0;
-      const int mt = b >> 4, r = b & 15;
-      float a[4];
+      for (int e = 0; e < EPT; ++e) {
+        if (!ev[e]) continue;
+        const int j = tid + e * 256;
+        const int b = eb[e], uu = eu[e] - u0;
+        const int mt = b >> 4, r = b & 15;
+        float a[4];
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int col = g * U + uu;
-        const int nt = col >> 4, n = col & 15;
-        const int src = ((r >> 2) * 16 + n) * 4 + (r & 3);    // accumulator (row r, col n) of a 16x16 tile
-        float sum = za[e][g];
+        for (int g = 0; g < 4; ++g) {
+          const int col = g * U + uu;
+          const int nt = col >> 4, n = col & 15;
+          const int src = ((r >> 2) * 16 + n) * 4 + (r & 3);    // accumulator (row r, col n) of a 16x16 tile
+          float sum = zcur[g * NE + j];
 #pragma unroll
-        for (int w = 0; w < 4; ++w) sum += Red[((w * MT + mt) * NT + nt) * 256 + src];
-        a[g] = sum;
+          for (int w = 0; w < 4; ++w) sum += Red[((w * MT + mt) * NT + nt) * 256 + src];
+          a[g] = sum;
+        }
+        const float gi = fsigmoid(a[0]), gf = fsigmoid(a[1]), go = fsigmoid(a[2]), gg = ftanh(a[3]);
+        const float cn = gf * creg[e] + gi * gg;
+        const float hn = go * ftanh(cn);
+        const bool valid = t < elen[e];
+        if (valid) { creg[e] = cn; hreg[e] = hn; }
+        st_dev(hcur + eslot[e], hreg[e]);
+        ocur[0 * NE + j] = gi; ocur[1 * NE + j] = gf; ocur[2 * NE + j] = go; ocur[3 * NE + j] = gg;
+        ocur[4 * NE + j] = valid ? hn : 0.f;
+        ocur[5 * NE + j] = creg[e];
       }
-      const float gi = fsigmoid(a[0]), gf = fsigmoid(a[1]), go = fsigmoid(a[2]), gg = ftanh(a[3]);
-      const float cn = gf * creg[e] + gi * gg;
-      const float hn = go * ftanh(cn);
-      const bool valid = t < elen[e];
-      if (valid) { creg[e] = cn; hreg[e] = hn; }
-      gate[e][0] = gi; gate[e][1] = gf; gate[e][2] = go; gate[e][3] = gg;
-      yv[e] = valid ? hn : 0.f;
-      st_dev(hcur + eslot[e], hreg[e]);          // publish the carried h
+      wait_stores_acked();
     }
-    wait_stores_acked();
     __syncthreads();
-    if (tid == 0) st_dev(D.flags + wg, (unsigned)(s + 1));
+    publish_flag(D.flags, wg, (unsigned)(s + 1));
 
-    // outputs of this frame (off the critical path), then the next frame's input part
-#pragma unroll
-    for (int e = 0; e < EPT; ++e) {
-      if (!ev[e]) continue;
-      const size_t row = (size_t)t * B + eb[e];
-      float* zrow = D.zg + row * 4 * H + eu[e];
-      zrow[0] = gate[e][0]; zrow[H] = gate[e][1]; zrow[2 * H] = gate[e][2]; zrow[3 * H] = gate[e][3];
-      D.y[row * p.ldy + eu[e]] = yv[e];
-      D.c[row * H + eu[e]] = creg[e];
-    }
-    if (s + 1 < T) {
-      const int tn = D.direction > 0 ? s + 1 : T - 2 - s;
-#pragma unroll
-      for (int e = 0; e < EPT; ++e)
-#pragma unroll
-        for (int g = 0; g < 4; ++g)
-          za[e][g] = ev[e] ? D.zg[((size_t)tn * B + eb[e]) * 4 * H + g * H + eu[e]] : 0.f;
-    }
   }
+  __syncthreads();
+  if (is_io) io_store(T - 1);
 
 #pragma unroll
   for (int e = 0; e < EPT; ++e) {
@@ -307,10 +364,15 @@ struct PBwdParams {
   int T, B, H, ldy, PG, Hq, nch;
 };
 
+// Same workgroup shape as the forward kernel: 4 compute wavefronts + 1 I/O wavefront that stages
+// the frame's gates, cell states and dy from HBM into LDS one step ahead and writes d a back to
+// HBM one step behind.
 template <int MT, int NT>
-__global__ __launch_bounds__(256) void lstm_bwd_persistent_kernel(PBwdParams p) {
+__global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwdParams p) {
   constexpr int U = 4 * NT, UG = 16 * NT, Bp = 16 * MT;
-  constexpr int EPT = (MT * 16 * U + 255) / 256;
+  constexpr int NE = MT * 16 * U;                // (sequence, unit) pairs owned by this workgroup
+  constexpr int EPT = (NE + 255) / 256;
+  constexpr int EPL = NE / 64;
   extern __shared__ __align__(16) float lds[];
   const int Gb = 4 * p.PG;
   const int dir = blockIdx.x / Gb, wg = blockIdx.x % Gb;
@@ -319,10 +381,14 @@ __global__ __launch_bounds__(256) void lstm_bwd_persistent_kernel(PBwdParams p) 
   const int T = p.T, B = p.B, H = p.H, Hq = p.Hq, nch = p.nch;
   const int u0 = wg * U;                         // owned units
   float* RTs = lds;                              // [4*Hq][UG]
-  float* Red = lds + (size_t)4 * Hq * UG;        // [4][MT][NT][256]
+  float* Red = RTs + (size_t)4 * Hq * UG;        // [4][MT][NT][256]
+  float* bin = Red + 4 * MT * NT * 256;          // [2][7][NE]  gates i,f,o,g, c, c_prev, dy of the frame
+  float* dzo = bin + 2 * 7 * NE;                 // [2][4][NE]  d a of the frame
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // wavefront-uniform, kept in a scalar register
+  const bool is_io = wave == 4;
+  const int lane = tid & 63;
   const int UW = Hq / 4;                         // units per wavefront of a quarter
   // Quarters that hold no unit (small H) contribute nothing: their workgroups publish no partial
   // tile and owners do not wait for one.  Every workgroup that does publish is paced by the flags
@@ -331,7 +397,7 @@ __global__ __launch_bounds__(256) void lstm_bwd_persistent_kernel(PBwdParams p) 
 
   // resident rows of R^T: row r = (wavefront w, unit ur of it, gate g) -> unit uk = qq*Hq + w*UW + ur;
   // RTs[r][n] = R[pg*UG + n][g*H + uk]
-  for (int idx = tid; idx < 4 * Hq * UG; idx += 256) {
+  for (int idx = tid; idx < 4 * Hq * UG; idx += kBlockThreads) {
     const int r = idx / UG, n = idx % UG;
     const int w = r / Hq, rr = r % Hq;
     const int uk = qq * Hq + w * UW + (rr >> 2), g = rr & 3;
@@ -343,15 +409,16 @@ __global__ __launch_bounds__(256) void lstm_bwd_persistent_kernel(PBwdParams p) 
   const size_t xsz = (size_t)16 * wblock;
   const size_t psz = (size_t)p.PG * 4 * Bp * UG;
 
+  // compute threads: carried gradients of the pairs they own
   float Dh[EPT], Dc[EPT], dbacc[EPT][4];
   int eb[EPT], eu[EPT], elen[EPT], eslot[EPT];
-  bool ev[EPT];
+  bool ev[EPT], vprev[EPT];
 #pragma unroll
   for (int e = 0; e < EPT; ++e) {
     const int j = tid + e * 256;
     eb[e] = j / U; eu[e] = u0 + j % U;
-    ev[e] = (j < MT * 16 * U) && eb[e] < B && eu[e] < H;
-    Dh[e] = 0.f; Dc[e] = 0.f; elen[e] = 0; eslot[e] = 0;
+    ev[e] = !is_io && (j < NE) && eb[e] < B && eu[e] < H;
+    Dh[e] = 0.f; Dc[e] = 0.f; elen[e] = 0; eslot[e] = 0; vprev[e] = false;
 #pragma unroll
     for (int g = 0; g < 4; ++g) dbacc[e][g] = 0.f;
     if (ev[e]) {
@@ -363,36 +430,76 @@ __global__ __launch_bounds__(256) void lstm_bwd_persistent_kernel(PBwdParams p) 
       eslot[e] = ((eu[e] / Hq) * 4 + ul / UW) * wblock + operand_slot<MT>((ul % UW) * 4, eb[e]);
     }
   }
+
+  // I/O lanes: the pairs they move.  Frames are visited in the reverse of the forward order:
+  // step s visits t(s); the frame processed before it in the forward pass is visited at step s+1,
+  // so c of step s+1's frame is c_prev of step s's frame.
+  int ib[EPL], iu[EPL];
+  bool iv[EPL];
+  float lr[EPL][6];                              // gates, c_prev, dy in flight
+  float cnext[EPL];                              // c of the frame staged next
+#pragma unroll
+  for (int i = 0; i < EPL; ++i) {
+    const int j = lane + i * 64;
+    ib[i] = j / U; iu[i] = u0 + j % U;
+    iv[i] = is_io && ib[i] < B && iu[i] < H;
+    cnext[i] = 0.f;
+  }
+  auto frame_of = [&](int step) { return D.direction > 0 ? T - 1 - step : step; };
+  auto io_load = [&](int step) {
+    const int t = frame_of(step);
+    const int tprev = D.direction > 0 ? t - 1 : t + 1;     // frame processed before t in the forward pass
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+      if (!iv[i]) continue;
+      const size_t row = (size_t)t * B + ib[i];
+      const float* zrow = D.zg + row * 4 * H + iu[i];
+      lr[i][0] = zrow[0]; lr[i][1] = zrow[H]; lr[i][2] = zrow[2 * H]; lr[i][3] = zrow[3 * H];
+      if (tprev >= 0 && tprev < T) lr[i][4] = D.c[((size_t)tprev * B + ib[i]) * H + iu[i]];
+      else lr[i][4] = D.c0 ? D.c0[(size_t)ib[i] * H + iu[i]] : 0.f;
+      lr[i][5] = D.dy[row * p.ldy + iu[i]];
+    }
+  };
+  auto io_stage = [&](int step) {
+    float* dst = bin + (step & 1) * 7 * NE;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+      const int j = lane + i * 64;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) dst[g * NE + j] = iv[i] ? lr[i][g] : 0.f;
+      dst[4 * NE + j] = cnext[i];
+      dst[5 * NE + j] = iv[i] ? lr[i][4] : 0.f;
+      dst[6 * NE + j] = iv[i] ? lr[i][5] : 0.f;
+      cnext[i] = iv[i] ? lr[i][4] : 0.f;
+    }
+  };
+  auto io_store = [&](int step) {
+    const int t = frame_of(step);
+    const float* src = dzo + (step & 1) * 4 * NE;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+      if (!iv[i]) continue;
+      const int j = lane + i * 64;
+      float* zrow = D.zg + ((size_t)t * B + ib[i]) * 4 * H + iu[i];
+      zrow[0] = src[0 * NE + j]; zrow[H] = src[1 * NE + j]; zrow[2 * H] = src[2 * NE + j]; zrow[3 * H] = src[3 * NE + j];
+    }
+  };
+  if (is_io) {
+    const int t0 = frame_of(0);
+#pragma unroll
+    for (int i = 0; i < EPL; ++i)
+      if (iv[i]) cnext[i] = D.c[((size_t)t0 * B + ib[i]) * H + iu[i]];
+    io_load(0);
+    io_stage(0);
+    if (T > 1) io_load(1);
+  }
   __syncthreads();
 
   // producers of this wavefront's rows: owners of units [qq*Hq + wave*UW, +UW)
   const int prod_first = (qq * Hq + wave * UW) / U, prod_count = UW / U;
+  const unsigned* myflags = D.flags + (wg % kFlagCopies) * kFlagCopyStride;
 
-  // inputs of the first visited frame
-  float gin[EPT][4], cti[EPT], cpi[EPT], dyi[EPT];
-  auto load_inputs = [&](int t, int tprev, bool first) {
-#pragma unroll
-    for (int e = 0; e < EPT; ++e) {
-      if (!ev[e]) continue;
-      const size_t row = (size_t)t * B + eb[e];
-      const float* zrow = D.zg + row * 4 * H + eu[e];
-      gin[e][0] = zrow[0]; gin[e][1] = zrow[H]; gin[e][2] = zrow[2 * H]; gin[e][3] = zrow[3 * H];
-      cti[e] = first ? D.c[row * H + eu[e]] : cpi[e];      // c of this frame = c_prev of the frame visited before
-      if (tprev >= 0 && tprev < T) cpi[e] = D.c[((size_t)tprev * B + eb[e]) * H + eu[e]];
-      else cpi[e] = D.c0 ? D.c0[(size_t)eb[e] * H + eu[e]] : 0.f;
-      dyi[e] = D.dy[row * p.ldy + eu[e]];
-    }
-  };
-  {
-    const int t = D.direction > 0 ? T - 1 : 0;
-    load_inputs(t, D.direction > 0 ? t - 1 : t + 1, true);
-  }
-
-  bool vprev[EPT];
-#pragma unroll
-  for (int e = 0; e < EPT; ++e) vprev[e] = false;
-
-  // sums the four partial tiles of step `step` for the owned pairs (tag = step + 1)
+  // sums the partial tiles of step `step` for the owned pairs (tag = step + 1)
   auto collect = [&](int step, float (&out)[EPT]) -> int {
     int fail = 0;
     const unsigned long long* pbuf = D.part + (size_t)(step & 1) * psz;
@@ -426,83 +533,80 @@ __global__ __launch_bounds__(256) void lstm_bwd_persistent_kernel(PBwdParams p) 
   };
 
   for (int s = 0; s < T; ++s) {
-    // frames are visited in the reverse of the forward processing order
-    const int t = D.direction > 0 ? T - 1 - s : s;
+    const int t = frame_of(s);
     float* dzcur = D.dzx + (size_t)(s & 1) * xsz;
     int fail = 0;
 
-    // d h carried into this frame: product of the previous step (+ carried d h where that frame was invalid)
-    if (s > 0) {
-      float g[EPT];
-      fail = collect(s - 1, g);
+    if (!is_io) {
+      // d h carried into this frame: product of the previous step (+ carried d h where that frame was invalid)
+      if (s > 0) {
+        float g[EPT];
+        fail = collect(s - 1, g);
 #pragma unroll
-      for (int e = 0; e < EPT; ++e) Dh[e] = vprev[e] ? g[e] : g[e] + Dh[e];
-    }
-
-    // gate derivatives
-    float dz[EPT][4];
-#pragma unroll
-    for (int e = 0; e < EPT; ++e) {
-#pragma unroll
-      for (int g = 0; g < 4; ++g) dz[e][g] = 0.f;
-      vprev[e] = false;
-      if (!ev[e]) continue;
-      const bool m = t < elen[e];
-      vprev[e] = m;
-      if (m) {
-        const float gi = gin[e][0], gf = gin[e][1], go = gin[e][2], gg = gin[e][3];
-        const float tc = ftanh(cti[e]);
-        const float dh = dyi[e] + Dh[e];
-        const float d_o = dh * tc;
-        const float dc = Dc[e] + dh * go * (1.0f - tc * tc);
-        dz[e][0] = dc * gg * gi * (1.0f - gi);
-        dz[e][1] = dc * cpi[e] * gf * (1.0f - gf);
-        dz[e][2] = d_o * go * (1.0f - go);
-        dz[e][3] = dc * gi * (1.0f - gg * gg);
-        Dc[e] = dc * gf;
+        for (int e = 0; e < EPT; ++e) Dh[e] = vprev[e] ? g[e] : g[e] + Dh[e];
       }
-      // rows (unit, gate 0..3) are lanes 0, 16, 32, 48 apart in operand order
+      // gate derivatives; publish d a of this frame
+      const float* in = bin + (s & 1) * 7 * NE;
+      float* out = dzo + (s & 1) * 4 * NE;
 #pragma unroll
-      for (int g = 0; g < 4; ++g) st_dev(dzcur + eslot[e] + g * 64, dz[e][g]);
+      for (int e = 0; e < EPT; ++e) {
+        vprev[e] = false;
+        if (!ev[e]) continue;
+        const int j = tid + e * 256;
+        float dz[4] = {0.f, 0.f, 0.f, 0.f};
+        const bool m = t < elen[e];
+        vprev[e] = m;
+        if (m) {
+          const float gi = in[0 * NE + j], gf = in[1 * NE + j], go = in[2 * NE + j], gg = in[3 * NE + j];
+          const float tc = ftanh(in[4 * NE + j]);
+          const float dh = in[6 * NE + j] + Dh[e];
+          const float d_o = dh * tc;
+          const float dc = Dc[e] + dh * go * (1.0f - tc * tc);
+          dz[0] = dc * gg * gi * (1.0f - gi);
+          dz[1] = dc * in[5 * NE + j] * gf * (1.0f - gf);
+          dz[2] = d_o * go * (1.0f - go);
+          dz[3] = dc * gi * (1.0f - gg * gg);
+          Dc[e] = dc * gf;
+        }
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          st_dev(dzcur + eslot[e] + g * 64, dz[g]);      // rows (unit, gate 0..3) are 16 lanes apart in operand order
+          out[g * NE + j] = dz[g];
+          dbacc[e][g] += dz[g];
+        }
+      }
+      wait_stores_acked();
+    } else {
+      // stage the next frame's inputs (loaded a step ago), write out the previous frame's d a,
+      // start loading the frame after next: every wait here is on work issued a step ago
+      if (s + 1 < T) io_stage(s + 1);
+      if (s > 0) io_store(s - 1);
+      if (s + 2 < T) io_load(s + 2);
     }
-    wait_stores_acked();
     if (__syncthreads_or(fail)) {
       if (tid == 0) st_dev(p.err, 1u);
       return;
     }
-    if (tid == 0) st_dev(D.flags + wg, (unsigned)(s + 1));
-
-    // d a of this frame in place over the gates; bias gradient; next frame's inputs
-#pragma unroll
-    for (int e = 0; e < EPT; ++e) {
-      if (!ev[e]) continue;
-      float* zrow = D.zg + ((size_t)t * B + eb[e]) * 4 * H + eu[e];
-      zrow[0] = dz[e][0]; zrow[H] = dz[e][1]; zrow[2 * H] = dz[e][2]; zrow[3 * H] = dz[e][3];
-#pragma unroll
-      for (int g = 0; g < 4; ++g) dbacc[e][g] += dz[e][g];
-    }
-    if (s + 1 < T) {
-      const int tn = D.direction > 0 ? T - 2 - s : s + 1;
-      load_inputs(tn, D.direction > 0 ? tn - 1 : tn + 1, false);
-    }
+    publish_flag(D.flags, wg, (unsigned)(s + 1));
 
     // this workgroup's quarter of d a_t R^T for its unit group
-    if (qq >= nq) continue;
     fail = 0;
-    if (!wave_wait_flags(D.flags, prod_first, prod_count, Gb, (unsigned)(s + 1), p.err)) fail = 1;
-    floatx4 acc[MT][NT];
-    wave_product<MT, NT>(dzcur + (size_t)(qq * 4 + wave) * wblock, wblock * 4, nch, RTs + (size_t)wave * Hq * UG, UG, acc);
+    if (!is_io && qq < nq) {
+      if (!wave_wait_flags(myflags, prod_first, prod_count, Gb, (unsigned)(s + 1), p.err)) fail = 1;
+      floatx4 acc[MT][NT];
+      wave_product<MT, NT>(dzcur + (size_t)(qq * 4 + wave) * wblock, wblock * 4, nch, RTs + (size_t)wave * Hq * UG, UG, acc);
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+      for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
-        *reinterpret_cast<floatx4*>(Red + ((wave * MT + mt) * NT + nt) * 256 + (tid & 63) * 4) = acc[mt][nt];
+        for (int nt = 0; nt < NT; ++nt)
+          *reinterpret_cast<floatx4*>(Red + ((wave * MT + mt) * NT + nt) * 256 + lane * 4) = acc[mt][nt];
+    }
     if (__syncthreads_or(fail)) {
       if (tid == 0) st_dev(p.err, 1u);
       return;
     }
     // sum the four wavefronts' tiles in order and hand (value, tag) to the owners
-    {
+    if (!is_io && qq < nq) {
       unsigned long long* pbuf = D.part + (size_t)(s & 1) * psz + (size_t)(pg * 4 + qq) * Bp * UG;
       const int ln = tid >> 2, reg = tid & 3;
       const int row = 4 * (ln >> 4) + reg, col = ln & 15;
@@ -518,25 +622,28 @@ __global__ __launch_bounds__(256) void lstm_bwd_persistent_kernel(PBwdParams p) 
                              __HIP_MEMORY_SCOPE_AGENT);
         }
     }
-    // Red is rewritten only after the next step's workgroup barrier
+    // Red is rewritten only after the next step's first workgroup barrier
   }
 
-  // gradient w.r.t. the initial state, and the bias gradient of the owned columns
-  {
+  // last frame's d a, gradient w.r.t. the initial state, bias gradient of the owned columns
+  int fail = 0;
+  if (is_io) {
+    io_store(T - 1);
+  } else {
     float g[EPT];
-    const int fail = collect(T - 1, g);
+    fail = collect(T - 1, g);
 #pragma unroll
     for (int e = 0; e < EPT; ++e) Dh[e] = vprev[e] ? g[e] : g[e] + Dh[e];
-    if (__syncthreads_or(fail)) {
-      if (tid == 0) st_dev(p.err, 1u);
-      return;
-    }
+  }
+  if (__syncthreads_or(fail)) {
+    if (tid == 0) st_dev(p.err, 1u);
+    return;
   }
   float* stage = Red;                            // [Bp][4U]
 #pragma unroll
   for (int e = 0; e < EPT; ++e) {
     const int j = tid + e * 256;
-    if (j < MT * 16 * U) {
+    if (!is_io && j < NE) {
       const int b = j / U, uu = j % U;
 #pragma unroll
       for (int g = 0; g < 4; ++g) stage[b * 4 * U + g * U + uu] = ev[e] ? dbacc[e][g] : 0.f;
@@ -589,6 +696,7 @@ __global__ __launch_bounds__(256) void seed_h0_kernel(PrepParams p) {
 
 // ---- host side ----------------------------------------------------------------
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+constexpr size_t kFlagBytes = (size_t)kFlagCopies * kFlagCopyStride * sizeof(unsigned);
 
 struct Plan {
   bool ok;
@@ -617,13 +725,18 @@ Plan make_plan(const RecShape& s, int num_cus, size_t max_lds) {
     // a wavefront polls at most 64 producers
     if (Hp / 4 / U > 64 || Hq / 4 / U > 64) continue;
     const size_t red = (size_t)4 * pl.MT * NT * 256;
-    const size_t lf = ((size_t)Hp * 16 * NT + red) * sizeof(float);
-    const size_t lb = ((size_t)4 * Hq * UG + red) * sizeof(float);
+    const size_t lf = ((size_t)Hp * 16 * NT + red + (size_t)(2 * 4 + 2 * 6) * pl.MT * 16 * U) * sizeof(float);
+    const size_t lb = ((size_t)4 * Hq * UG + red + (size_t)(2 * 7 + 2 * 4) * pl.MT * 16 * U) * sizeof(float);
     if (lf > max_lds || lb > max_lds) continue;
+    // One workgroup per CU: request more than half of the CU's LDS so that the dispatcher cannot
+    // stack two of these workgroups on one CU (they would share its matrix cores and every other
+    // workgroup would wait for them each step).
+    const size_t exclusive = max_lds / 2 + 1024;
+    const size_t lf_req = lf > exclusive ? lf : exclusive, lb_req = lb > exclusive ? lb : exclusive;
     pl.ok = true; pl.NT = NT; pl.U = U; pl.UG = UG;
     pl.Gf = Gf; pl.Hp = Hp; pl.nchF = (Hp / 16) * pl.MT / 4;
     pl.PG = PG; pl.Gb = Gb; pl.Hq = Hq; pl.nchB = (Hq / 4) * pl.MT / 4;
-    pl.ldsF = lf; pl.ldsB = lb;
+    pl.ldsF = lf_req; pl.ldsB = lb_req;
     return pl;
   }
   return pl;
@@ -634,7 +747,7 @@ Plan make_plan(const RecShape& s, int num_cus, size_t max_lds) {
 // A plain launch is used; other work on the device can delay residency but not prevent it,
 // and the kernels' own waits are bounded.
 template <typename K>
-hipError_t resident_launch(K kernel, int grid, size_t lds, int num_cus, hipStream_t stream, void* params,
+hipError_t resident_launch(K kernel, int grid, int block, size_t lds, int num_cus, hipStream_t stream, void* params,
                            int* resident_err) {
   hipError_t e = hipSuccess;
   const void* fn = reinterpret_cast<const void*>(kernel);
@@ -643,11 +756,11 @@ hipError_t resident_launch(K kernel, int grid, size_t lds, int num_cus, hipStrea
     if (e != hipSuccess) return e;
   }
   int per_cu = 0;
-  e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 256, lds);
+  e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, block, lds);
   if (e != hipSuccess) return e;
   if ((long long)per_cu * num_cus < grid) { *resident_err = 1; return hipErrorCooperativeLaunchTooLarge; }
   void* args[] = {params};
-  return hipLaunchKernel(fn, dim3((unsigned)grid), dim3(256), args, lds, stream);
+  return hipLaunchKernel(fn, dim3((unsigned)grid), dim3((unsigned)block), args, lds, stream);
 }
 
 }  // namespace
@@ -657,14 +770,14 @@ bool persistent_supported(const RecShape& s, int num_cus, size_t max_lds) {
 }
 
 // Upper bound (independent of the device) of the per-direction scratch, in bytes:
-// [flags 1 KiB][exchange arrays][partial tiles].
+// [flag copies][exchange arrays][partial tiles].
 size_t persistent_scratch_bytes_per_dir(const RecShape& s) {
   const size_t Bp = s.B <= 16 ? 16 : (s.B <= 32 ? 32 : 64);
   const size_t Hp = align_up((size_t)s.H, 64);
   const size_t Hq = align_up((size_t)s.H / 4 + 8, 32);
   const size_t exch = 2 * (Hp > 16 * Hq ? Hp : 16 * Hq) * Bp * sizeof(float);
   const size_t part = 2 * 4 * Bp * ((size_t)s.H + 32) * sizeof(unsigned long long);
-  return 1024 + align_up(exch, 256) + align_up(part, 256);
+  return kFlagBytes + align_up(exch, 256) + align_up(part, 256);
 }
 
 hipError_t persistent_forward(hipStream_t stream, const RecShape& s, const RecFwdDir* dirs, const int32_t* seq_lens,
@@ -679,9 +792,9 @@ hipError_t persistent_forward(hipStream_t stream, const RecShape& s, const RecFw
   PFwdParams kp{};
   for (int d = 0; d < s.ndir; ++d) {
     unsigned* flags = reinterpret_cast<unsigned*>(scratch[d]);
-    float* hx = reinterpret_cast<float*>(scratch[d] + 1024);
+    float* hx = reinterpret_cast<float*>(scratch[d] + kFlagBytes);
     pp.zero_words[d] = flags;
-    pp.nzero[d] = 256 + (size_t)2 * 4 * wblock;
+    pp.nzero[d] = kFlagBytes / 4 + (size_t)2 * 4 * wblock;
     pp.hx1[d] = hx + (size_t)4 * wblock;
     pp.h0[d] = dirs[d].h0;
     PFwdDir& k = kp.d[d];
@@ -702,7 +815,7 @@ hipError_t persistent_forward(hipStream_t stream, const RecShape& s, const RecFw
   const int grid = pl.Gf * s.ndir;
 #define RLSTM_FWD_CASE(MT_, NT_)                                                                      \
   if (pl.MT == MT_ && pl.NT == NT_)                                                                   \
-    return resident_launch(lstm_fwd_persistent_kernel<MT_, NT_>, grid, pl.ldsF, di.num_cus, stream, &kp, resident_err);
+    return resident_launch(lstm_fwd_persistent_kernel<MT_, NT_>, grid, kBlockThreads, pl.ldsF, di.num_cus, stream, &kp, resident_err);
   RLSTM_FWD_CASE(1, 1) RLSTM_FWD_CASE(2, 1) RLSTM_FWD_CASE(4, 1)
   RLSTM_FWD_CASE(1, 2) RLSTM_FWD_CASE(2, 2) RLSTM_FWD_CASE(4, 2)
 #undef RLSTM_FWD_CASE
@@ -723,10 +836,10 @@ hipError_t persistent_backward(hipStream_t stream, const RecShape& s, const RecB
   PBwdParams kp{};
   for (int d = 0; d < s.ndir; ++d) {
     unsigned* flags = reinterpret_cast<unsigned*>(scratch[d]);
-    float* dzx = reinterpret_cast<float*>(scratch[d] + 1024);
+    float* dzx = reinterpret_cast<float*>(scratch[d] + kFlagBytes);
     unsigned long long* part = reinterpret_cast<unsigned long long*>(dzx + align_up(exch_floats, 64));
     pp.zero_words[d] = flags;
-    pp.nzero[d] = 256 + align_up(exch_floats, 64) + 2 * part_words;
+    pp.nzero[d] = kFlagBytes / 4 + align_up(exch_floats, 64) + 2 * part_words;
     PBwdDir& k = kp.d[d];
     k.zg = dirs[d].zg; k.R = dirs[d].R; k.c = dirs[d].c; k.c0 = dirs[d].c0; k.dy = dirs[d].dy;
     k.dhT = dirs[d].dhT; k.dcT = dirs[d].dcT; k.dh0 = dirs[d].dh0; k.dc0 = dirs[d].dc0; k.db = dirs[d].db;
@@ -741,7 +854,7 @@ hipError_t persistent_backward(hipStream_t stream, const RecShape& s, const RecB
   const int grid = pl.Gb * s.ndir;
 #define RLSTM_BWD_CASE(MT_, NT_)                                                                      \
   if (pl.MT == MT_ && pl.NT == NT_)                                                                   \
-    return resident_launch(lstm_bwd_persistent_kernel<MT_, NT_>, grid, pl.ldsB, di.num_cus, stream, &kp, resident_err);
+    return resident_launch(lstm_bwd_persistent_kernel<MT_, NT_>, grid, kBlockThreads, pl.ldsB, di.num_cus, stream, &kp, resident_err);
   RLSTM_BWD_CASE(1, 1) RLSTM_BWD_CASE(2, 1) RLSTM_BWD_CASE(4, 1)
   RLSTM_BWD_CASE(1, 2) RLSTM_BWD_CASE(2, 2) RLSTM_BWD_CASE(4, 2)
 #undef RLSTM_BWD_CASE
