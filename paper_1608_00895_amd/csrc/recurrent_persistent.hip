@@ -22,10 +22,14 @@
 // backwards) goes through global memory with device-scope (sc1) stores and
 // loads only, never through plain cached accesses, and the data is its own
 // ready flag:
-//   * h_t and d a_t live in four step buffers (index = step mod 4) laid out in
-//     MFMA operand order, so a consumer wavefront fetches its rows with 16-byte
-//     device-scope buffer loads of 1 KiB contiguous per wavefront, all issued
-//     before the first MFMA.  A slot that has not been written yet holds a
+//   * h_t and d a_t live in four step buffers (index = step mod 4), stored
+//     [group of 4 K-rows][sequence][4]: a producer's values form whole 64-byte
+//     lines (no partial-line writes from different workgroups), and a consumer
+//     lane fetches with one 16-byte device-scope buffer load the four values it
+//     feeds to four consecutive MFMA k-steps (256 contiguous bytes per 16
+//     lanes); all loads are issued before the first MFMA.  The K index of the
+//     MFMA steps is permuted accordingly, and the resident R / R^T rows are
+//     stored in LDS in that same order.  A slot that has not been written yet holds a
 //     sentinel (one fixed NaN bit pattern); the consumer re-fetches only the
 //     16-byte chunks in which it still sees the sentinel.  Each producer, at
 //     step s, first waits until its older stores are acknowledged, then puts
@@ -85,23 +89,23 @@ constexpr int kStepBuffers = 4;
 __device__ __forceinline__ float fsigmoid(float u) { return __builtin_amdgcn_rcpf(1.0f + __expf(-u)); }
 __device__ __forceinline__ float ftanh(float u) { return 2.0f * __builtin_amdgcn_rcpf(1.0f + __expf(-2.0f * u)) - 1.0f; }
 
-// position of element (row k of a wavefront's K range, sequence b) inside that wavefront's
-// operand-ordered block: [chunk][lane][4], L = (k/4)*MT + b/16, chunk = L/4, lane = (k%4)*16 + b%16
-template <int MT>
-__device__ __forceinline__ int operand_slot(int k, int b) {
-  const int L = (k >> 2) * MT + (b >> 4);
-  return ((L >> 2) * 64 + (k & 3) * 16 + (b & 15)) * 4 + (L & 3);
-}
-
-// One wavefront's share of a [B x K] * [K x 16*NT] product.  A rows come from the exchange
-// array (device-scope 16-byte loads, operand order), B rows from LDS (row stride ldb floats).
-// Chunks that still hold the sentinel are fetched again until their producer has written them.
-// Returns false if the bounded wait expired.
+// Exchange layout: [K-row group r][sequence b][4].  Forward: r = unit / 4 and the 4 entries are
+// units 4r..4r+3.  Backward: r = unit and the 4 entries are its gates i, f, o, g.
+//
+// One wavefront's share of a [B x K] * [K x 16*NT] product over row groups row0 .. row0 + 4*nJ.
+// Lane (l16, lq) fetches for chunk (J, mt) the 16 bytes of group row0 + 4J + lq, sequence
+// mt*16 + l16, and feeds entry i of it to MFMA step (J, i) as A[row l16][k index lq]; the B rows
+// of that step are bs[((J*4 + i)*4 + lq)][...] (LDS, row stride ldb floats), i.e. the caller stores
+// its resident matrix in this step order.  Chunks that still hold the sentinel are fetched again
+// until their producer has written them.  Returns false if the bounded wait expired.
 template <int MT, int NT>
-__device__ __forceinline__ bool wave_product(const float* xblock, int xblock_bytes, int nch, const float* bs, int ldb,
+__device__ __forceinline__ bool wave_product(const float* xbuf, int xbuf_bytes, int row0, int nJ, const float* bs, int ldb,
                                              floatx4 (&acc)[MT][NT], unsigned* err) {
+  constexpr int Bp = 16 * MT;
   const int lane = threadIdx.x & 63, l16 = lane & 15, lq = lane >> 4;
-  __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(xblock), 0, xblock_bytes, 0x00020000);
+  __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(xbuf), 0, xbuf_bytes, 0x00020000);
+  const int nch = nJ * MT;                       // 16-byte chunks per lane
+  const int lane_off = ((row0 + lq) * Bp + l16) * 16;
   bool ok = true;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
@@ -113,10 +117,27 @@ __device__ __forceinline__ bool wave_product(const float* xblock, int xblock_byt
     unsigned pending = (1u << ng) - 1u;          // chunks of this group still to be fetched (wavefront-uniform)
     Spin sp;
     for (;;) {
+      // light spin on the first outstanding chunk only, so that waiting costs one 16-byte load per
+      // lane and round trip instead of re-reading the whole block
+      {
+        const int qf = __builtin_ctz(pending);
+        const int Jf = (c0 + qf) / MT, mf = (c0 + qf) % MT;
+        for (;;) {
+          const intx4 w = __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane_off + (4 * Jf * Bp + mf * 16) * 16, 0, kAuxSc1);
+          const bool unwritten = (unsigned)w[0] == kSentinel || (unsigned)w[1] == kSentinel ||
+                                 (unsigned)w[2] == kSentinel || (unsigned)w[3] == kSentinel;
+          if (!__any(unwritten)) break;
+          if (sp.expired(err)) { ok = false; break; }
+        }
+        if (!ok) break;
+      }
 #pragma unroll
       for (int q = 0; q < CG; ++q)
-        if ((pending >> q) & 1u)
-          v[q] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, ((c0 + q) * 64 + lane) * 16, 0, kAuxSc1));
+        if ((pending >> q) & 1u) {
+          const int J = c0 / MT + q / MT, mt = q % MT;
+          v[q] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                 rsrc, lane_off + (4 * J * Bp + mt * 16) * 16, 0, kAuxSc1));
+        }
       unsigned bad = 0;
 #pragma unroll
       for (int q = 0; q < CG; ++q) {
@@ -134,15 +155,14 @@ __device__ __forceinline__ bool wave_product(const float* xblock, int xblock_byt
 #pragma unroll
     for (int q = 0; q < CG; ++q) {
       if (q < ng) {
+        const int J = c0 / MT + q / MT;
+        const int mt = q % MT;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          constexpr int KPC = 4 / MT;                 // k-steps per chunk
-          const int ks = (c0 + q) * KPC + w / MT;
-          const int mt = w % MT;
+        for (int i = 0; i < 4; ++i) {
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt) {
-            const float bf = bs[(ks * 4 + lq) * ldb + nt * 16 + l16];
-            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(v[q][w], bf, acc[mt][nt], 0, 0, 0);
+            const float bf = bs[((J * 4 + i) * 4 + lq) * ldb + nt * 16 + l16];
+            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(v[q][i], bf, acc[mt][nt], 0, 0, 0);
           }
         }
       }
@@ -158,14 +178,14 @@ __device__ __forceinline__ bool wave_product(const float* xblock, int xblock_byt
 struct PFwdDir {
   float* zg; const float* R; const float* h0; const float* c0;
   float* y; float* c; float* hT; float* cT;
-  float* hx;            // kStepBuffers x [4 wavefronts][nch][64][4]
+  float* hx;            // kStepBuffers x [Hp/4][Bp][4]
   int direction;
 };
 struct PFwdParams {
   PFwdDir d[2];
   const int32_t* seq_lens;
   unsigned* err;
-  int T, B, H, ldy, Gf, Hp, nch;
+  int T, B, H, ldy, Gf, Hp;
 };
 
 // Workgroup = 4 compute wavefronts (threads 0..255) + 1 I/O wavefront (threads 256..319).
@@ -184,9 +204,10 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
   extern __shared__ __align__(16) float lds[];
   const int dir = blockIdx.x / p.Gf, wg = blockIdx.x % p.Gf;
   const PFwdDir& D = p.d[dir];
-  const int T = p.T, B = p.B, H = p.H, Hp = p.Hp, nch = p.nch;
+  constexpr int Bp = 16 * MT;
+  const int T = p.T, B = p.B, H = p.H, Hp = p.Hp;
   const int u0 = wg * U;
-  float* Rs = lds;                               // [Hp][NC]
+  float* Rs = lds;                               // [Hp][NC], rows in MFMA step order (see wave_product)
   float* Red = Rs + (size_t)Hp * NC;             // [4][MT][NT][256]
   float* zin = Red + 4 * MT * NT * 256;          // [2][4][NE]  input part of the frame, per gate
   float* gout = zin + 2 * 4 * NE;                // [2][6][NE]  gates i,f,o,g, y, c of the frame
@@ -196,16 +217,17 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
   const bool is_io = wave == 4;
   const int lane = tid & 63;
 
-  // resident slice of R: slice column g*U + uu is column g*H + u0 + uu of R
+  const int KW = Hp / 4;                         // rows of h per wavefront (multiple of 16)
+  // resident slice of R: slice column g*U + uu is column g*H + u0 + uu of R; LDS row
+  // w*KW + (J*4 + i)*4 + lq holds row k = w*KW + 16J + 4lq + i of R
   for (int idx = tid; idx < Hp * NC; idx += kBlockThreads) {
-    const int k = idx / NC, col = idx % NC;
+    const int row = idx / NC, col = idx % NC;
+    const int w = row / KW, r = row % KW;
+    const int k = w * KW + (r >> 4) * 16 + (r & 3) * 4 + ((r >> 2) & 3);
     const int g = col / U, u = u0 + col % U;
     Rs[idx] = (k < H && u < H) ? D.R[(size_t)k * 4 * H + g * H + u] : 0.f;
   }
-
-  const int KW = Hp / 4;                         // rows of h per wavefront
-  const int wblock = nch * 256;                  // floats of one wavefront's operand block
-  const size_t hxsz = (size_t)4 * wblock;
+  const size_t hxsz = (size_t)Hp * Bp;           // floats per step buffer
 
   // compute threads: carried state of the pairs they own
   float hreg[EPT], creg[EPT];
@@ -221,7 +243,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
       if (D.h0) hreg[e] = D.h0[(size_t)eb[e] * H + eu[e]];
       if (D.c0) creg[e] = D.c0[(size_t)eb[e] * H + eu[e]];
       elen[e] = min(max(p.seq_lens[eb[e]], 0), T);
-      eslot[e] = (eu[e] / KW) * wblock + operand_slot<MT>(eu[e] % KW, eb[e]);
+      eslot[e] = ((eu[e] >> 2) * Bp + eb[e]) * 4 + (eu[e] & 3);
     }
   }
   // I/O lanes: the pairs they move
@@ -281,7 +303,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
     if (!is_io) {
       // h_prev * R over this wavefront's rows of h_prev, fetched as soon as their producers have written them
       floatx4 acc[MT][NT];
-      if (!wave_product<MT, NT>(hprev + (size_t)wave * wblock, wblock * 4, nch, Rs + (size_t)wave * KW * NC, NC, acc, p.err))
+      if (!wave_product<MT, NT>(hprev, (int)(hxsz * 4), wave * (KW / 4), KW / 16, Rs + (size_t)wave * KW * NC, NC, acc, p.err))
         fail = 1;
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
@@ -359,7 +381,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
 struct PBwdDir {
   float* zg; const float* R; const float* c; const float* c0; const float* dy;
   const float* dhT; const float* dcT; float* dh0; float* dc0; float* db;
-  float* dzx;                   // kStepBuffers x [4 quarters][4 wavefronts][nch][64][4]
+  float* dzx;                   // kStepBuffers x [4*Hq units][Bp][4 gates]
   unsigned long long* part;     // 2 x [PG][4][Bp][UG] (value, tag)
   int direction;
 };
@@ -367,7 +389,7 @@ struct PBwdParams {
   PBwdDir d[2];
   const int32_t* seq_lens;
   unsigned* err;
-  int T, B, H, ldy, PG, Hq, nch;
+  int T, B, H, ldy, PG, Hq;
 };
 
 // Same workgroup shape as the forward kernel: 4 compute wavefronts + 1 I/O wavefront that stages
@@ -384,9 +406,9 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
   const int dir = blockIdx.x / Gb, wg = blockIdx.x % Gb;
   const int pg = wg >> 2, qq = wg & 3;           // unit group, K quarter (also: which quarter of the group it owns)
   const PBwdDir& D = p.d[dir];
-  const int T = p.T, B = p.B, H = p.H, Hq = p.Hq, nch = p.nch;
+  const int T = p.T, B = p.B, H = p.H, Hq = p.Hq;
   const int u0 = wg * U;                         // owned units
-  float* RTs = lds;                              // [4*Hq][UG]
+  float* RTs = lds;                              // [4*Hq][UG], rows in MFMA step order (see wave_product)
   float* Red = RTs + (size_t)4 * Hq * UG;        // [4][MT][NT][256]
   float* bin = Red + 4 * MT * NT * 256;          // [2][7][NE]  gates i,f,o,g, c, c_prev, dy of the frame
   float* dzo = bin + 2 * 7 * NE;                 // [2][4][NE]  d a of the frame
@@ -401,18 +423,16 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
   // of real producers, so no tile is overwritten before its owners have read it.
   const int nq = (H + Hq - 1) / Hq;
 
-  // resident rows of R^T: row r = (wavefront w, unit ur of it, gate g) -> unit uk = qq*Hq + w*UW + ur;
-  // RTs[r][n] = R[pg*UG + n][g*H + uk]
+  // resident rows of R^T: LDS row w*Hq + (J*4 + g)*4 + lq holds, for unit uk = qq*Hq + w*UW + 4J + lq
+  // and gate g, the values R[pg*UG + n][g*H + uk], n = 0..UG-1
   for (int idx = tid; idx < 4 * Hq * UG; idx += kBlockThreads) {
-    const int r = idx / UG, n = idx % UG;
-    const int w = r / Hq, rr = r % Hq;
-    const int uk = qq * Hq + w * UW + (rr >> 2), g = rr & 3;
+    const int row = idx / UG, n = idx % UG;
+    const int w = row / Hq, r = row % Hq;
+    const int uk = qq * Hq + w * UW + (r >> 4) * 4 + (r & 3), g = (r >> 2) & 3;
     const int un = pg * UG + n;
     RTs[idx] = (uk < H && un < H) ? D.R[(size_t)un * 4 * H + g * H + uk] : 0.f;
   }
-
-  const int wblock = nch * 256;                  // floats per (quarter, wavefront) operand block
-  const size_t xsz = (size_t)16 * wblock;
+  const size_t xsz = (size_t)16 * Hq * Bp;       // floats per step buffer
   const size_t psz = (size_t)p.PG * 4 * Bp * UG;
 
   // compute threads: carried gradients of the pairs they own
@@ -431,9 +451,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
       if (D.dhT) Dh[e] = D.dhT[(size_t)eb[e] * H + eu[e]];
       if (D.dcT) Dc[e] = D.dcT[(size_t)eb[e] * H + eu[e]];
       elen[e] = min(max(p.seq_lens[eb[e]], 0), T);
-      // d a of unit u, gate g sits in quarter u/Hq, wavefront (u%Hq)/UW, row ((u%Hq)%UW)*4 + g
-      const int ul = eu[e] % Hq;
-      eslot[e] = ((eu[e] / Hq) * 4 + ul / UW) * wblock + operand_slot<MT>((ul % UW) * 4, eb[e]);
+      eslot[e] = (eu[e] * Bp + eb[e]) * 4;         // the 4 gates of (unit, sequence) are one 16-byte entry
     }
   }
 
@@ -537,8 +555,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
 
   for (int s = 0; s < T; ++s) {
     const int t = frame_of(s);
-    float* dzcur = D.dzx + (size_t)(s & 3) * xsz;
-    float* dzreset = D.dzx + (size_t)((s + 2) & 3) * xsz;       // holds d a of step s-2: nobody reads it any more
+    const float* dzcur = D.dzx + (size_t)(s & 3) * xsz;        // buffer (s+2) mod 4 holds d a of step s-2: nobody reads it any more
     int fail = 0;
 
     if (!is_io) {
@@ -581,18 +598,20 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
         }
       }
       // older stores (issued a step ago) acknowledged -> sentinel into the buffer of step s+2 -> publish d a of step s
-      // (rows (unit, gate 0..3) are 16 lanes apart in operand order)
       wait_stores_acked();
+      {
+        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(D.dzx, 0, (int)(kStepBuffers * xsz * 4), 0x00020000);
+        const intx4 sent = intx4{(int)kSentinel, (int)kSentinel, (int)kSentinel, (int)kSentinel};
 #pragma unroll
-      for (int e = 0; e < EPT; ++e)
-        if (ev[e])
+        for (int e = 0; e < EPT; ++e)
+          if (ev[e])
+            __builtin_amdgcn_raw_buffer_store_b128(sent, rs, (int)((((s + 2) & 3) * xsz + eslot[e]) * 4), 0, kAuxSc1);
 #pragma unroll
-          for (int g = 0; g < 4; ++g) st_dev(reinterpret_cast<unsigned*>(dzreset) + eslot[e] + g * 64, kSentinel);
-#pragma unroll
-      for (int e = 0; e < EPT; ++e)
-        if (ev[e])
-#pragma unroll
-          for (int g = 0; g < 4; ++g) st_dev(dzcur + eslot[e] + g * 64, dz[e][g]);
+        for (int e = 0; e < EPT; ++e)
+          if (ev[e])
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(intx4, floatx4{dz[e][0], dz[e][1], dz[e][2], dz[e][3]}), rs,
+                                                   (int)(((s & 3) * xsz + eslot[e]) * 4), 0, kAuxSc1);
+      }
     } else {
       // stage the next frame's inputs (loaded a step ago), write out the previous frame's d a,
       // start loading the frame after next: every wait here is on work issued a step ago
@@ -608,7 +627,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
     fail = 0;
     if (!is_io && qq < nq) {
       floatx4 acc[MT][NT];
-      if (!wave_product<MT, NT>(dzcur + (size_t)(qq * 4 + wave) * wblock, wblock * 4, nch, RTs + (size_t)wave * Hq * UG, UG, acc, p.err))
+      if (!wave_product<MT, NT>(dzcur, (int)(xsz * 4), qq * Hq + wave * UW, UW / 4, RTs + (size_t)wave * Hq * UG, UG, acc, p.err))
         fail = 1;
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
@@ -685,18 +704,13 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
 struct PrepParams {
   unsigned* zero_words[2]; size_t nzero[2];       // per direction: words to clear (exchange arrays [+ partial tiles])
   float* xbase[2]; const float* h0[2];            // exchange arrays; forward only: h0 or null
-  int ndir, B, H, MT, backward;
-  int KW, wblock;                                 // forward: rows of h per wavefront, floats per wavefront block
-  int Hq;                                         // backward: units per quarter
+  int ndir, B, H, Bp, backward;
   size_t bufsz;                                   // floats per step buffer
 };
 __global__ __launch_bounds__(256) void prep_kernel(PrepParams p) {
   const size_t gtid = (size_t)blockIdx.x * 256 + threadIdx.x, gsz = (size_t)gridDim.x * 256;
   for (int d = 0; d < p.ndir; ++d)
     for (size_t i = gtid; i < p.nzero[d]; i += gsz) p.zero_words[d][i] = 0u;
-}
-__device__ __forceinline__ int operand_slot_rt(int MT, int k, int b) {
-  return MT == 1 ? operand_slot<1>(k, b) : (MT == 2 ? operand_slot<2>(k, b) : operand_slot<4>(k, b));
 }
 __global__ __launch_bounds__(256) void seed_kernel(PrepParams p) {
   const size_t gtid = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -705,15 +719,14 @@ __global__ __launch_bounds__(256) void seed_kernel(PrepParams p) {
   for (int d = 0; d < p.ndir; ++d) {
     unsigned* x = reinterpret_cast<unsigned*>(p.xbase[d]);
     if (!p.backward) {
-      const size_t slot = (size_t)(u / p.KW) * p.wblock + operand_slot_rt(p.MT, u % p.KW, b);
+      const size_t slot = ((size_t)(u >> 2) * p.Bp + b) * 4 + (u & 3);
       for (int k = 0; k < kStepBuffers - 1; ++k) x[k * p.bufsz + slot] = kSentinel;
       // step 0 reads buffer (0 - 1) mod 4 = 3
       p.xbase[d][(size_t)(kStepBuffers - 1) * p.bufsz + slot] = p.h0[d] ? p.h0[d][gtid] : 0.f;
     } else {
-      const int UW = p.Hq / 4, ul = u % p.Hq;
-      const size_t slot = (size_t)((u / p.Hq) * 4 + ul / UW) * p.wblock + operand_slot_rt(p.MT, (ul % UW) * 4, b);
+      const size_t slot = ((size_t)u * p.Bp + b) * 4;
       for (int k = 0; k < kStepBuffers; ++k)
-        for (int g = 0; g < 4; ++g) x[k * p.bufsz + slot + g * 64] = kSentinel;
+        for (int g = 0; g < 4; ++g) x[k * p.bufsz + slot + g] = kSentinel;
     }
   }
 }
@@ -724,8 +737,8 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct Plan {
   bool ok;
   int MT, NT, U, UG, Bp;
-  int Gf, Hp, nchF;
-  int PG, Gb, Hq, nchB;
+  int Gf, Hp;
+  int PG, Gb, Hq;
   size_t ldsF, ldsB;
 };
 
@@ -745,8 +758,6 @@ Plan make_plan(const RecShape& s, int num_cus, size_t max_lds) {
     if (Gf > per_dir || Gb > per_dir) continue;
     const int Hp = (int)align_up((size_t)s.H, 64);
     const int Hq = (int)align_up((size_t)PG * U, 32);
-    // a wavefront polls at most 64 producers
-    if (Hp / 4 / U > 64 || Hq / 4 / U > 64) continue;
     const size_t red = (size_t)4 * pl.MT * NT * 256;
     const size_t lf = ((size_t)Hp * 16 * NT + red + (size_t)(2 * 4 + 2 * 6) * pl.MT * 16 * U) * sizeof(float);
     const size_t lb = ((size_t)4 * Hq * UG + red + (size_t)(2 * 7 + 2 * 4) * pl.MT * 16 * U) * sizeof(float);
@@ -757,8 +768,8 @@ Plan make_plan(const RecShape& s, int num_cus, size_t max_lds) {
     const size_t exclusive = max_lds / 2 + 1024;
     const size_t lf_req = lf > exclusive ? lf : exclusive, lb_req = lb > exclusive ? lb : exclusive;
     pl.ok = true; pl.NT = NT; pl.U = U; pl.UG = UG;
-    pl.Gf = Gf; pl.Hp = Hp; pl.nchF = (Hp / 16) * pl.MT / 4;
-    pl.PG = PG; pl.Gb = Gb; pl.Hq = Hq; pl.nchB = (Hq / 4) * pl.MT / 4;
+    pl.Gf = Gf; pl.Hp = Hp;
+    pl.PG = PG; pl.Gb = Gb; pl.Hq = Hq;
     pl.ldsF = lf_req; pl.ldsB = lb_req;
     return pl;
   }
@@ -810,13 +821,13 @@ hipError_t persistent_forward(hipStream_t stream, const RecShape& s, const RecFw
   if (e != hipSuccess) return e;
   const Plan pl = make_plan(s, di.num_cus, di.max_lds);
   if (!pl.ok) { *resident_err = 1; return hipErrorInvalidValue; }
-  const int wblock = pl.nchF * 256;
+  const size_t bufsz = (size_t)pl.Hp * pl.Bp;
   PrepParams pp{};
   PFwdParams kp{};
   for (int d = 0; d < s.ndir; ++d) {
     float* hx = reinterpret_cast<float*>(scratch[d]);
     pp.zero_words[d] = reinterpret_cast<unsigned*>(hx);
-    pp.nzero[d] = (size_t)kStepBuffers * 4 * wblock;
+    pp.nzero[d] = (size_t)kStepBuffers * bufsz;
     pp.xbase[d] = hx;
     pp.h0[d] = dirs[d].h0;
     PFwdDir& k = kp.d[d];
@@ -824,10 +835,9 @@ hipError_t persistent_forward(hipStream_t stream, const RecShape& s, const RecFw
     k.y = dirs[d].y; k.c = dirs[d].c; k.hT = dirs[d].hT; k.cT = dirs[d].cT;
     k.hx = hx; k.direction = dirs[d].direction;
   }
-  pp.ndir = s.ndir; pp.B = s.B; pp.H = s.H; pp.KW = pl.Hp / 4; pp.wblock = wblock; pp.MT = pl.MT;
-  pp.backward = 0; pp.Hq = 0; pp.bufsz = (size_t)4 * wblock;
+  pp.ndir = s.ndir; pp.B = s.B; pp.H = s.H; pp.Bp = pl.Bp; pp.backward = 0; pp.bufsz = bufsz;
   kp.seq_lens = seq_lens; kp.err = err;
-  kp.T = s.T; kp.B = s.B; kp.H = s.H; kp.ldy = s.ldy; kp.Gf = pl.Gf; kp.Hp = pl.Hp; kp.nch = pl.nchF;
+  kp.T = s.T; kp.B = s.B; kp.H = s.H; kp.ldy = s.ldy; kp.Gf = pl.Gf; kp.Hp = pl.Hp;
   hipLaunchKernelGGL(prep_kernel, dim3(64), dim3(256), 0, stream, pp);
   {
     const size_t bh = (size_t)s.B * s.H;
@@ -852,8 +862,8 @@ hipError_t persistent_backward(hipStream_t stream, const RecShape& s, const RecB
   if (e != hipSuccess) return e;
   const Plan pl = make_plan(s, di.num_cus, di.max_lds);
   if (!pl.ok) { *resident_err = 1; return hipErrorInvalidValue; }
-  const int wblock = pl.nchB * 256;
-  const size_t exch_floats = (size_t)kStepBuffers * 16 * wblock;
+  const size_t bufsz = (size_t)16 * pl.Hq * pl.Bp;
+  const size_t exch_floats = (size_t)kStepBuffers * bufsz;
   const size_t part_words = (size_t)2 * pl.PG * 4 * pl.Bp * pl.UG;
   PrepParams pp{};
   PBwdParams kp{};
@@ -868,10 +878,9 @@ hipError_t persistent_backward(hipStream_t stream, const RecShape& s, const RecB
     k.dhT = dirs[d].dhT; k.dcT = dirs[d].dcT; k.dh0 = dirs[d].dh0; k.dc0 = dirs[d].dc0; k.db = dirs[d].db;
     k.dzx = dzx; k.part = part; k.direction = dirs[d].direction;
   }
-  pp.ndir = s.ndir; pp.B = s.B; pp.H = s.H; pp.MT = pl.MT; pp.backward = 1; pp.KW = 0; pp.wblock = wblock;
-  pp.Hq = pl.Hq; pp.bufsz = (size_t)16 * wblock;
+  pp.ndir = s.ndir; pp.B = s.B; pp.H = s.H; pp.Bp = pl.Bp; pp.backward = 1; pp.bufsz = bufsz;
   kp.seq_lens = seq_lens; kp.err = err;
-  kp.T = s.T; kp.B = s.B; kp.H = s.H; kp.ldy = s.ldy; kp.PG = pl.PG; kp.Hq = pl.Hq; kp.nch = pl.nchB;
+  kp.T = s.T; kp.B = s.B; kp.H = s.H; kp.ldy = s.ldy; kp.PG = pl.PG; kp.Hq = pl.Hq;
   hipLaunchKernelGGL(prep_kernel, dim3(128), dim3(256), 0, stream, pp);
   {
     const size_t bh = (size_t)s.B * s.H;
