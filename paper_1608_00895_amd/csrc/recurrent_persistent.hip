@@ -20,28 +20,19 @@
 //
 // Exchange between workgroups (h_t forwards; d a_t and the partial tiles
 // backwards) goes through global memory with device-scope (sc1) stores and
-// loads only, never through plain cached accesses, and the data is its own
-// ready flag:
-//   * h_t and d a_t live in four step buffers (index = step mod 4), stored
-//     [group of 4 K-rows][sequence][4]: a producer's values form whole 64-byte
-//     lines (no partial-line writes from different workgroups), and a consumer
-//     lane fetches with one 16-byte device-scope buffer load the four values it
-//     feeds to four consecutive MFMA k-steps (256 contiguous bytes per 16
-//     lanes); all loads are issued before the first MFMA.  The K index of the
-//     MFMA steps is permuted accordingly, and the resident R / R^T rows are
-//     stored in LDS in that same order.  A slot that has not been written yet holds a
-//     sentinel (one fixed NaN bit pattern); the consumer re-fetches only the
-//     16-byte chunks in which it still sees the sentinel.  Each producer, at
-//     step s, first waits until its older stores are acknowledged, then puts
-//     the sentinel back into its slots of the buffer that will be used at step
-//     s+2 (every reader of that buffer's old content is done by then), then
-//     stores its values of step s.  No flag, no acknowledgement wait and no
-//     device-wide barrier sits in the step's dependency chain.
+// loads only, never through plain cached accesses:
+//   * h_t and d a_t: the producer stores its values, waits until the stores
+//     are acknowledged (s_waitcnt vmcnt(0)), then raises its own step flag;
+//     a consumer wavefront polls only the flags of the producers whose rows it
+//     multiplies, then fetches those rows with 16-byte device-scope buffer
+//     loads, all issued before the first MFMA.  The exchange arrays are laid
+//     out in MFMA operand order so each such load is a contiguous 1 KiB per
+//     wavefront.  Buffers are double-buffered by step parity.
 //   * partial tiles: every value travels as one 64-bit word (value, step tag),
-//     double-buffered, so the owners poll the data itself.
-// No cache write-back / invalidate happens in the step loop.  All waits are
-// bounded: on expiry the kernel raises the timeout flag and every workgroup
-// leaves its loop.
+//     so the consumer polls the data itself and no flag round trip is needed.
+// There is no device-wide barrier and no cache write-back / invalidate in the
+// step loop.  All waits are bounded: on expiry the kernel raises the timeout
+// flag and every workgroup leaves its loop.
 #include "rlstm_internal.h"
 
 namespace rlstm {
@@ -81,95 +72,80 @@ __device__ __forceinline__ unsigned ld_dev(const unsigned* p) {
 __device__ __forceinline__ void wait_stores_acked() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 __device__ __forceinline__ void compiler_fence() { __atomic_signal_fence(__ATOMIC_SEQ_CST); }
 
-// "not written yet" marker of the exchange arrays: a NaN pattern no arithmetic here produces
-constexpr unsigned kSentinel = 0xFFF0DEADu;
-constexpr int kStepBuffers = 4;
+// Step flags.  Every producer keeps kFlagCopies copies of its flag, each copy set in its own
+// 4 KiB block, and a consumer workgroup polls copy (its index mod kFlagCopies): polls of one
+// memory line by many wavefronts are served one after the other, so with a single copy the
+// ~125 pollers of each line would queue behind each other for microseconds.
+constexpr int kFlagCopies = 64;
+constexpr int kFlagCopyStride = 1024;            // unsigned words between copies
+
+__device__ __forceinline__ void publish_flag(unsigned* flags, int wg, unsigned value) {
+  if (threadIdx.x < kFlagCopies) st_dev(flags + threadIdx.x * kFlagCopyStride + wg, value);
+}
+
+// A wavefront waits until flags[first .. first+count) (clipped to limit) have all reached `want`.
+__device__ __forceinline__ bool wave_wait_flags(const unsigned* flags, int first, int count, int limit,
+                                                unsigned want, unsigned* err) {
+  const int lane = threadIdx.x & 63;
+  const bool mine = lane < count && first + lane < limit;
+  const unsigned* src = flags + (mine ? first + lane : first);
+  Spin sp;
+  bool ok = true;
+  for (;;) {
+    const bool ready = !mine || ld_dev(src) >= want;
+    if (__all(ready)) break;
+    if (sp.expired(err)) { ok = false; break; }
+  }
+  compiler_fence();
+  return ok;
+}
 
 // fast gate functions: v_exp_f32 / v_rcp_f32 (about 1e-6 absolute error)
 __device__ __forceinline__ float fsigmoid(float u) { return __builtin_amdgcn_rcpf(1.0f + __expf(-u)); }
 __device__ __forceinline__ float ftanh(float u) { return 2.0f * __builtin_amdgcn_rcpf(1.0f + __expf(-2.0f * u)) - 1.0f; }
 
-// Exchange layout: [K-row group r][sequence b][4].  Forward: r = unit / 4 and the 4 entries are
-// units 4r..4r+3.  Backward: r = unit and the 4 entries are its gates i, f, o, g.
-//
-// One wavefront's share of a [B x K] * [K x 16*NT] product over row groups row0 .. row0 + 4*nJ.
-// Lane (l16, lq) fetches for chunk (J, mt) the 16 bytes of group row0 + 4J + lq, sequence
-// mt*16 + l16, and feeds entry i of it to MFMA step (J, i) as A[row l16][k index lq]; the B rows
-// of that step are bs[((J*4 + i)*4 + lq)][...] (LDS, row stride ldb floats), i.e. the caller stores
-// its resident matrix in this step order.  Chunks that still hold the sentinel are fetched again
-// until their producer has written them.  Returns false if the bounded wait expired.
+// position of element (row k of a wavefront's K range, sequence b) inside that wavefront's
+// operand-ordered block: [chunk][lane][4], L = (k/4)*MT + b/16, chunk = L/4, lane = (k%4)*16 + b%16
+template <int MT>
+__device__ __forceinline__ int operand_slot(int k, int b) {
+  const int L = (k >> 2) * MT + (b >> 4);
+  return ((L >> 2) * 64 + (k & 3) * 16 + (b & 15)) * 4 + (L & 3);
+}
+
+// One wavefront's share of a [B x K] * [K x 16*NT] product.  A rows come from the exchange
+// array (device-scope 16-byte loads, operand order), B rows from LDS (row stride ldb floats).
 template <int MT, int NT>
-__device__ __forceinline__ bool wave_product(const float* xbuf, int xbuf_bytes, int row0, int nJ, const float* bs, int ldb,
-                                             floatx4 (&acc)[MT][NT], unsigned* err) {
-  constexpr int Bp = 16 * MT;
+__device__ __forceinline__ void wave_product(const float* xblock, int xblock_bytes, int nch, const float* bs, int ldb,
+                                             floatx4 (&acc)[MT][NT]) {
   const int lane = threadIdx.x & 63, l16 = lane & 15, lq = lane >> 4;
-  __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(xbuf), 0, xbuf_bytes, 0x00020000);
-  const int nch = nJ * MT;                       // 16-byte chunks per lane
-  const int lane_off = ((row0 + lq) * Bp + l16) * 16;
-  bool ok = true;
+  __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(xblock), 0, xblock_bytes, 0x00020000);
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
   for (int c0 = 0; c0 < nch; c0 += CG) {
     floatx4 v[CG];
-    const int ng = min(nch - c0, CG);
-    unsigned pending = (1u << ng) - 1u;          // chunks of this group still to be fetched (wavefront-uniform)
-    Spin sp;
-    for (;;) {
-      // light spin on the first outstanding chunk only, so that waiting costs one 16-byte load per
-      // lane and round trip instead of re-reading the whole block
-      {
-        const int qf = __builtin_ctz(pending);
-        const int Jf = (c0 + qf) / MT, mf = (c0 + qf) % MT;
-        for (;;) {
-          const intx4 w = __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane_off + (4 * Jf * Bp + mf * 16) * 16, 0, kAuxSc1);
-          const bool unwritten = (unsigned)w[0] == kSentinel || (unsigned)w[1] == kSentinel ||
-                                 (unsigned)w[2] == kSentinel || (unsigned)w[3] == kSentinel;
-          if (!__any(unwritten)) break;
-          if (sp.expired(err)) { ok = false; break; }
-        }
-        if (!ok) break;
-      }
 #pragma unroll
-      for (int q = 0; q < CG; ++q)
-        if ((pending >> q) & 1u) {
-          const int J = c0 / MT + q / MT, mt = q % MT;
-          v[q] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(
-                                                 rsrc, lane_off + (4 * J * Bp + mt * 16) * 16, 0, kAuxSc1));
-        }
-      unsigned bad = 0;
-#pragma unroll
-      for (int q = 0; q < CG; ++q) {
-        if ((pending >> q) & 1u) {
-          const intx4 w = __builtin_bit_cast(intx4, v[q]);
-          const bool unwritten = (unsigned)w[0] == kSentinel || (unsigned)w[1] == kSentinel ||
-                                 (unsigned)w[2] == kSentinel || (unsigned)w[3] == kSentinel;
-          if (__any(unwritten)) bad |= 1u << q;
-        }
-      }
-      pending = bad;
-      if (!pending) break;
-      if (sp.expired(err)) { ok = false; break; }
-    }
+    for (int q = 0; q < CG; ++q)
+      v[q] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, ((c0 + q) * 64 + lane) * 16, 0, kAuxSc1));
+    // chunks past nch read beyond the buffer resource's size and return zeros; their MFMAs are skipped
 #pragma unroll
     for (int q = 0; q < CG; ++q) {
-      if (q < ng) {
-        const int J = c0 / MT + q / MT;
-        const int mt = q % MT;
+      if (c0 + q < nch) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int w = 0; w < 4; ++w) {
+          constexpr int KPC = 4 / MT;                 // k-steps per chunk
+          const int ks = (c0 + q) * KPC + w / MT;
+          const int mt = w % MT;
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt) {
-            const float bf = bs[((J * 4 + i) * 4 + lq) * ldb + nt * 16 + l16];
-            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(v[q][i], bf, acc[mt][nt], 0, 0, 0);
+            const float bf = bs[(ks * 4 + lq) * ldb + nt * 16 + l16];
+            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(v[q][w], bf, acc[mt][nt], 0, 0, 0);
           }
         }
       }
     }
   }
-  compiler_fence();
-  return ok;
 }
 
 // ---------------------------------------------------------------------------
@@ -178,14 +154,15 @@ __device__ __forceinline__ bool wave_product(const float* xbuf, int xbuf_bytes, 
 struct PFwdDir {
   float* zg; const float* R; const float* h0; const float* c0;
   float* y; float* c; float* hT; float* cT;
-  float* hx;            // kStepBuffers x [Hp/4][Bp][4]
+  float* hx;            // 2 x [4 wavefronts][nch][64][4]
+  unsigned* flags;      // [Gf]
   int direction;
 };
 struct PFwdParams {
   PFwdDir d[2];
   const int32_t* seq_lens;
   unsigned* err;
-  int T, B, H, ldy, Gf, Hp;
+  int T, B, H, ldy, Gf, Hp, nch;
 };
 
 // Workgroup = 4 compute wavefronts (threads 0..255) + 1 I/O wavefront (threads 256..319).
@@ -204,10 +181,9 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
   extern __shared__ __align__(16) float lds[];
   const int dir = blockIdx.x / p.Gf, wg = blockIdx.x % p.Gf;
   const PFwdDir& D = p.d[dir];
-  constexpr int Bp = 16 * MT;
-  const int T = p.T, B = p.B, H = p.H, Hp = p.Hp;
+  const int T = p.T, B = p.B, H = p.H, Hp = p.Hp, nch = p.nch;
   const int u0 = wg * U;
-  float* Rs = lds;                               // [Hp][NC], rows in MFMA step order (see wave_product)
+  float* Rs = lds;                               // [Hp][NC]
   float* Red = Rs + (size_t)Hp * NC;             // [4][MT][NT][256]
   float* zin = Red + 4 * MT * NT * 256;          // [2][4][NE]  input part of the frame, per gate
   float* gout = zin + 2 * 4 * NE;                // [2][6][NE]  gates i,f,o,g, y, c of the frame
@@ -217,17 +193,16 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
   const bool is_io = wave == 4;
   const int lane = tid & 63;
 
-  const int KW = Hp / 4;                         // rows of h per wavefront (multiple of 16)
-  // resident slice of R: slice column g*U + uu is column g*H + u0 + uu of R; LDS row
-  // w*KW + (J*4 + i)*4 + lq holds row k = w*KW + 16J + 4lq + i of R
+  // resident slice of R: slice column g*U + uu is column g*H + u0 + uu of R
   for (int idx = tid; idx < Hp * NC; idx += kBlockThreads) {
-    const int row = idx / NC, col = idx % NC;
-    const int w = row / KW, r = row % KW;
-    const int k = w * KW + (r >> 4) * 16 + (r & 3) * 4 + ((r >> 2) & 3);
+    const int k = idx / NC, col = idx % NC;
     const int g = col / U, u = u0 + col % U;
     Rs[idx] = (k < H && u < H) ? D.R[(size_t)k * 4 * H + g * H + u] : 0.f;
   }
-  const size_t hxsz = (size_t)Hp * Bp;           // floats per step buffer
+
+  const int KW = Hp / 4;                         // rows of h per wavefront
+  const int wblock = nch * 256;                  // floats of one wavefront's operand block
+  const size_t hxsz = (size_t)4 * wblock;
 
   // compute threads: carried state of the pairs they own
   float hreg[EPT], creg[EPT];
@@ -243,7 +218,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
       if (D.h0) hreg[e] = D.h0[(size_t)eb[e] * H + eu[e]];
       if (D.c0) creg[e] = D.c0[(size_t)eb[e] * H + eu[e]];
       elen[e] = min(max(p.seq_lens[eb[e]], 0), T);
-      eslot[e] = ((eu[e] >> 2) * Bp + eb[e]) * 4 + (eu[e] & 3);
+      eslot[e] = (eu[e] / KW) * wblock + operand_slot<MT>(eu[e] % KW, eb[e]);
     }
   }
   // I/O lanes: the pairs they move
@@ -292,19 +267,20 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
   }
   __syncthreads();
 
+  const int prod_first = wave * KW / U, prod_count = KW / U;
+  const unsigned* myflags = D.flags + (wg % kFlagCopies) * kFlagCopyStride;
 
   for (int s = 0; s < T; ++s) {
     const int t = D.direction > 0 ? s : T - 1 - s;
-    const float* hprev = D.hx + (size_t)((s + 3) & 3) * hxsz;    // h of step s-1
-    float* hcur = D.hx + (size_t)(s & 3) * hxsz;
-    float* hreset = D.hx + (size_t)((s + 2) & 3) * hxsz;         // holds h of step s-2: nobody reads it any more
+    const float* hprev = D.hx + (size_t)((s + 1) & 1) * hxsz;
+    float* hcur = D.hx + (size_t)(s & 1) * hxsz;
     int fail = 0;
 
     if (!is_io) {
-      // h_prev * R over this wavefront's rows of h_prev, fetched as soon as their producers have written them
+      // h of the previous step: wait for the producers of this wavefront's rows, then h_prev * R
+      if (s > 0 && !wave_wait_flags(myflags, prod_first, prod_count, p.Gf, (unsigned)s, p.err)) fail = 1;
       floatx4 acc[MT][NT];
-      if (!wave_product<MT, NT>(hprev, (int)(hxsz * 4), wave * (KW / 4), KW / 16, Rs + (size_t)wave * KW * NC, NC, acc, p.err))
-        fail = 1;
+      wave_product<MT, NT>(hprev + (size_t)wave * wblock, wblock * 4, nch, Rs + (size_t)wave * KW * NC, NC, acc);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -348,20 +324,15 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
         const float hn = go * ftanh(cn);
         const bool valid = t < elen[e];
         if (valid) { creg[e] = cn; hreg[e] = hn; }
+        st_dev(hcur + eslot[e], hreg[e]);
         ocur[0 * NE + j] = gi; ocur[1 * NE + j] = gf; ocur[2 * NE + j] = go; ocur[3 * NE + j] = gg;
         ocur[4 * NE + j] = valid ? hn : 0.f;
         ocur[5 * NE + j] = creg[e];
       }
-      // older stores (issued a step ago) acknowledged -> sentinel into the buffer of step s+2 -> publish h of step s
       wait_stores_acked();
-#pragma unroll
-      for (int e = 0; e < EPT; ++e)
-        if (ev[e]) st_dev(reinterpret_cast<unsigned*>(hreset) + eslot[e], kSentinel);
-#pragma unroll
-      for (int e = 0; e < EPT; ++e)
-        if (ev[e]) st_dev(hcur + eslot[e], hreg[e]);
     }
     __syncthreads();
+    publish_flag(D.flags, wg, (unsigned)(s + 1));
 
   }
   __syncthreads();
@@ -381,15 +352,16 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
 struct PBwdDir {
   float* zg; const float* R; const float* c; const float* c0; const float* dy;
   const float* dhT; const float* dcT; float* dh0; float* dc0; float* db;
-  float* dzx;                   // kStepBuffers x [4*Hq units][Bp][4 gates]
+  float* dzx;                   // 2 x [4 quarters][4 wavefronts][nch][64][4]
   unsigned long long* part;     // 2 x [PG][4][Bp][UG] (value, tag)
+  unsigned* flags;              // [Gb]
   int direction;
 };
 struct PBwdParams {
   PBwdDir d[2];
   const int32_t* seq_lens;
   unsigned* err;
-  int T, B, H, ldy, PG, Hq;
+  int T, B, H, ldy, PG, Hq, nch;
 };
 
 // Same workgroup shape as the forward kernel: 4 compute wavefronts + 1 I/O wavefront that stages
@@ -406,9 +378,9 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
   const int dir = blockIdx.x / Gb, wg = blockIdx.x % Gb;
   const int pg = wg >> 2, qq = wg & 3;           // unit group, K quarter (also: which quarter of the group it owns)
   const PBwdDir& D = p.d[dir];
-  const int T = p.T, B = p.B, H = p.H, Hq = p.Hq;
+  const int T = p.T, B = p.B, H = p.H, Hq = p.Hq, nch = p.nch;
   const int u0 = wg * U;                         // owned units
-  float* RTs = lds;                              // [4*Hq][UG], rows in MFMA step order (see wave_product)
+  float* RTs = lds;                              // [4*Hq][UG]
   float* Red = RTs + (size_t)4 * Hq * UG;        // [4][MT][NT][256]
   float* bin = Red + 4 * MT * NT * 256;          // [2][7][NE]  gates i,f,o,g, c, c_prev, dy of the frame
   float* dzo = bin + 2 * 7 * NE;                 // [2][4][NE]  d a of the frame
@@ -419,20 +391,22 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
   const int lane = tid & 63;
   const int UW = Hq / 4;                         // units per wavefront of a quarter
   // Quarters that hold no unit (small H) contribute nothing: their workgroups publish no partial
-  // tile and owners do not wait for one.  Every workgroup that does publish is paced by the d a
+  // tile and owners do not wait for one.  Every workgroup that does publish is paced by the flags
   // of real producers, so no tile is overwritten before its owners have read it.
   const int nq = (H + Hq - 1) / Hq;
 
-  // resident rows of R^T: LDS row w*Hq + (J*4 + g)*4 + lq holds, for unit uk = qq*Hq + w*UW + 4J + lq
-  // and gate g, the values R[pg*UG + n][g*H + uk], n = 0..UG-1
+  // resident rows of R^T: row r = (wavefront w, unit ur of it, gate g) -> unit uk = qq*Hq + w*UW + ur;
+  // RTs[r][n] = R[pg*UG + n][g*H + uk]
   for (int idx = tid; idx < 4 * Hq * UG; idx += kBlockThreads) {
-    const int row = idx / UG, n = idx % UG;
-    const int w = row / Hq, r = row % Hq;
-    const int uk = qq * Hq + w * UW + (r >> 4) * 4 + (r & 3), g = (r >> 2) & 3;
+    const int r = idx / UG, n = idx % UG;
+    const int w = r / Hq, rr = r % Hq;
+    const int uk = qq * Hq + w * UW + (rr >> 2), g = rr & 3;
     const int un = pg * UG + n;
     RTs[idx] = (uk < H && un < H) ? D.R[(size_t)un * 4 * H + g * H + uk] : 0.f;
   }
-  const size_t xsz = (size_t)16 * Hq * Bp;       // floats per step buffer
+
+  const int wblock = nch * 256;                  // floats per (quarter, wavefront) operand block
+  const size_t xsz = (size_t)16 * wblock;
   const size_t psz = (size_t)p.PG * 4 * Bp * UG;
 
   // compute threads: carried gradients of the pairs they own
@@ -451,7 +425,9 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
       if (D.dhT) Dh[e] = D.dhT[(size_t)eb[e] * H + eu[e]];
       if (D.dcT) Dc[e] = D.dcT[(size_t)eb[e] * H + eu[e]];
       elen[e] = min(max(p.seq_lens[eb[e]], 0), T);
-      eslot[e] = (eu[e] * Bp + eb[e]) * 4;         // the 4 gates of (unit, sequence) are one 16-byte entry
+      // d a of unit u, gate g sits in quarter u/Hq, wavefront (u%Hq)/UW, row ((u%Hq)%UW)*4 + g
+      const int ul = eu[e] % Hq;
+      eslot[e] = ((eu[e] / Hq) * 4 + ul / UW) * wblock + operand_slot<MT>((ul % UW) * 4, eb[e]);
     }
   }
 
@@ -519,6 +495,9 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
   }
   __syncthreads();
 
+  // producers of this wavefront's rows: owners of units [qq*Hq + wave*UW, +UW)
+  const int prod_first = (qq * Hq + wave * UW) / U, prod_count = UW / U;
+  const unsigned* myflags = D.flags + (wg % kFlagCopies) * kFlagCopyStride;
 
   // sums the partial tiles of step `step` for the owned pairs (tag = step + 1)
   auto collect = [&](int step, float (&out)[EPT]) -> int {
@@ -555,7 +534,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
 
   for (int s = 0; s < T; ++s) {
     const int t = frame_of(s);
-    const float* dzcur = D.dzx + (size_t)(s & 3) * xsz;        // buffer (s+2) mod 4 holds d a of step s-2: nobody reads it any more
+    float* dzcur = D.dzx + (size_t)(s & 1) * xsz;
     int fail = 0;
 
     if (!is_io) {
@@ -569,14 +548,12 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
       // gate derivatives; publish d a of this frame
       const float* in = bin + (s & 1) * 7 * NE;
       float* out = dzo + (s & 1) * 4 * NE;
-      float dz[EPT][4];
 #pragma unroll
       for (int e = 0; e < EPT; ++e) {
         vprev[e] = false;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) dz[e][g] = 0.f;
         if (!ev[e]) continue;
         const int j = tid + e * 256;
+        float dz[4] = {0.f, 0.f, 0.f, 0.f};
         const bool m = t < elen[e];
         vprev[e] = m;
         if (m) {
@@ -585,33 +562,20 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
           const float dh = in[6 * NE + j] + Dh[e];
           const float d_o = dh * tc;
           const float dc = Dc[e] + dh * go * (1.0f - tc * tc);
-          dz[e][0] = dc * gg * gi * (1.0f - gi);
-          dz[e][1] = dc * in[5 * NE + j] * gf * (1.0f - gf);
-          dz[e][2] = d_o * go * (1.0f - go);
-          dz[e][3] = dc * gi * (1.0f - gg * gg);
+          dz[0] = dc * gg * gi * (1.0f - gi);
+          dz[1] = dc * in[5 * NE + j] * gf * (1.0f - gf);
+          dz[2] = d_o * go * (1.0f - go);
+          dz[3] = dc * gi * (1.0f - gg * gg);
           Dc[e] = dc * gf;
         }
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          out[g * NE + j] = dz[e][g];
-          dbacc[e][g] += dz[e][g];
+          st_dev(dzcur + eslot[e] + g * 64, dz[g]);      // rows (unit, gate 0..3) are 16 lanes apart in operand order
+          out[g * NE + j] = dz[g];
+          dbacc[e][g] += dz[g];
         }
       }
-      // older stores (issued a step ago) acknowledged -> sentinel into the buffer of step s+2 -> publish d a of step s
       wait_stores_acked();
-      {
-        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(D.dzx, 0, (int)(kStepBuffers * xsz * 4), 0x00020000);
-        const intx4 sent = intx4{(int)kSentinel, (int)kSentinel, (int)kSentinel, (int)kSentinel};
-#pragma unroll
-        for (int e = 0; e < EPT; ++e)
-          if (ev[e])
-            __builtin_amdgcn_raw_buffer_store_b128(sent, rs, (int)((((s + 2) & 3) * xsz + eslot[e]) * 4), 0, kAuxSc1);
-#pragma unroll
-        for (int e = 0; e < EPT; ++e)
-          if (ev[e])
-            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(intx4, floatx4{dz[e][0], dz[e][1], dz[e][2], dz[e][3]}), rs,
-                                                   (int)(((s & 3) * xsz + eslot[e]) * 4), 0, kAuxSc1);
-      }
     } else {
       // stage the next frame's inputs (loaded a step ago), write out the previous frame's d a,
       // start loading the frame after next: every wait here is on work issued a step ago
@@ -623,12 +587,14 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
       if (tid == 0) st_dev(p.err, 1u);
       return;
     }
+    publish_flag(D.flags, wg, (unsigned)(s + 1));
+
     // this workgroup's quarter of d a_t R^T for its unit group
     fail = 0;
     if (!is_io && qq < nq) {
+      if (!wave_wait_flags(myflags, prod_first, prod_count, Gb, (unsigned)(s + 1), p.err)) fail = 1;
       floatx4 acc[MT][NT];
-      if (!wave_product<MT, NT>(dzcur, (int)(xsz * 4), qq * Hq + wave * UW, UW / 4, RTs + (size_t)wave * Hq * UG, UG, acc, p.err))
-        fail = 1;
+      wave_product<MT, NT>(dzcur + (size_t)(qq * 4 + wave) * wblock, wblock * 4, nch, RTs + (size_t)wave * Hq * UG, UG, acc);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -698,47 +664,45 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
 }
 
 // ---------------------------------------------------------------------------
-// set-up kernels: clear the exchange arrays and tile tags (padding slots stay 0 for good), then put
-// the sentinel into every slot that a producer will write, and h0 where step 0 reads it
+// set-up kernel: clears flags, exchange arrays and tags; seeds h0 in operand order
 // ---------------------------------------------------------------------------
 struct PrepParams {
-  unsigned* zero_words[2]; size_t nzero[2];       // per direction: words to clear (exchange arrays [+ partial tiles])
-  float* xbase[2]; const float* h0[2];            // exchange arrays; forward only: h0 or null
-  int ndir, B, H, Bp, backward;
-  size_t bufsz;                                   // floats per step buffer
+  unsigned* zero_words[2]; size_t nzero[2];       // per direction: words to clear (flags + exchange [+ partial tiles])
+  float* hx1[2]; const float* h0[2];              // forward only: buffer 1 of the h exchange, h0 or null
+  int ndir, B, H, KW, wblock, MT;
 };
 __global__ __launch_bounds__(256) void prep_kernel(PrepParams p) {
   const size_t gtid = (size_t)blockIdx.x * 256 + threadIdx.x, gsz = (size_t)gridDim.x * 256;
-  for (int d = 0; d < p.ndir; ++d)
+  for (int d = 0; d < p.ndir; ++d) {
     for (size_t i = gtid; i < p.nzero[d]; i += gsz) p.zero_words[d][i] = 0u;
+  }
+  // h0 lands in words this same thread grid has just cleared; order the two phases per thread
+  // by letting each thread write only h0 elements, after all clears, in a second kernel launch.
 }
-__global__ __launch_bounds__(256) void seed_kernel(PrepParams p) {
+__global__ __launch_bounds__(256) void seed_h0_kernel(PrepParams p) {
   const size_t gtid = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (gtid >= (size_t)p.B * p.H) return;
   const int b = (int)(gtid / p.H), u = (int)(gtid % p.H);
   for (int d = 0; d < p.ndir; ++d) {
-    unsigned* x = reinterpret_cast<unsigned*>(p.xbase[d]);
-    if (!p.backward) {
-      const size_t slot = ((size_t)(u >> 2) * p.Bp + b) * 4 + (u & 3);
-      for (int k = 0; k < kStepBuffers - 1; ++k) x[k * p.bufsz + slot] = kSentinel;
-      // step 0 reads buffer (0 - 1) mod 4 = 3
-      p.xbase[d][(size_t)(kStepBuffers - 1) * p.bufsz + slot] = p.h0[d] ? p.h0[d][gtid] : 0.f;
-    } else {
-      const size_t slot = ((size_t)u * p.Bp + b) * 4;
-      for (int k = 0; k < kStepBuffers; ++k)
-        for (int g = 0; g < 4; ++g) x[k * p.bufsz + slot + g] = kSentinel;
-    }
+    if (!p.h0[d]) continue;
+    const int k = u % p.KW;
+    int slot;
+    if (p.MT == 1) slot = operand_slot<1>(k, b);
+    else if (p.MT == 2) slot = operand_slot<2>(k, b);
+    else slot = operand_slot<4>(k, b);
+    p.hx1[d][(size_t)(u / p.KW) * p.wblock + slot] = p.h0[d][gtid];
   }
 }
 
 // ---- host side ----------------------------------------------------------------
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+constexpr size_t kFlagBytes = (size_t)kFlagCopies * kFlagCopyStride * sizeof(unsigned);
 
 struct Plan {
   bool ok;
   int MT, NT, U, UG, Bp;
-  int Gf, Hp;
-  int PG, Gb, Hq;
+  int Gf, Hp, nchF;
+  int PG, Gb, Hq, nchB;
   size_t ldsF, ldsB;
 };
 
@@ -758,6 +722,8 @@ Plan make_plan(const RecShape& s, int num_cus, size_t max_lds) {
     if (Gf > per_dir || Gb > per_dir) continue;
     const int Hp = (int)align_up((size_t)s.H, 64);
     const int Hq = (int)align_up((size_t)PG * U, 32);
+    // a wavefront polls at most 64 producers
+    if (Hp / 4 / U > 64 || Hq / 4 / U > 64) continue;
     const size_t red = (size_t)4 * pl.MT * NT * 256;
     const size_t lf = ((size_t)Hp * 16 * NT + red + (size_t)(2 * 4 + 2 * 6) * pl.MT * 16 * U) * sizeof(float);
     const size_t lb = ((size_t)4 * Hq * UG + red + (size_t)(2 * 7 + 2 * 4) * pl.MT * 16 * U) * sizeof(float);
@@ -768,8 +734,8 @@ Plan make_plan(const RecShape& s, int num_cus, size_t max_lds) {
     const size_t exclusive = max_lds / 2 + 1024;
     const size_t lf_req = lf > exclusive ? lf : exclusive, lb_req = lb > exclusive ? lb : exclusive;
     pl.ok = true; pl.NT = NT; pl.U = U; pl.UG = UG;
-    pl.Gf = Gf; pl.Hp = Hp;
-    pl.PG = PG; pl.Gb = Gb; pl.Hq = Hq;
+    pl.Gf = Gf; pl.Hp = Hp; pl.nchF = (Hp / 16) * pl.MT / 4;
+    pl.PG = PG; pl.Gb = Gb; pl.Hq = Hq; pl.nchB = (Hq / 4) * pl.MT / 4;
     pl.ldsF = lf_req; pl.ldsB = lb_req;
     return pl;
   }
@@ -804,14 +770,14 @@ bool persistent_supported(const RecShape& s, int num_cus, size_t max_lds) {
 }
 
 // Upper bound (independent of the device) of the per-direction scratch, in bytes:
-// [exchange arrays][partial tiles].
+// [flag copies][exchange arrays][partial tiles].
 size_t persistent_scratch_bytes_per_dir(const RecShape& s) {
   const size_t Bp = s.B <= 16 ? 16 : (s.B <= 32 ? 32 : 64);
   const size_t Hp = align_up((size_t)s.H, 64);
   const size_t Hq = align_up((size_t)s.H / 4 + 8, 32);
-  const size_t exch = kStepBuffers * (Hp > 16 * Hq ? Hp : 16 * Hq) * Bp * sizeof(float);
+  const size_t exch = 2 * (Hp > 16 * Hq ? Hp : 16 * Hq) * Bp * sizeof(float);
   const size_t part = 2 * 4 * Bp * ((size_t)s.H + 32) * sizeof(unsigned long long);
-  return align_up(exch, 256) + align_up(part, 256);
+  return kFlagBytes + align_up(exch, 256) + align_up(part, 256);
 }
 
 hipError_t persistent_forward(hipStream_t stream, const RecShape& s, const RecFwdDir* dirs, const int32_t* seq_lens,
@@ -821,27 +787,28 @@ hipError_t persistent_forward(hipStream_t stream, const RecShape& s, const RecFw
   if (e != hipSuccess) return e;
   const Plan pl = make_plan(s, di.num_cus, di.max_lds);
   if (!pl.ok) { *resident_err = 1; return hipErrorInvalidValue; }
-  const size_t bufsz = (size_t)pl.Hp * pl.Bp;
+  const int wblock = pl.nchF * 256;
   PrepParams pp{};
   PFwdParams kp{};
   for (int d = 0; d < s.ndir; ++d) {
-    float* hx = reinterpret_cast<float*>(scratch[d]);
-    pp.zero_words[d] = reinterpret_cast<unsigned*>(hx);
-    pp.nzero[d] = (size_t)kStepBuffers * bufsz;
-    pp.xbase[d] = hx;
+    unsigned* flags = reinterpret_cast<unsigned*>(scratch[d]);
+    float* hx = reinterpret_cast<float*>(scratch[d] + kFlagBytes);
+    pp.zero_words[d] = flags;
+    pp.nzero[d] = kFlagBytes / 4 + (size_t)2 * 4 * wblock;
+    pp.hx1[d] = hx + (size_t)4 * wblock;
     pp.h0[d] = dirs[d].h0;
     PFwdDir& k = kp.d[d];
     k.zg = dirs[d].zg; k.R = dirs[d].R; k.h0 = dirs[d].h0; k.c0 = dirs[d].c0;
     k.y = dirs[d].y; k.c = dirs[d].c; k.hT = dirs[d].hT; k.cT = dirs[d].cT;
-    k.hx = hx; k.direction = dirs[d].direction;
+    k.hx = hx; k.flags = flags; k.direction = dirs[d].direction;
   }
-  pp.ndir = s.ndir; pp.B = s.B; pp.H = s.H; pp.Bp = pl.Bp; pp.backward = 0; pp.bufsz = bufsz;
+  pp.ndir = s.ndir; pp.B = s.B; pp.H = s.H; pp.KW = pl.Hp / 4; pp.wblock = wblock; pp.MT = pl.MT;
   kp.seq_lens = seq_lens; kp.err = err;
-  kp.T = s.T; kp.B = s.B; kp.H = s.H; kp.ldy = s.ldy; kp.Gf = pl.Gf; kp.Hp = pl.Hp;
+  kp.T = s.T; kp.B = s.B; kp.H = s.H; kp.ldy = s.ldy; kp.Gf = pl.Gf; kp.Hp = pl.Hp; kp.nch = pl.nchF;
   hipLaunchKernelGGL(prep_kernel, dim3(64), dim3(256), 0, stream, pp);
-  {
+  if (pp.h0[0] || (s.ndir > 1 && pp.h0[1])) {
     const size_t bh = (size_t)s.B * s.H;
-    hipLaunchKernelGGL(seed_kernel, dim3((unsigned)((bh + 255) / 256)), dim3(256), 0, stream, pp);
+    hipLaunchKernelGGL(seed_h0_kernel, dim3((unsigned)((bh + 255) / 256)), dim3(256), 0, stream, pp);
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -862,30 +829,26 @@ hipError_t persistent_backward(hipStream_t stream, const RecShape& s, const RecB
   if (e != hipSuccess) return e;
   const Plan pl = make_plan(s, di.num_cus, di.max_lds);
   if (!pl.ok) { *resident_err = 1; return hipErrorInvalidValue; }
-  const size_t bufsz = (size_t)16 * pl.Hq * pl.Bp;
-  const size_t exch_floats = (size_t)kStepBuffers * bufsz;
+  const int wblock = pl.nchB * 256;
+  const size_t exch_floats = (size_t)2 * 16 * wblock;
   const size_t part_words = (size_t)2 * pl.PG * 4 * pl.Bp * pl.UG;
   PrepParams pp{};
   PBwdParams kp{};
   for (int d = 0; d < s.ndir; ++d) {
-    float* dzx = reinterpret_cast<float*>(scratch[d]);
+    unsigned* flags = reinterpret_cast<unsigned*>(scratch[d]);
+    float* dzx = reinterpret_cast<float*>(scratch[d] + kFlagBytes);
     unsigned long long* part = reinterpret_cast<unsigned long long*>(dzx + align_up(exch_floats, 64));
-    pp.zero_words[d] = reinterpret_cast<unsigned*>(dzx);
-    pp.nzero[d] = align_up(exch_floats, 64) + 2 * part_words;
-    pp.xbase[d] = dzx; pp.h0[d] = nullptr;
+    pp.zero_words[d] = flags;
+    pp.nzero[d] = kFlagBytes / 4 + align_up(exch_floats, 64) + 2 * part_words;
     PBwdDir& k = kp.d[d];
     k.zg = dirs[d].zg; k.R = dirs[d].R; k.c = dirs[d].c; k.c0 = dirs[d].c0; k.dy = dirs[d].dy;
     k.dhT = dirs[d].dhT; k.dcT = dirs[d].dcT; k.dh0 = dirs[d].dh0; k.dc0 = dirs[d].dc0; k.db = dirs[d].db;
-    k.dzx = dzx; k.part = part; k.direction = dirs[d].direction;
+    k.dzx = dzx; k.part = part; k.flags = flags; k.direction = dirs[d].direction;
   }
-  pp.ndir = s.ndir; pp.B = s.B; pp.H = s.H; pp.Bp = pl.Bp; pp.backward = 1; pp.bufsz = bufsz;
+  pp.ndir = s.ndir;
   kp.seq_lens = seq_lens; kp.err = err;
-  kp.T = s.T; kp.B = s.B; kp.H = s.H; kp.ldy = s.ldy; kp.PG = pl.PG; kp.Hq = pl.Hq;
+  kp.T = s.T; kp.B = s.B; kp.H = s.H; kp.ldy = s.ldy; kp.PG = pl.PG; kp.Hq = pl.Hq; kp.nch = pl.nchB;
   hipLaunchKernelGGL(prep_kernel, dim3(128), dim3(256), 0, stream, pp);
-  {
-    const size_t bh = (size_t)s.B * s.H;
-    hipLaunchKernelGGL(seed_kernel, dim3((unsigned)((bh + 255) / 256)), dim3(256), 0, stream, pp);
-  }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int grid = pl.Gb * s.ndir;
