@@ -428,13 +428,7 @@ int blstm_stack_fwd_bwd(const rblstm_desc* d, const float* x, const float* const
       ProfScope ps(sa, 2, l, 2);
       RLSTM_TRY_C(rec_backward(sa, rs, dirs, seq_lens, recws, flag, persistent, &resident_err));
     }
-    if (overlap) {
-      hipEvent_t ev;
-      RLSTM_TRY_C(new_event(&ev));
-      RLSTM_TRY_C(hipEventRecord(ev, sa));
-      RLSTM_TRY_C(hipStreamWaitEvent(sb, ev, 0));
-    }
-    // input gradient = next lower layer's dy (chain on stream a)
+    // input gradient = next lower layer's dy: on the dependent chain (stream a), so it runs first and alone
     float* dxl = (l == 0) ? dx : dybuf[l & 1];
     if (dxl) {
       for (int k = 0; k < 2; ++k) {
@@ -448,7 +442,14 @@ int blstm_stack_fwd_bwd(const rblstm_desc* d, const float* x, const float* const
         RLSTM_TRY_C(gemm(sa, g));
       }
     }
-    // weight gradients (independent of the chain: stream b)
+    // weight gradients are independent of the chain: stream b, released once the input gradient is
+    // done, so that they overlap the next layer's pass back through time rather than compete with dX
+    if (overlap) {
+      hipEvent_t ev;
+      RLSTM_TRY_C(new_event(&ev));
+      RLSTM_TRY_C(hipEventRecord(ev, sa));
+      RLSTM_TRY_C(hipStreamWaitEvent(sb, ev, 0));
+    }
     for (int k = 0; k < 2; ++k) {
       rc = weight_grads(sb, l, T, B, din, H, k == 0 ? 1 : -1, xin, din, yl + (size_t)k * H, 2 * H,
                         base + lay.zg[k], grads[6 * l + 3 * k + 0], grads[6 * l + 3 * k + 1], skws, skfloats,
