@@ -88,6 +88,9 @@ def main():
     ap.add_argument("--engine", type=int, default=0)
     ap.add_argument("--one-stream", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="after the timed region, run one plain 1 GiB copy kernel (known HBM traffic) "
+                         "so that a counter-collecting profiler run can scale FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -135,6 +138,12 @@ def main():
     rl.rlstm_profile_enable(False)
     prof = rl.rlstm_profile_read(1 << 16)
     assert rl.rlstm_last_timeout(ws) == 0
+    if args.calibration_copy:
+        n = 1 << 28
+        src = torch.ones(n, device=dev)
+        dst = torch.empty(n, device=dev)
+        rl.rlstm_copy_f32(dst, src, n)
+        torch.cuda.synchronize()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     frames_per_s = wl.frames / (ms_per_step * 1e-3)
 

@@ -203,6 +203,13 @@ typedef struct rlstm_profile_entry {
 RLSTM_API int rlstm_profile_enable(int on);
 RLSTM_API int rlstm_profile_read(rlstm_profile_entry* out, int max_entries);
 
+/*
+ * rlstm_copy_f32 - plain device-to-device copy kernel of n floats (one float4 per
+ * thread, grid-stride).  Measurement utility: a kernel of exactly known HBM traffic
+ * (4n bytes read, 4n bytes written) against which hardware counters are scaled.
+ */
+RLSTM_API int rlstm_copy_f32(float* dst, const float* src, size_t n, void* hip_stream);
+
 /* Reads (with a blocking device-to-host copy) the timeout flag that the
  * persistent kernels keep at the start of `workspace`: 0 = no bounded wait
  * expired since the last call that used this workspace, 1 = one did and the

@@ -24,7 +24,7 @@ RLSTM_ENGINE_STEPWISE = 2
 EXPORTS = [
     "rlstm_reserve_bytes", "rlstm_workspace_bytes", "rblstm_reserve_bytes", "rblstm_workspace_bytes",
     "lstm_fwd", "lstm_bwd", "blstm_stack_fwd_bwd", "blstm_stack_fwd",
-    "rlstm_gemm_f32", "rlstm_profile_enable", "rlstm_profile_read", "rlstm_last_timeout", "rlstm_resolve_engine", "rlstm_strerror", "rlstm_version",
+    "rlstm_gemm_f32", "rlstm_copy_f32", "rlstm_profile_enable", "rlstm_profile_read", "rlstm_last_timeout", "rlstm_resolve_engine", "rlstm_strerror", "rlstm_version",
 ]
 
 
@@ -81,6 +81,8 @@ def lib() -> ctypes.CDLL:
         L.blstm_stack_fwd.argtypes = [ctypes.POINTER(rblstm_desc), vp, ctypes.POINTER(vp), vp, vp, vp, vp, vp]
         L.rlstm_gemm_f32.restype = ip
         L.rlstm_gemm_f32.argtypes = [ip, ip, ip, ip, ip, vp, ip, vp, ip, vp, ip, vp, vp, ctypes.c_size_t, vp]
+        L.rlstm_copy_f32.restype = ip
+        L.rlstm_copy_f32.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.rlstm_profile_enable.restype = ip
         L.rlstm_profile_enable.argtypes = [ip]
         L.rlstm_profile_read.restype = ip
@@ -213,3 +215,10 @@ def rlstm_profile_read(max_entries: int = 4096):
     if n < 0:
         raise RlstmError(n, "rlstm_profile_read")
     return [(buf[i].kind, buf[i].layer, buf[i].ndir, float(buf[i].ms)) for i in range(min(n, max_entries))]
+
+
+def rlstm_copy_f32(dst, src, n, stream=None, check=True) -> int:
+    rc = lib().rlstm_copy_f32(_ptr(dst), _ptr(src), int(n), _stream(stream))
+    if check and rc != 0:
+        raise RlstmError(rc, "rlstm_copy_f32")
+    return rc

@@ -232,6 +232,13 @@ int rlstm_last_timeout(const void* workspace) {
   return v != 0 ? 1 : 0;
 }
 
+int rlstm_copy_f32(float* dst, const float* src, size_t n, void* hip_stream) {
+  if (!dst || !src) return RLSTM_ENULL;
+  int resident_err = 0;
+  RLSTM_TRY(copy_f32(static_cast<hipStream_t>(hip_stream), dst, src, n));
+  return RLSTM_OK;
+}
+
 int rlstm_profile_enable(int on) {
   g_prof_on = on != 0;
   return RLSTM_OK;

@@ -159,6 +159,14 @@ __global__ __launch_bounds__(256) void add_h0_outer_kernel(int T, int B, int H, 
 
 __global__ void clear_flag_kernel(unsigned* flag) { *flag = 0u; }
 
+__global__ __launch_bounds__(256) void copy_f32_kernel(float* __restrict__ dst, const float* __restrict__ src, size_t n) {
+  const size_t n4 = n / 4;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride)
+    reinterpret_cast<float4*>(dst)[i] = reinterpret_cast<const float4*>(src)[i];
+  for (size_t i = n4 * 4 + (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
 
 }  // namespace
 
@@ -174,6 +182,11 @@ hipError_t device_info(DeviceInfo* out) {
   out->num_cus = cus;
   out->max_lds = (size_t)lds;
   return hipSuccess;
+}
+
+hipError_t copy_f32(hipStream_t stream, float* dst, const float* src, size_t n) {
+  hipLaunchKernelGGL(copy_f32_kernel, dim3(4096), dim3(256), 0, stream, dst, src, n);
+  return hipGetLastError();
 }
 
 hipError_t clear_flag(hipStream_t stream, unsigned* flag) {

@@ -93,6 +93,8 @@ hipError_t add_h0_outer(hipStream_t stream, int T, int B, int H, int direction, 
                         const float* dz, const int32_t* seq_lens, float* dR);
 // column sums of a [rows, cols] matrix (stepwise engine's bias gradient)
 hipError_t column_sum(hipStream_t stream, const float* a, size_t rows, int cols, int lda, float* out);
+// plain copy kernel (counter calibration)
+hipError_t copy_f32(hipStream_t stream, float* dst, const float* src, size_t n);
 // zero the timeout flag
 hipError_t clear_flag(hipStream_t stream, unsigned* flag);
 
