@@ -165,9 +165,18 @@ def main():
         kernels.append(e)
         log(e)
     dom = max(kernels, key=lambda e: e["ms_per_step"])
+    # bytes per launch at the L2-to-fabric interface, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+    # summarised in profiles/blstm_stack_config3_hbm_counters.md (config 3 only; scaled by the copy kernel)
+    measured_traffic = {"recurrent_forward": 5.306e9 + 2.560e9, "recurrent_backward": 11.274e9 + 3.621e9,
+                        "input_projection": 0.903e9 + 0.274e9, "input_gradient": 2.226e9 + 0.145e9,
+                        "weight_gradient": 0.949e9 + 0.061e9, "recurrent_weight_gradient": 0.949e9 + 0.061e9}
     roofline = {"kernel": dom["kernel"], "bound": "mfma", "achieved": dom["tflops"], "peak": PEAK_FP32_MFMA_TFLOPS,
-                "unit": "TFLOP/s", "frac": dom["tflops"] / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
-                "avg_launch_ms": dom["avg_ms"]}
+                "unit": "TFLOP/s", "frac": dom["tflops"] / PEAK_FP32_MFMA_TFLOPS,
+                "traffic": measured_traffic.get(dom["kernel"]) if args.workload == "config3" else None,
+                "avg_launch_ms": dom["avg_ms"],
+                "note": "the recurrent kernels are bound by the serial chain of T dependent steps "
+                        "(see step_us), not by MFMA or HBM throughput; priced here against the fp32 MFMA "
+                        "peak with 2*B*H*4H FLOP per step and direction"}
 
     out = {
         "metric": "BLSTM train frames/sec (fwd+bwd)", "value": frames_per_s, "unit": "frames/s",

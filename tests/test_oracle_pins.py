@@ -360,3 +360,17 @@ def test_directional_derivative_medium_blstm():
 
         num = (shifted(eps) - shifted(-eps)) / (2 * eps)
         assert abs(num - inner) < 1e-6 * max(1.0, abs(inner))
+
+
+def test_config3_golden_file_matches_the_input_generator():
+    """The stored oracle samples belong to the workload the generator produces today."""
+    import os
+    g = np.load(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "config3_oracle_samples.npz"))
+    wl = synth.config3()
+    assert np.array_equal(g["seq_lens"], wl.seq_lens)
+    assert g["y_idx"].max() < wl.T * wl.B * 2 * wl.H and g["dW_0_0_idx"].max() < wl.D * 4 * wl.H
+    # padded frames are exact zeros in the oracle's output
+    t = g["y_idx"] // (wl.B * 2 * wl.H)
+    b = (g["y_idx"] // (2 * wl.H)) % wl.B
+    assert np.all(g["y_val"][t >= wl.seq_lens[b]] == 0.0)
+    assert 0.0 < float(g["y_max"]) < 1.0

@@ -190,3 +190,39 @@ def test_engine_resolution_and_unsupported_shape():
     assert rl.rlstm_resolve_engine(big) == rl.RLSTM_ENGINE_STEPWISE
     big.engine = rl.RLSTM_ENGINE_PERSISTENT
     assert rl.rlstm_resolve_engine(big) == -5
+
+
+def test_config3_full_size_against_oracle_samples():
+    """The benchmark workload at full size, in the launch configuration bench.py times (persistent
+    engine, two streams): sampled entries of every output against values the oracle wrote
+    (tests/golden/make_config3_golden.py), plus properties that hold at any size."""
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "config3_oracle_samples.npz")
+    g = np.load(path)
+    wl = synth.config3()
+    assert np.array_equal(g["seq_lens"], wl.seq_lens)
+    run = gh.StackRun(wl, engine=rl.RLSTM_ENGINE_PERSISTENT, want_dx=True, two_streams=True)
+    run.step()
+    got = run.results()
+
+    def check(name, arr, tol):
+        err = np.abs(arr.reshape(-1)[g[name + "_idx"]].astype(np.float64) - g[name + "_val"]).max() / float(g[name + "_max"])
+        print(f"config3 {name}: sampled rel err {err:.2e}", flush=True)
+        assert err < tol, (name, err)
+
+    check("y", got["y"], TOL_FWD)
+    check("dx", got["dx"], TOL_GRAD)
+    k = 0
+    for l in range(wl.L):
+        for d in range(2):
+            for nm in ("dW", "dR", "db"):
+                check(f"{nm}_{l}_{d}", got["grads"][k], TOL_GRAD)
+                k += 1
+    for n, ln in enumerate(wl.seq_lens):
+        assert np.all(got["y"][ln:, n] == 0.0) and np.all(got["dx"][ln:, n] == 0.0)
+    assert all(np.isfinite(a).all() for a in got["grads"])
+    # second call on the same buffers gives bit-identical results
+    run.step()
+    again = run.results()
+    assert np.array_equal(again["y"], got["y"])
+    assert all(np.array_equal(a, b) for a, b in zip(again["grads"], got["grads"]))
