@@ -182,6 +182,11 @@ RLSTM_API int blstm_stack_fwd(const rblstm_desc* desc, const float* x, const flo
 RLSTM_API int rlstm_gemm_f32(int trans_a, int trans_b, int M, int N, int K,
                    const float* A, int lda, const float* B, int ldb, float* C, int ldc,
                    const float* bias, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream);
+/* Same product with both operands rounded to bf16 (round to nearest even) and fp32
+ * accumulation; A, B, C and bias stay fp32 in memory (the operand_dtype = 1 variant). */
+RLSTM_API int rlstm_gemm_bf16(int trans_a, int trans_b, int M, int N, int K,
+                    const float* A, int lda, const float* B, int ldb, float* C, int ldc,
+                    const float* bias, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream);
 
 /*
  * Optional per-kernel timing for measurement (not part of the method).  While

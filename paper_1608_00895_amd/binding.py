@@ -24,7 +24,7 @@ RLSTM_ENGINE_STEPWISE = 2
 EXPORTS = [
     "rlstm_reserve_bytes", "rlstm_workspace_bytes", "rblstm_reserve_bytes", "rblstm_workspace_bytes",
     "lstm_fwd", "lstm_bwd", "blstm_stack_fwd_bwd", "blstm_stack_fwd",
-    "rlstm_gemm_f32", "rlstm_copy_f32", "rlstm_profile_enable", "rlstm_profile_read", "rlstm_last_timeout", "rlstm_resolve_engine", "rlstm_strerror", "rlstm_version",
+    "rlstm_gemm_f32", "rlstm_gemm_bf16", "rlstm_copy_f32", "rlstm_profile_enable", "rlstm_profile_read", "rlstm_last_timeout", "rlstm_resolve_engine", "rlstm_strerror", "rlstm_version",
 ]
 
 
@@ -81,6 +81,8 @@ def lib() -> ctypes.CDLL:
         L.blstm_stack_fwd.argtypes = [ctypes.POINTER(rblstm_desc), vp, ctypes.POINTER(vp), vp, vp, vp, vp, vp]
         L.rlstm_gemm_f32.restype = ip
         L.rlstm_gemm_f32.argtypes = [ip, ip, ip, ip, ip, vp, ip, vp, ip, vp, ip, vp, vp, ctypes.c_size_t, vp]
+        L.rlstm_gemm_bf16.restype = ip
+        L.rlstm_gemm_bf16.argtypes = L.rlstm_gemm_f32.argtypes
         L.rlstm_copy_f32.restype = ip
         L.rlstm_copy_f32.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.rlstm_profile_enable.restype = ip
@@ -221,4 +223,14 @@ def rlstm_copy_f32(dst, src, n, stream=None, check=True) -> int:
     rc = lib().rlstm_copy_f32(_ptr(dst), _ptr(src), int(n), _stream(stream))
     if check and rc != 0:
         raise RlstmError(rc, "rlstm_copy_f32")
+    return rc
+
+
+def rlstm_gemm_bf16(trans_a, trans_b, M, N, K, A, lda, B, ldb, C, ldc, bias=None, splitk_ws=None,
+                    stream=None, check=True) -> int:
+    nbytes = 0 if splitk_ws is None else splitk_ws.numel() * splitk_ws.element_size()
+    rc = lib().rlstm_gemm_bf16(int(trans_a), int(trans_b), M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc,
+                               _ptr(bias), _ptr(splitk_ws), nbytes, _stream(stream))
+    if check and rc != 0:
+        raise RlstmError(rc, "rlstm_gemm_bf16")
     return rc

@@ -267,9 +267,9 @@ int rlstm_profile_read(rlstm_profile_entry* out, int max_entries) {
   return rc;
 }
 
-int rlstm_gemm_f32(int trans_a, int trans_b, int M, int N, int K,
-                   const float* A, int lda, const float* B, int ldb, float* C, int ldc,
-                   const float* bias, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream) {
+static int gemm_entry(int operand_dtype, int trans_a, int trans_b, int M, int N, int K,
+                      const float* A, int lda, const float* B, int ldb, float* C, int ldc,
+                      const float* bias, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream) {
   if (!A || !B || !C) return RLSTM_ENULL;
   if (M <= 0 || N <= 0 || K < 0) return RLSTM_EDIM;
   if (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N) || ldc < N) return RLSTM_EDIM;
@@ -278,8 +278,21 @@ int rlstm_gemm_f32(int trans_a, int trans_b, int M, int N, int K,
   g.transA = trans_a != 0; g.transB = trans_b != 0;
   g.M = M; g.N = N; g.K = K; g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.bias = bias;
   g.splitk_ws = static_cast<float*>(splitk_ws); g.splitk_floats = splitk_ws ? splitk_ws_bytes / sizeof(float) : 0;
+  g.operand_dtype = operand_dtype;
   RLSTM_TRY(gemm(static_cast<hipStream_t>(hip_stream), g));
   return RLSTM_OK;
+}
+
+int rlstm_gemm_f32(int trans_a, int trans_b, int M, int N, int K,
+                   const float* A, int lda, const float* B, int ldb, float* C, int ldc,
+                   const float* bias, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream) {
+  return gemm_entry(0, trans_a, trans_b, M, N, K, A, lda, B, ldb, C, ldc, bias, splitk_ws, splitk_ws_bytes, hip_stream);
+}
+
+int rlstm_gemm_bf16(int trans_a, int trans_b, int M, int N, int K,
+                    const float* A, int lda, const float* B, int ldb, float* C, int ldc,
+                    const float* bias, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream) {
+  return gemm_entry(1, trans_a, trans_b, M, N, K, A, lda, B, ldb, C, ldc, bias, splitk_ws, splitk_ws_bytes, hip_stream);
 }
 
 int lstm_fwd(const rlstm_desc* d, const float* x, const float* W, const float* R, const float* b,

@@ -213,6 +213,190 @@ __global__ __launch_bounds__(256) void gemm_mfma_f32_kernel(GemmP p) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// bf16-operand variant: operands are rounded to bf16 (round to nearest even) on their way into
+// LDS, products accumulate in fp32 (v_mfma_f32_32x32x16_bf16), C stays fp32.  Same 128 x 128
+// tile and 2 x 2 wavefront layout; K slabs of 32.  LDS holds both operands [128][32 (+8)] bf16
+// with k contiguous, because a lane's MFMA operand is 8 consecutive k of one row (one 16-byte
+// ds_read).  The row stride of 40 bf16 (20 dwords) makes those reads conflict-free.
+// ---------------------------------------------------------------------------
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+constexpr int BKH = 32;        // K slab of the bf16 kernel
+constexpr int LDK = BKH + 8;   // LDS row stride in bf16 elements
+
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  bf16x2 v;
+  v[0] = (__bf16)lo; v[1] = (__bf16)hi;
+  return __builtin_bit_cast(unsigned, v);
+}
+
+// k-contiguous source: element (mn, k) at ptr[mn*ld + k]; slab is 128 rows of 32 floats
+template <bool VEC>
+__device__ __forceinline__ void load_kc(const float* __restrict__ ptr, int ld, int k0, int kend, int mn0, int MN,
+                                        float4 (&r)[4]) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int idx = tid + i * 256;
+    const int mn = mn0 + (idx >> 3), k = k0 + (idx & 7) * 4;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (mn < MN) {
+      const float* q = ptr + (size_t)mn * ld + k;
+      if (VEC) {
+        if (k < kend) v = *reinterpret_cast<const float4*>(q);
+      } else {
+        if (k + 0 < kend) v.x = q[0];
+        if (k + 1 < kend) v.y = q[1];
+        if (k + 2 < kend) v.z = q[2];
+        if (k + 3 < kend) v.w = q[3];
+      }
+    }
+    r[i] = v;
+  }
+}
+__device__ __forceinline__ void store_kc(unsigned short* __restrict__ s, const float4 (&r)[4]) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int idx = tid + i * 256;
+    const int mn = idx >> 3, kq = (idx & 7) * 4;
+    uint2 w;
+    w.x = pack_bf16(r[i].x, r[i].y);
+    w.y = pack_bf16(r[i].z, r[i].w);
+    *reinterpret_cast<uint2*>(s + mn * LDK + kq) = w;
+  }
+}
+// mn-contiguous source: element (k, mn) at ptr[k*ld + mn]; a work item is 2 k rows x 4 columns
+template <bool VEC>
+__device__ __forceinline__ void load_mc(const float* __restrict__ ptr, int ld, int k0, int kend, int mn0, int MN,
+                                        float4 (&r)[4]) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int idx = tid + i * 256;
+    const int mn = mn0 + (idx >> 4) * 4, k = k0 + (idx & 15) * 2;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (k + h < kend) {
+        const float* q = ptr + (size_t)(k + h) * ld + mn;
+        if (VEC) {
+          if (mn < MN) v = *reinterpret_cast<const float4*>(q);
+        } else {
+          if (mn + 0 < MN) v.x = q[0];
+          if (mn + 1 < MN) v.y = q[1];
+          if (mn + 2 < MN) v.z = q[2];
+          if (mn + 3 < MN) v.w = q[3];
+        }
+      }
+      r[i * 2 + h] = v;
+    }
+  }
+}
+__device__ __forceinline__ void store_mc(unsigned short* __restrict__ s, const float4 (&r)[4]) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int idx = tid + i * 256;
+    const int mn = (idx >> 4) * 4, k = (idx & 15) * 2;
+    const float4 a = r[i * 2], b = r[i * 2 + 1];
+    *reinterpret_cast<unsigned*>(s + (mn + 0) * LDK + k) = pack_bf16(a.x, b.x);
+    *reinterpret_cast<unsigned*>(s + (mn + 1) * LDK + k) = pack_bf16(a.y, b.y);
+    *reinterpret_cast<unsigned*>(s + (mn + 2) * LDK + k) = pack_bf16(a.z, b.z);
+    *reinterpret_cast<unsigned*>(s + (mn + 3) * LDK + k) = pack_bf16(a.w, b.w);
+  }
+}
+
+template <bool TA, bool TB, bool VEC>
+__global__ __launch_bounds__(256) void gemm_mfma_bf16_kernel(GemmP p) {
+  extern __shared__ __align__(16) float smem[];
+  unsigned short* As = reinterpret_cast<unsigned short*>(smem);     // [2][128][LDK]
+  unsigned short* Bs = As + 2 * TM * LDK;                           // [2][128][LDK]
+
+  const int tile = blockIdx.x;
+  const int tn = tile % p.tiles_n, tm = tile / p.tiles_n;
+  const int m0 = tm * TM, n0 = tn * TN;
+  const int kbeg = blockIdx.z * p.kchunk;
+  const int kend = min(p.K, kbeg + p.kchunk);
+  const int nslab = (kend - kbeg + BKH - 1) / BKH;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, lh = lane >> 5;
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  float4 ra[4], rb[4];
+  auto loadA = [&](int k0) {
+    if (TA) load_mc<VEC>(p.A, p.lda, k0, kend, m0, p.M, ra); else load_kc<VEC>(p.A, p.lda, k0, kend, m0, p.M, ra);
+  };
+  auto loadB = [&](int k0) {
+    if (TB) load_kc<VEC>(p.B, p.ldb, k0, kend, n0, p.N, rb); else load_mc<VEC>(p.B, p.ldb, k0, kend, n0, p.N, rb);
+  };
+  auto storeAB = [&](int buf) {
+    if (TA) store_mc(As + buf * TM * LDK, ra); else store_kc(As + buf * TM * LDK, ra);
+    if (TB) store_kc(Bs + buf * TN * LDK, rb); else store_mc(Bs + buf * TN * LDK, rb);
+  };
+
+  if (nslab > 0) {
+    loadA(kbeg); loadB(kbeg);
+    storeAB(0);
+  }
+  __syncthreads();
+
+  for (int s = 0; s < nslab; ++s) {
+    const int buf = s & 1;
+    if (s + 1 < nslab) { loadA(kbeg + (s + 1) * BKH); loadB(kbeg + (s + 1) * BKH); }
+    const unsigned short* as = As + buf * TM * LDK + (wm * 64 + l32) * LDK + lh * 8;
+    const unsigned short* bs = Bs + buf * TN * LDK + (wn * 64 + l32) * LDK + lh * 8;
+#pragma unroll
+    for (int ks = 0; ks < BKH; ks += 16) {
+      // lane l supplies row l%32, k = ks + 8*(l/32) .. +7
+      const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(as + ks);
+      const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(as + 32 * LDK + ks);
+      const bf16x8 b0 = *reinterpret_cast<const bf16x8*>(bs + ks);
+      const bf16x8 b1 = *reinterpret_cast<const bf16x8*>(bs + 32 * LDK + ks);
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc[1][1], 0, 0, 0);
+    }
+    if (s + 1 < nslab) storeAB(buf ^ 1);
+    __syncthreads();
+  }
+
+  float* Cout = p.C;
+  int ldc = p.ldc;
+  const bool partial = p.partial != nullptr;
+  if (partial) { Cout = p.partial + (size_t)blockIdx.z * p.M * p.N; ldc = p.N; }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int col = n0 + wn * 64 + j * 32 + l32;
+      if (col >= p.N) continue;
+      const float bv = (!partial && p.bias) ? p.bias[col] : 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wm * 64 + i * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
+        if (row < p.M) {
+          float* dst = Cout + (size_t)row * ldc + col;
+          float v = acc[i][j][r] + bv;
+          if (!partial && p.accumulate) v += *dst;
+          *dst = v;
+        }
+      }
+    }
+  }
+}
+
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int slices,
                                                              int M, int N, float* __restrict__ C, int ldc,
                                                              const float* __restrict__ bias, int accumulate) {
@@ -229,14 +413,15 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 }
 
 // Plain product for the stepwise engine: one thread per element of C.
-__global__ __launch_bounds__(256) void gemm_naive_kernel(GemmP p, int transA, int transB) {
+__global__ __launch_bounds__(256) void gemm_naive_kernel(GemmP p, int transA, int transB, int round_bf16) {
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= (size_t)p.M * p.N) return;
   const int m = (int)(idx / p.N), n = (int)(idx % p.N);
   float s = 0.f;
   for (int k = 0; k < p.K; ++k) {
-    const float a = transA ? p.A[(size_t)k * p.lda + m] : p.A[(size_t)m * p.lda + k];
-    const float b = transB ? p.B[(size_t)n * p.ldb + k] : p.B[(size_t)k * p.ldb + n];
+    float a = transA ? p.A[(size_t)k * p.lda + m] : p.A[(size_t)m * p.lda + k];
+    float b = transB ? p.B[(size_t)n * p.ldb + k] : p.B[(size_t)k * p.ldb + n];
+    if (round_bf16) { a = (float)(__bf16)a; b = (float)(__bf16)b; }
     s = fmaf(a, b, s);
   }
   if (p.bias) s += p.bias[n];
@@ -258,6 +443,17 @@ hipError_t launch_mfma(hipStream_t stream, const GemmP& p, dim3 grid, bool vec) 
   return hipGetLastError();
 }
 
+template <bool TA, bool TB>
+hipError_t launch_bf16(hipStream_t stream, const GemmP& p, dim3 grid, bool vec) {
+  const size_t lds = (size_t)2 * (TM + TN) * LDK * sizeof(unsigned short);
+  if (vec) {
+    hipLaunchKernelGGL((gemm_mfma_bf16_kernel<TA, TB, true>), grid, dim3(256), lds, stream, p);
+  } else {
+    hipLaunchKernelGGL((gemm_mfma_bf16_kernel<TA, TB, false>), grid, dim3(256), lds, stream, p);
+  }
+  return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t gemm(hipStream_t stream, const GemmCall& g) {
@@ -272,11 +468,12 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
   if (g.naive) {
     const size_t total = (size_t)g.M * g.N;
     hipLaunchKernelGGL(gemm_naive_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, p,
-                       g.transA ? 1 : 0, g.transB ? 1 : 0);
+                       g.transA ? 1 : 0, g.transB ? 1 : 0, g.operand_dtype == 1 ? 1 : 0);
     return hipGetLastError();
   }
 
-  constexpr int BK = 16;
+  const bool bf16 = g.operand_dtype == 1;
+  const int BK = bf16 ? BKH : 16;
   // float4 global loads need 16-byte aligned rows and whole float4s inside the matrix
   bool vec = aligned16(g.A) && aligned16(g.B) && (g.lda % 4 == 0) && (g.ldb % 4 == 0) && (g.K % 4 == 0);
   if (g.transA) vec = vec && (g.M % 4 == 0);
@@ -304,10 +501,17 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
   }
   dim3 grid((unsigned)tiles, 1, (unsigned)slices);
   hipError_t e;
-  if (!g.transA && !g.transB)      e = launch_mfma<BK, false, false>(stream, p, grid, vec);
-  else if (!g.transA && g.transB)  e = launch_mfma<BK, false, true>(stream, p, grid, vec);
-  else if (g.transA && !g.transB)  e = launch_mfma<BK, true, false>(stream, p, grid, vec);
-  else                             e = launch_mfma<BK, true, true>(stream, p, grid, vec);
+  if (bf16) {
+    if (!g.transA && !g.transB)      e = launch_bf16<false, false>(stream, p, grid, vec);
+    else if (!g.transA && g.transB)  e = launch_bf16<false, true>(stream, p, grid, vec);
+    else if (g.transA && !g.transB)  e = launch_bf16<true, false>(stream, p, grid, vec);
+    else                             e = launch_bf16<true, true>(stream, p, grid, vec);
+  } else {
+    if (!g.transA && !g.transB)      e = launch_mfma<16, false, false>(stream, p, grid, vec);
+    else if (!g.transA && g.transB)  e = launch_mfma<16, false, true>(stream, p, grid, vec);
+    else if (g.transA && !g.transB)  e = launch_mfma<16, true, false>(stream, p, grid, vec);
+    else                             e = launch_mfma<16, true, true>(stream, p, grid, vec);
+  }
   if (e != hipSuccess) return e;
   if (slices > 1) {
     const size_t total = (size_t)g.M * g.N;

@@ -100,9 +100,9 @@ __device__ __forceinline__ bool wave_wait_flags(const unsigned* flags, int first
   return ok;
 }
 
-// fast gate functions: v_exp_f32 / v_rcp_f32 (about 1e-6 absolute error)
-__device__ __forceinline__ float fsigmoid(float u) { return __builtin_amdgcn_rcpf(1.0f + __expf(-u)); }
-__device__ __forceinline__ float ftanh(float u) { return 2.0f * __builtin_amdgcn_rcpf(1.0f + __expf(-2.0f * u)) - 1.0f; }
+// gate functions: libm-accurate expf, hardware reciprocal (v_rcp_f32, 1 ulp)
+__device__ __forceinline__ float fsigmoid(float u) { return __builtin_amdgcn_rcpf(1.0f + expf(-u)); }
+__device__ __forceinline__ float ftanh(float u) { return 2.0f * __builtin_amdgcn_rcpf(1.0f + expf(-2.0f * u)) - 1.0f; }
 
 // position of element (row k of a wavefront's K range, sequence b) inside that wavefront's
 // operand-ordered block: [chunk][lane][4], L = (k/4)*MT + b/16, chunk = L/4, lane = (k%4)*16 + b%16

@@ -226,3 +226,34 @@ def test_config3_full_size_against_oracle_samples():
     again = run.results()
     assert np.array_equal(again["y"], got["y"])
     assert all(np.array_equal(a, b) for a, b in zip(again["grads"], got["grads"]))
+
+
+def _round_bf16(a):
+    """fp32 -> bf16 (round to nearest even) -> fp32, in numpy (the definition of the format)."""
+    u = np.ascontiguousarray(a, np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32)
+
+
+@pytest.mark.parametrize("case", [
+    (0, 0, 300, 200, 40), (0, 0, 257, 129, 1000), (0, 1, 260, 40, 512), (1, 0, 100, 260, 5000),
+    (1, 1, 64, 64, 64), (0, 0, 33, 17, 19), (1, 0, 37, 50, 4100), (0, 1, 128, 128, 32),
+])
+def test_gemm_bf16_against_numpy(case):
+    """bf16-operand product: equal to the fp64 product of the bf16-rounded operands up to fp32
+    accumulation, and within 2e-2 of the unrounded product."""
+    ta, tb, M, N, K = case
+    rng = _rng(sum(case) + 1)
+    A = rng.standard_normal((K, M) if ta else (M, K)).astype(np.float32)
+    Bm = rng.standard_normal((N, K) if tb else (K, N)).astype(np.float32)
+    bias = rng.standard_normal(N).astype(np.float32)
+    Ar, Br = _round_bf16(A).astype(np.float64), _round_bf16(Bm).astype(np.float64)
+    ref_rounded = (Ar.T if ta else Ar) @ (Br.T if tb else Br) + bias
+    ref = (A.T if ta else A).astype(np.float64) @ (Bm.T if tb else Bm).astype(np.float64) + bias
+    C = torch.full((M, N), float("nan"), device=gh.DEV)
+    ws = torch.empty(16 * M * N * 4, dtype=torch.uint8, device=gh.DEV)
+    rl.rlstm_gemm_bf16(ta, tb, M, N, K, gh.dev(A), A.shape[1], gh.dev(Bm), Bm.shape[1], C, N, gh.dev(bias), ws)
+    torch.cuda.synchronize()
+    got = C.cpu().numpy()
+    assert gh.rel_err(got, ref_rounded) < 1e-5, case
+    assert gh.rel_err(got, ref) < 2e-2, case
