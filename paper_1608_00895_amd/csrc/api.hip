@@ -21,7 +21,7 @@ int check_desc(const rlstm_desc* d) {
   if (d->ldy != 0 && d->ldy < d->H) return RLSTM_EDIM;
   if ((long long)d->T * d->B > (1ll << 30) || (long long)d->H * 4 > (1ll << 24)) return RLSTM_EDIM;
   if (d->direction != 1 && d->direction != -1) return RLSTM_EMODE;
-  if (d->operand_dtype != 0) return RLSTM_EMODE;
+  if (d->operand_dtype != 0 && d->operand_dtype != 1) return RLSTM_EMODE;
   if (d->engine < RLSTM_ENGINE_AUTO || d->engine > RLSTM_ENGINE_STEPWISE) return RLSTM_EMODE;
   return RLSTM_OK;
 }
@@ -29,7 +29,7 @@ int check_stack_desc(const rblstm_desc* d) {
   if (!d) return RLSTM_ENULL;
   if (d->L <= 0 || d->T <= 0 || d->B <= 0 || d->D <= 0 || d->H <= 0) return RLSTM_EDIM;
   if ((long long)d->T * d->B > (1ll << 30) || (long long)d->H * 4 > (1ll << 24)) return RLSTM_EDIM;
-  if (d->operand_dtype != 0) return RLSTM_EMODE;
+  if (d->operand_dtype != 0 && d->operand_dtype != 1) return RLSTM_EMODE;
   if (d->engine < RLSTM_ENGINE_AUTO || d->engine > RLSTM_ENGINE_STEPWISE) return RLSTM_EMODE;
   return RLSTM_OK;
 }
@@ -89,13 +89,13 @@ int hip_to_code(hipError_t e, int resident_err) {
 // processed frame; the h0 term is added separately by the single-layer entry point)
 int weight_grads(hipStream_t st, int layer, int T, int B, int Din, int H, int direction,
                  const float* x, int ldx, const float* y, int ldy, const float* dz,
-                 float* dW, float* dR, float* skws, size_t skfloats, bool naive) {
+                 float* dW, float* dR, float* skws, size_t skfloats, bool naive, int operand_dtype) {
   int resident_err = 0;
   GemmCall g;
   g.transA = true; g.transB = false;
   g.M = Din; g.N = 4 * H; g.K = T * B;
   g.A = x; g.lda = ldx; g.B = dz; g.ldb = 4 * H; g.C = dW; g.ldc = 4 * H;
-  g.splitk_ws = skws; g.splitk_floats = skfloats; g.naive = naive;
+  g.splitk_ws = skws; g.splitk_floats = skfloats; g.naive = naive; g.operand_dtype = operand_dtype;
   {
     ProfScope ps(st, 4, layer, 1);
     RLSTM_TRY(gemm(st, g));
@@ -155,7 +155,7 @@ int stack_forward(const rblstm_desc* d, const float* x, const float* const* para
       GemmCall g;
       g.M = T * B; g.N = 4 * H; g.K = din;
       g.A = in; g.lda = din; g.B = W; g.ldb = 4 * H; g.C = base + lay.zg[k]; g.ldc = 4 * H; g.bias = b;
-      g.naive = !persistent;
+      g.naive = !persistent; g.operand_dtype = d->operand_dtype;
       {
         ProfScope ps(sa, 0, l, 1);
         RLSTM_TRY(gemm(sa, g));
@@ -316,7 +316,7 @@ int lstm_fwd(const rlstm_desc* d, const float* x, const float* W, const float* R
   GemmCall g;
   g.M = d->T * d->B; g.N = 4 * d->H; g.K = d->D;
   g.A = x; g.lda = ldx; g.B = W; g.ldb = 4 * d->H; g.C = zg; g.ldc = 4 * d->H; g.bias = b;
-  g.naive = !persistent;
+  g.naive = !persistent; g.operand_dtype = d->operand_dtype;
   {
     ProfScope ps(st, 0, 0, 1);
     RLSTM_TRY(gemm(st, g));
@@ -359,7 +359,7 @@ int lstm_bwd(const rlstm_desc* d, const float* x, const float* W, const float* R
     ProfScope ps(st, 2, 0, 1);
     RLSTM_TRY(rec_backward(st, s, &dir, seq_lens, recws, flag, persistent, &resident_err));
   }
-  rc = weight_grads(st, 0, T, B, D, H, d->direction, x, ldx, y, ldy, zg, dW, dR, skws, skfloats, !persistent);
+  rc = weight_grads(st, 0, T, B, D, H, d->direction, x, ldx, y, ldy, zg, dW, dR, skws, skfloats, !persistent, d->operand_dtype);
   if (rc != RLSTM_OK) return rc;
   if (h0) RLSTM_TRY(add_h0_outer(st, T, B, H, d->direction, h0, zg, seq_lens, dR));
   if (dx) {
@@ -367,7 +367,7 @@ int lstm_bwd(const rlstm_desc* d, const float* x, const float* W, const float* R
     g.transB = true;
     g.M = T * B; g.N = D; g.K = 4 * H;
     g.A = zg; g.lda = 4 * H; g.B = W; g.ldb = 4 * H; g.C = dx; g.ldc = ldx;
-    g.naive = !persistent;
+    g.naive = !persistent; g.operand_dtype = d->operand_dtype;
     ProfScope ps(st, 3, 0, 1);
     RLSTM_TRY(gemm(st, g));
   }
@@ -457,7 +457,7 @@ int blstm_stack_fwd_bwd(const rblstm_desc* d, const float* x, const float* const
         g.M = T * B; g.N = din; g.K = 4 * H;
         g.A = base + lay.zg[k]; g.lda = 4 * H; g.B = params[6 * l + 3 * k + 0]; g.ldb = 4 * H;
         g.C = dxl; g.ldc = din; g.accumulate = (k == 1);
-        g.naive = !persistent;
+        g.naive = !persistent; g.operand_dtype = d->operand_dtype;
         ProfScope ps(sa, 3, l, 1);
         RLSTM_TRY_C(gemm(sa, g));
       }
@@ -473,7 +473,7 @@ int blstm_stack_fwd_bwd(const rblstm_desc* d, const float* x, const float* const
     for (int k = 0; k < 2; ++k) {
       rc = weight_grads(sb, l, T, B, din, H, k == 0 ? 1 : -1, xin, din, yl + (size_t)k * H, 2 * H,
                         base + lay.zg[k], grads[6 * l + 3 * k + 0], grads[6 * l + 3 * k + 1], skws, skfloats,
-                        !persistent);
+                        !persistent, d->operand_dtype);
       if (rc != RLSTM_OK) { cleanup(); return rc; }
     }
     dy = dxl;

@@ -148,13 +148,58 @@ __device__ __forceinline__ void wave_product(const float* xblock, int xblock_byt
   }
 }
 
+// ---- bf16-operand variant (operand_dtype = 1): the exchanged h_t / d a_t and the resident R / R^T are
+// bf16 (round to nearest even), products accumulate in fp32 (v_mfma_f32_16x16x32_bf16), everything else
+// stays fp32.  A lane's MFMA operand is 8 consecutive k of one row, i.e. one 16-byte chunk.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ unsigned short bf16_bits(float v) { return __builtin_bit_cast(unsigned short, (__bf16)v); }
+
+// position (in bf16 elements) of (row kr of a wavefront's K range, sequence b) inside that wavefront's
+// operand-ordered block: [chunk = (kr/32)*MT + b/16][lane = ((kr%32)/8)*16 + b%16][kr%8]
+template <int MT>
+__device__ __forceinline__ int operand_slot_bf(int kr, int b) {
+  const int chunk = (kr >> 5) * MT + (b >> 4);
+  return (chunk * 64 + ((kr >> 3) & 3) * 16 + (b & 15)) * 8 + (kr & 7);
+}
+
+// B rows in LDS: [k/8][ldn columns][8] bf16
+template <int MT, int NT>
+__device__ __forceinline__ void wave_product_bf(const void* xblock, int xblock_bytes, int nch, const unsigned short* bs, int ldn,
+                                                floatx4 (&acc)[MT][NT]) {
+  const int lane = threadIdx.x & 63, l16 = lane & 15, lq = lane >> 4;
+  __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(xblock), 0, xblock_bytes, 0x00020000);
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+  for (int c0 = 0; c0 < nch; c0 += CG) {
+    intx4 v[CG];
+#pragma unroll
+    for (int q = 0; q < CG; ++q)
+      v[q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, ((c0 + q) * 64 + lane) * 16, 0, kAuxSc1);
+#pragma unroll
+    for (int q = 0; q < CG; ++q) {
+      if (c0 + q < nch) {
+        const int ks = (c0 + q) / MT;              // CG is a multiple of MT, so q % MT is the batch tile
+        const int mt = q % MT;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          const bf16x8 bfrag = *reinterpret_cast<const bf16x8*>(bs + ((size_t)(ks * 4 + lq) * ldn + nt * 16 + l16) * 8);
+          acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v[q]), bfrag, acc[mt][nt], 0, 0, 0);
+        }
+      }
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------
 // forward
 // ---------------------------------------------------------------------------
 struct PFwdDir {
   float* zg; const float* R; const float* h0; const float* c0;
   float* y; float* c; float* hT; float* cT;
-  float* hx;            // 2 x [4 wavefronts][nch][64][4]
+  void* hx;             // 2 x [4 wavefronts][nch][64][16 bytes]
   unsigned* flags;      // [Gf]
   int direction;
 };
@@ -172,7 +217,7 @@ struct PFwdParams {
 // acknowledgements never sit in the step's dependency chain.
 constexpr int kBlockThreads = 320;
 
-template <int MT, int NT>
+template <int MT, int NT, bool BF>
 __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwdParams p) {
   constexpr int U = 4 * NT, NC = 16 * NT;
   constexpr int NE = MT * 16 * U;                // (sequence, unit) pairs of this workgroup (multiple of 64)
@@ -183,8 +228,9 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
   const PFwdDir& D = p.d[dir];
   const int T = p.T, B = p.B, H = p.H, Hp = p.Hp, nch = p.nch;
   const int u0 = wg * U;
-  float* Rs = lds;                               // [Hp][NC]
-  float* Red = Rs + (size_t)Hp * NC;             // [4][MT][NT][256]
+  float* Rs = lds;                               // fp32: [Hp][NC]; bf16: [Hp/8][NC][8] (half the size)
+  unsigned short* Rsb = reinterpret_cast<unsigned short*>(lds);
+  float* Red = Rs + (size_t)Hp * NC / (BF ? 2 : 1);   // [4][MT][NT][256]
   float* zin = Red + 4 * MT * NT * 256;          // [2][4][NE]  input part of the frame, per gate
   float* gout = zin + 2 * 4 * NE;                // [2][6][NE]  gates i,f,o,g, y, c of the frame
 
@@ -197,12 +243,15 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
   for (int idx = tid; idx < Hp * NC; idx += kBlockThreads) {
     const int k = idx / NC, col = idx % NC;
     const int g = col / U, u = u0 + col % U;
-    Rs[idx] = (k < H && u < H) ? D.R[(size_t)k * 4 * H + g * H + u] : 0.f;
+    const float v = (k < H && u < H) ? D.R[(size_t)k * 4 * H + g * H + u] : 0.f;
+    if (BF) Rsb[((size_t)(k >> 3) * NC + col) * 8 + (k & 7)] = bf16_bits(v);
+    else Rs[idx] = v;
   }
 
   const int KW = Hp / 4;                         // rows of h per wavefront
-  const int wblock = nch * 256;                  // floats of one wavefront's operand block
-  const size_t hxsz = (size_t)4 * wblock;
+  const int wbytes = nch * 1024;                 // bytes of one wavefront's operand block (64 lanes x 16 bytes per chunk)
+  const size_t hxsz = (size_t)4 * wbytes;        // bytes of one step buffer
+  char* const hxbase = static_cast<char*>(D.hx);
 
   // compute threads: carried state of the pairs they own
   float hreg[EPT], creg[EPT];
@@ -218,7 +267,8 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
       if (D.h0) hreg[e] = D.h0[(size_t)eb[e] * H + eu[e]];
       if (D.c0) creg[e] = D.c0[(size_t)eb[e] * H + eu[e]];
       elen[e] = min(max(p.seq_lens[eb[e]], 0), T);
-      eslot[e] = (eu[e] / KW) * wblock + operand_slot<MT>(eu[e] % KW, eb[e]);
+      eslot[e] = BF ? (eu[e] / KW) * (wbytes / 2) + operand_slot_bf<MT>(eu[e] % KW, eb[e])
+                    : (eu[e] / KW) * (wbytes / 4) + operand_slot<MT>(eu[e] % KW, eb[e]);
     }
   }
   // I/O lanes: the pairs they move
@@ -272,15 +322,17 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
 
   for (int s = 0; s < T; ++s) {
     const int t = D.direction > 0 ? s : T - 1 - s;
-    const float* hprev = D.hx + (size_t)((s + 1) & 1) * hxsz;
-    float* hcur = D.hx + (size_t)(s & 1) * hxsz;
+    const char* hprev = hxbase + (size_t)((s + 1) & 1) * hxsz;
+    char* hcur = hxbase + (size_t)(s & 1) * hxsz;
     int fail = 0;
 
     if (!is_io) {
       // h of the previous step: wait for the producers of this wavefront's rows, then h_prev * R
       if (s > 0 && !wave_wait_flags(myflags, prod_first, prod_count, p.Gf, (unsigned)s, p.err)) fail = 1;
       floatx4 acc[MT][NT];
-      wave_product<MT, NT>(hprev + (size_t)wave * wblock, wblock * 4, nch, Rs + (size_t)wave * KW * NC, NC, acc);
+      if (BF) wave_product_bf<MT, NT>(hprev + (size_t)wave * wbytes, wbytes, nch, Rsb + (size_t)wave * KW * NC, NC, acc);
+      else wave_product<MT, NT>(reinterpret_cast<const float*>(hprev + (size_t)wave * wbytes), wbytes, nch,
+                                Rs + (size_t)wave * KW * NC, NC, acc);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -304,6 +356,9 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
       float* ocur = gout + (s & 1) * 6 * NE;
 #pragma unroll
       for (int e = 0; e < EPT; ++e) {
+        if (BF) {
+          // (handled after the loop: bf16 values are published in pairs)
+        }
         if (!ev[e]) continue;
         const int j = tid + e * 256;
         const int b = eb[e], uu = eu[e] - u0;
@@ -324,10 +379,20 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
         const float hn = go * ftanh(cn);
         const bool valid = t < elen[e];
         if (valid) { creg[e] = cn; hreg[e] = hn; }
-        st_dev(hcur + eslot[e], hreg[e]);
+        if (!BF) st_dev(reinterpret_cast<float*>(hcur) + eslot[e], hreg[e]);
         ocur[0 * NE + j] = gi; ocur[1 * NE + j] = gf; ocur[2 * NE + j] = go; ocur[3 * NE + j] = gg;
         ocur[4 * NE + j] = valid ? hn : 0.f;
         ocur[5 * NE + j] = creg[e];
+      }
+      if (BF) {
+        // units u, u+1 (u even) are neighbouring lanes and neighbouring bf16 slots: publish them as one word
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+          const unsigned mine = ev[e] ? bf16_bits(hreg[e]) : 0u;
+          const unsigned other = __shfl_xor(mine, 1);
+          if (ev[e] && !(eu[e] & 1))
+            st_dev(reinterpret_cast<unsigned*>(hcur) + (eslot[e] >> 1), mine | (other << 16));
+        }
       }
       wait_stores_acked();
     }
@@ -352,7 +417,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
 struct PBwdDir {
   float* zg; const float* R; const float* c; const float* c0; const float* dy;
   const float* dhT; const float* dcT; float* dh0; float* dc0; float* db;
-  float* dzx;                   // 2 x [4 quarters][4 wavefronts][nch][64][4]
+  void* dzx;                    // 2 x [4 quarters][4 wavefronts][nch][64][16 bytes]
   unsigned long long* part;     // 2 x [PG][4][Bp][UG] (value, tag)
   unsigned* flags;              // [Gb]
   int direction;
@@ -367,7 +432,7 @@ struct PBwdParams {
 // Same workgroup shape as the forward kernel: 4 compute wavefronts + 1 I/O wavefront that stages
 // the frame's gates, cell states and dy from HBM into LDS one step ahead and writes d a back to
 // HBM one step behind.
-template <int MT, int NT>
+template <int MT, int NT, bool BF>
 __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwdParams p) {
   constexpr int U = 4 * NT, UG = 16 * NT, Bp = 16 * MT;
   constexpr int NE = MT * 16 * U;                // (sequence, unit) pairs owned by this workgroup
@@ -380,8 +445,9 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
   const PBwdDir& D = p.d[dir];
   const int T = p.T, B = p.B, H = p.H, Hq = p.Hq, nch = p.nch;
   const int u0 = wg * U;                         // owned units
-  float* RTs = lds;                              // [4*Hq][UG]
-  float* Red = RTs + (size_t)4 * Hq * UG;        // [4][MT][NT][256]
+  float* RTs = lds;                              // fp32: [4*Hq][UG]; bf16: [4*Hq/8][UG][8] (half the size)
+  unsigned short* RTb = reinterpret_cast<unsigned short*>(lds);
+  float* Red = RTs + (size_t)4 * Hq * UG / (BF ? 2 : 1);   // [4][MT][NT][256]
   float* bin = Red + 4 * MT * NT * 256;          // [2][7][NE]  gates i,f,o,g, c, c_prev, dy of the frame
   float* dzo = bin + 2 * 7 * NE;                 // [2][4][NE]  d a of the frame
 
@@ -402,11 +468,14 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
     const int w = r / Hq, rr = r % Hq;
     const int uk = qq * Hq + w * UW + (rr >> 2), g = rr & 3;
     const int un = pg * UG + n;
-    RTs[idx] = (uk < H && un < H) ? D.R[(size_t)un * 4 * H + g * H + uk] : 0.f;
+    const float v = (uk < H && un < H) ? D.R[(size_t)un * 4 * H + g * H + uk] : 0.f;
+    if (BF) RTb[((size_t)(r >> 3) * UG + n) * 8 + (r & 7)] = bf16_bits(v);
+    else RTs[idx] = v;
   }
 
-  const int wblock = nch * 256;                  // floats per (quarter, wavefront) operand block
-  const size_t xsz = (size_t)16 * wblock;
+  const int wbytes = nch * 1024;                 // bytes per (quarter, wavefront) operand block
+  const size_t xsz = (size_t)16 * wbytes;        // bytes of one step buffer
+  char* const dzbase = static_cast<char*>(D.dzx);
   const size_t psz = (size_t)p.PG * 4 * Bp * UG;
 
   // compute threads: carried gradients of the pairs they own
@@ -427,7 +496,8 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
       elen[e] = min(max(p.seq_lens[eb[e]], 0), T);
       // d a of unit u, gate g sits in quarter u/Hq, wavefront (u%Hq)/UW, row ((u%Hq)%UW)*4 + g
       const int ul = eu[e] % Hq;
-      eslot[e] = ((eu[e] / Hq) * 4 + ul / UW) * wblock + operand_slot<MT>((ul % UW) * 4, eb[e]);
+      eslot[e] = BF ? ((eu[e] / Hq) * 4 + ul / UW) * (wbytes / 2) + operand_slot_bf<MT>((ul % UW) * 4, eb[e])
+                    : ((eu[e] / Hq) * 4 + ul / UW) * (wbytes / 4) + operand_slot<MT>((ul % UW) * 4, eb[e]);
     }
   }
 
@@ -534,7 +604,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
 
   for (int s = 0; s < T; ++s) {
     const int t = frame_of(s);
-    float* dzcur = D.dzx + (size_t)(s & 1) * xsz;
+    char* dzcur = dzbase + (size_t)(s & 1) * xsz;
     int fail = 0;
 
     if (!is_io) {
@@ -568,9 +638,17 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
           dz[3] = dc * gi * (1.0f - gg * gg);
           Dc[e] = dc * gf;
         }
+        if (BF) {
+          // the 4 gates of a unit are 4 consecutive k: one 8-byte word of bf16
+          const unsigned long long w = (unsigned long long)bf16_bits(dz[0]) | ((unsigned long long)bf16_bits(dz[1]) << 16) |
+                                       ((unsigned long long)bf16_bits(dz[2]) << 32) | ((unsigned long long)bf16_bits(dz[3]) << 48);
+          __hip_atomic_store(reinterpret_cast<unsigned long long*>(dzcur) + (eslot[e] >> 2), w, __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+        }
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          st_dev(dzcur + eslot[e] + g * 64, dz[g]);      // rows (unit, gate 0..3) are 16 lanes apart in operand order
+          // fp32: rows (unit, gate 0..3) are 16 lanes apart in operand order
+          if (!BF) st_dev(reinterpret_cast<float*>(dzcur) + eslot[e] + g * 64, dz[g]);
           out[g * NE + j] = dz[g];
           dbacc[e][g] += dz[g];
         }
@@ -594,7 +672,9 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
     if (!is_io && qq < nq) {
       if (!wave_wait_flags(myflags, prod_first, prod_count, Gb, (unsigned)(s + 1), p.err)) fail = 1;
       floatx4 acc[MT][NT];
-      wave_product<MT, NT>(dzcur + (size_t)(qq * 4 + wave) * wblock, wblock * 4, nch, RTs + (size_t)wave * Hq * UG, UG, acc);
+      if (BF) wave_product_bf<MT, NT>(dzcur + (size_t)(qq * 4 + wave) * wbytes, wbytes, nch, RTb + (size_t)wave * Hq * UG, UG, acc);
+      else wave_product<MT, NT>(reinterpret_cast<const float*>(dzcur + (size_t)(qq * 4 + wave) * wbytes), wbytes, nch,
+                                RTs + (size_t)wave * Hq * UG, UG, acc);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -668,8 +748,8 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
 // ---------------------------------------------------------------------------
 struct PrepParams {
   unsigned* zero_words[2]; size_t nzero[2];       // per direction: words to clear (flags + exchange [+ partial tiles])
-  float* hx1[2]; const float* h0[2];              // forward only: buffer 1 of the h exchange, h0 or null
-  int ndir, B, H, KW, wblock, MT;
+  void* hx1[2]; const float* h0[2];               // forward only: buffer 1 of the h exchange, h0 or null
+  int ndir, B, H, KW, wbytes, MT, bf;
 };
 __global__ __launch_bounds__(256) void prep_kernel(PrepParams p) {
   const size_t gtid = (size_t)blockIdx.x * 256 + threadIdx.x, gsz = (size_t)gridDim.x * 256;
@@ -687,10 +767,17 @@ __global__ __launch_bounds__(256) void seed_h0_kernel(PrepParams p) {
     if (!p.h0[d]) continue;
     const int k = u % p.KW;
     int slot;
-    if (p.MT == 1) slot = operand_slot<1>(k, b);
-    else if (p.MT == 2) slot = operand_slot<2>(k, b);
-    else slot = operand_slot<4>(k, b);
-    p.hx1[d][(size_t)(u / p.KW) * p.wblock + slot] = p.h0[d][gtid];
+    if (p.bf) {
+      if (p.MT == 1) slot = operand_slot_bf<1>(k, b);
+      else if (p.MT == 2) slot = operand_slot_bf<2>(k, b);
+      else slot = operand_slot_bf<4>(k, b);
+      static_cast<unsigned short*>(p.hx1[d])[(size_t)(u / p.KW) * (p.wbytes / 2) + slot] = bf16_bits(p.h0[d][gtid]);
+    } else {
+      if (p.MT == 1) slot = operand_slot<1>(k, b);
+      else if (p.MT == 2) slot = operand_slot<2>(k, b);
+      else slot = operand_slot<4>(k, b);
+      static_cast<float*>(p.hx1[d])[(size_t)(u / p.KW) * (p.wbytes / 4) + slot] = p.h0[d][gtid];
+    }
   }
 }
 
@@ -700,7 +787,7 @@ constexpr size_t kFlagBytes = (size_t)kFlagCopies * kFlagCopyStride * sizeof(uns
 
 struct Plan {
   bool ok;
-  int MT, NT, U, UG, Bp;
+  int MT, NT, U, UG, Bp, bf;
   int Gf, Hp, nchF;
   int PG, Gb, Hq, nchB;
   size_t ldsF, ldsB;
@@ -709,8 +796,11 @@ struct Plan {
 Plan make_plan(const RecShape& s, int num_cus, size_t max_lds) {
   Plan pl{};
   pl.ok = false;
-  if (s.operand_dtype != 0) return pl;
+  if (s.operand_dtype != 0 && s.operand_dtype != 1) return pl;
   if (s.B < 1 || s.B > 64 || s.H < 1) return pl;
+  const int bf = s.operand_dtype == 1 ? 1 : 0;
+  const size_t es = bf ? 2 : 4;                  // bytes per element of the resident matrix and the exchanged rows
+  pl.bf = bf;
   pl.MT = s.B <= 16 ? 1 : (s.B <= 32 ? 2 : 4);
   pl.Bp = pl.MT * 16;
   const int per_dir = num_cus / s.ndir;
@@ -720,13 +810,13 @@ Plan make_plan(const RecShape& s, int num_cus, size_t max_lds) {
     const int PG = (s.H + UG - 1) / UG;
     const int Gb = 4 * PG;
     if (Gf > per_dir || Gb > per_dir) continue;
-    const int Hp = (int)align_up((size_t)s.H, 64);
+    const int Hp = (int)align_up((size_t)s.H, bf ? 128 : 64);   // rows of h per wavefront: whole MFMA k-steps
     const int Hq = (int)align_up((size_t)PG * U, 32);
     // a wavefront polls at most 64 producers
     if (Hp / 4 / U > 64 || Hq / 4 / U > 64) continue;
     const size_t red = (size_t)4 * pl.MT * NT * 256;
-    const size_t lf = ((size_t)Hp * 16 * NT + red + (size_t)(2 * 4 + 2 * 6) * pl.MT * 16 * U) * sizeof(float);
-    const size_t lb = ((size_t)4 * Hq * UG + red + (size_t)(2 * 7 + 2 * 4) * pl.MT * 16 * U) * sizeof(float);
+    const size_t lf = (size_t)Hp * 16 * NT * es + (red + (size_t)(2 * 4 + 2 * 6) * pl.MT * 16 * U) * sizeof(float);
+    const size_t lb = (size_t)4 * Hq * UG * es + (red + (size_t)(2 * 7 + 2 * 4) * pl.MT * 16 * U) * sizeof(float);
     if (lf > max_lds || lb > max_lds) continue;
     // One workgroup per CU: request more than half of the CU's LDS so that the dispatcher cannot
     // stack two of these workgroups on one CU (they would share its matrix cores and every other
@@ -734,8 +824,9 @@ Plan make_plan(const RecShape& s, int num_cus, size_t max_lds) {
     const size_t exclusive = max_lds / 2 + 1024;
     const size_t lf_req = lf > exclusive ? lf : exclusive, lb_req = lb > exclusive ? lb : exclusive;
     pl.ok = true; pl.NT = NT; pl.U = U; pl.UG = UG;
-    pl.Gf = Gf; pl.Hp = Hp; pl.nchF = (Hp / 16) * pl.MT / 4;
-    pl.PG = PG; pl.Gb = Gb; pl.Hq = Hq; pl.nchB = (Hq / 4) * pl.MT / 4;
+    // 16-byte chunks per lane and wavefront: fp32 4 values (4 k-steps x batch tiles / 4), bf16 8 values (1 k-step of 32)
+    pl.Gf = Gf; pl.Hp = Hp; pl.nchF = bf ? (Hp / 4 / 32) * pl.MT : (Hp / 16) * pl.MT / 4;
+    pl.PG = PG; pl.Gb = Gb; pl.Hq = Hq; pl.nchB = bf ? (Hq / 32) * pl.MT : (Hq / 4) * pl.MT / 4;
     pl.ldsF = lf_req; pl.ldsB = lb_req;
     return pl;
   }
@@ -773,7 +864,7 @@ bool persistent_supported(const RecShape& s, int num_cus, size_t max_lds) {
 // [flag copies][exchange arrays][partial tiles].
 size_t persistent_scratch_bytes_per_dir(const RecShape& s) {
   const size_t Bp = s.B <= 16 ? 16 : (s.B <= 32 ? 32 : 64);
-  const size_t Hp = align_up((size_t)s.H, 64);
+  const size_t Hp = align_up((size_t)s.H, 128);
   const size_t Hq = align_up((size_t)s.H / 4 + 8, 32);
   const size_t exch = 2 * (Hp > 16 * Hq ? Hp : 16 * Hq) * Bp * sizeof(float);
   const size_t part = 2 * 4 * Bp * ((size_t)s.H + 32) * sizeof(unsigned long long);
@@ -787,22 +878,22 @@ hipError_t persistent_forward(hipStream_t stream, const RecShape& s, const RecFw
   if (e != hipSuccess) return e;
   const Plan pl = make_plan(s, di.num_cus, di.max_lds);
   if (!pl.ok) { *resident_err = 1; return hipErrorInvalidValue; }
-  const int wblock = pl.nchF * 256;
+  const size_t wbytes = (size_t)pl.nchF * 1024;
   PrepParams pp{};
   PFwdParams kp{};
   for (int d = 0; d < s.ndir; ++d) {
     unsigned* flags = reinterpret_cast<unsigned*>(scratch[d]);
-    float* hx = reinterpret_cast<float*>(scratch[d] + kFlagBytes);
+    char* hx = scratch[d] + kFlagBytes;
     pp.zero_words[d] = flags;
-    pp.nzero[d] = kFlagBytes / 4 + (size_t)2 * 4 * wblock;
-    pp.hx1[d] = hx + (size_t)4 * wblock;
+    pp.nzero[d] = kFlagBytes / 4 + 2 * 4 * wbytes / 4;
+    pp.hx1[d] = hx + 4 * wbytes;
     pp.h0[d] = dirs[d].h0;
     PFwdDir& k = kp.d[d];
     k.zg = dirs[d].zg; k.R = dirs[d].R; k.h0 = dirs[d].h0; k.c0 = dirs[d].c0;
     k.y = dirs[d].y; k.c = dirs[d].c; k.hT = dirs[d].hT; k.cT = dirs[d].cT;
     k.hx = hx; k.flags = flags; k.direction = dirs[d].direction;
   }
-  pp.ndir = s.ndir; pp.B = s.B; pp.H = s.H; pp.KW = pl.Hp / 4; pp.wblock = wblock; pp.MT = pl.MT;
+  pp.ndir = s.ndir; pp.B = s.B; pp.H = s.H; pp.KW = pl.Hp / 4; pp.wbytes = (int)wbytes; pp.MT = pl.MT; pp.bf = pl.bf;
   kp.seq_lens = seq_lens; kp.err = err;
   kp.T = s.T; kp.B = s.B; kp.H = s.H; kp.ldy = s.ldy; kp.Gf = pl.Gf; kp.Hp = pl.Hp; kp.nch = pl.nchF;
   hipLaunchKernelGGL(prep_kernel, dim3(64), dim3(256), 0, stream, pp);
@@ -813,9 +904,14 @@ hipError_t persistent_forward(hipStream_t stream, const RecShape& s, const RecFw
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int grid = pl.Gf * s.ndir;
-#define RLSTM_FWD_CASE(MT_, NT_)                                                                      \
-  if (pl.MT == MT_ && pl.NT == NT_)                                                                   \
-    return resident_launch(lstm_fwd_persistent_kernel<MT_, NT_>, grid, kBlockThreads, pl.ldsF, di.num_cus, stream, &kp, resident_err);
+#define RLSTM_FWD_CASE(MT_, NT_)                                                                        \
+  if (pl.MT == MT_ && pl.NT == NT_) {                                                                   \
+    if (pl.bf)                                                                                          \
+      return resident_launch(lstm_fwd_persistent_kernel<MT_, NT_, true>, grid, kBlockThreads, pl.ldsF,  \
+                             di.num_cus, stream, &kp, resident_err);                                    \
+    return resident_launch(lstm_fwd_persistent_kernel<MT_, NT_, false>, grid, kBlockThreads, pl.ldsF,   \
+                           di.num_cus, stream, &kp, resident_err);                                      \
+  }
   RLSTM_FWD_CASE(1, 1) RLSTM_FWD_CASE(2, 1) RLSTM_FWD_CASE(4, 1)
   RLSTM_FWD_CASE(1, 2) RLSTM_FWD_CASE(2, 2) RLSTM_FWD_CASE(4, 2)
 #undef RLSTM_FWD_CASE
@@ -829,17 +925,17 @@ hipError_t persistent_backward(hipStream_t stream, const RecShape& s, const RecB
   if (e != hipSuccess) return e;
   const Plan pl = make_plan(s, di.num_cus, di.max_lds);
   if (!pl.ok) { *resident_err = 1; return hipErrorInvalidValue; }
-  const int wblock = pl.nchB * 256;
-  const size_t exch_floats = (size_t)2 * 16 * wblock;
+  const size_t wbytes = (size_t)pl.nchB * 1024;
+  const size_t exch_bytes = 2 * 16 * wbytes;
   const size_t part_words = (size_t)2 * pl.PG * 4 * pl.Bp * pl.UG;
   PrepParams pp{};
   PBwdParams kp{};
   for (int d = 0; d < s.ndir; ++d) {
     unsigned* flags = reinterpret_cast<unsigned*>(scratch[d]);
-    float* dzx = reinterpret_cast<float*>(scratch[d] + kFlagBytes);
-    unsigned long long* part = reinterpret_cast<unsigned long long*>(dzx + align_up(exch_floats, 64));
+    char* dzx = scratch[d] + kFlagBytes;
+    unsigned long long* part = reinterpret_cast<unsigned long long*>(dzx + align_up(exch_bytes, 256));
     pp.zero_words[d] = flags;
-    pp.nzero[d] = kFlagBytes / 4 + align_up(exch_floats, 64) + 2 * part_words;
+    pp.nzero[d] = kFlagBytes / 4 + align_up(exch_bytes, 256) / 4 + 2 * part_words;
     PBwdDir& k = kp.d[d];
     k.zg = dirs[d].zg; k.R = dirs[d].R; k.c = dirs[d].c; k.c0 = dirs[d].c0; k.dy = dirs[d].dy;
     k.dhT = dirs[d].dhT; k.dcT = dirs[d].dcT; k.dh0 = dirs[d].dh0; k.dc0 = dirs[d].dc0; k.db = dirs[d].db;
@@ -852,9 +948,14 @@ hipError_t persistent_backward(hipStream_t stream, const RecShape& s, const RecB
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int grid = pl.Gb * s.ndir;
-#define RLSTM_BWD_CASE(MT_, NT_)                                                                      \
-  if (pl.MT == MT_ && pl.NT == NT_)                                                                   \
-    return resident_launch(lstm_bwd_persistent_kernel<MT_, NT_>, grid, kBlockThreads, pl.ldsB, di.num_cus, stream, &kp, resident_err);
+#define RLSTM_BWD_CASE(MT_, NT_)                                                                        \
+  if (pl.MT == MT_ && pl.NT == NT_) {                                                                   \
+    if (pl.bf)                                                                                          \
+      return resident_launch(lstm_bwd_persistent_kernel<MT_, NT_, true>, grid, kBlockThreads, pl.ldsB,  \
+                             di.num_cus, stream, &kp, resident_err);                                    \
+    return resident_launch(lstm_bwd_persistent_kernel<MT_, NT_, false>, grid, kBlockThreads, pl.ldsB,   \
+                           di.num_cus, stream, &kp, resident_err);                                      \
+  }
   RLSTM_BWD_CASE(1, 1) RLSTM_BWD_CASE(2, 1) RLSTM_BWD_CASE(4, 1)
   RLSTM_BWD_CASE(1, 2) RLSTM_BWD_CASE(2, 2) RLSTM_BWD_CASE(4, 2)
 #undef RLSTM_BWD_CASE

@@ -19,7 +19,7 @@ struct SFwdDir {
   float* hbuf;          // 2 x [B,H] carried h, double-buffered
   int direction;
 };
-struct SFwdParams { SFwdDir d[2]; const int32_t* seq_lens; int T, B, H, ldy, s; };
+struct SFwdParams { SFwdDir d[2]; const int32_t* seq_lens; int T, B, H, ldy, s, bf; };
 
 __global__ __launch_bounds__(256) void step_fwd_kernel(SFwdParams p) {
   const SFwdDir& D = p.d[blockIdx.y];
@@ -36,9 +36,14 @@ __global__ __launch_bounds__(256) void step_fwd_kernel(SFwdParams p) {
   float* zrow = D.zg + row * 4 * H + u;
   float a0 = zrow[0], a1 = zrow[H], a2 = zrow[2 * H], a3 = zrow[3 * H];
   for (int k = 0; k < H; ++k) {
-    const float hv = hprev[(size_t)b * H + k];
+    float hv = hprev[(size_t)b * H + k];
     const float* rr = D.R + (size_t)k * 4 * H + u;
-    a0 = fmaf(hv, rr[0], a0); a1 = fmaf(hv, rr[H], a1); a2 = fmaf(hv, rr[2 * H], a2); a3 = fmaf(hv, rr[3 * H], a3);
+    float r0 = rr[0], r1 = rr[H], r2 = rr[2 * H], r3 = rr[3 * H];
+    if (p.bf) {   // bf16-operand variant: both factors rounded to bf16, fp32 accumulation
+      hv = (float)(__bf16)hv;
+      r0 = (float)(__bf16)r0; r1 = (float)(__bf16)r1; r2 = (float)(__bf16)r2; r3 = (float)(__bf16)r3;
+    }
+    a0 = fmaf(hv, r0, a0); a1 = fmaf(hv, r1, a1); a2 = fmaf(hv, r2, a2); a3 = fmaf(hv, r3, a3);
   }
   float cprev;
   if (tprev >= 0 && tprev < T) cprev = D.c[((size_t)tprev * B + b) * H + u];
@@ -75,7 +80,7 @@ struct SBwdDir {
   float* dcbuf;         // [B,H] carried Dc
   int direction;
 };
-struct SBwdParams { SBwdDir d[2]; const int32_t* seq_lens; int T, B, H, ldy, s; };
+struct SBwdParams { SBwdDir d[2]; const int32_t* seq_lens; int T, B, H, ldy, s, bf; };
 
 // gate derivatives of step s: reads Dh of buffer (s+1)&1, writes dz in place and updates Dc
 __global__ __launch_bounds__(256) void step_bwd_gates_kernel(SBwdParams p) {
@@ -124,7 +129,11 @@ __global__ __launch_bounds__(256) void step_bwd_dh_kernel(SBwdParams p) {
   const float* dz = D.zg + ((size_t)t * B + b) * 4 * H;
   const float* rr = D.R + (size_t)u * 4 * H;
   float sum = 0.f;
-  for (int k = 0; k < 4 * H; ++k) sum = fmaf(dz[k], rr[k], sum);
+  for (int k = 0; k < 4 * H; ++k) {
+    float a = dz[k], r = rr[k];
+    if (p.bf) { a = (float)(__bf16)a; r = (float)(__bf16)r; }
+    sum = fmaf(a, r, sum);
+  }
   const int len = min(max(p.seq_lens[b], 0), T);
   if (!(t < len)) sum += D.dhbuf[(size_t)((s + 1) & 1) * B * H + j];
   D.dhbuf[(size_t)(s & 1) * B * H + j] = sum;
@@ -222,7 +231,7 @@ hipError_t stepwise_forward(hipStream_t stream, const RecShape& s, const RecFwdD
     k.hT = dirs[d].hT; k.cT = dirs[d].cT; k.hbuf = buf[d]; k.direction = dirs[d].direction;
   }
   ip.ndir = s.ndir; ip.n = bh; ip.off = bh;      // step 0 reads buffer 1
-  kp.seq_lens = seq_lens; kp.T = s.T; kp.B = s.B; kp.H = s.H; kp.ldy = s.ldy;
+  kp.seq_lens = seq_lens; kp.T = s.T; kp.B = s.B; kp.H = s.H; kp.ldy = s.ldy; kp.bf = s.operand_dtype == 1 ? 1 : 0;
   const unsigned blocks = (unsigned)((bh + 255) / 256);
   hipLaunchKernelGGL(init_state_kernel, dim3(blocks), dim3(256), 0, stream, ip);
   for (int st = 0; st < s.T; ++st) {
@@ -247,7 +256,7 @@ hipError_t stepwise_backward(hipStream_t stream, const RecShape& s, const RecBwd
     k.dhbuf = buf[d]; k.dcbuf = buf[d] + 2 * bh; k.direction = dirs[d].direction;
   }
   ih.ndir = ic.ndir = s.ndir; ih.n = ic.n = bh; ih.off = bh; ic.off = 2 * bh;
-  kp.seq_lens = seq_lens; kp.T = s.T; kp.B = s.B; kp.H = s.H; kp.ldy = s.ldy;
+  kp.seq_lens = seq_lens; kp.T = s.T; kp.B = s.B; kp.H = s.H; kp.ldy = s.ldy; kp.bf = s.operand_dtype == 1 ? 1 : 0;
   const unsigned blocks = (unsigned)((bh + 255) / 256);
   hipLaunchKernelGGL(init_state_kernel, dim3(blocks), dim3(256), 0, stream, ih);
   hipLaunchKernelGGL(init_state_kernel, dim3(blocks), dim3(256), 0, stream, ic);

@@ -27,12 +27,13 @@ def rel_err(got, ref) -> float:
 
 
 def run_lstm_layer(x, W, R, b, seq_lens, direction, h0=None, c0=None, dy=None, dhT=None, dcT=None,
-                   engine=rl.RLSTM_ENGINE_AUTO, ldx=0, ldy=0, want_dx=True, fill=float("nan")):
+                   engine=rl.RLSTM_ENGINE_AUTO, ldx=0, ldy=0, want_dx=True, fill=float("nan"), operand_dtype=0):
     """lstm_fwd then lstm_bwd on the GPU.  x/y/dy may use padded row strides ldx/ldy
     (padding is filled with `fill` to show that it is neither read into results nor written)."""
     T, B, D = x.shape
     H = R.shape[0]
-    desc = rl.rlstm_desc(T=T, B=B, D=D, H=H, direction=direction, operand_dtype=0, ldx=ldx, ldy=ldy, engine=engine)
+    desc = rl.rlstm_desc(T=T, B=B, D=D, H=H, direction=direction, operand_dtype=operand_dtype, ldx=ldx, ldy=ldy,
+                         engine=engine)
     lx = ldx or D
     ly = ldy or H
     xd = torch.full((T, B, lx), fill, device=DEV)

@@ -257,3 +257,55 @@ def test_gemm_bf16_against_numpy(case):
     got = C.cpu().numpy()
     assert gh.rel_err(got, ref_rounded) < 1e-5, case
     assert gh.rel_err(got, ref) < 2e-2, case
+
+
+TOL_BF16 = 2e-2
+
+
+@pytest.mark.parametrize("engine", ENGINES)
+@pytest.mark.parametrize("direction", [1, -1])
+@pytest.mark.parametrize("shape", [
+    (13, 5, 12, 20, (13, 7, 1, 0, 9)),
+    (11, 18, 16, 36, None),
+    (25, 40, 24, 136, None),
+])
+def test_single_layer_bf16_operands(engine, direction, shape):
+    """operand_dtype = 1: matrix-product operands rounded to bf16, fp32 accumulation and cell state;
+    checked against the unrounded fp64 oracle within 2e-2."""
+    T, B, D, H, lens = shape
+    rng = _rng(2000 + T + B + H + (direction > 0))
+    x = rng.standard_normal((T, B, D)).astype(np.float32)
+    W = rng.uniform(-0.3, 0.3, (D, 4 * H)).astype(np.float32)
+    R = rng.uniform(-0.3, 0.3, (H, 4 * H)).astype(np.float32)
+    b = rng.uniform(-0.3, 0.3, (4 * H,)).astype(np.float32)
+    h0 = rng.uniform(-0.5, 0.5, (B, H)).astype(np.float32)
+    c0 = rng.uniform(-0.5, 0.5, (B, H)).astype(np.float32)
+    lens = np.array(lens if lens is not None else rng.integers(0, T + 1, B), dtype=np.int32)
+    dy = rng.standard_normal((T, B, H)).astype(np.float32)
+    dhT = rng.standard_normal((B, H)).astype(np.float32)
+    dcT = rng.standard_normal((B, H)).astype(np.float32)
+    fwd = lstm_forward(x, W, R, b, lens, direction, h0, c0)
+    grad = lstm_backward(fwd, dy, dhT, dcT)
+    got = gh.run_lstm_layer(x, W, R, b, lens, direction, h0, c0, dy, dhT, dcT, engine=engine, operand_dtype=1)
+    errs = {k: gh.rel_err(got[k], (fwd if k in fwd else grad)[k])
+            for k in ("y", "c", "hT", "cT", "dx", "dW", "dR", "db", "dh0", "dc0")}
+    print(f"bf16 shape={shape} dir={direction} engine={engine}", {k: f"{v:.1e}" for k, v in errs.items()}, flush=True)
+    assert all(v < TOL_BF16 for v in errs.values()), errs
+    # rounding must actually happen: the result differs from the fp32 path
+    assert errs["y"] > 1e-5
+    for n, ln in enumerate(lens):
+        assert np.all(got["y"][ln:, n] == 0.0) and np.all(got["dx"][ln:, n] == 0.0)
+
+
+@pytest.mark.parametrize("engine", ENGINES)
+def test_small_stack_bf16_operands(engine):
+    wl = synth.small_blstm(seed=13, L=3, B=20, D=12, H=40, len_lo=0, len_hi=37, T=40, wscale=0.2)
+    wl.operand_dtype = 1
+    ref = gh.oracle_stack(wl)
+    run = gh.StackRun(wl, engine=engine)
+    run.step()
+    got = run.results()
+    errs = [gh.rel_err(got["y"], ref["y"]), gh.rel_err(got["dx"], ref["dx"])] + \
+           [gh.rel_err(g, r) for g, r in zip(got["grads"], ref["grads"])]
+    print("bf16 stack", engine, [f"{e:.1e}" for e in errs], flush=True)
+    assert max(errs) < TOL_BF16
