@@ -23,6 +23,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X dense fp32 matrix peak
+PEAK_BF16_MFMA_TFLOPS = 2500.0    # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
 
 
@@ -30,28 +31,11 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def gemm_flops(kind, layer, wl):
-    """Algorithmic FLOP of one launch group of the given kind (2*M*N*K)."""
-    tb = wl.T * wl.B
-    din = wl.D if layer == 0 else 2 * wl.H
-    if kind == 0:
-        return 2.0 * tb * din * 4 * wl.H
-    if kind == 3:
-        return 2.0 * tb * din * 4 * wl.H
-    if kind == 4:
-        return 2.0 * tb * din * 4 * wl.H
-    if kind == 5:
-        return 2.0 * (wl.T - 1) * wl.B * wl.H * 4 * wl.H
-    if kind in (1, 2):
-        return 2.0 * 2 * tb * wl.H * 4 * wl.H      # both directions, h R (or dz R^T) over all steps
-    raise ValueError(kind)
-
-
-def rec_bytes(kind, wl):
-    """Algorithmic HBM bytes of one recurrent launch (both directions), fp32:
-    forward reads Z and writes gates, y, c; backward reads gates, c (twice), dy and writes dz."""
+def rec_bytes(kind, wl, steps):
+    """Algorithmic HBM bytes of `steps` recurrent steps (both directions), fp32: forward reads Z and writes
+    gates, y, c; backward reads gates, c (twice), dy and writes dz; the recurrent matrix is read once per launch."""
     per_slot_dir = 4 * ((4 + 4 + 1 + 1) * wl.H) if kind == 1 else 4 * ((4 + 2 + 1 + 4) * wl.H)
-    return 2.0 * wl.T * wl.B * per_slot_dir + 2 * 4.0 * wl.H * 4 * wl.H
+    return 2.0 * steps * wl.B * per_slot_dir
 
 
 def cpu_baseline(wl_full, seconds_budget=20.0):
@@ -84,9 +68,13 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config3", choices=["config2", "config3"])
+    ap.add_argument("--workload", default="config3", choices=["config2", "config3", "config4"])
     ap.add_argument("--engine", type=int, default=0)
     ap.add_argument("--one-stream", action="store_true")
+    ap.add_argument("--first-piece", type=int, default=None,
+                    help="steps of the first piece the recurrent passes are cut into (library default if omitted; 0 = uncut)")
+    ap.add_argument("--batch-groups", type=int, default=None,
+                    help="groups the sequences are dealt out to per direction (library default if omitted)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed region, run one plain 1 GiB copy kernel (known HBM traffic) "
@@ -104,10 +92,10 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
-    wl = synth.config3() if args.workload == "config3" else synth.config2()
+    wl = {"config2": synth.config2, "config3": synth.config3, "config4": synth.config4}[args.workload]()
     log(f"workload {wl.name}: L={wl.L} T={wl.T} B={wl.B} D={wl.D} H={wl.H} frames={wl.frames} slots={wl.T * wl.B}")
 
-    desc = rl.rblstm_desc(L=wl.L, T=wl.T, B=wl.B, D=wl.D, H=wl.H, operand_dtype=0, engine=args.engine)
+    desc = rl.rblstm_desc(L=wl.L, T=wl.T, B=wl.B, D=wl.D, H=wl.H, operand_dtype=wl.operand_dtype, engine=args.engine)
     x = torch.from_numpy(wl.x).to(dev)
     sl = torch.from_numpy(wl.seq_lens).to(dev)
     params = [torch.from_numpy(a).to(dev) for layer in wl.params for p in layer for a in p]
@@ -118,6 +106,10 @@ def main():
     ws = torch.empty(rl.rblstm_workspace_bytes(desc), dtype=torch.uint8, device=dev)
     sa = torch.cuda.current_stream()
     sb = None if args.one_stream else torch.cuda.Stream()
+    if args.first_piece is not None:
+        rl.rlstm_set_first_piece(args.first_piece)
+    if args.batch_groups is not None:
+        rl.rlstm_set_batch_groups(args.batch_groups)
 
     def step():
         # the bottom layer's input gradient is not needed for training and is skipped (dx = null)
@@ -149,19 +141,22 @@ def main():
 
     # per-kernel-group summary from the HIP events recorded inside the timed region
     by_kind = {}
-    for kind, layer, ndir, ms in prof:
-        d = by_kind.setdefault(kind, {"ms": 0.0, "launches": 0, "flop": 0.0})
+    for kind, layer, ndir, ms, nsteps, flop in prof:
+        d = by_kind.setdefault(kind, {"ms": 0.0, "launches": 0, "flop": 0.0, "rsteps": 0})
         d["ms"] += ms
         d["launches"] += 1
-        d["flop"] += gemm_flops(kind, layer, wl)
+        d["flop"] += flop
+        d["rsteps"] += nsteps
     kernels = []
     for kind, d in sorted(by_kind.items()):
         e = {"kernel": rl.PROFILE_KINDS[kind], "launches_per_step": d["launches"] / args.steps,
              "avg_ms": d["ms"] / d["launches"], "ms_per_step": d["ms"] / args.steps,
              "tflops": d["flop"] / (d["ms"] * 1e-3) / 1e12}
         if kind in (1, 2):
-            e["step_us"] = 1e3 * e["avg_ms"] / wl.T
-            e["hbm_gbs"] = rec_bytes(kind, wl) / (e["avg_ms"] * 1e-3) / 1e9
+            # a pass over the T steps may be cut into several launches
+            e["steps_per_launch"] = d["rsteps"] / d["launches"]
+            e["step_us"] = 1e3 * d["ms"] / d["rsteps"]
+            e["hbm_gbs"] = rec_bytes(kind, wl, d["rsteps"]) / (d["ms"] * 1e-3) / 1e9
         kernels.append(e)
         log(e)
     dom = max(kernels, key=lambda e: e["ms_per_step"])
@@ -170,8 +165,9 @@ def main():
     measured_traffic = {"recurrent_forward": 5.306e9 + 2.560e9, "recurrent_backward": 11.274e9 + 3.621e9,
                         "input_projection": 0.903e9 + 0.274e9, "input_gradient": 2.226e9 + 0.145e9,
                         "weight_gradient": 0.949e9 + 0.061e9, "recurrent_weight_gradient": 0.949e9 + 0.061e9}
-    roofline = {"kernel": dom["kernel"], "bound": "mfma", "achieved": dom["tflops"], "peak": PEAK_FP32_MFMA_TFLOPS,
-                "unit": "TFLOP/s", "frac": dom["tflops"] / PEAK_FP32_MFMA_TFLOPS,
+    peak = PEAK_FP32_MFMA_TFLOPS if wl.operand_dtype == 0 else PEAK_BF16_MFMA_TFLOPS
+    roofline = {"kernel": dom["kernel"], "bound": "mfma", "achieved": dom["tflops"], "peak": peak,
+                "unit": "TFLOP/s", "frac": dom["tflops"] / peak,
                 "traffic": measured_traffic.get(dom["kernel"]) if args.workload == "config3" else None,
                 "avg_launch_ms": dom["avg_ms"],
                 "note": "the recurrent kernels are bound by the serial chain of T dependent steps "
@@ -181,7 +177,8 @@ def main():
     out = {
         "metric": "BLSTM train frames/sec (fwd+bwd)", "value": frames_per_s, "unit": "frames/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if wl.operand_dtype == 0 else "bf16 operands, f32 accumulate", "data": "synthetic",
         "config": {"workload": wl.name, "layers": wl.L, "units_per_direction": wl.H, "batch": wl.B,
                    "T_padded": wl.T, "valid_frames": wl.frames, "padded_slots": wl.T * wl.B,
                    "padded_slots_per_s": wl.T * wl.B / (ms_per_step * 1e-3),
@@ -190,7 +187,7 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.workload != "config4":
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out), flush=True)
 

@@ -196,14 +196,18 @@ RLSTM_API int rlstm_gemm_bf16(int trans_a, int trans_b, int M, int N, int K,
  * clears the record; it returns the number of entries recorded (which may
  * exceed max_entries) or a negative code; when timing has been switched off it
  * also destroys the events it had created.  Not thread-safe.
- *   kind: 0 input projection X W + b        1 recurrent forward pass (all T steps)
+ *   kind: 0 input projection X W + b        1 recurrent forward pass
  *         2 pass back through time          3 input gradient dZ W^T
  *         4 weight gradient X^T dZ          5 recurrent weight gradient Hprev^T dZ
- *   layer: stack layer (0 for the single-layer entry points); ndir: directions covered
+ *   layer: stack layer (0 for the single-layer entry points); ndir: directions covered;
+ *   steps: recurrent steps the group covers (a pass may be cut into several groups; 0 for a
+ *   matrix product); flop: algorithmic floating-point operations of the group (2 M N K of a
+ *   product; 2 B H 4H per step and direction of a recurrent pass)
  */
 typedef struct rlstm_profile_entry {
-  int32_t kind, layer, ndir, reserved;
-  float ms;
+  int32_t kind, layer, ndir, steps;
+  float ms, reserved;
+  double flop;
 } rlstm_profile_entry;
 RLSTM_API int rlstm_profile_enable(int on);
 RLSTM_API int rlstm_profile_read(rlstm_profile_entry* out, int max_entries);
@@ -220,6 +224,36 @@ RLSTM_API int rlstm_copy_f32(float* dst, const float* src, size_t n, void* hip_s
  * expired since the last call that used this workspace, 1 = one did and the
  * results are invalid, negative = RLSTM_E* code.  Synchronises the device. */
 RLSTM_API int rlstm_last_timeout(const void* workspace);
+
+/*
+ * Tuning knob of blstm_stack_fwd_bwd with two streams and the persistent engine.  Each layer's
+ * recurrent pass is cut into pieces of `steps`, `steps`, 2*`steps`, 4*`steps`, ... steps, and the
+ * matrix product that feeds a piece (input projection in the forward pass, gradient w.r.t. the
+ * layer input in the backward pass) runs on stream b while stream a is inside the piece before it.
+ * 0 = passes are not cut.  Default 128.  Process-wide; results do not depend on it beyond the
+ * order of floating-point sums in the bias gradient.  Returns RLSTM_EDIM for a negative value.
+ */
+RLSTM_API int rlstm_set_first_piece(int steps);
+
+/*
+ * Tuning knob of the persistent engine.  The sequences of a minibatch are independent; the
+ * engine deals them out to `groups` groups of workgroups per direction, each with its own copy of
+ * the recurrent matrix, which exchange h_t / d a_t only among themselves.  0 (default) = chosen
+ * per shape; otherwise 1, 2, 4 or 8 with directions * groups <= 8 (a value the shape cannot use
+ * makes the persistent engine unavailable for it).  Process-wide.  Results do not depend on it
+ * beyond the order of floating-point sums in the bias gradient.
+ */
+RLSTM_API int rlstm_set_batch_groups(int groups);
+
+/*
+ * Test hook for the failure path of the persistent kernels (not part of the method).  From the
+ * next call on, workgroup `mute_workgroup` of every persistent launch withholds its step flags
+ * (-1: none does), and every wait between workgroups is bounded by `wait_ticks` ticks of the
+ * 100 MHz wall clock (0: the default of 4 s).  With a muted workgroup the others' waits expire,
+ * every workgroup leaves its loop, the kernels end normally, the results are invalid and
+ * rlstm_last_timeout() reports 1.  rlstm_test_hook(-1, 0) restores normal operation.
+ */
+RLSTM_API int rlstm_test_hook(int mute_workgroup, uint64_t wait_ticks);
 
 /* Which engine RLSTM_ENGINE_AUTO resolves to for this shape on the current
  * device: RLSTM_ENGINE_PERSISTENT or RLSTM_ENGINE_STEPWISE (negative: error). */

@@ -24,7 +24,7 @@ RLSTM_ENGINE_STEPWISE = 2
 EXPORTS = [
     "rlstm_reserve_bytes", "rlstm_workspace_bytes", "rblstm_reserve_bytes", "rblstm_workspace_bytes",
     "lstm_fwd", "lstm_bwd", "blstm_stack_fwd_bwd", "blstm_stack_fwd",
-    "rlstm_gemm_f32", "rlstm_gemm_bf16", "rlstm_copy_f32", "rlstm_profile_enable", "rlstm_profile_read", "rlstm_last_timeout", "rlstm_resolve_engine", "rlstm_strerror", "rlstm_version",
+    "rlstm_gemm_f32", "rlstm_gemm_bf16", "rlstm_copy_f32", "rlstm_profile_enable", "rlstm_profile_read", "rlstm_last_timeout", "rlstm_test_hook", "rlstm_set_first_piece", "rlstm_set_batch_groups", "rlstm_resolve_engine", "rlstm_strerror", "rlstm_version",
 ]
 
 
@@ -39,7 +39,8 @@ class rblstm_desc(ctypes.Structure):
 
 class rlstm_profile_entry(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int32), ("layer", ctypes.c_int32), ("ndir", ctypes.c_int32),
-                ("reserved", ctypes.c_int32), ("ms", ctypes.c_float)]
+                ("steps", ctypes.c_int32), ("ms", ctypes.c_float), ("reserved", ctypes.c_float),
+                ("flop", ctypes.c_double)]
 
 
 PROFILE_KINDS = {0: "input_projection", 1: "recurrent_forward", 2: "recurrent_backward",
@@ -91,6 +92,12 @@ def lib() -> ctypes.CDLL:
         L.rlstm_profile_read.argtypes = [ctypes.POINTER(rlstm_profile_entry), ip]
         L.rlstm_last_timeout.restype = ip
         L.rlstm_last_timeout.argtypes = [vp]
+        L.rlstm_set_batch_groups.restype = ip
+        L.rlstm_set_batch_groups.argtypes = [ip]
+        L.rlstm_set_first_piece.restype = ip
+        L.rlstm_set_first_piece.argtypes = [ip]
+        L.rlstm_test_hook.restype = ip
+        L.rlstm_test_hook.argtypes = [ip, ctypes.c_uint64]
         L.rlstm_resolve_engine.restype = ip
         L.rlstm_resolve_engine.argtypes = [ctypes.POINTER(rlstm_desc)]
         L.rlstm_strerror.restype = ctypes.c_char_p
@@ -211,12 +218,13 @@ def rlstm_profile_enable(on: bool) -> int:
 
 
 def rlstm_profile_read(max_entries: int = 4096):
-    """Returns the recorded (kind, layer, ndir, ms) entries in launch order and clears the record."""
+    """Returns the recorded (kind, layer, ndir, ms, steps, flop) entries in launch order and clears the record."""
     buf = (rlstm_profile_entry * max_entries)()
     n = int(lib().rlstm_profile_read(buf, max_entries))
     if n < 0:
         raise RlstmError(n, "rlstm_profile_read")
-    return [(buf[i].kind, buf[i].layer, buf[i].ndir, float(buf[i].ms)) for i in range(min(n, max_entries))]
+    return [(buf[i].kind, buf[i].layer, buf[i].ndir, float(buf[i].ms), buf[i].steps, float(buf[i].flop))
+            for i in range(min(n, max_entries))]
 
 
 def rlstm_copy_f32(dst, src, n, stream=None, check=True) -> int:
@@ -233,4 +241,22 @@ def rlstm_gemm_bf16(trans_a, trans_b, M, N, K, A, lda, B, ldb, C, ldc, bias=None
                                _ptr(bias), _ptr(splitk_ws), nbytes, _stream(stream))
     if check and rc != 0:
         raise RlstmError(rc, "rlstm_gemm_bf16")
+    return rc
+
+
+def rlstm_test_hook(mute_workgroup: int = -1, wait_ticks: int = 0) -> int:
+    return int(lib().rlstm_test_hook(int(mute_workgroup), int(wait_ticks)))
+
+
+def rlstm_set_first_piece(steps: int) -> int:
+    rc = int(lib().rlstm_set_first_piece(int(steps)))
+    if rc != 0:
+        raise RlstmError(rc, "rlstm_set_first_piece")
+    return rc
+
+
+def rlstm_set_batch_groups(groups: int) -> int:
+    rc = int(lib().rlstm_set_batch_groups(int(groups)))
+    if rc != 0:
+        raise RlstmError(rc, "rlstm_set_batch_groups")
     return rc

@@ -50,7 +50,7 @@ int resolve_engine(int engine, const RecShape& s) {
 }
 
 // ---- optional event timing of the enqueued kernel groups ---------------------
-struct ProfRec { int kind, layer, ndir; hipEvent_t a, b; };
+struct ProfRec { int kind, layer, ndir, steps; double flop; hipEvent_t a, b; };
 bool g_prof_on = false;
 std::vector<ProfRec> g_prof;
 std::vector<hipEvent_t> g_prof_pool;
@@ -63,15 +63,19 @@ hipEvent_t prof_event() {
 }
 struct ProfScope {
   hipStream_t st; hipEvent_t b = nullptr; bool on;
-  ProfScope(hipStream_t s, int kind, int layer, int ndir) : st(s), on(g_prof_on) {
+  // steps: recurrent steps covered (0 for a matrix product); flop: algorithmic FLOP of the group
+  ProfScope(hipStream_t s, int kind, int layer, int ndir, int steps, double flop) : st(s), on(g_prof_on) {
     if (!on) return;
     hipEvent_t a = prof_event(); b = prof_event();
     if (!a || !b) { on = false; return; }
     (void)hipEventRecord(a, st);
-    g_prof.push_back(ProfRec{kind, layer, ndir, a, b});
+    g_prof.push_back(ProfRec{kind, layer, ndir, steps, flop, a, b});
   }
   ~ProfScope() { if (on) (void)hipEventRecord(b, st); }
 };
+
+inline double gemm_flop(const GemmCall& g) { return 2.0 * g.M * g.N * g.K; }
+inline double rec_flop(const RecShape& s, int steps) { return 2.0 * s.B * s.H * 4.0 * s.H * steps * s.ndir; }
 
 int hip_to_code(hipError_t e, int resident_err) {
   if (e == hipSuccess) return RLSTM_OK;
@@ -97,7 +101,7 @@ int weight_grads(hipStream_t st, int layer, int T, int B, int Din, int H, int di
   g.A = x; g.lda = ldx; g.B = dz; g.ldb = 4 * H; g.C = dW; g.ldc = 4 * H;
   g.splitk_ws = skws; g.splitk_floats = skfloats; g.naive = naive; g.operand_dtype = operand_dtype;
   {
-    ProfScope ps(st, 4, layer, 1);
+    ProfScope ps(st, 4, layer, 1, 0, gemm_flop(g));
     RLSTM_TRY(gemm(st, g));
   }
   GemmCall r = g;
@@ -106,7 +110,7 @@ int weight_grads(hipStream_t st, int layer, int T, int B, int Din, int H, int di
   if (direction > 0) { r.A = y; r.B = dz + (size_t)B * 4 * H; }
   else               { r.A = y + (size_t)B * ldy; r.B = dz; }
   {
-    ProfScope ps(st, 5, layer, 1);
+    ProfScope ps(st, 5, layer, 1, 0, gemm_flop(r));
     RLSTM_TRY(gemm(st, r));
   }
   return RLSTM_OK;
@@ -133,14 +137,54 @@ RecShape stack_rec_shape(const rblstm_desc* d) {
   return s;
 }
 
+// Pipelining of a layer's recurrent pass with the matrix product that feeds it.  The pass over the
+// T steps is cut into pieces [b_k, b_k+1); the product for the frames of piece k+1 runs on the
+// second stream while the first stream is inside piece k.  Only the product of piece 0 is exposed,
+// so the pieces start small and double (the products run two to three times faster per frame than
+// the recurrence, so a piece of twice the size is ready in time).
+int g_first_piece = 128;         // steps of piece 0; 0 = do not cut
+
+std::vector<int> piece_bounds(int T, bool pipelined) {
+  std::vector<int> b{0};
+  if (pipelined && g_first_piece > 0) {
+    for (long long e = g_first_piece; e < T; e *= 2) b.push_back((int)e);
+    if (b.size() > 1 && T - b.back() < g_first_piece) b.pop_back();
+  }
+  b.push_back(T);
+  return b;
+}
+
+// events that order the two streams; destroyed when the call returns (the dependencies they
+// expressed stay in the streams)
+struct EventList {
+  std::vector<hipEvent_t> evs;
+  ~EventList() { for (hipEvent_t ev : evs) (void)hipEventDestroy(ev); }
+  // work enqueued on `after` from now on starts when everything enqueued on `first` so far is done
+  hipError_t order(hipStream_t first, hipStream_t after) {
+    if (first == after) return hipSuccess;
+    hipEvent_t ev;
+    hipError_t e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+    if (e != hipSuccess) return e;
+    evs.push_back(ev);
+    e = hipEventRecord(ev, first);
+    if (e != hipSuccess) return e;
+    return hipStreamWaitEvent(after, ev, 0);
+  }
+};
+
+// sb == sa: everything in order on one stream, passes uncut
 int stack_forward(const rblstm_desc* d, const float* x, const float* const* params, const int32_t* seq_lens,
-                  float* y_top, float* res, char* ws, hipStream_t sa, bool persistent) {
+                  float* y_top, float* res, char* ws, hipStream_t sa, hipStream_t sb, bool persistent) {
   int resident_err = 0;
   const StackLayout lay = stack_layout(d);
   const RecShape rs = stack_rec_shape(d);
   unsigned* flag = reinterpret_cast<unsigned*>(ws);
   void* recws = ws + kFlagBytes;
   const int T = d->T, B = d->B, H = d->H;
+  const bool pipelined = persistent && sb != sa;
+  const std::vector<int> pb = piece_bounds(T, pipelined);
+  const int np = (int)pb.size() - 1;
+  EventList evs;
   RLSTM_TRY(clear_flag(sa, flag));
   const float* in = x;
   int din = d->D;
@@ -148,24 +192,27 @@ int stack_forward(const rblstm_desc* d, const float* x, const float* const* para
     float* base = res + (size_t)l * lay.per_layer;
     float* yl = (l == d->L - 1) ? y_top : base + lay.y;
     RecFwdDir dirs[2];
-    for (int k = 0; k < 2; ++k) {
-      const float* W = params[6 * l + 3 * k + 0];
-      const float* R = params[6 * l + 3 * k + 1];
-      const float* b = params[6 * l + 3 * k + 2];
-      GemmCall g;
-      g.M = T * B; g.N = 4 * H; g.K = din;
-      g.A = in; g.lda = din; g.B = W; g.ldb = 4 * H; g.C = base + lay.zg[k]; g.ldc = 4 * H; g.bias = b;
-      g.naive = !persistent; g.operand_dtype = d->operand_dtype;
-      {
-        ProfScope ps(sa, 0, l, 1);
-        RLSTM_TRY(gemm(sa, g));
+    for (int k = 0; k < 2; ++k)
+      dirs[k] = RecFwdDir{base + lay.zg[k], params[6 * l + 3 * k + 1], nullptr, nullptr, yl + (size_t)k * H,
+                          base + lay.c[k], nullptr, nullptr, k == 0 ? 1 : -1};
+    // the layer's input (the caller's x, or the layer below on stream a) is complete
+    RLSTM_TRY(evs.order(sa, sb));
+    for (int pc = 0; pc < np; ++pc) {
+      const int s0 = pb[pc], s1 = pb[pc + 1];
+      // input part of the frames that steps [s0, s1) visit: direction +1 frames [s0, s1), direction -1 frames [T-s1, T-s0)
+      for (int k = 0; k < 2; ++k) {
+        const size_t f0 = (k == 0) ? (size_t)s0 : (size_t)(T - s1);
+        GemmCall g;
+        g.M = (s1 - s0) * B; g.N = 4 * H; g.K = din;
+        g.A = in + f0 * B * din; g.lda = din; g.B = params[6 * l + 3 * k + 0]; g.ldb = 4 * H;
+        g.C = base + lay.zg[k] + f0 * B * 4 * H; g.ldc = 4 * H; g.bias = params[6 * l + 3 * k + 2];
+        g.naive = !persistent; g.operand_dtype = d->operand_dtype;
+        ProfScope ps(sb, 0, l, 1, 0, gemm_flop(g));
+        RLSTM_TRY(gemm(sb, g));
       }
-      dirs[k] = RecFwdDir{base + lay.zg[k], R, nullptr, nullptr, yl + (size_t)k * H, base + lay.c[k],
-                          nullptr, nullptr, k == 0 ? 1 : -1};
-    }
-    {
-      ProfScope ps(sa, 1, l, 2);
-      RLSTM_TRY(rec_forward(sa, rs, dirs, seq_lens, recws, flag, persistent, &resident_err));
+      RLSTM_TRY(evs.order(sb, sa));
+      ProfScope ps(sa, 1, l, 2, s1 - s0, rec_flop(rs, s1 - s0));
+      RLSTM_TRY(rec_forward(sa, rs, dirs, seq_lens, recws, flag, persistent, &resident_err, s0, s1));
     }
     in = yl;
     din = 2 * H;
@@ -232,6 +279,23 @@ int rlstm_last_timeout(const void* workspace) {
   return v != 0 ? 1 : 0;
 }
 
+int rlstm_set_first_piece(int steps) {
+  if (steps < 0) return RLSTM_EDIM;
+  g_first_piece = steps;
+  return RLSTM_OK;
+}
+
+int rlstm_set_batch_groups(int groups) {
+  if (groups < 0 || groups > 8) return RLSTM_EDIM;
+  persistent_set_batch_groups(groups);
+  return RLSTM_OK;
+}
+
+int rlstm_test_hook(int mute_workgroup, uint64_t wait_ticks) {
+  persistent_test_hook(mute_workgroup, wait_ticks);
+  return RLSTM_OK;
+}
+
 int rlstm_copy_f32(float* dst, const float* src, size_t n, void* hip_stream) {
   if (!dst || !src) return RLSTM_ENULL;
   int resident_err = 0;
@@ -254,7 +318,7 @@ int rlstm_profile_read(rlstm_profile_entry* out, int max_entries) {
       (void)hipGetLastError();
       rc = RLSTM_EHIP;
     }
-    if (out && i < max_entries) out[i] = rlstm_profile_entry{r.kind, r.layer, r.ndir, 0, ms};
+    if (out && i < max_entries) out[i] = rlstm_profile_entry{r.kind, r.layer, r.ndir, r.steps, ms, 0.f, r.flop};
     g_prof_pool.push_back(r.a);
     g_prof_pool.push_back(r.b);
   }
@@ -318,13 +382,13 @@ int lstm_fwd(const rlstm_desc* d, const float* x, const float* W, const float* R
   g.A = x; g.lda = ldx; g.B = W; g.ldb = 4 * d->H; g.C = zg; g.ldc = 4 * d->H; g.bias = b;
   g.naive = !persistent; g.operand_dtype = d->operand_dtype;
   {
-    ProfScope ps(st, 0, 0, 1);
+    ProfScope ps(st, 0, 0, 1, 0, gemm_flop(g));
     RLSTM_TRY(gemm(st, g));
   }
   RecFwdDir dir{zg, R, h0, c0, y, c, hT, cT, d->direction};
   {
-    ProfScope ps(st, 1, 0, 1);
-    RLSTM_TRY(rec_forward(st, s, &dir, seq_lens, ws + kFlagBytes, flag, persistent, &resident_err));
+    ProfScope ps(st, 1, 0, 1, d->T, rec_flop(s, d->T));
+    RLSTM_TRY(rec_forward(st, s, &dir, seq_lens, ws + kFlagBytes, flag, persistent, &resident_err, 0, d->T));
   }
   return RLSTM_OK;
 }
@@ -356,8 +420,8 @@ int lstm_bwd(const rlstm_desc* d, const float* x, const float* W, const float* R
   RLSTM_TRY(clear_flag(st, flag));
   RecBwdDir dir{zg, R, c, c0, dy, dhT, dcT, dh0, dc0, db, d->direction};
   {
-    ProfScope ps(st, 2, 0, 1);
-    RLSTM_TRY(rec_backward(st, s, &dir, seq_lens, recws, flag, persistent, &resident_err));
+    ProfScope ps(st, 2, 0, 1, T, rec_flop(s, T));
+    RLSTM_TRY(rec_backward(st, s, &dir, seq_lens, recws, flag, persistent, &resident_err, 0, T));
   }
   rc = weight_grads(st, 0, T, B, D, H, d->direction, x, ldx, y, ldy, zg, dW, dR, skws, skfloats, !persistent, d->operand_dtype);
   if (rc != RLSTM_OK) return rc;
@@ -368,7 +432,7 @@ int lstm_bwd(const rlstm_desc* d, const float* x, const float* W, const float* R
     g.M = T * B; g.N = D; g.K = 4 * H;
     g.A = zg; g.lda = 4 * H; g.B = W; g.ldb = 4 * H; g.C = dx; g.ldc = ldx;
     g.naive = !persistent; g.operand_dtype = d->operand_dtype;
-    ProfScope ps(st, 3, 0, 1);
+    ProfScope ps(st, 3, 0, 1, 0, gemm_flop(g));
     RLSTM_TRY(gemm(st, g));
   }
   return RLSTM_OK;
@@ -383,7 +447,8 @@ int blstm_stack_fwd(const rblstm_desc* d, const float* x, const float* const* pa
   const int eng = resolve_engine(d->engine, stack_rec_shape(d));
   if (eng < 0) return eng;
   return stack_forward(d, x, params, seq_lens, y_top, static_cast<float*>(reserve), static_cast<char*>(workspace),
-                       static_cast<hipStream_t>(hip_stream_a), eng == RLSTM_ENGINE_PERSISTENT);
+                       static_cast<hipStream_t>(hip_stream_a), static_cast<hipStream_t>(hip_stream_a),
+                       eng == RLSTM_ENGINE_PERSISTENT);
 }
 
 int blstm_stack_fwd_bwd(const rblstm_desc* d, const float* x, const float* const* params,
@@ -405,7 +470,7 @@ int blstm_stack_fwd_bwd(const rblstm_desc* d, const float* x, const float* const
 
   float* res = static_cast<float*>(reserve);
   char* ws = static_cast<char*>(workspace);
-  rc = stack_forward(d, x, params, seq_lens, y_top, res, ws, sa, persistent);
+  rc = stack_forward(d, x, params, seq_lens, y_top, res, ws, sa, sb, persistent);
   if (rc != RLSTM_OK) return rc;
 
   int resident_err = 0;
@@ -419,18 +484,15 @@ int blstm_stack_fwd_bwd(const rblstm_desc* d, const float* x, const float* const
   const size_t dyfloats = align_up((size_t)T * B * 2 * H, 64);
   float* dybuf[2] = {skws + skfloats, skws + skfloats + dyfloats};
 
-  std::vector<hipEvent_t> events;
-  auto new_event = [&](hipEvent_t* ev) -> hipError_t {
-    hipError_t e = hipEventCreateWithFlags(ev, hipEventDisableTiming);
-    if (e == hipSuccess) events.push_back(*ev);
-    return e;
-  };
-  auto cleanup = [&]() { for (hipEvent_t ev : events) (void)hipEventDestroy(ev); };
-#define RLSTM_TRY_C(expr)                                                         \
-  do {                                                                            \
-    hipError_t e_ = (expr);                                                       \
-    if (e_ != hipSuccess) { cleanup(); return hip_to_code(e_, resident_err); }    \
-  } while (0)
+  // Stream a carries the chain of recurrent passes, stream b every matrix product.  The gradient
+  // w.r.t. a layer's input is the dy of the layer below: it is produced on stream b in the pieces,
+  // and in the frame order, in which that layer's pass back through time consumes it, one piece
+  // ahead; the weight gradients follow on stream b and overlap the rest of that pass.
+  const bool pipelined = persistent && overlap;
+  const std::vector<int> pb = piece_bounds(T, pipelined);
+  const int np = (int)pb.size() - 1;
+  EventList evs;
+  std::vector<hipEvent_t> ready;       // ready[pc]: dy of piece pc of the layer about to run is complete
 
   const float* dy = dy_top;
   for (int l = L - 1; l >= 0; --l) {
@@ -444,13 +506,41 @@ int blstm_stack_fwd_bwd(const rblstm_desc* d, const float* x, const float* const
                           dy + (size_t)k * H, nullptr, nullptr, nullptr, nullptr, grads[6 * l + 3 * k + 2],
                           k == 0 ? 1 : -1};
     }
-    {
-      ProfScope ps(sa, 2, l, 2);
-      RLSTM_TRY_C(rec_backward(sa, rs, dirs, seq_lens, recws, flag, persistent, &resident_err));
+    for (int pc = 0; pc < np; ++pc) {
+      if (!ready.empty()) RLSTM_TRY(hipStreamWaitEvent(sa, ready[pc], 0));
+      ProfScope ps(sa, 2, l, 2, pb[pc + 1] - pb[pc], rec_flop(rs, pb[pc + 1] - pb[pc]));
+      RLSTM_TRY(rec_backward(sa, rs, dirs, seq_lens, recws, flag, persistent, &resident_err, pb[pc], pb[pc + 1]));
     }
-    // input gradient = next lower layer's dy: on the dependent chain (stream a), so it runs first and alone
+    ready.clear();
+    RLSTM_TRY(evs.order(sa, sb));
+
     float* dxl = (l == 0) ? dx : dybuf[l & 1];
-    if (dxl) {
+    if (dxl && l > 0 && sb != sa) {
+      // columns [0,H) feed direction +1 of the layer below, which visits frames T-1 .. 0;
+      // columns [H,2H) feed direction -1, which visits frames 0 .. T-1
+      for (int pc = 0; pc < np; ++pc) {
+        const int s0 = pb[pc], s1 = pb[pc + 1];
+        for (int tk = 0; tk < 2; ++tk) {
+          const size_t f0 = (tk == 0) ? (size_t)(T - s1) : (size_t)s0;
+          for (int k = 0; k < 2; ++k) {
+            GemmCall g;
+            g.transB = true;
+            g.M = (s1 - s0) * B; g.N = H; g.K = 4 * H;
+            g.A = base + lay.zg[k] + f0 * B * 4 * H; g.lda = 4 * H;
+            g.B = params[6 * l + 3 * k + 0] + (size_t)tk * H * 4 * H; g.ldb = 4 * H;
+            g.C = dxl + f0 * B * din + (size_t)tk * H; g.ldc = din; g.accumulate = (k == 1);
+            g.naive = !persistent; g.operand_dtype = d->operand_dtype;
+            ProfScope ps(sb, 3, l, 1, 0, gemm_flop(g));
+            RLSTM_TRY(gemm(sb, g));
+          }
+        }
+        hipEvent_t ev;
+        RLSTM_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+        evs.evs.push_back(ev);
+        RLSTM_TRY(hipEventRecord(ev, sb));
+        ready.push_back(ev);
+      }
+    } else if (dxl) {
       for (int k = 0; k < 2; ++k) {
         GemmCall g;
         g.transB = true;
@@ -458,33 +548,21 @@ int blstm_stack_fwd_bwd(const rblstm_desc* d, const float* x, const float* const
         g.A = base + lay.zg[k]; g.lda = 4 * H; g.B = params[6 * l + 3 * k + 0]; g.ldb = 4 * H;
         g.C = dxl; g.ldc = din; g.accumulate = (k == 1);
         g.naive = !persistent; g.operand_dtype = d->operand_dtype;
-        ProfScope ps(sa, 3, l, 1);
-        RLSTM_TRY_C(gemm(sa, g));
+        ProfScope ps(sb, 3, l, 1, 0, gemm_flop(g));
+        RLSTM_TRY(gemm(sb, g));
       }
-    }
-    // weight gradients are independent of the chain: stream b, released once the input gradient is
-    // done, so that they overlap the next layer's pass back through time rather than compete with dX
-    if (overlap) {
-      hipEvent_t ev;
-      RLSTM_TRY_C(new_event(&ev));
-      RLSTM_TRY_C(hipEventRecord(ev, sa));
-      RLSTM_TRY_C(hipStreamWaitEvent(sb, ev, 0));
+      // one stream: already in order
     }
     for (int k = 0; k < 2; ++k) {
       rc = weight_grads(sb, l, T, B, din, H, k == 0 ? 1 : -1, xin, din, yl + (size_t)k * H, 2 * H,
                         base + lay.zg[k], grads[6 * l + 3 * k + 0], grads[6 * l + 3 * k + 1], skws, skfloats,
                         !persistent, d->operand_dtype);
-      if (rc != RLSTM_OK) { cleanup(); return rc; }
+      if (rc != RLSTM_OK) return rc;
     }
     dy = dxl;
   }
-  if (overlap) {
-    hipEvent_t ev;
-    RLSTM_TRY_C(new_event(&ev));
-    RLSTM_TRY_C(hipEventRecord(ev, sb));
-    RLSTM_TRY_C(hipStreamWaitEvent(sa, ev, 0));
-  }
-  cleanup();
+  // the caller's stream a sees the end of everything
+  RLSTM_TRY(evs.order(sb, sa));
   return RLSTM_OK;
 }
 

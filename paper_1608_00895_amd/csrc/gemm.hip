@@ -37,9 +37,25 @@ struct GemmP {
   const float* bias;
   int accumulate;
   int tiles_n;
-  int kchunk;          // K range per blockIdx.z slice (multiple of BK)
+  int tiles;           // output tiles (tiles_m * tiles_n)
+  int work;            // tiles * split-K slices: work items of the launch
+  int per_xcd;         // ceil(work / 8); the grid is 8 * per_xcd workgroups
+  int kchunk;          // K range per split-K slice (multiple of BK)
   float* partial;      // split-K scratch [slices][M][N] or null
 };
+
+// Work item of a workgroup.  The dispatcher deals consecutive workgroups out to the 8 XCDs in
+// turn, each with its own L2.  Workgroup i therefore takes item (i % 8) * per_xcd + i / 8: every
+// XCD works through one contiguous range of items (n fastest, then m, then K slice), so the
+// operand panels that neighbouring tiles share are fetched into one L2 instead of all eight.
+__device__ __forceinline__ bool work_item(const GemmP& p, int* tile, int* kz) {
+  const int i = blockIdx.x;
+  const int item = (i & 7) * p.per_xcd + (i >> 3);
+  if ((i >> 3) >= p.per_xcd || item >= p.work) return false;
+  *kz = item / p.tiles;
+  *tile = item - *kz * p.tiles;
+  return true;
+}
 
 // ---- slab loaders: global -> registers -> LDS ------------------------------
 
@@ -127,10 +143,11 @@ __global__ __launch_bounds__(256) void gemm_mfma_f32_kernel(GemmP p) {
   float* As = smem;                       // [2][BK][LDT]
   float* Bs = smem + 2 * BK * LDT;        // [2][BK][LDT]
 
-  const int tile = blockIdx.x;
+  int tile, kz;
+  if (!work_item(p, &tile, &kz)) return;
   const int tn = tile % p.tiles_n, tm = tile / p.tiles_n;
   const int m0 = tm * TM, n0 = tn * TN;
-  const int kbeg = blockIdx.z * p.kchunk;
+  const int kbeg = kz * p.kchunk;
   const int kend = min(p.K, kbeg + p.kchunk);
   const int nslab = (kend - kbeg + BK - 1) / BK;
 
@@ -171,16 +188,23 @@ __global__ __launch_bounds__(256) void gemm_mfma_f32_kernel(GemmP p) {
     if (s + 1 < nslab) { loadA(kbeg + (s + 1) * BK); loadB(kbeg + (s + 1) * BK); }
     const float* as = As + buf * BK * LDT + wm * 64 + l32;
     const float* bs = Bs + buf * BK * LDT + wn * 64 + l32;
+    // operand fragments of step kk+2 are fetched from LDS before the MFMAs of step kk are issued
+    float a0 = as[lh * LDT], a1 = as[lh * LDT + 32], b0 = bs[lh * LDT], b1 = bs[lh * LDT + 32];
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 2) {
-      const float a0 = as[(kk + lh) * LDT];
-      const float a1 = as[(kk + lh) * LDT + 32];
-      const float b0 = bs[(kk + lh) * LDT];
-      const float b1 = bs[(kk + lh) * LDT + 32];
+      float na0 = 0.f, na1 = 0.f, nb0 = 0.f, nb1 = 0.f;
+      if (kk + 2 < BK) {
+        na0 = as[(kk + 2 + lh) * LDT];
+        na1 = as[(kk + 2 + lh) * LDT + 32];
+        nb0 = bs[(kk + 2 + lh) * LDT];
+        nb1 = bs[(kk + 2 + lh) * LDT + 32];
+      }
+      __builtin_amdgcn_sched_barrier(0);   // keep the LDS reads above ahead of this step's MFMAs
       acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
       acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
       acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
       acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+      a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;
     }
     if (s + 1 < nslab) storeAB(buf ^ 1);
     __syncthreads();
@@ -191,7 +215,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_f32_kernel(GemmP p) {
   float* Cout = p.C;
   int ldc = p.ldc;
   const bool partial = p.partial != nullptr;
-  if (partial) { Cout = p.partial + (size_t)blockIdx.z * p.M * p.N; ldc = p.N; }
+  if (partial) { Cout = p.partial + (size_t)kz * p.M * p.N; ldc = p.N; }
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
 #pragma unroll
@@ -314,10 +338,11 @@ __global__ __launch_bounds__(256) void gemm_mfma_bf16_kernel(GemmP p) {
   unsigned short* As = reinterpret_cast<unsigned short*>(smem);     // [2][128][LDK]
   unsigned short* Bs = As + 2 * TM * LDK;                           // [2][128][LDK]
 
-  const int tile = blockIdx.x;
+  int tile, kz;
+  if (!work_item(p, &tile, &kz)) return;
   const int tn = tile % p.tiles_n, tm = tile / p.tiles_n;
   const int m0 = tm * TM, n0 = tn * TN;
-  const int kbeg = blockIdx.z * p.kchunk;
+  const int kbeg = kz * p.kchunk;
   const int kend = min(p.K, kbeg + p.kchunk);
   const int nslab = (kend - kbeg + BKH - 1) / BKH;
 
@@ -375,7 +400,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_bf16_kernel(GemmP p) {
   float* Cout = p.C;
   int ldc = p.ldc;
   const bool partial = p.partial != nullptr;
-  if (partial) { Cout = p.partial + (size_t)blockIdx.z * p.M * p.N; ldc = p.N; }
+  if (partial) { Cout = p.partial + (size_t)kz * p.M * p.N; ldc = p.N; }
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
 #pragma unroll
@@ -499,7 +524,10 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
     p.kchunk = kchunk;
     p.partial = g.splitk_ws;
   }
-  dim3 grid((unsigned)tiles, 1, (unsigned)slices);
+  p.tiles = tiles;
+  p.work = tiles * slices;
+  p.per_xcd = (p.work + 7) / 8;
+  dim3 grid((unsigned)(8 * p.per_xcd), 1, 1);
   hipError_t e;
   if (bf16) {
     if (!g.transA && !g.transB)      e = launch_bf16<false, false>(stream, p, grid, vec);

@@ -7,34 +7,33 @@ namespace rlstm {
 namespace {
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-size_t per_dir_bytes(const RecShape& s) {
-  const size_t a = persistent_scratch_bytes_per_dir(s);
-  const size_t b = stepwise_scratch_floats_per_dir(s) * sizeof(float);
-  return align_up(a > b ? a : b, 256);
-}
+size_t stepwise_dir_bytes(const RecShape& s) { return align_up(stepwise_scratch_floats_per_dir(s) * sizeof(float), 256); }
 }  // namespace
 
-size_t rec_workspace_bytes(const RecShape& s) { return 2 * per_dir_bytes(s); }
+size_t rec_workspace_bytes(const RecShape& s) {
+  const size_t a = persistent_scratch_bytes(s), b = 2 * stepwise_dir_bytes(s);
+  return align_up(a > b ? a : b, 256);
+}
 
 bool rec_persistent_supported(const RecShape& s, int num_cus, size_t max_lds) {
   return persistent_supported(s, num_cus, max_lds);
 }
 
 hipError_t rec_forward(hipStream_t stream, const RecShape& s, const RecFwdDir* dirs, const int32_t* seq_lens,
-                       void* ws, unsigned* flag, bool persistent, int* resident_err) {
+                       void* ws, unsigned* flag, bool persistent, int* resident_err, int s_begin, int s_end) {
   char* base = static_cast<char*>(ws);
-  char* scratch[2] = {base, base + per_dir_bytes(s)};
-  if (persistent) return persistent_forward(stream, s, dirs, seq_lens, scratch, flag, resident_err);
-  float* buf[2] = {reinterpret_cast<float*>(scratch[0]), reinterpret_cast<float*>(scratch[1])};
+  if (persistent) return persistent_forward(stream, s, dirs, seq_lens, base, flag, resident_err, s_begin, s_end);
+  if (s_begin != 0 || s_end != s.T) return hipErrorInvalidValue;
+  float* buf[2] = {reinterpret_cast<float*>(base), reinterpret_cast<float*>(base + stepwise_dir_bytes(s))};
   return stepwise_forward(stream, s, dirs, seq_lens, buf);
 }
 
 hipError_t rec_backward(hipStream_t stream, const RecShape& s, const RecBwdDir* dirs, const int32_t* seq_lens,
-                        void* ws, unsigned* flag, bool persistent, int* resident_err) {
+                        void* ws, unsigned* flag, bool persistent, int* resident_err, int s_begin, int s_end) {
   char* base = static_cast<char*>(ws);
-  char* scratch[2] = {base, base + per_dir_bytes(s)};
-  if (persistent) return persistent_backward(stream, s, dirs, seq_lens, scratch, flag, resident_err);
-  float* buf[2] = {reinterpret_cast<float*>(scratch[0]), reinterpret_cast<float*>(scratch[1])};
+  if (persistent) return persistent_backward(stream, s, dirs, seq_lens, base, flag, resident_err, s_begin, s_end);
+  if (s_begin != 0 || s_end != s.T) return hipErrorInvalidValue;
+  float* buf[2] = {reinterpret_cast<float*>(base), reinterpret_cast<float*>(base + stepwise_dir_bytes(s))};
   return stepwise_backward(stream, s, dirs, seq_lens, buf);
 }
 

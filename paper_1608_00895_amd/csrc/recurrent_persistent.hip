@@ -42,7 +42,7 @@ typedef int intx4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
-constexpr unsigned long long kWaitTimeoutTicks = 400000000ull;   // 4 s of the 100 MHz wall clock
+constexpr unsigned long long kDefaultWaitTicks = 400000000ull;   // 4 s of the 100 MHz wall clock
 constexpr int CG = 16;                  // 16-byte loads in flight per lane
 constexpr int kAuxSc1 = 16;             // buffer-load cache policy: device scope
 
@@ -50,12 +50,14 @@ constexpr int kAuxSc1 = 16;             // buffer-load cache policy: device scop
 struct Spin {
   unsigned n = 0;
   unsigned long long t0 = 0;
+  unsigned long long limit;
+  __device__ __forceinline__ explicit Spin(unsigned long long wait_ticks) : limit(wait_ticks) {}
   // call once per unsuccessful poll; true = give up
   __device__ __forceinline__ bool expired(unsigned* err) {
     if ((++n & 1023u) != 0) return false;
     const unsigned long long now = wall_clock64();
     if (t0 == 0) { t0 = now; return false; }
-    if (now - t0 > kWaitTimeoutTicks) return true;
+    if (now - t0 > limit) return true;
     return __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
   }
 };
@@ -85,11 +87,11 @@ __device__ __forceinline__ void publish_flag(unsigned* flags, int wg, unsigned v
 
 // A wavefront waits until flags[first .. first+count) (clipped to limit) have all reached `want`.
 __device__ __forceinline__ bool wave_wait_flags(const unsigned* flags, int first, int count, int limit,
-                                                unsigned want, unsigned* err) {
+                                                unsigned want, unsigned* err, unsigned long long wait_ticks) {
   const int lane = threadIdx.x & 63;
   const bool mine = lane < count && first + lane < limit;
   const unsigned* src = flags + (mine ? first + lane : first);
-  Spin sp;
+  Spin sp(wait_ticks);
   bool ok = true;
   for (;;) {
     const bool ready = !mine || ld_dev(src) >= want;
@@ -112,12 +114,20 @@ __device__ __forceinline__ int operand_slot(int k, int b) {
   return ((L >> 2) * 64 + (k & 3) * 16 + (b & 15)) * 4 + (L & 3);
 }
 
+// column of the resident fp32 matrix in LDS: row k keeps its 16*NT columns rotated by 16*(k%4), so
+// that the four rows one MFMA operand fetch touches fall into different banks
+template <int NT>
+__device__ __forceinline__ int rotated_col(int k, int col) { return (col + 16 * (k & 3)) & (16 * NT - 1); }
+
 // One wavefront's share of a [B x K] * [K x 16*NT] product.  A rows come from the exchange
-// array (device-scope 16-byte loads, operand order), B rows from LDS (row stride ldb floats).
-template <int MT, int NT>
-__device__ __forceinline__ void wave_product(const float* xblock, int xblock_bytes, int nch, const float* bs, int ldb,
+// array (device-scope 16-byte loads, operand order), B rows from LDS (row stride 16*NT floats,
+// columns rotated per row).  HALF: only sequences 0..7 of the tile exist; the other lanes load nothing.
+template <int MT, int NT, bool HALF>
+__device__ __forceinline__ void wave_product(const float* xblock, int xblock_bytes, int nch, const float* bs,
                                              floatx4 (&acc)[MT][NT]) {
+  constexpr int ldb = 16 * NT;
   const int lane = threadIdx.x & 63, l16 = lane & 15, lq = lane >> 4;
+  const bool loads = !HALF || l16 < 8;
   __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(xblock), 0, xblock_bytes, 0x00020000);
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
@@ -126,8 +136,11 @@ __device__ __forceinline__ void wave_product(const float* xblock, int xblock_byt
   for (int c0 = 0; c0 < nch; c0 += CG) {
     floatx4 v[CG];
 #pragma unroll
-    for (int q = 0; q < CG; ++q)
-      v[q] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, ((c0 + q) * 64 + lane) * 16, 0, kAuxSc1));
+    for (int q = 0; q < CG; ++q) {
+      v[q] = floatx4{0.f, 0.f, 0.f, 0.f};
+      if (loads)
+        v[q] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, ((c0 + q) * 64 + lane) * 16, 0, kAuxSc1));
+    }
     // chunks past nch read beyond the buffer resource's size and return zeros; their MFMAs are skipped
 #pragma unroll
     for (int q = 0; q < CG; ++q) {
@@ -139,7 +152,7 @@ __device__ __forceinline__ void wave_product(const float* xblock, int xblock_byt
           const int mt = w % MT;
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt) {
-            const float bf = bs[(ks * 4 + lq) * ldb + nt * 16 + l16];
+            const float bf = bs[(ks * 4 + lq) * ldb + ((nt + lq) & (NT - 1)) * 16 + l16];
             acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(v[q][w], bf, acc[mt][nt], 0, 0, 0);
           }
         }
@@ -164,10 +177,12 @@ __device__ __forceinline__ int operand_slot_bf(int kr, int b) {
 }
 
 // B rows in LDS: [k/8][ldn columns][8] bf16
-template <int MT, int NT>
-__device__ __forceinline__ void wave_product_bf(const void* xblock, int xblock_bytes, int nch, const unsigned short* bs, int ldn,
+template <int MT, int NT, bool HALF>
+__device__ __forceinline__ void wave_product_bf(const void* xblock, int xblock_bytes, int nch, const unsigned short* bs,
                                                 floatx4 (&acc)[MT][NT]) {
+  constexpr int ldn = 16 * NT;
   const int lane = threadIdx.x & 63, l16 = lane & 15, lq = lane >> 4;
+  const bool loads = !HALF || l16 < 8;
   __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(xblock), 0, xblock_bytes, 0x00020000);
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
@@ -176,8 +191,10 @@ __device__ __forceinline__ void wave_product_bf(const void* xblock, int xblock_b
   for (int c0 = 0; c0 < nch; c0 += CG) {
     intx4 v[CG];
 #pragma unroll
-    for (int q = 0; q < CG; ++q)
-      v[q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, ((c0 + q) * 64 + lane) * 16, 0, kAuxSc1);
+    for (int q = 0; q < CG; ++q) {
+      v[q] = intx4{0, 0, 0, 0};
+      if (loads) v[q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, ((c0 + q) * 64 + lane) * 16, 0, kAuxSc1);
+    }
 #pragma unroll
     for (int q = 0; q < CG; ++q) {
       if (c0 + q < nch) {
@@ -196,18 +213,28 @@ __device__ __forceinline__ void wave_product_bf(const void* xblock, int xblock_b
 // ---------------------------------------------------------------------------
 // forward
 // ---------------------------------------------------------------------------
+// Workgroups form NG = ndir * nb groups: group g runs direction g % ndir for the sequences
+// [(g / ndir) * Bg, + Bg) and exchanges data only among its own members.  Workgroup index =
+// member * NG + g: the dispatcher deals consecutive workgroups out to the 8 XCDs in turn, so with
+// NG = 8 a group sits on one XCD (with NG = 4 on two), whose L2 then serves the group's exchange.
+constexpr int kMaxGroups = 8;
 struct PFwdDir {
   float* zg; const float* R; const float* h0; const float* c0;
   float* y; float* c; float* hT; float* cT;
-  void* hx;             // 2 x [4 wavefronts][nch][64][16 bytes]
-  unsigned* flags;      // [Gf]
+  float* hstate; float* cstate;   // [B,H] each: carried state between launches that split the T steps
   int direction;
 };
 struct PFwdParams {
   PFwdDir d[2];
+  void* hx[kMaxGroups];            // per group: 2 x [4 wavefronts][nch][64][16 bytes]
+  unsigned* flags[kMaxGroups];     // per group: [flag copies][Gf]
+  int ndir, NG, Bg;
   const int32_t* seq_lens;
   unsigned* err;
+  unsigned long long wait_ticks;   // bound of every wait, in 100 MHz wall-clock ticks
+  int mute_wg;                     // test hook: this workgroup withholds its step flags (-1: none)
   int T, B, H, ldy, Gf, Hp, nch;
+  int s_begin, s_end;              // steps [s_begin, s_end) of the T steps are done by this launch
 };
 
 // Workgroup = 4 compute wavefronts (threads 0..255) + 1 I/O wavefront (threads 256..319).
@@ -217,16 +244,28 @@ struct PFwdParams {
 // acknowledgements never sit in the step's dependency chain.
 constexpr int kBlockThreads = 320;
 
-template <int MT, int NT, bool BF>
+// ROWS: sequences a group can hold (8, 16, 32 or 64); 8 uses half of one 16-row MFMA tile.
+template <int ROWS, int NT, bool BF>
 __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwdParams p) {
+  constexpr int MT = ROWS <= 16 ? 1 : ROWS / 16;
+  constexpr bool HALF = ROWS == 8;
   constexpr int U = 4 * NT, NC = 16 * NT;
-  constexpr int NE = MT * 16 * U;                // (sequence, unit) pairs of this workgroup (multiple of 64)
+  constexpr int NE = ROWS * U;                   // (sequence, unit) pairs of this workgroup (multiple of 64)
   constexpr int EPT = (NE + 255) / 256;          // pairs per compute thread
   constexpr int EPL = NE / 64;                   // pairs per I/O lane
+  static_assert(NE % 64 == 0, "pairs must fill whole I/O wavefronts");
   extern __shared__ __align__(16) float lds[];
-  const int dir = blockIdx.x / p.Gf, wg = blockIdx.x % p.Gf;
+  const int grp = blockIdx.x % p.NG, wg = blockIdx.x / p.NG;
+  const int dir = grp % p.ndir, b0 = (grp / p.ndir) * p.Bg;
   const PFwdDir& D = p.d[dir];
-  const int T = p.T, B = p.B, H = p.H, Hp = p.Hp, nch = p.nch;
+  const int T = p.T, H = p.H, Hp = p.Hp, nch = p.nch;
+  const int B = min(p.Bg, p.B - b0);             // sequences of this group (local index 0 .. B-1, global b0 + index)
+  if (B <= 0) return;                            // a group without sequences: all its workgroups leave
+  const int s_begin = p.s_begin, s_end = p.s_end;
+  // an earlier launch of this pass gave up waiting: the exchange arrays are not valid, do nothing
+  if (ld_dev(p.err) != 0u) return;
+  // the step chain is latency-bound: its wavefronts go before those of any kernel sharing the CU
+  __builtin_amdgcn_s_setprio(3);
   const int u0 = wg * U;
   float* Rs = lds;                               // fp32: [Hp][NC]; bf16: [Hp/8][NC][8] (half the size)
   unsigned short* Rsb = reinterpret_cast<unsigned short*>(lds);
@@ -245,13 +284,14 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
     const int g = col / U, u = u0 + col % U;
     const float v = (k < H && u < H) ? D.R[(size_t)k * 4 * H + g * H + u] : 0.f;
     if (BF) Rsb[((size_t)(k >> 3) * NC + col) * 8 + (k & 7)] = bf16_bits(v);
-    else Rs[idx] = v;
+    else Rs[k * NC + rotated_col<NT>(k, col)] = v;
   }
 
   const int KW = Hp / 4;                         // rows of h per wavefront
   const int wbytes = nch * 1024;                 // bytes of one wavefront's operand block (64 lanes x 16 bytes per chunk)
   const size_t hxsz = (size_t)4 * wbytes;        // bytes of one step buffer
-  char* const hxbase = static_cast<char*>(D.hx);
+  char* const hxbase = static_cast<char*>(p.hx[grp]);
+  unsigned* const gflags = p.flags[grp];
 
   // compute threads: carried state of the pairs they own
   float hreg[EPT], creg[EPT];
@@ -264,9 +304,13 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
     ev[e] = !is_io && (j < NE) && eb[e] < B && eu[e] < H;
     hreg[e] = 0.f; creg[e] = 0.f; elen[e] = 0; eslot[e] = 0;
     if (ev[e]) {
-      if (D.h0) hreg[e] = D.h0[(size_t)eb[e] * H + eu[e]];
-      if (D.c0) creg[e] = D.c0[(size_t)eb[e] * H + eu[e]];
-      elen[e] = min(max(p.seq_lens[eb[e]], 0), T);
+      const size_t bu = (size_t)(b0 + eb[e]) * H + eu[e];
+      if (s_begin > 0) { hreg[e] = D.hstate[bu]; creg[e] = D.cstate[bu]; }
+      else {
+        if (D.h0) hreg[e] = D.h0[bu];
+        if (D.c0) creg[e] = D.c0[bu];
+      }
+      elen[e] = min(max(p.seq_lens[b0 + eb[e]], 0), T);
       eslot[e] = BF ? (eu[e] / KW) * (wbytes / 2) + operand_slot_bf<MT>(eu[e] % KW, eb[e])
                     : (eu[e] / KW) * (wbytes / 4) + operand_slot<MT>(eu[e] % KW, eb[e]);
     }
@@ -287,7 +331,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
     for (int i = 0; i < EPL; ++i)
 #pragma unroll
       for (int g = 0; g < 4; ++g)
-        zr[i][g] = iv[i] ? D.zg[((size_t)t * B + ib[i]) * 4 * H + g * H + iu[i]] : 0.f;
+        zr[i][g] = iv[i] ? D.zg[((size_t)t * p.B + b0 + ib[i]) * 4 * H + g * H + iu[i]] : 0.f;
   };
   auto io_stage = [&](int step) {                // registers -> LDS buffer of `step`
     float* dst = zin + (step & 1) * 4 * NE;
@@ -303,7 +347,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
     for (int i = 0; i < EPL; ++i) {
       if (!iv[i]) continue;
       const int j = lane + i * 64;
-      const size_t row = (size_t)t * B + ib[i];
+      const size_t row = (size_t)t * p.B + b0 + ib[i];
       float* zrow = D.zg + row * 4 * H + iu[i];
       zrow[0] = src[0 * NE + j]; zrow[H] = src[1 * NE + j]; zrow[2 * H] = src[2 * NE + j]; zrow[3 * H] = src[3 * NE + j];
       D.y[row * p.ldy + iu[i]] = src[4 * NE + j];
@@ -311,16 +355,18 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
     }
   };
   if (is_io) {
-    io_load(0);
-    io_stage(0);
-    if (T > 1) io_load(1);
+    io_load(s_begin);
+    io_stage(s_begin);
+    if (s_begin + 1 < s_end) io_load(s_begin + 1);
   }
   __syncthreads();
 
   const int prod_first = wave * KW / U, prod_count = KW / U;
-  const unsigned* myflags = D.flags + (wg % kFlagCopies) * kFlagCopyStride;
+  const unsigned* myflags = gflags + (wg % kFlagCopies) * kFlagCopyStride;
 
-  for (int s = 0; s < T; ++s) {
+  // Step s reads the h that step s-1 left in the exchange array, also when step s-1 was the last
+  // step of the previous launch: flags, exchange arrays and tags live in device memory.
+  for (int s = s_begin; s < s_end; ++s) {
     const int t = D.direction > 0 ? s : T - 1 - s;
     const char* hprev = hxbase + (size_t)((s + 1) & 1) * hxsz;
     char* hcur = hxbase + (size_t)(s & 1) * hxsz;
@@ -328,11 +374,11 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
 
     if (!is_io) {
       // h of the previous step: wait for the producers of this wavefront's rows, then h_prev * R
-      if (s > 0 && !wave_wait_flags(myflags, prod_first, prod_count, p.Gf, (unsigned)s, p.err)) fail = 1;
+      if (s > 0 && !wave_wait_flags(myflags, prod_first, prod_count, p.Gf, (unsigned)s, p.err, p.wait_ticks)) fail = 1;
       floatx4 acc[MT][NT];
-      if (BF) wave_product_bf<MT, NT>(hprev + (size_t)wave * wbytes, wbytes, nch, Rsb + (size_t)wave * KW * NC, NC, acc);
-      else wave_product<MT, NT>(reinterpret_cast<const float*>(hprev + (size_t)wave * wbytes), wbytes, nch,
-                                Rs + (size_t)wave * KW * NC, NC, acc);
+      if (BF) wave_product_bf<MT, NT, HALF>(hprev + (size_t)wave * wbytes, wbytes, nch, Rsb + (size_t)wave * KW * NC, acc);
+      else wave_product<MT, NT, HALF>(reinterpret_cast<const float*>(hprev + (size_t)wave * wbytes), wbytes, nch,
+                                      Rs + (size_t)wave * KW * NC, acc);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -341,9 +387,9 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
     } else {
       // stage the next frame's input part (loaded a step ago), write out the previous frame's
       // outputs, start loading the frame after next: every wait here is on work issued a step ago
-      if (s + 1 < T) io_stage(s + 1);
-      if (s > 0) io_store(s - 1);
-      if (s + 2 < T) io_load(s + 2);
+      if (s + 1 < s_end) io_stage(s + 1);
+      if (s > s_begin) io_store(s - 1);
+      if (s + 2 < s_end) io_load(s + 2);
     }
     if (__syncthreads_or(fail)) {
       if (tid == 0) st_dev(p.err, 1u);
@@ -397,17 +443,21 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
       wait_stores_acked();
     }
     __syncthreads();
-    publish_flag(D.flags, wg, (unsigned)(s + 1));
+    if ((int)blockIdx.x != p.mute_wg) publish_flag(gflags, wg, (unsigned)(s + 1));
 
   }
   __syncthreads();
-  if (is_io) io_store(T - 1);
+  if (is_io) io_store(s_end - 1);
 
 #pragma unroll
   for (int e = 0; e < EPT; ++e) {
     if (!ev[e]) continue;
-    if (D.hT) D.hT[(size_t)eb[e] * H + eu[e]] = hreg[e];
-    if (D.cT) D.cT[(size_t)eb[e] * H + eu[e]] = creg[e];
+    const size_t bu = (size_t)(b0 + eb[e]) * H + eu[e];
+    if (s_end < T) { D.hstate[bu] = hreg[e]; D.cstate[bu] = creg[e]; }
+    else {
+      if (D.hT) D.hT[bu] = hreg[e];
+      if (D.cT) D.cT[bu] = creg[e];
+    }
   }
 }
 
@@ -417,33 +467,48 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
 struct PBwdDir {
   float* zg; const float* R; const float* c; const float* c0; const float* dy;
   const float* dhT; const float* dcT; float* dh0; float* dc0; float* db;
-  void* dzx;                    // 2 x [4 quarters][4 wavefronts][nch][64][16 bytes]
-  unsigned long long* part;     // 2 x [PG][4][Bp][UG] (value, tag)
-  unsigned* flags;              // [Gb]
+  float* dhstate; float* dcstate;   // [B,H] each: carried gradients between launches that split the T steps
+  float* dbpart;                    // [nb][4H]: bias gradient of each group of sequences (summed afterwards)
   int direction;
 };
 struct PBwdParams {
   PBwdDir d[2];
+  void* dzx[kMaxGroups];                  // per group: 2 x [4 quarters][4 wavefronts][nch][64][16 bytes]
+  unsigned long long* part[kMaxGroups];   // per group: 2 x [PG][4][Bp][UG] (value, tag)
+  unsigned* flags[kMaxGroups];            // per group: [flag copies][Gb]
+  int ndir, NG, Bg;
   const int32_t* seq_lens;
   unsigned* err;
+  unsigned long long wait_ticks;
+  int mute_wg;
   int T, B, H, ldy, PG, Hq, nch;
+  int s_begin, s_end;
 };
 
 // Same workgroup shape as the forward kernel: 4 compute wavefronts + 1 I/O wavefront that stages
 // the frame's gates, cell states and dy from HBM into LDS one step ahead and writes d a back to
 // HBM one step behind.
-template <int MT, int NT, bool BF>
+template <int ROWS, int NT, bool BF>
 __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwdParams p) {
+  constexpr int MT = ROWS <= 16 ? 1 : ROWS / 16;
+  constexpr bool HALF = ROWS == 8;
   constexpr int U = 4 * NT, UG = 16 * NT, Bp = 16 * MT;
-  constexpr int NE = MT * 16 * U;                // (sequence, unit) pairs owned by this workgroup
+  constexpr int NE = ROWS * U;                   // (sequence, unit) pairs owned by this workgroup
   constexpr int EPT = (NE + 255) / 256;
   constexpr int EPL = NE / 64;
+  static_assert(NE % 64 == 0, "pairs must fill whole I/O wavefronts");
   extern __shared__ __align__(16) float lds[];
   const int Gb = 4 * p.PG;
-  const int dir = blockIdx.x / Gb, wg = blockIdx.x % Gb;
+  const int grp = blockIdx.x % p.NG, wg = blockIdx.x / p.NG;
+  const int dir = grp % p.ndir, bgi = grp / p.ndir, b0 = bgi * p.Bg;
   const int pg = wg >> 2, qq = wg & 3;           // unit group, K quarter (also: which quarter of the group it owns)
   const PBwdDir& D = p.d[dir];
-  const int T = p.T, B = p.B, H = p.H, Hq = p.Hq, nch = p.nch;
+  const int T = p.T, H = p.H, Hq = p.Hq, nch = p.nch;
+  const int B = min(p.Bg, p.B - b0);             // sequences of this group (local index; global b0 + index)
+  if (B <= 0) return;
+  const int s_begin = p.s_begin, s_end = p.s_end;
+  if (ld_dev(p.err) != 0u) return;               // an earlier launch of this pass gave up waiting
+  __builtin_amdgcn_s_setprio(3);                 // latency-bound chain: ahead of any kernel sharing the CU
   const int u0 = wg * U;                         // owned units
   float* RTs = lds;                              // fp32: [4*Hq][UG]; bf16: [4*Hq/8][UG][8] (half the size)
   unsigned short* RTb = reinterpret_cast<unsigned short*>(lds);
@@ -470,12 +535,14 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
     const int un = pg * UG + n;
     const float v = (uk < H && un < H) ? D.R[(size_t)un * 4 * H + g * H + uk] : 0.f;
     if (BF) RTb[((size_t)(r >> 3) * UG + n) * 8 + (r & 7)] = bf16_bits(v);
-    else RTs[idx] = v;
+    else RTs[r * UG + rotated_col<NT>(r, n)] = v;
   }
 
   const int wbytes = nch * 1024;                 // bytes per (quarter, wavefront) operand block
   const size_t xsz = (size_t)16 * wbytes;        // bytes of one step buffer
-  char* const dzbase = static_cast<char*>(D.dzx);
+  char* const dzbase = static_cast<char*>(p.dzx[grp]);
+  unsigned long long* const gpart = p.part[grp];
+  unsigned* const gflags = p.flags[grp];
   const size_t psz = (size_t)p.PG * 4 * Bp * UG;
 
   // compute threads: carried gradients of the pairs they own
@@ -491,9 +558,16 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
 #pragma unroll
     for (int g = 0; g < 4; ++g) dbacc[e][g] = 0.f;
     if (ev[e]) {
-      if (D.dhT) Dh[e] = D.dhT[(size_t)eb[e] * H + eu[e]];
-      if (D.dcT) Dc[e] = D.dcT[(size_t)eb[e] * H + eu[e]];
-      elen[e] = min(max(p.seq_lens[eb[e]], 0), T);
+      const size_t bu = (size_t)(b0 + eb[e]) * H + eu[e];
+      elen[e] = min(max(p.seq_lens[b0 + eb[e]], 0), T);
+      if (s_begin > 0) {
+        Dh[e] = D.dhstate[bu]; Dc[e] = D.dcstate[bu];
+        const int tlast = D.direction > 0 ? T - s_begin : s_begin - 1;   // frame of step s_begin - 1
+        vprev[e] = tlast < elen[e];
+      } else {
+        if (D.dhT) Dh[e] = D.dhT[bu];
+        if (D.dcT) Dc[e] = D.dcT[bu];
+      }
       // d a of unit u, gate g sits in quarter u/Hq, wavefront (u%Hq)/UW, row ((u%Hq)%UW)*4 + g
       const int ul = eu[e] % Hq;
       eslot[e] = BF ? ((eu[e] / Hq) * 4 + ul / UW) * (wbytes / 2) + operand_slot_bf<MT>((ul % UW) * 4, eb[e])
@@ -522,11 +596,11 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
 #pragma unroll
     for (int i = 0; i < EPL; ++i) {
       if (!iv[i]) continue;
-      const size_t row = (size_t)t * B + ib[i];
+      const size_t row = (size_t)t * p.B + b0 + ib[i];
       const float* zrow = D.zg + row * 4 * H + iu[i];
       lr[i][0] = zrow[0]; lr[i][1] = zrow[H]; lr[i][2] = zrow[2 * H]; lr[i][3] = zrow[3 * H];
-      if (tprev >= 0 && tprev < T) lr[i][4] = D.c[((size_t)tprev * B + ib[i]) * H + iu[i]];
-      else lr[i][4] = D.c0 ? D.c0[(size_t)ib[i] * H + iu[i]] : 0.f;
+      if (tprev >= 0 && tprev < T) lr[i][4] = D.c[((size_t)tprev * p.B + b0 + ib[i]) * H + iu[i]];
+      else lr[i][4] = D.c0 ? D.c0[(size_t)(b0 + ib[i]) * H + iu[i]] : 0.f;
       lr[i][5] = D.dy[row * p.ldy + iu[i]];
     }
   };
@@ -550,29 +624,29 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
     for (int i = 0; i < EPL; ++i) {
       if (!iv[i]) continue;
       const int j = lane + i * 64;
-      float* zrow = D.zg + ((size_t)t * B + ib[i]) * 4 * H + iu[i];
+      float* zrow = D.zg + ((size_t)t * p.B + b0 + ib[i]) * 4 * H + iu[i];
       zrow[0] = src[0 * NE + j]; zrow[H] = src[1 * NE + j]; zrow[2 * H] = src[2 * NE + j]; zrow[3 * H] = src[3 * NE + j];
     }
   };
   if (is_io) {
-    const int t0 = frame_of(0);
+    const int t0 = frame_of(s_begin);
 #pragma unroll
     for (int i = 0; i < EPL; ++i)
-      if (iv[i]) cnext[i] = D.c[((size_t)t0 * B + ib[i]) * H + iu[i]];
-    io_load(0);
-    io_stage(0);
-    if (T > 1) io_load(1);
+      if (iv[i]) cnext[i] = D.c[((size_t)t0 * p.B + b0 + ib[i]) * H + iu[i]];
+    io_load(s_begin);
+    io_stage(s_begin);
+    if (s_begin + 1 < s_end) io_load(s_begin + 1);
   }
   __syncthreads();
 
   // producers of this wavefront's rows: owners of units [qq*Hq + wave*UW, +UW)
   const int prod_first = (qq * Hq + wave * UW) / U, prod_count = UW / U;
-  const unsigned* myflags = D.flags + (wg % kFlagCopies) * kFlagCopyStride;
+  const unsigned* myflags = gflags + (wg % kFlagCopies) * kFlagCopyStride;
 
   // sums the partial tiles of step `step` for the owned pairs (tag = step + 1)
   auto collect = [&](int step, float (&out)[EPT]) -> int {
     int fail = 0;
-    const unsigned long long* pbuf = D.part + (size_t)(step & 1) * psz;
+    const unsigned long long* pbuf = gpart + (size_t)(step & 1) * psz;
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
       out[e] = 0.f;
@@ -580,7 +654,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
       const int n = qq * U + (eu[e] - u0);
       const unsigned long long* src = pbuf + ((size_t)(pg * 4) * Bp + eb[e]) * UG + n;
       unsigned long long v[4];
-      Spin sp;
+      Spin sp(p.wait_ticks);
       for (;;) {
         bool ok = true;
 #pragma unroll
@@ -602,7 +676,9 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
     return fail;
   };
 
-  for (int s = 0; s < T; ++s) {
+  // Step s sums the partial tiles of step s-1, also when step s-1 was the last step of the
+  // previous launch: flags, exchange arrays and tagged tiles live in device memory.
+  for (int s = s_begin; s < s_end; ++s) {
     const int t = frame_of(s);
     char* dzcur = dzbase + (size_t)(s & 1) * xsz;
     int fail = 0;
@@ -657,24 +733,24 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
     } else {
       // stage the next frame's inputs (loaded a step ago), write out the previous frame's d a,
       // start loading the frame after next: every wait here is on work issued a step ago
-      if (s + 1 < T) io_stage(s + 1);
-      if (s > 0) io_store(s - 1);
-      if (s + 2 < T) io_load(s + 2);
+      if (s + 1 < s_end) io_stage(s + 1);
+      if (s > s_begin) io_store(s - 1);
+      if (s + 2 < s_end) io_load(s + 2);
     }
     if (__syncthreads_or(fail)) {
       if (tid == 0) st_dev(p.err, 1u);
       return;
     }
-    publish_flag(D.flags, wg, (unsigned)(s + 1));
+    if ((int)blockIdx.x != p.mute_wg) publish_flag(gflags, wg, (unsigned)(s + 1));
 
     // this workgroup's quarter of d a_t R^T for its unit group
     fail = 0;
     if (!is_io && qq < nq) {
-      if (!wave_wait_flags(myflags, prod_first, prod_count, Gb, (unsigned)(s + 1), p.err)) fail = 1;
+      if (!wave_wait_flags(myflags, prod_first, prod_count, Gb, (unsigned)(s + 1), p.err, p.wait_ticks)) fail = 1;
       floatx4 acc[MT][NT];
-      if (BF) wave_product_bf<MT, NT>(dzcur + (size_t)(qq * 4 + wave) * wbytes, wbytes, nch, RTb + (size_t)wave * Hq * UG, UG, acc);
-      else wave_product<MT, NT>(reinterpret_cast<const float*>(dzcur + (size_t)(qq * 4 + wave) * wbytes), wbytes, nch,
-                                RTs + (size_t)wave * Hq * UG, UG, acc);
+      if (BF) wave_product_bf<MT, NT, HALF>(dzcur + (size_t)(qq * 4 + wave) * wbytes, wbytes, nch, RTb + (size_t)wave * Hq * UG, acc);
+      else wave_product<MT, NT, HALF>(reinterpret_cast<const float*>(dzcur + (size_t)(qq * 4 + wave) * wbytes), wbytes, nch,
+                                      RTs + (size_t)wave * Hq * UG, acc);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -687,13 +763,14 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
     }
     // sum the four wavefronts' tiles in order and hand (value, tag) to the owners
     if (!is_io && qq < nq) {
-      unsigned long long* pbuf = D.part + (size_t)(s & 1) * psz + (size_t)(pg * 4 + qq) * Bp * UG;
+      unsigned long long* pbuf = gpart + (size_t)(s & 1) * psz + (size_t)(pg * 4 + qq) * Bp * UG;
       const int ln = tid >> 2, reg = tid & 3;
       const int row = 4 * (ln >> 4) + reg, col = ln & 15;
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
+          if (HALF && row >= 8) continue;          // rows that hold no sequence: nobody reads them
           float sum = 0.f;
 #pragma unroll
           for (int w = 0; w < 4; ++w) sum += Red[((w * MT + mt) * NT + nt) * 256 + tid];
@@ -708,8 +785,8 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
   // last frame's d a, gradient w.r.t. the initial state, bias gradient of the owned columns
   int fail = 0;
   if (is_io) {
-    io_store(T - 1);
-  } else {
+    io_store(s_end - 1);
+  } else if (s_end == T) {
     float g[EPT];
     fail = collect(T - 1, g);
 #pragma unroll
@@ -729,108 +806,165 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
       for (int g = 0; g < 4; ++g) stage[b * 4 * U + g * U + uu] = ev[e] ? dbacc[e][g] : 0.f;
     }
     if (!ev[e]) continue;
-    if (D.dh0) D.dh0[(size_t)eb[e] * H + eu[e]] = Dh[e];
-    if (D.dc0) D.dc0[(size_t)eb[e] * H + eu[e]] = Dc[e];
+    const size_t bu = (size_t)(b0 + eb[e]) * H + eu[e];
+    if (s_end < T) { D.dhstate[bu] = Dh[e]; D.dcstate[bu] = Dc[e]; }
+    else {
+      if (D.dh0) D.dh0[bu] = Dh[e];
+      if (D.dc0) D.dc0[bu] = Dc[e];
+    }
   }
   __syncthreads();
   if (tid < 4 * U) {
     const int g = tid / U, u = u0 + tid % U;
     if (u < H) {
+      // launches that split the T steps add their share in launch order; with several groups of
+      // sequences each group keeps its own sum (added up in group order by a kernel that follows)
       float sum = 0.f;
       for (int b = 0; b < B; ++b) sum += stage[b * 4 * U + tid];
-      D.db[g * H + u] = sum;
+      float* dst = (p.NG > p.ndir ? D.dbpart + (size_t)bgi * 4 * H : D.db) + g * H + u;
+      *dst = s_begin > 0 ? *dst + sum : sum;
     }
   }
 }
 
 // ---------------------------------------------------------------------------
-// set-up kernel: clears flags, exchange arrays and tags; seeds h0 in operand order
+// set-up kernels: clear flags, exchange arrays and tags; seed h0 in operand order;
+// add up the bias gradients of the groups of sequences
 // ---------------------------------------------------------------------------
 struct PrepParams {
-  unsigned* zero_words[2]; size_t nzero[2];       // per direction: words to clear (flags + exchange [+ partial tiles])
-  void* hx1[2]; const float* h0[2];               // forward only: buffer 1 of the h exchange, h0 or null
-  int ndir, B, H, KW, wbytes, MT, bf;
+  unsigned* zero_words; size_t nzero;             // flags + exchange (+ partial tiles) of all groups
+  void* hx1[kMaxGroups]; const float* h0[2];      // forward only: buffer 1 of each group's h exchange, h0 or null
+  int ndir, B, Bg, H, KW, wbytes, MT, bf;
 };
 __global__ __launch_bounds__(256) void prep_kernel(PrepParams p) {
   const size_t gtid = (size_t)blockIdx.x * 256 + threadIdx.x, gsz = (size_t)gridDim.x * 256;
-  for (int d = 0; d < p.ndir; ++d) {
-    for (size_t i = gtid; i < p.nzero[d]; i += gsz) p.zero_words[d][i] = 0u;
-  }
-  // h0 lands in words this same thread grid has just cleared; order the two phases per thread
-  // by letting each thread write only h0 elements, after all clears, in a second kernel launch.
+  for (size_t i = gtid; i < p.nzero; i += gsz) p.zero_words[i] = 0u;
 }
+// runs after prep_kernel (same stream): h0 lands in words that kernel has cleared
 __global__ __launch_bounds__(256) void seed_h0_kernel(PrepParams p) {
   const size_t gtid = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (gtid >= (size_t)p.B * p.H) return;
-  const int b = (int)(gtid / p.H), u = (int)(gtid % p.H);
+  const int bglob = (int)(gtid / p.H), u = (int)(gtid % p.H);
+  const int bgi = bglob / p.Bg, b = bglob % p.Bg;      // group of sequences, index inside it
   for (int d = 0; d < p.ndir; ++d) {
     if (!p.h0[d]) continue;
+    void* hx1 = p.hx1[bgi * p.ndir + d];
     const int k = u % p.KW;
     int slot;
     if (p.bf) {
       if (p.MT == 1) slot = operand_slot_bf<1>(k, b);
       else if (p.MT == 2) slot = operand_slot_bf<2>(k, b);
       else slot = operand_slot_bf<4>(k, b);
-      static_cast<unsigned short*>(p.hx1[d])[(size_t)(u / p.KW) * (p.wbytes / 2) + slot] = bf16_bits(p.h0[d][gtid]);
+      static_cast<unsigned short*>(hx1)[(size_t)(u / p.KW) * (p.wbytes / 2) + slot] = bf16_bits(p.h0[d][gtid]);
     } else {
       if (p.MT == 1) slot = operand_slot<1>(k, b);
       else if (p.MT == 2) slot = operand_slot<2>(k, b);
       else slot = operand_slot<4>(k, b);
-      static_cast<float*>(p.hx1[d])[(size_t)(u / p.KW) * (p.wbytes / 4) + slot] = p.h0[d][gtid];
+      static_cast<float*>(hx1)[(size_t)(u / p.KW) * (p.wbytes / 4) + slot] = p.h0[d][gtid];
     }
+  }
+}
+struct DbSumParams { float* db[2]; const float* dbpart[2]; int ndir, nb, n; };
+__global__ __launch_bounds__(256) void db_sum_kernel(DbSumParams p) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= p.n) return;
+  for (int d = 0; d < p.ndir; ++d) {
+    float sum = 0.f;
+    for (int g = 0; g < p.nb; ++g) sum += p.dbpart[d][(size_t)g * p.n + i];
+    p.db[d][i] = sum;
   }
 }
 
 // ---- host side ----------------------------------------------------------------
+unsigned long long g_wait_ticks = kDefaultWaitTicks;
+int g_mute_wg = -1;
+int g_batch_groups = 0;                          // 0: chosen by make_plan
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 constexpr size_t kFlagBytes = (size_t)kFlagCopies * kFlagCopyStride * sizeof(unsigned);
 
 struct Plan {
   bool ok;
-  int MT, NT, U, UG, Bp, bf;
+  int ROWS, MT, NT, U, UG, Bp, bf;
+  int nb, Bg, NG;                                // groups of sequences per direction, sequences per group, all groups
   int Gf, Hp, nchF;
   int PG, Gb, Hq, nchB;
   size_t ldsF, ldsB;
 };
 
-Plan make_plan(const RecShape& s, int num_cus, size_t max_lds) {
+// kernels exist for these (ROWS, NT)
+inline bool have_kernel(int rows, int nt) {
+  if (nt == 1) return rows >= 16;
+  if (nt == 2) return true;
+  return rows <= 16;                             // nt == 4
+}
+
+// One plan for a given number nb of groups of sequences per direction, or !ok.
+Plan plan_for(const RecShape& s, int num_cus, size_t max_lds, int nb) {
   Plan pl{};
   pl.ok = false;
-  if (s.operand_dtype != 0 && s.operand_dtype != 1) return pl;
-  if (s.B < 1 || s.B > 64 || s.H < 1) return pl;
   const int bf = s.operand_dtype == 1 ? 1 : 0;
   const size_t es = bf ? 2 : 4;                  // bytes per element of the resident matrix and the exchanged rows
-  pl.bf = bf;
-  pl.MT = s.B <= 16 ? 1 : (s.B <= 32 ? 2 : 4);
-  pl.Bp = pl.MT * 16;
-  const int per_dir = num_cus / s.ndir;
-  for (int NT = 1; NT <= 2; ++NT) {
+  const int NG = s.ndir * nb;
+  if (NG > kMaxGroups || nb > s.B) return pl;
+  const int Bg = (s.B + nb - 1) / nb;
+  if (Bg > 64) return pl;
+  const int per_group = num_cus / NG;
+  for (int NT = 1; NT <= 4; NT *= 2) {
+    const int rows = Bg <= 8 && have_kernel(8, NT) ? 8 : (Bg <= 16 ? 16 : (Bg <= 32 ? 32 : 64));
+    if (!have_kernel(rows, NT)) continue;
+    const int MT = rows <= 16 ? 1 : rows / 16;
     const int U = 4 * NT, UG = 16 * NT;
     const int Gf = (s.H + U - 1) / U;
     const int PG = (s.H + UG - 1) / UG;
     const int Gb = 4 * PG;
-    if (Gf > per_dir || Gb > per_dir) continue;
+    if (Gf > per_group || Gb > per_group) continue;
     const int Hp = (int)align_up((size_t)s.H, bf ? 128 : 64);   // rows of h per wavefront: whole MFMA k-steps
     const int Hq = (int)align_up((size_t)PG * U, 32);
     // a wavefront polls at most 64 producers
     if (Hp / 4 / U > 64 || Hq / 4 / U > 64) continue;
-    const size_t red = (size_t)4 * pl.MT * NT * 256;
-    const size_t lf = (size_t)Hp * 16 * NT * es + (red + (size_t)(2 * 4 + 2 * 6) * pl.MT * 16 * U) * sizeof(float);
-    const size_t lb = (size_t)4 * Hq * UG * es + (red + (size_t)(2 * 7 + 2 * 4) * pl.MT * 16 * U) * sizeof(float);
+    const size_t red = (size_t)4 * MT * NT * 256;
+    const size_t ne = (size_t)rows * U;
+    const size_t lf = (size_t)Hp * 16 * NT * es + (red + (2 * 4 + 2 * 6) * ne) * sizeof(float);
+    const size_t lb = (size_t)4 * Hq * UG * es + (red + (2 * 7 + 2 * 4) * ne) * sizeof(float);
     if (lf > max_lds || lb > max_lds) continue;
     // One workgroup per CU: request more than half of the CU's LDS so that the dispatcher cannot
     // stack two of these workgroups on one CU (they would share its matrix cores and every other
     // workgroup would wait for them each step).
     const size_t exclusive = max_lds / 2 + 1024;
-    const size_t lf_req = lf > exclusive ? lf : exclusive, lb_req = lb > exclusive ? lb : exclusive;
-    pl.ok = true; pl.NT = NT; pl.U = U; pl.UG = UG;
+    pl.ok = true; pl.ROWS = rows; pl.MT = MT; pl.NT = NT; pl.U = U; pl.UG = UG; pl.Bp = 16 * MT; pl.bf = bf;
+    pl.nb = nb; pl.Bg = Bg; pl.NG = NG;
     // 16-byte chunks per lane and wavefront: fp32 4 values (4 k-steps x batch tiles / 4), bf16 8 values (1 k-step of 32)
-    pl.Gf = Gf; pl.Hp = Hp; pl.nchF = bf ? (Hp / 4 / 32) * pl.MT : (Hp / 16) * pl.MT / 4;
-    pl.PG = PG; pl.Gb = Gb; pl.Hq = Hq; pl.nchB = bf ? (Hq / 32) * pl.MT : (Hq / 4) * pl.MT / 4;
-    pl.ldsF = lf_req; pl.ldsB = lb_req;
+    pl.Gf = Gf; pl.Hp = Hp; pl.nchF = bf ? (Hp / 4 / 32) * MT : (Hp / 16) * MT / 4;
+    pl.PG = PG; pl.Gb = Gb; pl.Hq = Hq; pl.nchB = bf ? (Hq / 32) * MT : (Hq / 4) * MT / 4;
+    pl.ldsF = lf > exclusive ? lf : exclusive; pl.ldsB = lb > exclusive ? lb : exclusive;
     return pl;
   }
   return pl;
+}
+
+// The sequences of a minibatch are independent, so they can be dealt out to nb groups of
+// workgroups per direction, each group holding its own copy of the recurrent matrix (spread over
+// fewer, larger slices) and exchanging h_t / d a_t only among its own members.  Smaller groups
+// exchange faster (fewer producers to wait for, fewer bytes per consumer); in return each
+// workgroup multiplies a larger slice, and below 16 sequences per group the 16-row MFMA tiles
+// are partly empty.  Preferred: the largest nb that leaves at least 16 sequences per group.
+Plan make_plan(const RecShape& s, int num_cus, size_t max_lds) {
+  Plan none{};
+  none.ok = false;
+  if (s.operand_dtype != 0 && s.operand_dtype != 1) return none;
+  if (s.B < 1 || s.H < 1 || s.ndir < 1 || s.ndir > 2) return none;
+  if (g_batch_groups > 0) return plan_for(s, num_cus, max_lds, g_batch_groups);
+  int first = 1;
+  while (first * 2 * s.ndir <= kMaxGroups && (s.B + first * 2 - 1) / (first * 2) >= 16) first *= 2;
+  for (int nb = first; nb >= 1; nb /= 2) {
+    const Plan pl = plan_for(s, num_cus, max_lds, nb);
+    if (pl.ok) return pl;
+  }
+  for (int nb = first * 2; nb * s.ndir <= kMaxGroups; nb *= 2) {   // more sequences than one group can hold
+    const Plan pl = plan_for(s, num_cus, max_lds, nb);
+    if (pl.ok) return pl;
+  }
+  return none;
 }
 
 // Launches a kernel whose workgroups wait on each other.  All of them must be resident at
@@ -854,72 +988,114 @@ hipError_t resident_launch(K kernel, int grid, int block, size_t lds, int num_cu
   return hipLaunchKernel(fn, dim3((unsigned)grid), dim3((unsigned)block), args, lds, stream);
 }
 
+// Scratch layout (bytes), independent of the device: per group [flag copies][exchange arrays]
+// [partial tiles], then per direction [2 state arrays][per-group bias gradients].  Sized for the
+// worst case over the numbers of groups a plan may choose.
+struct GroupBytes { size_t exch, part, total; };
+GroupBytes group_bytes(const RecShape& s, int nb) {
+  const size_t Bg = ((size_t)s.B + nb - 1) / nb;
+  const size_t Bp = Bg <= 16 ? 16 : (Bg <= 32 ? 32 : 64);
+  const size_t Hp = align_up((size_t)s.H, 128);
+  const size_t Hq = align_up((size_t)s.H / 4 + 16, 32);
+  GroupBytes g;
+  g.exch = align_up(2 * (Hp > 16 * Hq ? Hp : 16 * Hq) * Bp * sizeof(float), 256);
+  g.part = align_up(2 * 4 * Bp * ((size_t)s.H + 64) * sizeof(unsigned long long), 256);
+  g.total = kFlagBytes + g.exch + g.part;
+  return g;
+}
+size_t groups_bytes_max(const RecShape& s) {
+  size_t m = 0;
+  for (int nb = 1; nb * s.ndir <= kMaxGroups; nb *= 2) {
+    const size_t v = (size_t)nb * s.ndir * group_bytes(s, nb).total;
+    if (v > m) m = v;
+  }
+  return m;
+}
+size_t state_bytes(const RecShape& s) { return align_up((size_t)s.B * s.H * sizeof(float), 256); }
+size_t dbpart_bytes(const RecShape& s) { return align_up((size_t)kMaxGroups * 4 * s.H * sizeof(float), 256); }
+// per-direction arrays behind the groups: which = 0, 1 state arrays, 2 per-group bias gradients
+float* dir_array(char* scratch, const RecShape& s, int d, int which) {
+  char* base = scratch + groups_bytes_max(s) + (size_t)d * (2 * state_bytes(s) + dbpart_bytes(s));
+  return reinterpret_cast<float*>(base + (size_t)which * state_bytes(s));
+}
+
 }  // namespace
+
+void persistent_test_hook(int mute_workgroup, unsigned long long wait_ticks) {
+  g_mute_wg = mute_workgroup;
+  g_wait_ticks = wait_ticks ? wait_ticks : kDefaultWaitTicks;
+}
+void persistent_set_batch_groups(int nb) { g_batch_groups = nb; }
 
 bool persistent_supported(const RecShape& s, int num_cus, size_t max_lds) {
   return make_plan(s, num_cus, max_lds).ok;
 }
 
-// Upper bound (independent of the device) of the per-direction scratch, in bytes:
-// [flag copies][exchange arrays][partial tiles].
-size_t persistent_scratch_bytes_per_dir(const RecShape& s) {
-  const size_t Bp = s.B <= 16 ? 16 : (s.B <= 32 ? 32 : 64);
-  const size_t Hp = align_up((size_t)s.H, 128);
-  const size_t Hq = align_up((size_t)s.H / 4 + 8, 32);
-  const size_t exch = 2 * (Hp > 16 * Hq ? Hp : 16 * Hq) * Bp * sizeof(float);
-  const size_t part = 2 * 4 * Bp * ((size_t)s.H + 32) * sizeof(unsigned long long);
-  return kFlagBytes + align_up(exch, 256) + align_up(part, 256);
+size_t persistent_scratch_bytes(const RecShape& s) {
+  return groups_bytes_max(s) + (size_t)s.ndir * (2 * state_bytes(s) + dbpart_bytes(s));
 }
 
 hipError_t persistent_forward(hipStream_t stream, const RecShape& s, const RecFwdDir* dirs, const int32_t* seq_lens,
-                              char* const* scratch, unsigned* err, int* resident_err) {
+                              char* scratch, unsigned* err, int* resident_err, int s_begin, int s_end) {
+  if (s_begin < 0 || s_end > s.T || s_begin >= s_end) return hipErrorInvalidValue;
   DeviceInfo di;
   hipError_t e = device_info(&di);
   if (e != hipSuccess) return e;
   const Plan pl = make_plan(s, di.num_cus, di.max_lds);
   if (!pl.ok) { *resident_err = 1; return hipErrorInvalidValue; }
   const size_t wbytes = (size_t)pl.nchF * 1024;
+  const GroupBytes gb = group_bytes(s, pl.nb);
+  if (2 * 4 * wbytes > gb.exch) return hipErrorInvalidValue;
   PrepParams pp{};
   PFwdParams kp{};
+  for (int g = 0; g < pl.NG; ++g) {
+    char* base = scratch + (size_t)g * gb.total;
+    kp.flags[g] = reinterpret_cast<unsigned*>(base);
+    kp.hx[g] = base + kFlagBytes;
+    pp.hx1[g] = base + kFlagBytes + 4 * wbytes;
+  }
   for (int d = 0; d < s.ndir; ++d) {
-    unsigned* flags = reinterpret_cast<unsigned*>(scratch[d]);
-    char* hx = scratch[d] + kFlagBytes;
-    pp.zero_words[d] = flags;
-    pp.nzero[d] = kFlagBytes / 4 + 2 * 4 * wbytes / 4;
-    pp.hx1[d] = hx + 4 * wbytes;
     pp.h0[d] = dirs[d].h0;
     PFwdDir& k = kp.d[d];
     k.zg = dirs[d].zg; k.R = dirs[d].R; k.h0 = dirs[d].h0; k.c0 = dirs[d].c0;
     k.y = dirs[d].y; k.c = dirs[d].c; k.hT = dirs[d].hT; k.cT = dirs[d].cT;
-    k.hx = hx; k.flags = flags; k.direction = dirs[d].direction;
+    k.hstate = dir_array(scratch, s, d, 0); k.cstate = dir_array(scratch, s, d, 1);
+    k.direction = dirs[d].direction;
   }
-  pp.ndir = s.ndir; pp.B = s.B; pp.H = s.H; pp.KW = pl.Hp / 4; pp.wbytes = (int)wbytes; pp.MT = pl.MT; pp.bf = pl.bf;
-  kp.seq_lens = seq_lens; kp.err = err;
+  pp.zero_words = reinterpret_cast<unsigned*>(scratch); pp.nzero = (size_t)pl.NG * gb.total / 4;
+  pp.ndir = s.ndir; pp.B = s.B; pp.Bg = pl.Bg; pp.H = s.H; pp.KW = pl.Hp / 4; pp.wbytes = (int)wbytes; pp.MT = pl.MT; pp.bf = pl.bf;
+  kp.ndir = s.ndir; kp.NG = pl.NG; kp.Bg = pl.Bg;
+  kp.seq_lens = seq_lens; kp.err = err; kp.wait_ticks = g_wait_ticks; kp.mute_wg = g_mute_wg;
   kp.T = s.T; kp.B = s.B; kp.H = s.H; kp.ldy = s.ldy; kp.Gf = pl.Gf; kp.Hp = pl.Hp; kp.nch = pl.nchF;
-  hipLaunchKernelGGL(prep_kernel, dim3(64), dim3(256), 0, stream, pp);
-  if (pp.h0[0] || (s.ndir > 1 && pp.h0[1])) {
-    const size_t bh = (size_t)s.B * s.H;
-    hipLaunchKernelGGL(seed_h0_kernel, dim3((unsigned)((bh + 255) / 256)), dim3(256), 0, stream, pp);
+  kp.s_begin = s_begin; kp.s_end = s_end;
+  if (s_begin == 0) {
+    hipLaunchKernelGGL(prep_kernel, dim3(256), dim3(256), 0, stream, pp);
+    if (pp.h0[0] || (s.ndir > 1 && pp.h0[1])) {
+      const size_t bh = (size_t)s.B * s.H;
+      hipLaunchKernelGGL(seed_h0_kernel, dim3((unsigned)((bh + 255) / 256)), dim3(256), 0, stream, pp);
+    }
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const int grid = pl.Gf * s.ndir;
-#define RLSTM_FWD_CASE(MT_, NT_)                                                                        \
-  if (pl.MT == MT_ && pl.NT == NT_) {                                                                   \
-    if (pl.bf)                                                                                          \
-      return resident_launch(lstm_fwd_persistent_kernel<MT_, NT_, true>, grid, kBlockThreads, pl.ldsF,  \
-                             di.num_cus, stream, &kp, resident_err);                                    \
-    return resident_launch(lstm_fwd_persistent_kernel<MT_, NT_, false>, grid, kBlockThreads, pl.ldsF,   \
-                           di.num_cus, stream, &kp, resident_err);                                      \
+  const int grid = pl.Gf * pl.NG;
+#define RLSTM_FWD_CASE(ROWS_, NT_)                                                                       \
+  if (pl.ROWS == ROWS_ && pl.NT == NT_) {                                                                \
+    if (pl.bf)                                                                                           \
+      return resident_launch(lstm_fwd_persistent_kernel<ROWS_, NT_, true>, grid, kBlockThreads, pl.ldsF, \
+                             di.num_cus, stream, &kp, resident_err);                                     \
+    return resident_launch(lstm_fwd_persistent_kernel<ROWS_, NT_, false>, grid, kBlockThreads, pl.ldsF,  \
+                           di.num_cus, stream, &kp, resident_err);                                       \
   }
-  RLSTM_FWD_CASE(1, 1) RLSTM_FWD_CASE(2, 1) RLSTM_FWD_CASE(4, 1)
-  RLSTM_FWD_CASE(1, 2) RLSTM_FWD_CASE(2, 2) RLSTM_FWD_CASE(4, 2)
+  RLSTM_FWD_CASE(16, 1) RLSTM_FWD_CASE(32, 1) RLSTM_FWD_CASE(64, 1)
+  RLSTM_FWD_CASE(8, 2) RLSTM_FWD_CASE(16, 2) RLSTM_FWD_CASE(32, 2) RLSTM_FWD_CASE(64, 2)
+  RLSTM_FWD_CASE(8, 4) RLSTM_FWD_CASE(16, 4)
 #undef RLSTM_FWD_CASE
   return hipErrorInvalidValue;
 }
 
 hipError_t persistent_backward(hipStream_t stream, const RecShape& s, const RecBwdDir* dirs, const int32_t* seq_lens,
-                               char* const* scratch, unsigned* err, int* resident_err) {
+                               char* scratch, unsigned* err, int* resident_err, int s_begin, int s_end) {
+  if (s_begin < 0 || s_end > s.T || s_begin >= s_end) return hipErrorInvalidValue;
   DeviceInfo di;
   hipError_t e = device_info(&di);
   if (e != hipSuccess) return e;
@@ -928,38 +1104,58 @@ hipError_t persistent_backward(hipStream_t stream, const RecShape& s, const RecB
   const size_t wbytes = (size_t)pl.nchB * 1024;
   const size_t exch_bytes = 2 * 16 * wbytes;
   const size_t part_words = (size_t)2 * pl.PG * 4 * pl.Bp * pl.UG;
+  const GroupBytes gb = group_bytes(s, pl.nb);
+  if (exch_bytes > gb.exch || part_words * sizeof(unsigned long long) > gb.part) return hipErrorInvalidValue;
   PrepParams pp{};
   PBwdParams kp{};
+  for (int g = 0; g < pl.NG; ++g) {
+    char* base = scratch + (size_t)g * gb.total;
+    kp.flags[g] = reinterpret_cast<unsigned*>(base);
+    kp.dzx[g] = base + kFlagBytes;
+    kp.part[g] = reinterpret_cast<unsigned long long*>(base + kFlagBytes + gb.exch);
+  }
+  DbSumParams ds{};
   for (int d = 0; d < s.ndir; ++d) {
-    unsigned* flags = reinterpret_cast<unsigned*>(scratch[d]);
-    char* dzx = scratch[d] + kFlagBytes;
-    unsigned long long* part = reinterpret_cast<unsigned long long*>(dzx + align_up(exch_bytes, 256));
-    pp.zero_words[d] = flags;
-    pp.nzero[d] = kFlagBytes / 4 + align_up(exch_bytes, 256) / 4 + 2 * part_words;
     PBwdDir& k = kp.d[d];
     k.zg = dirs[d].zg; k.R = dirs[d].R; k.c = dirs[d].c; k.c0 = dirs[d].c0; k.dy = dirs[d].dy;
     k.dhT = dirs[d].dhT; k.dcT = dirs[d].dcT; k.dh0 = dirs[d].dh0; k.dc0 = dirs[d].dc0; k.db = dirs[d].db;
-    k.dzx = dzx; k.part = part; k.flags = flags; k.direction = dirs[d].direction;
+    k.dhstate = dir_array(scratch, s, d, 0); k.dcstate = dir_array(scratch, s, d, 1);
+    k.dbpart = dir_array(scratch, s, d, 2);
+    k.direction = dirs[d].direction;
+    ds.db[d] = dirs[d].db; ds.dbpart[d] = k.dbpart;
   }
+  pp.zero_words = reinterpret_cast<unsigned*>(scratch); pp.nzero = (size_t)pl.NG * gb.total / 4;
   pp.ndir = s.ndir;
-  kp.seq_lens = seq_lens; kp.err = err;
+  kp.ndir = s.ndir; kp.NG = pl.NG; kp.Bg = pl.Bg;
+  kp.seq_lens = seq_lens; kp.err = err; kp.wait_ticks = g_wait_ticks; kp.mute_wg = g_mute_wg;
   kp.T = s.T; kp.B = s.B; kp.H = s.H; kp.ldy = s.ldy; kp.PG = pl.PG; kp.Hq = pl.Hq; kp.nch = pl.nchB;
-  hipLaunchKernelGGL(prep_kernel, dim3(128), dim3(256), 0, stream, pp);
+  kp.s_begin = s_begin; kp.s_end = s_end;
+  if (s_begin == 0) hipLaunchKernelGGL(prep_kernel, dim3(256), dim3(256), 0, stream, pp);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const int grid = pl.Gb * s.ndir;
-#define RLSTM_BWD_CASE(MT_, NT_)                                                                        \
-  if (pl.MT == MT_ && pl.NT == NT_) {                                                                   \
-    if (pl.bf)                                                                                          \
-      return resident_launch(lstm_bwd_persistent_kernel<MT_, NT_, true>, grid, kBlockThreads, pl.ldsB,  \
-                             di.num_cus, stream, &kp, resident_err);                                    \
-    return resident_launch(lstm_bwd_persistent_kernel<MT_, NT_, false>, grid, kBlockThreads, pl.ldsB,   \
-                           di.num_cus, stream, &kp, resident_err);                                      \
+  const int grid = pl.Gb * pl.NG;
+  e = hipErrorInvalidValue;
+#define RLSTM_BWD_CASE(ROWS_, NT_)                                                                       \
+  if (pl.ROWS == ROWS_ && pl.NT == NT_) {                                                                \
+    if (pl.bf)                                                                                           \
+      e = resident_launch(lstm_bwd_persistent_kernel<ROWS_, NT_, true>, grid, kBlockThreads, pl.ldsB,    \
+                          di.num_cus, stream, &kp, resident_err);                                        \
+    else                                                                                                 \
+      e = resident_launch(lstm_bwd_persistent_kernel<ROWS_, NT_, false>, grid, kBlockThreads, pl.ldsB,   \
+                          di.num_cus, stream, &kp, resident_err);                                        \
   }
-  RLSTM_BWD_CASE(1, 1) RLSTM_BWD_CASE(2, 1) RLSTM_BWD_CASE(4, 1)
-  RLSTM_BWD_CASE(1, 2) RLSTM_BWD_CASE(2, 2) RLSTM_BWD_CASE(4, 2)
+  RLSTM_BWD_CASE(16, 1) RLSTM_BWD_CASE(32, 1) RLSTM_BWD_CASE(64, 1)
+  RLSTM_BWD_CASE(8, 2) RLSTM_BWD_CASE(16, 2) RLSTM_BWD_CASE(32, 2) RLSTM_BWD_CASE(64, 2)
+  RLSTM_BWD_CASE(8, 4) RLSTM_BWD_CASE(16, 4)
 #undef RLSTM_BWD_CASE
-  return hipErrorInvalidValue;
+  if (e != hipSuccess) return e;
+  if (pl.nb > 1 && s_end == s.T) {
+    // the groups of sequences that exist: group g holds sequences [g*Bg, ...)
+    ds.ndir = s.ndir; ds.nb = (s.B + pl.Bg - 1) / pl.Bg; ds.n = 4 * s.H;
+    hipLaunchKernelGGL(db_sum_kernel, dim3((unsigned)((ds.n + 255) / 256)), dim3(256), 0, stream, ds);
+    e = hipGetLastError();
+  }
+  return e;
 }
 
 }  // namespace rlstm

@@ -70,18 +70,27 @@ size_t rec_workspace_bytes(const RecShape& s);
 // true if the persistent kernels can hold this shape (LDS, grid <= CUs).
 bool rec_persistent_supported(const RecShape& s, int num_cus, size_t max_lds);
 
+// [s_begin, s_end): the steps of the pass (in processing order) that this call enqueues; a pass may
+// be split into consecutive calls on one stream that together cover [0, T) (persistent engine only;
+// the stepwise engine takes the whole range).  The scratch carries the state from call to call.
 hipError_t rec_forward(hipStream_t stream, const RecShape& s, const RecFwdDir* dirs,
-                       const int32_t* seq_lens, void* ws, unsigned* flag, bool persistent, int* resident_err);
+                       const int32_t* seq_lens, void* ws, unsigned* flag, bool persistent, int* resident_err,
+                       int s_begin, int s_end);
 hipError_t rec_backward(hipStream_t stream, const RecShape& s, const RecBwdDir* dirs,
-                        const int32_t* seq_lens, void* ws, unsigned* flag, bool persistent, int* resident_err);
+                        const int32_t* seq_lens, void* ws, unsigned* flag, bool persistent, int* resident_err,
+                        int s_begin, int s_end);
 
 // the two engines behind rec_forward / rec_backward
 bool persistent_supported(const RecShape& s, int num_cus, size_t max_lds);
-size_t persistent_scratch_bytes_per_dir(const RecShape& s);
+size_t persistent_scratch_bytes(const RecShape& s);
+// number of groups the sequences of a minibatch are dealt out to per direction (0: chosen per shape)
+void persistent_set_batch_groups(int nb);
+// test hook: workgroup `mute_workgroup` (-1: none) withholds its step flags; wait bound in 100 MHz ticks (0: default)
+void persistent_test_hook(int mute_workgroup, unsigned long long wait_ticks);
 hipError_t persistent_forward(hipStream_t stream, const RecShape& s, const RecFwdDir* dirs, const int32_t* seq_lens,
-                              char* const* scratch, unsigned* err, int* resident_err);
+                              char* scratch, unsigned* err, int* resident_err, int s_begin, int s_end);
 hipError_t persistent_backward(hipStream_t stream, const RecShape& s, const RecBwdDir* dirs, const int32_t* seq_lens,
-                               char* const* scratch, unsigned* err, int* resident_err);
+                               char* scratch, unsigned* err, int* resident_err, int s_begin, int s_end);
 size_t stepwise_scratch_floats_per_dir(const RecShape& s);
 hipError_t stepwise_forward(hipStream_t stream, const RecShape& s, const RecFwdDir* dirs, const int32_t* seq_lens,
                             float* const* buf);

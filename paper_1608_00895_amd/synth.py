@@ -111,6 +111,13 @@ def config4() -> Workload:
                          len_hi=1500, wscale=0.03, seed=4, operand_dtype=1)
 
 
+def config4_short() -> Workload:
+    """Config 4's network (6 layers, H=1000, B=64, bf16 operands) on short sequences (lengths uniform in
+    [16, 48]) so that the CPU oracle can run the whole minibatch."""
+    return make_workload("config4_short_blstm6x1000_B64_bf16", L=6, B=64, D=40, H=1000, len_lo=16, len_hi=48,
+                         wscale=0.03, seed=44, operand_dtype=1)
+
+
 def small_blstm(seed: int = 11, *, L: int = 2, B: int = 5, D: int = 12, H: int = 20,
                 len_lo: int = 3, len_hi: int = 37, wscale: float = 0.3,
                 bias_scale: float = 0.2, T: Optional[int] = None) -> Workload:
