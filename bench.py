@@ -161,18 +161,22 @@ def main():
         log(e)
     dom = max(kernels, key=lambda e: e["ms_per_step"])
     # bytes per launch at the L2-to-fabric interface, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-    # summarised in profiles/blstm_stack_config3_hbm_counters.md (config 3 only; scaled by the copy kernel)
-    measured_traffic = {"recurrent_forward": 5.306e9 + 2.560e9, "recurrent_backward": 11.274e9 + 3.621e9,
-                        "input_projection": 0.903e9 + 0.274e9, "input_gradient": 2.226e9 + 0.145e9,
-                        "weight_gradient": 0.949e9 + 0.061e9, "recurrent_weight_gradient": 0.949e9 + 0.061e9}
+    # summarised in profiles/blstm_stack_config3_hbm_counters.md (config 3 with the library's default cut of
+    # the passes and groups of sequences only; scaled by the copy kernel)
+    measured_traffic = {"recurrent_forward": 0.391e9 + 0.481e9, "recurrent_backward": 1.074e9 + 0.713e9,
+                        "input_projection": 0.135e9 + 0.070e9, "input_gradient": 0.112e9 + 0.017e9,
+                        "weight_gradient": 0.572e9 + 0.062e9, "recurrent_weight_gradient": 0.572e9 + 0.062e9}
+    default_knobs = args.first_piece is None and args.batch_groups is None and not args.one_stream and args.engine == 0
     peak = PEAK_FP32_MFMA_TFLOPS if wl.operand_dtype == 0 else PEAK_BF16_MFMA_TFLOPS
     roofline = {"kernel": dom["kernel"], "bound": "mfma", "achieved": dom["tflops"], "peak": peak,
                 "unit": "TFLOP/s", "frac": dom["tflops"] / peak,
-                "traffic": measured_traffic.get(dom["kernel"]) if args.workload == "config3" else None,
+                "traffic": measured_traffic.get(dom["kernel"]) if args.workload == "config3" and default_knobs else None,
                 "avg_launch_ms": dom["avg_ms"],
+                "steps_per_launch": dom.get("steps_per_launch"),
                 "note": "the recurrent kernels are bound by the serial chain of T dependent steps "
                         "(see step_us), not by MFMA or HBM throughput; priced here against the fp32 MFMA "
-                        "peak with 2*B*H*4H FLOP per step and direction"}
+                        "peak with 2*B*H*4H FLOP per step and direction; a pass over the T steps is cut "
+                        "into several launches (steps_per_launch)"}
 
     out = {
         "metric": "BLSTM train frames/sec (fwd+bwd)", "value": frames_per_s, "unit": "frames/s",
