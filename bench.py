@@ -178,6 +178,32 @@ def main():
                         "peak with 2*B*H*4H FLOP per step and direction; a pass over the T steps is cut "
                         "into several launches (steps_per_launch)"}
 
+    # Floor of the step chain: the bare exchange of one hop (store, acknowledge, flag, poll, load; no
+    # arithmetic) timed live at the same group shape.  Forward: one hop per step (h_t); backward: two
+    # (d a_t, then the partial tiles, which the kernel sends as tagged words; timed here with flags).
+    if args.engine in (0, 1):
+        try:
+            plan = rl.rblstm_plan(desc)
+            es = 2 if wl.operand_dtype == 1 else 4
+            ng, bp, u = plan["groups"], max(16, plan["rows"]), plan["units_per_workgroup"]
+            def floor(members, tile, read):
+                wsf = torch.empty(rl.rlstm_exchange_floor_bytes(ng, members, tile), dtype=torch.uint8, device=dev)
+                return rl.rlstm_exchange_floor(ng, members, tile, read, 2000, wsf)
+            f_fwd = floor(plan["members_fwd"], bp * u * es, plan["members_fwd"] * bp * u * es)
+            f_dz = floor(plan["members_bwd"], bp * u * 4 * es, plan["members_bwd"] * bp * u * es)
+            f_part = floor(plan["members_bwd"], bp * 4 * u * 8, 4 * bp * u * 8)
+            for e in kernels:
+                if e["kernel"] == "recurrent_forward":
+                    e["exchange_floor_us"] = f_fwd
+                if e["kernel"] == "recurrent_backward":
+                    e["exchange_floor_us"] = f_dz + f_part
+            roofline["plan"] = plan
+            if dom["kernel"] in ("recurrent_forward", "recurrent_backward"):
+                roofline["step_us"] = dom["step_us"]
+                roofline["exchange_floor_us"] = dom["exchange_floor_us"]
+        except rl.RlstmError as ex:
+            log("exchange floor not measured:", ex)
+
     out = {
         "metric": "BLSTM train frames/sec (fwd+bwd)", "value": frames_per_s, "unit": "frames/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,

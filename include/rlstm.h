@@ -236,6 +236,32 @@ RLSTM_API int rlstm_last_timeout(const void* workspace);
 RLSTM_API int rlstm_set_first_piece(int steps);
 
 /*
+ * How the persistent engine lays a stack's recurrent passes out on this device (for reports).
+ * out[8] (host): {groups of workgroups (directions * groups of sequences), sequences per group,
+ * rows a group's tiles hold, units per workgroup, workgroups per group in the forward kernel,
+ * workgroups per group in the backward kernel, padded H of the forward product, units per K
+ * quarter of the backward product}.  RLSTM_ERESIDENT if the persistent engine cannot hold the shape.
+ */
+RLSTM_API int rblstm_plan(const rblstm_desc* d, int32_t* out);
+
+/*
+ * Measurement aid (not part of the method): times the bare exchange that one hop of the
+ * persistent kernels' step chain consists of, without their arithmetic.  `groups` (1..8) groups
+ * of `members` workgroups, placed like the recurrent kernels' (one per CU, workgroup index =
+ * member * groups + group); per step every workgroup stores `tile_bytes` (multiple of 16) with
+ * device-scope stores, waits for their acknowledgement, raises its step flag, waits for the flags
+ * of all members of its group and loads the first `read_bytes` (<= members * tile_bytes) of the
+ * group's tiles with device-scope loads.  Runs `steps` steps three times on the stream,
+ * synchronises, and writes the best time per step in microseconds to *us_per_step (host pointer).
+ * workspace: device memory of at least rlstm_exchange_floor_bytes() bytes (0 = bad arguments).
+ * Returns RLSTM_ERESIDENT when groups * members exceeds the CUs, RLSTM_EHIP when a bounded wait
+ * expired (1 s) or a HIP call failed.
+ */
+RLSTM_API size_t rlstm_exchange_floor_bytes(int groups, int members, int tile_bytes);
+RLSTM_API int rlstm_exchange_floor(int groups, int members, int tile_bytes, int read_bytes, int steps,
+                                   void* workspace, size_t workspace_bytes, float* us_per_step, void* hip_stream);
+
+/*
  * Tuning knob of the persistent engine.  The sequences of a minibatch are independent; the
  * engine deals them out to `groups` groups of workgroups per direction, each with its own copy of
  * the recurrent matrix, which exchange h_t / d a_t only among themselves.  0 (default) = chosen

@@ -24,7 +24,7 @@ RLSTM_ENGINE_STEPWISE = 2
 EXPORTS = [
     "rlstm_reserve_bytes", "rlstm_workspace_bytes", "rblstm_reserve_bytes", "rblstm_workspace_bytes",
     "lstm_fwd", "lstm_bwd", "blstm_stack_fwd_bwd", "blstm_stack_fwd",
-    "rlstm_gemm_f32", "rlstm_gemm_bf16", "rlstm_copy_f32", "rlstm_profile_enable", "rlstm_profile_read", "rlstm_last_timeout", "rlstm_test_hook", "rlstm_set_first_piece", "rlstm_set_batch_groups", "rlstm_resolve_engine", "rlstm_strerror", "rlstm_version",
+    "rlstm_gemm_f32", "rlstm_gemm_bf16", "rlstm_copy_f32", "rlstm_profile_enable", "rlstm_profile_read", "rlstm_last_timeout", "rlstm_test_hook", "rlstm_set_first_piece", "rlstm_set_batch_groups", "rblstm_plan", "rlstm_exchange_floor_bytes", "rlstm_exchange_floor", "rlstm_resolve_engine", "rlstm_strerror", "rlstm_version",
 ]
 
 
@@ -92,6 +92,12 @@ def lib() -> ctypes.CDLL:
         L.rlstm_profile_read.argtypes = [ctypes.POINTER(rlstm_profile_entry), ip]
         L.rlstm_last_timeout.restype = ip
         L.rlstm_last_timeout.argtypes = [vp]
+        L.rblstm_plan.restype = ip
+        L.rblstm_plan.argtypes = [ctypes.POINTER(rblstm_desc), ctypes.POINTER(ctypes.c_int32)]
+        L.rlstm_exchange_floor_bytes.restype = ctypes.c_size_t
+        L.rlstm_exchange_floor_bytes.argtypes = [ip, ip, ip]
+        L.rlstm_exchange_floor.restype = ip
+        L.rlstm_exchange_floor.argtypes = [ip, ip, ip, ip, ip, vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_float), vp]
         L.rlstm_set_batch_groups.restype = ip
         L.rlstm_set_batch_groups.argtypes = [ip]
         L.rlstm_set_first_piece.restype = ip
@@ -260,3 +266,27 @@ def rlstm_set_batch_groups(groups: int) -> int:
     if rc != 0:
         raise RlstmError(rc, "rlstm_set_batch_groups")
     return rc
+
+
+def rlstm_exchange_floor_bytes(groups: int, members: int, tile_bytes: int) -> int:
+    return int(lib().rlstm_exchange_floor_bytes(int(groups), int(members), int(tile_bytes)))
+
+
+def rlstm_exchange_floor(groups, members, tile_bytes, read_bytes, steps, workspace, stream=None, check=True):
+    """Microseconds per step of the bare exchange (best of three runs)."""
+    out = ctypes.c_float(0.0)
+    nbytes = workspace.numel() * workspace.element_size()
+    rc = lib().rlstm_exchange_floor(int(groups), int(members), int(tile_bytes), int(read_bytes), int(steps),
+                                    _ptr(workspace), nbytes, ctypes.byref(out), _stream(stream))
+    if check and rc != 0:
+        raise RlstmError(rc, "rlstm_exchange_floor")
+    return float(out.value) if rc == 0 else rc
+
+
+def rblstm_plan(desc) -> dict:
+    out = (ctypes.c_int32 * 8)()
+    rc = int(lib().rblstm_plan(ctypes.byref(desc), out))
+    if rc != 0:
+        raise RlstmError(rc, "rblstm_plan")
+    keys = ("groups", "sequences_per_group", "rows", "units_per_workgroup", "members_fwd", "members_bwd", "Hp", "Hq")
+    return dict(zip(keys, [int(v) for v in out]))

@@ -285,6 +285,35 @@ int rlstm_set_first_piece(int steps) {
   return RLSTM_OK;
 }
 
+int rblstm_plan(const rblstm_desc* d, int32_t* out) {
+  int rc = check_stack_desc(d);
+  if (rc != RLSTM_OK) return rc;
+  if (!out) return RLSTM_ENULL;
+  DeviceInfo di;
+  if (device_info(&di) != hipSuccess) { (void)hipGetLastError(); return RLSTM_EHIP; }
+  int v[8];
+  if (!persistent_plan_info(stack_rec_shape(d), di.num_cus, di.max_lds, v)) return RLSTM_ERESIDENT;
+  for (int i = 0; i < 8; ++i) out[i] = v[i];
+  return RLSTM_OK;
+}
+
+size_t rlstm_exchange_floor_bytes(int groups, int members, int tile_bytes) {
+  if (groups < 1 || groups > 8 || members < 1 || members > 1024 || tile_bytes < 16 || tile_bytes > (1 << 20) || tile_bytes % 16) return 0;
+  return exchange_probe_bytes(groups, members, tile_bytes);
+}
+
+int rlstm_exchange_floor(int groups, int members, int tile_bytes, int read_bytes, int steps,
+                         void* workspace, size_t workspace_bytes, float* us_per_step, void* hip_stream) {
+  if (!workspace || !us_per_step) return RLSTM_ENULL;
+  const size_t need = rlstm_exchange_floor_bytes(groups, members, tile_bytes);
+  if (need == 0 || steps < 1 || steps > 1000000 || read_bytes < 0 || (long long)read_bytes > (long long)members * tile_bytes) return RLSTM_EDIM;
+  if (workspace_bytes < need) return RLSTM_ESIZE;
+  int resident_err = 0, timed_out = 0;
+  RLSTM_TRY(exchange_probe(static_cast<hipStream_t>(hip_stream), groups, members, tile_bytes, read_bytes, steps,
+                           workspace, us_per_step, &timed_out, &resident_err));
+  return timed_out ? RLSTM_EHIP : RLSTM_OK;
+}
+
 int rlstm_set_batch_groups(int groups) {
   if (groups < 0 || groups > 8) return RLSTM_EDIM;
   persistent_set_batch_groups(groups);

@@ -1031,6 +1031,14 @@ bool persistent_supported(const RecShape& s, int num_cus, size_t max_lds) {
   return make_plan(s, num_cus, max_lds).ok;
 }
 
+bool persistent_plan_info(const RecShape& s, int num_cus, size_t max_lds, int out[8]) {
+  const Plan pl = make_plan(s, num_cus, max_lds);
+  if (!pl.ok) return false;
+  out[0] = pl.NG; out[1] = pl.Bg; out[2] = pl.ROWS; out[3] = pl.U;
+  out[4] = pl.Gf; out[5] = pl.Gb; out[6] = pl.Hp; out[7] = pl.Hq;
+  return true;
+}
+
 size_t persistent_scratch_bytes(const RecShape& s) {
   return groups_bytes_max(s) + (size_t)s.ndir * (2 * state_bytes(s) + dbpart_bytes(s));
 }

@@ -83,6 +83,8 @@ hipError_t rec_backward(hipStream_t stream, const RecShape& s, const RecBwdDir* 
 // the two engines behind rec_forward / rec_backward
 bool persistent_supported(const RecShape& s, int num_cus, size_t max_lds);
 size_t persistent_scratch_bytes(const RecShape& s);
+// {groups, sequences per group, rows a group can hold, units per workgroup, forward members, backward members, Hp, Hq}
+bool persistent_plan_info(const RecShape& s, int num_cus, size_t max_lds, int out[8]);
 // number of groups the sequences of a minibatch are dealt out to per direction (0: chosen per shape)
 void persistent_set_batch_groups(int nb);
 // test hook: workgroup `mute_workgroup` (-1: none) withholds its step flags; wait bound in 100 MHz ticks (0: default)
@@ -106,6 +108,11 @@ hipError_t column_sum(hipStream_t stream, const float* a, size_t rows, int cols,
 hipError_t copy_f32(hipStream_t stream, float* dst, const float* src, size_t n);
 // zero the timeout flag
 hipError_t clear_flag(hipStream_t stream, unsigned* flag);
+
+// bare exchange of the persistent kernels' step chain (measurement aid, see exchange_probe.hip)
+size_t exchange_probe_bytes(int groups, int members, int tile_bytes);
+hipError_t exchange_probe(hipStream_t stream, int groups, int members, int tile_bytes, int read_bytes, int steps,
+                          void* ws, float* us_per_step, int* timed_out, int* resident_err);
 
 struct DeviceInfo { int num_cus; size_t max_lds; };
 hipError_t device_info(DeviceInfo* out);

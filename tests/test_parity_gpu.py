@@ -480,3 +480,21 @@ def test_single_layer_initial_and_final_state_with_groups_of_sequences(groups, d
     finally:
         rl.rlstm_set_batch_groups(0)
     _check_layer(got, fwd, grad, lens, f"groups={groups} dir={direction}")
+
+
+def test_plan_query_and_exchange_floor_probe():
+    """Measurement aids: the plan the persistent engine uses for config 3, and the bare-exchange probe
+    (argument checks; a run ends normally and reports a plausible time per step)."""
+    wl = synth.config3()
+    desc = rl.rblstm_desc(L=wl.L, T=wl.T, B=wl.B, D=wl.D, H=wl.H, operand_dtype=0, engine=rl.RLSTM_ENGINE_AUTO)
+    plan = rl.rblstm_plan(desc)
+    assert plan["groups"] * plan["members_fwd"] <= 256 and plan["groups"] * plan["members_bwd"] <= 256
+    assert plan["members_fwd"] * plan["units_per_workgroup"] >= wl.H
+    assert plan["groups"] // 2 * plan["sequences_per_group"] >= wl.B
+    assert rl.rlstm_exchange_floor_bytes(9, 4, 64) == 0 and rl.rlstm_exchange_floor_bytes(2, 4, 24) == 0
+    ws = torch.empty(rl.rlstm_exchange_floor_bytes(2, 16, 256), dtype=torch.uint8, device=gh.DEV)
+    assert rl.rlstm_exchange_floor(2, 16, 256, 16 * 256 + 16, 100, ws, check=False) == -2      # reads past the tiles
+    assert rl.rlstm_exchange_floor(2, 16, 256, 16 * 256, 100, ws[:1024], check=False) == -4    # workspace too small
+    assert rl.rlstm_exchange_floor(2, 200, 256, 256, 100, ws, check=False) in (-4, -5)
+    us = rl.rlstm_exchange_floor(2, 16, 256, 16 * 256, 200, ws)
+    assert 0.2 < us < 100.0, us
