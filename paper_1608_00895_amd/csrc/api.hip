@@ -93,13 +93,15 @@ int hip_to_code(hipError_t e, int resident_err) {
 // processed frame; the h0 term is added separately by the single-layer entry point)
 int weight_grads(hipStream_t st, int layer, int T, int B, int Din, int H, int direction,
                  const float* x, int ldx, const float* y, int ldy, const float* dz,
-                 float* dW, float* dR, float* skws, size_t skfloats, bool naive, int operand_dtype) {
+                 float* dW, float* dR, float* skws, size_t skfloats, bool naive, int operand_dtype,
+                 bool small_footprint) {
   int resident_err = 0;
   GemmCall g;
   g.transA = true; g.transB = false;
   g.M = Din; g.N = 4 * H; g.K = T * B;
   g.A = x; g.lda = ldx; g.B = dz; g.ldb = 4 * H; g.C = dW; g.ldc = 4 * H;
   g.splitk_ws = skws; g.splitk_floats = skfloats; g.naive = naive; g.operand_dtype = operand_dtype;
+  g.small_footprint = small_footprint;
   {
     ProfScope ps(st, 4, layer, 1, 0, gemm_flop(g));
     RLSTM_TRY(gemm(st, g));
@@ -144,6 +146,15 @@ RecShape stack_rec_shape(const rblstm_desc* d) {
 // the recurrence, so a piece of twice the size is ready in time).
 int g_first_piece = 128;         // steps of piece 0; 0 = do not cut
 
+// Cutting the passes pays only if a matrix-product workgroup fits on a CU next to a workgroup of
+// the persistent kernels (LDS); otherwise the products just queue behind the recurrent launches.
+bool products_can_share_cus(const RecShape& rs, int operand_dtype) {
+  DeviceInfo di;
+  if (device_info(&di) != hipSuccess) { (void)hipGetLastError(); return false; }
+  const size_t rec = persistent_lds_bytes(rs, di.num_cus, di.max_lds);
+  return rec != 0 && rec + gemm_small_lds_bytes(operand_dtype) <= di.max_lds;
+}
+
 std::vector<int> piece_bounds(int T, bool pipelined) {
   std::vector<int> b{0};
   if (pipelined && g_first_piece > 0) {
@@ -181,7 +192,7 @@ int stack_forward(const rblstm_desc* d, const float* x, const float* const* para
   unsigned* flag = reinterpret_cast<unsigned*>(ws);
   void* recws = ws + kFlagBytes;
   const int T = d->T, B = d->B, H = d->H;
-  const bool pipelined = persistent && sb != sa;
+  const bool pipelined = persistent && sb != sa && products_can_share_cus(rs, d->operand_dtype);
   const std::vector<int> pb = piece_bounds(T, pipelined);
   const int np = (int)pb.size() - 1;
   EventList evs;
@@ -206,7 +217,7 @@ int stack_forward(const rblstm_desc* d, const float* x, const float* const* para
         g.M = (s1 - s0) * B; g.N = 4 * H; g.K = din;
         g.A = in + f0 * B * din; g.lda = din; g.B = params[6 * l + 3 * k + 0]; g.ldb = 4 * H;
         g.C = base + lay.zg[k] + f0 * B * 4 * H; g.ldc = 4 * H; g.bias = params[6 * l + 3 * k + 2];
-        g.naive = !persistent; g.operand_dtype = d->operand_dtype;
+        g.naive = !persistent; g.operand_dtype = d->operand_dtype; g.small_footprint = pipelined;
         ProfScope ps(sb, 0, l, 1, 0, gemm_flop(g));
         RLSTM_TRY(gemm(sb, g));
       }
@@ -452,7 +463,8 @@ int lstm_bwd(const rlstm_desc* d, const float* x, const float* W, const float* R
     ProfScope ps(st, 2, 0, 1, T, rec_flop(s, T));
     RLSTM_TRY(rec_backward(st, s, &dir, seq_lens, recws, flag, persistent, &resident_err, 0, T));
   }
-  rc = weight_grads(st, 0, T, B, D, H, d->direction, x, ldx, y, ldy, zg, dW, dR, skws, skfloats, !persistent, d->operand_dtype);
+  rc = weight_grads(st, 0, T, B, D, H, d->direction, x, ldx, y, ldy, zg, dW, dR, skws, skfloats, !persistent, d->operand_dtype,
+                    false);
   if (rc != RLSTM_OK) return rc;
   if (h0) RLSTM_TRY(add_h0_outer(st, T, B, H, d->direction, h0, zg, seq_lens, dR));
   if (dx) {
@@ -517,7 +529,7 @@ int blstm_stack_fwd_bwd(const rblstm_desc* d, const float* x, const float* const
   // w.r.t. a layer's input is the dy of the layer below: it is produced on stream b in the pieces,
   // and in the frame order, in which that layer's pass back through time consumes it, one piece
   // ahead; the weight gradients follow on stream b and overlap the rest of that pass.
-  const bool pipelined = persistent && overlap;
+  const bool pipelined = persistent && overlap && products_can_share_cus(rs, d->operand_dtype);
   const std::vector<int> pb = piece_bounds(T, pipelined);
   const int np = (int)pb.size() - 1;
   EventList evs;
@@ -558,7 +570,7 @@ int blstm_stack_fwd_bwd(const rblstm_desc* d, const float* x, const float* const
             g.A = base + lay.zg[k] + f0 * B * 4 * H; g.lda = 4 * H;
             g.B = params[6 * l + 3 * k + 0] + (size_t)tk * H * 4 * H; g.ldb = 4 * H;
             g.C = dxl + f0 * B * din + (size_t)tk * H; g.ldc = din; g.accumulate = (k == 1);
-            g.naive = !persistent; g.operand_dtype = d->operand_dtype;
+            g.naive = !persistent; g.operand_dtype = d->operand_dtype; g.small_footprint = pipelined;
             ProfScope ps(sb, 3, l, 1, 0, gemm_flop(g));
             RLSTM_TRY(gemm(sb, g));
           }
@@ -585,7 +597,7 @@ int blstm_stack_fwd_bwd(const rblstm_desc* d, const float* x, const float* const
     for (int k = 0; k < 2; ++k) {
       rc = weight_grads(sb, l, T, B, din, H, k == 0 ? 1 : -1, xin, din, yl + (size_t)k * H, 2 * H,
                         base + lay.zg[k], grads[6 * l + 3 * k + 0], grads[6 * l + 3 * k + 1], skws, skfloats,
-                        !persistent, d->operand_dtype);
+                        !persistent, d->operand_dtype, pipelined);
       if (rc != RLSTM_OK) return rc;
     }
     dy = dxl;

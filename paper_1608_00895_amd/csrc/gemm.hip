@@ -255,13 +255,13 @@ __device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(unsigned, v);
 }
 
-// k-contiguous source: element (mn, k) at ptr[mn*ld + k]; slab is 128 rows of 32 floats
-template <bool VEC>
+// k-contiguous source: element (mn, k) at ptr[mn*ld + k]; slab is ROWS rows of 32 floats
+template <int ROWS, bool VEC>
 __device__ __forceinline__ void load_kc(const float* __restrict__ ptr, int ld, int k0, int kend, int mn0, int MN,
-                                        float4 (&r)[4]) {
+                                        float4 (&r)[ROWS / 32]) {
   const int tid = threadIdx.x;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < ROWS / 32; ++i) {
     const int idx = tid + i * 256;
     const int mn = mn0 + (idx >> 3), k = k0 + (idx & 7) * 4;
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -279,10 +279,11 @@ __device__ __forceinline__ void load_kc(const float* __restrict__ ptr, int ld, i
     r[i] = v;
   }
 }
-__device__ __forceinline__ void store_kc(unsigned short* __restrict__ s, const float4 (&r)[4]) {
+template <int ROWS>
+__device__ __forceinline__ void store_kc(unsigned short* __restrict__ s, const float4 (&r)[ROWS / 32]) {
   const int tid = threadIdx.x;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < ROWS / 32; ++i) {
     const int idx = tid + i * 256;
     const int mn = idx >> 3, kq = (idx & 7) * 4;
     uint2 w;
@@ -292,12 +293,12 @@ __device__ __forceinline__ void store_kc(unsigned short* __restrict__ s, const f
   }
 }
 // mn-contiguous source: element (k, mn) at ptr[k*ld + mn]; a work item is 2 k rows x 4 columns
-template <bool VEC>
+template <int ROWS, bool VEC>
 __device__ __forceinline__ void load_mc(const float* __restrict__ ptr, int ld, int k0, int kend, int mn0, int MN,
-                                        float4 (&r)[4]) {
+                                        float4 (&r)[ROWS / 32]) {
   const int tid = threadIdx.x;
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < ROWS / 64; ++i) {
     const int idx = tid + i * 256;
     const int mn = mn0 + (idx >> 4) * 4, k = k0 + (idx & 15) * 2;
 #pragma unroll
@@ -318,10 +319,11 @@ __device__ __forceinline__ void load_mc(const float* __restrict__ ptr, int ld, i
     }
   }
 }
-__device__ __forceinline__ void store_mc(unsigned short* __restrict__ s, const float4 (&r)[4]) {
+template <int ROWS>
+__device__ __forceinline__ void store_mc(unsigned short* __restrict__ s, const float4 (&r)[ROWS / 32]) {
   const int tid = threadIdx.x;
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < ROWS / 64; ++i) {
     const int idx = tid + i * 256;
     const int mn = (idx >> 4) * 4, k = (idx & 15) * 2;
     const float4 a = r[i * 2], b = r[i * 2 + 1];
@@ -332,16 +334,20 @@ __device__ __forceinline__ void store_mc(unsigned short* __restrict__ s, const f
   }
 }
 
-template <bool TA, bool TB, bool VEC>
+// WM x WN: 32 x 32 MFMA tiles per wavefront; the workgroup's 2 x 2 wavefronts cover a
+// (64*WM) x (64*WN) tile of C: 128 x 128 for small products, 256 x 256 where there are enough
+// tiles to fill the chip (each operand byte fetched then feeds twice the MFMA work).
+template <int WM, int WN, bool TA, bool TB, bool VEC>
 __global__ __launch_bounds__(256) void gemm_mfma_bf16_kernel(GemmP p) {
+  constexpr int TMB = 64 * WM, TNB = 64 * WN;
   extern __shared__ __align__(16) float smem[];
-  unsigned short* As = reinterpret_cast<unsigned short*>(smem);     // [2][128][LDK]
-  unsigned short* Bs = As + 2 * TM * LDK;                           // [2][128][LDK]
+  unsigned short* As = reinterpret_cast<unsigned short*>(smem);     // [2][TMB][LDK]
+  unsigned short* Bs = As + 2 * TMB * LDK;                          // [2][TNB][LDK]
 
   int tile, kz;
   if (!work_item(p, &tile, &kz)) return;
   const int tn = tile % p.tiles_n, tm = tile / p.tiles_n;
-  const int m0 = tm * TM, n0 = tn * TN;
+  const int m0 = tm * TMB, n0 = tn * TNB;
   const int kbeg = kz * p.kchunk;
   const int kend = min(p.K, kbeg + p.kchunk);
   const int nslab = (kend - kbeg + BKH - 1) / BKH;
@@ -350,24 +356,24 @@ __global__ __launch_bounds__(256) void gemm_mfma_bf16_kernel(GemmP p) {
   const int wm = wave >> 1, wn = wave & 1;
   const int l32 = lane & 31, lh = lane >> 5;
 
-  floatx16 acc[2][2];
+  floatx16 acc[WM][WN];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < WM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < WN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  float4 ra[4], rb[4];
+  float4 ra[TMB / 32], rb[TNB / 32];
   auto loadA = [&](int k0) {
-    if (TA) load_mc<VEC>(p.A, p.lda, k0, kend, m0, p.M, ra); else load_kc<VEC>(p.A, p.lda, k0, kend, m0, p.M, ra);
+    if (TA) load_mc<TMB, VEC>(p.A, p.lda, k0, kend, m0, p.M, ra); else load_kc<TMB, VEC>(p.A, p.lda, k0, kend, m0, p.M, ra);
   };
   auto loadB = [&](int k0) {
-    if (TB) load_kc<VEC>(p.B, p.ldb, k0, kend, n0, p.N, rb); else load_mc<VEC>(p.B, p.ldb, k0, kend, n0, p.N, rb);
+    if (TB) load_kc<TNB, VEC>(p.B, p.ldb, k0, kend, n0, p.N, rb); else load_mc<TNB, VEC>(p.B, p.ldb, k0, kend, n0, p.N, rb);
   };
   auto storeAB = [&](int buf) {
-    if (TA) store_mc(As + buf * TM * LDK, ra); else store_kc(As + buf * TM * LDK, ra);
-    if (TB) store_kc(Bs + buf * TN * LDK, rb); else store_mc(Bs + buf * TN * LDK, rb);
+    if (TA) store_mc<TMB>(As + buf * TMB * LDK, ra); else store_kc<TMB>(As + buf * TMB * LDK, ra);
+    if (TB) store_kc<TNB>(Bs + buf * TNB * LDK, rb); else store_mc<TNB>(Bs + buf * TNB * LDK, rb);
   };
 
   if (nslab > 0) {
@@ -379,19 +385,21 @@ __global__ __launch_bounds__(256) void gemm_mfma_bf16_kernel(GemmP p) {
   for (int s = 0; s < nslab; ++s) {
     const int buf = s & 1;
     if (s + 1 < nslab) { loadA(kbeg + (s + 1) * BKH); loadB(kbeg + (s + 1) * BKH); }
-    const unsigned short* as = As + buf * TM * LDK + (wm * 64 + l32) * LDK + lh * 8;
-    const unsigned short* bs = Bs + buf * TN * LDK + (wn * 64 + l32) * LDK + lh * 8;
+    const unsigned short* as = As + buf * TMB * LDK + (wm * 32 * WM + l32) * LDK + lh * 8;
+    const unsigned short* bs = Bs + buf * TNB * LDK + (wn * 32 * WN + l32) * LDK + lh * 8;
 #pragma unroll
     for (int ks = 0; ks < BKH; ks += 16) {
       // lane l supplies row l%32, k = ks + 8*(l/32) .. +7
-      const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(as + ks);
-      const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(as + 32 * LDK + ks);
-      const bf16x8 b0 = *reinterpret_cast<const bf16x8*>(bs + ks);
-      const bf16x8 b1 = *reinterpret_cast<const bf16x8*>(bs + 32 * LDK + ks);
-      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc[0][1], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc[1][1], 0, 0, 0);
+      bf16x8 af[WM], bfr[WN];
+#pragma unroll
+      for (int i = 0; i < WM; ++i) af[i] = *reinterpret_cast<const bf16x8*>(as + i * 32 * LDK + ks);
+#pragma unroll
+      for (int j = 0; j < WN; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(bs + j * 32 * LDK + ks);
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
     if (s + 1 < nslab) storeAB(buf ^ 1);
     __syncthreads();
@@ -402,15 +410,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_bf16_kernel(GemmP p) {
   const bool partial = p.partial != nullptr;
   if (partial) { Cout = p.partial + (size_t)kz * p.M * p.N; ldc = p.N; }
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < WM; ++i) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int col = n0 + wn * 64 + j * 32 + l32;
+    for (int j = 0; j < WN; ++j) {
+      const int col = n0 + (wn * WN + j) * 32 + l32;
       if (col >= p.N) continue;
       const float bv = (!partial && p.bias) ? p.bias[col] : 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm * 64 + i * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
+        const int row = m0 + (wm * WM + i) * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
         if (row < p.M) {
           float* dst = Cout + (size_t)row * ldc + col;
           float v = acc[i][j][r] + bv;
@@ -468,15 +476,21 @@ hipError_t launch_mfma(hipStream_t stream, const GemmP& p, dim3 grid, bool vec) 
   return hipGetLastError();
 }
 
-template <bool TA, bool TB>
-hipError_t launch_bf16(hipStream_t stream, const GemmP& p, dim3 grid, bool vec) {
-  const size_t lds = (size_t)2 * (TM + TN) * LDK * sizeof(unsigned short);
-  if (vec) {
-    hipLaunchKernelGGL((gemm_mfma_bf16_kernel<TA, TB, true>), grid, dim3(256), lds, stream, p);
-  } else {
-    hipLaunchKernelGGL((gemm_mfma_bf16_kernel<TA, TB, false>), grid, dim3(256), lds, stream, p);
+template <int WM, int WN, bool TA, bool TB, bool VEC>
+hipError_t launch_bf16_v(hipStream_t stream, const GemmP& p, dim3 grid) {
+  const size_t lds = (size_t)2 * 64 * (WM + WN) * LDK * sizeof(unsigned short);
+  const void* fn = reinterpret_cast<const void*>(gemm_mfma_bf16_kernel<WM, WN, TA, TB, VEC>);
+  if (lds > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
   }
+  hipLaunchKernelGGL((gemm_mfma_bf16_kernel<WM, WN, TA, TB, VEC>), grid, dim3(256), lds, stream, p);
   return hipGetLastError();
+}
+template <bool TA, bool TB>
+hipError_t launch_bf16(hipStream_t stream, const GemmP& p, dim3 grid, bool vec, bool big) {
+  if (big) return vec ? launch_bf16_v<4, 4, TA, TB, true>(stream, p, grid) : launch_bf16_v<4, 4, TA, TB, false>(stream, p, grid);
+  return vec ? launch_bf16_v<2, 2, TA, TB, true>(stream, p, grid) : launch_bf16_v<2, 2, TA, TB, false>(stream, p, grid);
 }
 
 }  // namespace
@@ -487,7 +501,11 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
   p.M = g.M; p.N = g.N; p.K = g.K;
   p.A = g.A; p.lda = g.lda; p.B = g.B; p.ldb = g.ldb; p.C = g.C; p.ldc = g.ldc;
   p.bias = g.bias; p.accumulate = g.accumulate ? 1 : 0;
-  p.tiles_n = (g.N + TN - 1) / TN;
+  const bool bf16 = g.operand_dtype == 1;
+  // bf16 operands: 256 x 256 tiles once those alone give every CU work
+  const bool big = bf16 && !g.naive && !g.small_footprint && (long long)((g.M + 255) / 256) * ((g.N + 255) / 256) >= 128;
+  const int tile_m = big ? 256 : TM, tile_n = big ? 256 : TN;
+  p.tiles_n = (g.N + tile_n - 1) / tile_n;
   p.kchunk = g.K; p.partial = nullptr;
 
   if (g.naive) {
@@ -497,14 +515,13 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
     return hipGetLastError();
   }
 
-  const bool bf16 = g.operand_dtype == 1;
   const int BK = bf16 ? BKH : 16;
   // float4 global loads need 16-byte aligned rows and whole float4s inside the matrix
   bool vec = aligned16(g.A) && aligned16(g.B) && (g.lda % 4 == 0) && (g.ldb % 4 == 0) && (g.K % 4 == 0);
   if (g.transA) vec = vec && (g.M % 4 == 0);
   if (!g.transB) vec = vec && (g.N % 4 == 0);
 
-  const int tiles_m = (g.M + TM - 1) / TM;
+  const int tiles_m = (g.M + tile_m - 1) / tile_m;
   const int tiles = tiles_m * p.tiles_n;
   int slices = 1;
   if (g.splitk_ws && g.K >= 4 * 1024 && tiles < 512) {
@@ -530,10 +547,10 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
   dim3 grid((unsigned)(8 * p.per_xcd), 1, 1);
   hipError_t e;
   if (bf16) {
-    if (!g.transA && !g.transB)      e = launch_bf16<false, false>(stream, p, grid, vec);
-    else if (!g.transA && g.transB)  e = launch_bf16<false, true>(stream, p, grid, vec);
-    else if (g.transA && !g.transB)  e = launch_bf16<true, false>(stream, p, grid, vec);
-    else                             e = launch_bf16<true, true>(stream, p, grid, vec);
+    if (!g.transA && !g.transB)      e = launch_bf16<false, false>(stream, p, grid, vec, big);
+    else if (!g.transA && g.transB)  e = launch_bf16<false, true>(stream, p, grid, vec, big);
+    else if (g.transA && !g.transB)  e = launch_bf16<true, false>(stream, p, grid, vec, big);
+    else                             e = launch_bf16<true, true>(stream, p, grid, vec, big);
   } else {
     if (!g.transA && !g.transB)      e = launch_mfma<16, false, false>(stream, p, grid, vec);
     else if (!g.transA && g.transB)  e = launch_mfma<16, false, true>(stream, p, grid, vec);
@@ -548,6 +565,10 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
     e = hipGetLastError();
   }
   return e;
+}
+
+size_t gemm_small_lds_bytes(int operand_dtype) {
+  return operand_dtype == 1 ? (size_t)2 * (TM + TN) * LDK * sizeof(unsigned short) : (size_t)4 * 16 * LDT * sizeof(float);
 }
 
 }  // namespace rlstm

@@ -1031,6 +1031,12 @@ bool persistent_supported(const RecShape& s, int num_cus, size_t max_lds) {
   return make_plan(s, num_cus, max_lds).ok;
 }
 
+size_t persistent_lds_bytes(const RecShape& s, int num_cus, size_t max_lds) {
+  const Plan pl = make_plan(s, num_cus, max_lds);
+  if (!pl.ok) return 0;
+  return pl.ldsF > pl.ldsB ? pl.ldsF : pl.ldsB;
+}
+
 bool persistent_plan_info(const RecShape& s, int num_cus, size_t max_lds, int out[8]) {
   const Plan pl = make_plan(s, num_cus, max_lds);
   if (!pl.ok) return false;

@@ -30,6 +30,7 @@ struct GemmCall {
   float* splitk_ws = nullptr; size_t splitk_floats = 0;
   int operand_dtype = 0;
   bool naive = false;
+  bool small_footprint = false;   // keep to the 128 x 128 kernel, which can share a CU with a recurrent workgroup
 };
 hipError_t gemm(hipStream_t stream, const GemmCall& g);
 
@@ -83,6 +84,10 @@ hipError_t rec_backward(hipStream_t stream, const RecShape& s, const RecBwdDir* 
 // the two engines behind rec_forward / rec_backward
 bool persistent_supported(const RecShape& s, int num_cus, size_t max_lds);
 size_t persistent_scratch_bytes(const RecShape& s);
+// LDS a workgroup of the persistent kernels requests (larger of forward / backward); 0: shape not supported
+size_t persistent_lds_bytes(const RecShape& s, int num_cus, size_t max_lds);
+// LDS of the matrix-product kernel that can share a CU with other work (128 x 128 tiles)
+size_t gemm_small_lds_bytes(int operand_dtype);
 // {groups, sequences per group, rows a group can hold, units per workgroup, forward members, backward members, Hp, Hq}
 bool persistent_plan_info(const RecShape& s, int num_cus, size_t max_lds, int out[8]);
 // number of groups the sequences of a minibatch are dealt out to per direction (0: chosen per shape)

@@ -246,6 +246,8 @@ def _round_bf16(a):
 @pytest.mark.parametrize("case", [
     (0, 0, 300, 200, 40), (0, 0, 257, 129, 1000), (0, 1, 260, 40, 512), (1, 0, 100, 260, 5000),
     (1, 1, 64, 64, 64), (0, 0, 33, 17, 19), (1, 0, 37, 50, 4100), (0, 1, 128, 128, 32),
+    # enough tiles for the 256 x 256 kernel: ragged edges in m, n and k, every operand layout, split-K
+    (0, 0, 3000, 2900, 100), (0, 1, 2830, 3100, 77), (1, 0, 2900, 2950, 4100), (1, 1, 2820, 2900, 40),
 ])
 def test_gemm_bf16_against_numpy(case):
     """bf16-operand product: equal to the fp64 product of the bf16-rounded operands up to fp32
