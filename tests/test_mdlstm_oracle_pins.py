@@ -1,0 +1,301 @@
+"""Pins for oracle/mdlstm_oracle.py against things other than itself: finite differences, autograd of
+an independent torch formulation, reduction to the one-dimensional LSTM oracle (itself pinned against
+torch.nn.LSTM), closed forms, and the invariants the paper's anti-diagonal scheme rests on."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import lstm_backward, lstm_forward
+from oracle.mdlstm_oracle import (DIRECTIONS, mdlstm4_backward, mdlstm4_forward, mdlstm_backward, mdlstm_forward,
+                                  visiting_order)
+
+
+def _rng(seed):
+    return np.random.Generator(np.random.Philox(seed))
+
+
+def _params(rng, D, H, scale=0.4):
+    return (rng.uniform(-scale, scale, (D, 5 * H)), rng.uniform(-scale, scale, (H, 5 * H)),
+            rng.uniform(-scale, scale, (H, 5 * H)), rng.uniform(-scale, scale, (5 * H,)))
+
+
+def _loss(x, p, widths, du, dv, G):
+    return float((mdlstm_forward(x, *p, widths, du, dv)["y"] * G).sum())
+
+
+@pytest.mark.parametrize("direction", DIRECTIONS)
+def test_central_finite_differences_of_every_input(direction):
+    du, dv = direction
+    rng = _rng(100 + 3 * du + dv)
+    Hh, Ww, B, D, H = 3, 4, 2, 2, 3
+    x = rng.standard_normal((Hh, Ww, B, D))
+    p = list(_params(rng, D, H))
+    widths = np.array([4, 2])
+    G = rng.standard_normal((Hh, Ww, B, H))
+    g = mdlstm_backward(mdlstm_forward(x, *p, widths, du, dv), G)
+    eps = 1e-6
+    for name, arr, grad in (("x", x, g["dx"]), ("W", p[0], g["dW"]), ("Ru", p[1], g["dRu"]), ("Rv", p[2], g["dRv"]),
+                            ("b", p[3], g["db"])):
+        num = np.zeros_like(arr)
+        it = np.nditer(arr, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            old = arr[idx]
+            arr[idx] = old + eps
+            lp = _loss(x, p, widths, du, dv, G)
+            arr[idx] = old - eps
+            lm = _loss(x, p, widths, du, dv, G)
+            arr[idx] = old
+            num[idx] = (lp - lm) / (2 * eps)
+        err = np.abs(num - grad).max() / max(np.abs(grad).max(), 1e-30)
+        assert err < 2e-8, (name, err)
+
+
+def _torch_scan(x, W, Ru, Rv, b, widths, du, dv):
+    """The same layer written a different way (no explicit backward): state kept in Python dicts of
+    torch tensors, pixels outside an image replaced by zeros with torch.where."""
+    Hh, Ww, B, _ = x.shape
+    H = Ru.shape[0]
+    hs, cs = {}, {}
+    zero = torch.zeros(B, H, dtype=torch.float64)
+    rows = []
+    for iu in range(Hh):
+        u = iu if du == 1 else Hh - 1 - iu
+        for iv in range(Ww):
+            v = iv if dv == 1 else Ww - 1 - iv
+            hu, cu = hs.get((u - du, v), zero), cs.get((u - du, v), zero)
+            hl, cl = hs.get((u, v - dv), zero), cs.get((u, v - dv), zero)
+            a = x[u, v] @ W + hu @ Ru + hl @ Rv + b
+            i, fu, fv, o, g = a.split(H, dim=1)
+            c = torch.sigmoid(fu) * cu + torch.sigmoid(fv) * cl + torch.sigmoid(i) * torch.tanh(g)
+            h = torch.sigmoid(o) * torch.tanh(c)
+            inside = (v < widths).unsqueeze(1)
+            hs[(u, v)] = torch.where(inside, h, zero)
+            cs[(u, v)] = torch.where(inside, c, zero)
+    for u in range(Hh):
+        rows.append(torch.stack([hs[(u, v)] for v in range(Ww)]))
+    return torch.stack(rows)
+
+
+@pytest.mark.parametrize("direction", DIRECTIONS)
+def test_gradients_against_torch_autograd(direction):
+    du, dv = direction
+    rng = _rng(200 + 3 * du + dv)
+    Hh, Ww, B, D, H = 4, 5, 3, 2, 4
+    x = rng.standard_normal((Hh, Ww, B, D))
+    p = _params(rng, D, H)
+    widths = np.array([5, 3, 0])
+    G = rng.standard_normal((Hh, Ww, B, H))
+    fwd = mdlstm_forward(x, *p, widths, du, dv)
+    g = mdlstm_backward(fwd, G)
+    tx, tW, tRu, tRv, tb = (torch.tensor(a, dtype=torch.float64, requires_grad=True) for a in (x, *p))
+    ty = _torch_scan(tx, tW, tRu, tRv, tb, torch.tensor(widths), du, dv)
+    (ty * torch.tensor(G)).sum().backward()
+    assert np.abs(ty.detach().numpy() - fwd["y"]).max() < 1e-13
+    for name, t, mine in (("dx", tx, g["dx"]), ("dW", tW, g["dW"]), ("dRu", tRu, g["dRu"]), ("dRv", tRv, g["dRv"]),
+                          ("db", tb, g["db"])):
+        ref = t.grad.numpy()
+        assert np.abs(ref - mine).max() < 1e-12 * max(1.0, np.abs(ref).max()), name
+
+
+def _four_gate(p, H, which):
+    """Columns (i, f, o, g) of a one-dimensional LSTM taken from the five-block parameters;
+    which = 'v' keeps f_v and R_v, 'u' keeps f_u and R_u."""
+    W, Ru, Rv, b = p
+    f = 2 if which == "v" else 1
+    cols = np.concatenate([np.arange(0, H), np.arange(f * H, (f + 1) * H), np.arange(3 * H, 4 * H), np.arange(4 * H, 5 * H)])
+    R = Rv if which == "v" else Ru
+    return W[:, cols], R[:, cols], b[cols], cols
+
+
+@pytest.mark.parametrize("direction", DIRECTIONS)
+def test_image_of_height_one_is_the_one_dimensional_lstm(direction):
+    du, dv = direction
+    rng = _rng(300 + 3 * du + dv)
+    Ww, B, D, H = 9, 4, 3, 5
+    x = rng.standard_normal((1, Ww, B, D))
+    p = _params(rng, D, H)
+    widths = np.array([9, 4, 0, 7])
+    G = rng.standard_normal((1, Ww, B, H))
+    fwd = mdlstm_forward(x, *p, widths, du, dv)
+    g = mdlstm_backward(fwd, G)
+    W4, R4, b4, cols = _four_gate(p, H, "v")
+    f1 = lstm_forward(x[0], W4, R4, b4, widths, dv)
+    g1 = lstm_backward(f1, G[0])
+    assert np.abs(fwd["y"][0] - f1["y"]).max() < 1e-14
+    assert np.abs(g["dx"][0] - g1["dx"]).max() < 1e-13
+    assert np.abs(g["dW"][:, cols] - g1["dW"]).max() < 1e-12
+    assert np.abs(g["dRv"][:, cols] - g1["dR"]).max() < 1e-12
+    assert np.abs(g["db"][cols] - g1["db"]).max() < 1e-12
+    # the vertical predecessor never exists: its recurrent matrix and forget gate get no gradient
+    assert not g["dRu"].any() and not g["dW"][:, H:2 * H].any() and not g["db"][H:2 * H].any()
+
+
+@pytest.mark.parametrize("direction", DIRECTIONS)
+def test_image_of_width_one_is_the_one_dimensional_lstm(direction):
+    du, dv = direction
+    rng = _rng(400 + 3 * du + dv)
+    Hh, B, D, H = 7, 3, 2, 4
+    x = rng.standard_normal((Hh, 1, B, D))
+    p = _params(rng, D, H)
+    widths = np.array([1, 0, 1])
+    G = rng.standard_normal((Hh, 1, B, H))
+    fwd = mdlstm_forward(x, *p, widths, du, dv)
+    g = mdlstm_backward(fwd, G)
+    W4, R4, b4, cols = _four_gate(p, H, "u")
+    f1 = lstm_forward(x[:, 0], W4, R4, b4, widths * Hh, du)     # an empty image is a sequence of length 0
+    g1 = lstm_backward(f1, G[:, 0])
+    assert np.abs(fwd["y"][:, 0] - f1["y"]).max() < 1e-14
+    assert np.abs(g["dx"][:, 0] - g1["dx"]).max() < 1e-13
+    assert np.abs(g["dRu"][:, cols] - g1["dR"]).max() < 1e-12
+    assert np.abs(g["db"][cols] - g1["db"]).max() < 1e-12
+    assert not g["dRv"].any()
+
+
+def test_closed_form_with_constant_gates():
+    """Zero matrices and a bias on the g block only: i = f_u = f_v = o = 1/2, g = tanh(beta), so
+    c(u,v) = (tanh(beta)/2) * sum over (p,q) <= (u,v) of C(p+q,p) 2^-(p+q)  (every monotone path from
+    an earlier pixel halves the contribution at each step) and y = tanh(c)/2."""
+    Hh, Ww, B, D, H = 5, 6, 1, 2, 3
+    beta = 0.7
+    b = np.zeros(5 * H)
+    b[4 * H:] = beta
+    x = _rng(5).standard_normal((Hh, Ww, B, D))
+    z = np.zeros
+    fwd = mdlstm_forward(x, z((D, 5 * H)), z((H, 5 * H)), z((H, 5 * H)), b, np.array([Ww]), 1, 1)
+    for u in range(Hh):
+        for v in range(Ww):
+            s = sum(math.comb(p + q, p) * 0.5 ** (p + q) for p in range(u + 1) for q in range(v + 1))
+            c = 0.5 * math.tanh(beta) * s
+            assert abs(fwd["c"][u, v, 0, 0] - c) < 1e-13
+            assert abs(fwd["y"][u, v, 0, 1] - 0.5 * math.tanh(c)) < 1e-13
+    # the other corners see the same numbers mirrored
+    f2 = mdlstm_forward(x, z((D, 5 * H)), z((H, 5 * H)), z((H, 5 * H)), b, np.array([Ww]), -1, -1)
+    assert np.abs(f2["c"][::-1, ::-1] - fwd["c"]).max() < 1e-15
+
+
+def test_gate_block_order_and_untransposed_matrices():
+    """One-hot parameters: only input 0 -> o-gate of unit 1, and R_u[2, g-block unit 0]."""
+    Hh, Ww, B, D, H = 2, 1, 1, 2, 3
+    W = np.zeros((D, 5 * H)); Ru = np.zeros((H, 5 * H)); Rv = np.zeros((H, 5 * H)); b = np.zeros(5 * H)
+    b[0:H] = 30.0          # i = 1
+    b[3 * H:4 * H] = 30.0  # o = 1
+    b[4 * H + 2] = 1.0     # g of unit 2 = tanh(1)
+    Ru[2, 4 * H + 0] = 2.0  # h of unit 2 in the row above drives g of unit 0 below
+    x = np.zeros((Hh, Ww, B, D))
+    fwd = mdlstm_forward(x, W, Ru, Rv, b, np.array([1]), 1, 1)
+    h_top = math.tanh(math.tanh(1.0))
+    assert abs(fwd["y"][0, 0, 0, 2] - h_top) < 1e-12 and abs(fwd["y"][0, 0, 0, 0]) < 1e-12
+    c_bottom0 = math.tanh(2.0 * h_top)
+    assert abs(fwd["y"][1, 0, 0, 0] - math.tanh(c_bottom0)) < 1e-9
+
+
+@pytest.mark.parametrize("direction", DIRECTIONS)
+def test_visiting_order_does_not_matter(direction):
+    du, dv = direction
+    rng = _rng(500 + 3 * du + dv)
+    Hh, Ww, B, D, H = 5, 7, 3, 2, 4
+    x = rng.standard_normal((Hh, Ww, B, D))
+    p = _params(rng, D, H)
+    widths = np.array([7, 2, 5])
+    G = rng.standard_normal((Hh, Ww, B, H))
+    base = mdlstm_forward(x, *p, widths, du, dv, order="rows")
+    gb = mdlstm_backward(base, G, order="rows")
+    for order in ("columns", "diagonals"):
+        # every visiting order puts a pixel after its two predecessors
+        seen = set()
+        for (u, v) in visiting_order(Hh, Ww, du, dv, order):
+            assert (not 0 <= u - du < Hh or (u - du, v) in seen) and (not 0 <= v - dv < Ww or (u, v - dv) in seen)
+            seen.add((u, v))
+        assert len(seen) == Hh * Ww
+        f = mdlstm_forward(x, *p, widths, du, dv, order=order)
+        assert np.array_equal(f["y"], base["y"]) and np.array_equal(f["c"], base["c"])
+        g = mdlstm_backward(f, G, order=order)
+        assert np.array_equal(g["dx"], gb["dx"]) and np.array_equal(g["dz"], gb["dz"])
+        for k in ("dW", "dRu", "dRv", "db"):
+            assert np.abs(g[k] - gb[k]).max() < 1e-12
+
+
+def test_directions_are_flips_of_each_other():
+    rng = _rng(6)
+    Hh, Ww, B, D, H = 4, 6, 3, 2, 3
+    x = rng.standard_normal((Hh, Ww, B, D))
+    p = _params(rng, D, H)
+    widths = np.array([6, 6, 6])
+    G = rng.standard_normal((Hh, Ww, B, H))
+    base = mdlstm_forward(x, *p, widths, 1, 1)
+    gb = mdlstm_backward(base, G)
+    for (du, dv) in DIRECTIONS[1:]:
+        su = slice(None, None, du)
+        sv = slice(None, None, dv)
+        f = mdlstm_forward(x[su, sv], *p, widths, du, dv)
+        assert np.array_equal(f["y"][su, sv], base["y"])
+        g = mdlstm_backward(f, G[su, sv])
+        assert np.array_equal(g["dx"][su, sv], gb["dx"])
+        assert np.abs(g["dW"] - gb["dW"]).max() < 1e-12 and np.abs(g["dRv"] - gb["dRv"]).max() < 1e-12
+    # a vertical flip also holds with ragged widths (columns stay where they are)
+    widths = np.array([6, 1, 4])
+    a = mdlstm_forward(x, *p, widths, 1, -1)
+    b_ = mdlstm_forward(x[::-1], *p, widths, -1, -1)
+    assert np.array_equal(b_["y"][::-1], a["y"])
+
+
+@pytest.mark.parametrize("direction", DIRECTIONS)
+def test_every_image_is_processed_as_if_alone_and_padding_has_no_influence(direction):
+    du, dv = direction
+    rng = _rng(700 + 3 * du + dv)
+    Hh, Ww, B, D, H = 4, 6, 3, 2, 3
+    x = rng.standard_normal((Hh, Ww, B, D))
+    p = _params(rng, D, H)
+    widths = np.array([6, 3, 0])
+    G = rng.standard_normal((Hh, Ww, B, H))
+    fwd = mdlstm_forward(x, *p, widths, du, dv)
+    g = mdlstm_backward(fwd, G)
+    dW = np.zeros_like(g["dW"])
+    for n, w in enumerate(widths):
+        assert not fwd["y"][:, w:, n].any() and not fwd["c"][:, w:, n].any() and not g["dz"][:, w:, n].any()
+        if w == 0:
+            continue
+        f1 = mdlstm_forward(x[:, :w, n:n + 1], *p, np.array([w]), du, dv)
+        # (a library product of 1 row and of 3 rows may sum in a different order: not bitwise)
+        assert np.abs(f1["y"][:, :, 0] - fwd["y"][:, :w, n]).max() < 1e-14
+        g1 = mdlstm_backward(f1, G[:, :w, n:n + 1])
+        assert np.abs(g1["dx"][:, :, 0] - g["dx"][:, :w, n]).max() < 1e-13
+        dW += g1["dW"]
+    assert np.abs(dW - g["dW"]).max() < 1e-12
+    x2 = x.copy()
+    x2[:, 3:, 1] = 99.0
+    x2[:, :, 2] = -99.0
+    f2 = mdlstm_forward(x2, *p, widths, du, dv)
+    g2 = mdlstm_backward(f2, G)
+    assert np.array_equal(f2["y"], fwd["y"])
+    for k in ("dW", "dRu", "dRv", "db"):
+        assert np.array_equal(g2[k], g[k])
+
+
+def test_four_directional_layer_concatenates_and_sums():
+    rng = _rng(8)
+    Hh, Ww, B, D, H = 3, 5, 2, 2, 3
+    x = rng.standard_normal((Hh, Ww, B, D))
+    params = [_params(rng, D, H) for _ in range(4)]
+    widths = np.array([5, 2])
+    G = rng.standard_normal((Hh, Ww, B, 4 * H))
+    y, fwds = mdlstm4_forward(x, params, widths)
+    grads, dx = mdlstm4_backward(fwds, G)
+    dx_sum = np.zeros_like(x)
+    for d, (du, dv) in enumerate(DIRECTIONS):
+        f = mdlstm_forward(x, *params[d], widths, du, dv)
+        assert np.array_equal(y[..., d * H:(d + 1) * H], f["y"])
+        g = mdlstm_backward(f, G[..., d * H:(d + 1) * H])
+        dx_sum += g["dx"]
+        for k in ("dW", "dRu", "dRv", "db"):
+            assert np.array_equal(grads[d][k], g[k])
+    assert np.abs(dx - dx_sum).max() < 1e-13
+    # directional derivative of sum(y * G) along a random direction in x
+    v = rng.standard_normal(x.shape)
+    eps = 1e-6
+    lp = (mdlstm4_forward(x + eps * v, params, widths)[0] * G).sum()
+    lm = (mdlstm4_forward(x - eps * v, params, widths)[0] * G).sum()
+    assert abs((lp - lm) / (2 * eps) - (dx * v).sum()) < 1e-7 * max(1.0, abs((dx * v).sum()))
