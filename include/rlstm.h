@@ -236,6 +236,42 @@ RLSTM_API int rlstm_last_timeout(const void* workspace);
 RLSTM_API int rlstm_set_first_piece(int steps);
 
 /*
+ * Two-dimensional (multidimensional) LSTM layer with four scan directions (Sec. 4.2: the state of
+ * pixel (u, v) depends on the states of its two predecessors (u-1, v) and (u, v-1) in scan order;
+ * all pixels of an anti-diagonal are computed together; the four directions and all images of the
+ * batch run at once).  The paper names the cell by citation only; the cell used is the
+ * multidimensional LSTM with one forget gate per dimension:
+ *     a  = b + x(u,v) W + h(u',v) R_u + h(u,v') R_v          5H wide, blocks i | f_u | f_v | o | g
+ *     c~ = f_u * c(u',v) + f_v * c(u,v') + i * g ,   h~ = o * tanh(c~)
+ * with (u', v') the predecessor row / column of the scan direction, sigmoid on i, f_u, f_v, o, tanh
+ * on g.  A predecessor outside the image contributes zero state.  All images have Hh rows; image n
+ * has widths[n] columns (clamped to [0, Ww]); a pixel at or beyond its image's width is outside the
+ * image (y = 0 there, no influence on anything), so every image is processed as if alone.
+ * Directions, in this order: (du, dv) = (+1,+1), (+1,-1), (-1,+1), (-1,-1).
+ *
+ * Layouts (device memory, fp32, row-major): x [Hh, Ww, B, D]; y, dy [Hh, Ww, B, 4H] (the four
+ * directions' outputs side by side in the order above); params / grads: 16 pointers, per direction
+ * W [D, 5H], R_u [H, 5H], R_v [H, 5H], b [5H]; widths [B] int32.  Gradients are plain sums and
+ * are overwritten.  dx [Hh, Ww, B, D] may be null.  reserve (rmdlstm_reserve_bytes) carries the
+ * gates, cell states and predecessor outputs from mdlstm_fwd to mdlstm_bwd, which overwrites it;
+ * workspace (rmdlstm_workspace_bytes) is scratch.  The caller owns all buffers; nothing is
+ * allocated and the device is not synchronised.
+ * Limits of the kernels: Hh <= 64, H <= 32, operand_dtype 0; other shapes return RLSTM_ERESIDENT
+ * (the size queries then return 0).  Other errors as for lstm_fwd.
+ */
+typedef struct rmdlstm_desc {
+  int32_t Hh, Ww, B, D, H;
+  int32_t operand_dtype;      /* 0 (fp32) */
+} rmdlstm_desc;
+RLSTM_API size_t rmdlstm_reserve_bytes(const rmdlstm_desc* d);
+RLSTM_API size_t rmdlstm_workspace_bytes(const rmdlstm_desc* d);
+RLSTM_API int mdlstm_fwd(const rmdlstm_desc* d, const float* x, const float* const* params, const int32_t* widths,
+                         float* y, void* reserve, void* workspace, void* hip_stream);
+RLSTM_API int mdlstm_bwd(const rmdlstm_desc* d, const float* x, const float* const* params, const int32_t* widths,
+                         void* reserve, const float* dy, float* dx, float* const* grads, void* workspace,
+                         void* hip_stream);
+
+/*
  * How the persistent engine lays a stack's recurrent passes out on this device (for reports).
  * out[8] (host): {groups of workgroups (directions * groups of sequences), sequences per group,
  * rows a group's tiles hold, units per workgroup, workgroups per group in the forward kernel,

@@ -79,9 +79,12 @@ def visiting_order(Hh: int, Ww: int, du: int, dv: int, order: str = "rows") -> L
     raise ValueError("order must be rows, columns or diagonals")
 
 
-def mdlstm_forward(x, W, Ru, Rv, b, widths, du: int, dv: int, order: str = "rows") -> Dict[str, np.ndarray]:
+def mdlstm_forward(x, W, Ru, Rv, b, widths, du: int, dv: int, order: str = "rows", dtype=F64) -> Dict[str, np.ndarray]:
     """One scan direction.  x [Hh,Ww,B,D]; W [D,5H]; Ru, Rv [H,5H]; b [5H]; widths [B].
-    Returns y, c [Hh,Ww,B,H], the activated gates [Hh,Ww,B,5H] and what the backward pass needs."""
+    Returns y, c [Hh,Ww,B,H], the activated gates [Hh,Ww,B,5H] and what the backward pass needs.
+    dtype: float64 is the oracle; float32 evaluates the same definition in single precision, which
+    tests use only to see how far rounding alone moves a result (to set tolerances)."""
+    F64 = dtype
     x = np.asarray(x, F64)
     W, Ru, Rv, b = (np.asarray(a, F64) for a in (W, Ru, Rv, b))
     widths = np.asarray(widths).astype(np.int64)
@@ -106,7 +109,7 @@ def mdlstm_forward(x, W, Ru, Rv, b, widths, du: int, dv: int, order: str = "rows
         h[u, v] = m * ht
         c[u, v] = m * ct
         gates[u, v] = np.concatenate([gi, gfu, gfv, go, gg], axis=1)
-    return dict(y=h, c=c, gates=gates, x=x, W=W, Ru=Ru, Rv=Rv, widths=widths, du=du, dv=dv)
+    return dict(y=h, c=c, gates=gates, x=x, W=W, Ru=Ru, Rv=Rv, widths=widths, du=du, dv=dv, dtype=dtype)
 
 
 def mdlstm_backward(fwd: Dict[str, np.ndarray], dy, order: str = "rows") -> Dict[str, np.ndarray]:
@@ -115,6 +118,7 @@ def mdlstm_backward(fwd: Dict[str, np.ndarray], dy, order: str = "rows") -> Dict
     x, W, Ru, Rv, widths = fwd["x"], fwd["W"], fwd["Ru"], fwd["Rv"], fwd["widths"]
     du, dv = fwd["du"], fwd["dv"]
     h, c, gates = fwd["y"], fwd["c"], fwd["gates"]
+    F64 = fwd["dtype"]
     dy = np.asarray(dy, F64)
     Hh, Ww, B, D = x.shape
     H = Ru.shape[0]
@@ -163,17 +167,17 @@ def mdlstm_backward(fwd: Dict[str, np.ndarray], dy, order: str = "rows") -> Dict
 Params = Sequence[Tuple[np.ndarray, np.ndarray, np.ndarray, np.ndarray]]   # per direction (W, Ru, Rv, b)
 
 
-def mdlstm4_forward(x, params: Params, widths, order: str = "rows"):
+def mdlstm4_forward(x, params: Params, widths, order: str = "rows", dtype=F64):
     """The four-directional layer: y [Hh,Ww,B,4H] = concatenation of the four scans, in the order of DIRECTIONS."""
     assert len(params) == 4
-    fwds = [mdlstm_forward(x, *params[d], widths, *DIRECTIONS[d], order=order) for d in range(4)]
+    fwds = [mdlstm_forward(x, *params[d], widths, *DIRECTIONS[d], order=order, dtype=dtype) for d in range(4)]
     return np.concatenate([f["y"] for f in fwds], axis=3), fwds
 
 
 def mdlstm4_backward(fwds, dy, order: str = "rows"):
     """Gradients of sum(y * dy): per direction dict(dW, dRu, dRv, db), and dx summed over the directions."""
     H = fwds[0]["Ru"].shape[0]
-    dy = np.asarray(dy, F64)
+    dy = np.asarray(dy, fwds[0]["dtype"])
     grads, dx = [], None
     for d in range(4):
         g = mdlstm_backward(fwds[d], dy[..., d * H:(d + 1) * H], order=order)

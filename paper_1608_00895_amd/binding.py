@@ -24,7 +24,7 @@ RLSTM_ENGINE_STEPWISE = 2
 EXPORTS = [
     "rlstm_reserve_bytes", "rlstm_workspace_bytes", "rblstm_reserve_bytes", "rblstm_workspace_bytes",
     "lstm_fwd", "lstm_bwd", "blstm_stack_fwd_bwd", "blstm_stack_fwd",
-    "rlstm_gemm_f32", "rlstm_gemm_bf16", "rlstm_copy_f32", "rlstm_profile_enable", "rlstm_profile_read", "rlstm_last_timeout", "rlstm_test_hook", "rlstm_set_first_piece", "rlstm_set_batch_groups", "rblstm_plan", "rlstm_exchange_floor_bytes", "rlstm_exchange_floor", "rlstm_resolve_engine", "rlstm_strerror", "rlstm_version",
+    "rlstm_gemm_f32", "rlstm_gemm_bf16", "rlstm_copy_f32", "rlstm_profile_enable", "rlstm_profile_read", "rlstm_last_timeout", "rlstm_test_hook", "rlstm_set_first_piece", "rlstm_set_batch_groups", "rmdlstm_reserve_bytes", "rmdlstm_workspace_bytes", "mdlstm_fwd", "mdlstm_bwd", "rblstm_plan", "rlstm_exchange_floor_bytes", "rlstm_exchange_floor", "rlstm_resolve_engine", "rlstm_strerror", "rlstm_version",
 ]
 
 
@@ -35,6 +35,11 @@ class rlstm_desc(ctypes.Structure):
 
 class rblstm_desc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("L", "T", "B", "D", "H", "operand_dtype", "engine")]
+
+
+class rmdlstm_desc(ctypes.Structure):
+    _fields_ = [("Hh", ctypes.c_int32), ("Ww", ctypes.c_int32), ("B", ctypes.c_int32), ("D", ctypes.c_int32),
+                ("H", ctypes.c_int32), ("operand_dtype", ctypes.c_int32)]
 
 
 class rlstm_profile_entry(ctypes.Structure):
@@ -92,6 +97,14 @@ def lib() -> ctypes.CDLL:
         L.rlstm_profile_read.argtypes = [ctypes.POINTER(rlstm_profile_entry), ip]
         L.rlstm_last_timeout.restype = ip
         L.rlstm_last_timeout.argtypes = [vp]
+        for name in ("rmdlstm_reserve_bytes", "rmdlstm_workspace_bytes"):
+            getattr(L, name).restype = ctypes.c_size_t
+            getattr(L, name).argtypes = [ctypes.POINTER(rmdlstm_desc)]
+        L.mdlstm_fwd.restype = ip
+        L.mdlstm_fwd.argtypes = [ctypes.POINTER(rmdlstm_desc), vp, ctypes.POINTER(vp), vp, vp, vp, vp, vp]
+        L.mdlstm_bwd.restype = ip
+        L.mdlstm_bwd.argtypes = [ctypes.POINTER(rmdlstm_desc), vp, ctypes.POINTER(vp), vp, vp, vp, vp,
+                                 ctypes.POINTER(vp), vp, vp]
         L.rblstm_plan.restype = ip
         L.rblstm_plan.argtypes = [ctypes.POINTER(rblstm_desc), ctypes.POINTER(ctypes.c_int32)]
         L.rlstm_exchange_floor_bytes.restype = ctypes.c_size_t
@@ -290,3 +303,27 @@ def rblstm_plan(desc) -> dict:
         raise RlstmError(rc, "rblstm_plan")
     keys = ("groups", "sequences_per_group", "rows", "units_per_workgroup", "members_fwd", "members_bwd", "Hp", "Hq")
     return dict(zip(keys, [int(v) for v in out]))
+
+
+def rmdlstm_reserve_bytes(desc) -> int:
+    return int(lib().rmdlstm_reserve_bytes(ctypes.byref(desc)))
+
+
+def rmdlstm_workspace_bytes(desc) -> int:
+    return int(lib().rmdlstm_workspace_bytes(ctypes.byref(desc)))
+
+
+def mdlstm_fwd(desc, x, params, widths, y, reserve, workspace, stream=None, check=True) -> int:
+    rc = lib().mdlstm_fwd(ctypes.byref(desc), _ptr(x), _ptr_array(params), _ptr(widths), _ptr(y), _ptr(reserve),
+                          _ptr(workspace), _stream(stream))
+    if check and rc != 0:
+        raise RlstmError(rc, "mdlstm_fwd")
+    return rc
+
+
+def mdlstm_bwd(desc, x, params, widths, reserve, dy, dx, grads, workspace, stream=None, check=True) -> int:
+    rc = lib().mdlstm_bwd(ctypes.byref(desc), _ptr(x), _ptr_array(params), _ptr(widths), _ptr(reserve), _ptr(dy),
+                          _ptr(dx), _ptr_array(grads), _ptr(workspace), _stream(stream))
+    if check and rc != 0:
+        raise RlstmError(rc, "mdlstm_bwd")
+    return rc

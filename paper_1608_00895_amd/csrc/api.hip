@@ -336,6 +336,114 @@ int rlstm_test_hook(int mute_workgroup, uint64_t wait_ticks) {
   return RLSTM_OK;
 }
 
+// ---- two-dimensional LSTM layer ------------------------------------------------
+static int check_md_desc(const rmdlstm_desc* d) {
+  if (!d) return RLSTM_ENULL;
+  if (d->Hh <= 0 || d->Ww <= 0 || d->B <= 0 || d->D <= 0 || d->H <= 0) return RLSTM_EDIM;
+  if ((long long)d->Hh * d->Ww * d->B > (1ll << 28)) return RLSTM_EDIM;
+  if (d->operand_dtype != 0) return RLSTM_EMODE;
+  MdShape s{d->Hh, d->Ww, d->B, d->H};
+  if (!mdlstm_supported(s)) return RLSTM_ERESIDENT;
+  return RLSTM_OK;
+}
+static size_t md_pixels(const rmdlstm_desc* d) { return (size_t)d->Hh * d->Ww * d->B; }
+static size_t md_dir_floats(const rmdlstm_desc* d) { return align_up(md_pixels(d) * 8 * d->H, 64); }
+static size_t md_splitk_floats(const rmdlstm_desc* d) {
+  const int mm = d->D > d->H ? d->D : d->H;
+  return align_up((size_t)16 * mm * 5 * d->H, 64);
+}
+static void md_dirs(const rmdlstm_desc* d, float* res, const float* const* params, MdDir* dirs) {
+  const size_t P = md_pixels(d);
+  for (int k = 0; k < 4; ++k) {
+    float* base = res + (size_t)k * md_dir_floats(d);
+    dirs[k] = MdDir{base, base + P * 5 * d->H, base + P * 6 * d->H, params[4 * k + 1], params[4 * k + 2]};
+  }
+}
+
+size_t rmdlstm_reserve_bytes(const rmdlstm_desc* d) {
+  if (check_md_desc(d) != RLSTM_OK) return 0;
+  return 4 * md_dir_floats(d) * sizeof(float);
+}
+
+size_t rmdlstm_workspace_bytes(const rmdlstm_desc* d) {
+  if (check_md_desc(d) != RLSTM_OK) return 0;
+  return md_splitk_floats(d) * sizeof(float);
+}
+
+int mdlstm_fwd(const rmdlstm_desc* d, const float* x, const float* const* params, const int32_t* widths,
+               float* y, void* reserve, void* workspace, void* hip_stream) {
+  int rc = check_md_desc(d);
+  if (rc != RLSTM_OK) return rc;
+  if (!x || !params || !widths || !y || !reserve || !workspace) return RLSTM_ENULL;
+  for (int i = 0; i < 16; ++i) if (!params[i]) return RLSTM_ENULL;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  int resident_err = 0;
+  const int P = (int)md_pixels(d), H = d->H;
+  MdDir dirs[4];
+  md_dirs(d, static_cast<float*>(reserve), params, dirs);
+  for (int k = 0; k < 4; ++k) {
+    GemmCall g;
+    g.M = P; g.N = 5 * H; g.K = d->D;
+    g.A = x; g.lda = d->D; g.B = params[4 * k + 0]; g.ldb = 5 * H; g.C = dirs[k].zg; g.ldc = 5 * H;
+    g.bias = params[4 * k + 3];
+    ProfScope ps(st, 0, 0, 1, 0, gemm_flop(g));
+    RLSTM_TRY(gemm(st, g));
+  }
+  MdShape s{d->Hh, d->Ww, d->B, H};
+  const int diag = d->Hh + d->Ww - 1;
+  ProfScope ps(st, 1, 0, 4, diag, 2.0 * P * 2 * H * 5 * H * 4);
+  RLSTM_TRY(mdlstm_forward(st, s, dirs, widths, y));
+  return RLSTM_OK;
+}
+
+int mdlstm_bwd(const rmdlstm_desc* d, const float* x, const float* const* params, const int32_t* widths,
+               void* reserve, const float* dy, float* dx, float* const* grads, void* workspace, void* hip_stream) {
+  int rc = check_md_desc(d);
+  if (rc != RLSTM_OK) return rc;
+  if (!x || !params || !widths || !reserve || !dy || !grads || !workspace) return RLSTM_ENULL;
+  for (int i = 0; i < 16; ++i) if (!params[i] || !grads[i]) return RLSTM_ENULL;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  int resident_err = 0;
+  const int P = (int)md_pixels(d), H = d->H, D = d->D;
+  MdDir dirs[4];
+  md_dirs(d, static_cast<float*>(reserve), params, dirs);
+  MdShape s{d->Hh, d->Ww, d->B, H};
+  {
+    ProfScope ps(st, 2, 0, 4, d->Hh + d->Ww - 1, 2.0 * P * 2 * H * 5 * H * 4);
+    RLSTM_TRY(mdlstm_backward(st, s, dirs, widths, dy));
+  }
+  float* skws = static_cast<float*>(workspace);
+  const size_t skfloats = md_splitk_floats(d);
+  for (int k = 0; k < 4; ++k) {
+    GemmCall g;
+    g.transA = true;
+    g.M = D; g.N = 5 * H; g.K = P;
+    g.A = x; g.lda = D; g.B = dirs[k].zg; g.ldb = 5 * H; g.C = grads[4 * k + 0]; g.ldc = 5 * H;
+    g.splitk_ws = skws; g.splitk_floats = skfloats;
+    {
+      ProfScope ps(st, 4, 0, 1, 0, gemm_flop(g));
+      RLSTM_TRY(gemm(st, g));
+    }
+    for (int w = 0; w < 2; ++w) {      // d R_u from the vertical predecessors' h, d R_v from the horizontal ones'
+      GemmCall r = g;
+      r.M = H; r.A = dirs[k].hc + (size_t)w * H; r.lda = 2 * H; r.C = grads[4 * k + 1 + w];
+      ProfScope ps(st, 5, 0, 1, 0, gemm_flop(r));
+      RLSTM_TRY(gemm(st, r));
+    }
+    RLSTM_TRY(column_sum(st, dirs[k].zg, (size_t)P, 5 * H, 5 * H, grads[4 * k + 3]));
+    if (dx) {
+      GemmCall q;
+      q.transB = true;
+      q.M = P; q.N = D; q.K = 5 * H;
+      q.A = dirs[k].zg; q.lda = 5 * H; q.B = params[4 * k + 0]; q.ldb = 5 * H; q.C = dx; q.ldc = D;
+      q.accumulate = k > 0;
+      ProfScope ps(st, 3, 0, 1, 0, gemm_flop(q));
+      RLSTM_TRY(gemm(st, q));
+    }
+  }
+  return RLSTM_OK;
+}
+
 int rlstm_copy_f32(float* dst, const float* src, size_t n, void* hip_stream) {
   if (!dst || !src) return RLSTM_ENULL;
   int resident_err = 0;

@@ -114,6 +114,23 @@ hipError_t copy_f32(hipStream_t stream, float* dst, const float* src, size_t n);
 // zero the timeout flag
 hipError_t clear_flag(hipStream_t stream, unsigned* flag);
 
+// ---------------------------------------------------------------------------
+// Two-dimensional LSTM layer: the scans over the anti-diagonals (mdlstm.hip).
+// P = Hh * Ww * B pixel slots, pixel (u, v) of image n at index (u * Ww + v) * B + n.
+// ---------------------------------------------------------------------------
+struct MdShape { int Hh, Ww, B, H; };
+struct MdDir {
+  float* zg;          // [P, 5H] in: b + x W ; forward out: gates i|f_u|f_v|o|g ; backward out: d loss / d a
+  float* c;           // [P, H]
+  float* hc;          // [P, 2H] forward out: h of the vertical | horizontal predecessor of every pixel
+  const float* Ru;    // [H, 5H]
+  const float* Rv;    // [H, 5H]
+};
+bool mdlstm_supported(const MdShape& s);
+// dirs[4] in the order (du, dv) = (+,+), (+,-), (-,+), (-,-); y, dy: [P, 4H]
+hipError_t mdlstm_forward(hipStream_t stream, const MdShape& s, const MdDir* dirs, const int32_t* widths, float* y);
+hipError_t mdlstm_backward(hipStream_t stream, const MdShape& s, const MdDir* dirs, const int32_t* widths, const float* dy);
+
 // bare exchange of the persistent kernels' step chain (measurement aid, see exchange_probe.hip)
 size_t exchange_probe_bytes(int groups, int members, int tile_bytes);
 hipError_t exchange_probe(hipStream_t stream, int groups, int members, int tile_bytes, int read_bytes, int steps,

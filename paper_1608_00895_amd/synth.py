@@ -124,3 +124,53 @@ def small_blstm(seed: int = 11, *, L: int = 2, B: int = 5, D: int = 12, H: int =
     """A ragged multi-layer BLSTM small enough for the oracle to finish in well under a second."""
     return make_workload(f"small_blstm_s{seed}", L=L, B=B, D=D, H=H, len_lo=len_lo, len_hi=len_hi,
                          wscale=wscale, seed=seed, bias_scale=bias_scale, T=T)
+
+
+@dataclass
+class ImageWorkload:
+    """Batch of grayscale-like images for the two-dimensional LSTM layer (four scan directions)."""
+    name: str
+    Hh: int                # rows of every image
+    Ww: int                # padded width (= max widths)
+    B: int                 # images per minibatch
+    D: int                 # values per pixel
+    H: int                 # units per direction
+    widths: np.ndarray     # int32 [B]
+    x: np.ndarray          # float32 [Hh, Ww, B, D], zero beyond each image's width
+    # params[d] = (W [D, 5H], Ru [H, 5H], Rv [H, 5H], b [5H]) float32, d over the four scan directions
+    params: List[Tuple[np.ndarray, np.ndarray, np.ndarray, np.ndarray]] = field(default_factory=list)
+    G: Optional[np.ndarray] = None  # float32 [Hh, Ww, B, 4H]: loss = sum(y * G)
+
+    @property
+    def pixels(self) -> int:
+        return int(self.widths.sum()) * self.Hh
+
+
+def make_image_workload(name: str, *, Hh: int, B: int, D: int, H: int, w_lo: int, w_hi: int, wscale: float,
+                        seed: int, bias_scale: float = 0.0) -> ImageWorkload:
+    """Widths are uniform integers in [w_lo, w_hi]; image 0 is forced to w_hi so that the padded width is
+    the same for every seed.  Pixel values are uniform in [0, 1).  Draw order: widths, x, then per scan
+    direction W, Ru, Rv, b, then G."""
+    rng = np.random.Generator(np.random.Philox(seed))
+    widths = rng.integers(w_lo, w_hi + 1, size=B).astype(np.int32)
+    widths[0] = w_hi
+    Ww = int(w_hi)
+    x = rng.random((Hh, Ww, B, D), dtype=np.float32)
+    for n in range(B):
+        x[:, widths[n]:, n, :] = 0.0
+    params = []
+    for _ in range(4):
+        W = rng.uniform(-wscale, wscale, (D, 5 * H)).astype(np.float32)
+        Ru = rng.uniform(-wscale, wscale, (H, 5 * H)).astype(np.float32)
+        Rv = rng.uniform(-wscale, wscale, (H, 5 * H)).astype(np.float32)
+        b = (rng.uniform(-bias_scale, bias_scale, (5 * H,)) if bias_scale else np.zeros(5 * H)).astype(np.float32)
+        params.append((W, Ru, Rv, b))
+    G = rng.standard_normal((Hh, Ww, B, 4 * H)).astype(np.float32)
+    return ImageWorkload(name, Hh, Ww, B, D, H, widths, x, params, G)
+
+
+def config5() -> ImageWorkload:
+    """Config 5: two-dimensional LSTM, 4 scan directions, images of height 64 and width uniform in
+    [200, 800], pixel values U(0,1), B = 8, H = 32 per direction, fp32."""
+    return make_image_workload("config5_mdlstm_h64_B8_H32", Hh=64, B=8, D=1, H=32, w_lo=200, w_hi=800,
+                               wscale=0.1, seed=5)
