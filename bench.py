@@ -63,12 +63,102 @@ def cpu_baseline(wl_full, seconds_budget=20.0):
                       f"sequences ({frames} frames), numpy fp64 forward+backward, {dt:.1f} s"}
 
 
+def bench_config5(args):
+    """The two-dimensional LSTM layer (four scan directions) on config 5: one step = mdlstm_fwd + mdlstm_bwd
+    on one batch of 8 images resident in HBM, gradients of every parameter, no dx (the layer is the bottom one)."""
+    import numpy as np
+    import torch
+    from paper_1608_00895_amd import binding as rl
+    from paper_1608_00895_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    wl = synth.config5()
+    log(f"workload {wl.name}: Hh={wl.Hh} Ww={wl.Ww} B={wl.B} D={wl.D} H={wl.H} pixels={wl.pixels}")
+    desc = rl.rmdlstm_desc(Hh=wl.Hh, Ww=wl.Ww, B=wl.B, D=wl.D, H=wl.H, operand_dtype=0)
+    x = torch.from_numpy(wl.x).to(dev)
+    widths = torch.from_numpy(wl.widths).to(dev)
+    params = [torch.from_numpy(a).to(dev) for p in wl.params for a in p]
+    grads = [torch.empty_like(p) for p in params]
+    G = torch.from_numpy(wl.G).to(dev)
+    y = torch.empty((wl.Hh, wl.Ww, wl.B, 4 * wl.H), device=dev)
+    reserve = torch.empty(rl.rmdlstm_reserve_bytes(desc), dtype=torch.uint8, device=dev)
+    ws = torch.empty(rl.rmdlstm_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+
+    def step():
+        rl.mdlstm_fwd(desc, x, params, widths, y, reserve, ws)
+        rl.mdlstm_bwd(desc, x, params, widths, reserve, G, None, grads, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    rl.rlstm_profile_read()
+    rl.rlstm_profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    rl.rlstm_profile_enable(False)
+    prof = rl.rlstm_profile_read(1 << 16)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    by_kind = {}
+    for kind, layer, ndir, ms, nsteps, flop in prof:
+        d = by_kind.setdefault(kind, {"ms": 0.0, "launches": 0, "flop": 0.0, "rsteps": 0})
+        d["ms"] += ms; d["launches"] += 1; d["flop"] += flop; d["rsteps"] += nsteps
+    names = {0: "input_projection", 1: "mdlstm_forward_scan", 2: "mdlstm_backward_scan", 3: "input_gradient",
+             4: "weight_gradient", 5: "recurrent_weight_gradient"}
+    kernels = []
+    # the scans only do arithmetic inside the images: price them with the valid pixels, not the padded slots
+    valid_frac = wl.pixels / float(wl.Hh * wl.Ww * wl.B)
+    for kind, d in sorted(by_kind.items()):
+        flop = d["flop"] * (valid_frac if kind in (1, 2) else 1.0)
+        e = {"kernel": names[kind], "launches_per_step": d["launches"] / args.steps, "avg_ms": d["ms"] / d["launches"],
+             "ms_per_step": d["ms"] / args.steps, "tflops": flop / (d["ms"] * 1e-3) / 1e12}
+        if kind in (1, 2):
+            e["diagonals_per_launch"] = d["rsteps"] / d["launches"]
+            e["diagonal_us"] = 1e3 * d["ms"] / d["rsteps"]
+        kernels.append(e)
+        log(e)
+    dom = max(kernels, key=lambda e: e["ms_per_step"])
+    roofline = {"kernel": dom["kernel"], "bound": "mfma", "achieved": dom["tflops"], "peak": PEAK_FP32_MFMA_TFLOPS,
+                "unit": "TFLOP/s", "frac": dom["tflops"] / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                "avg_launch_ms": dom["avg_ms"],
+                "note": "one workgroup per (scan direction, image): 32 of the 256 CUs work, and the chain of "
+                        "anti-diagonals is serial; priced against the whole chip's fp32 MFMA peak with "
+                        "2 * 2H * 5H FLOP per valid pixel and direction"}
+    out = {"metric": "MDLSTM train pixels/sec (fwd+bwd), 4 scan directions", "value": wl.pixels / (ms_per_step * 1e-3),
+           "unit": "pixels/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": wl.name, "height": wl.Hh, "padded_width": wl.Ww, "images": wl.B,
+                      "units_per_direction": wl.H, "valid_pixels": wl.pixels,
+                      "padded_pixel_slots": wl.Hh * wl.Ww * wl.B},
+           "roofline": roofline, "kernels": kernels}
+    if not args.no_cpu_baseline:
+        from threadpoolctl import threadpool_info
+        from oracle import mdlstm4_backward, mdlstm4_forward
+        wc = 24                                    # the oracle on the first 24 columns of every image
+        p64 = [tuple(a.astype(np.float64) for a in p) for p in wl.params]
+        wcrop = np.minimum(wl.widths, wc)
+        t0 = time.perf_counter()
+        yc, fw = mdlstm4_forward(wl.x[:, :wc].astype(np.float64), p64, wcrop)
+        mdlstm4_backward(fw, wl.G[:, :wc].astype(np.float64))
+        dt = time.perf_counter() - t0
+        threads = max([i.get("num_threads", 1) for i in threadpool_info() if i.get("user_api") == "blas"] or [1])
+        px = int(wcrop.sum()) * wl.Hh
+        out["cpu_baseline"] = {"value": px / dt, "unit": "pixels/s", "cores": int(threads), "kind": "oracle",
+                               "sample": f"{wl.name}: first {wc} columns of all {wl.B} images ({px} pixels), "
+                                         f"numpy fp64 forward+backward, {dt:.1f} s"}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config3", choices=["config2", "config3", "config4"])
+    ap.add_argument("--workload", default="config3", choices=["config2", "config3", "config4", "config5"])
     ap.add_argument("--engine", type=int, default=0)
     ap.add_argument("--one-stream", action="store_true")
     ap.add_argument("--first-piece", type=int, default=None,
@@ -84,6 +174,9 @@ def main():
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
+
+    if args.workload == "config5":
+        return bench_config5(args)
 
     import numpy as np
     import torch

@@ -349,9 +349,11 @@ static int check_md_desc(const rmdlstm_desc* d) {
 static size_t md_pixels(const rmdlstm_desc* d) { return (size_t)d->Hh * d->Ww * d->B; }
 static size_t md_dir_floats(const rmdlstm_desc* d) { return align_up(md_pixels(d) * 8 * d->H, 64); }
 static size_t md_splitk_floats(const rmdlstm_desc* d) {
+  // the weight gradients are tiny matrices summed over every pixel: room for 512 partial results
   const int mm = d->D > d->H ? d->D : d->H;
-  return align_up((size_t)16 * mm * 5 * d->H, 64);
+  return align_up((size_t)512 * mm * 5 * d->H, 64);
 }
+static size_t md_dbpart_floats(const rmdlstm_desc* d) { return align_up((size_t)4 * d->B * 5 * d->H, 64); }
 static void md_dirs(const rmdlstm_desc* d, float* res, const float* const* params, MdDir* dirs) {
   const size_t P = md_pixels(d);
   for (int k = 0; k < 4; ++k) {
@@ -367,7 +369,7 @@ size_t rmdlstm_reserve_bytes(const rmdlstm_desc* d) {
 
 size_t rmdlstm_workspace_bytes(const rmdlstm_desc* d) {
   if (check_md_desc(d) != RLSTM_OK) return 0;
-  return md_splitk_floats(d) * sizeof(float);
+  return (md_splitk_floats(d) + md_dbpart_floats(d)) * sizeof(float);
 }
 
 int mdlstm_fwd(const rmdlstm_desc* d, const float* x, const float* const* params, const int32_t* widths,
@@ -408,12 +410,13 @@ int mdlstm_bwd(const rmdlstm_desc* d, const float* x, const float* const* params
   MdDir dirs[4];
   md_dirs(d, static_cast<float*>(reserve), params, dirs);
   MdShape s{d->Hh, d->Ww, d->B, H};
-  {
-    ProfScope ps(st, 2, 0, 4, d->Hh + d->Ww - 1, 2.0 * P * 2 * H * 5 * H * 4);
-    RLSTM_TRY(mdlstm_backward(st, s, dirs, widths, dy));
-  }
   float* skws = static_cast<float*>(workspace);
   const size_t skfloats = md_splitk_floats(d);
+  {
+    float* db[4] = {grads[3], grads[7], grads[11], grads[15]};
+    ProfScope ps(st, 2, 0, 4, d->Hh + d->Ww - 1, 2.0 * P * 2 * H * 5 * H * 4);
+    RLSTM_TRY(mdlstm_backward(st, s, dirs, widths, dy, skws + skfloats, db));
+  }
   for (int k = 0; k < 4; ++k) {
     GemmCall g;
     g.transA = true;
@@ -430,7 +433,6 @@ int mdlstm_bwd(const rmdlstm_desc* d, const float* x, const float* const* params
       ProfScope ps(st, 5, 0, 1, 0, gemm_flop(r));
       RLSTM_TRY(gemm(st, r));
     }
-    RLSTM_TRY(column_sum(st, dirs[k].zg, (size_t)P, 5 * H, 5 * H, grads[4 * k + 3]));
     if (dx) {
       GemmCall q;
       q.transB = true;

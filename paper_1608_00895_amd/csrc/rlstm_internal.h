@@ -129,7 +129,10 @@ struct MdDir {
 bool mdlstm_supported(const MdShape& s);
 // dirs[4] in the order (du, dv) = (+,+), (+,-), (-,+), (-,-); y, dy: [P, 4H]
 hipError_t mdlstm_forward(hipStream_t stream, const MdShape& s, const MdDir* dirs, const int32_t* widths, float* y);
-hipError_t mdlstm_backward(hipStream_t stream, const MdShape& s, const MdDir* dirs, const int32_t* widths, const float* dy);
+// dbpart: scratch of mdlstm_dbpart_floats(); db[4]: bias gradients [5H] per direction
+size_t mdlstm_dbpart_floats(const MdShape& s);
+hipError_t mdlstm_backward(hipStream_t stream, const MdShape& s, const MdDir* dirs, const int32_t* widths, const float* dy,
+                           float* dbpart, float* const* db);
 
 // bare exchange of the persistent kernels' step chain (measurement aid, see exchange_probe.hip)
 size_t exchange_probe_bytes(int groups, int members, int tile_bytes);

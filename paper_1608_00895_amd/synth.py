@@ -147,10 +147,10 @@ class ImageWorkload:
 
 
 def make_image_workload(name: str, *, Hh: int, B: int, D: int, H: int, w_lo: int, w_hi: int, wscale: float,
-                        seed: int, bias_scale: float = 0.0) -> ImageWorkload:
+                        seed: int, bias_scale: float = 0.0, forget_bias: float = 0.0) -> ImageWorkload:
     """Widths are uniform integers in [w_lo, w_hi]; image 0 is forced to w_hi so that the padded width is
     the same for every seed.  Pixel values are uniform in [0, 1).  Draw order: widths, x, then per scan
-    direction W, Ru, Rv, b, then G."""
+    direction W, Ru, Rv, b, then G.  ``forget_bias`` is added to the bias of both forget-gate blocks."""
     rng = np.random.Generator(np.random.Philox(seed))
     widths = rng.integers(w_lo, w_hi + 1, size=B).astype(np.int32)
     widths[0] = w_hi
@@ -164,6 +164,7 @@ def make_image_workload(name: str, *, Hh: int, B: int, D: int, H: int, w_lo: int
         Ru = rng.uniform(-wscale, wscale, (H, 5 * H)).astype(np.float32)
         Rv = rng.uniform(-wscale, wscale, (H, 5 * H)).astype(np.float32)
         b = (rng.uniform(-bias_scale, bias_scale, (5 * H,)) if bias_scale else np.zeros(5 * H)).astype(np.float32)
+        b[H:3 * H] += np.float32(forget_bias)
         params.append((W, Ru, Rv, b))
     G = rng.standard_normal((Hh, Ww, B, 4 * H)).astype(np.float32)
     return ImageWorkload(name, Hh, Ww, B, D, H, widths, x, params, G)
@@ -171,6 +172,8 @@ def make_image_workload(name: str, *, Hh: int, B: int, D: int, H: int, w_lo: int
 
 def config5() -> ImageWorkload:
     """Config 5: two-dimensional LSTM, 4 scan directions, images of height 64 and width uniform in
-    [200, 800], pixel values U(0,1), B = 8, H = 32 per direction, fp32."""
+    [200, 800], pixel values U(0,1), B = 8, H = 32 per direction, fp32.  Weights U(-0.1, 0.1); the two
+    forget gates start at bias -1 (f_u + f_v < 1): with zero forget biases the cell state of a 64 x 800
+    image is not contractive and float32 arithmetic itself is 1e-3 .. 1e-2 away from float64."""
     return make_image_workload("config5_mdlstm_h64_B8_H32", Hh=64, B=8, D=1, H=32, w_lo=200, w_hi=800,
-                               wscale=0.1, seed=5)
+                               wscale=0.1, seed=5, forget_bias=-1.0)

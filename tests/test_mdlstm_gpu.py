@@ -124,3 +124,27 @@ def test_mdlstm_argument_errors():
     assert rl.mdlstm_fwd(ok, None, [t] * 16, t, t, t, t, check=False) == -1
     bad = rl.rmdlstm_desc(Hh=8, Ww=0, B=1, D=1, H=8, operand_dtype=0)
     assert rl.mdlstm_fwd(bad, t, [t] * 16, t, t, t, t, check=False) == -2
+
+
+def test_config5_full_size_against_oracle_samples():
+    """Config 5 at full size (the shape bench.py --workload config5 times) against sampled entries of every
+    output of the oracle (tests/golden/config5_oracle_samples.npz, written by make_config5_golden.py)."""
+    import os
+    wl = synth.config5()
+    gold = np.load(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "config5_oracle_samples.npz"))
+    assert np.array_equal(gold["widths"], wl.widths)
+    got = run_layer(wl)
+    errs = {}
+
+    def cmp(name, arr):
+        flat = arr.reshape(-1).astype(np.float64)
+        errs[name] = float(np.abs(flat[gold[name + "_idx"]] - gold[name + "_val"]).max() / gold[name + "_max"])
+
+    cmp("y", got["y"])
+    cmp("dx", got["dx"])
+    for d in range(4):
+        for i, k in enumerate(("dW", "dRu", "dRv", "db")):
+            cmp(f"{k}_{d}", got["grads"][4 * d + i])
+    print("config5 errors", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    assert errs["y"] < TOL_FWD, errs
+    assert all(v < TOL_GRAD for k, v in errs.items() if k != "y"), errs
