@@ -347,18 +347,22 @@ static int check_md_desc(const rmdlstm_desc* d) {
   return RLSTM_OK;
 }
 static size_t md_pixels(const rmdlstm_desc* d) { return (size_t)d->Hh * d->Ww * d->B; }
-static size_t md_dir_floats(const rmdlstm_desc* d) { return align_up(md_pixels(d) * 8 * d->H, 64); }
+// For a narrow input x is kept next to [h_up | h_left] so that one product yields dR_u, dR_v and dW.
+static bool md_fused(const rmdlstm_desc* d) { return d->D <= 32; }
+static int md_stride(const rmdlstm_desc* d) { return (int)align_up((size_t)2 * d->H + (md_fused(d) ? d->D : 0), 4); }
+static size_t md_dir_floats(const rmdlstm_desc* d) { return align_up(md_pixels(d) * (6 * d->H + md_stride(d)), 64); }
+static int md_grad_rows(const rmdlstm_desc* d) { return md_fused(d) ? 2 * d->H + d->D : (d->D > d->H ? d->D : d->H); }
 static size_t md_splitk_floats(const rmdlstm_desc* d) {
-  // the weight gradients are tiny matrices summed over every pixel: room for 512 partial results
-  const int mm = d->D > d->H ? d->D : d->H;
-  return align_up((size_t)512 * mm * 5 * d->H, 64);
+  // the weight gradients are tiny matrices summed over every pixel: room for 256 partial results
+  return align_up((size_t)256 * md_grad_rows(d) * 5 * d->H, 64);
 }
+static size_t md_stacked_floats(const rmdlstm_desc* d) { return align_up((size_t)4 * (2 * d->H + d->D) * 5 * d->H, 64); }
 static size_t md_dbpart_floats(const rmdlstm_desc* d) { return align_up((size_t)4 * d->B * 5 * d->H, 64); }
 static void md_dirs(const rmdlstm_desc* d, float* res, const float* const* params, MdDir* dirs) {
   const size_t P = md_pixels(d);
   for (int k = 0; k < 4; ++k) {
     float* base = res + (size_t)k * md_dir_floats(d);
-    dirs[k] = MdDir{base, base + P * 5 * d->H, base + P * 6 * d->H, params[4 * k + 1], params[4 * k + 2]};
+    dirs[k] = MdDir{base, base + P * 5 * d->H, base + P * 6 * d->H, params[4 * k + 1], params[4 * k + 2]};   // zg | c | hc
   }
 }
 
@@ -369,7 +373,7 @@ size_t rmdlstm_reserve_bytes(const rmdlstm_desc* d) {
 
 size_t rmdlstm_workspace_bytes(const rmdlstm_desc* d) {
   if (check_md_desc(d) != RLSTM_OK) return 0;
-  return (md_splitk_floats(d) + md_dbpart_floats(d)) * sizeof(float);
+  return (md_splitk_floats(d) + md_dbpart_floats(d) + md_stacked_floats(d)) * sizeof(float);
 }
 
 int mdlstm_fwd(const rmdlstm_desc* d, const float* x, const float* const* params, const int32_t* widths,
@@ -391,7 +395,8 @@ int mdlstm_fwd(const rmdlstm_desc* d, const float* x, const float* const* params
     ProfScope ps(st, 0, 0, 1, 0, gemm_flop(g));
     RLSTM_TRY(gemm(st, g));
   }
-  MdShape s{d->Hh, d->Ww, d->B, H};
+  MdShape s{d->Hh, d->Ww, d->B, H, md_stride(d)};
+  if (md_fused(d)) RLSTM_TRY(mdlstm_copy_x(st, s, dirs, x, d->D));
   const int diag = d->Hh + d->Ww - 1;
   ProfScope ps(st, 1, 0, 4, diag, 2.0 * P * 2 * H * 5 * H * 4);
   RLSTM_TRY(mdlstm_forward(st, s, dirs, widths, y));
@@ -409,7 +414,7 @@ int mdlstm_bwd(const rmdlstm_desc* d, const float* x, const float* const* params
   const int P = (int)md_pixels(d), H = d->H, D = d->D;
   MdDir dirs[4];
   md_dirs(d, static_cast<float*>(reserve), params, dirs);
-  MdShape s{d->Hh, d->Ww, d->B, H};
+  MdShape s{d->Hh, d->Ww, d->B, H, md_stride(d)};
   float* skws = static_cast<float*>(workspace);
   const size_t skfloats = md_splitk_floats(d);
   {
@@ -417,21 +422,31 @@ int mdlstm_bwd(const rmdlstm_desc* d, const float* x, const float* const* params
     ProfScope ps(st, 2, 0, 4, d->Hh + d->Ww - 1, 2.0 * P * 2 * H * 5 * H * 4);
     RLSTM_TRY(mdlstm_backward(st, s, dirs, widths, dy, skws + skfloats, db));
   }
+  float* stacked = skws + skfloats + md_dbpart_floats(d);
+  const size_t stacked_one = (size_t)(2 * H + D) * 5 * H;
   for (int k = 0; k < 4; ++k) {
     GemmCall g;
     g.transA = true;
-    g.M = D; g.N = 5 * H; g.K = P;
-    g.A = x; g.lda = D; g.B = dirs[k].zg; g.ldb = 5 * H; g.C = grads[4 * k + 0]; g.ldc = 5 * H;
+    g.N = 5 * H; g.K = P;
+    g.B = dirs[k].zg; g.ldb = 5 * H; g.ldc = 5 * H;
     g.splitk_ws = skws; g.splitk_floats = skfloats;
-    {
-      ProfScope ps(st, 4, 0, 1, 0, gemm_flop(g));
+    if (md_fused(d)) {
+      // [h_up | h_left | x]^T dA: d R_u, d R_v and d W stacked
+      g.M = 2 * H + D; g.A = dirs[k].hc; g.lda = s.S; g.C = stacked + (size_t)k * stacked_one;
+      ProfScope ps(st, 5, 0, 1, 0, gemm_flop(g));
       RLSTM_TRY(gemm(st, g));
-    }
-    for (int w = 0; w < 2; ++w) {      // d R_u from the vertical predecessors' h, d R_v from the horizontal ones'
-      GemmCall r = g;
-      r.M = H; r.A = dirs[k].hc + (size_t)w * H; r.lda = 2 * H; r.C = grads[4 * k + 1 + w];
-      ProfScope ps(st, 5, 0, 1, 0, gemm_flop(r));
-      RLSTM_TRY(gemm(st, r));
+    } else {
+      g.M = D; g.A = x; g.lda = D; g.C = grads[4 * k + 0];
+      {
+        ProfScope ps(st, 4, 0, 1, 0, gemm_flop(g));
+        RLSTM_TRY(gemm(st, g));
+      }
+      for (int w = 0; w < 2; ++w) {      // d R_u from the vertical predecessors' h, d R_v from the horizontal ones'
+        GemmCall r = g;
+        r.M = H; r.A = dirs[k].hc + (size_t)w * H; r.lda = s.S; r.C = grads[4 * k + 1 + w];
+        ProfScope ps(st, 5, 0, 1, 0, gemm_flop(r));
+        RLSTM_TRY(gemm(st, r));
+      }
     }
     if (dx) {
       GemmCall q;
@@ -442,6 +457,14 @@ int mdlstm_bwd(const rmdlstm_desc* d, const float* x, const float* const* params
       ProfScope ps(st, 3, 0, 1, 0, gemm_flop(q));
       RLSTM_TRY(gemm(st, q));
     }
+  }
+  if (md_fused(d)) {
+    const float* src[4]; float* dRu[4]; float* dRv[4]; float* dWp[4];
+    for (int k = 0; k < 4; ++k) {
+      src[k] = stacked + (size_t)k * stacked_one;
+      dWp[k] = grads[4 * k + 0]; dRu[k] = grads[4 * k + 1]; dRv[k] = grads[4 * k + 2];
+    }
+    RLSTM_TRY(mdlstm_scatter_grads(st, D, H, src, dRu, dRv, dWp));
   }
   return RLSTM_OK;
 }

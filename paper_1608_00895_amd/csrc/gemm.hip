@@ -531,7 +531,7 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
     const size_t per = (size_t)g.M * g.N;
     const size_t max_by_ws = g.splitk_floats / per;
     if ((size_t)slices > max_by_ws) slices = (int)max_by_ws;
-    if (slices > 512) slices = 512;
+    if (slices > 256) slices = 256;
     if (slices < 1) slices = 1;
   }
   if (slices > 1) {

@@ -41,14 +41,14 @@ __device__ __forceinline__ float md_tanh(float u) { return 2.0f * __builtin_amdg
 struct MdParams {
   float* zg[4];            // [P, 5H]: X W + b -> gates i|f_u|f_v|o|g -> d a
   float* c[4];             // [P, H]
-  float* hc[4];            // [P, 2H]: h_up | h_left of every pixel
+  float* hc[4];            // [P, S]: h_up | h_left (| x) of every pixel, row stride S
   const float* Ru[4];      // [H, 5H]
   const float* Rv[4];
   float* y;                // forward: [P, 4H] output
   const float* dy;         // backward: [P, 4H]
   float* dbpart;           // backward: [4][B][5H] bias gradient of every (direction, image)
   const int32_t* widths;   // [B]
-  int Hh, Ww, B, H;
+  int Hh, Ww, B, H, S;
 };
 
 // scan coordinates (row r, column q) of image n, direction (du, dv), image width wn -> pixel index
@@ -177,8 +177,8 @@ __global__ __launch_bounds__(256 * HT) void mdlstm_fwd_kernel(MdParams p) {
       st4<VEC>(zrow + 3 * H, go, nv); st4<VEC>(zrow + 4 * H, gg, nv);
       st4<VEC>(cd + pix * H + j0, ct, nv);
       st4<VEC>(p.y + pix * 4 * H + d * H + j0, ht, nv);
-      st4<VEC>(hcd + pix * 2 * H + j0, h_up, nv);
-      st4<VEC>(hcd + pix * 2 * H + H + j0, h_left, nv);
+      st4<VEC>(hcd + pix * p.S + j0, h_up, nv);
+      st4<VEC>(hcd + pix * p.S + H + j0, h_left, nv);
     }
     prefetch(s + 1);
   }
@@ -191,8 +191,8 @@ __global__ __launch_bounds__(256 * HT) void mdlstm_fwd_kernel(MdParams p) {
     const size_t pix = ((size_t)u * p.Ww + v) * p.B + n;
     p.y[pix * 4 * H + d * H + jj] = 0.f;
     cd[pix * H + jj] = 0.f;
-    hcd[pix * 2 * H + jj] = 0.f;
-    hcd[pix * 2 * H + H + jj] = 0.f;
+    hcd[pix * p.S + jj] = 0.f;
+    hcd[pix * p.S + H + jj] = 0.f;
   }
 }
 
@@ -355,6 +355,33 @@ __global__ __launch_bounds__(256) void mdlstm_db_sum_kernel(MdDbParams p) {
   }
 }
 
+// x [P, D] into columns [2H, 2H + D) of the four [P, S] predecessor-output arrays, so that
+// [h_up | h_left | x]^T dA gives dR_u, dR_v and dW in one product
+struct MdXCopyParams { float* hc[4]; const float* x; size_t P; int D, H, S; };
+__global__ __launch_bounds__(256) void mdlstm_xcopy_kernel(MdXCopyParams p) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= p.P * p.D) return;
+  const size_t pix = idx / p.D;
+  const int i = (int)(idx % p.D);
+  const float v = p.x[idx];
+#pragma unroll
+  for (int d = 0; d < 4; ++d) p.hc[d][pix * p.S + 2 * p.H + i] = v;
+}
+// rows of the stacked gradient [2H + D, 5H] of every direction to the caller's dR_u, dR_v, dW
+struct MdScatterParams { const float* stacked[4]; float* dRu[4]; float* dRv[4]; float* dW[4]; int D, H; };
+__global__ __launch_bounds__(256) void mdlstm_scatter_kernel(MdScatterParams p) {
+  const int n5 = 5 * p.H, rows = 2 * p.H + p.D;
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= rows * n5) return;
+  const int row = idx / n5, col = idx % n5;
+  for (int d = 0; d < 4; ++d) {
+    const float v = p.stacked[d][idx];
+    if (row < p.H) p.dRu[d][row * n5 + col] = v;
+    else if (row < 2 * p.H) p.dRv[d][(row - p.H) * n5 + col] = v;
+    else p.dW[d][(row - 2 * p.H) * n5 + col] = v;
+  }
+}
+
 size_t md_lds_fwd(int HT) {
   const int HP = 16 * HT, NG = 5 * HP;
   return ((size_t)2 * HP * (NG + 8) + (size_t)4 * (kRows + 1) * (HP + 1)) * sizeof(float);
@@ -380,7 +407,7 @@ MdParams md_params(const MdShape& s, const MdDir* dirs, const int32_t* widths) {
   for (int d = 0; d < 4; ++d) {
     p.zg[d] = dirs[d].zg; p.c[d] = dirs[d].c; p.hc[d] = dirs[d].hc; p.Ru[d] = dirs[d].Ru; p.Rv[d] = dirs[d].Rv;
   }
-  p.widths = widths; p.Hh = s.Hh; p.Ww = s.Ww; p.B = s.B; p.H = s.H;
+  p.widths = widths; p.Hh = s.Hh; p.Ww = s.Ww; p.B = s.B; p.H = s.H; p.S = s.S;
   return p;
 }
 
@@ -410,6 +437,25 @@ hipError_t mdlstm_forward(hipStream_t stream, const MdShape& s, const MdDir* dir
 }
 
 size_t mdlstm_dbpart_floats(const MdShape& s) { return (size_t)4 * s.B * 5 * s.H; }
+
+hipError_t mdlstm_copy_x(hipStream_t stream, const MdShape& s, const MdDir* dirs, const float* x, int D) {
+  MdXCopyParams q{};
+  for (int d = 0; d < 4; ++d) q.hc[d] = dirs[d].hc;
+  q.x = x; q.P = (size_t)s.Hh * s.Ww * s.B; q.D = D; q.H = s.H; q.S = s.S;
+  const size_t total = q.P * D;
+  hipLaunchKernelGGL(mdlstm_xcopy_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, q);
+  return hipGetLastError();
+}
+
+hipError_t mdlstm_scatter_grads(hipStream_t stream, int D, int H, const float* const* stacked, float* const* dRu,
+                                float* const* dRv, float* const* dW) {
+  MdScatterParams q{};
+  for (int d = 0; d < 4; ++d) { q.stacked[d] = stacked[d]; q.dRu[d] = dRu[d]; q.dRv[d] = dRv[d]; q.dW[d] = dW[d]; }
+  q.D = D; q.H = H;
+  const int total = (2 * H + D) * 5 * H;
+  hipLaunchKernelGGL(mdlstm_scatter_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, q);
+  return hipGetLastError();
+}
 
 hipError_t mdlstm_backward(hipStream_t stream, const MdShape& s, const MdDir* dirs, const int32_t* widths, const float* dy,
                            float* dbpart, float* const* db) {

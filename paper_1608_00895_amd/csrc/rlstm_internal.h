@@ -118,17 +118,22 @@ hipError_t clear_flag(hipStream_t stream, unsigned* flag);
 // Two-dimensional LSTM layer: the scans over the anti-diagonals (mdlstm.hip).
 // P = Hh * Ww * B pixel slots, pixel (u, v) of image n at index (u * Ww + v) * B + n.
 // ---------------------------------------------------------------------------
-struct MdShape { int Hh, Ww, B, H; };
+struct MdShape { int Hh, Ww, B, H, S; };   // S: row stride of the hc arrays (>= 2H, multiple of 4)
 struct MdDir {
   float* zg;          // [P, 5H] in: b + x W ; forward out: gates i|f_u|f_v|o|g ; backward out: d loss / d a
   float* c;           // [P, H]
-  float* hc;          // [P, 2H] forward out: h of the vertical | horizontal predecessor of every pixel
+  float* hc;          // [P, S] forward out: h of the vertical | horizontal predecessor of every pixel (| x, see mdlstm_copy_x)
   const float* Ru;    // [H, 5H]
   const float* Rv;    // [H, 5H]
 };
 bool mdlstm_supported(const MdShape& s);
 // dirs[4] in the order (du, dv) = (+,+), (+,-), (-,+), (-,-); y, dy: [P, 4H]
 hipError_t mdlstm_forward(hipStream_t stream, const MdShape& s, const MdDir* dirs, const int32_t* widths, float* y);
+// x into columns [2H, 2H + D) of the four hc arrays (S >= 2H + D)
+hipError_t mdlstm_copy_x(hipStream_t stream, const MdShape& s, const MdDir* dirs, const float* x, int D);
+// rows [0,H), [H,2H), [2H,2H+D) of four stacked [2H + D, 5H] gradients to dRu, dRv, dW
+hipError_t mdlstm_scatter_grads(hipStream_t stream, int D, int H, const float* const* stacked, float* const* dRu,
+                                float* const* dRv, float* const* dW);
 // dbpart: scratch of mdlstm_dbpart_floats(); db[4]: bias gradients [5H] per direction
 size_t mdlstm_dbpart_floats(const MdShape& s);
 hipError_t mdlstm_backward(hipStream_t stream, const MdShape& s, const MdDir* dirs, const int32_t* widths, const float* dy,

@@ -76,6 +76,7 @@ def check(got, ref, what, ref32=None):
     dict(Hh=64, B=2, D=1, H=32, w_lo=10, w_hi=40, wscale=0.1),
     dict(Hh=3, B=5, D=4, H=32, w_lo=50, w_hi=70, wscale=0.15),  # wide and flat
     dict(Hh=50, B=3, D=2, H=7, w_lo=1, w_hi=2, wscale=0.3),     # narrow and tall
+    dict(Hh=6, B=2, D=40, H=12, w_lo=4, w_hi=11, wscale=0.2),   # wide input: dW as a product of its own
 ])
 def test_mdlstm_shapes_against_oracle(shape):
     wl = synth.make_image_workload("t", bias_scale=0.2, seed=50 + shape["Hh"] + shape["H"], **shape)
