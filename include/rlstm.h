@@ -256,7 +256,10 @@ RLSTM_API int rlstm_set_first_piece(int steps);
  * gates, cell states and predecessor outputs from mdlstm_fwd to mdlstm_bwd, which overwrites it;
  * workspace (rmdlstm_workspace_bytes) is scratch.  The caller owns all buffers; nothing is
  * allocated and the device is not synchronised.
- * Limits of the kernels: Hh <= 64, H <= 32, operand_dtype 0; other shapes return RLSTM_ERESIDENT
+ * The rows of a scan are dealt out to workgroups in bands of 32 that hand one row per
+ * anti-diagonal to their neighbour through the workspace; all such waits are bounded (2 s) and
+ * rlstm_last_timeout(workspace) tells whether one expired (the results are then invalid).
+ * Limits of the kernels: Hh <= 256, H <= 32, operand_dtype 0; other shapes return RLSTM_ERESIDENT
  * (the size queries then return 0).  Other errors as for lstm_fwd.
  */
 typedef struct rmdlstm_desc {

@@ -357,7 +357,14 @@ static size_t md_splitk_floats(const rmdlstm_desc* d) {
   return align_up((size_t)256 * md_grad_rows(d) * 5 * d->H, 64);
 }
 static size_t md_stacked_floats(const rmdlstm_desc* d) { return align_up((size_t)4 * (2 * d->H + d->D) * 5 * d->H, 64); }
-static size_t md_dbpart_floats(const rmdlstm_desc* d) { return align_up((size_t)4 * d->B * 5 * d->H, 64); }
+static size_t md_dbpart_floats(const rmdlstm_desc* d) {
+  MdShape s{d->Hh, d->Ww, d->B, d->H, 0};
+  return align_up(mdlstm_dbpart_floats(s), 64);
+}
+static size_t md_halo_bytes(const rmdlstm_desc* d) {
+  MdShape s{d->Hh, d->Ww, d->B, d->H, 0};
+  return align_up(mdlstm_halo_words(s) * sizeof(unsigned long long), 256);
+}
 static void md_dirs(const rmdlstm_desc* d, float* res, const float* const* params, MdDir* dirs) {
   const size_t P = md_pixels(d);
   for (int k = 0; k < 4; ++k) {
@@ -373,7 +380,8 @@ size_t rmdlstm_reserve_bytes(const rmdlstm_desc* d) {
 
 size_t rmdlstm_workspace_bytes(const rmdlstm_desc* d) {
   if (check_md_desc(d) != RLSTM_OK) return 0;
-  return (md_splitk_floats(d) + md_dbpart_floats(d) + md_stacked_floats(d)) * sizeof(float);
+  // [timeout flag][split-K partials][bias gradients of the bands][stacked weight gradients][rows handed between bands]
+  return kFlagBytes + (md_splitk_floats(d) + md_dbpart_floats(d) + md_stacked_floats(d)) * sizeof(float) + md_halo_bytes(d);
 }
 
 int mdlstm_fwd(const rmdlstm_desc* d, const float* x, const float* const* params, const int32_t* widths,
@@ -398,8 +406,11 @@ int mdlstm_fwd(const rmdlstm_desc* d, const float* x, const float* const* params
   MdShape s{d->Hh, d->Ww, d->B, H, md_stride(d)};
   if (md_fused(d)) RLSTM_TRY(mdlstm_copy_x(st, s, dirs, x, d->D));
   const int diag = d->Hh + d->Ww - 1;
+  char* ws = static_cast<char*>(workspace);
+  float* wsf = reinterpret_cast<float*>(ws + kFlagBytes);
+  unsigned long long* halo = reinterpret_cast<unsigned long long*>(wsf + md_splitk_floats(d) + md_dbpart_floats(d) + md_stacked_floats(d));
   ProfScope ps(st, 1, 0, 4, diag, 2.0 * P * 2 * H * 5 * H * 4);
-  RLSTM_TRY(mdlstm_forward(st, s, dirs, widths, y));
+  RLSTM_TRY(mdlstm_forward(st, s, dirs, widths, y, halo, reinterpret_cast<unsigned*>(ws)));
   return RLSTM_OK;
 }
 
@@ -415,12 +426,14 @@ int mdlstm_bwd(const rmdlstm_desc* d, const float* x, const float* const* params
   MdDir dirs[4];
   md_dirs(d, static_cast<float*>(reserve), params, dirs);
   MdShape s{d->Hh, d->Ww, d->B, H, md_stride(d)};
-  float* skws = static_cast<float*>(workspace);
+  char* ws = static_cast<char*>(workspace);
+  float* skws = reinterpret_cast<float*>(ws + kFlagBytes);
   const size_t skfloats = md_splitk_floats(d);
+  unsigned long long* halo = reinterpret_cast<unsigned long long*>(skws + skfloats + md_dbpart_floats(d) + md_stacked_floats(d));
   {
     float* db[4] = {grads[3], grads[7], grads[11], grads[15]};
     ProfScope ps(st, 2, 0, 4, d->Hh + d->Ww - 1, 2.0 * P * 2 * H * 5 * H * 4);
-    RLSTM_TRY(mdlstm_backward(st, s, dirs, widths, dy, skws + skfloats, db));
+    RLSTM_TRY(mdlstm_backward(st, s, dirs, widths, dy, skws + skfloats, db, halo, reinterpret_cast<unsigned*>(ws)));
   }
   float* stacked = skws + skfloats + md_dbpart_floats(d);
   const size_t stacked_one = (size_t)(2 * H + D) * 5 * H;

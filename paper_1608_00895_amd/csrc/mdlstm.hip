@@ -2,9 +2,10 @@
 // needs the states of (u-1, v) and (u, v-1) in scan order, so all pixels of one anti-diagonal can
 // be computed together; four scan directions and several images run at once.
 //
-// One workgroup (4 wavefronts per 16 units) per (scan direction, image); it walks the anti-diagonals of its
-// image from the first pixel of the scan to the last, at the image's own width, so images of a
-// batch never wait for each other and nothing is exchanged between workgroups.  In scan
+// One workgroup (2 wavefronts per 16 units) per (scan direction, image, band of 32 rows); it walks the
+// anti-diagonals on which its band has pixels, at the image's own width, so images of a batch never
+// wait for each other.  A band needs one row of its neighbouring band per diagonal; that dependency
+// runs one way (see "rows handed between the bands" below), so the neighbour runs ahead.  In scan
 // coordinates (row r = 0 .. Hh-1, column q = 0 .. width-1) diagonal s holds the pixels r + q = s;
 // the pixel of row r on diagonal s has its vertical predecessor in row r-1 and its horizontal
 // predecessor in row r, both on diagonal s-1.  The workgroup keeps h and c of the previous
@@ -29,7 +30,9 @@ namespace {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr int kRows = 64;      // image rows a workgroup holds (4 wavefronts x one 16-row MFMA tile)
+constexpr int kBand = 16;      // image rows a workgroup holds (whole 16-row MFMA tiles)
+constexpr int kTiles = kBand / 16;
+constexpr int kMaxBands = 256 / kBand;
 
 // Gate functions on the hardware exponential (v_exp_f32, 1 ulp) and reciprocal (v_rcp_f32, 1 ulp): the
 // gating of 8 (row, unit) pairs per lane is as long as the step's matrix product, so the libm expf
@@ -46,9 +49,11 @@ struct MdParams {
   const float* Rv[4];
   float* y;                // forward: [P, 4H] output
   const float* dy;         // backward: [P, 4H]
-  float* dbpart;           // backward: [4][B][5H] bias gradient of every (direction, image)
+  float* dbpart;           // backward: [4 B][NB][5H] bias gradient of every (direction, image, band)
+  unsigned long long* halo;   // rows handed from a band to its neighbour: (value, diagonal + 1) words
+  unsigned* err;           // raised when a bounded wait expired
   const int32_t* widths;   // [B]
-  int Hh, Ww, B, H, S;
+  int Hh, Ww, B, H, S, NB;
 };
 
 // scan coordinates (row r, column q) of image n, direction (du, dv), image width wn -> pixel index
@@ -74,30 +79,66 @@ __device__ __forceinline__ void st4(float* q, floatx4 v, int nvalid) {
   for (int i = 0; i < 4; ++i) if (i < nvalid) q[i] = v[i];
 }
 
-// VEC: H is a multiple of 4, so every group of four units starts 16-byte aligned in all tensors
+// ---- rows handed between the bands of one scan -------------------------------------------------
+// The image rows of a scan are cut into bands of kBand rows, one workgroup each.  A band needs, per
+// anti-diagonal, one row of its neighbour (forward: h, c of the last row of the band above; backward:
+// d a and f_u * d c~ of the first row of the band below).  The dependency runs one way, so the
+// neighbour simply runs a diagonal or two ahead and nobody waits for a round trip.  Every value
+// travels as one 64-bit word (value, diagonal + 1) written and read with device-scope accesses,
+// so the reader polls the data itself; the words are cleared before every pass; waits are bounded.
+constexpr unsigned long long kMdWaitTicks = 200000000ull;     // 2 s of the 100 MHz wall clock
+
+__device__ __forceinline__ unsigned long long md_ld_word(const unsigned long long* q) {
+  return __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void md_st_word(unsigned long long* q, float v, int diag) {
+  __hip_atomic_store(q, ((unsigned long long)(unsigned)(diag + 1) << 32) | __float_as_uint(v), __ATOMIC_RELAXED,
+                     __HIP_MEMORY_SCOPE_AGENT);
+}
+// waits until word w (already loaded once) carries diagonal `diag`; false: gave up
+__device__ __forceinline__ bool md_wait_word(const unsigned long long* q, unsigned long long& w, int diag, unsigned* err) {
+  unsigned n = 0;
+  unsigned long long t0 = 0;
+  while ((unsigned)(w >> 32) != (unsigned)(diag + 1)) {
+    w = md_ld_word(q);
+    if ((++n & 255u) == 0) {
+      const unsigned long long now = wall_clock64();
+      if (t0 == 0) t0 = now;
+      else if (now - t0 > kMdWaitTicks) return false;
+      if (__hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) return false;
+    }
+  }
+  return true;
+}
+
+// VEC: H is a multiple of 4, so every group of four units starts 16-byte aligned in all tensors.
+// Workgroup = (band, direction, image); 2 row tiles x HT unit halves, one wavefront each.
 template <int HT, bool VEC>
-__global__ __launch_bounds__(256 * HT) void mdlstm_fwd_kernel(MdParams p) {
-  constexpr int NTH = 256 * HT;        // threads: 4 row tiles x HT unit halves, one wavefront each
+__global__ __launch_bounds__(64 * kTiles * HT) void mdlstm_fwd_kernel(MdParams p) {
+  constexpr int NTH = 64 * kTiles * HT;
   constexpr int HP = 16 * HT;          // padded units
   constexpr int NG = 5 * HP;           // padded pre-activation width
   constexpr int KS = 2 * HP / 4;       // MFMA k-steps
   constexpr int LDR = NG + 8;          // LDS row stride of [R_u ; R_v] (rows 4 apart fall into different banks)
   constexpr int LDH = HP + 1;
+  constexpr int HW = 2 * HP;           // words of a handed row: h | c
   extern __shared__ __align__(16) float lds[];
   float* Rs = lds;                                   // [2HP][LDR]
-  float* hb = Rs + 2 * HP * LDR;                     // [2][kRows + 1][LDH]; entry 0 is row -1 and stays zero
-  float* cb = hb + 2 * (kRows + 1) * LDH;            // same for c
+  float* hb = Rs + 2 * HP * LDR;                     // [2][kBand + 1][LDH]; entry 0 is the row above the band
+  float* cb = hb + 2 * (kBand + 1) * LDH;            // same for c
 
-  const int d = blockIdx.x & 3, n = blockIdx.x >> 2;
+  const int dn = blockIdx.x % (4 * p.B), band = blockIdx.x / (4 * p.B);   // bands above come first in the grid
+  const int d = dn & 3, n = dn >> 2;
   const int du = (d & 2) ? -1 : 1, dv = (d & 1) ? -1 : 1;
   const int H = p.H, Hh = p.Hh;
   const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, lq = lane >> 4;
-  const int wave = (tid >> 6) & 3;     // row tile
-  const int r = 16 * wave + l16;       // row of this lane
-  const int jm = 16 * (tid >> 8) + l16;        // unit whose columns this lane feeds to the MFMA (A operand row)
-  const int j0 = 16 * (tid >> 8) + 4 * lq;     // first of the four units this lane gates (accumulator rows)
+  const int lr = 16 * ((tid >> 6) % kTiles) + l16;  // row inside the band
+  const int r = kBand * band + lr;             // row of this lane
+  const int jm = 16 * (tid / (64 * kTiles)) + l16;        // unit whose columns this lane feeds to the MFMA (A operand row)
+  const int j0 = 16 * (tid / (64 * kTiles)) + 4 * lq;     // first of the four units this lane gates (accumulator rows)
   const int nv = min(max(H - j0, 0), 4);       // how many of them exist
   const int wn = min(max(p.widths[n], 0), p.Ww);
+  const int rows_here = min(Hh - kBand * band, kBand);
 
   for (int idx = tid; idx < 2 * HP * NG; idx += NTH) {
     const int k = idx / NG, col = idx % NG;
@@ -106,31 +147,68 @@ __global__ __launch_bounds__(256 * HT) void mdlstm_fwd_kernel(MdParams p) {
     if (kk < H && jj < H) v = (k < HP ? p.Ru[d] : p.Rv[d])[(size_t)kk * 5 * H + g * H + jj];
     Rs[k * LDR + col] = v;
   }
-  for (int idx = tid; idx < 2 * (kRows + 1) * LDH; idx += NTH) { hb[idx] = 0.f; cb[idx] = 0.f; }
+  for (int idx = tid; idx < 2 * (kBand + 1) * LDH; idx += NTH) { hb[idx] = 0.f; cb[idx] = 0.f; }
   __syncthreads();
 
   float* zgd = p.zg[d];
   float* cd = p.c[d];
   float* hcd = p.hc[d];
-  const int nsteps = wn > 0 ? Hh + wn - 1 : 0;
+  // diagonals on which this band has pixels
+  const int s_lo = kBand * band, s_hi = wn > 0 ? kBand * band + rows_here - 1 + wn - 1 : s_lo - 1;
+  const int ndiag = Hh + p.Ww;
+  // the row above the band (last row of the band above) has pixels on diagonals s_lo - 1 .. s_lo - 1 + wn - 1
+  const bool takes = band > 0, gives = band < p.NB - 1;
+  const unsigned long long* halo_in = takes ? p.halo + ((size_t)dn * (p.NB - 1) + (band - 1)) * ndiag * 64 : p.halo;
+  unsigned long long* halo_out = gives ? p.halo + ((size_t)dn * (p.NB - 1) + band) * ndiag * 64 : p.halo;
+  const bool hands = tid < HW;         // the lanes that move the handed row (wavefront 0)
+
+  // h, c of the row above on diagonal sd -> entry 0 of the given buffers; returns false when a wait expired
+  unsigned long long hw = 0;
+  auto halo_issue = [&](int sd) {
+    if (hands && takes && sd >= s_lo - 1 && sd <= s_lo - 1 + wn - 1) hw = md_ld_word(halo_in + (size_t)sd * 64 + tid);
+  };
+  auto halo_take = [&](int sd, float* hdst, float* cdst) -> bool {
+    if (!hands) return true;
+    float v = 0.f;
+    bool good = true;
+    if (takes && sd >= s_lo - 1 && sd <= s_lo - 1 + wn - 1) {
+      good = md_wait_word(halo_in + (size_t)sd * 64 + tid, hw, sd, p.err);
+      v = __uint_as_float((unsigned)hw);
+    }
+    if (tid < HP) hdst[tid] = v; else cdst[tid - HP] = v;
+    return good;
+  };
 
   // input part of the lane's row and four units on diagonal s
   floatx4 zr[5];
   auto prefetch = [&](int s) {
     const int q = s - r;
-    const bool ok = r < Hh && q >= 0 && q < wn && s < nsteps && nv > 0;
+    const bool ok = lr < rows_here && q >= 0 && q < wn && s <= s_hi && nv > 0;
     const size_t pix = ok ? md_pixel(p, du, dv, wn, n, r, q) : 0;
 #pragma unroll
     for (int g = 0; g < 5; ++g)
       zr[g] = ok ? ld4<VEC>(zgd + pix * 5 * H + g * H + j0, nv) : floatx4{0.f, 0.f, 0.f, 0.f};
   };
-  prefetch(0);
+  prefetch(s_lo);
+  int fail = 0;
+  {
+    // the row above on the diagonal before the first one
+    float* hprev0 = hb + ((s_lo + 1) & 1) * (kBand + 1) * LDH;
+    float* cprev0 = cb + ((s_lo + 1) & 1) * (kBand + 1) * LDH;
+    halo_issue(s_lo - 1);
+    if (!halo_take(s_lo - 1, hprev0, cprev0)) fail = 1;
+  }
+  if (__syncthreads_or(fail)) {
+    if (tid == 0) __hip_atomic_store(p.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return;
+  }
 
-  for (int s = 0; s < nsteps; ++s) {
-    const float* hprev = hb + ((s + 1) & 1) * (kRows + 1) * LDH;
-    const float* cprev = cb + ((s + 1) & 1) * (kRows + 1) * LDH;
-    float* hcur = hb + (s & 1) * (kRows + 1) * LDH;
-    float* ccur = cb + (s & 1) * (kRows + 1) * LDH;
+  for (int s = s_lo; s <= s_hi; ++s) {
+    const float* hprev = hb + ((s + 1) & 1) * (kBand + 1) * LDH;
+    const float* cprev = cb + ((s + 1) & 1) * (kBand + 1) * LDH;
+    float* hcur = hb + (s & 1) * (kBand + 1) * LDH;
+    float* ccur = cb + (s & 1) * (kBand + 1) * LDH;
+    halo_issue(s);                     // arrives while the MFMAs run
 
     // a^T = [R_u ; R_v]^T [h_up | h_left]^T: accumulator g holds gate g of units j0 .. j0+3 (its 4 rows) for the
     // image row of this lane (its column).  A[m][k] = R[k][gate column of unit jm]; B[k][n]: k < HP: h of the
@@ -138,7 +216,7 @@ __global__ __launch_bounds__(256 * HT) void mdlstm_fwd_kernel(MdParams p) {
     floatx4 acc[5];
 #pragma unroll
     for (int g = 0; g < 5; ++g) acc[g] = floatx4{0.f, 0.f, 0.f, 0.f};
-    const float* brow = hprev + r * LDH;
+    const float* brow = hprev + lr * LDH;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       const int k = 4 * ks + lq;
@@ -149,7 +227,7 @@ __global__ __launch_bounds__(256 * HT) void mdlstm_fwd_kernel(MdParams p) {
     }
 
     const int q = s - r;
-    const bool ok = r < Hh && q >= 0 && q < wn && nv > 0;
+    const bool ok = lr < rows_here && q >= 0 && q < wn && nv > 0;
     const size_t pix = ok ? md_pixel(p, du, dv, wn, n, r, q) : 0;
     floatx4 gi, gfu, gfv, go, gg, ct, ht, h_up, h_left;
 #pragma unroll
@@ -160,17 +238,24 @@ __global__ __launch_bounds__(256 * HT) void mdlstm_fwd_kernel(MdParams p) {
       gfv[i] = md_sigmoid(acc[2][i] + zr[2][i]);
       go[i] = md_sigmoid(acc[3][i] + zr[3][i]);
       gg[i] = md_tanh(acc[4][i] + zr[4][i]);
-      h_up[i] = hprev[r * LDH + j]; h_left[i] = hprev[(r + 1) * LDH + j];
-      const float c_up = cprev[r * LDH + j], c_left = cprev[(r + 1) * LDH + j];
+      h_up[i] = hprev[lr * LDH + j]; h_left[i] = hprev[(lr + 1) * LDH + j];
+      const float c_up = cprev[lr * LDH + j], c_left = cprev[(lr + 1) * LDH + j];
       ct[i] = gfu[i] * c_up + gfv[i] * c_left + gi[i] * gg[i];
       ht[i] = go[i] * md_tanh(ct[i]);
       const bool oki = ok && i < nv;
-      hcur[(r + 1) * LDH + j] = oki ? ht[i] : 0.f;
-      ccur[(r + 1) * LDH + j] = oki ? ct[i] : 0.f;
+      hcur[(lr + 1) * LDH + j] = oki ? ht[i] : 0.f;
+      ccur[(lr + 1) * LDH + j] = oki ? ct[i] : 0.f;
     }
+    // the row above on this diagonal, for the next step
+    fail = halo_take(s, hcur, ccur) ? 0 : 1;
     // the next diagonal only needs the LDS rows: the stores to HBM and the next prefetch follow the barrier, so
     // that one wavefront's memory instructions overlap the MFMAs of the wavefront it shares the SIMD with
-    __syncthreads();
+    if (__syncthreads_or(fail)) {
+      if (tid == 0) __hip_atomic_store(p.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      return;
+    }
+    if (gives && hands)                // last row of the band to the band below
+      md_st_word(halo_out + (size_t)s * 64 + tid, tid < HP ? hcur[kBand * LDH + tid] : ccur[kBand * LDH + tid - HP], s);
     if (ok) {
       float* zrow = zgd + pix * 5 * H + j0;
       st4<VEC>(zrow, gi, nv); st4<VEC>(zrow + H, gfu, nv); st4<VEC>(zrow + 2 * H, gfv, nv);
@@ -184,10 +269,11 @@ __global__ __launch_bounds__(256 * HT) void mdlstm_fwd_kernel(MdParams p) {
   }
 
   // pixels beyond the image's width: y = 0, and zeros where the products after the backward pass read
-  const int npad = (p.Ww - wn) * Hh;
+  const int npad = (p.Ww - wn) * rows_here;
   for (int idx = tid; idx < npad * H; idx += NTH) {
     const int jj = idx % H, cell = idx / H;
-    const int u = cell / (p.Ww - wn), v = wn + cell % (p.Ww - wn);
+    const int rr = kBand * band + cell / (p.Ww - wn), v = wn + cell % (p.Ww - wn);
+    const int u = du > 0 ? rr : Hh - 1 - rr;
     const size_t pix = ((size_t)u * p.Ww + v) * p.B + n;
     p.y[pix * 4 * H + d * H + jj] = 0.f;
     cd[pix * H + jj] = 0.f;
@@ -197,30 +283,34 @@ __global__ __launch_bounds__(256 * HT) void mdlstm_fwd_kernel(MdParams p) {
 }
 
 template <int HT, bool VEC>
-__global__ __launch_bounds__(256 * HT) void mdlstm_bwd_kernel(MdParams p) {
-  constexpr int NTH = 256 * HT;
+__global__ __launch_bounds__(64 * kTiles * HT) void mdlstm_bwd_kernel(MdParams p) {
+  constexpr int NTH = 64 * kTiles * HT;
   constexpr int HP = 16 * HT;
   constexpr int NG = 5 * HP;
   constexpr int KS = 2 * NG / 4;
   constexpr int LDT = HP + 8;          // LDS row stride of [R_u ; R_v]^T
   constexpr int LDZ = NG + 4;          // LDS row stride of the d a rows
   constexpr int LDH = HP + 1;
+  constexpr int HW = NG + HP;          // words of a handed row: d a | f_u * d c~
   extern __shared__ __align__(16) float lds[];
   float* RT = lds;                                   // [2NG][LDT]: row k < NG: R_u[.][k]; else R_v[.][k - NG]
-  float* dzb = RT + 2 * NG * LDT;                    // [kRows + 1][LDZ]: d a of the diagonal done last; entry kRows stays zero
-  float* dcu = dzb + (kRows + 1) * LDZ;              // [2][kRows + 1][LDH]: f_u * d c~ of a diagonal's pixels
-  float* dcv = dcu + 2 * (kRows + 1) * LDH;          // same with f_v
+  float* dzb = RT + 2 * NG * LDT;                    // [kBand + 1][LDZ]: d a of the diagonal done last; entry kBand is the row below the band
+  float* dcu = dzb + (kBand + 1) * LDZ;              // [2][kBand + 1][LDH]: f_u * d c~ of a diagonal's pixels; entry kBand: row below
+  float* dcv = dcu + 2 * (kBand + 1) * LDH;          // same with f_v
 
-  const int d = blockIdx.x & 3, n = blockIdx.x >> 2;
+  // bands below come first in the grid
+  const int dn = blockIdx.x % (4 * p.B), band = p.NB - 1 - blockIdx.x / (4 * p.B);
+  const int d = dn & 3, n = dn >> 2;
   const int du = (d & 2) ? -1 : 1, dv = (d & 1) ? -1 : 1;
   const int H = p.H, Hh = p.Hh;
   const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, lq = lane >> 4;
-  const int wave = (tid >> 6) & 3;     // row tile
-  const int r = 16 * wave + l16;       // row of this lane
-  const int jm = 16 * (tid >> 8) + l16;        // unit whose row of [R_u ; R_v]^T this lane feeds to the MFMA
-  const int j0 = 16 * (tid >> 8) + 4 * lq;     // first of the four units this lane handles
+  const int lr = 16 * ((tid >> 6) % kTiles) + l16;  // row inside the band
+  const int r = kBand * band + lr;             // row of this lane
+  const int jm = 16 * (tid / (64 * kTiles)) + l16;        // unit whose row of [R_u ; R_v]^T this lane feeds to the MFMA
+  const int j0 = 16 * (tid / (64 * kTiles)) + 4 * lq;     // first of the four units this lane handles
   const int nv = min(max(H - j0, 0), 4);
   const int wn = min(max(p.widths[n], 0), p.Ww);
+  const int rows_here = min(Hh - kBand * band, kBand);
 
   for (int idx = tid; idx < 2 * NG * HP; idx += NTH) {
     const int k = idx / HP, jo = idx % HP;
@@ -229,13 +319,45 @@ __global__ __launch_bounds__(256 * HT) void mdlstm_bwd_kernel(MdParams p) {
     if (jj < H && jo < H) v = (k < NG ? p.Ru[d] : p.Rv[d])[(size_t)jo * 5 * H + g * H + jj];
     RT[k * LDT + jo] = v;
   }
-  for (int idx = tid; idx < (kRows + 1) * LDZ; idx += NTH) dzb[idx] = 0.f;
-  for (int idx = tid; idx < 2 * (kRows + 1) * LDH; idx += NTH) { dcu[idx] = 0.f; dcv[idx] = 0.f; }
+  for (int idx = tid; idx < (kBand + 1) * LDZ; idx += NTH) dzb[idx] = 0.f;
+  for (int idx = tid; idx < 2 * (kBand + 1) * LDH; idx += NTH) { dcu[idx] = 0.f; dcv[idx] = 0.f; }
   __syncthreads();
 
   float* zgd = p.zg[d];
   const float* cd = p.c[d];
-  const int nsteps = wn > 0 ? Hh + wn - 1 : 0;
+  const int s_lo = kBand * band, s_hi = wn > 0 ? kBand * band + rows_here - 1 + wn - 1 : s_lo - 1;
+  const int ndiag = Hh + p.Ww;
+  // the row below the band (first row of the band below) has pixels on diagonals b_lo .. b_lo + wn - 1
+  const int b_lo = kBand * (band + 1);
+  const bool takes = band < p.NB - 1, gives = band > 0;
+  const unsigned long long* halo_in = takes ? p.halo + ((size_t)dn * (p.NB - 1) + band) * ndiag * 192 : p.halo;
+  unsigned long long* halo_out = gives ? p.halo + ((size_t)dn * (p.NB - 1) + (band - 1)) * ndiag * 192 : p.halo;
+
+  // d a and f_u * d c~ of the row below on diagonal sd -> entry kBand of dzb / the given dcu buffer (wavefront 0)
+  unsigned long long hw[3] = {0, 0, 0};
+  auto halo_issue = [&](int sd) {
+    if (tid < 64 && takes && sd >= b_lo && sd <= b_lo + wn - 1)
+#pragma unroll
+      for (int k = 0; k < 3; ++k)
+        if (tid + 64 * k < HW) hw[k] = md_ld_word(halo_in + (size_t)sd * 192 + tid + 64 * k);
+  };
+  auto halo_take = [&](int sd, float* dcu_dst) -> bool {
+    if (tid >= 64) return true;
+    bool good = true;
+    const bool have = takes && sd >= b_lo && sd <= b_lo + wn - 1;
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+      const int w = tid + 64 * k;
+      if (w >= HW) continue;
+      float v = 0.f;
+      if (have) {
+        good = md_wait_word(halo_in + (size_t)sd * 192 + w, hw[k], sd, p.err) && good;
+        v = __uint_as_float((unsigned)hw[k]);
+      }
+      if (w < NG) dzb[kBand * LDZ + w] = v; else dcu_dst[kBand * LDH + w - NG] = v;
+    }
+    return good;
+  };
 
   // bias gradient of the lane's four units, summed over all diagonals
   floatx4 dbacc[5];
@@ -246,7 +368,7 @@ __global__ __launch_bounds__(256 * HT) void mdlstm_bwd_kernel(MdParams p) {
   floatx4 in[9];
   auto prefetch = [&](int s) {
     const int q = s - r;
-    const bool ok = s >= 0 && r < Hh && q >= 0 && q < wn && nv > 0;
+    const bool ok = s >= s_lo && lr < rows_here && q >= 0 && q < wn && nv > 0;
     const floatx4 zero = floatx4{0.f, 0.f, 0.f, 0.f};
     const size_t pix = ok ? md_pixel(p, du, dv, wn, n, r, q) : 0;
 #pragma unroll
@@ -256,18 +378,29 @@ __global__ __launch_bounds__(256 * HT) void mdlstm_bwd_kernel(MdParams p) {
     in[7] = (ok && q >= 1) ? ld4<VEC>(cd + md_pixel(p, du, dv, wn, n, r, q - 1) * H + j0, nv) : zero;
     in[8] = ok ? ld4<VEC>(p.dy + pix * 4 * H + d * H + j0, nv) : zero;
   };
-  prefetch(nsteps - 1);
+  prefetch(s_hi);
+  int fail = 0;
+  {
+    // the row below on the diagonal after the last one
+    halo_issue(s_hi + 1);
+    if (!halo_take(s_hi + 1, dcu + ((s_hi + 1) & 1) * (kBand + 1) * LDH)) fail = 1;
+  }
+  if (__syncthreads_or(fail)) {
+    if (tid == 0) __hip_atomic_store(p.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return;
+  }
 
-  for (int s = nsteps - 1; s >= 0; --s) {
-    const float* dcu_prev = dcu + ((s + 1) & 1) * (kRows + 1) * LDH;
-    const float* dcv_prev = dcv + ((s + 1) & 1) * (kRows + 1) * LDH;
-    float* dcu_cur = dcu + (s & 1) * (kRows + 1) * LDH;
-    float* dcv_cur = dcv + (s & 1) * (kRows + 1) * LDH;
+  for (int s = s_hi; s >= s_lo; --s) {
+    const float* dcu_prev = dcu + ((s + 1) & 1) * (kBand + 1) * LDH;
+    const float* dcv_prev = dcv + ((s + 1) & 1) * (kBand + 1) * LDH;
+    float* dcu_cur = dcu + (s & 1) * (kBand + 1) * LDH;
+    float* dcv_cur = dcv + (s & 1) * (kBand + 1) * LDH;
+    if (s > s_lo) halo_issue(s);       // arrives while the MFMAs run
 
     // d h^T of diagonal s = [R_u ; R_v] [d a(row + 1) | d a(row)]^T of diagonal s+1 (the successor below sits in
     // row r+1, the one to the right in row r); two accumulators so that consecutive MFMAs do not wait for each other
     floatx4 acc0 = floatx4{0.f, 0.f, 0.f, 0.f}, acc1 = floatx4{0.f, 0.f, 0.f, 0.f};
-    const float* brow = dzb + r * LDZ;
+    const float* brow = dzb + lr * LDZ;
 #pragma unroll 8
     for (int ks = 0; ks < KS; ks += 2) {
       const int k0 = 4 * ks + lq, k1 = k0 + 4;
@@ -280,7 +413,7 @@ __global__ __launch_bounds__(256 * HT) void mdlstm_bwd_kernel(MdParams p) {
     __syncthreads();     // every wavefront has read the d a rows of diagonal s+1
 
     const int q = s - r;
-    const bool ok = r < Hh && q >= 0 && q < wn && nv > 0;
+    const bool ok = lr < rows_here && q >= 0 && q < wn && nv > 0;
     const size_t pix = ok ? md_pixel(p, du, dv, wn, n, r, q) : 0;
     floatx4 dz[5];
 #pragma unroll
@@ -291,20 +424,33 @@ __global__ __launch_bounds__(256 * HT) void mdlstm_bwd_kernel(MdParams p) {
       const float tc = md_tanh(in[5][i]);
       const float dh = in[8][i] + acc[i];
       const float d_o = dh * tc;
-      const float dct = dcu_prev[(r + 1) * LDH + j] + dcv_prev[r * LDH + j] + dh * go * (1.0f - tc * tc);
+      const float dct = dcu_prev[(lr + 1) * LDH + j] + dcv_prev[lr * LDH + j] + dh * go * (1.0f - tc * tc);
       dz[0][i] = oki ? dct * gg * gi * (1.0f - gi) : 0.f;
       dz[1][i] = oki ? dct * in[6][i] * gfu * (1.0f - gfu) : 0.f;
       dz[2][i] = oki ? dct * in[7][i] * gfv * (1.0f - gfv) : 0.f;
       dz[3][i] = oki ? d_o * go * (1.0f - go) : 0.f;
       dz[4][i] = oki ? dct * gi * (1.0f - gg * gg) : 0.f;
-      dcu_cur[r * LDH + j] = oki ? dct * gfu : 0.f;
-      dcv_cur[r * LDH + j] = oki ? dct * gfv : 0.f;
+      dcu_cur[lr * LDH + j] = oki ? dct * gfu : 0.f;
+      dcv_cur[lr * LDH + j] = oki ? dct * gfv : 0.f;
 #pragma unroll
-      for (int g = 0; g < 5; ++g) dzb[r * LDZ + g * HP + j] = dz[g][i];
+      for (int g = 0; g < 5; ++g) dzb[lr * LDZ + g * HP + j] = dz[g][i];
     }
 #pragma unroll
     for (int g = 0; g < 5; ++g) dbacc[g] += dz[g];
-    __syncthreads();     // the LDS rows of diagonal s are complete; HBM traffic follows the barrier
+    // the row below on this diagonal, for the next step
+    fail = (s > s_lo ? halo_take(s, dcu_cur) : true) ? 0 : 1;
+    // the LDS rows of diagonal s are complete; HBM traffic follows the barrier
+    if (__syncthreads_or(fail)) {
+      if (tid == 0) __hip_atomic_store(p.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      return;
+    }
+    if (gives && tid < 64) {           // first row of the band to the band above
+#pragma unroll
+      for (int k = 0; k < 3; ++k) {
+        const int w = tid + 64 * k;
+        if (w < HW) md_st_word(halo_out + (size_t)s * 192 + w, w < NG ? dzb[w] : dcu_cur[w - NG], s);
+      }
+    }
     if (ok) {
       float* zrow = zgd + pix * 5 * H + j0;
 #pragma unroll
@@ -314,7 +460,7 @@ __global__ __launch_bounds__(256 * HT) void mdlstm_bwd_kernel(MdParams p) {
   }
   __syncthreads();
 
-  // bias gradient of this (direction, image): the 16 threads that share a unit are added in thread order
+  // bias gradient of this (direction, image, band): the threads that share a unit are added in thread order
   float* stage = dzb;                                // [threads][5][4]
 #pragma unroll
   for (int g = 0; g < 5; ++g)
@@ -326,33 +472,42 @@ __global__ __launch_bounds__(256 * HT) void mdlstm_bwd_kernel(MdParams p) {
     if (jo < H) {
       // threads that handle unit jo: unit half jo / 16, quad (jo % 16) / 4, every row tile and row lane
       float sum = 0.f;
-      for (int w = 0; w < 4; ++w)
+      for (int w = 0; w < kTiles; ++w)
         for (int l = 0; l < 16; ++l)
-          sum += stage[((256 * (jo >> 4) + 64 * w + 16 * ((jo & 15) >> 2) + l) * 5 + g) * 4 + (jo & 3)];
-      p.dbpart[((size_t)d * p.B + n) * 5 * H + g * H + jo] = sum;
+          sum += stage[((64 * kTiles * (jo >> 4) + 64 * w + 16 * ((jo & 15) >> 2) + l) * 5 + g) * 4 + (jo & 3)];
+      p.dbpart[((size_t)dn * p.NB + band) * 5 * H + g * H + jo] = sum;
     }
   }
 
   // d a = 0 beyond the image's width
-  const int npad = (p.Ww - wn) * Hh;
+  const int npad = (p.Ww - wn) * rows_here;
   for (int idx = tid; idx < npad * 5 * H; idx += NTH) {
     const int col = idx % (5 * H), cell = idx / (5 * H);
-    const int u = cell / (p.Ww - wn), v = wn + cell % (p.Ww - wn);
+    const int rr = kBand * band + cell / (p.Ww - wn), v = wn + cell % (p.Ww - wn);
+    const int u = du > 0 ? rr : Hh - 1 - rr;
     const size_t pix = ((size_t)u * p.Ww + v) * p.B + n;
     zgd[pix * 5 * H + col] = 0.f;
   }
 }
 
-// db[d][col] = sum over the images, in image order
-struct MdDbParams { float* db[4]; const float* dbpart; int B, n; };
+// db[d][col] = sum over the images and their bands, in that order
+struct MdDbParams { float* db[4]; const float* dbpart; int B, NB, n; };
 __global__ __launch_bounds__(256) void mdlstm_db_sum_kernel(MdDbParams p) {
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i >= p.n) return;
   for (int d = 0; d < 4; ++d) {
     float sum = 0.f;
-    for (int b = 0; b < p.B; ++b) sum += p.dbpart[((size_t)d * p.B + b) * p.n + i];
+    for (int b = 0; b < p.B; ++b)
+      for (int k = 0; k < p.NB; ++k) sum += p.dbpart[((size_t)(b * 4 + d) * p.NB + k) * p.n + i];
     p.db[d][i] = sum;
   }
+}
+
+// clears the handed-row words and the timeout flag before a pass
+__global__ __launch_bounds__(256) void mdlstm_clear_kernel(unsigned long long* words, size_t n, unsigned* err) {
+  const size_t gsz = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += gsz) words[i] = 0ull;
+  if (blockIdx.x == 0 && threadIdx.x == 0) *err = 0u;
 }
 
 // x [P, D] into columns [2H, 2H + D) of the four [P, S] predecessor-output arrays, so that
@@ -384,11 +539,11 @@ __global__ __launch_bounds__(256) void mdlstm_scatter_kernel(MdScatterParams p) 
 
 size_t md_lds_fwd(int HT) {
   const int HP = 16 * HT, NG = 5 * HP;
-  return ((size_t)2 * HP * (NG + 8) + (size_t)4 * (kRows + 1) * (HP + 1)) * sizeof(float);
+  return ((size_t)2 * HP * (NG + 8) + (size_t)4 * (kBand + 1) * (HP + 1)) * sizeof(float);
 }
 size_t md_lds_bwd(int HT) {
   const int HP = 16 * HT, NG = 5 * HP;
-  return ((size_t)2 * NG * (HP + 8) + (size_t)(kRows + 1) * (NG + 4) + (size_t)4 * (kRows + 1) * (HP + 1)) * sizeof(float);
+  return ((size_t)2 * NG * (HP + 8) + (size_t)(kBand + 1) * (NG + 4) + (size_t)4 * (kBand + 1) * (HP + 1)) * sizeof(float);
 }
 
 template <typename K>
@@ -408,6 +563,7 @@ MdParams md_params(const MdShape& s, const MdDir* dirs, const int32_t* widths) {
     p.zg[d] = dirs[d].zg; p.c[d] = dirs[d].c; p.hc[d] = dirs[d].hc; p.Ru[d] = dirs[d].Ru; p.Rv[d] = dirs[d].Rv;
   }
   p.widths = widths; p.Hh = s.Hh; p.Ww = s.Ww; p.B = s.B; p.H = s.H; p.S = s.S;
+  p.NB = (s.Hh + kBand - 1) / kBand;
   return p;
 }
 
@@ -423,20 +579,39 @@ bool md_vec(const MdShape& s, const MdDir* dirs, const float* yy) {
 }
 }  // namespace
 
-bool mdlstm_supported(const MdShape& s) { return s.Hh >= 1 && s.Hh <= kRows && s.H >= 1 && s.H <= 32; }
+bool mdlstm_supported(const MdShape& s) { return s.Hh >= 1 && s.Hh <= kBand * kMaxBands && s.H >= 1 && s.H <= 32; }
 
-hipError_t mdlstm_forward(hipStream_t stream, const MdShape& s, const MdDir* dirs, const int32_t* widths, float* y) {
-  if (!mdlstm_supported(s)) return hipErrorInvalidValue;
-  MdParams p = md_params(s, dirs, widths);
-  p.y = y;
-  const bool vec = md_vec(s, dirs, y);
-  if (s.H <= 16) return vec ? md_launch(mdlstm_fwd_kernel<1, true>, 4 * s.B, 256, md_lds_fwd(1), stream, p)
-                            : md_launch(mdlstm_fwd_kernel<1, false>, 4 * s.B, 256, md_lds_fwd(1), stream, p);
-  return vec ? md_launch(mdlstm_fwd_kernel<2, true>, 4 * s.B, 512, md_lds_fwd(2), stream, p)
-             : md_launch(mdlstm_fwd_kernel<2, false>, 4 * s.B, 512, md_lds_fwd(2), stream, p);
+// 64-bit words for the rows handed between bands (the backward pass needs the larger array)
+size_t mdlstm_halo_words(const MdShape& s) {
+  const size_t nb = (size_t)(s.Hh + kBand - 1) / kBand;
+  return (size_t)4 * s.B * (nb - 1) * ((size_t)s.Hh + s.Ww) * 192;
 }
 
-size_t mdlstm_dbpart_floats(const MdShape& s) { return (size_t)4 * s.B * 5 * s.H; }
+namespace {
+hipError_t md_clear(hipStream_t stream, const MdShape& s, unsigned long long* halo, unsigned* err, int words_per_diag) {
+  const size_t nb = (size_t)(s.Hh + kBand - 1) / kBand;
+  const size_t n = (size_t)4 * s.B * (nb - 1) * ((size_t)s.Hh + s.Ww) * words_per_diag;
+  hipLaunchKernelGGL(mdlstm_clear_kernel, dim3(256), dim3(256), 0, stream, halo, n, err);
+  return hipGetLastError();
+}
+}  // namespace
+
+hipError_t mdlstm_forward(hipStream_t stream, const MdShape& s, const MdDir* dirs, const int32_t* widths, float* y,
+                          unsigned long long* halo, unsigned* err) {
+  if (!mdlstm_supported(s)) return hipErrorInvalidValue;
+  MdParams p = md_params(s, dirs, widths);
+  p.y = y; p.halo = halo; p.err = err;
+  hipError_t e = md_clear(stream, s, halo, err, 64);
+  if (e != hipSuccess) return e;
+  const bool vec = md_vec(s, dirs, y);
+  const int grid = 4 * s.B * p.NB;
+  if (s.H <= 16) return vec ? md_launch(mdlstm_fwd_kernel<1, true>, grid, 64 * kTiles, md_lds_fwd(1), stream, p)
+                            : md_launch(mdlstm_fwd_kernel<1, false>, grid, 64 * kTiles, md_lds_fwd(1), stream, p);
+  return vec ? md_launch(mdlstm_fwd_kernel<2, true>, grid, 128 * kTiles, md_lds_fwd(2), stream, p)
+             : md_launch(mdlstm_fwd_kernel<2, false>, grid, 128 * kTiles, md_lds_fwd(2), stream, p);
+}
+
+size_t mdlstm_dbpart_floats(const MdShape& s) { return (size_t)4 * s.B * kMaxBands * 5 * s.H; }
 
 hipError_t mdlstm_copy_x(hipStream_t stream, const MdShape& s, const MdDir* dirs, const float* x, int D) {
   MdXCopyParams q{};
@@ -458,21 +633,22 @@ hipError_t mdlstm_scatter_grads(hipStream_t stream, int D, int H, const float* c
 }
 
 hipError_t mdlstm_backward(hipStream_t stream, const MdShape& s, const MdDir* dirs, const int32_t* widths, const float* dy,
-                           float* dbpart, float* const* db) {
+                           float* dbpart, float* const* db, unsigned long long* halo, unsigned* err) {
   if (!mdlstm_supported(s)) return hipErrorInvalidValue;
   MdParams p = md_params(s, dirs, widths);
-  p.dy = dy;
-  p.dbpart = dbpart;
+  p.dy = dy; p.dbpart = dbpart; p.halo = halo; p.err = err;
+  hipError_t e = md_clear(stream, s, halo, err, 192);
+  if (e != hipSuccess) return e;
   const bool vec = md_vec(s, dirs, dy);
-  hipError_t e;
-  if (s.H <= 16) e = vec ? md_launch(mdlstm_bwd_kernel<1, true>, 4 * s.B, 256, md_lds_bwd(1), stream, p)
-                         : md_launch(mdlstm_bwd_kernel<1, false>, 4 * s.B, 256, md_lds_bwd(1), stream, p);
-  else e = vec ? md_launch(mdlstm_bwd_kernel<2, true>, 4 * s.B, 512, md_lds_bwd(2), stream, p)
-               : md_launch(mdlstm_bwd_kernel<2, false>, 4 * s.B, 512, md_lds_bwd(2), stream, p);
+  const int grid = 4 * s.B * p.NB;
+  if (s.H <= 16) e = vec ? md_launch(mdlstm_bwd_kernel<1, true>, grid, 64 * kTiles, md_lds_bwd(1), stream, p)
+                         : md_launch(mdlstm_bwd_kernel<1, false>, grid, 64 * kTiles, md_lds_bwd(1), stream, p);
+  else e = vec ? md_launch(mdlstm_bwd_kernel<2, true>, grid, 128 * kTiles, md_lds_bwd(2), stream, p)
+               : md_launch(mdlstm_bwd_kernel<2, false>, grid, 128 * kTiles, md_lds_bwd(2), stream, p);
   if (e != hipSuccess) return e;
   MdDbParams q{};
   for (int d = 0; d < 4; ++d) q.db[d] = db[d];
-  q.dbpart = dbpart; q.B = s.B; q.n = 5 * s.H;
+  q.dbpart = dbpart; q.B = s.B; q.NB = p.NB; q.n = 5 * s.H;
   hipLaunchKernelGGL(mdlstm_db_sum_kernel, dim3((unsigned)((q.n + 255) / 256)), dim3(256), 0, stream, q);
   return hipGetLastError();
 }

@@ -128,7 +128,10 @@ struct MdDir {
 };
 bool mdlstm_supported(const MdShape& s);
 // dirs[4] in the order (du, dv) = (+,+), (+,-), (-,+), (-,-); y, dy: [P, 4H]
-hipError_t mdlstm_forward(hipStream_t stream, const MdShape& s, const MdDir* dirs, const int32_t* widths, float* y);
+// halo: mdlstm_halo_words() 64-bit words of scratch (rows handed between bands); err: timeout flag
+size_t mdlstm_halo_words(const MdShape& s);
+hipError_t mdlstm_forward(hipStream_t stream, const MdShape& s, const MdDir* dirs, const int32_t* widths, float* y,
+                          unsigned long long* halo, unsigned* err);
 // x into columns [2H, 2H + D) of the four hc arrays (S >= 2H + D)
 hipError_t mdlstm_copy_x(hipStream_t stream, const MdShape& s, const MdDir* dirs, const float* x, int D);
 // rows [0,H), [H,2H), [2H,2H+D) of four stacked [2H + D, 5H] gradients to dRu, dRv, dW
@@ -137,7 +140,7 @@ hipError_t mdlstm_scatter_grads(hipStream_t stream, int D, int H, const float* c
 // dbpart: scratch of mdlstm_dbpart_floats(); db[4]: bias gradients [5H] per direction
 size_t mdlstm_dbpart_floats(const MdShape& s);
 hipError_t mdlstm_backward(hipStream_t stream, const MdShape& s, const MdDir* dirs, const int32_t* widths, const float* dy,
-                           float* dbpart, float* const* db);
+                           float* dbpart, float* const* db, unsigned long long* halo, unsigned* err);
 
 // bare exchange of the persistent kernels' step chain (measurement aid, see exchange_probe.hip)
 size_t exchange_probe_bytes(int groups, int members, int tile_bytes);

@@ -32,6 +32,7 @@ def run_layer(wl, want_dx=True, fill=float("nan")):
     dx = torch.full_like(x, fill) if want_dx else None
     rl.mdlstm_bwd(desc, x, params, widths, reserve, dy, dx, grads, ws)
     torch.cuda.synchronize()
+    assert rl.rlstm_last_timeout(ws) == 0
     out = dict(y=y.cpu().numpy(), grads=[g.cpu().numpy() for g in grads])
     if want_dx:
         out["dx"] = dx.cpu().numpy()
@@ -77,6 +78,8 @@ def check(got, ref, what, ref32=None):
     dict(Hh=3, B=5, D=4, H=32, w_lo=50, w_hi=70, wscale=0.15),  # wide and flat
     dict(Hh=50, B=3, D=2, H=7, w_lo=1, w_hi=2, wscale=0.3),     # narrow and tall
     dict(Hh=6, B=2, D=40, H=12, w_lo=4, w_hi=11, wscale=0.2),   # wide input: dW as a product of its own
+    dict(Hh=33, B=3, D=2, H=16, w_lo=2, w_hi=12, wscale=0.2),   # two bands of rows, one row in the second
+    dict(Hh=100, B=2, D=1, H=24, w_lo=5, w_hi=30, wscale=0.12), # four bands handing rows to each other
 ])
 def test_mdlstm_shapes_against_oracle(shape):
     wl = synth.make_image_workload("t", bias_scale=0.2, seed=50 + shape["Hh"] + shape["H"], **shape)
@@ -115,7 +118,7 @@ def test_mdlstm_padding_values_have_no_influence():
 
 
 def test_mdlstm_argument_errors():
-    d = rl.rmdlstm_desc(Hh=65, Ww=4, B=1, D=1, H=8, operand_dtype=0)
+    d = rl.rmdlstm_desc(Hh=257, Ww=4, B=1, D=1, H=8, operand_dtype=0)
     assert rl.rmdlstm_reserve_bytes(d) == 0
     d2 = rl.rmdlstm_desc(Hh=8, Ww=4, B=1, D=1, H=33, operand_dtype=0)
     assert rl.rmdlstm_workspace_bytes(d2) == 0
