@@ -158,7 +158,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config3", choices=["config2", "config3", "config4", "config5"])
+    ap.add_argument("--workload", default="config3", choices=["config2", "config3", "config4", "config5", "paper_chunks"])
     ap.add_argument("--engine", type=int, default=0)
     ap.add_argument("--one-stream", action="store_true")
     ap.add_argument("--first-piece", type=int, default=None,
@@ -185,12 +185,31 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
-    wl = {"config2": synth.config2, "config3": synth.config3, "config4": synth.config4}[args.workload]()
+    wl = {"config2": synth.config2, "config3": synth.config3, "config4": synth.config4,
+          "paper_chunks": synth.paper_chunks}[args.workload]()
     log(f"workload {wl.name}: L={wl.L} T={wl.T} B={wl.B} D={wl.D} H={wl.H} frames={wl.frames} slots={wl.T * wl.B}")
 
     desc = rl.rblstm_desc(L=wl.L, T=wl.T, B=wl.B, D=wl.D, H=wl.H, operand_dtype=wl.operand_dtype, engine=args.engine)
     x = torch.from_numpy(wl.x).to(dev)
     sl = torch.from_numpy(wl.seq_lens).to(dev)
+    chunking = None
+    if args.workload == "paper_chunks":
+        # the batch is cut from the corpus on the device: segment table on the host, gather kernel
+        cx, clens = synth.paper_corpus()
+        cseq, cstart, clen = rl.rlstm_chunk_plan(clens, wl.T, wl.T)
+        cxd = torch.from_numpy(cx).to(dev)
+        tab = [torch.from_numpy(a[:wl.B].copy()).to(dev) for a in (cseq, cstart, clen)]
+        x = torch.empty((wl.T, wl.B, wl.D), device=dev)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        rl.rlstm_chunk_gather(cxd, tab[0], tab[1], tab[2], wl.T, x)
+        e0.record()
+        rl.rlstm_chunk_gather(cxd, tab[0], tab[1], tab[2], wl.T, x)
+        e1.record()
+        torch.cuda.synchronize()
+        assert np.array_equal(x.cpu().numpy(), wl.x) and np.array_equal(clen[:wl.B], wl.seq_lens)
+        sl = tab[2]
+        chunking = {"corpus_sequences": int(len(clens)), "corpus_frames": int(clens.sum()), "segments": int(len(cseq)),
+                    "segment_frames": wl.T, "gather_ms": e0.elapsed_time(e1)}
     params = [torch.from_numpy(a).to(dev) for layer in wl.params for p in layer for a in p]
     grads = [torch.empty_like(p) for p in params]
     G = torch.from_numpy(wl.G).to(dev)
@@ -310,6 +329,8 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
     }
+    if chunking:
+        out["config"]["chunking"] = chunking
     if not args.no_cpu_baseline and args.workload != "config4":
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out), flush=True)

@@ -275,6 +275,30 @@ RLSTM_API int mdlstm_bwd(const rmdlstm_desc* d, const float* x, const float* con
                          void* hip_stream);
 
 /*
+ * Chunking (Sec. 3: sequences whose lengths differ a lot are cut into segments of constant
+ * length, possibly overlapping, so that a minibatch carries little zero padding, at the price of
+ * the context across segment borders; Sec. 6 trains on segments of 250 frames, zero-padded where a
+ * sequence ends, 81 per batch).
+ *
+ * rlstm_chunk_plan (host, integers only): the segments of a sequence of n = seq_lens[b] frames
+ * start at frames 0, step, 2*step, ... (every start < n) and hold min(size, n - start) frames.
+ * Writes, sequence by sequence with starts ascending, for chunk k: chunk_seq[k] = b,
+ * chunk_start[k], chunk_len[k] (host arrays of max_chunks entries; any may be null) and returns
+ * the number of segments, which may exceed max_chunks (then only the first max_chunks entries were
+ * written), or a negative code.
+ *
+ * rlstm_chunk_gather (device): xc[t, k, :] = x[chunk_start[k] + t, chunk_seq[k], :] for
+ * t < chunk_len[k], else 0; x [T, B, ldx] (ldx = 0 means D), xc [size, n_chunks, D], the three
+ * tables are device arrays of n_chunks entries.  chunk_len is the seq_lens of the minibatch xc.
+ * Table entries that point outside x are treated as padding.
+ */
+RLSTM_API long long rlstm_chunk_plan(const int32_t* seq_lens, int B, int size, int step, int32_t* chunk_seq,
+                                     int32_t* chunk_start, int32_t* chunk_len, long long max_chunks);
+RLSTM_API int rlstm_chunk_gather(const float* x, int T, int B, int D, int ldx, const int32_t* chunk_seq,
+                                 const int32_t* chunk_start, const int32_t* chunk_len, int n_chunks, int size,
+                                 float* xc, void* hip_stream);
+
+/*
  * How the persistent engine lays a stack's recurrent passes out on this device (for reports).
  * out[8] (host): {groups of workgroups (directions * groups of sequences), sequences per group,
  * rows a group's tiles hold, units per workgroup, workgroups per group in the forward kernel,

@@ -2,7 +2,8 @@
 from .lstm_oracle import (blstm_stack_backward, blstm_stack_forward, blstm_stack_loss,
                           lstm_backward, lstm_forward, sigmoid)
 
+from .chunking_oracle import chunk_batch, chunk_table
 from .mdlstm_oracle import DIRECTIONS, mdlstm4_backward, mdlstm4_forward, mdlstm_backward, mdlstm_forward
 
-__all__ = ["mdlstm_forward", "mdlstm_backward", "mdlstm4_forward", "mdlstm4_backward", "DIRECTIONS", "lstm_forward", "lstm_backward", "blstm_stack_forward", "blstm_stack_backward",
+__all__ = ["chunk_table", "chunk_batch", "mdlstm_forward", "mdlstm_backward", "mdlstm4_forward", "mdlstm4_backward", "DIRECTIONS", "lstm_forward", "lstm_backward", "blstm_stack_forward", "blstm_stack_backward",
            "blstm_stack_loss", "sigmoid"]

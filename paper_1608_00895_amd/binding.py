@@ -24,7 +24,7 @@ RLSTM_ENGINE_STEPWISE = 2
 EXPORTS = [
     "rlstm_reserve_bytes", "rlstm_workspace_bytes", "rblstm_reserve_bytes", "rblstm_workspace_bytes",
     "lstm_fwd", "lstm_bwd", "blstm_stack_fwd_bwd", "blstm_stack_fwd",
-    "rlstm_gemm_f32", "rlstm_gemm_bf16", "rlstm_copy_f32", "rlstm_profile_enable", "rlstm_profile_read", "rlstm_last_timeout", "rlstm_test_hook", "rlstm_set_first_piece", "rlstm_set_batch_groups", "rmdlstm_reserve_bytes", "rmdlstm_workspace_bytes", "mdlstm_fwd", "mdlstm_bwd", "rblstm_plan", "rlstm_exchange_floor_bytes", "rlstm_exchange_floor", "rlstm_resolve_engine", "rlstm_strerror", "rlstm_version",
+    "rlstm_gemm_f32", "rlstm_gemm_bf16", "rlstm_copy_f32", "rlstm_profile_enable", "rlstm_profile_read", "rlstm_last_timeout", "rlstm_test_hook", "rlstm_set_first_piece", "rlstm_set_batch_groups", "rmdlstm_reserve_bytes", "rmdlstm_workspace_bytes", "mdlstm_fwd", "mdlstm_bwd", "rlstm_chunk_plan", "rlstm_chunk_gather", "rblstm_plan", "rlstm_exchange_floor_bytes", "rlstm_exchange_floor", "rlstm_resolve_engine", "rlstm_strerror", "rlstm_version",
 ]
 
 
@@ -105,6 +105,11 @@ def lib() -> ctypes.CDLL:
         L.mdlstm_bwd.restype = ip
         L.mdlstm_bwd.argtypes = [ctypes.POINTER(rmdlstm_desc), vp, ctypes.POINTER(vp), vp, vp, vp, vp,
                                  ctypes.POINTER(vp), vp, vp]
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        L.rlstm_chunk_plan.restype = ctypes.c_longlong
+        L.rlstm_chunk_plan.argtypes = [i32p, ip, ip, ip, i32p, i32p, i32p, ctypes.c_longlong]
+        L.rlstm_chunk_gather.restype = ip
+        L.rlstm_chunk_gather.argtypes = [vp, ip, ip, ip, ip, vp, vp, vp, ip, ip, vp, vp]
         L.rblstm_plan.restype = ip
         L.rblstm_plan.argtypes = [ctypes.POINTER(rblstm_desc), ctypes.POINTER(ctypes.c_int32)]
         L.rlstm_exchange_floor_bytes.restype = ctypes.c_size_t
@@ -326,4 +331,29 @@ def mdlstm_bwd(desc, x, params, widths, reserve, dy, dx, grads, workspace, strea
                           _ptr(dx), _ptr_array(grads), _ptr(workspace), _stream(stream))
     if check and rc != 0:
         raise RlstmError(rc, "mdlstm_bwd")
+    return rc
+
+
+def rlstm_chunk_plan(seq_lens, size: int, step: int):
+    """Segment table (host): returns numpy int32 arrays (chunk_seq, chunk_start, chunk_len)."""
+    import numpy as np
+    sl = np.ascontiguousarray(np.asarray(seq_lens), dtype=np.int32)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    n = int(lib().rlstm_chunk_plan(sl.ctypes.data_as(i32p), len(sl), int(size), int(step), None, None, None, 0))
+    if n < 0:
+        raise RlstmError(n, "rlstm_chunk_plan")
+    seq, start, ln = (np.empty(n, np.int32) for _ in range(3))
+    m = int(lib().rlstm_chunk_plan(sl.ctypes.data_as(i32p), len(sl), int(size), int(step), seq.ctypes.data_as(i32p),
+                                   start.ctypes.data_as(i32p), ln.ctypes.data_as(i32p), n))
+    assert m == n
+    return seq, start, ln
+
+
+def rlstm_chunk_gather(x, chunk_seq, chunk_start, chunk_len, size: int, xc, ldx: int = 0, stream=None, check=True) -> int:
+    T, B = int(x.shape[0]), int(x.shape[1])
+    D = int(xc.shape[2])
+    rc = lib().rlstm_chunk_gather(_ptr(x), T, B, D, int(ldx), _ptr(chunk_seq), _ptr(chunk_start), _ptr(chunk_len),
+                                  int(chunk_seq.numel()), int(size), _ptr(xc), _stream(stream))
+    if check and rc != 0:
+        raise RlstmError(rc, "rlstm_chunk_gather")
     return rc

@@ -482,6 +482,23 @@ int mdlstm_bwd(const rmdlstm_desc* d, const float* x, const float* const* params
   return RLSTM_OK;
 }
 
+long long rlstm_chunk_plan(const int32_t* seq_lens, int B, int size, int step, int32_t* chunk_seq, int32_t* chunk_start,
+                           int32_t* chunk_len, long long max_chunks) {
+  if (!seq_lens) return RLSTM_ENULL;
+  if (B <= 0 || size <= 0 || step <= 0 || max_chunks < 0) return RLSTM_EDIM;
+  return chunk_plan(seq_lens, B, size, step, chunk_seq, chunk_start, chunk_len, max_chunks);
+}
+
+int rlstm_chunk_gather(const float* x, int T, int B, int D, int ldx, const int32_t* chunk_seq, const int32_t* chunk_start,
+                       const int32_t* chunk_len, int n_chunks, int size, float* xc, void* hip_stream) {
+  if (!x || !chunk_seq || !chunk_start || !chunk_len || !xc) return RLSTM_ENULL;
+  if (T <= 0 || B <= 0 || D <= 0 || n_chunks < 0 || size <= 0 || (ldx != 0 && ldx < D)) return RLSTM_EDIM;
+  int resident_err = 0;
+  RLSTM_TRY(chunk_gather(static_cast<hipStream_t>(hip_stream), x, T, B, D, ldx ? ldx : D, chunk_seq, chunk_start,
+                         chunk_len, n_chunks, size, xc));
+  return RLSTM_OK;
+}
+
 int rlstm_copy_f32(float* dst, const float* src, size_t n, void* hip_stream) {
   if (!dst || !src) return RLSTM_ENULL;
   int resident_err = 0;

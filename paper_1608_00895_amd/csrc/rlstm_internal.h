@@ -142,6 +142,12 @@ size_t mdlstm_dbpart_floats(const MdShape& s);
 hipError_t mdlstm_backward(hipStream_t stream, const MdShape& s, const MdDir* dirs, const int32_t* widths, const float* dy,
                            float* dbpart, float* const* db, unsigned long long* halo, unsigned* err);
 
+// chunking (chunking.hip): segment table on the host, gather of the segments into a minibatch on the device
+long long chunk_plan(const int32_t* seq_lens, int B, int size, int step, int32_t* seq, int32_t* start, int32_t* len,
+                     long long max_chunks);
+hipError_t chunk_gather(hipStream_t stream, const float* x, int T, int B, int D, int ldx, const int32_t* seq,
+                        const int32_t* start, const int32_t* len, int nchunks, int size, float* xc);
+
 // bare exchange of the persistent kernels' step chain (measurement aid, see exchange_probe.hip)
 size_t exchange_probe_bytes(int groups, int members, int tile_bytes);
 hipError_t exchange_probe(hipStream_t stream, int groups, int members, int tile_bytes, int read_bytes, int steps,

@@ -177,3 +177,50 @@ def config5() -> ImageWorkload:
     image is not contractive and float32 arithmetic itself is 1e-3 .. 1e-2 away from float64."""
     return make_image_workload("config5_mdlstm_h64_B8_H32", Hh=64, B=8, D=1, H=32, w_lo=200, w_hi=800,
                                wscale=0.1, seed=5, forget_bias=-1.0)
+
+
+def paper_corpus(n_seq: int = 40, seed: int = 6) -> Tuple[np.ndarray, np.ndarray]:
+    """A corpus shaped like the one the paper's experiments use (Sec. 6): 45 values per frame, segment
+    lengths around 738 frames with a spread of 291 (drawn normal, clipped to [100, 1600]).  Returns
+    (x [T, n_seq, 45] float32 ~ N(0,1), zero past each length; lengths int32)."""
+    rng = np.random.Generator(np.random.Philox(seed))
+    lens = np.clip(np.rint(rng.normal(738.0, 291.0, n_seq)), 100, 1600).astype(np.int32)
+    T = int(lens.max())
+    x = rng.standard_normal((T, n_seq, 45), dtype=np.float32)
+    for b in range(n_seq):
+        x[lens[b]:, b, :] = 0.0
+    return x, lens
+
+
+def paper_chunks() -> Workload:
+    """The batch shape the paper times (Sec. 6): the corpus above cut into segments of 250 frames without
+    overlap, the first 81 segments as one minibatch, three bidirectional layers of 512 units, fp32.
+    The segmentation here is plain slicing of the corpus arrays (no LSTM arithmetic)."""
+    cx, clens = paper_corpus()
+    size, nb = 250, 81
+    cols, lens = [], []
+    for b in range(len(clens)):
+        for t0 in range(0, int(clens[b]), size):
+            n = min(size, int(clens[b]) - t0)
+            seg = np.zeros((size, cx.shape[2]), np.float32)
+            seg[:n] = cx[t0:t0 + n, b]
+            cols.append(seg)
+            lens.append(n)
+    assert len(cols) >= nb
+    x = np.ascontiguousarray(np.stack(cols[:nb], axis=1))
+    seq_lens = np.array(lens[:nb], np.int32)
+    rng = np.random.Generator(np.random.Philox(66))
+    L, D, H = 3, 45, 512
+    params = []
+    for l in range(L):
+        din = D if l == 0 else 2 * H
+        layer = []
+        for _ in range(2):
+            W = rng.uniform(-0.05, 0.05, (din, 4 * H)).astype(np.float32)
+            R = rng.uniform(-0.05, 0.05, (H, 4 * H)).astype(np.float32)
+            layer.append((W, R, np.zeros(4 * H, np.float32)))
+        params.append(layer)
+    G = rng.standard_normal((size, nb, 2 * H)).astype(np.float32)
+    for b in range(nb):
+        G[seq_lens[b]:, b, :] = 0.0
+    return Workload("paper_3x512_81_segments_of_250", L, size, nb, D, H, True, 0, seq_lens, x, params, G)
