@@ -38,9 +38,10 @@ def rec_bytes(kind, wl, steps):
     return 2.0 * steps * wl.B * per_slot_dir
 
 
-def cpu_baseline(wl_full, seconds_budget=20.0):
+def cpu_baseline(wl_full, seconds_budget=20.0, output_layer=None):
     """Times the oracle (as it is, numpy fp64) on a bounded sample of the same workload:
-    the same network on the first Ts frames of the minibatch."""
+    the same network on the first Ts frames of the minibatch.  output_layer = (Wo, bo, labels): the
+    sample is a whole training step (output layer between the passes, Adam update of every parameter)."""
     import numpy as np
     from threadpoolctl import threadpool_info
     from oracle import blstm_stack_backward, blstm_stack_forward
@@ -52,15 +53,27 @@ def cpu_baseline(wl_full, seconds_budget=20.0):
     params = [[tuple(a.astype(np.float64) for a in p) for p in layer] for layer in wl_full.params]
     x = wl_full.x[:Ts].astype(np.float64)
     G = wl_full.G[:Ts].astype(np.float64)
+    what = "forward+backward"
     t0 = time.perf_counter()
     y, caches = blstm_stack_forward(x, params, lens)
-    blstm_stack_backward(caches, G)
+    if output_layer is None:
+        blstm_stack_backward(caches, G)
+    else:
+        from oracle import adam_step, softmax_ce_backward, softmax_ce_forward
+        Wo, bo, labels = output_layer
+        g = softmax_ce_backward(softmax_ce_forward(y, Wo, bo, labels[:Ts], lens))
+        grads, _ = blstm_stack_backward(caches, g["dy"])
+        flat_p = [a for layer in params for p in layer for a in p] + [Wo.astype(np.float64), bo.astype(np.float64)]
+        flat_g = [grads[l][d][k] for l in range(wl_full.L) for d in range(2) for k in ("dW", "dR", "db")] + [g["dWo"], g["dbo"]]
+        for p, gr in zip(flat_p, flat_g):
+            adam_step(p, gr, np.zeros_like(p), np.zeros_like(p), 1e-5, 0.9, 0.999, 1e-8, 1)
+        what = "training step (forward, softmax/cross-entropy, backward, Adam)"
     dt = time.perf_counter() - t0
     threads = max([i.get("num_threads", 1) for i in threadpool_info() if i.get("user_api") == "blas"] or [1])
     frames = int(lens.sum())
     return {"value": frames / dt, "unit": "frames/s", "cores": int(threads), "kind": "oracle",
             "sample": f"{wl_full.name}: same {wl_full.L}-layer network, first {Ts} frames of all {wl_full.B} "
-                      f"sequences ({frames} frames), numpy fp64 forward+backward, {dt:.1f} s"}
+                      f"sequences ({frames} frames), numpy fp64 {what}, {dt:.1f} s"}
 
 
 def bench_config5(args):
@@ -158,7 +171,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config3", choices=["config2", "config3", "config4", "config5", "paper_chunks"])
+    ap.add_argument("--workload", default="config3", choices=["config2", "config3", "config4", "config5", "paper_chunks", "paper_train"])
     ap.add_argument("--engine", type=int, default=0)
     ap.add_argument("--one-stream", action="store_true")
     ap.add_argument("--first-piece", type=int, default=None,
@@ -186,14 +199,14 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     wl = {"config2": synth.config2, "config3": synth.config3, "config4": synth.config4,
-          "paper_chunks": synth.paper_chunks}[args.workload]()
+          "paper_chunks": synth.paper_chunks, "paper_train": synth.paper_chunks}[args.workload]()
     log(f"workload {wl.name}: L={wl.L} T={wl.T} B={wl.B} D={wl.D} H={wl.H} frames={wl.frames} slots={wl.T * wl.B}")
 
     desc = rl.rblstm_desc(L=wl.L, T=wl.T, B=wl.B, D=wl.D, H=wl.H, operand_dtype=wl.operand_dtype, engine=args.engine)
     x = torch.from_numpy(wl.x).to(dev)
     sl = torch.from_numpy(wl.seq_lens).to(dev)
     chunking = None
-    if args.workload == "paper_chunks":
+    if args.workload in ("paper_chunks", "paper_train"):
         # the batch is cut from the corpus on the device: segment table on the host, gather kernel
         cx, clens = synth.paper_corpus()
         cseq, cstart, clen = rl.rlstm_chunk_plan(clens, wl.T, wl.T)
@@ -210,8 +223,33 @@ def main():
         sl = tab[2]
         chunking = {"corpus_sequences": int(len(clens)), "corpus_frames": int(clens.sum()), "segments": int(len(cseq)),
                     "segment_frames": wl.T, "gather_ms": e0.elapsed_time(e1)}
-    params = [torch.from_numpy(a).to(dev) for layer in wl.params for p in layer for a in p]
-    grads = [torch.empty_like(p) for p in params]
+    train = None
+    host_params = [a for layer in wl.params for p in layer for a in p]
+    if args.workload == "paper_train":
+        # a whole training step: the 1501-class softmax / cross-entropy layer on top (Sec. 6) and an Adam update of
+        # every parameter; parameters, gradients and Adam's two moments live in one flat buffer each
+        C = 1501
+        Wo, bo, labels = synth.output_layer(wl.T, wl.B, 2 * wl.H, C, seed=67, wscale=0.05)
+        host_params = host_params + [Wo, bo]
+        train = {"C": C, "Wo": Wo, "bo": bo, "labels": labels}
+    n_all = sum(a.size for a in host_params)
+    flat_p = torch.empty(n_all, device=dev)
+    flat_g = torch.zeros(n_all, device=dev)
+    params, grads, o = [], [], 0
+    for a in host_params:
+        flat_p[o:o + a.size] = torch.from_numpy(a).reshape(-1).to(dev)
+        params.append(flat_p[o:o + a.size].view(a.shape))
+        grads.append(flat_g[o:o + a.size].view(a.shape))
+        o += a.size
+    if train:
+        train.update(dWo=grads[-2], dbo=grads[-1], dev_Wo=params[-2], dev_bo=params[-1],
+                     labels_dev=torch.from_numpy(labels).to(dev), m=torch.zeros(n_all, device=dev),
+                     v=torch.zeros(n_all, device=dev), loss=torch.zeros(1, device=dev),
+                     errors=torch.zeros(1, dtype=torch.int32, device=dev),
+                     dy=torch.empty((wl.T, wl.B, 2 * wl.H), device=dev),
+                     ws=torch.empty(rl.rlstm_ce_workspace_bytes(wl.T, wl.B, 2 * wl.H, C), dtype=torch.uint8, device=dev),
+                     step=0)
+        params, grads = params[:-2], grads[:-2]
     G = torch.from_numpy(wl.G).to(dev)
     y_top = torch.empty((wl.T, wl.B, 2 * wl.H), device=dev)
     reserve = torch.empty(rl.rblstm_reserve_bytes(desc), dtype=torch.uint8, device=dev)
@@ -225,7 +263,17 @@ def main():
 
     def step():
         # the bottom layer's input gradient is not needed for training and is skipped (dx = null)
-        rl.blstm_stack_fwd_bwd(desc, x, params, sl, G, y_top, grads, None, reserve, ws, sa, sb)
+        if train is None:
+            rl.blstm_stack_fwd_bwd(desc, x, params, sl, G, y_top, grads, None, reserve, ws, sa, sb)
+            return
+        F = 2 * wl.H
+        rl.blstm_stack_fwd(desc, x, params, sl, y_top, reserve, ws, sa)
+        rl.softmax_ce_fwd_bwd(wl.T, wl.B, F, train["C"], wl.operand_dtype, y_top, train["dev_Wo"], train["dev_bo"],
+                              train["labels_dev"], sl, train["loss"], train["errors"], train["dy"], train["dWo"],
+                              train["dbo"], train["ws"], sa)
+        rl.blstm_stack_bwd(desc, x, params, sl, train["dy"], y_top, grads, None, reserve, ws, sa, sb)
+        train["step"] += 1
+        rl.rlstm_adam_step(flat_p, flat_g, train["m"], train["v"], 1e-5, 0.9, 0.999, 1e-8, train["step"], sa)
 
     for _ in range(args.warmup):
         step()
@@ -331,8 +379,13 @@ def main():
     }
     if chunking:
         out["config"]["chunking"] = chunking
+    if train:
+        out["metric"] = "BLSTM train frames/sec (whole training step: fwd, softmax/CE, bwd, Adam)"
+        out["config"].update(classes=train["C"], update="adam", parameters=int(n_all),
+                             loss_per_frame=float(train["loss"].item()) / wl.frames,
+                             frame_error_rate=int(train["errors"].item()) / wl.frames)
     if not args.no_cpu_baseline and args.workload != "config4":
-        out["cpu_baseline"] = cpu_baseline(wl)
+        out["cpu_baseline"] = cpu_baseline(wl, output_layer=(train["Wo"], train["bo"], train["labels"]) if train else None)
     print(json.dumps(out), flush=True)
 
 

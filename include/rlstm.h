@@ -63,7 +63,7 @@ extern "C" {
 #define RLSTM_ENULL      -1   /* a required pointer is null */
 #define RLSTM_EDIM       -2   /* a dimension is <= 0 or a leading dimension is too small */
 #define RLSTM_EMODE      -3   /* bad direction / operand_dtype / engine */
-#define RLSTM_ESIZE      -4   /* reserved */
+#define RLSTM_ESIZE      -4   /* a workspace passed with its size is too small */
 #define RLSTM_ERESIDENT  -5   /* persistent kernel cannot be made co-resident / shape unsupported by the engine */
 #define RLSTM_EHIP       -6   /* a HIP runtime call failed */
 
@@ -163,6 +163,17 @@ RLSTM_API int blstm_stack_fwd_bwd(const rblstm_desc* desc, const float* x, const
                         float* y_top, float* const* grads, float* dx,
                         void* reserve, void* workspace, void* hip_stream_a, void* hip_stream_b);
 
+/*
+ * blstm_stack_bwd - the backward half alone: the same arguments, after a blstm_stack_fwd (or
+ * blstm_stack_fwd_bwd) call with the same descriptor, x, params, seq_lens, reserve and workspace
+ * whose y_top is passed back in.  This is the form a loss layer on top of the stack needs, whose
+ * dy_top depends on y_top (softmax_ce_fwd_bwd below).  dy_top must be complete in stream_a's order.
+ */
+RLSTM_API int blstm_stack_bwd(const rblstm_desc* desc, const float* x, const float* const* params,
+                    const int32_t* seq_lens, const float* dy_top, const float* y_top,
+                    float* const* grads, float* dx,
+                    void* reserve, void* workspace, void* hip_stream_a, void* hip_stream_b);
+
 /* Forward half only of the stack (inference / parity of hidden layers):
  * same arguments as above without gradients. */
 RLSTM_API int blstm_stack_fwd(const rblstm_desc* desc, const float* x, const float* const* params,
@@ -199,6 +210,7 @@ RLSTM_API int rlstm_gemm_bf16(int trans_a, int trans_b, int M, int N, int K,
  *   kind: 0 input projection X W + b        1 recurrent forward pass
  *         2 pass back through time          3 input gradient dZ W^T
  *         4 weight gradient X^T dZ          5 recurrent weight gradient Hprev^T dZ
+ *         6 product of the output layer     7 softmax / cross-entropy rows and their sums
  *   layer: stack layer (0 for the single-layer entry points); ndir: directions covered;
  *   steps: recurrent steps the group covers (a pass may be cut into several groups; 0 for a
  *   matrix product); flop: algorithmic floating-point operations of the group (2 M N K of a
@@ -297,6 +309,41 @@ RLSTM_API long long rlstm_chunk_plan(const int32_t* seq_lens, int B, int size, i
 RLSTM_API int rlstm_chunk_gather(const float* x, int T, int B, int D, int ldx, const int32_t* chunk_seq,
                                  const int32_t* chunk_start, const int32_t* chunk_len, int n_chunks, int size,
                                  float* xc, void* hip_stream);
+
+/*
+ * softmax_ce_fwd_bwd - the frame-wise output layer of the acoustic model (Sec. 6: a softmax
+ * output layer over the tied-state classes on top of the BLSTM stack, trained with the
+ * cross-entropy criterion; the frame error rate is what Table 3 reports) and its gradients:
+ *   z = y Wo + bo;  p = softmax(z) per frame;  loss = sum over valid frames of -log p[label];
+ *   errors = number of valid frames whose largest p (lowest index on ties) is not the label;
+ *   dz = p - onehot(label) on valid frames, 0 elsewhere;  dy = dz Wo^T;  dWo = y^T dz;
+ *   dbo = column sums of dz.  A frame (t, b) is valid when t < seq_lens[b] (clamped to [0, T])
+ *   and 0 <= label < C; batch gradients are sums, as everywhere in this library.
+ *   y [T,B,F] in;  Wo [F,C], bo [C] in;  labels [T,B] int32 in;  seq_lens [B] in;
+ *   loss (one float), errors (one int32), dy [T,B,F], dWo [F,C], dbo [C] out; all DEVICE.
+ *   operand_dtype as in rlstm_desc (the three products).  workspace: rlstm_ce_workspace_bytes()
+ *   bytes of DEVICE scratch (logits with the class dimension padded to a multiple of 4, padded
+ *   copies of Wo and dWo, partial sums); RLSTM_ESIZE when workspace_bytes is smaller.
+ *   All sums are taken in a fixed order: results are bit-reproducible from run to run.
+ *
+ * rlstm_sgd_momentum_step, rlstm_adam_step - the two update rules the training runs use (Sec. 4.3,
+ * Sec. 6), elementwise over n parameters, in place, DEVICE arrays:
+ *   SGD with momentum:  v <- momentum v + g;  param <- param - learning_rate v
+ *   Adam (Kingma & Ba): m <- b1 m + (1 - b1) g;  v <- b2 v + (1 - b2) g^2;
+ *       param <- param - learning_rate (m / (1 - b1^step)) / (sqrt(v / (1 - b2^step)) + epsilon),
+ *       step = 1 for the first update.  RLSTM_EDIM for step < 1 or a beta outside [0, 1).
+ *   The hyper-parameters are doubles: 1 - beta and the two bias corrections are formed in double
+ *   and rounded to float32 once; the elementwise arithmetic is float32.
+ */
+RLSTM_API size_t rlstm_ce_workspace_bytes(int T, int B, int F, int C);
+RLSTM_API int softmax_ce_fwd_bwd(int T, int B, int F, int C, int operand_dtype, const float* y, const float* Wo,
+                                 const float* bo, const int32_t* labels, const int32_t* seq_lens, float* loss,
+                                 int32_t* errors, float* dy, float* dWo, float* dbo, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream);
+RLSTM_API int rlstm_sgd_momentum_step(float* param, const float* grad, float* velocity, size_t n, double learning_rate,
+                                      double momentum, void* hip_stream);
+RLSTM_API int rlstm_adam_step(float* param, const float* grad, float* m, float* v, size_t n, double learning_rate,
+                              double beta1, double beta2, double epsilon, int step, void* hip_stream);
 
 /*
  * How the persistent engine lays a stack's recurrent passes out on this device (for reports).

@@ -10,7 +10,8 @@ with Adam (cited), gradients of a batch are sums (not scaled by the batch size);
 outside their sequence must have no influence.
 Readings where the paper is silent: the output layer is an affine map of the top layer's output followed
 by a softmax over the classes; the loss is the sum over the valid frames of -log p(label); a frame counts
-as misclassified when the largest logit is not the label's (first index wins a tie); Adam as published by
+as misclassified when the largest logit is not the label's (first index wins a tie); a frame whose label is
+not a class index (negative, or >= C) is left out like a frame outside its sequence; Adam as published by
 Kingma & Ba (bias-corrected first and second moments); momentum as v <- mu v + g, theta <- theta - lr v.
 """
 from __future__ import annotations
@@ -37,7 +38,7 @@ def softmax_ce_forward(y, Wo, bo, labels, seq_lens):
         z = z - z.max(axis=1, keepdims=True)
         logp = z - np.log(np.exp(z).sum(axis=1, keepdims=True))
         for b in range(B):
-            if t < seq_lens[b]:
+            if t < seq_lens[b] and 0 <= labels[t, b] < C:
                 p[t, b] = np.exp(logp[b])
                 loss -= logp[b, labels[t, b]]
                 errors += int(np.argmax(z[b]) != labels[t, b])
@@ -51,7 +52,7 @@ def softmax_ce_backward(fwd):
     dz = p.copy()
     for t in range(T):
         for b in range(B):
-            if t < seq_lens[b]:
+            if t < seq_lens[b] and 0 <= labels[t, b] < C:
                 dz[t, b, labels[t, b]] -= 1.0
     dWo = np.zeros_like(Wo)
     dbo = np.zeros(C, F64)

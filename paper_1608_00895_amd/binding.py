@@ -23,7 +23,8 @@ RLSTM_ENGINE_STEPWISE = 2
 
 EXPORTS = [
     "rlstm_reserve_bytes", "rlstm_workspace_bytes", "rblstm_reserve_bytes", "rblstm_workspace_bytes",
-    "lstm_fwd", "lstm_bwd", "blstm_stack_fwd_bwd", "blstm_stack_fwd",
+    "lstm_fwd", "lstm_bwd", "blstm_stack_fwd_bwd", "blstm_stack_fwd", "blstm_stack_bwd",
+    "rlstm_ce_workspace_bytes", "softmax_ce_fwd_bwd", "rlstm_sgd_momentum_step", "rlstm_adam_step",
     "rlstm_gemm_f32", "rlstm_gemm_bf16", "rlstm_copy_f32", "rlstm_profile_enable", "rlstm_profile_read", "rlstm_last_timeout", "rlstm_test_hook", "rlstm_set_first_piece", "rlstm_set_batch_groups", "rmdlstm_reserve_bytes", "rmdlstm_workspace_bytes", "mdlstm_fwd", "mdlstm_bwd", "rlstm_chunk_plan", "rlstm_chunk_gather", "rblstm_plan", "rlstm_exchange_floor_bytes", "rlstm_exchange_floor", "rlstm_resolve_engine", "rlstm_strerror", "rlstm_version",
 ]
 
@@ -49,7 +50,8 @@ class rlstm_profile_entry(ctypes.Structure):
 
 
 PROFILE_KINDS = {0: "input_projection", 1: "recurrent_forward", 2: "recurrent_backward",
-                 3: "input_gradient", 4: "weight_gradient", 5: "recurrent_weight_gradient"}
+                 3: "input_gradient", 4: "weight_gradient", 5: "recurrent_weight_gradient",
+                 6: "output_layer_product", 7: "softmax_cross_entropy_rows"}
 
 
 class RlstmError(RuntimeError):
@@ -83,6 +85,18 @@ def lib() -> ctypes.CDLL:
         L.blstm_stack_fwd_bwd.restype = ip
         L.blstm_stack_fwd_bwd.argtypes = [ctypes.POINTER(rblstm_desc), vp, ctypes.POINTER(vp), vp, vp, vp,
                                           ctypes.POINTER(vp), vp, vp, vp, vp, vp]
+        L.blstm_stack_bwd.restype = ip
+        L.blstm_stack_bwd.argtypes = [ctypes.POINTER(rblstm_desc), vp, ctypes.POINTER(vp), vp, vp, vp,
+                                      ctypes.POINTER(vp), vp, vp, vp, vp, vp]
+        L.rlstm_ce_workspace_bytes.restype = ctypes.c_size_t
+        L.rlstm_ce_workspace_bytes.argtypes = [ip, ip, ip, ip]
+        L.softmax_ce_fwd_bwd.restype = ip
+        L.softmax_ce_fwd_bwd.argtypes = [ip, ip, ip, ip, ip] + [vp] * 11 + [ctypes.c_size_t, vp]
+        L.rlstm_sgd_momentum_step.restype = ip
+        L.rlstm_sgd_momentum_step.argtypes = [vp, vp, vp, ctypes.c_size_t, ctypes.c_double, ctypes.c_double, vp]
+        L.rlstm_adam_step.restype = ip
+        L.rlstm_adam_step.argtypes = [vp, vp, vp, vp, ctypes.c_size_t, ctypes.c_double, ctypes.c_double, ctypes.c_double,
+                                      ctypes.c_double, ip, vp]
         L.blstm_stack_fwd.restype = ip
         L.blstm_stack_fwd.argtypes = [ctypes.POINTER(rblstm_desc), vp, ctypes.POINTER(vp), vp, vp, vp, vp, vp]
         L.rlstm_gemm_f32.restype = ip
@@ -215,6 +229,49 @@ def blstm_stack_fwd_bwd(desc, x, params, seq_lens, dy_top, y_top, grads, dx, res
                                    ga, _ptr(dx), _ptr(reserve), _ptr(workspace), _stream(stream_a), sb)
     if check and rc != 0:
         raise RlstmError(rc, "blstm_stack_fwd_bwd")
+    return rc
+
+
+def blstm_stack_bwd(desc, x, params, seq_lens, dy_top, y_top, grads, dx, reserve, workspace,
+                    stream_a=None, stream_b=None, check=True) -> int:
+    """Backward half alone, after blstm_stack_fwd with the same reserve and workspace."""
+    pa, ga = _ptr_array(params), _ptr_array(grads)
+    sb = ctypes.c_void_p(stream_b.cuda_stream) if stream_b is not None else None
+    rc = lib().blstm_stack_bwd(ctypes.byref(desc), _ptr(x), pa, _ptr(seq_lens), _ptr(dy_top), _ptr(y_top),
+                               ga, _ptr(dx), _ptr(reserve), _ptr(workspace), _stream(stream_a), sb)
+    if check and rc != 0:
+        raise RlstmError(rc, "blstm_stack_bwd")
+    return rc
+
+
+def rlstm_ce_workspace_bytes(T: int, B: int, F: int, C: int) -> int:
+    return int(lib().rlstm_ce_workspace_bytes(T, B, F, C))
+
+
+def softmax_ce_fwd_bwd(T, B, F, C, operand_dtype, y, Wo, bo, labels, seq_lens, loss, errors, dy, dWo, dbo, workspace,
+                       stream=None, check=True) -> int:
+    """loss: float32[1], errors: int32[1] device tensors; workspace: uint8 tensor of rlstm_ce_workspace_bytes()."""
+    rc = lib().softmax_ce_fwd_bwd(T, B, F, C, operand_dtype, _ptr(y), _ptr(Wo), _ptr(bo), _ptr(labels), _ptr(seq_lens),
+                                  _ptr(loss), _ptr(errors), _ptr(dy), _ptr(dWo), _ptr(dbo), _ptr(workspace),
+                                  workspace.numel() * workspace.element_size(), _stream(stream))
+    if check and rc != 0:
+        raise RlstmError(rc, "softmax_ce_fwd_bwd")
+    return rc
+
+
+def rlstm_sgd_momentum_step(param, grad, velocity, learning_rate, momentum, stream=None, check=True) -> int:
+    rc = lib().rlstm_sgd_momentum_step(_ptr(param), _ptr(grad), _ptr(velocity), param.numel(), learning_rate, momentum,
+                                       _stream(stream))
+    if check and rc != 0:
+        raise RlstmError(rc, "rlstm_sgd_momentum_step")
+    return rc
+
+
+def rlstm_adam_step(param, grad, m, v, learning_rate, beta1, beta2, epsilon, step, stream=None, check=True) -> int:
+    rc = lib().rlstm_adam_step(_ptr(param), _ptr(grad), _ptr(m), _ptr(v), param.numel(), learning_rate, beta1, beta2,
+                               epsilon, step, _stream(stream))
+    if check and rc != 0:
+        raise RlstmError(rc, "rlstm_adam_step")
     return rc
 
 

@@ -5,6 +5,7 @@
 #include "../../include/rlstm.h"
 #include "rlstm_internal.h"
 
+#include <cmath>
 #include <vector>
 
 using namespace rlstm;
@@ -228,6 +229,106 @@ int stack_forward(const rblstm_desc* d, const float* x, const float* const* para
     in = yl;
     din = 2 * H;
   }
+  return RLSTM_OK;
+}
+
+// Backward half of a training pass over the stack: consumes the reserve a forward pass left.
+int stack_backward(const rblstm_desc* d, const float* x, const float* const* params, const int32_t* seq_lens,
+                   const float* dy_top, const float* y_top, float* const* grads, float* dx, float* res, char* ws,
+                   hipStream_t sa, hipStream_t sb, bool persistent) {
+  const RecShape rs = stack_rec_shape(d);
+  const bool overlap = sb != sa;
+  int rc = RLSTM_OK;
+  int resident_err = 0;
+  const StackLayout lay = stack_layout(d);
+  const int T = d->T, B = d->B, H = d->H, L = d->L;
+  unsigned* flag = reinterpret_cast<unsigned*>(ws);
+  char* recws = ws + kFlagBytes;
+  float* skws = reinterpret_cast<float*>(recws + align_up(rec_workspace_bytes(rs), 256));
+  const int mm = d->D > 2 * H ? d->D : 2 * H;
+  const size_t skfloats = splitk_floats(mm, H);
+  const size_t dyfloats = align_up((size_t)T * B * 2 * H, 64);
+  float* dybuf[2] = {skws + skfloats, skws + skfloats + dyfloats};
+
+  // Stream a carries the chain of recurrent passes, stream b every matrix product.  The gradient
+  // w.r.t. a layer's input is the dy of the layer below: it is produced on stream b in the pieces,
+  // and in the frame order, in which that layer's pass back through time consumes it, one piece
+  // ahead; the weight gradients follow on stream b and overlap the rest of that pass.
+  const bool pipelined = persistent && overlap && products_can_share_cus(rs, d->operand_dtype);
+  const std::vector<int> pb = piece_bounds(T, pipelined);
+  const int np = (int)pb.size() - 1;
+  EventList evs;
+  std::vector<hipEvent_t> ready;       // ready[pc]: dy of piece pc of the layer about to run is complete
+
+  const float* dy = dy_top;
+  for (int l = L - 1; l >= 0; --l) {
+    float* base = res + (size_t)l * lay.per_layer;
+    const float* yl = (l == L - 1) ? y_top : base + lay.y;
+    const float* xin = (l == 0) ? x : res + (size_t)(l - 1) * lay.per_layer + lay.y;
+    const int din = (l == 0) ? d->D : 2 * H;
+    RecBwdDir dirs[2];
+    for (int k = 0; k < 2; ++k) {
+      dirs[k] = RecBwdDir{base + lay.zg[k], params[6 * l + 3 * k + 1], base + lay.c[k], nullptr,
+                          dy + (size_t)k * H, nullptr, nullptr, nullptr, nullptr, grads[6 * l + 3 * k + 2],
+                          k == 0 ? 1 : -1};
+    }
+    for (int pc = 0; pc < np; ++pc) {
+      if (!ready.empty()) RLSTM_TRY(hipStreamWaitEvent(sa, ready[pc], 0));
+      ProfScope ps(sa, 2, l, 2, pb[pc + 1] - pb[pc], rec_flop(rs, pb[pc + 1] - pb[pc]));
+      RLSTM_TRY(rec_backward(sa, rs, dirs, seq_lens, recws, flag, persistent, &resident_err, pb[pc], pb[pc + 1]));
+    }
+    ready.clear();
+    RLSTM_TRY(evs.order(sa, sb));
+
+    float* dxl = (l == 0) ? dx : dybuf[l & 1];
+    if (dxl && l > 0 && sb != sa) {
+      // columns [0,H) feed direction +1 of the layer below, which visits frames T-1 .. 0;
+      // columns [H,2H) feed direction -1, which visits frames 0 .. T-1
+      for (int pc = 0; pc < np; ++pc) {
+        const int s0 = pb[pc], s1 = pb[pc + 1];
+        for (int tk = 0; tk < 2; ++tk) {
+          const size_t f0 = (tk == 0) ? (size_t)(T - s1) : (size_t)s0;
+          for (int k = 0; k < 2; ++k) {
+            GemmCall g;
+            g.transB = true;
+            g.M = (s1 - s0) * B; g.N = H; g.K = 4 * H;
+            g.A = base + lay.zg[k] + f0 * B * 4 * H; g.lda = 4 * H;
+            g.B = params[6 * l + 3 * k + 0] + (size_t)tk * H * 4 * H; g.ldb = 4 * H;
+            g.C = dxl + f0 * B * din + (size_t)tk * H; g.ldc = din; g.accumulate = (k == 1);
+            g.naive = !persistent; g.operand_dtype = d->operand_dtype; g.small_footprint = pipelined;
+            ProfScope ps(sb, 3, l, 1, 0, gemm_flop(g));
+            RLSTM_TRY(gemm(sb, g));
+          }
+        }
+        hipEvent_t ev;
+        RLSTM_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+        evs.evs.push_back(ev);
+        RLSTM_TRY(hipEventRecord(ev, sb));
+        ready.push_back(ev);
+      }
+    } else if (dxl) {
+      for (int k = 0; k < 2; ++k) {
+        GemmCall g;
+        g.transB = true;
+        g.M = T * B; g.N = din; g.K = 4 * H;
+        g.A = base + lay.zg[k]; g.lda = 4 * H; g.B = params[6 * l + 3 * k + 0]; g.ldb = 4 * H;
+        g.C = dxl; g.ldc = din; g.accumulate = (k == 1);
+        g.naive = !persistent; g.operand_dtype = d->operand_dtype;
+        ProfScope ps(sb, 3, l, 1, 0, gemm_flop(g));
+        RLSTM_TRY(gemm(sb, g));
+      }
+      // one stream: already in order
+    }
+    for (int k = 0; k < 2; ++k) {
+      rc = weight_grads(sb, l, T, B, din, H, k == 0 ? 1 : -1, xin, din, yl + (size_t)k * H, 2 * H,
+                        base + lay.zg[k], grads[6 * l + 3 * k + 0], grads[6 * l + 3 * k + 1], skws, skfloats,
+                        !persistent, d->operand_dtype, pipelined);
+      if (rc != RLSTM_OK) return rc;
+    }
+    dy = dxl;
+  }
+  // the caller's stream a sees the end of everything
+  RLSTM_TRY(evs.order(sb, sa));
   return RLSTM_OK;
 }
 
@@ -499,6 +600,94 @@ int rlstm_chunk_gather(const float* x, int T, int B, int D, int ldx, const int32
   return RLSTM_OK;
 }
 
+// ---- output layer and parameter updates ------------------------------------------------------
+static int ce_pitch(int C) { return (int)align_up((size_t)C, 4); }
+static const int kCeSlices = 16;
+struct CeLayout { size_t z, wo, dwo, bo, scratch, splitk, total; };
+static CeLayout ce_layout(int T, int B, int F, int C) {
+  const size_t rows = (size_t)T * B, Cp = ce_pitch(C);
+  CeLayout l;
+  size_t o = 0;
+  l.z = o;       o += align_up(rows * Cp, 64);
+  l.wo = o;      o += align_up((size_t)F * Cp, 64);
+  l.dwo = o;     o += align_up((size_t)F * Cp, 64);
+  l.bo = o;      o += align_up(Cp, 64);
+  l.scratch = o; o += align_up(ce_scratch_floats((int)rows, (int)Cp), 64);
+  l.splitk = o;  o += align_up((size_t)kCeSlices * F * Cp, 64);
+  l.total = o;
+  return l;
+}
+
+size_t rlstm_ce_workspace_bytes(int T, int B, int F, int C) {
+  if (T <= 0 || B <= 0 || F <= 0 || C <= 0 || (long long)T * B > (1ll << 30) / 4) return 0;
+  return ce_layout(T, B, F, C).total * sizeof(float);
+}
+
+int softmax_ce_fwd_bwd(int T, int B, int F, int C, int operand_dtype, const float* y, const float* Wo, const float* bo,
+                       const int32_t* labels, const int32_t* seq_lens, float* loss, int32_t* errors,
+                       float* dy, float* dWo, float* dbo, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (T <= 0 || B <= 0 || F <= 0 || C <= 0 || (long long)T * B > (1ll << 30) / 4) return RLSTM_EDIM;
+  if (operand_dtype != 0 && operand_dtype != 1) return RLSTM_EMODE;
+  if (!y || !Wo || !bo || !labels || !seq_lens || !loss || !errors || !dy || !dWo || !dbo || !workspace) return RLSTM_ENULL;
+  const CeLayout lay = ce_layout(T, B, F, C);
+  if (workspace_bytes < lay.total * sizeof(float)) return RLSTM_ESIZE;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  float* ws = static_cast<float*>(workspace);
+  const int rows = T * B, Cp = ce_pitch(C);
+  int resident_err = 0;
+  // the class dimension is padded to whole float4s inside the workspace (zero weights, zero gradients there)
+  RLSTM_TRY(repitch(st, Wo, C, C, ws + lay.wo, Cp, Cp, F));
+  RLSTM_TRY(repitch(st, bo, C, C, ws + lay.bo, Cp, Cp, 1));
+  {
+    GemmCall g;                                   // logits = y Wo + bo
+    g.M = rows; g.N = Cp; g.K = F; g.A = y; g.lda = F; g.B = ws + lay.wo; g.ldb = Cp; g.C = ws + lay.z; g.ldc = Cp;
+    g.bias = ws + lay.bo; g.operand_dtype = operand_dtype;
+    ProfScope ps(st, 6, 0, 1, 0, gemm_flop(g));
+    RLSTM_TRY(gemm(st, g));
+  }
+  {
+    ProfScope ps(st, 7, 0, 1, 0, 0.0);
+    RLSTM_TRY(softmax_ce_rows(st, ws + lay.z, Cp, labels, seq_lens, T, B, C, ws + lay.scratch, loss, errors, dbo));
+  }
+  {
+    GemmCall g;                                   // dy = dz Wo^T
+    g.transB = true;
+    g.M = rows; g.N = F; g.K = Cp; g.A = ws + lay.z; g.lda = Cp; g.B = ws + lay.wo; g.ldb = Cp; g.C = dy; g.ldc = F;
+    g.operand_dtype = operand_dtype;
+    ProfScope ps(st, 6, 0, 1, 0, gemm_flop(g));
+    RLSTM_TRY(gemm(st, g));
+  }
+  {
+    GemmCall g;                                   // dWo = y^T dz
+    g.transA = true;
+    g.M = F; g.N = Cp; g.K = rows; g.A = y; g.lda = F; g.B = ws + lay.z; g.ldb = Cp; g.C = ws + lay.dwo; g.ldc = Cp;
+    g.splitk_ws = ws + lay.splitk; g.splitk_floats = (size_t)kCeSlices * F * Cp; g.operand_dtype = operand_dtype;
+    ProfScope ps(st, 6, 0, 1, 0, gemm_flop(g));
+    RLSTM_TRY(gemm(st, g));
+  }
+  RLSTM_TRY(repitch(st, ws + lay.dwo, Cp, Cp, dWo, C, C, F));
+  return RLSTM_OK;
+}
+
+int rlstm_sgd_momentum_step(float* param, const float* grad, float* velocity, size_t n, double learning_rate, double momentum,
+                            void* hip_stream) {
+  if (n == 0) return RLSTM_OK;
+  if (!param || !grad || !velocity) return RLSTM_ENULL;
+  int resident_err = 0;
+  RLSTM_TRY(sgd_momentum(static_cast<hipStream_t>(hip_stream), param, grad, velocity, n, (float)learning_rate, (float)momentum));
+  return RLSTM_OK;
+}
+
+int rlstm_adam_step(float* param, const float* grad, float* m, float* v, size_t n, double learning_rate, double beta1,
+                    double beta2, double epsilon, int step, void* hip_stream) {
+  if (n == 0) return RLSTM_OK;
+  if (!param || !grad || !m || !v) return RLSTM_ENULL;
+  if (step < 1 || !(beta1 >= 0.0 && beta1 < 1.0) || !(beta2 >= 0.0 && beta2 < 1.0)) return RLSTM_EDIM;
+  int resident_err = 0;
+  RLSTM_TRY(adam(static_cast<hipStream_t>(hip_stream), param, grad, m, v, n, learning_rate, beta1, beta2, epsilon, step));
+  return RLSTM_OK;
+}
+
 int rlstm_copy_f32(float* dst, const float* src, size_t n, void* hip_stream) {
   if (!dst || !src) return RLSTM_ENULL;
   int resident_err = 0;
@@ -676,98 +865,26 @@ int blstm_stack_fwd_bwd(const rblstm_desc* d, const float* x, const float* const
   char* ws = static_cast<char*>(workspace);
   rc = stack_forward(d, x, params, seq_lens, y_top, res, ws, sa, sb, persistent);
   if (rc != RLSTM_OK) return rc;
-
-  int resident_err = 0;
-  const StackLayout lay = stack_layout(d);
-  const int T = d->T, B = d->B, H = d->H, L = d->L;
-  unsigned* flag = reinterpret_cast<unsigned*>(ws);
-  char* recws = ws + kFlagBytes;
-  float* skws = reinterpret_cast<float*>(recws + align_up(rec_workspace_bytes(rs), 256));
-  const int mm = d->D > 2 * H ? d->D : 2 * H;
-  const size_t skfloats = splitk_floats(mm, H);
-  const size_t dyfloats = align_up((size_t)T * B * 2 * H, 64);
-  float* dybuf[2] = {skws + skfloats, skws + skfloats + dyfloats};
-
-  // Stream a carries the chain of recurrent passes, stream b every matrix product.  The gradient
-  // w.r.t. a layer's input is the dy of the layer below: it is produced on stream b in the pieces,
-  // and in the frame order, in which that layer's pass back through time consumes it, one piece
-  // ahead; the weight gradients follow on stream b and overlap the rest of that pass.
-  const bool pipelined = persistent && overlap && products_can_share_cus(rs, d->operand_dtype);
-  const std::vector<int> pb = piece_bounds(T, pipelined);
-  const int np = (int)pb.size() - 1;
-  EventList evs;
-  std::vector<hipEvent_t> ready;       // ready[pc]: dy of piece pc of the layer about to run is complete
-
-  const float* dy = dy_top;
-  for (int l = L - 1; l >= 0; --l) {
-    float* base = res + (size_t)l * lay.per_layer;
-    const float* yl = (l == L - 1) ? y_top : base + lay.y;
-    const float* xin = (l == 0) ? x : res + (size_t)(l - 1) * lay.per_layer + lay.y;
-    const int din = (l == 0) ? d->D : 2 * H;
-    RecBwdDir dirs[2];
-    for (int k = 0; k < 2; ++k) {
-      dirs[k] = RecBwdDir{base + lay.zg[k], params[6 * l + 3 * k + 1], base + lay.c[k], nullptr,
-                          dy + (size_t)k * H, nullptr, nullptr, nullptr, nullptr, grads[6 * l + 3 * k + 2],
-                          k == 0 ? 1 : -1};
-    }
-    for (int pc = 0; pc < np; ++pc) {
-      if (!ready.empty()) RLSTM_TRY(hipStreamWaitEvent(sa, ready[pc], 0));
-      ProfScope ps(sa, 2, l, 2, pb[pc + 1] - pb[pc], rec_flop(rs, pb[pc + 1] - pb[pc]));
-      RLSTM_TRY(rec_backward(sa, rs, dirs, seq_lens, recws, flag, persistent, &resident_err, pb[pc], pb[pc + 1]));
-    }
-    ready.clear();
-    RLSTM_TRY(evs.order(sa, sb));
-
-    float* dxl = (l == 0) ? dx : dybuf[l & 1];
-    if (dxl && l > 0 && sb != sa) {
-      // columns [0,H) feed direction +1 of the layer below, which visits frames T-1 .. 0;
-      // columns [H,2H) feed direction -1, which visits frames 0 .. T-1
-      for (int pc = 0; pc < np; ++pc) {
-        const int s0 = pb[pc], s1 = pb[pc + 1];
-        for (int tk = 0; tk < 2; ++tk) {
-          const size_t f0 = (tk == 0) ? (size_t)(T - s1) : (size_t)s0;
-          for (int k = 0; k < 2; ++k) {
-            GemmCall g;
-            g.transB = true;
-            g.M = (s1 - s0) * B; g.N = H; g.K = 4 * H;
-            g.A = base + lay.zg[k] + f0 * B * 4 * H; g.lda = 4 * H;
-            g.B = params[6 * l + 3 * k + 0] + (size_t)tk * H * 4 * H; g.ldb = 4 * H;
-            g.C = dxl + f0 * B * din + (size_t)tk * H; g.ldc = din; g.accumulate = (k == 1);
-            g.naive = !persistent; g.operand_dtype = d->operand_dtype; g.small_footprint = pipelined;
-            ProfScope ps(sb, 3, l, 1, 0, gemm_flop(g));
-            RLSTM_TRY(gemm(sb, g));
-          }
-        }
-        hipEvent_t ev;
-        RLSTM_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
-        evs.evs.push_back(ev);
-        RLSTM_TRY(hipEventRecord(ev, sb));
-        ready.push_back(ev);
-      }
-    } else if (dxl) {
-      for (int k = 0; k < 2; ++k) {
-        GemmCall g;
-        g.transB = true;
-        g.M = T * B; g.N = din; g.K = 4 * H;
-        g.A = base + lay.zg[k]; g.lda = 4 * H; g.B = params[6 * l + 3 * k + 0]; g.ldb = 4 * H;
-        g.C = dxl; g.ldc = din; g.accumulate = (k == 1);
-        g.naive = !persistent; g.operand_dtype = d->operand_dtype;
-        ProfScope ps(sb, 3, l, 1, 0, gemm_flop(g));
-        RLSTM_TRY(gemm(sb, g));
-      }
-      // one stream: already in order
-    }
-    for (int k = 0; k < 2; ++k) {
-      rc = weight_grads(sb, l, T, B, din, H, k == 0 ? 1 : -1, xin, din, yl + (size_t)k * H, 2 * H,
-                        base + lay.zg[k], grads[6 * l + 3 * k + 0], grads[6 * l + 3 * k + 1], skws, skfloats,
-                        !persistent, d->operand_dtype, pipelined);
-      if (rc != RLSTM_OK) return rc;
-    }
-    dy = dxl;
-  }
-  // the caller's stream a sees the end of everything
-  RLSTM_TRY(evs.order(sb, sa));
-  return RLSTM_OK;
+  return stack_backward(d, x, params, seq_lens, dy_top, y_top, grads, dx, res, ws, sa, sb, persistent);
 }
+
+int blstm_stack_bwd(const rblstm_desc* d, const float* x, const float* const* params,
+                    const int32_t* seq_lens, const float* dy_top, const float* y_top,
+                    float* const* grads, float* dx,
+                    void* reserve, void* workspace, void* hip_stream_a, void* hip_stream_b) {
+  int rc = check_stack_desc(d);
+  if (rc != RLSTM_OK) return rc;
+  if (!x || !params || !seq_lens || !dy_top || !y_top || !grads || !reserve || !workspace) return RLSTM_ENULL;
+  for (int i = 0; i < 6 * d->L; ++i) if (!params[i] || !grads[i]) return RLSTM_ENULL;
+  const RecShape rs = stack_rec_shape(d);
+  const int eng = resolve_engine(d->engine, rs);
+  if (eng < 0) return eng;
+  hipStream_t sa = static_cast<hipStream_t>(hip_stream_a);
+  hipStream_t sb = static_cast<hipStream_t>(hip_stream_b);
+  if (sb == nullptr) sb = sa;
+  return stack_backward(d, x, params, seq_lens, dy_top, y_top, grads, dx, static_cast<float*>(reserve),
+                        static_cast<char*>(workspace), sa, sb, eng == RLSTM_ENGINE_PERSISTENT);
+}
+
 
 }  // extern "C"

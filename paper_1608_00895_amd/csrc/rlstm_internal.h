@@ -142,6 +142,17 @@ size_t mdlstm_dbpart_floats(const MdShape& s);
 hipError_t mdlstm_backward(hipStream_t stream, const MdShape& s, const MdDir* dirs, const int32_t* widths, const float* dy,
                            float* dbpart, float* const* db, unsigned long long* halo, unsigned* err);
 
+// output layer and updates (output_layer.hip).  z: [T*B, ld], logits in columns [0, C) in, d loss / d logits out with
+// columns [C, ld) zeroed; scratch: ce_scratch_floats(); loss, errors: one value each; dbo: [C] column sums of the result
+size_t ce_scratch_floats(int rows, int C);
+hipError_t softmax_ce_rows(hipStream_t stream, float* z, int ld, const int32_t* labels, const int32_t* seq_lens, int T, int B,
+                           int C, float* scratch, float* loss, int32_t* errors, float* dbo);
+// dst[r, 0..cols_dst) = src[r, 0..cols_src) followed by zeros
+hipError_t repitch(hipStream_t stream, const float* src, int ld_src, int cols_src, float* dst, int ld_dst, int cols_dst, int rows);
+hipError_t sgd_momentum(hipStream_t stream, float* p, const float* g, float* v, size_t n, float lr, float mu);
+hipError_t adam(hipStream_t stream, float* p, const float* g, float* m, float* v, size_t n, double lr, double b1, double b2,
+                double eps, int step);
+
 // chunking (chunking.hip): segment table on the host, gather of the segments into a minibatch on the device
 long long chunk_plan(const int32_t* seq_lens, int B, int size, int step, int32_t* seq, int32_t* start, int32_t* len,
                      long long max_chunks);

@@ -224,3 +224,13 @@ def paper_chunks() -> Workload:
     for b in range(nb):
         G[seq_lens[b]:, b, :] = 0.0
     return Workload("paper_3x512_81_segments_of_250", L, size, nb, D, H, True, 0, seq_lens, x, params, G)
+
+
+def output_layer(T: int, B: int, F: int, C: int, seed: int, wscale: float = 0.1):
+    """Random output-layer weights Wo [F,C], bo [C] and frame labels [T,B] (uniform over the classes).  No arithmetic
+    of the method: the caller decides which frames are valid."""
+    rng = np.random.Generator(np.random.Philox(seed))
+    Wo = rng.uniform(-wscale, wscale, (F, C)).astype(np.float32)
+    bo = rng.uniform(-wscale, wscale, (C,)).astype(np.float32)
+    labels = rng.integers(0, C, (T, B)).astype(np.int32)
+    return Wo, bo, labels

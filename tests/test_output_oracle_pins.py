@@ -77,6 +77,25 @@ def test_against_torch_cross_entropy():
     assert int(wrong.sum()) == f["errors"]
 
 
+def test_labels_outside_the_classes_are_left_out_like_padding():
+    y, Wo, bo, labels, lens = _case(5, T=6, B=3, F=4, C=7, lens=(6, 4, 5))
+    labels = labels.copy()
+    labels[1, 0], labels[3, 1], labels[0, 2] = -1, 7, -100
+    f = softmax_ce_forward(y, Wo, bo, labels, lens)
+    g = softmax_ce_backward(f)
+    ty, tW, tb = (torch.tensor(a, dtype=torch.float64, requires_grad=True) for a in (y, Wo, bo))
+    z = ty @ tW + tb
+    mask = torch.tensor(np.arange(6)[:, None] < lens[None, :])
+    tl = torch.tensor(np.where((labels < 0) | (labels >= 7), -100, labels))
+    loss = torch.nn.functional.cross_entropy(z[mask], tl[mask], reduction="sum", ignore_index=-100)
+    loss.backward()
+    assert abs(loss.item() - f["loss"]) < 1e-10
+    assert np.abs(ty.grad.numpy() - g["dy"]).max() < 1e-12 and np.abs(tW.grad.numpy() - g["dWo"]).max() < 1e-12
+    assert not g["dy"][1, 0].any() and not f["p"][3, 1].any()
+    wrong = (z.argmax(dim=2) != tl) & mask & (tl >= 0)
+    assert int(wrong.sum()) == f["errors"]
+
+
 def test_updates_against_torch_optimizers():
     rng = _rng(4)
     p0 = rng.standard_normal(50)
