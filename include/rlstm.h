@@ -311,6 +311,40 @@ RLSTM_API int rlstm_chunk_gather(const float* x, int T, int B, int D, int ldx, c
                                  float* xc, void* hip_stream);
 
 /*
+ * Streaming mode: a unidirectional (direction +1) stack of L LSTM layers reads its sequences in S
+ * consecutive segments of Tc frames; every layer starts a segment from the final state it reached
+ * in the segment before (Sec. 4.1: final states handed on from one recurrent layer to another),
+ * so the forward result is that of the uncut sequences and the context that plain cutting into
+ * segments gives up (Sec. 3) is kept.  Back-propagation through time is truncated at the segment
+ * boundaries: the backward pass of a segment takes the segment's initial state as a constant,
+ * no gradient arrives at its final state, and the gradients of the segments are summed.  Memory:
+ * one segment of activations, whatever S is.  Calling with S = 1 once per segment, passing the
+ * same `state` array every time, streams a sequence of any length (and lets a loss layer run
+ * between the calls).
+ *   x [S*Tc,B,D] in; seq_lens [B] in: lengths of the whole sequences (segment s holds
+ *   clamp(len - s*Tc, 0, Tc) valid frames of a sequence; a sequence that has ended keeps its state)
+ *   params: HOST array of 3*L DEVICE pointers: params[3l] = W [D_l,4H], +1 = R [H,4H], +2 = b [4H];
+ *           D_0 = D, D_l = H otherwise
+ *   dy_top [S*Tc,B,H] in; y_top [S*Tc,B,H] out
+ *   grads: HOST array of 3*L DEVICE pointers laid out like params, out (sums over the S segments)
+ *   dx [S*Tc,B,D] out, may be null
+ *   state [L,2,B,H] in/out, may be null: per layer h then c; in: state before the first segment
+ *         (null: zeros); out: state after the last segment
+ *   reserve: rlstm_stream_reserve_bytes(); workspace: rlstm_stream_workspace_bytes(); all DEVICE.
+ * Engines and errors as for lstm_fwd / lstm_bwd (the shape seen by the engine is T = Tc).
+ */
+typedef struct rlstm_stream_desc {
+  int32_t L, S, Tc, B, D, H;
+  int32_t operand_dtype;  /* as in rlstm_desc */
+  int32_t engine;         /* RLSTM_ENGINE_* */
+} rlstm_stream_desc;
+RLSTM_API size_t rlstm_stream_reserve_bytes(const rlstm_stream_desc* desc);
+RLSTM_API size_t rlstm_stream_workspace_bytes(const rlstm_stream_desc* desc);
+RLSTM_API int lstm_stream_fwd_bwd(const rlstm_stream_desc* desc, const float* x, const float* const* params,
+                                  const int32_t* seq_lens, const float* dy_top, float* y_top, float* const* grads,
+                                  float* dx, float* state, void* reserve, void* workspace, void* hip_stream);
+
+/*
  * softmax_ce_fwd_bwd - the frame-wise output layer of the acoustic model (Sec. 6: a softmax
  * output layer over the tied-state classes on top of the BLSTM stack, trained with the
  * cross-entropy criterion; the frame error rate is what Table 3 reports) and its gradients:

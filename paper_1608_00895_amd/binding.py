@@ -25,6 +25,7 @@ EXPORTS = [
     "rlstm_reserve_bytes", "rlstm_workspace_bytes", "rblstm_reserve_bytes", "rblstm_workspace_bytes",
     "lstm_fwd", "lstm_bwd", "blstm_stack_fwd_bwd", "blstm_stack_fwd", "blstm_stack_bwd",
     "rlstm_ce_workspace_bytes", "softmax_ce_fwd_bwd", "rlstm_sgd_momentum_step", "rlstm_adam_step",
+    "rlstm_stream_reserve_bytes", "rlstm_stream_workspace_bytes", "lstm_stream_fwd_bwd",
     "rlstm_gemm_f32", "rlstm_gemm_bf16", "rlstm_copy_f32", "rlstm_profile_enable", "rlstm_profile_read", "rlstm_last_timeout", "rlstm_test_hook", "rlstm_set_first_piece", "rlstm_set_batch_groups", "rmdlstm_reserve_bytes", "rmdlstm_workspace_bytes", "mdlstm_fwd", "mdlstm_bwd", "rlstm_chunk_plan", "rlstm_chunk_gather", "rblstm_plan", "rlstm_exchange_floor_bytes", "rlstm_exchange_floor", "rlstm_resolve_engine", "rlstm_strerror", "rlstm_version",
 ]
 
@@ -36,6 +37,10 @@ class rlstm_desc(ctypes.Structure):
 
 class rblstm_desc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("L", "T", "B", "D", "H", "operand_dtype", "engine")]
+
+
+class rlstm_stream_desc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("L", "S", "Tc", "B", "D", "H", "operand_dtype", "engine")]
 
 
 class rmdlstm_desc(ctypes.Structure):
@@ -88,6 +93,12 @@ def lib() -> ctypes.CDLL:
         L.blstm_stack_bwd.restype = ip
         L.blstm_stack_bwd.argtypes = [ctypes.POINTER(rblstm_desc), vp, ctypes.POINTER(vp), vp, vp, vp,
                                       ctypes.POINTER(vp), vp, vp, vp, vp, vp]
+        for name in ("rlstm_stream_reserve_bytes", "rlstm_stream_workspace_bytes"):
+            getattr(L, name).restype = ctypes.c_size_t
+            getattr(L, name).argtypes = [ctypes.POINTER(rlstm_stream_desc)]
+        L.lstm_stream_fwd_bwd.restype = ip
+        L.lstm_stream_fwd_bwd.argtypes = [ctypes.POINTER(rlstm_stream_desc), vp, ctypes.POINTER(vp), vp, vp, vp,
+                                          ctypes.POINTER(vp), vp, vp, vp, vp, vp]
         L.rlstm_ce_workspace_bytes.restype = ctypes.c_size_t
         L.rlstm_ce_workspace_bytes.argtypes = [ip, ip, ip, ip]
         L.softmax_ce_fwd_bwd.restype = ip
@@ -241,6 +252,25 @@ def blstm_stack_bwd(desc, x, params, seq_lens, dy_top, y_top, grads, dx, reserve
                                ga, _ptr(dx), _ptr(reserve), _ptr(workspace), _stream(stream_a), sb)
     if check and rc != 0:
         raise RlstmError(rc, "blstm_stack_bwd")
+    return rc
+
+
+def rlstm_stream_reserve_bytes(desc) -> int:
+    return int(lib().rlstm_stream_reserve_bytes(ctypes.byref(desc)))
+
+
+def rlstm_stream_workspace_bytes(desc) -> int:
+    return int(lib().rlstm_stream_workspace_bytes(ctypes.byref(desc)))
+
+
+def lstm_stream_fwd_bwd(desc, x, params, seq_lens, dy_top, y_top, grads, dx, state, reserve, workspace, stream=None,
+                        check=True) -> int:
+    """params / grads: flat sequences of 3*L tensors (W, R, b per layer); state: [L,2,B,H] tensor or None."""
+    pa, ga = _ptr_array(params), _ptr_array(grads)
+    rc = lib().lstm_stream_fwd_bwd(ctypes.byref(desc), _ptr(x), pa, _ptr(seq_lens), _ptr(dy_top), _ptr(y_top), ga,
+                                   _ptr(dx), _ptr(state), _ptr(reserve), _ptr(workspace), _stream(stream))
+    if check and rc != 0:
+        raise RlstmError(rc, "lstm_stream_fwd_bwd")
     return rc
 
 

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librlstm.so")
-SOURCES = ["gemm.hip", "recurrent.hip", "recurrent_persistent.hip", "recurrent_stepwise.hip", "exchange_probe.hip", "mdlstm.hip", "chunking.hip", "output_layer.hip", "api.hip"]
+SOURCES = ["gemm.hip", "recurrent.hip", "recurrent_persistent.hip", "recurrent_stepwise.hip", "exchange_probe.hip", "mdlstm.hip", "chunking.hip", "output_layer.hip", "stream.hip", "api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

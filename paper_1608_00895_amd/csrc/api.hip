@@ -95,14 +95,14 @@ int hip_to_code(hipError_t e, int resident_err) {
 int weight_grads(hipStream_t st, int layer, int T, int B, int Din, int H, int direction,
                  const float* x, int ldx, const float* y, int ldy, const float* dz,
                  float* dW, float* dR, float* skws, size_t skfloats, bool naive, int operand_dtype,
-                 bool small_footprint) {
+                 bool small_footprint, bool accumulate = false) {
   int resident_err = 0;
   GemmCall g;
   g.transA = true; g.transB = false;
   g.M = Din; g.N = 4 * H; g.K = T * B;
   g.A = x; g.lda = ldx; g.B = dz; g.ldb = 4 * H; g.C = dW; g.ldc = 4 * H;
   g.splitk_ws = skws; g.splitk_floats = skfloats; g.naive = naive; g.operand_dtype = operand_dtype;
-  g.small_footprint = small_footprint;
+  g.small_footprint = small_footprint; g.accumulate = accumulate;
   {
     ProfScope ps(st, 4, layer, 1, 0, gemm_flop(g));
     RLSTM_TRY(gemm(st, g));
@@ -685,6 +685,140 @@ int rlstm_adam_step(float* param, const float* grad, float* m, float* v, size_t 
   if (step < 1 || !(beta1 >= 0.0 && beta1 < 1.0) || !(beta2 >= 0.0 && beta2 < 1.0)) return RLSTM_EDIM;
   int resident_err = 0;
   RLSTM_TRY(adam(static_cast<hipStream_t>(hip_stream), param, grad, m, v, n, learning_rate, beta1, beta2, epsilon, step));
+  return RLSTM_OK;
+}
+
+// ---- streaming mode: segments chained by their final states, truncated back-propagation ------------
+static int check_stream_desc(const rlstm_stream_desc* d) {
+  if (!d) return RLSTM_ENULL;
+  if (d->L <= 0 || d->S <= 0 || d->Tc <= 0 || d->B <= 0 || d->D <= 0 || d->H <= 0) return RLSTM_EDIM;
+  if (d->L > 64 || (long long)d->S * d->Tc * d->B > (1ll << 30) || (long long)d->H * 4 > (1ll << 24)) return RLSTM_EDIM;
+  if (d->operand_dtype != 0 && d->operand_dtype != 1) return RLSTM_EMODE;
+  if (d->engine < RLSTM_ENGINE_AUTO || d->engine > RLSTM_ENGINE_STEPWISE) return RLSTM_EMODE;
+  return RLSTM_OK;
+}
+struct StreamLayout {
+  size_t zg, c, y, per_layer;                       // reserve, floats, one segment per layer
+  size_t rec, splitk, splitk_floats, dy[2], db, lens, state[2], total;   // workspace, bytes
+};
+static StreamLayout stream_layout(const rlstm_stream_desc* d) {
+  StreamLayout l;
+  const size_t tb = (size_t)d->Tc * d->B;
+  l.zg = 0; l.c = align_up(tb * 4 * d->H, 64); l.y = l.c + align_up(tb * d->H, 64);
+  l.per_layer = l.y + align_up(tb * d->H, 64);
+  const RecShape rs{d->Tc, d->B, d->H, d->H, 1, d->operand_dtype};
+  size_t o = kFlagBytes;
+  l.rec = o;     o += align_up(rec_workspace_bytes(rs), 256);
+  l.splitk_floats = splitk_floats(d->D > d->H ? d->D : d->H, d->H);
+  l.splitk = o;  o += align_up(l.splitk_floats * sizeof(float), 256);
+  for (int k = 0; k < 2; ++k) { l.dy[k] = o; o += align_up(tb * d->H * sizeof(float), 256); }
+  l.db = o;      o += align_up((size_t)4 * d->H * sizeof(float), 256);
+  l.lens = o;    o += align_up((size_t)d->S * d->B * sizeof(int32_t), 256);
+  for (int k = 0; k < 2; ++k) { l.state[k] = o; o += align_up((size_t)d->L * 2 * d->B * d->H * sizeof(float), 256); }
+  l.total = o;
+  return l;
+}
+
+size_t rlstm_stream_reserve_bytes(const rlstm_stream_desc* d) {
+  if (check_stream_desc(d) != RLSTM_OK) return 0;
+  return align_up(stream_layout(d).per_layer * d->L * sizeof(float), 256);
+}
+
+size_t rlstm_stream_workspace_bytes(const rlstm_stream_desc* d) {
+  if (check_stream_desc(d) != RLSTM_OK) return 0;
+  return stream_layout(d).total;
+}
+
+int lstm_stream_fwd_bwd(const rlstm_stream_desc* d, const float* x, const float* const* params, const int32_t* seq_lens,
+                        const float* dy_top, float* y_top, float* const* grads, float* dx, float* state,
+                        void* reserve, void* workspace, void* hip_stream) {
+  int rc = check_stream_desc(d);
+  if (rc != RLSTM_OK) return rc;
+  if (!x || !params || !seq_lens || !dy_top || !y_top || !grads || !reserve || !workspace) return RLSTM_ENULL;
+  for (int i = 0; i < 3 * d->L; ++i) if (!params[i] || !grads[i]) return RLSTM_ENULL;
+  const int L = d->L, S = d->S, Tc = d->Tc, B = d->B, D = d->D, H = d->H;
+  const RecShape rs{Tc, B, H, H, 1, d->operand_dtype};
+  const int eng = resolve_engine(d->engine, rs);
+  if (eng < 0) return eng;
+  const bool persistent = eng == RLSTM_ENGINE_PERSISTENT;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const StreamLayout lay = stream_layout(d);
+  float* res = static_cast<float*>(reserve);
+  char* ws = static_cast<char*>(workspace);
+  unsigned* flag = reinterpret_cast<unsigned*>(ws);
+  char* recws = ws + lay.rec;
+  float* skws = reinterpret_cast<float*>(ws + lay.splitk);
+  float* dybuf[2] = {reinterpret_cast<float*>(ws + lay.dy[0]), reinterpret_cast<float*>(ws + lay.dy[1])};
+  float* dbtmp = reinterpret_cast<float*>(ws + lay.db);
+  int32_t* lens = reinterpret_cast<int32_t*>(ws + lay.lens);
+  float* sbuf[2] = {reinterpret_cast<float*>(ws + lay.state[0]), reinterpret_cast<float*>(ws + lay.state[1])};
+  const size_t bh = (size_t)B * H, nstate = (size_t)L * 2 * bh, tb = (size_t)Tc * B;
+  int resident_err = 0;
+
+  RLSTM_TRY(clear_flag(st, flag));
+  RLSTM_TRY(segment_lens(st, seq_lens, B, S, Tc, lens));
+  if (state) RLSTM_TRY(accumulate(st, sbuf[0], state, nstate, true));
+  else       RLSTM_TRY(fill_f32(st, sbuf[0], nstate, 0.f));
+
+  for (int s = 0; s < S; ++s) {
+    const int32_t* slens = lens + (size_t)s * B;
+    float* cur = sbuf[s & 1];          // state the segment starts from: [L][h | c][B, H]
+    float* nxt = sbuf[(s + 1) & 1];    // state it ends in
+    // forward through the layers
+    const float* in = x + (size_t)s * tb * D;
+    int din = D;
+    for (int l = 0; l < L; ++l) {
+      float* base = res + (size_t)l * lay.per_layer;
+      float* yl = (l == L - 1) ? y_top + (size_t)s * tb * H : base + lay.y;
+      GemmCall g;
+      g.M = Tc * B; g.N = 4 * H; g.K = din;
+      g.A = in; g.lda = din; g.B = params[3 * l + 0]; g.ldb = 4 * H; g.C = base + lay.zg; g.ldc = 4 * H;
+      g.bias = params[3 * l + 2]; g.naive = !persistent; g.operand_dtype = d->operand_dtype;
+      {
+        ProfScope ps(st, 0, l, 1, 0, gemm_flop(g));
+        RLSTM_TRY(gemm(st, g));
+      }
+      RecFwdDir dir{base + lay.zg, params[3 * l + 1], cur + (size_t)(2 * l) * bh, cur + (size_t)(2 * l + 1) * bh, yl,
+                    base + lay.c, nxt + (size_t)(2 * l) * bh, nxt + (size_t)(2 * l + 1) * bh, 1};
+      {
+        ProfScope ps(st, 1, l, 1, Tc, rec_flop(rs, Tc));
+        RLSTM_TRY(rec_forward(st, rs, &dir, slens, recws, flag, persistent, &resident_err, 0, Tc));
+      }
+      in = yl; din = H;
+    }
+    // backward through the layers; nothing flows into the segment's final state, and nothing is passed back
+    const float* dy = dy_top + (size_t)s * tb * H;
+    for (int l = L - 1; l >= 0; --l) {
+      float* base = res + (size_t)l * lay.per_layer;
+      const float* yl = (l == L - 1) ? y_top + (size_t)s * tb * H : base + lay.y;
+      const float* xin = (l == 0) ? x + (size_t)s * tb * D : res + (size_t)(l - 1) * lay.per_layer + lay.y;
+      const int dl = (l == 0) ? D : H;
+      const float* h0 = cur + (size_t)(2 * l) * bh;
+      RecBwdDir dir{base + lay.zg, params[3 * l + 1], base + lay.c, cur + (size_t)(2 * l + 1) * bh, dy, nullptr, nullptr,
+                    nullptr, nullptr, dbtmp, 1};
+      {
+        ProfScope ps(st, 2, l, 1, Tc, rec_flop(rs, Tc));
+        RLSTM_TRY(rec_backward(st, rs, &dir, slens, recws, flag, persistent, &resident_err, 0, Tc));
+      }
+      RLSTM_TRY(accumulate(st, grads[3 * l + 2], dbtmp, (size_t)4 * H, s == 0));
+      rc = weight_grads(st, l, Tc, B, dl, H, 1, xin, dl, yl, H, base + lay.zg, grads[3 * l + 0], grads[3 * l + 1], skws,
+                        lay.splitk_floats, !persistent, d->operand_dtype, false, s > 0);
+      if (rc != RLSTM_OK) return rc;
+      RLSTM_TRY(add_h0_outer(st, Tc, B, H, 1, h0, base + lay.zg, slens, grads[3 * l + 1]));
+      float* dxl = (l == 0) ? (dx ? dx + (size_t)s * tb * D : nullptr) : dybuf[l & 1];
+      if (dxl) {
+        GemmCall g;
+        g.transB = true;
+        g.M = Tc * B; g.N = dl; g.K = 4 * H;
+        g.A = base + lay.zg; g.lda = 4 * H; g.B = params[3 * l + 0]; g.ldb = 4 * H; g.C = dxl; g.ldc = dl;
+        g.naive = !persistent; g.operand_dtype = d->operand_dtype;
+        ProfScope ps(st, 3, l, 1, 0, gemm_flop(g));
+        RLSTM_TRY(gemm(st, g));
+      }
+      dy = dxl;
+    }
+  }
+  if (state) RLSTM_TRY(accumulate(st, state, sbuf[S & 1], nstate, true));
   return RLSTM_OK;
 }
 

@@ -153,6 +153,11 @@ hipError_t sgd_momentum(hipStream_t stream, float* p, const float* g, float* v, 
 hipError_t adam(hipStream_t stream, float* p, const float* g, float* m, float* v, size_t n, double lr, double b1, double b2,
                 double eps, int step);
 
+// streaming mode (stream.hip): out[s * B + b] = clamp(seq_lens[b] - s * Tc, 0, Tc); dst (+)= src; fill
+hipError_t segment_lens(hipStream_t stream, const int32_t* seq_lens, int B, int S, int Tc, int32_t* out);
+hipError_t accumulate(hipStream_t stream, float* dst, const float* src, size_t n, bool assign);
+hipError_t fill_f32(hipStream_t stream, float* dst, size_t n, float v);
+
 // chunking (chunking.hip): segment table on the host, gather of the segments into a minibatch on the device
 long long chunk_plan(const int32_t* seq_lens, int B, int size, int step, int32_t* seq, int32_t* start, int32_t* len,
                      long long max_chunks);
