@@ -166,12 +166,108 @@ def bench_config5(args):
     print(json.dumps(out), flush=True)
 
 
+def bench_stream(args):
+    """The streaming mode on whole sequences: one step = one lstm_stream_fwd_bwd call (all segments, forward and
+    truncated backward, gradients of every parameter) on sequences resident in HBM."""
+    import numpy as np
+    import torch
+    from paper_1608_00895_amd import binding as rl
+    from paper_1608_00895_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    wl = synth.paper_stream()
+    log(f"workload {wl.name}: L={wl.L} S={wl.S} Tc={wl.Tc} B={wl.B} D={wl.D} H={wl.H} frames={wl.frames}")
+    desc = rl.rlstm_stream_desc(L=wl.L, S=wl.S, Tc=wl.Tc, B=wl.B, D=wl.D, H=wl.H, operand_dtype=0, engine=args.engine)
+    x = torch.from_numpy(wl.x).to(dev)
+    sl = torch.from_numpy(wl.seq_lens).to(dev)
+    params = [torch.from_numpy(a).to(dev) for p in wl.params for a in p]
+    grads = [torch.empty_like(p) for p in params]
+    G = torch.from_numpy(wl.G).to(dev)
+    y = torch.empty((wl.S * wl.Tc, wl.B, wl.H), device=dev)
+    state = torch.zeros((wl.L, 2, wl.B, wl.H), device=dev)
+    reserve = torch.empty(rl.rlstm_stream_reserve_bytes(desc), dtype=torch.uint8, device=dev)
+    ws = torch.empty(rl.rlstm_stream_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+    if args.batch_groups is not None:
+        rl.rlstm_set_batch_groups(args.batch_groups)
+
+    def step():
+        state.zero_()
+        rl.lstm_stream_fwd_bwd(desc, x, params, sl, G, y, grads, None, state, reserve, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    assert rl.rlstm_last_timeout(ws) == 0
+    rl.rlstm_profile_read()
+    rl.rlstm_profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    rl.rlstm_profile_enable(False)
+    prof = rl.rlstm_profile_read(1 << 16)
+    assert rl.rlstm_last_timeout(ws) == 0
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    by_kind = {}
+    for kind, layer, ndir, ms, nsteps, flop in prof:
+        d = by_kind.setdefault(kind, {"ms": 0.0, "launches": 0, "flop": 0.0, "rsteps": 0})
+        d["ms"] += ms; d["launches"] += 1; d["flop"] += flop; d["rsteps"] += nsteps
+    kernels = []
+    for kind, d in sorted(by_kind.items()):
+        e = {"kernel": rl.PROFILE_KINDS[kind], "launches_per_step": d["launches"] / args.steps,
+             "avg_ms": d["ms"] / d["launches"], "ms_per_step": d["ms"] / args.steps,
+             "tflops": d["flop"] / (d["ms"] * 1e-3) / 1e12}
+        if kind in (1, 2):
+            e["steps_per_launch"] = d["rsteps"] / d["launches"]
+            e["step_us"] = 1e3 * d["ms"] / d["rsteps"]
+        kernels.append(e)
+        log(e)
+    dom = max(kernels, key=lambda e: e["ms_per_step"])
+    roofline = {"kernel": dom["kernel"], "bound": "mfma", "achieved": dom["tflops"], "peak": PEAK_FP32_MFMA_TFLOPS,
+                "unit": "TFLOP/s", "frac": dom["tflops"] / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                "avg_launch_ms": dom["avg_ms"], "steps_per_launch": dom.get("steps_per_launch"), "step_us": dom.get("step_us"),
+                "note": "the recurrent kernels are bound by the serial chain of dependent steps (see step_us); priced "
+                        "against the fp32 MFMA peak with 2*B*H*4H FLOP per step"}
+    slots = wl.S * wl.Tc * wl.B
+    out = {"metric": "LSTM streaming train frames/sec (segments chained by final states, truncated BPTT)",
+           "value": wl.frames / (ms_per_step * 1e-3), "unit": "frames/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": wl.name, "layers": wl.L, "units": wl.H, "sequences": wl.B, "segments": wl.S,
+                      "segment_frames": wl.Tc, "valid_frames": wl.frames, "padded_slots": slots,
+                      "engine": "persistent" if args.engine in (0, 1) else "stepwise"},
+           "roofline": roofline, "kernels": kernels}
+    try:
+        out["config"]["plan"] = rl.rblstm_plan(rl.rblstm_desc(L=wl.L, T=wl.Tc, B=wl.B, D=wl.D, H=wl.H, operand_dtype=0,
+                                                              engine=args.engine))
+        out["config"]["plan_note"] = "plan of a bidirectional stack of the same shape, for reference only"
+    except rl.RlstmError:
+        pass
+    if not args.no_cpu_baseline:
+        from threadpoolctl import threadpool_info
+        from oracle import lstm_stream_forward_backward
+        Tc, S2 = 100, 2                            # the oracle on the first 2 segments of 100 frames
+        p64 = [tuple(a.astype(np.float64) for a in p) for p in wl.params]
+        lens = np.minimum(wl.seq_lens, Tc * S2)
+        t0 = time.perf_counter()
+        lstm_stream_forward_backward(wl.x[:Tc * S2].astype(np.float64), p64, lens, wl.G[:Tc * S2].astype(np.float64), Tc)
+        dt = time.perf_counter() - t0
+        threads = max([i.get("num_threads", 1) for i in threadpool_info() if i.get("user_api") == "blas"] or [1])
+        out["cpu_baseline"] = {"value": int(lens.sum()) / dt, "unit": "frames/s", "cores": int(threads), "kind": "oracle",
+                               "sample": f"{wl.name}: same network, first {S2} segments of {Tc} frames of all {wl.B} "
+                                         f"sequences ({int(lens.sum())} frames), numpy fp64, {dt:.1f} s"}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config3", choices=["config2", "config3", "config4", "config5", "paper_chunks", "paper_train"])
+    ap.add_argument("--workload", default="config3", choices=["config2", "config3", "config4", "config5", "paper_chunks", "paper_train", "paper_stream"])
     ap.add_argument("--engine", type=int, default=0)
     ap.add_argument("--one-stream", action="store_true")
     ap.add_argument("--first-piece", type=int, default=None,
@@ -190,6 +286,8 @@ def main():
 
     if args.workload == "config5":
         return bench_config5(args)
+    if args.workload == "paper_stream":
+        return bench_stream(args)
 
     import numpy as np
     import torch

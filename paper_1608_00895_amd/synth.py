@@ -234,3 +234,44 @@ def output_layer(T: int, B: int, F: int, C: int, seed: int, wscale: float = 0.1)
     bo = rng.uniform(-wscale, wscale, (C,)).astype(np.float32)
     labels = rng.integers(0, C, (T, B)).astype(np.int32)
     return Wo, bo, labels
+
+
+@dataclass
+class StreamWorkload:
+    name: str
+    L: int                 # stacked unidirectional layers
+    S: int                 # segments
+    Tc: int                # frames per segment
+    B: int
+    D: int
+    H: int
+    seq_lens: np.ndarray   # int32 [B], lengths of the whole sequences (<= S * Tc)
+    x: np.ndarray          # float32 [S*Tc, B, D], zero past each sequence's length
+    params: List[Tuple[np.ndarray, np.ndarray, np.ndarray]] = field(default_factory=list)   # per layer (W, R, b)
+    G: Optional[np.ndarray] = None   # float32 [S*Tc, B, H]
+
+    @property
+    def frames(self) -> int:
+        return int(self.seq_lens.sum())
+
+
+def paper_stream() -> StreamWorkload:
+    """Whole sequences of the corpus statistics of Sec. 6 (64 of them, lengths around 738 +- 291 frames, 45 values per
+    frame) read in segments of 250 frames by three unidirectional layers of 512 units, fp32: the streaming mode's
+    workload.  No arithmetic of the method here."""
+    cx, lens = paper_corpus(n_seq=64, seed=8)
+    Tc = 250
+    S = (int(lens.max()) + Tc - 1) // Tc
+    x = np.zeros((S * Tc, cx.shape[1], cx.shape[2]), np.float32)
+    x[:cx.shape[0]] = cx
+    rng = np.random.Generator(np.random.Philox(88))
+    L, D, H = 3, 45, 512
+    params = []
+    for l in range(L):
+        din = D if l == 0 else H
+        params.append((rng.uniform(-0.05, 0.05, (din, 4 * H)).astype(np.float32),
+                       rng.uniform(-0.05, 0.05, (H, 4 * H)).astype(np.float32), np.zeros(4 * H, np.float32)))
+    G = rng.standard_normal((S * Tc, x.shape[1], H)).astype(np.float32)
+    for b in range(x.shape[1]):
+        G[lens[b]:, b, :] = 0.0
+    return StreamWorkload(f"paper_stream_3x512_64_sequences_{S}_segments_of_250", L, S, Tc, x.shape[1], D, H, lens, x, params, G)

@@ -269,3 +269,67 @@ def test_training_step_against_oracle(rule):
             err = np.abs(p.cpu().numpy() - r)
             assert np.all(err <= 2e-7 + slack[i]), (step, i, float((err - slack[i]).max()))
             assert np.median(err) < 1e-6, (step, i, float(np.median(err)))       # and the typical entry is far inside
+
+
+def test_paper_train_step_full_size_against_oracle_samples():
+    """A whole training step at full size, in the launch configuration bench.py times (81 segments of 250 frames,
+    3 x 512 BLSTM, 1501 classes, flat parameter / gradient / moment buffers, one Adam launch): loss, frame errors and
+    sampled entries of every gradient and of the updated parameters against values the oracle wrote
+    (tests/golden/make_paper_train_golden.py)."""
+    import os
+    g = np.load(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_train_oracle_samples.npz"))
+    wl = synth.paper_chunks()
+    assert np.array_equal(g["seq_lens"], wl.seq_lens)
+    C, lr = 1501, 1e-3
+    T, B, F = wl.T, wl.B, 2 * wl.H
+    Wo, bo, labels = synth.output_layer(T, B, F, C, seed=67, wscale=0.05)
+    host = [a for layer in wl.params for p in layer for a in p] + [Wo, bo]
+    n_all = sum(a.size for a in host)
+    flat_p = torch.empty(n_all, device=gh.DEV)
+    flat_g = torch.full((n_all,), float("nan"), device=gh.DEV)
+    params, grads, o = [], [], 0
+    for a in host:
+        flat_p[o:o + a.size] = gh.dev(a).reshape(-1)
+        params.append(flat_p[o:o + a.size].view(a.shape))
+        grads.append(flat_g[o:o + a.size].view(a.shape))
+        o += a.size
+    desc = rl.rblstm_desc(L=wl.L, T=T, B=B, D=wl.D, H=wl.H, operand_dtype=0, engine=rl.RLSTM_ENGINE_PERSISTENT)
+    x, sl, lab = gh.dev(wl.x), gh.dev(wl.seq_lens, torch.int32), gh.dev(labels, torch.int32)
+    y_top = torch.empty((T, B, F), device=gh.DEV)
+    dy = torch.empty((T, B, F), device=gh.DEV)
+    reserve = torch.empty(rl.rblstm_reserve_bytes(desc), dtype=torch.uint8, device=gh.DEV)
+    ws = torch.empty(rl.rblstm_workspace_bytes(desc), dtype=torch.uint8, device=gh.DEV)
+    cews = torch.empty(rl.rlstm_ce_workspace_bytes(T, B, F, C), dtype=torch.uint8, device=gh.DEV)
+    loss = torch.zeros(1, device=gh.DEV)
+    errors = torch.zeros(1, dtype=torch.int32, device=gh.DEV)
+    m, v = torch.zeros(n_all, device=gh.DEV), torch.zeros(n_all, device=gh.DEV)
+    sb = torch.cuda.Stream()
+    print("paper train step: forward", flush=True)
+    rl.blstm_stack_fwd(desc, x, params[:-2], sl, y_top, reserve, ws)
+    rl.softmax_ce_fwd_bwd(T, B, F, C, 0, y_top, params[-2], params[-1], lab, sl, loss, errors, dy, grads[-2], grads[-1], cews)
+    print("paper train step: backward", flush=True)
+    rl.blstm_stack_bwd(desc, x, params[:-2], sl, dy, y_top, grads[:-2], None, reserve, ws, None, sb)
+    torch.cuda.synchronize()
+    assert rl.rlstm_last_timeout(ws) == 0
+    got_g = [a.cpu().numpy() for a in grads]
+    rl.rlstm_adam_step(flat_p, flat_g, m, v, lr, 0.9, 0.999, 1e-8, 1)
+    torch.cuda.synchronize()
+    assert abs(float(loss.item()) - float(g["loss"])) < TOL_LOSS * float(g["loss"]), (float(loss.item()), float(g["loss"]))
+    # the error count is an integer decided by float32 comparisons: exact unless a valid frame's two largest logits
+    # are closer than float32 resolves (the oracle recorded how many such frames there are, and the smallest gap)
+    assert abs(int(errors.item()) - int(g["errors"])) <= int(g["frames_with_gap_below_1e_5"]), (int(errors.item()), int(g["errors"]))
+    err = np.abs(dy.cpu().numpy().reshape(-1)[g["dy_idx"]] - g["dy_val"]).max() / float(g["dy_max"])
+    assert err < TOL_GRAD, ("dy", err)
+    for i, (a, p) in enumerate(zip(got_g, params)):
+        idx = g[f"grad_{i}_idx"]
+        err = np.abs(a.reshape(-1)[idx] - g[f"grad_{i}_val"]).max() / float(g[f"grad_{i}_max"])
+        print(f"tensor {i}: gradient error {err:.2e}", flush=True)
+        assert err < TOL_GRAD, (i, err)
+        # first Adam step: lr * g / (|g| + eps); a gradient within delta of the oracle's moves it by at most
+        # about 2 lr delta / (|g| + eps) (see test_training_step_against_oracle)
+        delta = TOL_GRAD * float(g[f"grad_{i}_max"])
+        slack = 2e-7 + 3.0 * lr * delta / (np.abs(g[f"grad_{i}_val"]) + 1e-8)
+        perr = np.abs(p.cpu().numpy().reshape(-1)[idx] - g[f"param_{i}_val"])
+        assert np.all(perr <= slack), (i, float((perr - slack).max()))
+        moved = np.abs(g[f"param_{i}_val"] - g[f"param_{i}_old"])
+        assert np.median(perr) < 1e-3 * np.median(moved) + 1e-7, (i, float(np.median(perr)), float(np.median(moved)))

@@ -166,3 +166,28 @@ def test_encoder_decoder_hand_off(engine):
     # sequence 3 has no encoder frames: the decoder starts from zero there; sequence 4 has no decoder frames:
     # nothing but the hand-back of zero reaches the encoder from it
     assert not enc["hT"][3].any() and not dec["dh0"][4].any()
+
+
+def test_paper_stream_full_size_against_oracle_samples():
+    """The streaming workload at full size (64 sequences, 6 segments of 250 frames, 3 x 512 units), in the launch
+    configuration bench.py times: sampled entries of every output against values the oracle wrote
+    (tests/golden/make_paper_stream_golden.py)."""
+    import os
+    from paper_1608_00895_amd import synth
+    g = np.load(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_stream_oracle_samples.npz"))
+    wl = synth.paper_stream()
+    assert np.array_equal(g["seq_lens"], wl.seq_lens)
+    run = StreamRun(wl.L, wl.S, wl.Tc, wl.B, wl.D, wl.H, rl.RLSTM_ENGINE_PERSISTENT)
+    got = run.run(wl.x, wl.params, wl.seq_lens, wl.G, np.zeros((wl.L, 2, wl.B, wl.H), np.float32))
+
+    def check(name, arr, tol):
+        err = np.abs(arr.reshape(-1)[g[name + "_idx"]].astype(np.float64) - g[name + "_val"]).max() / float(g[name + "_max"])
+        print(name, err, flush=True)
+        assert err < tol, (name, err)
+
+    check("y", got["y"], TOL_FWD)
+    check("state", got["state"], TOL_FWD)
+    check("dx", got["dx"], TOL_GRAD)
+    for l in range(wl.L):
+        for j, nm in enumerate(("dW", "dR", "db")):
+            check(f"{nm}_{l}", got["grads"][3 * l + j], TOL_GRAD)
