@@ -274,6 +274,8 @@ def main():
                     help="steps of the first piece the recurrent passes are cut into (library default if omitted; 0 = uncut)")
     ap.add_argument("--batch-groups", type=int, default=None,
                     help="groups the sequences are dealt out to per direction (library default if omitted)")
+    ap.add_argument("--overlap-mode", type=int, default=None,
+                    help="-1 per shape (library default), 0 serial, 1 products share CUs with the recurrent kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed region, run one plain 1 GiB copy kernel (known HBM traffic) "
@@ -354,6 +356,8 @@ def main():
     ws = torch.empty(rl.rblstm_workspace_bytes(desc), dtype=torch.uint8, device=dev)
     sa = torch.cuda.current_stream()
     sb = None if args.one_stream else torch.cuda.Stream()
+    if args.overlap_mode is not None:
+        rl.rlstm_set_overlap_mode(args.overlap_mode)
     if args.first_piece is not None:
         rl.rlstm_set_first_piece(args.first_piece)
     if args.batch_groups is not None:

@@ -416,6 +416,25 @@ RLSTM_API int rlstm_exchange_floor(int groups, int members, int tile_bytes, int 
 RLSTM_API int rlstm_set_batch_groups(int groups);
 
 /*
+ * How blstm_stack_fwd_bwd / blstm_stack_bwd with two streams run the matrix products beside the recurrent
+ * passes (testing and measurement; process-wide, not thread-safe):
+ * -1 (default) chosen per shape;  0 one after the other;  1 products and recurrent workgroups share CUs and
+ * the passes are cut into pieces (falls back to 0 where the two LDS footprints do not fit one CU).
+ * RLSTM_EDIM for any other value.  The choice changes the order
+ * of floating-point sums (kernel shapes), never which frames or parameters are computed.
+ */
+RLSTM_API int rlstm_set_overlap_mode(int mode);
+
+/*
+ * Choice among the fp32 matrix-product kernels (testing and measurement; process-wide, not thread-safe):
+ * 0 (default) the library decides per call: the pipelined kernel where both operands consist of whole,
+ *   16-byte aligned float4s and the product does not run beside the recurrent kernels on the same CUs,
+ *   the plain kernel otherwise;  1: the pipelined kernel wherever its operand conditions hold;
+ * 2: the plain kernel.  RLSTM_EDIM for any other value.
+ */
+RLSTM_API int rlstm_set_gemm_variant(int variant);
+
+/*
  * Test hook for the failure path of the persistent kernels (not part of the method).  From the
  * next call on, workgroup `mute_workgroup` of every persistent launch withholds its step flags
  * (-1: none does), and every wait between workgroups is bounded by `wait_ticks` ticks of the

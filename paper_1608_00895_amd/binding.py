@@ -26,7 +26,7 @@ EXPORTS = [
     "lstm_fwd", "lstm_bwd", "blstm_stack_fwd_bwd", "blstm_stack_fwd", "blstm_stack_bwd",
     "rlstm_ce_workspace_bytes", "softmax_ce_fwd_bwd", "rlstm_sgd_momentum_step", "rlstm_adam_step",
     "rlstm_stream_reserve_bytes", "rlstm_stream_workspace_bytes", "lstm_stream_fwd_bwd",
-    "rlstm_gemm_f32", "rlstm_gemm_bf16", "rlstm_copy_f32", "rlstm_profile_enable", "rlstm_profile_read", "rlstm_last_timeout", "rlstm_test_hook", "rlstm_set_first_piece", "rlstm_set_batch_groups", "rmdlstm_reserve_bytes", "rmdlstm_workspace_bytes", "mdlstm_fwd", "mdlstm_bwd", "rlstm_chunk_plan", "rlstm_chunk_gather", "rblstm_plan", "rlstm_exchange_floor_bytes", "rlstm_exchange_floor", "rlstm_resolve_engine", "rlstm_strerror", "rlstm_version",
+    "rlstm_gemm_f32", "rlstm_gemm_bf16", "rlstm_copy_f32", "rlstm_profile_enable", "rlstm_profile_read", "rlstm_last_timeout", "rlstm_test_hook", "rlstm_set_first_piece", "rlstm_set_batch_groups", "rlstm_set_gemm_variant", "rlstm_set_overlap_mode", "rmdlstm_reserve_bytes", "rmdlstm_workspace_bytes", "mdlstm_fwd", "mdlstm_bwd", "rlstm_chunk_plan", "rlstm_chunk_gather", "rblstm_plan", "rlstm_exchange_floor_bytes", "rlstm_exchange_floor", "rlstm_resolve_engine", "rlstm_strerror", "rlstm_version",
 ]
 
 
@@ -143,6 +143,10 @@ def lib() -> ctypes.CDLL:
         L.rlstm_exchange_floor.argtypes = [ip, ip, ip, ip, ip, vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_float), vp]
         L.rlstm_set_batch_groups.restype = ip
         L.rlstm_set_batch_groups.argtypes = [ip]
+        L.rlstm_set_overlap_mode.restype = ip
+        L.rlstm_set_overlap_mode.argtypes = [ip]
+        L.rlstm_set_gemm_variant.restype = ip
+        L.rlstm_set_gemm_variant.argtypes = [ip]
         L.rlstm_set_first_piece.restype = ip
         L.rlstm_set_first_piece.argtypes = [ip]
         L.rlstm_test_hook.restype = ip
@@ -370,6 +374,20 @@ def rlstm_set_batch_groups(groups: int) -> int:
     rc = int(lib().rlstm_set_batch_groups(int(groups)))
     if rc != 0:
         raise RlstmError(rc, "rlstm_set_batch_groups")
+    return rc
+
+
+def rlstm_set_overlap_mode(mode: int) -> int:
+    rc = lib().rlstm_set_overlap_mode(int(mode))
+    if rc != 0:
+        raise RlstmError(rc, "rlstm_set_overlap_mode")
+    return rc
+
+
+def rlstm_set_gemm_variant(variant: int) -> int:
+    rc = lib().rlstm_set_gemm_variant(int(variant))
+    if rc != 0:
+        raise RlstmError(rc, "rlstm_set_gemm_variant")
     return rc
 
 

@@ -149,11 +149,29 @@ int g_first_piece = 128;         // steps of piece 0; 0 = do not cut
 
 // Cutting the passes pays only if a matrix-product workgroup fits on a CU next to a workgroup of
 // the persistent kernels (LDS); otherwise the products just queue behind the recurrent launches.
-bool products_can_share_cus(const RecShape& rs, int operand_dtype) {
+// How the products on stream b run beside the recurrent passes on stream a.
+//  kShare:  products and recurrent workgroups share CUs, the passes are cut into pieces and fed one piece ahead.
+//           Pays when the recurrent kernels leave the matrix cores idle most of a step (small tiles per workgroup:
+//           (sequences per group / 16) * (units per workgroup / 4) <= 2) and both footprints fit a CU's LDS.
+//           4 x 500 stack, B = 32: 65.3 ms against 69.9 ms serial, although every recurrent step gets slower
+//           (5.9 / 9.0 us against 4.85 / 6.4 us alone).
+//  kSerial: one after the other on stream a.  81 segments of 250 frames, 3 x 512: 25.9 ms against 28.6 ms shared
+//           (three 16-row tiles per workgroup keep the matrix cores busy; products beside them crawl).
+// Also measured and dropped: giving the recurrent kernels half of the CUs and the products the other half (both
+// asking for more than half of a CU's LDS): 67.6 ms on the 4 x 500 stack; the products at half rate become the
+// critical path and the recurrent steps still slow down (5.9 / 8.3 us) through the shared memory system.
+enum OverlapMode { kSerial = 0, kShare = 1 };
+int g_overlap_mode = -1;         // -1: chosen per shape; otherwise forced (kShare falls back to kSerial where the LDS does not fit)
+
+OverlapMode overlap_mode(const RecShape& rs, int operand_dtype, bool persistent, bool two_streams) {
+  if (!persistent || !two_streams || g_overlap_mode == kSerial) return kSerial;
   DeviceInfo di;
-  if (device_info(&di) != hipSuccess) { (void)hipGetLastError(); return false; }
+  if (device_info(&di) != hipSuccess) { (void)hipGetLastError(); return kSerial; }
+  int plan[8];
   const size_t rec = persistent_lds_bytes(rs, di.num_cus, di.max_lds);
-  return rec != 0 && rec + gemm_small_lds_bytes(operand_dtype) <= di.max_lds;
+  const bool fits = rec != 0 && rec + gemm_small_lds_bytes(operand_dtype) <= di.max_lds;
+  const bool idle_cores = persistent_plan_info(rs, di.num_cus, di.max_lds, plan) && ((plan[2] + 15) / 16) * (plan[3] / 4) <= 2;
+  return (fits && (idle_cores || g_overlap_mode == kShare)) ? kShare : kSerial;
 }
 
 std::vector<int> piece_bounds(int T, bool pipelined) {
@@ -193,7 +211,9 @@ int stack_forward(const rblstm_desc* d, const float* x, const float* const* para
   unsigned* flag = reinterpret_cast<unsigned*>(ws);
   void* recws = ws + kFlagBytes;
   const int T = d->T, B = d->B, H = d->H;
-  const bool pipelined = persistent && sb != sa && products_can_share_cus(rs, d->operand_dtype);
+  const OverlapMode mode = overlap_mode(rs, d->operand_dtype, persistent, sb != sa);
+  if (mode == kSerial) sb = sa;
+  const bool pipelined = mode != kSerial;
   const std::vector<int> pb = piece_bounds(T, pipelined);
   const int np = (int)pb.size() - 1;
   EventList evs;
@@ -218,7 +238,8 @@ int stack_forward(const rblstm_desc* d, const float* x, const float* const* para
         g.M = (s1 - s0) * B; g.N = 4 * H; g.K = din;
         g.A = in + f0 * B * din; g.lda = din; g.B = params[6 * l + 3 * k + 0]; g.ldb = 4 * H;
         g.C = base + lay.zg[k] + f0 * B * 4 * H; g.ldc = 4 * H; g.bias = params[6 * l + 3 * k + 2];
-        g.naive = !persistent; g.operand_dtype = d->operand_dtype; g.small_footprint = pipelined;
+        g.naive = !persistent; g.operand_dtype = d->operand_dtype;
+        g.small_footprint = mode == kShare;
         ProfScope ps(sb, 0, l, 1, 0, gemm_flop(g));
         RLSTM_TRY(gemm(sb, g));
       }
@@ -237,7 +258,8 @@ int stack_backward(const rblstm_desc* d, const float* x, const float* const* par
                    const float* dy_top, const float* y_top, float* const* grads, float* dx, float* res, char* ws,
                    hipStream_t sa, hipStream_t sb, bool persistent) {
   const RecShape rs = stack_rec_shape(d);
-  const bool overlap = sb != sa;
+  const OverlapMode mode = overlap_mode(rs, d->operand_dtype, persistent, sb != sa);
+  if (mode == kSerial) sb = sa;
   int rc = RLSTM_OK;
   int resident_err = 0;
   const StackLayout lay = stack_layout(d);
@@ -254,7 +276,7 @@ int stack_backward(const rblstm_desc* d, const float* x, const float* const* par
   // w.r.t. a layer's input is the dy of the layer below: it is produced on stream b in the pieces,
   // and in the frame order, in which that layer's pass back through time consumes it, one piece
   // ahead; the weight gradients follow on stream b and overlap the rest of that pass.
-  const bool pipelined = persistent && overlap && products_can_share_cus(rs, d->operand_dtype);
+  const bool pipelined = mode != kSerial;
   const std::vector<int> pb = piece_bounds(T, pipelined);
   const int np = (int)pb.size() - 1;
   EventList evs;
@@ -295,7 +317,8 @@ int stack_backward(const rblstm_desc* d, const float* x, const float* const* par
             g.A = base + lay.zg[k] + f0 * B * 4 * H; g.lda = 4 * H;
             g.B = params[6 * l + 3 * k + 0] + (size_t)tk * H * 4 * H; g.ldb = 4 * H;
             g.C = dxl + f0 * B * din + (size_t)tk * H; g.ldc = din; g.accumulate = (k == 1);
-            g.naive = !persistent; g.operand_dtype = d->operand_dtype; g.small_footprint = pipelined;
+            g.naive = !persistent; g.operand_dtype = d->operand_dtype;
+            g.small_footprint = mode == kShare;
             ProfScope ps(sb, 3, l, 1, 0, gemm_flop(g));
             RLSTM_TRY(gemm(sb, g));
           }
@@ -322,7 +345,7 @@ int stack_backward(const rblstm_desc* d, const float* x, const float* const* par
     for (int k = 0; k < 2; ++k) {
       rc = weight_grads(sb, l, T, B, din, H, k == 0 ? 1 : -1, xin, din, yl + (size_t)k * H, 2 * H,
                         base + lay.zg[k], grads[6 * l + 3 * k + 0], grads[6 * l + 3 * k + 1], skws, skfloats,
-                        !persistent, d->operand_dtype, pipelined);
+                        !persistent, d->operand_dtype, mode == kShare);
       if (rc != RLSTM_OK) return rc;
     }
     dy = dxl;
@@ -424,6 +447,18 @@ int rlstm_exchange_floor(int groups, int members, int tile_bytes, int read_bytes
   RLSTM_TRY(exchange_probe(static_cast<hipStream_t>(hip_stream), groups, members, tile_bytes, read_bytes, steps,
                            workspace, us_per_step, &timed_out, &resident_err));
   return timed_out ? RLSTM_EHIP : RLSTM_OK;
+}
+
+int rlstm_set_overlap_mode(int mode) {
+  if (mode < -1 || mode > 1) return RLSTM_EDIM;
+  g_overlap_mode = mode;
+  return RLSTM_OK;
+}
+
+int rlstm_set_gemm_variant(int variant) {
+  if (variant < 0 || variant > 2) return RLSTM_EDIM;
+  gemm_set_variant(variant);
+  return RLSTM_OK;
 }
 
 int rlstm_set_batch_groups(int groups) {

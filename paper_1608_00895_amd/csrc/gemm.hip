@@ -238,6 +238,202 @@ __global__ __launch_bounds__(256) void gemm_mfma_f32_kernel(GemmP p) {
 }
 
 // ---------------------------------------------------------------------------
+// Pipelined fp32 kernel for operands whose rows are whole, 16-byte aligned float4s (the usual case).
+// Same tile shape as above; what differs is how a slab gets from memory into LDS:
+//  * buffer loads with a byte range instead of branches: a lane outside the matrix (row or column tail,
+//    K tail, slab beyond the last) gets an offset beyond the range and reads zeros;
+//  * the loads of slab s+2 and the LDS stores of slab s+1 are spread over the MFMA steps of slab s, so a
+//    wavefront keeps the matrix core fed by itself instead of relying on other wavefronts to cover a
+//    bulk transition between slabs;
+//  * an operand that is k-contiguous in memory stays k-contiguous in LDS ([128 rows][16 k], one 16-byte
+//    store per float4, chunks XOR-swizzled by row so that stores and 16-byte reads are conflict-free).
+//    The MFMA sums over k in any order as long as both operands agree: step j of a slab takes
+//    k = 8 * (lane / 32) + j, so a lane's eight k values of a row are two 16-byte reads.
+// ---------------------------------------------------------------------------
+constexpr int BK2 = 16;
+constexpr int SLAB_FLOATS = BK2 * LDT;             // also covers the k-contiguous form (128 * 16)
+constexpr unsigned kOutOfRange = 0x80000000u;      // beyond any num_records this kernel sets (< 2^31)
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ floatx4 buffer_load_x4(__amdgpu_buffer_rsrc_t rsrc, unsigned off) {
+  return __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, 0));
+}
+
+// chunk (16 bytes = 4 k) kq of row r of a k-contiguous slab sits at float offset:
+__device__ __forceinline__ int kc_offset(int r, int kq) { return (r * 4 + (kq ^ ((r >> 1) & 3))) * 4; }
+
+// One operand's side of the pipeline.  KC: k-contiguous in memory (A [M,K] or B stored [N,K]).
+template <bool KC>
+struct SlabFeeder {
+  __amdgpu_buffer_rsrc_t rsrc;
+  unsigned voff[2];     // byte offset of this thread's two float4s within slab 0 (or kOutOfRange)
+  unsigned step;        // byte advance per slab
+  int lds_off[2];       // float offset of the two float4s inside a slab buffer
+  int kq4[2];           // KC: first k (relative to the slab) of each float4
+  int klen;             // kend - kbeg
+  floatx4 r[2];
+
+  __device__ __forceinline__ void init(const float* ptr, int ld, int mn0, int MN, int kbeg, int kend) {
+    const int tid = threadIdx.x;
+    klen = kend - kbeg;
+    if (KC) {
+      const int rows = min(TM, MN - mn0);
+      const float* base = ptr + (size_t)mn0 * ld + kbeg;
+      rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(base), 0, (int)((size_t)rows * ld * 4 - (size_t)kbeg * 4), 0x00020000);
+      step = BK2 * 4;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int idx = tid + i * 256;
+        const int row = idx >> 2, kq = idx & 3;
+        voff[i] = (unsigned)row * (unsigned)ld * 4u + kq * 16u;      // rows beyond the matrix fall outside num_records
+        kq4[i] = kq * 4;
+        lds_off[i] = kc_offset(row, kq);
+      }
+    } else {
+      const float* base = ptr + (size_t)kbeg * ld + mn0;
+      rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(base), 0, (int)((size_t)klen * ld * 4), 0x00020000);
+      step = (unsigned)BK2 * (unsigned)ld * 4u;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int idx = tid + i * 256;
+        const int row = idx >> 5, c4 = idx & 31;
+        voff[i] = (mn0 + c4 * 4 < MN) ? (unsigned)row * (unsigned)ld * 4u + c4 * 16u : kOutOfRange;   // k tail: num_records
+        kq4[i] = 0;
+        lds_off[i] = row * LDT + c4 * 4;
+      }
+    }
+  }
+  // issue the loads of slab s (any s >= 0; slabs beyond the last read zeros)
+  __device__ __forceinline__ void load(int s) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      unsigned off = voff[i] + (unsigned)s * step;
+      if (KC) off = (s * BK2 + kq4[i] < klen) ? off : kOutOfRange;
+      if (!KC) off = (s * BK2 < klen) ? off : kOutOfRange;       // keeps s * step from wrapping around
+      r[i] = buffer_load_x4(rsrc, off);
+    }
+  }
+  __device__ __forceinline__ void store(float* slab) const {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) *reinterpret_cast<floatx4*>(slab + lds_off[i]) = r[i];
+  }
+};
+
+// fragments of a k-contiguous slab for one wavefront: its two 32-row tiles, eight k per lane
+__device__ __forceinline__ void read_kc(const float* slab, int row0, int l32, int lh, float (&f)[2][8]) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int r = row0 + i * 32 + l32;
+    const floatx4 lo = *reinterpret_cast<const floatx4*>(slab + kc_offset(r, 2 * lh));
+    const floatx4 hi = *reinterpret_cast<const floatx4*>(slab + kc_offset(r, 2 * lh + 1));
+#pragma unroll
+    for (int q = 0; q < 4; ++q) { f[i][q] = lo[q]; f[i][4 + q] = hi[q]; }
+  }
+}
+
+// TA: A stored [K,M]; TB: B stored [N,K] (as in the kernel above)
+template <bool TA, bool TB>
+__global__ __launch_bounds__(256) void gemm_mfma_f32_v2_kernel(GemmP p) {
+  extern __shared__ __align__(16) float smem[];
+  float* As = smem;                          // [2][SLAB_FLOATS]
+  float* Bs = smem + 2 * SLAB_FLOATS;        // [2][SLAB_FLOATS]
+  constexpr bool AKC = !TA, BKC = TB;
+
+  int tile, kz;
+  if (!work_item(p, &tile, &kz)) return;
+  const int tn = tile % p.tiles_n, tm = tile / p.tiles_n;
+  const int m0 = tm * TM, n0 = tn * TN;
+  const int kbeg = kz * p.kchunk;
+  const int kend = min(p.K, kbeg + p.kchunk);
+  const int nslab = (kend - kbeg + BK2 - 1) / BK2;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, lh = lane >> 5;
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  SlabFeeder<AKC> fa;
+  SlabFeeder<BKC> fb;
+  fa.init(p.A, p.lda, m0, p.M, kbeg, kend);
+  fb.init(p.B, p.ldb, n0, p.N, kbeg, kend);
+
+  fa.load(0); fb.load(0);
+  fa.store(As); fb.store(Bs);
+  fa.load(1); fb.load(1);
+  __syncthreads();
+
+  for (int s = 0; s < nslab; ++s) {
+    const int buf = s & 1;
+    const float* as = As + buf * SLAB_FLOATS;
+    const float* bs = Bs + buf * SLAB_FLOATS;
+    float* as_next = As + (buf ^ 1) * SLAB_FLOATS;
+    float* bs_next = Bs + (buf ^ 1) * SLAB_FLOATS;
+    float af[2][8], bf[2][8];
+    if (AKC) read_kc(as, wm * 64, l32, lh, af);
+    if (BKC) read_kc(bs, wn * 64, l32, lh, bf);
+    // natural slabs: element (k, mn) at [k][mn]; this lane's k in step j is lh * 8 + j
+    const float* an = as + (lh * 8) * LDT + wm * 64 + l32;
+    const float* bn = bs + (lh * 8) * LDT + wn * 64 + l32;
+    float a0 = 0.f, a1 = 0.f, b0 = 0.f, b1 = 0.f;
+    if (!AKC) { a0 = an[0]; a1 = an[32]; }
+    if (!BKC) { b0 = bn[0]; b1 = bn[32]; }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float na0 = 0.f, na1 = 0.f, nb0 = 0.f, nb1 = 0.f;
+      if (j + 1 < 8) {
+        if (!AKC) { na0 = an[(j + 1) * LDT]; na1 = an[(j + 1) * LDT + 32]; }
+        if (!BKC) { nb0 = bn[(j + 1) * LDT]; nb1 = bn[(j + 1) * LDT + 32]; }
+      }
+      // the next slab's way into LDS and the loads of the one after it, spread over the first steps
+      if (j == 0) fa.store(as_next);
+      if (j == 1) fb.store(bs_next);
+      if (j == 2) fa.load(s + 2);
+      if (j == 3) fb.load(s + 2);
+      __builtin_amdgcn_sched_barrier(0);
+      const float x0 = AKC ? af[0][j] : a0, x1 = AKC ? af[1][j] : a1;
+      const float y0 = BKC ? bf[0][j] : b0, y1 = BKC ? bf[1][j] : b1;
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(x0, y0, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(x0, y1, acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(x1, y0, acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(x1, y1, acc[1][1], 0, 0, 0);
+      a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;
+    }
+    __syncthreads();
+  }
+
+  float* Cout = p.C;
+  int ldc = p.ldc;
+  const bool partial = p.partial != nullptr;
+  if (partial) { Cout = p.partial + (size_t)kz * p.M * p.N; ldc = p.N; }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int col = n0 + wn * 64 + j * 32 + l32;
+      if (col >= p.N) continue;
+      const float bv = (!partial && p.bias) ? p.bias[col] : 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wm * 64 + i * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
+        if (row < p.M) {
+          float* dst = Cout + (size_t)row * ldc + col;
+          float v = acc[i][j][r] + bv;
+          if (!partial && p.accumulate) v += *dst;
+          *dst = v;
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // bf16-operand variant: operands are rounded to bf16 (round to nearest even) on their way into
 // LDS, products accumulate in fp32 (v_mfma_f32_32x32x16_bf16), C stays fp32.  Same 128 x 128
 // tile and 2 x 2 wavefront layout; K slabs of 32.  LDS holds both operands [128][32 (+8)] bf16
@@ -476,6 +672,13 @@ hipError_t launch_mfma(hipStream_t stream, const GemmP& p, dim3 grid, bool vec) 
   return hipGetLastError();
 }
 
+template <bool TA, bool TB>
+hipError_t launch_mfma_v2(hipStream_t stream, const GemmP& p, dim3 grid) {
+  const size_t lds = (size_t)4 * SLAB_FLOATS * sizeof(float);
+  hipLaunchKernelGGL((gemm_mfma_f32_v2_kernel<TA, TB>), grid, dim3(256), lds, stream, p);
+  return hipGetLastError();
+}
+
 template <int WM, int WN, bool TA, bool TB, bool VEC>
 hipError_t launch_bf16_v(hipStream_t stream, const GemmP& p, dim3 grid) {
   const size_t lds = (size_t)2 * 64 * (WM + WN) * LDK * sizeof(unsigned short);
@@ -494,6 +697,9 @@ hipError_t launch_bf16(hipStream_t stream, const GemmP& p, dim3 grid, bool vec, 
 }
 
 }  // namespace
+
+namespace { int g_gemm_variant = 0; }
+void gemm_set_variant(int v) { g_gemm_variant = v; }
 
 hipError_t gemm(hipStream_t stream, const GemmCall& g) {
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
@@ -517,9 +723,10 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
 
   const int BK = bf16 ? BKH : 16;
   // float4 global loads need 16-byte aligned rows and whole float4s inside the matrix
-  bool vec = aligned16(g.A) && aligned16(g.B) && (g.lda % 4 == 0) && (g.ldb % 4 == 0) && (g.K % 4 == 0);
-  if (g.transA) vec = vec && (g.M % 4 == 0);
-  if (!g.transB) vec = vec && (g.N % 4 == 0);
+  // (the dimension a float4 runs along must be a multiple of 4: k for an operand that is k-contiguous in
+  // memory, m or n otherwise; the other dimension, and K of the weight-gradient products, may be anything)
+  bool vec = aligned16(g.A) && aligned16(g.B) && (g.lda % 4 == 0) && (g.ldb % 4 == 0);
+  vec = vec && ((g.transA ? g.M : g.K) % 4 == 0) && ((g.transB ? g.K : g.N) % 4 == 0);
 
   const int tiles_m = (g.M + tile_m - 1) / tile_m;
   const int tiles = tiles_m * p.tiles_n;
@@ -541,6 +748,11 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
     p.kchunk = kchunk;
     p.partial = g.splitk_ws;
   }
+  // the pipelined kernel addresses an operand panel with 31-bit byte offsets
+  const size_t kspan = (size_t)p.kchunk;
+  const size_t a_panel = g.transA ? kspan * g.lda * 4 : (size_t)TM * g.lda * 4;
+  const size_t b_panel = g.transB ? (size_t)TN * g.ldb * 4 : kspan * g.ldb * 4;
+  const bool pipelined_ok = a_panel < (1ull << 31) && b_panel < (1ull << 31);
   p.tiles = tiles;
   p.work = tiles * slices;
   p.per_xcd = (p.work + 7) / 8;
@@ -551,6 +763,14 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
     else if (!g.transA && g.transB)  e = launch_bf16<false, true>(stream, p, grid, vec, big);
     else if (g.transA && !g.transB)  e = launch_bf16<true, false>(stream, p, grid, vec, big);
     else                             e = launch_bf16<true, true>(stream, p, grid, vec, big);
+  } else if (vec && pipelined_ok && (g_gemm_variant == 1 || (g_gemm_variant == 0 && !g.small_footprint))) {
+    // A product that shares its CUs with the recurrent kernels keeps to the plain kernel: measured on the
+    // 4 x 500 stack, the pipelined kernel beside them finishes its products sooner but slows every recurrent
+    // step (6.04 / 9.37 us against 5.89 / 9.02 us), and the step chain is what bounds the pass.
+    if (!g.transA && !g.transB)      e = launch_mfma_v2<false, false>(stream, p, grid);
+    else if (!g.transA && g.transB)  e = launch_mfma_v2<false, true>(stream, p, grid);
+    else if (g.transA && !g.transB)  e = launch_mfma_v2<true, false>(stream, p, grid);
+    else                             e = launch_mfma_v2<true, true>(stream, p, grid);
   } else {
     if (!g.transA && !g.transB)      e = launch_mfma<16, false, false>(stream, p, grid, vec);
     else if (!g.transA && g.transB)  e = launch_mfma<16, false, true>(stream, p, grid, vec);

@@ -43,7 +43,8 @@ typedef int intx4 __attribute__((ext_vector_type(4)));
 namespace {
 
 constexpr unsigned long long kDefaultWaitTicks = 400000000ull;   // 4 s of the 100 MHz wall clock
-constexpr int CG = 16;                  // 16-byte loads in flight per lane
+// 16-byte loads in flight per lane: a multiple of the batch tiles MT, so that a group of loads starts at a whole k-step
+template <int MT> constexpr int load_group() { return MT == 3 ? 12 : 16; }
 constexpr int kAuxSc1 = 16;             // buffer-load cache policy: device scope
 
 // ---- bounded spinning --------------------------------------------------------
@@ -133,6 +134,7 @@ __device__ __forceinline__ void wave_product(const float* xblock, int xblock_byt
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+  constexpr int CG = load_group<MT>();
   for (int c0 = 0; c0 < nch; c0 += CG) {
     floatx4 v[CG];
 #pragma unroll
@@ -147,9 +149,10 @@ __device__ __forceinline__ void wave_product(const float* xblock, int xblock_byt
       if (c0 + q < nch) {
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-          constexpr int KPC = 4 / MT;                 // k-steps per chunk
-          const int ks = (c0 + q) * KPC + w / MT;
-          const int mt = w % MT;
+          // element w of chunk c0 + q is pair L = (c0 + q) * 4 + w of the (k-step, batch tile) sequence;
+          // 4 * CG is a multiple of MT, so the tile index does not depend on c0
+          const int ks = (c0 * 4) / MT + (q * 4 + w) / MT;
+          const int mt = (q * 4 + w) % MT;
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt) {
             const float bf = bs[(ks * 4 + lq) * ldb + ((nt + lq) & (NT - 1)) * 16 + l16];
@@ -188,6 +191,7 @@ __device__ __forceinline__ void wave_product_bf(const void* xblock, int xblock_b
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+  constexpr int CG = load_group<MT>();
   for (int c0 = 0; c0 < nch; c0 += CG) {
     intx4 v[CG];
 #pragma unroll
@@ -244,7 +248,7 @@ struct PFwdParams {
 // acknowledgements never sit in the step's dependency chain.
 constexpr int kBlockThreads = 320;
 
-// ROWS: sequences a group can hold (8, 16, 32 or 64); 8 uses half of one 16-row MFMA tile.
+// ROWS: sequences a group can hold (8, 16, 32, 48 or 64); 8 uses half of one 16-row MFMA tile.
 template <int ROWS, int NT, bool BF>
 __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwdParams p) {
   constexpr int MT = ROWS <= 16 ? 1 : ROWS / 16;
@@ -854,11 +858,13 @@ __global__ __launch_bounds__(256) void seed_h0_kernel(PrepParams p) {
     if (p.bf) {
       if (p.MT == 1) slot = operand_slot_bf<1>(k, b);
       else if (p.MT == 2) slot = operand_slot_bf<2>(k, b);
+      else if (p.MT == 3) slot = operand_slot_bf<3>(k, b);
       else slot = operand_slot_bf<4>(k, b);
       static_cast<unsigned short*>(hx1)[(size_t)(u / p.KW) * (p.wbytes / 2) + slot] = bf16_bits(p.h0[d][gtid]);
     } else {
       if (p.MT == 1) slot = operand_slot<1>(k, b);
       else if (p.MT == 2) slot = operand_slot<2>(k, b);
+      else if (p.MT == 3) slot = operand_slot<3>(k, b);
       else slot = operand_slot<4>(k, b);
       static_cast<float*>(hx1)[(size_t)(u / p.KW) * (p.wbytes / 4) + slot] = p.h0[d][gtid];
     }
@@ -910,7 +916,7 @@ Plan plan_for(const RecShape& s, int num_cus, size_t max_lds, int nb) {
   if (Bg > 64) return pl;
   const int per_group = num_cus / NG;
   for (int NT = 1; NT <= 4; NT *= 2) {
-    const int rows = Bg <= 8 && have_kernel(8, NT) ? 8 : (Bg <= 16 ? 16 : (Bg <= 32 ? 32 : 64));
+    const int rows = Bg <= 8 && have_kernel(8, NT) ? 8 : (Bg <= 16 ? 16 : (Bg <= 32 ? 32 : (Bg <= 48 && have_kernel(48, NT) ? 48 : 64)));
     if (!have_kernel(rows, NT)) continue;
     const int MT = rows <= 16 ? 1 : rows / 16;
     const int U = 4 * NT, UG = 16 * NT;
@@ -1100,8 +1106,8 @@ hipError_t persistent_forward(hipStream_t stream, const RecShape& s, const RecFw
     return resident_launch(lstm_fwd_persistent_kernel<ROWS_, NT_, false>, grid, kBlockThreads, pl.ldsF,  \
                            di.num_cus, stream, &kp, resident_err);                                       \
   }
-  RLSTM_FWD_CASE(16, 1) RLSTM_FWD_CASE(32, 1) RLSTM_FWD_CASE(64, 1)
-  RLSTM_FWD_CASE(8, 2) RLSTM_FWD_CASE(16, 2) RLSTM_FWD_CASE(32, 2) RLSTM_FWD_CASE(64, 2)
+  RLSTM_FWD_CASE(16, 1) RLSTM_FWD_CASE(32, 1) RLSTM_FWD_CASE(48, 1) RLSTM_FWD_CASE(64, 1)
+  RLSTM_FWD_CASE(8, 2) RLSTM_FWD_CASE(16, 2) RLSTM_FWD_CASE(32, 2) RLSTM_FWD_CASE(48, 2) RLSTM_FWD_CASE(64, 2)
   RLSTM_FWD_CASE(8, 4) RLSTM_FWD_CASE(16, 4)
 #undef RLSTM_FWD_CASE
   return hipErrorInvalidValue;
@@ -1158,8 +1164,8 @@ hipError_t persistent_backward(hipStream_t stream, const RecShape& s, const RecB
       e = resident_launch(lstm_bwd_persistent_kernel<ROWS_, NT_, false>, grid, kBlockThreads, pl.ldsB,   \
                           di.num_cus, stream, &kp, resident_err);                                        \
   }
-  RLSTM_BWD_CASE(16, 1) RLSTM_BWD_CASE(32, 1) RLSTM_BWD_CASE(64, 1)
-  RLSTM_BWD_CASE(8, 2) RLSTM_BWD_CASE(16, 2) RLSTM_BWD_CASE(32, 2) RLSTM_BWD_CASE(64, 2)
+  RLSTM_BWD_CASE(16, 1) RLSTM_BWD_CASE(32, 1) RLSTM_BWD_CASE(48, 1) RLSTM_BWD_CASE(64, 1)
+  RLSTM_BWD_CASE(8, 2) RLSTM_BWD_CASE(16, 2) RLSTM_BWD_CASE(32, 2) RLSTM_BWD_CASE(48, 2) RLSTM_BWD_CASE(64, 2)
   RLSTM_BWD_CASE(8, 4) RLSTM_BWD_CASE(16, 4)
 #undef RLSTM_BWD_CASE
   if (e != hipSuccess) return e;

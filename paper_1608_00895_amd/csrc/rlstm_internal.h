@@ -30,9 +30,11 @@ struct GemmCall {
   float* splitk_ws = nullptr; size_t splitk_floats = 0;
   int operand_dtype = 0;
   bool naive = false;
-  bool small_footprint = false;   // keep to the 128 x 128 kernel, which can share a CU with a recurrent workgroup
+  bool small_footprint = false;   // runs beside the recurrent kernels on shared CUs: keep to the plain 128 x 128 kernel
 };
 hipError_t gemm(hipStream_t stream, const GemmCall& g);
+// fp32 kernel choice: 0 by call (default), 1 the pipelined kernel wherever it applies, 2 the plain kernel
+void gemm_set_variant(int v);
 
 // ---------------------------------------------------------------------------
 // Recurrent passes.  One call handles ndir (1 or 2) independent directions of
