@@ -166,6 +166,61 @@ def bench_config5(args):
     print(json.dumps(out), flush=True)
 
 
+def bench_gemm(args):
+    """The whole-minibatch matrix products alone, at the shapes of config 3 and of the paper's batch: one step = one
+    launch of every shape; reports TFLOP/s per shape (fp32 MFMA roofline) for the kernel variant the library picks
+    and for the plain kernel."""
+    import torch
+    from paper_1608_00895_amd import binding as rl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    shapes = [("config3 projection X W (NN)", 0, 0, 32000, 2000, 1000), ("config3 input gradient dZ W^T (NT)", 0, 1, 32000, 500, 2000),
+              ("config3 weight gradient X^T dZ (TN)", 1, 0, 1000, 2000, 32000), ("config3 recurrent weight gradient (TN)", 1, 0, 500, 2000, 31968),
+              ("paper batch projection (NN)", 0, 0, 20250, 2048, 1024), ("paper batch input gradient (NT)", 0, 1, 20250, 512, 2048),
+              ("paper batch weight gradient (TN)", 1, 0, 1024, 2048, 20250), ("paper batch output layer logits (NN)", 0, 0, 20250, 1504, 1024),
+              ("square 8192 (NN)", 0, 0, 8192, 8192, 8192)]
+    sk = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+    kernels, total_flop, total_ms = [], 0.0, 0.0
+    # bring the clocks up before the first timed shape
+    Aw, Bw, Cw = torch.randn((4096, 4096), device=dev), torch.randn((4096, 4096), device=dev), torch.empty((4096, 4096), device=dev)
+    for _ in range(40):
+        rl.rlstm_gemm_f32(0, 0, 4096, 4096, 4096, Aw, 4096, Bw, 4096, Cw, 4096, None, None)
+    torch.cuda.synchronize()
+    for name, ta, tb, M, N, K in shapes:
+        A = torch.randn((K, M) if ta else (M, K), device=dev)
+        B = torch.randn((N, K) if tb else (K, N), device=dev)
+        C = torch.empty((M, N), device=dev)
+        lda, ldb = (M if ta else K), (K if tb else N)
+        res = {}
+        for variant, tag in ((0, "picked"), (2, "plain")):
+            rl.rlstm_set_gemm_variant(variant)
+            for _ in range(args.warmup):
+                rl.rlstm_gemm_f32(ta, tb, M, N, K, A, lda, B, ldb, C, N, None, sk)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                rl.rlstm_gemm_f32(ta, tb, M, N, K, A, lda, B, ldb, C, N, None, sk)
+            e1.record()
+            torch.cuda.synchronize()
+            res[tag] = e0.elapsed_time(e1) / args.steps
+        rl.rlstm_set_gemm_variant(0)
+        flop = 2.0 * M * N * K
+        kernels.append({"kernel": name, "M": M, "N": N, "K": K, "avg_ms": res["picked"], "tflops": flop / res["picked"] / 1e9,
+                        "plain_kernel_ms": res["plain"], "plain_kernel_tflops": flop / res["plain"] / 1e9})
+        log(kernels[-1])
+        total_flop += flop; total_ms += res["picked"]
+    dom = kernels[0]
+    out = {"metric": "fp32 matrix products alone, TFLOP/s over all shapes", "value": total_flop / total_ms / 1e9, "unit": "TFLOP/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": total_ms, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "matrix products at the shapes of config 3 and of the paper's batch"},
+           "roofline": {"kernel": dom["kernel"], "bound": "mfma", "achieved": dom["tflops"], "peak": PEAK_FP32_MFMA_TFLOPS,
+                        "unit": "TFLOP/s", "frac": dom["tflops"] / PEAK_FP32_MFMA_TFLOPS, "traffic": None},
+           "kernels": kernels}
+    print(json.dumps(out), flush=True)
+
+
 def bench_stream(args):
     """The streaming mode on whole sequences: one step = one lstm_stream_fwd_bwd call (all segments, forward and
     truncated backward, gradients of every parameter) on sequences resident in HBM."""
@@ -267,7 +322,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config3", choices=["config2", "config3", "config4", "config5", "paper_chunks", "paper_train", "paper_stream"])
+    ap.add_argument("--workload", default="config3", choices=["config2", "config3", "config4", "config5", "paper_chunks", "paper_train", "paper_stream", "gemm"])
     ap.add_argument("--engine", type=int, default=0)
     ap.add_argument("--one-stream", action="store_true")
     ap.add_argument("--first-piece", type=int, default=None,
@@ -290,6 +345,8 @@ def main():
         return bench_config5(args)
     if args.workload == "paper_stream":
         return bench_stream(args)
+    if args.workload == "gemm":
+        return bench_gemm(args)
 
     import numpy as np
     import torch
