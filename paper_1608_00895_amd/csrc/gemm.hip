@@ -679,6 +679,208 @@ hipError_t launch_mfma_v2(hipStream_t stream, const GemmP& p, dim3 grid) {
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Pipelined form of the bf16-operand kernel (operands of whole, 16-byte aligned float4s, as for the pipelined
+// fp32 kernel): the same tiles and the same LDS layout as above; the fp32 operands of slab s+2 are fetched with
+// range-checked buffer loads, and rounded and stored into LDS as slab s+1, in between the MFMAs of slab s.
+// A timing probe of the kernel above without its loads and LDS stores ran at 0.84-1.48 PFLOP/s against
+// 0.29-0.54 with them: the bulk transition between slabs, not the matrix core, set its speed.
+// ---------------------------------------------------------------------------
+// One operand's side: ROWS rows of the tile, a slab of 32 k.  A unit is two float4 of one thread.
+template <int ROWS, bool KC>
+struct SlabFeederBf {
+  static constexpr int kUnits = ROWS / 64;
+  __amdgpu_buffer_rsrc_t rsrc;
+  unsigned voff[kUnits][2];
+  unsigned step;
+  int lds_off[kUnits][2];      // KC: bf16 offset of each float4's 4 values; !KC: [u][0] = offset of the unit's first row
+  int kq[kUnits][2];           // KC: first k of each float4 inside the slab
+  int klen;
+  floatx4 r[kUnits][2];
+
+  __device__ __forceinline__ void init(const float* ptr, int ld, int mn0, int MN, int kbeg, int kend) {
+    const int tid = threadIdx.x;
+    klen = kend - kbeg;
+    if (KC) {
+      const int rows = min(ROWS, MN - mn0);
+      const float* base = ptr + (size_t)mn0 * ld + kbeg;
+      rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(base), 0, (int)((size_t)rows * ld * 4 - (size_t)kbeg * 4), 0x00020000);
+      step = BKH * 4;
+#pragma unroll
+      for (int u = 0; u < kUnits; ++u)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const int idx = tid + (u * 2 + h) * 256;
+          const int row = idx >> 3, q = (idx & 7) * 4;
+          voff[u][h] = (unsigned)row * (unsigned)ld * 4u + q * 4u;
+          kq[u][h] = q;
+          lds_off[u][h] = row * LDK + q;
+        }
+    } else {
+      const float* base = ptr + (size_t)kbeg * ld + mn0;
+      rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(base), 0, (int)((size_t)klen * ld * 4), 0x00020000);
+      step = (unsigned)BKH * (unsigned)ld * 4u;
+#pragma unroll
+      for (int u = 0; u < kUnits; ++u) {
+        const int idx = tid + u * 256;
+        const int mn = (idx >> 4) * 4, k = (idx & 15) * 2;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          voff[u][h] = (mn0 + mn < MN) ? (unsigned)(k + h) * (unsigned)ld * 4u + mn * 4u : kOutOfRange;
+          kq[u][h] = 0;
+        }
+        lds_off[u][0] = mn * LDK + k;
+        lds_off[u][1] = 0;
+      }
+    }
+  }
+  __device__ __forceinline__ void load(int u, int s) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      unsigned off = voff[u][h] + (unsigned)s * step;
+      if (KC) off = (s * BKH + kq[u][h] < klen) ? off : kOutOfRange;
+      else    off = (s * BKH < klen) ? off : kOutOfRange;
+      r[u][h] = buffer_load_x4(rsrc, off);
+    }
+  }
+  __device__ __forceinline__ void store(int u, unsigned short* slab) const {
+    if (KC) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        uint2 w;
+        w.x = pack_bf16(r[u][h][0], r[u][h][1]);
+        w.y = pack_bf16(r[u][h][2], r[u][h][3]);
+        *reinterpret_cast<uint2*>(slab + lds_off[u][h]) = w;
+      }
+    } else {
+      // rows k and k+1 of four columns: each column's pair of k is one 32-bit store
+      unsigned short* q = slab + lds_off[u][0];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) *reinterpret_cast<unsigned*>(q + c * LDK) = pack_bf16(r[u][0][c], r[u][1][c]);
+    }
+  }
+};
+
+template <int WM, int WN, bool TA, bool TB>
+__global__ __launch_bounds__(256) void gemm_mfma_bf16_v2_kernel(GemmP p) {
+  constexpr int TMB = 64 * WM, TNB = 64 * WN;
+  constexpr bool AKC = !TA, BKC = TB;
+  extern __shared__ __align__(16) float smem[];
+  unsigned short* As = reinterpret_cast<unsigned short*>(smem);     // [2][TMB][LDK]
+  unsigned short* Bs = As + 2 * TMB * LDK;                          // [2][TNB][LDK]
+
+  int tile, kz;
+  if (!work_item(p, &tile, &kz)) return;
+  const int tn = tile % p.tiles_n, tm = tile / p.tiles_n;
+  const int m0 = tm * TMB, n0 = tn * TNB;
+  const int kbeg = kz * p.kchunk;
+  const int kend = min(p.K, kbeg + p.kchunk);
+  const int nslab = (kend - kbeg + BKH - 1) / BKH;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, lh = lane >> 5;
+
+  floatx16 acc[WM][WN];
+#pragma unroll
+  for (int i = 0; i < WM; ++i)
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  SlabFeederBf<TMB, AKC> fa;
+  SlabFeederBf<TNB, BKC> fb;
+  fa.init(p.A, p.lda, m0, p.M, kbeg, kend);
+  fb.init(p.B, p.ldb, n0, p.N, kbeg, kend);
+  constexpr int UA = SlabFeederBf<TMB, AKC>::kUnits, UB = SlabFeederBf<TNB, BKC>::kUnits;
+  constexpr int NOPS = 2 * (UA + UB);            // stores of slab s+1 (A then B), then loads of slab s+2 (A then B)
+  constexpr int NMFMA = 2 * WM * WN;             // per slab and wavefront
+  constexpr int OPM = (NOPS + NMFMA - 1) / NMFMA;
+
+#pragma unroll
+  for (int u = 0; u < UA; ++u) fa.load(u, 0);
+#pragma unroll
+  for (int u = 0; u < UB; ++u) fb.load(u, 0);
+#pragma unroll
+  for (int u = 0; u < UA; ++u) fa.store(u, As);
+#pragma unroll
+  for (int u = 0; u < UB; ++u) fb.store(u, Bs);
+#pragma unroll
+  for (int u = 0; u < UA; ++u) fa.load(u, 1);
+#pragma unroll
+  for (int u = 0; u < UB; ++u) fb.load(u, 1);
+  __syncthreads();
+
+  for (int s = 0; s < nslab; ++s) {
+    const int buf = s & 1;
+    const unsigned short* as = As + buf * TMB * LDK + (wm * 32 * WM + l32) * LDK + lh * 8;
+    const unsigned short* bs = Bs + buf * TNB * LDK + (wn * 32 * WN + l32) * LDK + lh * 8;
+    unsigned short* as_next = As + (buf ^ 1) * TMB * LDK;
+    unsigned short* bs_next = Bs + (buf ^ 1) * TNB * LDK;
+#pragma unroll
+    for (int ks = 0; ks < BKH; ks += 16) {
+      bf16x8 af[WM], bfr[WN];
+#pragma unroll
+      for (int i = 0; i < WM; ++i) af[i] = *reinterpret_cast<const bf16x8*>(as + i * 32 * LDK + ks);
+#pragma unroll
+      for (int j = 0; j < WN; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(bs + j * 32 * LDK + ks);
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j) {
+          const int m = (ks / 16) * WM * WN + i * WN + j;       // index of this MFMA inside the slab
+#pragma unroll
+          for (int o = m * OPM; o < (m + 1) * OPM; ++o) {
+            if (o < UA) fa.store(o, as_next);
+            else if (o < UA + UB) fb.store(o - UA, bs_next);
+            else if (o < 2 * UA + UB) fa.load(o - UA - UB, s + 2);
+            else if (o < NOPS) fb.load(o - 2 * UA - UB, s + 2);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+    }
+    __syncthreads();
+  }
+
+  float* Cout = p.C;
+  int ldc = p.ldc;
+  const bool partial = p.partial != nullptr;
+  if (partial) { Cout = p.partial + (size_t)kz * p.M * p.N; ldc = p.N; }
+#pragma unroll
+  for (int i = 0; i < WM; ++i) {
+#pragma unroll
+    for (int j = 0; j < WN; ++j) {
+      const int col = n0 + (wn * WN + j) * 32 + l32;
+      if (col >= p.N) continue;
+      const float bv = (!partial && p.bias) ? p.bias[col] : 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + (wm * WM + i) * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
+        if (row < p.M) {
+          float* dst = Cout + (size_t)row * ldc + col;
+          float v = acc[i][j][r] + bv;
+          if (!partial && p.accumulate) v += *dst;
+          *dst = v;
+        }
+      }
+    }
+  }
+}
+
+template <int WM, int WN, bool TA, bool TB>
+hipError_t launch_bf16_v2(hipStream_t stream, const GemmP& p, dim3 grid) {
+  const size_t lds = (size_t)2 * 64 * (WM + WN) * LDK * sizeof(unsigned short);
+  const void* fn = reinterpret_cast<const void*>(gemm_mfma_bf16_v2_kernel<WM, WN, TA, TB>);
+  if (lds > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((gemm_mfma_bf16_v2_kernel<WM, WN, TA, TB>), grid, dim3(256), lds, stream, p);
+  return hipGetLastError();
+}
+
 template <int WM, int WN, bool TA, bool TB, bool VEC>
 hipError_t launch_bf16_v(hipStream_t stream, const GemmP& p, dim3 grid) {
   const size_t lds = (size_t)2 * 64 * (WM + WN) * LDK * sizeof(unsigned short);
@@ -691,7 +893,9 @@ hipError_t launch_bf16_v(hipStream_t stream, const GemmP& p, dim3 grid) {
   return hipGetLastError();
 }
 template <bool TA, bool TB>
-hipError_t launch_bf16(hipStream_t stream, const GemmP& p, dim3 grid, bool vec, bool big) {
+hipError_t launch_bf16(hipStream_t stream, const GemmP& p, dim3 grid, bool vec, bool big, bool pipelined) {
+  // the pipelined form pays with 256 x 256 tiles only (128 x 128: 204 against 294 TFLOP/s at 1000 x 4000 x 96000)
+  if (pipelined && big) return launch_bf16_v2<4, 4, TA, TB>(stream, p, grid);
   if (big) return vec ? launch_bf16_v<4, 4, TA, TB, true>(stream, p, grid) : launch_bf16_v<4, 4, TA, TB, false>(stream, p, grid);
   return vec ? launch_bf16_v<2, 2, TA, TB, true>(stream, p, grid) : launch_bf16_v<2, 2, TA, TB, false>(stream, p, grid);
 }
@@ -709,7 +913,10 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
   p.bias = g.bias; p.accumulate = g.accumulate ? 1 : 0;
   const bool bf16 = g.operand_dtype == 1;
   // bf16 operands: 256 x 256 tiles once those alone give every CU work
-  const bool big = bf16 && !g.naive && !g.small_footprint && (long long)((g.M + 255) / 256) * ((g.N + 255) / 256) >= 128;
+  // (or, where K is split into slices that multiply the work items, half as many such tiles)
+  const long long big_tiles = (long long)((g.M + 255) / 256) * ((g.N + 255) / 256);
+  const bool big = bf16 && !g.naive && !g.small_footprint &&
+                   (big_tiles >= 128 || (g.splitk_ws && g.K >= 16 * 1024 && big_tiles >= 48));
   const int tile_m = big ? 256 : TM, tile_n = big ? 256 : TN;
   p.tiles_n = (g.N + tile_n - 1) / tile_n;
   p.kchunk = g.K; p.partial = nullptr;
@@ -750,20 +957,21 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
   }
   // the pipelined kernel addresses an operand panel with 31-bit byte offsets
   const size_t kspan = (size_t)p.kchunk;
-  const size_t a_panel = g.transA ? kspan * g.lda * 4 : (size_t)TM * g.lda * 4;
-  const size_t b_panel = g.transB ? (size_t)TN * g.ldb * 4 : kspan * g.ldb * 4;
+  const size_t a_panel = g.transA ? kspan * g.lda * 4 : (size_t)tile_m * g.lda * 4;
+  const size_t b_panel = g.transB ? (size_t)tile_n * g.ldb * 4 : kspan * g.ldb * 4;
   const bool pipelined_ok = a_panel < (1ull << 31) && b_panel < (1ull << 31);
   p.tiles = tiles;
   p.work = tiles * slices;
   p.per_xcd = (p.work + 7) / 8;
   dim3 grid((unsigned)(8 * p.per_xcd), 1, 1);
   hipError_t e;
+  const bool pipelined = vec && pipelined_ok && (g_gemm_variant == 1 || (g_gemm_variant == 0 && !g.small_footprint));
   if (bf16) {
-    if (!g.transA && !g.transB)      e = launch_bf16<false, false>(stream, p, grid, vec, big);
-    else if (!g.transA && g.transB)  e = launch_bf16<false, true>(stream, p, grid, vec, big);
-    else if (g.transA && !g.transB)  e = launch_bf16<true, false>(stream, p, grid, vec, big);
-    else                             e = launch_bf16<true, true>(stream, p, grid, vec, big);
-  } else if (vec && pipelined_ok && (g_gemm_variant == 1 || (g_gemm_variant == 0 && !g.small_footprint))) {
+    if (!g.transA && !g.transB)      e = launch_bf16<false, false>(stream, p, grid, vec, big, pipelined);
+    else if (!g.transA && g.transB)  e = launch_bf16<false, true>(stream, p, grid, vec, big, pipelined);
+    else if (g.transA && !g.transB)  e = launch_bf16<true, false>(stream, p, grid, vec, big, pipelined);
+    else                             e = launch_bf16<true, true>(stream, p, grid, vec, big, pipelined);
+  } else if (pipelined) {
     // A product that shares its CUs with the recurrent kernels keeps to the plain kernel: measured on the
     // 4 x 500 stack, the pipelined kernel beside them finishes its products sooner but slows every recurrent
     // step (6.04 / 9.37 us against 5.89 / 9.02 us), and the step chain is what bounds the pass.
