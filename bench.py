@@ -497,6 +497,32 @@ def main():
                         "peak with 2*B*H*4H FLOP per step and direction; a pass over the T steps is cut "
                         "into several launches (steps_per_launch)"}
 
+    # The same recurrent kernels with nothing beside them: two calls with the products in serial order on one
+    # stream (outside the timed region), for the step time the kernels reach alone.
+    if args.engine in (0, 1) and train is None and not args.one_stream and args.overlap_mode is None:
+        rl.rlstm_set_overlap_mode(0)
+        try:
+            step()
+            torch.cuda.synchronize()
+            rl.rlstm_profile_read()
+            rl.rlstm_profile_enable(True)
+            step()
+            torch.cuda.synchronize()
+            rl.rlstm_profile_enable(False)
+            alone = {}
+            for kind, layer, ndir, ms, nsteps, flop in rl.rlstm_profile_read(1 << 16):
+                if kind in (1, 2):
+                    a = alone.setdefault(kind, [0.0, 0])
+                    a[0] += ms; a[1] += nsteps
+            for e in kernels:
+                for kind, nm in ((1, "recurrent_forward"), (2, "recurrent_backward")):
+                    if e["kernel"] == nm and kind in alone and alone[kind][1]:
+                        e["step_us_alone"] = 1e3 * alone[kind][0] / alone[kind][1]
+            if "step_us_alone" in dom:
+                roofline["step_us_alone"] = dom["step_us_alone"]
+        finally:
+            rl.rlstm_set_overlap_mode(-1)
+
     # Floor of the step chain: the bare exchange of one hop (store, acknowledge, flag, poll, load; no
     # arithmetic) timed live at the same group shape.  Forward: one hop per step (h_t); backward: two
     # (d a_t, then the partial tiles, which the kernel sends as tagged words; timed here with flags).
