@@ -253,6 +253,25 @@ int stack_forward(const rblstm_desc* d, const float* x, const float* const* para
   return RLSTM_OK;
 }
 
+// dR += h0^T dz(first processed valid frame of each sequence).  Direction +1 starts every sequence at frame 0
+// (a sequence without frames has dz = 0 there), so the term is one small product accumulated into dR; direction -1
+// starts each sequence at its own last frame and keeps the gathering kernel.
+int h0_term(hipStream_t st, bool persistent, int operand_dtype, int T, int B, int H, int direction, const float* h0,
+            const float* dz, const int32_t* seq_lens, float* dR) {
+  int resident_err = 0;
+  if (persistent && direction > 0) {
+    GemmCall g;
+    g.transA = true;
+    g.M = H; g.N = 4 * H; g.K = B;
+    g.A = h0; g.lda = H; g.B = dz; g.ldb = 4 * H; g.C = dR; g.ldc = 4 * H; g.accumulate = true;
+    g.operand_dtype = operand_dtype;
+    RLSTM_TRY(gemm(st, g));
+    return RLSTM_OK;
+  }
+  RLSTM_TRY(add_h0_outer(st, T, B, H, direction, h0, dz, seq_lens, dR));
+  return RLSTM_OK;
+}
+
 // Backward half of a training pass over the stack: consumes the reserve a forward pass left.
 int stack_backward(const rblstm_desc* d, const float* x, const float* const* params, const int32_t* seq_lens,
                    const float* dy_top, const float* y_top, float* const* grads, float* dx, float* res, char* ws,
@@ -839,7 +858,8 @@ int lstm_stream_fwd_bwd(const rlstm_stream_desc* d, const float* x, const float*
       rc = weight_grads(st, l, Tc, B, dl, H, 1, xin, dl, yl, H, base + lay.zg, grads[3 * l + 0], grads[3 * l + 1], skws,
                         lay.splitk_floats, !persistent, d->operand_dtype, false, s > 0);
       if (rc != RLSTM_OK) return rc;
-      RLSTM_TRY(add_h0_outer(st, Tc, B, H, 1, h0, base + lay.zg, slens, grads[3 * l + 1]));
+      rc = h0_term(st, persistent, d->operand_dtype, Tc, B, H, 1, h0, base + lay.zg, slens, grads[3 * l + 1]);
+      if (rc != RLSTM_OK) return rc;
       float* dxl = (l == 0) ? (dx ? dx + (size_t)s * tb * D : nullptr) : dybuf[l & 1];
       if (dxl) {
         GemmCall g;
@@ -987,7 +1007,10 @@ int lstm_bwd(const rlstm_desc* d, const float* x, const float* W, const float* R
   rc = weight_grads(st, 0, T, B, D, H, d->direction, x, ldx, y, ldy, zg, dW, dR, skws, skfloats, !persistent, d->operand_dtype,
                     false);
   if (rc != RLSTM_OK) return rc;
-  if (h0) RLSTM_TRY(add_h0_outer(st, T, B, H, d->direction, h0, zg, seq_lens, dR));
+  if (h0) {
+    rc = h0_term(st, persistent, d->operand_dtype, T, B, H, d->direction, h0, zg, seq_lens, dR);
+    if (rc != RLSTM_OK) return rc;
+  }
   if (dx) {
     GemmCall g;
     g.transB = true;
