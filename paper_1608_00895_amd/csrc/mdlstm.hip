@@ -203,6 +203,13 @@ __global__ __launch_bounds__(64 * kTiles * HT) void mdlstm_fwd_kernel(MdParams p
     return;
   }
 
+  // this lane's A operands of every MFMA of a step: they do not change from diagonal to diagonal
+  float ra[KS][5];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+    for (int g = 0; g < 5; ++g) ra[ks][g] = Rs[(4 * ks + lq) * LDR + g * HP + jm];
+
   for (int s = s_lo; s <= s_hi; ++s) {
     const float* hprev = hb + ((s + 1) & 1) * (kBand + 1) * LDH;
     const float* cprev = cb + ((s + 1) & 1) * (kBand + 1) * LDH;
@@ -223,7 +230,7 @@ __global__ __launch_bounds__(64 * kTiles * HT) void mdlstm_fwd_kernel(MdParams p
       const float hv = k < HP ? brow[k] : brow[LDH + k - HP];
 #pragma unroll
       for (int g = 0; g < 5; ++g)
-        acc[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(Rs[k * LDR + g * HP + jm], hv, acc[g], 0, 0, 0);
+        acc[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(ra[ks][g], hv, acc[g], 0, 0, 0);
     }
 
     const int q = s - r;
@@ -390,6 +397,11 @@ __global__ __launch_bounds__(64 * kTiles * HT) void mdlstm_bwd_kernel(MdParams p
     return;
   }
 
+  // this lane's A operands of every MFMA of a step: they do not change from diagonal to diagonal
+  float rt[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) rt[ks] = RT[(4 * ks + lq) * LDT + jm];
+
   for (int s = s_hi; s >= s_lo; --s) {
     const float* dcu_prev = dcu + ((s + 1) & 1) * (kBand + 1) * LDH;
     const float* dcv_prev = dcv + ((s + 1) & 1) * (kBand + 1) * LDH;
@@ -401,13 +413,13 @@ __global__ __launch_bounds__(64 * kTiles * HT) void mdlstm_bwd_kernel(MdParams p
     // row r+1, the one to the right in row r); two accumulators so that consecutive MFMAs do not wait for each other
     floatx4 acc0 = floatx4{0.f, 0.f, 0.f, 0.f}, acc1 = floatx4{0.f, 0.f, 0.f, 0.f};
     const float* brow = dzb + lr * LDZ;
-#pragma unroll 8
+#pragma unroll
     for (int ks = 0; ks < KS; ks += 2) {
       const int k0 = 4 * ks + lq, k1 = k0 + 4;
       const float b0 = k0 < NG ? brow[LDZ + k0] : brow[k0 - NG];
       const float b1 = k1 < NG ? brow[LDZ + k1] : brow[k1 - NG];
-      acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(RT[k0 * LDT + jm], b0, acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(RT[k1 * LDT + jm], b1, acc1, 0, 0, 0);
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(rt[ks], b0, acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(rt[ks + 1], b1, acc1, 0, 0, 0);
     }
     const floatx4 acc = acc0 + acc1;
     __syncthreads();     // every wavefront has read the d a rows of diagonal s+1
