@@ -138,7 +138,7 @@ def bench_config5(args):
     roofline = {"kernel": dom["kernel"], "bound": "mfma", "achieved": dom["tflops"], "peak": PEAK_FP32_MFMA_TFLOPS,
                 "unit": "TFLOP/s", "frac": dom["tflops"] / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
                 "avg_launch_ms": dom["avg_ms"],
-                "note": "one workgroup per (scan direction, image): 32 of the 256 CUs work, and the chain of "
+                "note": "one two-wavefront workgroup per (scan direction, image, band of 16 rows): 128 of the 256 CUs work, and the chain of "
                         "anti-diagonals is serial; priced against the whole chip's fp32 MFMA peak with "
                         "2 * 2H * 5H FLOP per valid pixel and direction"}
     out = {"metric": "MDLSTM train pixels/sec (fwd+bwd), 4 scan directions", "value": wl.pixels / (ms_per_step * 1e-3),
