@@ -506,12 +506,12 @@ static size_t md_pixels(const rmdlstm_desc* d) { return (size_t)d->Hh * d->Ww * 
 static bool md_fused(const rmdlstm_desc* d) { return d->D <= 32; }
 static int md_stride(const rmdlstm_desc* d) { return (int)align_up((size_t)2 * d->H + (md_fused(d) ? d->D : 0), 4); }
 static size_t md_dir_floats(const rmdlstm_desc* d) { return align_up(md_pixels(d) * (6 * d->H + md_stride(d)), 64); }
-static int md_grad_rows(const rmdlstm_desc* d) { return md_fused(d) ? 2 * d->H + d->D : (d->D > d->H ? d->D : d->H); }
+static int md_grad_rows(const rmdlstm_desc* d) { return md_fused(d) ? md_stride(d) : (d->D > d->H ? d->D : d->H); }
 static size_t md_splitk_floats(const rmdlstm_desc* d) {
-  // the weight gradients are tiny matrices summed over every pixel: room for 256 partial results
-  return align_up((size_t)256 * md_grad_rows(d) * 5 * d->H, 64);
+  // the weight gradients are tiny matrices summed over every pixel: room for 512 partial results
+  return align_up((size_t)512 * md_grad_rows(d) * 5 * d->H, 64);
 }
-static size_t md_stacked_floats(const rmdlstm_desc* d) { return align_up((size_t)4 * (2 * d->H + d->D) * 5 * d->H, 64); }
+static size_t md_stacked_floats(const rmdlstm_desc* d) { return align_up((size_t)4 * md_stride(d) * 5 * d->H, 64); }
 static size_t md_dbpart_floats(const rmdlstm_desc* d) {
   MdShape s{d->Hh, d->Ww, d->B, d->H, 0};
   return align_up(mdlstm_dbpart_floats(s), 64);
@@ -591,7 +591,7 @@ int mdlstm_bwd(const rmdlstm_desc* d, const float* x, const float* const* params
     RLSTM_TRY(mdlstm_backward(st, s, dirs, widths, dy, skws + skfloats, db, halo, reinterpret_cast<unsigned*>(ws)));
   }
   float* stacked = skws + skfloats + md_dbpart_floats(d);
-  const size_t stacked_one = (size_t)(2 * H + D) * 5 * H;
+  const size_t stacked_one = (size_t)s.S * 5 * H;
   for (int k = 0; k < 4; ++k) {
     GemmCall g;
     g.transA = true;
@@ -599,8 +599,10 @@ int mdlstm_bwd(const rmdlstm_desc* d, const float* x, const float* const* params
     g.B = dirs[k].zg; g.ldb = 5 * H; g.ldc = 5 * H;
     g.splitk_ws = skws; g.splitk_floats = skfloats;
     if (md_fused(d)) {
-      // [h_up | h_left | x]^T dA: d R_u, d R_v and d W stacked
-      g.M = 2 * H + D; g.A = dirs[k].hc; g.lda = s.S; g.C = stacked + (size_t)k * stacked_one;
+      // [h_up | h_left | x]^T dA: d R_u, d R_v and d W stacked.  All S columns of the array take part (S is the
+      // row stride, a multiple of 4, which keeps the product on the float4 path); the rows of the result that
+      // belong to the padding columns are never read.
+      g.M = s.S; g.A = dirs[k].hc; g.lda = s.S; g.C = stacked + (size_t)k * stacked_one;
       ProfScope ps(st, 5, 0, 1, 0, gemm_flop(g));
       RLSTM_TRY(gemm(st, g));
     } else {

@@ -641,6 +641,32 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
   *dst = s;
 }
 
+// Many slices of a small matrix (weight gradients summed over hundreds of thousands of rows): 64 outputs per
+// workgroup, the slices dealt to 4 groups of threads in contiguous runs, the four sums added in group order.
+// The order of additions depends only on the slice count, so results stay bit-reproducible.
+__global__ __launch_bounds__(256) void splitk_reduce4_kernel(const float* __restrict__ partial, int slices,
+                                                              int M, int N, float* __restrict__ C, int ldc,
+                                                              const float* __restrict__ bias, int accumulate) {
+  __shared__ float part[4][64];
+  const int o = threadIdx.x & 63, grp = threadIdx.x >> 6;
+  const size_t idx = (size_t)blockIdx.x * 64 + o;
+  const size_t mn = (size_t)M * N;
+  const int per = (slices + 3) / 4;
+  const int z0 = grp * per, z1 = min(slices, z0 + per);
+  float s = 0.f;
+  if (idx < mn)
+    for (int z = z0; z < z1; ++z) s += partial[(size_t)z * mn + idx];
+  part[grp][o] = s;
+  __syncthreads();
+  if (grp != 0 || idx >= mn) return;
+  s = ((part[0][o] + part[1][o]) + part[2][o]) + part[3][o];
+  const int m = (int)(idx / N), n = (int)(idx % N);
+  if (bias) s += bias[n];
+  float* dst = C + (size_t)m * ldc + n;
+  if (accumulate) s += *dst;
+  *dst = s;
+}
+
 // Plain product for the stepwise engine: one thread per element of C.
 __global__ __launch_bounds__(256) void gemm_naive_kernel(GemmP p, int transA, int transB, int round_bf16) {
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -945,7 +971,7 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
     const size_t per = (size_t)g.M * g.N;
     const size_t max_by_ws = g.splitk_floats / per;
     if ((size_t)slices > max_by_ws) slices = (int)max_by_ws;
-    if (slices > 256) slices = 256;
+    if (slices > 512) slices = 512;
     if (slices < 1) slices = 1;
   }
   if (slices > 1) {
@@ -988,8 +1014,12 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
   if (e != hipSuccess) return e;
   if (slices > 1) {
     const size_t total = (size_t)g.M * g.N;
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
-                       g.splitk_ws, slices, g.M, g.N, g.C, g.ldc, g.bias, g.accumulate ? 1 : 0);
+    if (slices >= 64 && total <= (size_t)256 * 1024)
+      hipLaunchKernelGGL(splitk_reduce4_kernel, dim3((unsigned)((total + 63) / 64)), dim3(256), 0, stream,
+                         g.splitk_ws, slices, g.M, g.N, g.C, g.ldc, g.bias, g.accumulate ? 1 : 0);
+    else
+      hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+                         g.splitk_ws, slices, g.M, g.N, g.C, g.ldc, g.bias, g.accumulate ? 1 : 0);
     e = hipGetLastError();
   }
   return e;
