@@ -550,7 +550,10 @@ int mdlstm_fwd(const rmdlstm_desc* d, const float* x, const float* const* params
   const int P = (int)md_pixels(d), H = d->H;
   MdDir dirs[4];
   md_dirs(d, static_cast<float*>(reserve), params, dirs);
-  for (int k = 0; k < 4; ++k) {
+  // One input value per pixel (grayscale images): b + x W is an outer product, formed inside the scan kernel
+  // instead of being written to and read back from HBM; the kernel also leaves x next to [h_up | h_left].
+  const bool xin = d->D == 1;
+  for (int k = 0; k < 4 && !xin; ++k) {
     GemmCall g;
     g.M = P; g.N = 5 * H; g.K = d->D;
     g.A = x; g.lda = d->D; g.B = params[4 * k + 0]; g.ldb = 5 * H; g.C = dirs[k].zg; g.ldc = 5 * H;
@@ -559,13 +562,15 @@ int mdlstm_fwd(const rmdlstm_desc* d, const float* x, const float* const* params
     RLSTM_TRY(gemm(st, g));
   }
   MdShape s{d->Hh, d->Ww, d->B, H, md_stride(d)};
-  if (md_fused(d)) RLSTM_TRY(mdlstm_copy_x(st, s, dirs, x, d->D));
+  if (md_fused(d) && !xin) RLSTM_TRY(mdlstm_copy_x(st, s, dirs, x, d->D));
+  const float* W1[4]; const float* b1[4];
+  for (int k = 0; k < 4; ++k) { W1[k] = params[4 * k + 0]; b1[k] = params[4 * k + 3]; }
   const int diag = d->Hh + d->Ww - 1;
   char* ws = static_cast<char*>(workspace);
   float* wsf = reinterpret_cast<float*>(ws + kFlagBytes);
   unsigned long long* halo = reinterpret_cast<unsigned long long*>(wsf + md_splitk_floats(d) + md_dbpart_floats(d) + md_stacked_floats(d));
   ProfScope ps(st, 1, 0, 4, diag, 2.0 * P * 2 * H * 5 * H * 4);
-  RLSTM_TRY(mdlstm_forward(st, s, dirs, widths, y, halo, reinterpret_cast<unsigned*>(ws)));
+  RLSTM_TRY(mdlstm_forward(st, s, dirs, widths, y, halo, reinterpret_cast<unsigned*>(ws), xin ? x : nullptr, W1, b1));
   return RLSTM_OK;
 }
 

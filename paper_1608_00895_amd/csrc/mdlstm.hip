@@ -53,6 +53,9 @@ struct MdParams {
   unsigned long long* halo;   // rows handed from a band to its neighbour: (value, diagonal + 1) words
   unsigned* err;           // raised when a bounded wait expired
   const int32_t* widths;   // [B]
+  const float* x;          // forward with a one-value input (XIN): [P] pixels
+  const float* W[4];       //   [1, 5H] input weights per direction
+  const float* bias[4];    //   [5H]
   int Hh, Ww, B, H, S, NB;
 };
 
@@ -113,7 +116,10 @@ __device__ __forceinline__ bool md_wait_word(const unsigned long long* q, unsign
 
 // VEC: H is a multiple of 4, so every group of four units starts 16-byte aligned in all tensors.
 // Workgroup = (band, direction, image); 2 row tiles x HT unit halves, one wavefront each.
-template <int HT, bool VEC>
+// XIN: the input has one value per pixel (grayscale images): the input part b + x W of the pre-activation is formed
+// here from x and this lane's 20 weights and biases instead of being read from zg, and x is written next to
+// [h_up | h_left] for the weight-gradient product.
+template <int HT, bool VEC, bool XIN>
 __global__ __launch_bounds__(64 * kTiles * HT) void mdlstm_fwd_kernel(MdParams p) {
   constexpr int NTH = 64 * kTiles * HT;
   constexpr int HP = 16 * HT;          // padded units
@@ -181,13 +187,28 @@ __global__ __launch_bounds__(64 * kTiles * HT) void mdlstm_fwd_kernel(MdParams p
 
   // input part of the lane's row and four units on diagonal s
   floatx4 zr[5];
+  floatx4 wx[5], bx[5];                // XIN: weights and biases of this lane's four units, per gate
+  float xcur = 0.f;                    // XIN: x of the pixel whose input part zr holds
+  if (XIN) {
+#pragma unroll
+    for (int g = 0; g < 5; ++g)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        wx[g][i] = i < nv ? p.W[d][g * H + j0 + i] : 0.f;
+        bx[g][i] = i < nv ? p.bias[d][g * H + j0 + i] : 0.f;
+      }
+  }
   auto prefetch = [&](int s) {
     const int q = s - r;
     const bool ok = lr < rows_here && q >= 0 && q < wn && s <= s_hi && nv > 0;
     const size_t pix = ok ? md_pixel(p, du, dv, wn, n, r, q) : 0;
+    if (XIN) {
+      xcur = ok ? p.x[pix] : 0.f;       // used after the step's MFMAs, so the load has a step's time to arrive
+    } else {
 #pragma unroll
-    for (int g = 0; g < 5; ++g)
-      zr[g] = ok ? ld4<VEC>(zgd + pix * 5 * H + g * H + j0, nv) : floatx4{0.f, 0.f, 0.f, 0.f};
+      for (int g = 0; g < 5; ++g)
+        zr[g] = ok ? ld4<VEC>(zgd + pix * 5 * H + g * H + j0, nv) : floatx4{0.f, 0.f, 0.f, 0.f};
+    }
   };
   prefetch(s_lo);
   int fail = 0;
@@ -237,6 +258,10 @@ __global__ __launch_bounds__(64 * kTiles * HT) void mdlstm_fwd_kernel(MdParams p
     const bool ok = lr < rows_here && q >= 0 && q < wn && nv > 0;
     const size_t pix = ok ? md_pixel(p, du, dv, wn, n, r, q) : 0;
     floatx4 gi, gfu, gfv, go, gg, ct, ht, h_up, h_left;
+    if (XIN) {
+#pragma unroll
+      for (int g = 0; g < 5; ++g) zr[g] = bx[g] + xcur * wx[g];
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int j = j0 + i;
@@ -271,6 +296,7 @@ __global__ __launch_bounds__(64 * kTiles * HT) void mdlstm_fwd_kernel(MdParams p
       st4<VEC>(p.y + pix * 4 * H + d * H + j0, ht, nv);
       st4<VEC>(hcd + pix * p.S + j0, h_up, nv);
       st4<VEC>(hcd + pix * p.S + H + j0, h_left, nv);
+      if (XIN && j0 == 0) hcd[pix * p.S + 2 * H] = xcur;
     }
     prefetch(s + 1);
   }
@@ -286,6 +312,7 @@ __global__ __launch_bounds__(64 * kTiles * HT) void mdlstm_fwd_kernel(MdParams p
     cd[pix * H + jj] = 0.f;
     hcd[pix * p.S + jj] = 0.f;
     hcd[pix * p.S + H + jj] = 0.f;
+    if (XIN && jj == 0) hcd[pix * p.S + 2 * H] = 0.f;
   }
 }
 
@@ -609,18 +636,28 @@ hipError_t md_clear(hipStream_t stream, const MdShape& s, unsigned long long* ha
 }  // namespace
 
 hipError_t mdlstm_forward(hipStream_t stream, const MdShape& s, const MdDir* dirs, const int32_t* widths, float* y,
-                          unsigned long long* halo, unsigned* err) {
+                          unsigned long long* halo, unsigned* err, const float* x1, const float* const* W1,
+                          const float* const* b1) {
   if (!mdlstm_supported(s)) return hipErrorInvalidValue;
   MdParams p = md_params(s, dirs, widths);
   p.y = y; p.halo = halo; p.err = err;
+  const bool xin = x1 != nullptr;
+  if (xin) {
+    p.x = x1;
+    for (int d = 0; d < 4; ++d) { p.W[d] = W1[d]; p.bias[d] = b1[d]; }
+  }
   hipError_t e = md_clear(stream, s, halo, err, 64);
   if (e != hipSuccess) return e;
   const bool vec = md_vec(s, dirs, y);
   const int grid = 4 * s.B * p.NB;
-  if (s.H <= 16) return vec ? md_launch(mdlstm_fwd_kernel<1, true>, grid, 64 * kTiles, md_lds_fwd(1), stream, p)
-                            : md_launch(mdlstm_fwd_kernel<1, false>, grid, 64 * kTiles, md_lds_fwd(1), stream, p);
-  return vec ? md_launch(mdlstm_fwd_kernel<2, true>, grid, 128 * kTiles, md_lds_fwd(2), stream, p)
-             : md_launch(mdlstm_fwd_kernel<2, false>, grid, 128 * kTiles, md_lds_fwd(2), stream, p);
+#define RLSTM_MD_FWD(HT_, VEC_, XIN_) md_launch(mdlstm_fwd_kernel<HT_, VEC_, XIN_>, grid, 64 * HT_ * kTiles, md_lds_fwd(HT_), stream, p)
+  if (s.H <= 16) {
+    if (xin) return vec ? RLSTM_MD_FWD(1, true, true) : RLSTM_MD_FWD(1, false, true);
+    return vec ? RLSTM_MD_FWD(1, true, false) : RLSTM_MD_FWD(1, false, false);
+  }
+  if (xin) return vec ? RLSTM_MD_FWD(2, true, true) : RLSTM_MD_FWD(2, false, true);
+  return vec ? RLSTM_MD_FWD(2, true, false) : RLSTM_MD_FWD(2, false, false);
+#undef RLSTM_MD_FWD
 }
 
 size_t mdlstm_dbpart_floats(const MdShape& s) { return (size_t)4 * s.B * kMaxBands * 5 * s.H; }

@@ -132,8 +132,11 @@ bool mdlstm_supported(const MdShape& s);
 // dirs[4] in the order (du, dv) = (+,+), (+,-), (-,+), (-,-); y, dy: [P, 4H]
 // halo: mdlstm_halo_words() 64-bit words of scratch (rows handed between bands); err: timeout flag
 size_t mdlstm_halo_words(const MdShape& s);
+// x1 != null: the input has one value per pixel; zg is not read, the input part is formed in the kernel from x1 [P],
+// W1[4] ([1, 5H] each) and b1[4] ([5H]), and x1 is written into column 2H of the hc arrays (S >= 2H + 1)
 hipError_t mdlstm_forward(hipStream_t stream, const MdShape& s, const MdDir* dirs, const int32_t* widths, float* y,
-                          unsigned long long* halo, unsigned* err);
+                          unsigned long long* halo, unsigned* err, const float* x1 = nullptr,
+                          const float* const* W1 = nullptr, const float* const* b1 = nullptr);
 // x into columns [2H, 2H + D) of the four hc arrays (S >= 2H + D)
 hipError_t mdlstm_copy_x(hipStream_t stream, const MdShape& s, const MdDir* dirs, const float* x, int D);
 // rows [0,H), [H,2H), [2H,2H+D) of four stacked [2H + D, 5H] gradients to dRu, dRv, dW
