@@ -2,7 +2,7 @@
 // needs the states of (u-1, v) and (u, v-1) in scan order, so all pixels of one anti-diagonal can
 // be computed together; four scan directions and several images run at once.
 //
-// One workgroup (2 wavefronts per 16 units) per (scan direction, image, band of 32 rows); it walks the
+// One workgroup per (scan direction, image, band of 16 rows); it walks the
 // anti-diagonals on which its band has pixels, at the image's own width, so images of a batch never
 // wait for each other.  A band needs one row of its neighbouring band per diagonal; that dependency
 // runs one way (see "rows handed between the bands" below), so the neighbour runs ahead.  In scan
@@ -10,14 +10,14 @@
 // the pixel of row r on diagonal s has its vertical predecessor in row r-1 and its horizontal
 // predecessor in row r, both on diagonal s-1.  The workgroup keeps h and c of the previous
 // diagonal in LDS, indexed by row (rows without a pixel hold zeros, which is also what a
-// predecessor outside the image contributes), and the recurrent matrices [R_u ; R_v] in LDS for
-// the whole scan.
+// predecessor outside the image contributes); a lane's entries of the recurrent matrices
+// [R_u ; R_v] never change and stay in registers for the whole scan.
 //
-// Forward step: [64 rows x 2H] * [2H x 5H] on the matrix cores (v_mfma_f32_16x16x4_f32; a wavefront
-// owns rows 16w .. 16w+15 and the five gate columns of 16 units, so the five gate pre-activations of
-// a (row, unit) pair end up in one lane and the gating needs no exchange; with 32 units two
-// wavefronts share a SIMD and one's gating overlaps the other's MFMAs), plus the input part
-// X W + b that a whole-image product wrote beforehand, prefetched one diagonal ahead.
+// Forward step: [16 rows x 2H] * [2H x 5H] on the matrix cores (v_mfma_f32_16x16x4_f32), one wavefront
+// per (gate, 16 units): 16 MFMAs and one nonlinearity on four units per lane; the output-gate wavefronts
+// collect the other activated gates from LDS and do the cell update.  The input part X W + b comes from
+// a whole-image product, prefetched one diagonal ahead, or, for one input value per pixel, is formed
+// in the kernel.
 // Backward step (diagonals in reverse): d h = [d a(r+1) | d a(r)] of diagonal s+1 times
 // [R_u ; R_v]^T, K = 10H, same row / lane assignment; the gate derivatives follow in registers.
 // d a overwrites the gates in place; [h_up | h_left] of every pixel is kept from the forward pass
@@ -116,42 +116,50 @@ __device__ __forceinline__ bool md_wait_word(const unsigned long long* q, unsign
 
 // VEC: H is a multiple of 4, so every group of four units starts 16-byte aligned in all tensors.
 // Workgroup = (band, direction, image); 2 row tiles x HT unit halves, one wavefront each.
+// Forward scan.  One wavefront per (gate, 16 units): 5 * HT wavefronts.  A step's product
+// a^T = [R_u ; R_v]^T [h_up | h_left]^T is then 16 MFMAs per wavefront instead of 80, and a lane applies one
+// nonlinearity to its four units instead of five; the wavefronts of the output gate pick up the other four
+// activated gates from LDS (same lane, one 16-byte read each) and do the cell update.  The lane's 16 matrix
+// operands (its column of [R_u ; R_v] for its gate and unit) never change and stay in registers.
 // XIN: the input has one value per pixel (grayscale images): the input part b + x W of the pre-activation is formed
-// here from x and this lane's 20 weights and biases instead of being read from zg, and x is written next to
+// here from x and this lane's weights and biases instead of being read from zg, and x is written next to
 // [h_up | h_left] for the weight-gradient product.
 template <int HT, bool VEC, bool XIN>
-__global__ __launch_bounds__(64 * kTiles * HT) void mdlstm_fwd_kernel(MdParams p) {
-  constexpr int NTH = 64 * kTiles * HT;
+__global__ __launch_bounds__(64 * 5 * HT) void mdlstm_fwd_kernel(MdParams p) {
+  static_assert(kTiles == 1, "one 16-row tile per band");
+  constexpr int NTH = 64 * 5 * HT;
   constexpr int HP = 16 * HT;          // padded units
-  constexpr int NG = 5 * HP;           // padded pre-activation width
   constexpr int KS = 2 * HP / 4;       // MFMA k-steps
-  constexpr int LDR = NG + 8;          // LDS row stride of [R_u ; R_v] (rows 4 apart fall into different banks)
   constexpr int LDH = HP + 1;
   constexpr int HW = 2 * HP;           // words of a handed row: h | c
   extern __shared__ __align__(16) float lds[];
-  float* Rs = lds;                                   // [2HP][LDR]
-  float* hb = Rs + 2 * HP * LDR;                     // [2][kBand + 1][LDH]; entry 0 is the row above the band
+  float* hb = lds;                                   // [2][kBand + 1][LDH]; entry 0 is the row above the band
   float* cb = hb + 2 * (kBand + 1) * LDH;            // same for c
+  floatx4* gact = reinterpret_cast<floatx4*>(cb + 2 * (kBand + 1) * LDH);   // [i, f_u, f_v, g][HT][64 lanes]
 
   const int dn = blockIdx.x % (4 * p.B), band = blockIdx.x / (4 * p.B);   // bands above come first in the grid
   const int d = dn & 3, n = dn >> 2;
   const int du = (d & 2) ? -1 : 1, dv = (d & 1) ? -1 : 1;
   const int H = p.H, Hh = p.Hh;
   const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, lq = lane >> 4;
-  const int lr = 16 * ((tid >> 6) % kTiles) + l16;  // row inside the band
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = wave / HT, ht = wave % HT;     // gate (i, f_u, f_v, o, g) and group of 16 units of this wavefront
+  const int lr = l16;                          // row inside the band
   const int r = kBand * band + lr;             // row of this lane
-  const int jm = 16 * (tid / (64 * kTiles)) + l16;        // unit whose columns this lane feeds to the MFMA (A operand row)
-  const int j0 = 16 * (tid / (64 * kTiles)) + 4 * lq;     // first of the four units this lane gates (accumulator rows)
+  const int jm = 16 * ht + l16;                // unit whose column this lane feeds to the MFMA (A operand row)
+  const int j0 = 16 * ht + 4 * lq;             // first of the four units this lane holds (accumulator rows)
   const int nv = min(max(H - j0, 0), 4);       // how many of them exist
   const int wn = min(max(p.widths[n], 0), p.Ww);
   const int rows_here = min(Hh - kBand * band, kBand);
+  const int slot = g < 3 ? g : 3;              // where this gate's activations go in gact (the output gate has none)
 
-  for (int idx = tid; idx < 2 * HP * NG; idx += NTH) {
-    const int k = idx / NG, col = idx % NG;
-    const int g = col / HP, jj = col % HP, kk = k % HP;
-    float v = 0.f;
-    if (kk < H && jj < H) v = (k < HP ? p.Ru[d] : p.Rv[d])[(size_t)kk * 5 * H + g * H + jj];
-    Rs[k * LDR + col] = v;
+  // A[m][k] = [R_u ; R_v][k][gate column of unit m]
+  float ra[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    const int k = 4 * ks + lq, kk = k % HP;
+    const float* R = k < HP ? p.Ru[d] : p.Rv[d];
+    ra[ks] = (kk < H && jm < H) ? R[(size_t)kk * 5 * H + g * H + jm] : 0.f;
   }
   for (int idx = tid; idx < 2 * (kBand + 1) * LDH; idx += NTH) { hb[idx] = 0.f; cb[idx] = 0.f; }
   __syncthreads();
@@ -185,30 +193,23 @@ __global__ __launch_bounds__(64 * kTiles * HT) void mdlstm_fwd_kernel(MdParams p
     return good;
   };
 
-  // input part of the lane's row and four units on diagonal s
-  floatx4 zr[5];
-  floatx4 wx[5], bx[5];                // XIN: weights and biases of this lane's four units, per gate
-  float xcur = 0.f;                    // XIN: x of the pixel whose input part zr holds
+  // input part of this lane's gate, row and four units on diagonal s
+  floatx4 zr = floatx4{0.f, 0.f, 0.f, 0.f};
+  floatx4 wx = zr, bx = zr;            // XIN: weights and biases of this lane's four units for its gate
+  float xcur = 0.f;                    // XIN: x of the pixel of the diagonal at hand
   if (XIN) {
 #pragma unroll
-    for (int g = 0; g < 5; ++g)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        wx[g][i] = i < nv ? p.W[d][g * H + j0 + i] : 0.f;
-        bx[g][i] = i < nv ? p.bias[d][g * H + j0 + i] : 0.f;
-      }
+    for (int i = 0; i < 4; ++i) {
+      wx[i] = i < nv ? p.W[d][g * H + j0 + i] : 0.f;
+      bx[i] = i < nv ? p.bias[d][g * H + j0 + i] : 0.f;
+    }
   }
   auto prefetch = [&](int s) {
     const int q = s - r;
     const bool ok = lr < rows_here && q >= 0 && q < wn && s <= s_hi && nv > 0;
     const size_t pix = ok ? md_pixel(p, du, dv, wn, n, r, q) : 0;
-    if (XIN) {
-      xcur = ok ? p.x[pix] : 0.f;       // used after the step's MFMAs, so the load has a step's time to arrive
-    } else {
-#pragma unroll
-      for (int g = 0; g < 5; ++g)
-        zr[g] = ok ? ld4<VEC>(zgd + pix * 5 * H + g * H + j0, nv) : floatx4{0.f, 0.f, 0.f, 0.f};
-    }
+    if (XIN) xcur = ok ? p.x[pix] : 0.f;       // used after the step's MFMAs, so the load has a step's time to arrive
+    else zr = ok ? ld4<VEC>(zgd + pix * 5 * H + g * H + j0, nv) : floatx4{0.f, 0.f, 0.f, 0.f};
   };
   prefetch(s_lo);
   int fail = 0;
@@ -224,13 +225,6 @@ __global__ __launch_bounds__(64 * kTiles * HT) void mdlstm_fwd_kernel(MdParams p
     return;
   }
 
-  // this lane's A operands of every MFMA of a step: they do not change from diagonal to diagonal
-  float ra[KS][5];
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-    for (int g = 0; g < 5; ++g) ra[ks][g] = Rs[(4 * ks + lq) * LDR + g * HP + jm];
-
   for (int s = s_lo; s <= s_hi; ++s) {
     const float* hprev = hb + ((s + 1) & 1) * (kBand + 1) * LDH;
     const float* cprev = cb + ((s + 1) & 1) * (kBand + 1) * LDH;
@@ -238,50 +232,51 @@ __global__ __launch_bounds__(64 * kTiles * HT) void mdlstm_fwd_kernel(MdParams p
     float* ccur = cb + (s & 1) * (kBand + 1) * LDH;
     halo_issue(s);                     // arrives while the MFMAs run
 
-    // a^T = [R_u ; R_v]^T [h_up | h_left]^T: accumulator g holds gate g of units j0 .. j0+3 (its 4 rows) for the
-    // image row of this lane (its column).  A[m][k] = R[k][gate column of unit jm]; B[k][n]: k < HP: h of the
-    // row above (entry index = row), else h of the same row (entry index row + 1)
-    floatx4 acc[5];
-#pragma unroll
-    for (int g = 0; g < 5; ++g) acc[g] = floatx4{0.f, 0.f, 0.f, 0.f};
+    // accumulator rows: units j0 .. j0+3 of this gate; column: the image row of this lane.
+    // B[k][n]: k < HP: h of the row above (entry index = row), else h of the same row (entry index row + 1)
+    floatx4 acc0 = floatx4{0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
     const float* brow = hprev + lr * LDH;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const int k = 4 * ks + lq;
-      const float hv = k < HP ? brow[k] : brow[LDH + k - HP];
-#pragma unroll
-      for (int g = 0; g < 5; ++g)
-        acc[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(ra[ks][g], hv, acc[g], 0, 0, 0);
+    for (int ks = 0; ks < KS; ks += 2) {
+      const int k0 = 4 * ks + lq, k1 = k0 + 4;
+      const float h0 = k0 < HP ? brow[k0] : brow[LDH + k0 - HP];
+      const float h1 = k1 < HP ? brow[k1] : brow[LDH + k1 - HP];
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(ra[ks], h0, acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(ra[ks + 1], h1, acc1, 0, 0, 0);
     }
 
     const int q = s - r;
     const bool ok = lr < rows_here && q >= 0 && q < wn && nv > 0;
     const size_t pix = ok ? md_pixel(p, du, dv, wn, n, r, q) : 0;
-    floatx4 gi, gfu, gfv, go, gg, ct, ht, h_up, h_left;
-    if (XIN) {
-#pragma unroll
-      for (int g = 0; g < 5; ++g) zr[g] = bx[g] + xcur * wx[g];
-    }
+    if (XIN) zr = bx + xcur * wx;
+    floatx4 act;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int j = j0 + i;
-      gi[i] = md_sigmoid(acc[0][i] + zr[0][i]);
-      gfu[i] = md_sigmoid(acc[1][i] + zr[1][i]);
-      gfv[i] = md_sigmoid(acc[2][i] + zr[2][i]);
-      go[i] = md_sigmoid(acc[3][i] + zr[3][i]);
-      gg[i] = md_tanh(acc[4][i] + zr[4][i]);
-      h_up[i] = hprev[lr * LDH + j]; h_left[i] = hprev[(lr + 1) * LDH + j];
-      const float c_up = cprev[lr * LDH + j], c_left = cprev[(lr + 1) * LDH + j];
-      ct[i] = gfu[i] * c_up + gfv[i] * c_left + gi[i] * gg[i];
-      ht[i] = go[i] * md_tanh(ct[i]);
-      const bool oki = ok && i < nv;
-      hcur[(lr + 1) * LDH + j] = oki ? ht[i] : 0.f;
-      ccur[(lr + 1) * LDH + j] = oki ? ct[i] : 0.f;
+      const float a = acc0[i] + acc1[i] + zr[i];
+      act[i] = g == 4 ? md_tanh(a) : md_sigmoid(a);
     }
-    // the row above on this diagonal, for the next step
+    if (g != 3) gact[(slot * HT + ht) * 64 + lane] = act;
+    // the row above on this diagonal, for the next step (entry 0 of the buffers nobody reads in this step)
     fail = halo_take(s, hcur, ccur) ? 0 : 1;
-    // the next diagonal only needs the LDS rows: the stores to HBM and the next prefetch follow the barrier, so
-    // that one wavefront's memory instructions overlap the MFMAs of the wavefront it shares the SIMD with
+    __syncthreads();
+
+    floatx4 ct = floatx4{0.f, 0.f, 0.f, 0.f}, hn = ct, h_up = ct, h_left = ct;
+    if (g == 3) {
+      const floatx4 gi = gact[(0 * HT + ht) * 64 + lane], gfu = gact[(1 * HT + ht) * 64 + lane];
+      const floatx4 gfv = gact[(2 * HT + ht) * 64 + lane], gg = gact[(3 * HT + ht) * 64 + lane];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int j = j0 + i;
+        h_up[i] = hprev[lr * LDH + j]; h_left[i] = hprev[(lr + 1) * LDH + j];
+        const float c_up = cprev[lr * LDH + j], c_left = cprev[(lr + 1) * LDH + j];
+        ct[i] = gfu[i] * c_up + gfv[i] * c_left + gi[i] * gg[i];
+        hn[i] = act[i] * md_tanh(ct[i]);
+        const bool oki = ok && i < nv;
+        hcur[(lr + 1) * LDH + j] = oki ? hn[i] : 0.f;
+        ccur[(lr + 1) * LDH + j] = oki ? ct[i] : 0.f;
+      }
+    }
+    // the next diagonal only needs the LDS rows: the stores to HBM and the next prefetch follow the barrier
     if (__syncthreads_or(fail)) {
       if (tid == 0) __hip_atomic_store(p.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       return;
@@ -289,14 +284,14 @@ __global__ __launch_bounds__(64 * kTiles * HT) void mdlstm_fwd_kernel(MdParams p
     if (gives && hands)                // last row of the band to the band below
       md_st_word(halo_out + (size_t)s * 64 + tid, tid < HP ? hcur[kBand * LDH + tid] : ccur[kBand * LDH + tid - HP], s);
     if (ok) {
-      float* zrow = zgd + pix * 5 * H + j0;
-      st4<VEC>(zrow, gi, nv); st4<VEC>(zrow + H, gfu, nv); st4<VEC>(zrow + 2 * H, gfv, nv);
-      st4<VEC>(zrow + 3 * H, go, nv); st4<VEC>(zrow + 4 * H, gg, nv);
-      st4<VEC>(cd + pix * H + j0, ct, nv);
-      st4<VEC>(p.y + pix * 4 * H + d * H + j0, ht, nv);
-      st4<VEC>(hcd + pix * p.S + j0, h_up, nv);
-      st4<VEC>(hcd + pix * p.S + H + j0, h_left, nv);
-      if (XIN && j0 == 0) hcd[pix * p.S + 2 * H] = xcur;
+      st4<VEC>(zgd + pix * 5 * H + g * H + j0, act, nv);
+      if (g == 3) {
+        st4<VEC>(cd + pix * H + j0, ct, nv);
+        st4<VEC>(p.y + pix * 4 * H + d * H + j0, hn, nv);
+        st4<VEC>(hcd + pix * p.S + j0, h_up, nv);
+        st4<VEC>(hcd + pix * p.S + H + j0, h_left, nv);
+        if (XIN && j0 == 0) hcd[pix * p.S + 2 * H] = xcur;
+      }
     }
     prefetch(s + 1);
   }
@@ -315,6 +310,7 @@ __global__ __launch_bounds__(64 * kTiles * HT) void mdlstm_fwd_kernel(MdParams p
     if (XIN && jj == 0) hcd[pix * p.S + 2 * H] = 0.f;
   }
 }
+
 
 template <int HT, bool VEC>
 __global__ __launch_bounds__(64 * kTiles * HT) void mdlstm_bwd_kernel(MdParams p) {
@@ -577,8 +573,8 @@ __global__ __launch_bounds__(256) void mdlstm_scatter_kernel(MdScatterParams p) 
 }
 
 size_t md_lds_fwd(int HT) {
-  const int HP = 16 * HT, NG = 5 * HP;
-  return ((size_t)2 * HP * (NG + 8) + (size_t)4 * (kBand + 1) * (HP + 1)) * sizeof(float);
+  const int HP = 16 * HT;
+  return (size_t)4 * (kBand + 1) * (HP + 1) * sizeof(float) + (size_t)4 * HT * 64 * 16;
 }
 size_t md_lds_bwd(int HT) {
   const int HP = 16 * HT, NG = 5 * HP;
@@ -650,7 +646,7 @@ hipError_t mdlstm_forward(hipStream_t stream, const MdShape& s, const MdDir* dir
   if (e != hipSuccess) return e;
   const bool vec = md_vec(s, dirs, y);
   const int grid = 4 * s.B * p.NB;
-#define RLSTM_MD_FWD(HT_, VEC_, XIN_) md_launch(mdlstm_fwd_kernel<HT_, VEC_, XIN_>, grid, 64 * HT_ * kTiles, md_lds_fwd(HT_), stream, p)
+#define RLSTM_MD_FWD(HT_, VEC_, XIN_) md_launch(mdlstm_fwd_kernel<HT_, VEC_, XIN_>, grid, 64 * 5 * HT_, md_lds_fwd(HT_), stream, p)
   if (s.H <= 16) {
     if (xin) return vec ? RLSTM_MD_FWD(1, true, true) : RLSTM_MD_FWD(1, false, true);
     return vec ? RLSTM_MD_FWD(1, true, false) : RLSTM_MD_FWD(1, false, false);
