@@ -124,10 +124,11 @@ __device__ __forceinline__ bool md_wait_word(const unsigned long long* q, unsign
 // XIN: the input has one value per pixel (grayscale images): the input part b + x W of the pre-activation is formed
 // here from x and this lane's weights and biases instead of being read from zg, and x is written next to
 // [h_up | h_left] for the weight-gradient product.
-template <int HT, bool VEC, bool XIN>
-__global__ __launch_bounds__(64 * 5 * HT) void mdlstm_fwd_kernel(MdParams p) {
+template <int HT, bool VEC, int XM>
+__global__ __launch_bounds__(64 * (5 * HT + 1)) void mdlstm_fwd_kernel(MdParams p) {
+  constexpr bool XIN = XM != 0;        // XM: 0 input part read from zg, 1 x read from HBM, 2 the band's x staged in LDS
   static_assert(kTiles == 1, "one 16-row tile per band");
-  constexpr int NTH = 64 * 5 * HT;
+  constexpr int NTH = 64 * (5 * HT + 1);   // one more wavefront takes the rows handed from the band above
   constexpr int HP = 16 * HT;          // padded units
   constexpr int KS = 2 * HP / 4;       // MFMA k-steps
   constexpr int LDH = HP + 1;
@@ -136,6 +137,8 @@ __global__ __launch_bounds__(64 * 5 * HT) void mdlstm_fwd_kernel(MdParams p) {
   float* hb = lds;                                   // [2][kBand + 1][LDH]; entry 0 is the row above the band
   float* cb = hb + 2 * (kBand + 1) * LDH;            // same for c
   floatx4* gact = reinterpret_cast<floatx4*>(cb + 2 * (kBand + 1) * LDH);   // [i, f_u, f_v, g][HT][64 lanes]
+  int* gaveup = reinterpret_cast<int*>(gact + 4 * HT * 64);                  // raised when a bounded wait expired (16 bytes)
+  float* xs = reinterpret_cast<float*>(gaveup + 4);                          // XIN, staged: [kBand][Ww] x in scan coordinates
 
   const int dn = blockIdx.x % (4 * p.B), band = blockIdx.x / (4 * p.B);   // bands above come first in the grid
   const int d = dn & 3, n = dn >> 2;
@@ -143,15 +146,20 @@ __global__ __launch_bounds__(64 * 5 * HT) void mdlstm_fwd_kernel(MdParams p) {
   const int H = p.H, Hh = p.Hh;
   const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, lq = lane >> 4;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int g = wave / HT, ht = wave % HT;     // gate (i, f_u, f_v, o, g) and group of 16 units of this wavefront
+  // Wavefront 5 HT only moves the handed rows in: it issues the only global loads of the scan.  A wavefront's memory
+  // counter retires in order, so a wavefront that waits for a load waits for every store it issued before, and
+  // a store to HBM takes about as long as a step; the gate wavefronts, which store, therefore never load.
+  const bool is_halo = wave == 5 * HT;
+  const int g = is_halo ? 5 : wave / HT, ht = wave % HT;     // gate (i, f_u, f_v, o, g) and group of 16 units of this wavefront
   const int lr = l16;                          // row inside the band
   const int r = kBand * band + lr;             // row of this lane
   const int jm = 16 * ht + l16;                // unit whose column this lane feeds to the MFMA (A operand row)
   const int j0 = 16 * ht + 4 * lq;             // first of the four units this lane holds (accumulator rows)
-  const int nv = min(max(H - j0, 0), 4);       // how many of them exist
+  const int nv = is_halo ? 0 : min(max(H - j0, 0), 4);       // how many of them exist
   const int wn = min(max(p.widths[n], 0), p.Ww);
   const int rows_here = min(Hh - kBand * band, kBand);
   const int slot = g < 3 ? g : 3;              // where this gate's activations go in gact (the output gate has none)
+  const float act_scale = g == 4 ? 2.f : 1.f, act_shift = 1.f - act_scale;
 
   // A[m][k] = [R_u ; R_v][k][gate column of unit m]
   float ra[KS];
@@ -159,9 +167,20 @@ __global__ __launch_bounds__(64 * 5 * HT) void mdlstm_fwd_kernel(MdParams p) {
   for (int ks = 0; ks < KS; ++ks) {
     const int k = 4 * ks + lq, kk = k % HP;
     const float* R = k < HP ? p.Ru[d] : p.Rv[d];
-    ra[ks] = (kk < H && jm < H) ? R[(size_t)kk * 5 * H + g * H + jm] : 0.f;
+    ra[ks] = (!is_halo && kk < H && jm < H) ? R[(size_t)kk * 5 * H + g * H + jm] : 0.f;
   }
   for (int idx = tid; idx < 2 * (kBand + 1) * LDH; idx += NTH) { hb[idx] = 0.f; cb[idx] = 0.f; }
+  if (tid == 0) *gaveup = 0;
+  // One input value per pixel: the band's x goes to LDS once, so that no step of the scan waits for a load from
+  // HBM (the memory counter retires in order: waiting for a load issued after a step's stores means waiting for
+  // the stores, about as long as a step; issuing the load first was measured slower still).
+  constexpr bool xstaged = XM == 2;
+  if (xstaged) {
+    for (int idx = tid; idx < rows_here * wn; idx += NTH) {
+      const int rr = idx / wn, qq = idx % wn;
+      xs[rr * p.Ww + qq] = p.x[md_pixel(p, du, dv, wn, n, kBand * band + rr, qq)];
+    }
+  }
   __syncthreads();
 
   float* zgd = p.zg[d];
@@ -174,22 +193,23 @@ __global__ __launch_bounds__(64 * 5 * HT) void mdlstm_fwd_kernel(MdParams p) {
   const bool takes = band > 0, gives = band < p.NB - 1;
   const unsigned long long* halo_in = takes ? p.halo + ((size_t)dn * (p.NB - 1) + (band - 1)) * ndiag * 64 : p.halo;
   unsigned long long* halo_out = gives ? p.halo + ((size_t)dn * (p.NB - 1) + band) * ndiag * 64 : p.halo;
-  const bool hands = tid < HW;         // the lanes that move the handed row (wavefront 0)
+  const bool hands = is_halo && lane < HW;     // the lanes that move the handed row in
+  const bool sends = wave == 1 && lane < HW;   // the lanes that hand this band's last row on (a wavefront that never loads)
 
   // h, c of the row above on diagonal sd -> entry 0 of the given buffers; returns false when a wait expired
   unsigned long long hw = 0;
   auto halo_issue = [&](int sd) {
-    if (hands && takes && sd >= s_lo - 1 && sd <= s_lo - 1 + wn - 1) hw = md_ld_word(halo_in + (size_t)sd * 64 + tid);
+    if (hands && takes && sd >= s_lo - 1 && sd <= s_lo - 1 + wn - 1) hw = md_ld_word(halo_in + (size_t)sd * 64 + lane);
   };
   auto halo_take = [&](int sd, float* hdst, float* cdst) -> bool {
     if (!hands) return true;
     float v = 0.f;
     bool good = true;
     if (takes && sd >= s_lo - 1 && sd <= s_lo - 1 + wn - 1) {
-      good = md_wait_word(halo_in + (size_t)sd * 64 + tid, hw, sd, p.err);
+      good = md_wait_word(halo_in + (size_t)sd * 64 + lane, hw, sd, p.err);
       v = __uint_as_float((unsigned)hw);
     }
-    if (tid < HP) hdst[tid] = v; else cdst[tid - HP] = v;
+    if (lane < HP) hdst[lane] = v; else cdst[lane - HP] = v;
     return good;
   };
 
@@ -208,7 +228,7 @@ __global__ __launch_bounds__(64 * 5 * HT) void mdlstm_fwd_kernel(MdParams p) {
     const int q = s - r;
     const bool ok = lr < rows_here && q >= 0 && q < wn && s <= s_hi && nv > 0;
     const size_t pix = ok ? md_pixel(p, du, dv, wn, n, r, q) : 0;
-    if (XIN) xcur = ok ? p.x[pix] : 0.f;       // used after the step's MFMAs, so the load has a step's time to arrive
+    if (XIN) xcur = ok ? (xstaged ? xs[lr * p.Ww + q] : p.x[pix]) : 0.f;   // used after the step's MFMAs
     else zr = ok ? ld4<VEC>(zgd + pix * 5 * H + g * H + j0, nv) : floatx4{0.f, 0.f, 0.f, 0.f};
   };
   prefetch(s_lo);
@@ -220,69 +240,95 @@ __global__ __launch_bounds__(64 * 5 * HT) void mdlstm_fwd_kernel(MdParams p) {
     halo_issue(s_lo - 1);
     if (!halo_take(s_lo - 1, hprev0, cprev0)) fail = 1;
   }
-  if (__syncthreads_or(fail)) {
+  if (fail) *gaveup = 1;
+  __syncthreads();
+  if (*gaveup) {
     if (tid == 0) __hip_atomic_store(p.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return;
   }
 
+  // The wavefront that takes the handed rows runs a loop of its own with the same barriers, so that the gate
+  // wavefronts' loop holds no load and hence no wait on the memory counter.
+  if (is_halo) {
+    for (int s = s_lo; s <= s_hi; ++s) {
+      halo_issue(s);                   // has the whole step to arrive
+      __syncthreads();
+      // the row above on this diagonal, for the next step (entry 0 of the buffers nobody reads in this step)
+      if (!halo_take(s, hb + (s & 1) * (kBand + 1) * LDH, cb + (s & 1) * (kBand + 1) * LDH)) *gaveup = 1;
+      __syncthreads();
+      if (*gaveup) return;
+    }
+  } else
   for (int s = s_lo; s <= s_hi; ++s) {
     const float* hprev = hb + ((s + 1) & 1) * (kBand + 1) * LDH;
     const float* cprev = cb + ((s + 1) & 1) * (kBand + 1) * LDH;
     float* hcur = hb + (s & 1) * (kBand + 1) * LDH;
     float* ccur = cb + (s & 1) * (kBand + 1) * LDH;
-    halo_issue(s);                     // arrives while the MFMAs run
 
     // accumulator rows: units j0 .. j0+3 of this gate; column: the image row of this lane.
     // B[k][n]: k < HP: h of the row above (entry index = row), else h of the same row (entry index row + 1)
     floatx4 acc0 = floatx4{0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
     const float* brow = hprev + lr * LDH;
+    // all of the step's B operands are fetched before the first MFMA (left to itself the compiler reuses two
+    // registers and waits for an LDS read in front of every pair of MFMAs)
+    float hv[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int k = 4 * ks + lq;
+      hv[ks] = k < HP ? brow[k] : brow[LDH + k - HP];
+    }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int ks = 0; ks < KS; ks += 2) {
-      const int k0 = 4 * ks + lq, k1 = k0 + 4;
-      const float h0 = k0 < HP ? brow[k0] : brow[LDH + k0 - HP];
-      const float h1 = k1 < HP ? brow[k1] : brow[LDH + k1 - HP];
-      acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(ra[ks], h0, acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(ra[ks + 1], h1, acc1, 0, 0, 0);
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(ra[ks], hv[ks], acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(ra[ks + 1], hv[ks + 1], acc1, 0, 0, 0);
     }
 
     const int q = s - r;
     const bool ok = lr < rows_here && q >= 0 && q < wn && nv > 0;
     const size_t pix = ok ? md_pixel(p, du, dv, wn, n, r, q) : 0;
     if (XIN) zr = bx + xcur * wx;
+    // sigmoid for the four gates, tanh(a) = 2 sigmoid(2a) - 1 for the cell input: one branch-free form
     floatx4 act;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float a = acc0[i] + acc1[i] + zr[i];
-      act[i] = g == 4 ? md_tanh(a) : md_sigmoid(a);
-    }
+    for (int i = 0; i < 4; ++i) act[i] = act_scale * md_sigmoid(act_scale * (acc0[i] + acc1[i] + zr[i])) + act_shift;
     if (g != 3) gact[(slot * HT + ht) * 64 + lane] = act;
-    // the row above on this diagonal, for the next step (entry 0 of the buffers nobody reads in this step)
-    fail = halo_take(s, hcur, ccur) ? 0 : 1;
     __syncthreads();
 
     floatx4 ct = floatx4{0.f, 0.f, 0.f, 0.f}, hn = ct, h_up = ct, h_left = ct;
     if (g == 3) {
       const floatx4 gi = gact[(0 * HT + ht) * 64 + lane], gfu = gact[(1 * HT + ht) * 64 + lane];
       const floatx4 gfv = gact[(2 * HT + ht) * 64 + lane], gg = gact[(3 * HT + ht) * 64 + lane];
+      // every LDS read of the update comes before its first LDS write (the compiler cannot tell that the rows it
+      // writes are not the rows it reads, and would wait after every unit)
+      floatx4 c_up, c_left;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int j = j0 + i;
         h_up[i] = hprev[lr * LDH + j]; h_left[i] = hprev[(lr + 1) * LDH + j];
-        const float c_up = cprev[lr * LDH + j], c_left = cprev[(lr + 1) * LDH + j];
-        ct[i] = gfu[i] * c_up + gfv[i] * c_left + gi[i] * gg[i];
+        c_up[i] = cprev[lr * LDH + j]; c_left[i] = cprev[(lr + 1) * LDH + j];
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        ct[i] = gfu[i] * c_up[i] + gfv[i] * c_left[i] + gi[i] * gg[i];
         hn[i] = act[i] * md_tanh(ct[i]);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
         const bool oki = ok && i < nv;
-        hcur[(lr + 1) * LDH + j] = oki ? hn[i] : 0.f;
-        ccur[(lr + 1) * LDH + j] = oki ? ct[i] : 0.f;
+        hcur[(lr + 1) * LDH + j0 + i] = oki ? hn[i] : 0.f;
+        ccur[(lr + 1) * LDH + j0 + i] = oki ? ct[i] : 0.f;
       }
     }
     // the next diagonal only needs the LDS rows: the stores to HBM and the next prefetch follow the barrier
-    if (__syncthreads_or(fail)) {
+    __syncthreads();
+    if (*gaveup) {
       if (tid == 0) __hip_atomic_store(p.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       return;
     }
-    if (gives && hands)                // last row of the band to the band below
-      md_st_word(halo_out + (size_t)s * 64 + tid, tid < HP ? hcur[kBand * LDH + tid] : ccur[kBand * LDH + tid - HP], s);
+    if (gives && sends)                // last row of the band to the band below
+      md_st_word(halo_out + (size_t)s * 64 + lane, lane < HP ? hcur[kBand * LDH + lane] : ccur[kBand * LDH + lane - HP], s);
     if (ok) {
       st4<VEC>(zgd + pix * 5 * H + g * H + j0, act, nv);
       if (g == 3) {
@@ -574,8 +620,10 @@ __global__ __launch_bounds__(256) void mdlstm_scatter_kernel(MdScatterParams p) 
 
 size_t md_lds_fwd(int HT) {
   const int HP = 16 * HT;
-  return (size_t)4 * (kBand + 1) * (HP + 1) * sizeof(float) + (size_t)4 * HT * 64 * 16;
+  return (size_t)4 * (kBand + 1) * (HP + 1) * sizeof(float) + (size_t)4 * HT * 64 * 16 + 16;
 }
+// room for a band's x values behind that, when it fits
+size_t md_lds_xstage(int Ww) { return (size_t)kBand * Ww * sizeof(float); }
 size_t md_lds_bwd(int HT) {
   const int HP = 16 * HT, NG = 5 * HP;
   return ((size_t)2 * NG * (HP + 8) + (size_t)(kBand + 1) * (NG + 4) + (size_t)4 * (kBand + 1) * (HP + 1)) * sizeof(float);
@@ -646,7 +694,12 @@ hipError_t mdlstm_forward(hipStream_t stream, const MdShape& s, const MdDir* dir
   if (e != hipSuccess) return e;
   const bool vec = md_vec(s, dirs, y);
   const int grid = 4 * s.B * p.NB;
-#define RLSTM_MD_FWD(HT_, VEC_, XIN_) md_launch(mdlstm_fwd_kernel<HT_, VEC_, XIN_>, grid, 64 * 5 * HT_, md_lds_fwd(HT_), stream, p)
+  const bool xstage = xin && md_lds_fwd(2) + md_lds_xstage(s.Ww) <= (size_t)96 * 1024;
+  const size_t xlds = xstage ? md_lds_xstage(s.Ww) : 0;
+#define RLSTM_MD_FWD(HT_, VEC_, XIN_) \
+  (!(XIN_) ? md_launch(mdlstm_fwd_kernel<HT_, VEC_, 0>, grid, 64 * (5 * HT_ + 1), md_lds_fwd(HT_), stream, p)                \
+   : !xstage ? md_launch(mdlstm_fwd_kernel<HT_, VEC_, 1>, grid, 64 * (5 * HT_ + 1), md_lds_fwd(HT_), stream, p)              \
+             : md_launch(mdlstm_fwd_kernel<HT_, VEC_, 2>, grid, 64 * (5 * HT_ + 1), md_lds_fwd(HT_) + xlds, stream, p))
   if (s.H <= 16) {
     if (xin) return vec ? RLSTM_MD_FWD(1, true, true) : RLSTM_MD_FWD(1, false, true);
     return vec ? RLSTM_MD_FWD(1, true, false) : RLSTM_MD_FWD(1, false, false);
