@@ -19,10 +19,11 @@
 // a whole-image product, prefetched one diagonal ahead, or, for one input value per pixel, is formed
 // in the kernel.
 // Backward step (diagonals in reverse): d h = [d a(r+1) | d a(r)] of diagonal s+1 times
-// [R_u ; R_v]^T, K = 10H, same row / lane assignment; the gate derivatives follow in registers.
-// d a overwrites the gates in place; [h_up | h_left] of every pixel is kept from the forward pass
-// so that d R_u and d R_v are one whole-image product each afterwards.
+// [R_u ; R_v]^T, K = 10H, split five ways over the same wavefronts; the gate derivatives follow with one
+// lane per (row, unit).  d a overwrites the gates in place; [h_up | h_left] of every pixel is kept from
+// the forward pass so that d R_u and d R_v are one whole-image product each afterwards.
 #include "rlstm_internal.h"
+#include <type_traits>
 
 namespace rlstm {
 
@@ -358,21 +359,37 @@ __global__ __launch_bounds__(64 * (5 * HT + 1)) void mdlstm_fwd_kernel(MdParams 
 }
 
 
+// Backward scan.  d h^T of a diagonal = [R_u ; R_v] [d a(row + 1) | d a(row)]^T of the diagonal done before it, a
+// contraction over K = 10 HP.  A step has two phases with a barrier between them.
+// Product: 5 * HT compute wavefronts; wavefront (g, ht) takes the columns of gate g (a fifth of K) for the 16 units
+// of ht (16 MFMAs for HT = 2, its operands of [R_u ; R_v] in registers) and leaves its partial sums in LDS.
+// Gate derivatives: one lane per (row, unit) of the diagonal (16 * HP lanes, HP / 4 of the compute wavefronts): it
+// adds the five partial sums in a fixed order and forms the five d a of its pixel and unit.  What limits a step is
+// the number of vector instructions the workgroup issues (a SIMD issues one wavefront instruction per 4 cycles, and
+// the wavefronts of a SIMD share it), so every value is computed exactly once and the lane's addresses advance by a
+// constant per diagonal instead of being recomputed.
+// A wavefront's memory counter retires in order, so a wavefront that waits for a load waits for every store it issued
+// before; loads and stores are therefore kept in different wavefronts: the compute wavefronts only load (two diagonals
+// ahead, see below), two more wavefronts only store (d a rows out of LDS, and the row handed to the band above) and
+// one only takes the row handed from the band below.
 template <int HT, bool VEC>
-__global__ __launch_bounds__(64 * kTiles * HT) void mdlstm_bwd_kernel(MdParams p) {
-  constexpr int NTH = 64 * kTiles * HT;
+__global__ __launch_bounds__(64 * (5 * HT + 3)) void mdlstm_bwd_kernel(MdParams p) {
+  static_assert(kTiles == 1, "one 16-row tile per band");
+  constexpr int NC = 5 * HT;           // compute wavefronts
+  constexpr int NTH = 64 * (NC + 3);
   constexpr int HP = 16 * HT;
   constexpr int NG = 5 * HP;
-  constexpr int KS = 2 * NG / 4;
-  constexpr int LDT = HP + 8;          // LDS row stride of [R_u ; R_v]^T
-  constexpr int LDZ = NG + 4;          // LDS row stride of the d a rows
+  constexpr int KS = 2 * HP / 4;       // MFMA k-steps of one wavefront: a fifth of K = 2 NG
+  constexpr int LDZ = NG + 4;          // LDS row stride of the d a rows (a multiple of 4: rows stay 16-byte aligned)
   constexpr int LDH = HP + 1;
   constexpr int HW = NG + HP;          // words of a handed row: d a | f_u * d c~
   extern __shared__ __align__(16) float lds[];
-  float* RT = lds;                                   // [2NG][LDT]: row k < NG: R_u[.][k]; else R_v[.][k - NG]
-  float* dzb = RT + 2 * NG * LDT;                    // [kBand + 1][LDZ]: d a of the diagonal done last; entry kBand is the row below the band
+  constexpr int LDP = HP + 4;          // row stride of the partial sums (a multiple of 4)
+  float* part = lds;                                 // [5][16 rows][LDP]: partial d h of every fifth of K
+  float* dzb = lds + 5 * 16 * LDP;                   // [kBand + 1][LDZ]: d a of the diagonal done last; entry kBand is the row below the band
   float* dcu = dzb + (kBand + 1) * LDZ;              // [2][kBand + 1][LDH]: f_u * d c~ of a diagonal's pixels; entry kBand: row below
   float* dcv = dcu + 2 * (kBand + 1) * LDH;          // same with f_v
+  int* gaveup = reinterpret_cast<int*>(dcv + 2 * (kBand + 1) * LDH);   // raised when a bounded wait expired
 
   // bands below come first in the grid
   const int dn = blockIdx.x % (4 * p.B), band = p.NB - 1 - blockIdx.x / (4 * p.B);
@@ -380,23 +397,28 @@ __global__ __launch_bounds__(64 * kTiles * HT) void mdlstm_bwd_kernel(MdParams p
   const int du = (d & 2) ? -1 : 1, dv = (d & 1) ? -1 : 1;
   const int H = p.H, Hh = p.Hh;
   const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, lq = lane >> 4;
-  const int lr = 16 * ((tid >> 6) % kTiles) + l16;  // row inside the band
-  const int r = kBand * band + lr;             // row of this lane
-  const int jm = 16 * (tid / (64 * kTiles)) + l16;        // unit whose row of [R_u ; R_v]^T this lane feeds to the MFMA
-  const int j0 = 16 * (tid / (64 * kTiles)) + 4 * lq;     // first of the four units this lane handles
-  const int nv = min(max(H - j0, 0), 4);
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const bool computes = wave < NC, stores = wave == NC || wave == NC + 1, is_halo = wave == NC + 2;
+  const int g = computes ? wave / HT : 0, ht = wave % HT;   // gate, which is also the fifth of K, and group of 16 units
+  const int lr = l16;                          // row inside the band
+  const int jm = 16 * ht + l16;                // unit whose row of [R_u ; R_v] this lane feeds to the MFMA
+  const int j0 = 16 * ht + 4 * lq;             // first of the four units this lane handles
   const int wn = min(max(p.widths[n], 0), p.Ww);
   const int rows_here = min(Hh - kBand * band, kBand);
 
-  for (int idx = tid; idx < 2 * NG * HP; idx += NTH) {
-    const int k = idx / HP, jo = idx % HP;
-    const int kk = k % NG, g = kk / HP, jj = kk % HP;
-    float v = 0.f;
-    if (jj < H && jo < H) v = (k < NG ? p.Ru[d] : p.Rv[d])[(size_t)jo * 5 * H + g * H + jj];
-    RT[k * LDT + jo] = v;
+  // The fifth of K of wavefront (g, ht): the columns of gate g, first of R_u (against d a of the row below,
+  // row + 1), then of R_v (against d a of the same row).  A[m][k] = R[unit m][column k of gate g].
+  float ra[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    const int jj = 4 * (ks % (KS / 2)) + lq;
+    const float* R = ks < KS / 2 ? p.Ru[d] : p.Rv[d];
+    ra[ks] = (computes && jj < H && jm < H) ? R[(size_t)jm * 5 * H + g * H + jj] : 0.f;
   }
+  const float* bbase = dzb + lr * LDZ + g * HP + lq;   // B[k][row]: + LDZ + 4 ks for the first half, + 4 (ks - KS/2) for the second
   for (int idx = tid; idx < (kBand + 1) * LDZ; idx += NTH) dzb[idx] = 0.f;
   for (int idx = tid; idx < 2 * (kBand + 1) * LDH; idx += NTH) { dcu[idx] = 0.f; dcv[idx] = 0.f; }
+  if (tid == 0) *gaveup = 0;
   __syncthreads();
 
   float* zgd = p.zg[d];
@@ -409,21 +431,21 @@ __global__ __launch_bounds__(64 * kTiles * HT) void mdlstm_bwd_kernel(MdParams p
   const unsigned long long* halo_in = takes ? p.halo + ((size_t)dn * (p.NB - 1) + band) * ndiag * 192 : p.halo;
   unsigned long long* halo_out = gives ? p.halo + ((size_t)dn * (p.NB - 1) + (band - 1)) * ndiag * 192 : p.halo;
 
-  // d a and f_u * d c~ of the row below on diagonal sd -> entry kBand of dzb / the given dcu buffer (wavefront 0)
+  // d a and f_u * d c~ of the row below on diagonal sd -> entry kBand of dzb / of dcu's buffer for sd
   unsigned long long hw[3] = {0, 0, 0};
   auto halo_issue = [&](int sd) {
-    if (tid < 64 && takes && sd >= b_lo && sd <= b_lo + wn - 1)
+    if (takes && sd >= b_lo && sd <= b_lo + wn - 1)
 #pragma unroll
       for (int k = 0; k < 3; ++k)
-        if (tid + 64 * k < HW) hw[k] = md_ld_word(halo_in + (size_t)sd * 192 + tid + 64 * k);
+        if (lane + 64 * k < HW) hw[k] = md_ld_word(halo_in + (size_t)sd * 192 + lane + 64 * k);
   };
-  auto halo_take = [&](int sd, float* dcu_dst) -> bool {
-    if (tid >= 64) return true;
+  auto halo_take = [&](int sd) -> bool {
     bool good = true;
     const bool have = takes && sd >= b_lo && sd <= b_lo + wn - 1;
+    float* dcu_dst = dcu + (sd & 1) * (kBand + 1) * LDH;
 #pragma unroll
     for (int k = 0; k < 3; ++k) {
-      const int w = tid + 64 * k;
+      const int w = lane + 64 * k;
       if (w >= HW) continue;
       float v = 0.f;
       if (have) {
@@ -435,139 +457,211 @@ __global__ __launch_bounds__(64 * kTiles * HT) void mdlstm_bwd_kernel(MdParams p
     return good;
   };
 
-  // bias gradient of the lane's four units, summed over all diagonals
-  floatx4 dbacc[5];
-#pragma unroll
-  for (int g = 0; g < 5; ++g) dbacc[g] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-  // gates, c, c of the two predecessors and dy of the lane's row and four units on diagonal s
-  floatx4 in[9];
-  auto prefetch = [&](int s) {
-    const int q = s - r;
-    const bool ok = s >= s_lo && lr < rows_here && q >= 0 && q < wn && nv > 0;
-    const floatx4 zero = floatx4{0.f, 0.f, 0.f, 0.f};
-    const size_t pix = ok ? md_pixel(p, du, dv, wn, n, r, q) : 0;
-#pragma unroll
-    for (int g = 0; g < 5; ++g) in[g] = ok ? ld4<VEC>(zgd + pix * 5 * H + g * H + j0, nv) : zero;
-    in[5] = ok ? ld4<VEC>(cd + pix * H + j0, nv) : zero;
-    in[6] = (ok && r >= 1) ? ld4<VEC>(cd + md_pixel(p, du, dv, wn, n, r - 1, q) * H + j0, nv) : zero;
-    in[7] = (ok && q >= 1) ? ld4<VEC>(cd + md_pixel(p, du, dv, wn, n, r, q - 1) * H + j0, nv) : zero;
-    in[8] = ok ? ld4<VEC>(p.dy + pix * 4 * H + d * H + j0, nv) : zero;
+  // The wavefront whose wait expired raises the flag in HBM itself: a store in the compute wavefronts' loop, even on
+  // a path that leaves it, would make the compiler wait for every load in flight on each diagonal (loads and
+  // stores pending on one counter count as unordered).
+  auto give_up = [&]() {
+    *gaveup = 1;
+    __hip_atomic_store(p.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   };
-  prefetch(s_hi);
-  int fail = 0;
-  {
+  if (is_halo) {
     // the row below on the diagonal after the last one
     halo_issue(s_hi + 1);
-    if (!halo_take(s_hi + 1, dcu + ((s_hi + 1) & 1) * (kBand + 1) * LDH)) fail = 1;
+    if (!halo_take(s_hi + 1)) give_up();
   }
-  if (__syncthreads_or(fail)) {
-    if (tid == 0) __hip_atomic_store(p.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  if (*gaveup) return;
+
+  // Every wavefront passes the same two barriers per diagonal: A after the partial products (the d a rows of the
+  // diagonal before have been read), B when the LDS rows of the diagonal are complete.
+  if (is_halo) {
+    for (int s = s_hi; s >= s_lo; --s) {
+      if (s > s_lo) halo_issue(s);     // has the whole step to arrive
+      __syncthreads();
+      const int stop = *gaveup;        // raised during the diagonal before: every wavefront reads it here
+      if (s > s_lo && !halo_take(s)) give_up();
+      __syncthreads();
+      if (stop) return;
+    }
+    __syncthreads();                   // the barrier of the bias-gradient sum below
     return;
   }
 
-  // this lane's A operands of every MFMA of a step: they do not change from diagonal to diagonal
-  float rt[KS];
+  if (stores) {
+    // lane -> (row, eight lanes a row); the row's d a leave LDS 16 bytes at a time
+    const int t = 64 * (wave - NC) + lane, row = t >> 3, c8 = t & 7;
+    auto store_rows = [&](int s) {
+      if (gives && wave == NC) {       // first row of the band to the band above, first: that band waits for it
+        const float* dcu_s = dcu + (s & 1) * (kBand + 1) * LDH;
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) rt[ks] = RT[(4 * ks + lq) * LDT + jm];
+        for (int k = 0; k < 3; ++k) {
+          const int w = lane + 64 * k;
+          if (w < HW) md_st_word(halo_out + (size_t)s * 192 + w, w < NG ? dzb[w] : dcu_s[w - NG], s);
+        }
+      }
+      const int q = s - (kBand * band + row);
+      if (row < rows_here && q >= 0 && q < wn) {
+        float* zrow = zgd + md_pixel(p, du, dv, wn, n, kBand * band + row, q) * 5 * H;
+#pragma unroll
+        for (int k = 0; k < (NG / 4 + 7) / 8; ++k) {
+          const int colf = 4 * (c8 + 8 * k), gk = colf / HP, jj = colf % HP;
+          if (colf < NG && jj < H) st4<VEC>(zrow + gk * H + jj, *reinterpret_cast<const floatx4*>(dzb + row * LDZ + colf), min(H - jj, 4));
+        }
+      }
+    };
+    for (int s = s_hi; s >= s_lo; --s) {
+      if (s < s_hi) store_rows(s + 1);
+      __syncthreads();
+      const int stop = *gaveup;
+      __syncthreads();
+      if (stop) return;
+    }
+    if (s_hi >= s_lo) store_rows(s_lo);
+    __syncthreads();                   // the barrier of the bias-gradient sum below
+    return;
+  }
 
-  for (int s = s_hi; s >= s_lo; --s) {
+  // ---- compute wavefronts ----
+  floatx4* part_w = reinterpret_cast<floatx4*>(part + (g * 16 + lr) * LDP + j0);   // where the product phase leaves its sums
+
+  // gate-derivative phase: lane -> (row, unit) of the band
+  constexpr int NE = HP / 4;           // wavefronts that take part in it
+  const bool elem = wave < NE;
+  const int er = (64 * wave + lane) / HP, ej = (64 * wave + lane) % HP;   // row inside the band, unit
+  const int rr = kBand * band + er;    // row of this lane's pixels
+  const bool live = elem && er < rows_here && ej < H;
+  // element offsets of the lane's pixel on diagonal s in the tensors with 5H, H and 4H values per pixel; they move
+  // by a constant from one diagonal to the next (q falls by one: the pixel index moves by -dv * B), also while the
+  // lane has no pixel on the diagonal, when nothing is loaded
+  long long oz, oc, oy;
+  {
+    const long long u = du > 0 ? rr : Hh - 1 - rr;
+    const long long q0 = (long long)s_hi - rr, v0 = dv > 0 ? q0 : wn - 1 - q0;
+    const long long pix = (u * p.Ww + v0) * p.B + n;
+    oz = pix * 5 * H + ej; oc = pix * H + ej; oy = pix * 4 * H + d * H + ej;
+  }
+  const long long pstep = -(long long)dv * p.B;                                     // pixel index, per diagonal
+  const long long c_up = -(long long)du * p.Ww * p.B * H, c_left = -(long long)dv * p.B * H;   // c of the predecessors, relative to oc
+  const float* dyd = p.dy;
+  // Two register sets, loaded two diagonals ahead.  Every load is issued on every diagonal (a lane without a pixel
+  // there reads the tensors' first words and drops them when it uses them): with no branch around the loads the
+  // wait for one set leaves the other, younger one in flight.
+  struct In { float gi, gfu, gfv, go, gg, cc, cu, cl, dy; };
+  auto issue = [&](In& in, int s) {
+    const int q = s - rr;
+    const bool ok = live && s >= s_lo && q >= 0 && q < wn;
+    const long long az = ok ? oz : 0, ac = ok ? oc : 0, ay = ok ? oy : 0;
+    const long long au = (ok && rr >= 1) ? oc + c_up : 0, al = (ok && q >= 1) ? oc + c_left : 0;
+    const float* z = zgd + az;
+    in.cc = cd[ac];
+    in.dy = dyd[ay];
+    in.go = z[3 * H];
+    in.gi = z[0]; in.gfu = z[H]; in.gfv = z[2 * H]; in.gg = z[4 * H];
+    in.cu = cd[au];
+    in.cl = cd[al];
+    oz += pstep * 5 * H; oc += pstep * H; oy += pstep * 4 * H;
+  };
+
+  float dbacc[5] = {0.f, 0.f, 0.f, 0.f, 0.f};   // bias gradient of the lane's unit over its row's pixels
+  // one diagonal; false: a wait expired somewhere in the workgroup
+  auto step = [&](auto takes_part, In& in, int s) -> bool {
+    constexpr bool ELEM = decltype(takes_part)::value;
     const float* dcu_prev = dcu + ((s + 1) & 1) * (kBand + 1) * LDH;
     const float* dcv_prev = dcv + ((s + 1) & 1) * (kBand + 1) * LDH;
     float* dcu_cur = dcu + (s & 1) * (kBand + 1) * LDH;
     float* dcv_cur = dcv + (s & 1) * (kBand + 1) * LDH;
-    if (s > s_lo) halo_issue(s);       // arrives while the MFMAs run
-
-    // d h^T of diagonal s = [R_u ; R_v] [d a(row + 1) | d a(row)]^T of diagonal s+1 (the successor below sits in
-    // row r+1, the one to the right in row r); two accumulators so that consecutive MFMAs do not wait for each other
-    floatx4 acc0 = floatx4{0.f, 0.f, 0.f, 0.f}, acc1 = floatx4{0.f, 0.f, 0.f, 0.f};
-    const float* brow = dzb + lr * LDZ;
+    // all of the step's B operands are fetched before the first MFMA; two accumulators so that consecutive MFMAs
+    // do not wait for each other
+    float hv[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) hv[ks] = ks < KS / 2 ? bbase[LDZ + 4 * ks] : bbase[4 * (ks - KS / 2)];
+    __builtin_amdgcn_sched_barrier(0);
+    floatx4 acc0 = floatx4{0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
 #pragma unroll
     for (int ks = 0; ks < KS; ks += 2) {
-      const int k0 = 4 * ks + lq, k1 = k0 + 4;
-      const float b0 = k0 < NG ? brow[LDZ + k0] : brow[k0 - NG];
-      const float b1 = k1 < NG ? brow[LDZ + k1] : brow[k1 - NG];
-      acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(rt[ks], b0, acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(rt[ks + 1], b1, acc1, 0, 0, 0);
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(ra[ks], hv[ks], acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(ra[ks + 1], hv[ks + 1], acc1, 0, 0, 0);
     }
-    const floatx4 acc = acc0 + acc1;
-    __syncthreads();     // every wavefront has read the d a rows of diagonal s+1
+    *part_w = acc0 + acc1;
+    __syncthreads();     // A
 
-    const int q = s - r;
-    const bool ok = lr < rows_here && q >= 0 && q < wn && nv > 0;
-    const size_t pix = ok ? md_pixel(p, du, dv, wn, n, r, q) : 0;
-    floatx4 dz[5];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int j = j0 + i;
-      const bool oki = ok && i < nv;
-      const float gi = in[0][i], gfu = in[1][i], gfv = in[2][i], go = in[3][i], gg = in[4][i];
-      const float tc = md_tanh(in[5][i]);
-      const float dh = in[8][i] + acc[i];
-      const float d_o = dh * tc;
-      const float dct = dcu_prev[(lr + 1) * LDH + j] + dcv_prev[lr * LDH + j] + dh * go * (1.0f - tc * tc);
-      dz[0][i] = oki ? dct * gg * gi * (1.0f - gi) : 0.f;
-      dz[1][i] = oki ? dct * in[6][i] * gfu * (1.0f - gfu) : 0.f;
-      dz[2][i] = oki ? dct * in[7][i] * gfv * (1.0f - gfv) : 0.f;
-      dz[3][i] = oki ? d_o * go * (1.0f - go) : 0.f;
-      dz[4][i] = oki ? dct * gi * (1.0f - gg * gg) : 0.f;
-      dcu_cur[lr * LDH + j] = oki ? dct * gfu : 0.f;
-      dcv_cur[lr * LDH + j] = oki ? dct * gfv : 0.f;
-#pragma unroll
-      for (int g = 0; g < 5; ++g) dzb[lr * LDZ + g * HP + j] = dz[g][i];
+    // a flag raised during the diagonal before is seen here by every wavefront alike
+    const int stop = *gaveup;
+    if (ELEM) {
+      const int q = s - rr;
+      const bool ok = live && q >= 0 && q < wn;
+      const float* pr = part + er * LDP + ej;
+      const float p0 = pr[0], p1 = pr[16 * LDP], p2 = pr[2 * 16 * LDP], p3 = pr[3 * 16 * LDP], p4 = pr[4 * 16 * LDP];
+      const float su = dcu_prev[(er + 1) * LDH + ej], sv = dcv_prev[er * LDH + ej];
+      const float gi = in.gi, gfu = in.gfu, gfv = in.gfv, go = in.go, gg = in.gg;
+      const float cu = rr >= 1 ? in.cu : 0.f, cl = q >= 1 ? in.cl : 0.f;   // c of a predecessor outside the image is zero
+      const float tc = md_tanh(in.cc);
+      const float dh = in.dy + ((((p0 + p1) + p2) + p3) + p4);
+      const float dct = su + sv + dh * go * (1.0f - tc * tc);
+      const float dz0 = ok ? dct * gg * gi * (1.0f - gi) : 0.f;
+      const float dz1 = ok ? dct * cu * gfu * (1.0f - gfu) : 0.f;
+      const float dz2 = ok ? dct * cl * gfv * (1.0f - gfv) : 0.f;
+      const float dz3 = ok ? dh * tc * go * (1.0f - go) : 0.f;
+      const float dz4 = ok ? dct * gi * (1.0f - gg * gg) : 0.f;
+      float* zr = dzb + er * LDZ + ej;
+      zr[0] = dz0; zr[HP] = dz1; zr[2 * HP] = dz2; zr[3 * HP] = dz3; zr[4 * HP] = dz4;
+      dcu_cur[er * LDH + ej] = ok ? dct * gfu : 0.f;
+      dcv_cur[er * LDH + ej] = ok ? dct * gfv : 0.f;
+      dbacc[0] += dz0; dbacc[1] += dz1; dbacc[2] += dz2; dbacc[3] += dz3; dbacc[4] += dz4;
+      issue(in, s - 2);
     }
-#pragma unroll
-    for (int g = 0; g < 5; ++g) dbacc[g] += dz[g];
-    // the row below on this diagonal, for the next step
-    fail = (s > s_lo ? halo_take(s, dcu_cur) : true) ? 0 : 1;
-    // the LDS rows of diagonal s are complete; HBM traffic follows the barrier
-    if (__syncthreads_or(fail)) {
-      if (tid == 0) __hip_atomic_store(p.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      return;
+    __syncthreads();     // B
+    return stop == 0;
+  };
+
+  // nothing older than the two register sets may be in flight when the loop starts, or the waits inside it turn
+  // into waits for everything (vmcnt(0), expcnt and lgkmcnt left alone)
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  // The wavefronts without a part in the gate derivatives run a loop of their own: a branch around the loads inside
+  // one common loop would again make every wait a wait for everything.
+  In inA, inB;
+  if (elem) {
+    issue(inA, s_hi);
+    issue(inB, s_hi - 1);
+    for (int s = s_hi; s >= s_lo; s -= 2) {
+      if (!step(std::true_type{}, inA, s)) return;
+      if (s - 1 < s_lo) break;
+      if (!step(std::true_type{}, inB, s - 1)) return;
     }
-    if (gives && tid < 64) {           // first row of the band to the band above
+  } else {
+    for (int s = s_hi; s >= s_lo; --s)
+      if (!step(std::false_type{}, inA, s)) return;
+  }
+
+  // bias gradient of this (direction, image, band): the 16 rows of a unit are added in row order
+  float* stage = part;                               // [5 HP][16 rows]; the last step's partial sums have been read
+  if (elem) {
 #pragma unroll
-      for (int k = 0; k < 3; ++k) {
-        const int w = tid + 64 * k;
-        if (w < HW) md_st_word(halo_out + (size_t)s * 192 + w, w < NG ? dzb[w] : dcu_cur[w - NG], s);
-      }
-    }
-    if (ok) {
-      float* zrow = zgd + pix * 5 * H + j0;
-#pragma unroll
-      for (int g = 0; g < 5; ++g) st4<VEC>(zrow + g * H, dz[g], nv);
-    }
-    prefetch(s - 1);
+    for (int k = 0; k < 5; ++k) stage[(k * HP + ej) * 16 + er] = dbacc[k];
   }
   __syncthreads();
-
-  // bias gradient of this (direction, image, band): the threads that share a unit are added in thread order
-  float* stage = dzb;                                // [threads][5][4]
-#pragma unroll
-  for (int g = 0; g < 5; ++g)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) stage[(tid * 5 + g) * 4 + i] = dbacc[g][i];
-  __syncthreads();
-  for (int idx = tid; idx < 5 * HP; idx += NTH) {
-    const int g = idx / HP, jo = idx % HP;
+  for (int idx = tid; idx < 5 * HP; idx += 64 * NC) {
+    const int gk = idx / HP, jo = idx % HP;
     if (jo < H) {
-      // threads that handle unit jo: unit half jo / 16, quad (jo % 16) / 4, every row tile and row lane
       float sum = 0.f;
-      for (int w = 0; w < kTiles; ++w)
-        for (int l = 0; l < 16; ++l)
-          sum += stage[((64 * kTiles * (jo >> 4) + 64 * w + 16 * ((jo & 15) >> 2) + l) * 5 + g) * 4 + (jo & 3)];
-      p.dbpart[((size_t)dn * p.NB + band) * 5 * H + g * H + jo] = sum;
+      for (int l = 0; l < 16; ++l) sum += stage[idx * 16 + l];
+      p.dbpart[((size_t)dn * p.NB + band) * 5 * H + gk * H + jo] = sum;
     }
   }
+}
 
-  // d a = 0 beyond the image's width
-  const int npad = (p.Ww - wn) * rows_here;
-  for (int idx = tid; idx < npad * 5 * H; idx += NTH) {
-    const int col = idx % (5 * H), cell = idx / (5 * H);
-    const int rr = kBand * band + cell / (p.Ww - wn), v = wn + cell % (p.Ww - wn);
-    const int u = du > 0 ? rr : Hh - 1 - rr;
-    const size_t pix = ((size_t)u * p.Ww + v) * p.B + n;
-    zgd[pix * 5 * H + col] = 0.f;
+// zeros in the pixel slots beyond every image's width of four [P, cols] tensors: a launch of its own over the whole
+// chip (a scan's workgroup would spend longer on the slots of a narrow image than on the image)
+struct MdZeroParams { float* a[4]; const int32_t* widths; int Hh, Ww, B, cols; };
+__global__ __launch_bounds__(256) void mdlstm_zero_pad_kernel(MdZeroParams p) {
+  const int n = blockIdx.x % p.B, u = blockIdx.x / p.B;
+  const int wn = min(max(p.widths[n], 0), p.Ww);
+  const int total = (p.Ww - wn) * p.cols;
+  for (int idx = threadIdx.x; idx < total; idx += 256) {
+    const int v = wn + idx / p.cols, col = idx % p.cols;
+    const size_t o = (((size_t)u * p.Ww + v) * p.B + n) * p.cols + col;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) p.a[d][o] = 0.f;
   }
 }
 
@@ -626,7 +720,7 @@ size_t md_lds_fwd(int HT) {
 size_t md_lds_xstage(int Ww) { return (size_t)kBand * Ww * sizeof(float); }
 size_t md_lds_bwd(int HT) {
   const int HP = 16 * HT, NG = 5 * HP;
-  return ((size_t)2 * NG * (HP + 8) + (size_t)(kBand + 1) * (NG + 4) + (size_t)4 * (kBand + 1) * (HP + 1)) * sizeof(float);
+  return ((size_t)5 * 16 * (HP + 4) + (size_t)(kBand + 1) * (NG + 4) + (size_t)4 * (kBand + 1) * (HP + 1)) * sizeof(float) + 16;
 }
 
 template <typename K>
@@ -739,10 +833,19 @@ hipError_t mdlstm_backward(hipStream_t stream, const MdShape& s, const MdDir* di
   if (e != hipSuccess) return e;
   const bool vec = md_vec(s, dirs, dy);
   const int grid = 4 * s.B * p.NB;
-  if (s.H <= 16) e = vec ? md_launch(mdlstm_bwd_kernel<1, true>, grid, 64 * kTiles, md_lds_bwd(1), stream, p)
-                         : md_launch(mdlstm_bwd_kernel<1, false>, grid, 64 * kTiles, md_lds_bwd(1), stream, p);
-  else e = vec ? md_launch(mdlstm_bwd_kernel<2, true>, grid, 128 * kTiles, md_lds_bwd(2), stream, p)
-               : md_launch(mdlstm_bwd_kernel<2, false>, grid, 128 * kTiles, md_lds_bwd(2), stream, p);
+  {
+    // d a = 0 beyond the images' widths (the products over all pixel slots read it)
+    MdZeroParams z{};
+    for (int d = 0; d < 4; ++d) z.a[d] = dirs[d].zg;
+    z.widths = widths; z.Hh = s.Hh; z.Ww = s.Ww; z.B = s.B; z.cols = 5 * s.H;
+    hipLaunchKernelGGL(mdlstm_zero_pad_kernel, dim3((unsigned)(s.Hh * s.B)), dim3(256), 0, stream, z);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  if (s.H <= 16) e = vec ? md_launch(mdlstm_bwd_kernel<1, true>, grid, 64 * 8, md_lds_bwd(1), stream, p)
+                         : md_launch(mdlstm_bwd_kernel<1, false>, grid, 64 * 8, md_lds_bwd(1), stream, p);
+  else e = vec ? md_launch(mdlstm_bwd_kernel<2, true>, grid, 64 * 13, md_lds_bwd(2), stream, p)
+               : md_launch(mdlstm_bwd_kernel<2, false>, grid, 64 * 13, md_lds_bwd(2), stream, p);
   if (e != hipSuccess) return e;
   MdDbParams q{};
   for (int d = 0; d < 4; ++d) q.db[d] = db[d];
