@@ -103,9 +103,20 @@ __device__ __forceinline__ bool wave_wait_flags(const unsigned* flags, int first
   return ok;
 }
 
-// gate functions: libm-accurate expf, hardware reciprocal (v_rcp_f32, 1 ulp)
-__device__ __forceinline__ float fsigmoid(float u) { return __builtin_amdgcn_rcpf(1.0f + expf(-u)); }
-__device__ __forceinline__ float ftanh(float u) { return 2.0f * __builtin_amdgcn_rcpf(1.0f + expf(-2.0f * u)) - 1.0f; }
+// Workgroup barrier that also tells every thread whether any thread failed (a bounded wait expired).  `flag` is a
+// word of LDS that starts at zero and is only ever raised; two successive uses need two different words, or a
+// plain barrier between them.  (__syncthreads_or costs three barriers.)
+__device__ __forceinline__ bool barrier_any_failed(int fail, int* flag) {
+  if (fail) *flag = 1;
+  __syncthreads();
+  return *flag != 0;
+}
+
+// gate functions on the hardware exponential (v_exp_f32, 1 ulp) and reciprocal (v_rcp_f32, 1 ulp): the gating sits in
+// the step chain, and the libm expf is a dozen instructions longer per call.  Absolute error ~2e-7.
+__device__ __forceinline__ float fexp(float u) { return __builtin_amdgcn_exp2f(u * 1.44269504088896341f); }
+__device__ __forceinline__ float fsigmoid(float u) { return __builtin_amdgcn_rcpf(1.0f + fexp(-u)); }
+__device__ __forceinline__ float ftanh(float u) { return 2.0f * __builtin_amdgcn_rcpf(1.0f + fexp(-2.0f * u)) - 1.0f; }
 
 // position of element (row k of a wavefront's K range, sequence b) inside that wavefront's
 // operand-ordered block: [chunk][lane][4], L = (k/4)*MT + b/16, chunk = L/4, lane = (k%4)*16 + b%16
@@ -276,6 +287,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
   float* Red = Rs + (size_t)Hp * NC / (BF ? 2 : 1);   // [4][MT][NT][256]
   float* zin = Red + 4 * MT * NT * 256;          // [2][4][NE]  input part of the frame, per gate
   float* gout = zin + 2 * 4 * NE;                // [2][6][NE]  gates i,f,o,g, y, c of the frame
+  int* failed = reinterpret_cast<int*>(gout + 2 * 6 * NE);   // raised when a bounded wait expired
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // wavefront-uniform, kept in a scalar register
@@ -363,6 +375,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
     io_stage(s_begin);
     if (s_begin + 1 < s_end) io_load(s_begin + 1);
   }
+  if (tid == 0) *failed = 0;
   __syncthreads();
 
   const int prod_first = wave * KW / U, prod_count = KW / U;
@@ -395,7 +408,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
       if (s > s_begin) io_store(s - 1);
       if (s + 2 < s_end) io_load(s + 2);
     }
-    if (__syncthreads_or(fail)) {
+    if (barrier_any_failed(fail, failed)) {      // the plain barrier further down separates this use from the next
       if (tid == 0) st_dev(p.err, 1u);
       return;
     }
@@ -519,6 +532,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
   float* Red = RTs + (size_t)4 * Hq * UG / (BF ? 2 : 1);   // [4][MT][NT][256]
   float* bin = Red + 4 * MT * NT * 256;          // [2][7][NE]  gates i,f,o,g, c, c_prev, dy of the frame
   float* dzo = bin + 2 * 7 * NE;                 // [2][4][NE]  d a of the frame
+  int* failed = reinterpret_cast<int*>(dzo + 2 * 4 * NE);   // two words raised when a bounded wait expired
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // wavefront-uniform, kept in a scalar register
@@ -641,6 +655,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
     io_stage(s_begin);
     if (s_begin + 1 < s_end) io_load(s_begin + 1);
   }
+  if (tid < 2) failed[tid] = 0;
   __syncthreads();
 
   // producers of this wavefront's rows: owners of units [qq*Hq + wave*UW, +UW)
@@ -741,7 +756,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
       if (s > s_begin) io_store(s - 1);
       if (s + 2 < s_end) io_load(s + 2);
     }
-    if (__syncthreads_or(fail)) {
+    if (barrier_any_failed(fail, failed)) {
       if (tid == 0) st_dev(p.err, 1u);
       return;
     }
@@ -761,7 +776,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
         for (int nt = 0; nt < NT; ++nt)
           *reinterpret_cast<floatx4*>(Red + ((wave * MT + mt) * NT + nt) * 256 + lane * 4) = acc[mt][nt];
     }
-    if (__syncthreads_or(fail)) {
+    if (barrier_any_failed(fail, failed + 1)) {
       if (tid == 0) st_dev(p.err, 1u);
       return;
     }
@@ -796,7 +811,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
 #pragma unroll
     for (int e = 0; e < EPT; ++e) Dh[e] = vprev[e] ? g[e] : g[e] + Dh[e];
   }
-  if (__syncthreads_or(fail)) {
+  if (barrier_any_failed(fail, failed)) {
     if (tid == 0) st_dev(p.err, 1u);
     return;
   }
@@ -930,8 +945,8 @@ Plan plan_for(const RecShape& s, int num_cus, size_t max_lds, int nb) {
     if (Hp / 4 / U > 64 || Hq / 4 / U > 64) continue;
     const size_t red = (size_t)4 * MT * NT * 256;
     const size_t ne = (size_t)rows * U;
-    const size_t lf = (size_t)Hp * 16 * NT * es + (red + (2 * 4 + 2 * 6) * ne) * sizeof(float);
-    const size_t lb = (size_t)4 * Hq * UG * es + (red + (2 * 7 + 2 * 4) * ne) * sizeof(float);
+    const size_t lf = (size_t)Hp * 16 * NT * es + (red + (2 * 4 + 2 * 6) * ne) * sizeof(float) + 16;
+    const size_t lb = (size_t)4 * Hq * UG * es + (red + (2 * 7 + 2 * 4) * ne) * sizeof(float) + 16;
     if (lf > max_lds || lb > max_lds) continue;
     // One workgroup per CU: request more than half of the CU's LDS so that the dispatcher cannot
     // stack two of these workgroups on one CU (they would share its matrix cores and every other
