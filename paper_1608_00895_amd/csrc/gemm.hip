@@ -17,6 +17,7 @@
 // writes per-slice partial tiles to scratch and sums them in slice order in a
 // second kernel, so results are bit-reproducible run to run.
 #include "rlstm_internal.h"
+#include <algorithm>
 
 namespace rlstm {
 
@@ -667,6 +668,104 @@ __global__ __launch_bounds__(256) void splitk_reduce4_kernel(const float* __rest
   *dst = s;
 }
 
+// ---------------------------------------------------------------------------
+// Tall and skinny: C[M,N] = sum_k A[k,m] B[k,n] with M <= 80, N <= 160 and K in the hundreds of thousands (the
+// weight gradients of a layer with few units summed over every pixel of a batch of images).  The 128 x 128
+// tiles of the kernels above would be half empty, and this product is bound by the matrix cores, not by HBM
+// (24 FLOP per byte in fp32).  Here the whole of C is one tile of 5 x 10 MFMA blocks: a workgroup of five
+// wavefronts takes a slice of K, wavefront w the two block columns 2w, 2w + 1 of all five block rows (10
+// accumulators, 7 LDS reads per 10 MFMAs).  Both operands are row-contiguous in k, so a chunk of 32 rows is a
+// flat copy: HBM -> registers one chunk ahead -> LDS (row pitches 80 and 176 floats: the four k of an MFMA
+// operand fall into different banks).  Partial sums [slices][M][N] are added by the split-K reduction above.
+// ---------------------------------------------------------------------------
+constexpr int TS_KC = 32;                  // rows of a chunk
+constexpr int TS_MB = 5, TS_NW = 5;        // block rows; wavefronts (two block columns each)
+constexpr int TS_PA = 16 * TS_MB;          // 80: = 16 mod 32
+constexpr int TS_PB = 32 * TS_NW + 16;     // 176: = 16 mod 32
+constexpr int TS_THREADS = 64 * TS_NW;
+constexpr int TS_NLD = (TS_KC * (TS_PA / 4 + 32 * TS_NW / 4) + TS_THREADS - 1) / TS_THREADS;   // float4 per thread and chunk
+struct TsP { const float* A; const float* B; float* partial; int M, N, K, lda, ldb, kchunk; };
+
+__global__ __launch_bounds__(TS_THREADS) void tsmm_tn_f32_kernel(TsP p) {
+  __shared__ __align__(16) float As[TS_KC * TS_PA];
+  __shared__ __align__(16) float Bs[TS_KC * TS_PB];
+  const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, lq = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int M4 = p.M / 4, N4 = p.N / 4, nA = TS_KC * M4, nAB = nA + TS_KC * N4;
+  const int k_begin = blockIdx.x * p.kchunk, k_end = min(p.K, k_begin + p.kchunk);
+
+  for (int i = tid; i < TS_KC * TS_PA; i += TS_THREADS) As[i] = 0.f;   // columns beyond M, N stay zero
+  for (int i = tid; i < TS_KC * TS_PB; i += TS_THREADS) Bs[i] = 0.f;
+
+  // the float4s this thread moves per chunk: row of the chunk, offset in HBM relative to the chunk's first row, offset in LDS
+  int srow[TS_NLD], slds[TS_NLD];
+  long long sg[TS_NLD];
+  bool sa[TS_NLD];
+#pragma unroll
+  for (int i = 0; i < TS_NLD; ++i) {
+    const int idx = tid + i * TS_THREADS;
+    sa[i] = idx < nA;
+    const int j = sa[i] ? idx : idx - nA, w4 = sa[i] ? M4 : N4;
+    srow[i] = idx < nAB ? j / w4 : TS_KC * 2;                          // beyond the chunk: never loaded
+    const int c4 = j % w4;
+    sg[i] = (long long)srow[i] * (sa[i] ? p.lda : p.ldb) + 4 * c4;
+    slds[i] = srow[i] * (sa[i] ? TS_PA : TS_PB) + 4 * c4;
+  }
+  floatx4 st[TS_NLD];
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < TS_NLD; ++i) {
+      st[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+      if (srow[i] < TS_KC && k0 + srow[i] < k_end) {
+        const float* src = sa[i] ? p.A + (size_t)k0 * p.lda + sg[i] : p.B + (size_t)k0 * p.ldb + sg[i];
+        st[i] = *reinterpret_cast<const floatx4*>(src);
+      }
+    }
+  };
+  auto stage = [&]() {
+#pragma unroll
+    for (int i = 0; i < TS_NLD; ++i)
+      if (srow[i] < TS_KC) *reinterpret_cast<floatx4*>((sa[i] ? As : Bs) + slds[i]) = st[i];
+  };
+
+  floatx4 acc[TS_MB][2];
+#pragma unroll
+  for (int mb = 0; mb < TS_MB; ++mb) { acc[mb][0] = floatx4{0.f, 0.f, 0.f, 0.f}; acc[mb][1] = acc[mb][0]; }
+
+  fetch(k_begin);
+  for (int k0 = k_begin; k0 < k_end; k0 += TS_KC) {
+    __syncthreads();                   // the chunk before has been read
+    stage();
+    __syncthreads();
+    if (k0 + TS_KC < k_end) fetch(k0 + TS_KC);
+    const float* a = As + lq * TS_PA + l16;
+    const float* b = Bs + lq * TS_PB + 32 * wave + l16;
+#pragma unroll
+    for (int j = 0; j < TS_KC / 4; ++j) {
+      float av[TS_MB];
+#pragma unroll
+      for (int mb = 0; mb < TS_MB; ++mb) av[mb] = a[4 * j * TS_PA + 16 * mb];
+      const float b0 = b[4 * j * TS_PB], b1 = b[4 * j * TS_PB + 16];
+#pragma unroll
+      for (int mb = 0; mb < TS_MB; ++mb) {
+        acc[mb][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[mb], b0, acc[mb][0], 0, 0, 0);
+        acc[mb][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[mb], b1, acc[mb][1], 0, 0, 0);
+      }
+    }
+  }
+
+  float* out = p.partial + (size_t)blockIdx.x * p.M * p.N;
+#pragma unroll
+  for (int mb = 0; mb < TS_MB; ++mb)
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int m = 16 * mb + 4 * lq + i, n = 32 * wave + 16 * nb + l16;
+        if (m < p.M && n < p.N) out[(size_t)m * p.N + n] = acc[mb][nb][i];
+      }
+}
+
 // Plain product for the stepwise engine: one thread per element of C.
 __global__ __launch_bounds__(256) void gemm_naive_kernel(GemmP p, int transA, int transB, int round_bf16) {
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -952,6 +1051,30 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
     hipLaunchKernelGGL(gemm_naive_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, p,
                        g.transA ? 1 : 0, g.transB ? 1 : 0, g.operand_dtype == 1 ? 1 : 0);
     return hipGetLastError();
+  }
+
+  // few columns on both sides and a long sum: the kernel with one tile for the whole of C
+  if (!bf16 && g.transA && !g.transB && g.M <= 16 * TS_MB && g.N <= 32 * TS_NW && g.K >= 16 * 1024 && g.splitk_ws &&
+      !g.small_footprint && g.M % 4 == 0 && g.N % 4 == 0 && g.lda % 4 == 0 && g.ldb % 4 == 0 && aligned16(g.A) &&
+      aligned16(g.B) && g_gemm_variant != 2) {
+    const size_t per = (size_t)g.M * g.N;
+    int slices = (int)std::min<size_t>(512, std::min<size_t>(g.splitk_floats / per, (size_t)g.K / (4 * TS_KC)));
+    if (slices >= 2) {
+      int kchunk = (g.K + slices - 1) / slices;
+      kchunk = (kchunk + TS_KC - 1) / TS_KC * TS_KC;
+      slices = (g.K + kchunk - 1) / kchunk;
+      TsP t{g.A, g.B, g.splitk_ws, g.M, g.N, g.K, g.lda, g.ldb, kchunk};
+      hipLaunchKernelGGL(tsmm_tn_f32_kernel, dim3((unsigned)slices), dim3(TS_THREADS), 0, stream, t);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+      if (slices >= 64 && per <= (size_t)256 * 1024)
+        hipLaunchKernelGGL(splitk_reduce4_kernel, dim3((unsigned)((per + 63) / 64)), dim3(256), 0, stream,
+                           g.splitk_ws, slices, g.M, g.N, g.C, g.ldc, g.bias, g.accumulate ? 1 : 0);
+      else
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((per + 255) / 256)), dim3(256), 0, stream,
+                           g.splitk_ws, slices, g.M, g.N, g.C, g.ldc, g.bias, g.accumulate ? 1 : 0);
+      return hipGetLastError();
+    }
   }
 
   const int BK = bf16 ? BKH : 16;

@@ -197,6 +197,9 @@ def test_engines_agree_on_medium_stack():
     # one slab, fewer K than a slab, M and N tails, split-K with a K that is no multiple of 4
     (0, 0, 260, 132, 1004), (0, 1, 200, 260, 36), (1, 0, 132, 260, 4098), (1, 1, 260, 136, 520), (0, 0, 128, 128, 4),
     (1, 0, 516, 1028, 20250), (0, 1, 1000, 36, 2000), (1, 1, 4, 4, 8),
+    # few columns on both sides and a long sum (one tile for the whole result): full and ragged tiles, a K that is
+    # no multiple of the 32-row chunk
+    (1, 0, 68, 160, 40000), (1, 0, 80, 160, 16500), (1, 0, 36, 84, 20001), (1, 0, 4, 4, 16384),
 ])
 @pytest.mark.parametrize("variant", [0, 2])
 def test_gemm_against_numpy(case, variant):
