@@ -643,16 +643,17 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 }
 
 // Many slices of a small matrix (weight gradients summed over hundreds of thousands of rows): 64 outputs per
-// workgroup, the slices dealt to 4 groups of threads in contiguous runs, the four sums added in group order.
+// workgroup, the slices dealt to G groups of threads in contiguous runs, the G sums added in group order.
 // The order of additions depends only on the slice count, so results stay bit-reproducible.
-__global__ __launch_bounds__(256) void splitk_reduce4_kernel(const float* __restrict__ partial, int slices,
-                                                              int M, int N, float* __restrict__ C, int ldc,
-                                                              const float* __restrict__ bias, int accumulate) {
-  __shared__ float part[4][64];
+template <int G>
+__global__ __launch_bounds__(64 * G) void splitk_reduce_groups_kernel(const float* __restrict__ partial, int slices,
+                                                                      int M, int N, float* __restrict__ C, int ldc,
+                                                                      const float* __restrict__ bias, int accumulate) {
+  __shared__ float part[G][64];
   const int o = threadIdx.x & 63, grp = threadIdx.x >> 6;
   const size_t idx = (size_t)blockIdx.x * 64 + o;
   const size_t mn = (size_t)M * N;
-  const int per = (slices + 3) / 4;
+  const int per = (slices + G - 1) / G;
   const int z0 = grp * per, z1 = min(slices, z0 + per);
   float s = 0.f;
   if (idx < mn)
@@ -660,12 +661,31 @@ __global__ __launch_bounds__(256) void splitk_reduce4_kernel(const float* __rest
   part[grp][o] = s;
   __syncthreads();
   if (grp != 0 || idx >= mn) return;
-  s = ((part[0][o] + part[1][o]) + part[2][o]) + part[3][o];
+  s = part[0][o];
+#pragma unroll
+  for (int k = 1; k < G; ++k) s += part[k][o];
   const int m = (int)(idx / N), n = (int)(idx % N);
   if (bias) s += bias[n];
   float* dst = C + (size_t)m * ldc + n;
   if (accumulate) s += *dst;
   *dst = s;
+}
+
+// sum of the split-K partial results [slices][M][N] into C
+hipError_t splitk_reduce(hipStream_t stream, const float* partial, int slices, int M, int N, float* C, int ldc,
+                         const float* bias, bool accumulate) {
+  const size_t total = (size_t)M * N;
+  const int acc = accumulate ? 1 : 0;
+  if (slices >= 256 && total <= (size_t)64 * 1024)
+    hipLaunchKernelGGL(splitk_reduce_groups_kernel<16>, dim3((unsigned)((total + 63) / 64)), dim3(1024), 0, stream,
+                       partial, slices, M, N, C, ldc, bias, acc);
+  else if (slices >= 64 && total <= (size_t)256 * 1024)
+    hipLaunchKernelGGL(splitk_reduce_groups_kernel<4>, dim3((unsigned)((total + 63) / 64)), dim3(256), 0, stream,
+                       partial, slices, M, N, C, ldc, bias, acc);
+  else
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+                       partial, slices, M, N, C, ldc, bias, acc);
+  return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------
@@ -1067,13 +1087,7 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
       hipLaunchKernelGGL(tsmm_tn_f32_kernel, dim3((unsigned)slices), dim3(TS_THREADS), 0, stream, t);
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
-      if (slices >= 64 && per <= (size_t)256 * 1024)
-        hipLaunchKernelGGL(splitk_reduce4_kernel, dim3((unsigned)((per + 63) / 64)), dim3(256), 0, stream,
-                           g.splitk_ws, slices, g.M, g.N, g.C, g.ldc, g.bias, g.accumulate ? 1 : 0);
-      else
-        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((per + 255) / 256)), dim3(256), 0, stream,
-                           g.splitk_ws, slices, g.M, g.N, g.C, g.ldc, g.bias, g.accumulate ? 1 : 0);
-      return hipGetLastError();
+      return splitk_reduce(stream, g.splitk_ws, slices, g.M, g.N, g.C, g.ldc, g.bias, g.accumulate);
     }
   }
 
@@ -1136,14 +1150,7 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
   }
   if (e != hipSuccess) return e;
   if (slices > 1) {
-    const size_t total = (size_t)g.M * g.N;
-    if (slices >= 64 && total <= (size_t)256 * 1024)
-      hipLaunchKernelGGL(splitk_reduce4_kernel, dim3((unsigned)((total + 63) / 64)), dim3(256), 0, stream,
-                         g.splitk_ws, slices, g.M, g.N, g.C, g.ldc, g.bias, g.accumulate ? 1 : 0);
-    else
-      hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
-                         g.splitk_ws, slices, g.M, g.N, g.C, g.ldc, g.bias, g.accumulate ? 1 : 0);
-    e = hipGetLastError();
+    e = splitk_reduce(stream, g.splitk_ws, slices, g.M, g.N, g.C, g.ldc, g.bias, g.accumulate);
   }
   return e;
 }

@@ -667,15 +667,13 @@ __global__ __launch_bounds__(256) void mdlstm_zero_pad_kernel(MdZeroParams p) {
 
 // db[d][col] = sum over the images and their bands, in that order
 struct MdDbParams { float* db[4]; const float* dbpart; int B, NB, n; };
-__global__ __launch_bounds__(256) void mdlstm_db_sum_kernel(MdDbParams p) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
+__global__ __launch_bounds__(64) void mdlstm_db_sum_kernel(MdDbParams p) {
+  const int i = blockIdx.x * 64 + threadIdx.x, d = blockIdx.y;
   if (i >= p.n) return;
-  for (int d = 0; d < 4; ++d) {
-    float sum = 0.f;
-    for (int b = 0; b < p.B; ++b)
-      for (int k = 0; k < p.NB; ++k) sum += p.dbpart[((size_t)(b * 4 + d) * p.NB + k) * p.n + i];
-    p.db[d][i] = sum;
-  }
+  float sum = 0.f;
+  for (int b = 0; b < p.B; ++b)
+    for (int k = 0; k < p.NB; ++k) sum += p.dbpart[((size_t)(b * 4 + d) * p.NB + k) * p.n + i];
+  p.db[d][i] = sum;
 }
 
 // clears the handed-row words and the timeout flag before a pass
@@ -850,7 +848,7 @@ hipError_t mdlstm_backward(hipStream_t stream, const MdShape& s, const MdDir* di
   MdDbParams q{};
   for (int d = 0; d < 4; ++d) q.db[d] = db[d];
   q.dbpart = dbpart; q.B = s.B; q.NB = p.NB; q.n = 5 * s.H;
-  hipLaunchKernelGGL(mdlstm_db_sum_kernel, dim3((unsigned)((q.n + 255) / 256)), dim3(256), 0, stream, q);
+  hipLaunchKernelGGL(mdlstm_db_sum_kernel, dim3((unsigned)((q.n + 63) / 64), 4), dim3(64), 0, stream, q);
   return hipGetLastError();
 }
 
