@@ -364,7 +364,7 @@ int stack_backward(const rblstm_desc* d, const float* x, const float* const* par
     for (int k = 0; k < 2; ++k) {
       rc = weight_grads(sb, l, T, B, din, H, k == 0 ? 1 : -1, xin, din, yl + (size_t)k * H, 2 * H,
                         base + lay.zg[k], grads[6 * l + 3 * k + 0], grads[6 * l + 3 * k + 1], skws, skfloats,
-                        !persistent, d->operand_dtype, mode == kShare);
+                        !persistent, d->operand_dtype, mode == kShare && l > 0);   // layer 0's run after the last recurrent piece: nothing beside them
       if (rc != RLSTM_OK) return rc;
     }
     dy = dxl;
