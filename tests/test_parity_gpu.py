@@ -222,6 +222,26 @@ def test_gemm_against_numpy(case, variant):
     assert gh.rel_err(C.cpu().numpy(), ref) < 1e-5, (case, variant)
 
 
+def test_gemm_tall_skinny_many_slices():
+    """The one-tile kernel with 512 K slices and the 16-group sum of the slices, as the two-dimensional layer's
+    weight gradients use it; twice, for bit reproducibility."""
+    M, N, K = 68, 160, 300000
+    rng = _rng(5)
+    A = rng.standard_normal((K, M)).astype(np.float32)
+    Bm = rng.standard_normal((K, N)).astype(np.float32)
+    ref = A.T.astype(np.float64) @ Bm.astype(np.float64)
+    Ad, Bd = gh.dev(A), gh.dev(Bm)
+    ws = torch.empty(512 * M * N * 4, dtype=torch.uint8, device=gh.DEV)
+    outs = []
+    for _ in range(2):
+        C = torch.full((M, N), float("nan"), device=gh.DEV)
+        rl.rlstm_gemm_f32(1, 0, M, N, K, Ad, M, Bd, N, C, N, None, ws)
+        torch.cuda.synchronize()
+        outs.append(C.cpu().numpy())
+    assert gh.rel_err(outs[0], ref) < 1e-5
+    assert np.array_equal(outs[0], outs[1])
+
+
 def test_engine_resolution_and_unsupported_shape():
     d = rl.rlstm_desc(T=4, B=2, D=3, H=16, direction=1, engine=rl.RLSTM_ENGINE_AUTO)
     assert rl.rlstm_resolve_engine(d) == rl.RLSTM_ENGINE_PERSISTENT
