@@ -441,6 +441,8 @@ RLSTM_API int rlstm_set_gemm_variant(int variant);
  * 100 MHz wall clock (0: the default of 4 s).  With a muted workgroup the others' waits expire,
  * every workgroup leaves its loop, the kernels end normally, the results are invalid and
  * rlstm_last_timeout() reports 1.  rlstm_test_hook(-1, 0) restores normal operation.
+ * The scan kernels of the two-dimensional layer obey the same hook: workgroup `mute_workgroup` hands no
+ * row to the neighbouring band, whose wait (default 2 s) then expires.
  */
 RLSTM_API int rlstm_test_hook(int mute_workgroup, uint64_t wait_ticks);
 

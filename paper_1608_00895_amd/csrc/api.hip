@@ -488,6 +488,7 @@ int rlstm_set_batch_groups(int groups) {
 
 int rlstm_test_hook(int mute_workgroup, uint64_t wait_ticks) {
   persistent_test_hook(mute_workgroup, wait_ticks);
+  mdlstm_test_hook(mute_workgroup, wait_ticks);
   return RLSTM_OK;
 }
 

@@ -58,6 +58,8 @@ struct MdParams {
   const float* W[4];       //   [1, 5H] input weights per direction
   const float* bias[4];    //   [5H]
   int Hh, Ww, B, H, S, NB;
+  int mute_wg;             // test hook: this workgroup hands no row on (-1: none)
+  unsigned long long wait_ticks;   // bound of a wait for a handed row, in ticks of the 100 MHz wall clock
 };
 
 // scan coordinates (row r, column q) of image n, direction (du, dv), image width wn -> pixel index
@@ -100,7 +102,8 @@ __device__ __forceinline__ void md_st_word(unsigned long long* q, float v, int d
                      __HIP_MEMORY_SCOPE_AGENT);
 }
 // waits until word w (already loaded once) carries diagonal `diag`; false: gave up
-__device__ __forceinline__ bool md_wait_word(const unsigned long long* q, unsigned long long& w, int diag, unsigned* err) {
+__device__ __forceinline__ bool md_wait_word(const unsigned long long* q, unsigned long long& w, int diag, unsigned* err,
+                                             unsigned long long ticks) {
   unsigned n = 0;
   unsigned long long t0 = 0;
   while ((unsigned)(w >> 32) != (unsigned)(diag + 1)) {
@@ -108,7 +111,7 @@ __device__ __forceinline__ bool md_wait_word(const unsigned long long* q, unsign
     if ((++n & 255u) == 0) {
       const unsigned long long now = wall_clock64();
       if (t0 == 0) t0 = now;
-      else if (now - t0 > kMdWaitTicks) return false;
+      else if (now - t0 > ticks) return false;
       if (__hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) return false;
     }
   }
@@ -191,7 +194,7 @@ __global__ __launch_bounds__(64 * (5 * HT + 1)) void mdlstm_fwd_kernel(MdParams 
   const int s_lo = kBand * band, s_hi = wn > 0 ? kBand * band + rows_here - 1 + wn - 1 : s_lo - 1;
   const int ndiag = Hh + p.Ww;
   // the row above the band (last row of the band above) has pixels on diagonals s_lo - 1 .. s_lo - 1 + wn - 1
-  const bool takes = band > 0, gives = band < p.NB - 1;
+  const bool takes = band > 0, gives = band < p.NB - 1 && (int)blockIdx.x != p.mute_wg;
   const unsigned long long* halo_in = takes ? p.halo + ((size_t)dn * (p.NB - 1) + (band - 1)) * ndiag * 64 : p.halo;
   unsigned long long* halo_out = gives ? p.halo + ((size_t)dn * (p.NB - 1) + band) * ndiag * 64 : p.halo;
   const bool hands = is_halo && lane < HW;     // the lanes that move the handed row in
@@ -207,7 +210,7 @@ __global__ __launch_bounds__(64 * (5 * HT + 1)) void mdlstm_fwd_kernel(MdParams 
     float v = 0.f;
     bool good = true;
     if (takes && sd >= s_lo - 1 && sd <= s_lo - 1 + wn - 1) {
-      good = md_wait_word(halo_in + (size_t)sd * 64 + lane, hw, sd, p.err);
+      good = md_wait_word(halo_in + (size_t)sd * 64 + lane, hw, sd, p.err, p.wait_ticks);
       v = __uint_as_float((unsigned)hw);
     }
     if (lane < HP) hdst[lane] = v; else cdst[lane - HP] = v;
@@ -427,7 +430,7 @@ __global__ __launch_bounds__(64 * (5 * HT + 3)) void mdlstm_bwd_kernel(MdParams 
   const int ndiag = Hh + p.Ww;
   // the row below the band (first row of the band below) has pixels on diagonals b_lo .. b_lo + wn - 1
   const int b_lo = kBand * (band + 1);
-  const bool takes = band < p.NB - 1, gives = band > 0;
+  const bool takes = band < p.NB - 1, gives = band > 0 && (int)blockIdx.x != p.mute_wg;
   const unsigned long long* halo_in = takes ? p.halo + ((size_t)dn * (p.NB - 1) + band) * ndiag * 192 : p.halo;
   unsigned long long* halo_out = gives ? p.halo + ((size_t)dn * (p.NB - 1) + (band - 1)) * ndiag * 192 : p.halo;
 
@@ -449,7 +452,7 @@ __global__ __launch_bounds__(64 * (5 * HT + 3)) void mdlstm_bwd_kernel(MdParams 
       if (w >= HW) continue;
       float v = 0.f;
       if (have) {
-        good = md_wait_word(halo_in + (size_t)sd * 192 + w, hw[k], sd, p.err) && good;
+        good = md_wait_word(halo_in + (size_t)sd * 192 + w, hw[k], sd, p.err, p.wait_ticks) && good;
         v = __uint_as_float((unsigned)hw[k]);
       }
       if (w < NG) dzb[kBand * LDZ + w] = v; else dcu_dst[kBand * LDH + w - NG] = v;
@@ -732,6 +735,9 @@ hipError_t md_launch(K kernel, int grid, int block, size_t lds, hipStream_t stre
   return hipLaunchKernel(fn, dim3((unsigned)grid), dim3((unsigned)block), args, lds, stream);
 }
 
+int g_md_mute_wg = -1;
+unsigned long long g_md_wait_ticks = 0;
+
 MdParams md_params(const MdShape& s, const MdDir* dirs, const int32_t* widths) {
   MdParams p{};
   for (int d = 0; d < 4; ++d) {
@@ -739,6 +745,8 @@ MdParams md_params(const MdShape& s, const MdDir* dirs, const int32_t* widths) {
   }
   p.widths = widths; p.Hh = s.Hh; p.Ww = s.Ww; p.B = s.B; p.H = s.H; p.S = s.S;
   p.NB = (s.Hh + kBand - 1) / kBand;
+  p.mute_wg = g_md_mute_wg;
+  p.wait_ticks = g_md_wait_ticks ? g_md_wait_ticks : kMdWaitTicks;
   return p;
 }
 
@@ -753,6 +761,11 @@ bool md_vec(const MdShape& s, const MdDir* dirs, const float* yy) {
   return v;
 }
 }  // namespace
+
+void mdlstm_test_hook(int mute_workgroup, unsigned long long wait_ticks) {
+  g_md_mute_wg = mute_workgroup;
+  g_md_wait_ticks = wait_ticks;
+}
 
 bool mdlstm_supported(const MdShape& s) { return s.Hh >= 1 && s.Hh <= kBand * kMaxBands && s.H >= 1 && s.H <= 32; }
 

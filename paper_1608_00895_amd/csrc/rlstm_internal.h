@@ -129,6 +129,8 @@ struct MdDir {
   const float* Rv;    // [H, 5H]
 };
 bool mdlstm_supported(const MdShape& s);
+// test hook: workgroup `mute_workgroup` (-1: none) hands no row on; wait bound in 100 MHz ticks (0: default)
+void mdlstm_test_hook(int mute_workgroup, unsigned long long wait_ticks);
 // dirs[4] in the order (du, dv) = (+,+), (+,-), (-,+), (-,-); y, dy: [P, 4H]
 // halo: mdlstm_halo_words() 64-bit words of scratch (rows handed between bands); err: timeout flag
 size_t mdlstm_halo_words(const MdShape& s);

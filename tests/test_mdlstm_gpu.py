@@ -117,6 +117,40 @@ def test_mdlstm_padding_values_have_no_influence():
         assert np.array_equal(a["dx"][:, :w, n], b["dx"][:, :w, n])
 
 
+def test_mdlstm_failure_path_forced_from_the_host():
+    """A band that never receives its neighbour's row: the wait is bounded (here to 2 ms), every workgroup leaves
+    its loop, the kernels end normally and the timeout is reported; the next call is correct."""
+    import time
+    wl = synth.make_image_workload("t", Hh=37, B=2, D=1, H=16, w_lo=6, w_hi=20, wscale=0.2, seed=80)
+    desc = rl.rmdlstm_desc(Hh=wl.Hh, Ww=wl.Ww, B=wl.B, D=wl.D, H=wl.H, operand_dtype=0)
+    x = torch.from_numpy(wl.x).to(DEV)
+    widths = torch.from_numpy(wl.widths).to(DEV)
+    params = [torch.from_numpy(a).to(DEV) for p in wl.params for a in p]
+    grads = [torch.zeros_like(p) for p in params]
+    y = torch.zeros((wl.Hh, wl.Ww, wl.B, 4 * wl.H), device=DEV)
+    reserve = torch.zeros((rl.rmdlstm_reserve_bytes(desc) // 4,), device=DEV)
+    ws = torch.zeros((rl.rmdlstm_workspace_bytes(desc) // 4,), device=DEV)
+    dy = torch.from_numpy(wl.G).to(DEV)
+    try:
+        rl.rlstm_test_hook(1, 200_000)
+        t0 = time.time()
+        rl.mdlstm_fwd(desc, x, params, widths, y, reserve, ws)
+        torch.cuda.synchronize()
+        assert time.time() - t0 < 5.0
+        assert rl.rlstm_last_timeout(ws) == 1
+        t0 = time.time()
+        rl.mdlstm_bwd(desc, x, params, widths, reserve, dy, None, grads, ws)
+        torch.cuda.synchronize()
+        assert time.time() - t0 < 5.0
+        assert rl.rlstm_last_timeout(ws) == 1
+    finally:
+        rl.rlstm_test_hook(-1, 0)
+    got = run_layer(wl, want_dx=False)
+    ref = oracle_layer(wl)
+    ref32 = oracle_layer(wl, dtype=np.float32)
+    check(got, ref, "after a forced timeout", ref32)
+
+
 def test_mdlstm_argument_errors():
     d = rl.rmdlstm_desc(Hh=257, Ww=4, B=1, D=1, H=8, operand_dtype=0)
     assert rl.rmdlstm_reserve_bytes(d) == 0
