@@ -239,7 +239,7 @@ int stack_forward(const rblstm_desc* d, const float* x, const float* const* para
         g.A = in + f0 * B * din; g.lda = din; g.B = params[6 * l + 3 * k + 0]; g.ldb = 4 * H;
         g.C = base + lay.zg[k] + f0 * B * 4 * H; g.ldc = 4 * H; g.bias = params[6 * l + 3 * k + 2];
         g.naive = !persistent; g.operand_dtype = d->operand_dtype;
-        g.small_footprint = mode == kShare;
+        g.small_footprint = mode == kShare && pc > 0;   // the first piece's product runs while the chain waits for it
         ProfScope ps(sb, 0, l, 1, 0, gemm_flop(g));
         RLSTM_TRY(gemm(sb, g));
       }
@@ -337,7 +337,7 @@ int stack_backward(const rblstm_desc* d, const float* x, const float* const* par
             g.B = params[6 * l + 3 * k + 0] + (size_t)tk * H * 4 * H; g.ldb = 4 * H;
             g.C = dxl + f0 * B * din + (size_t)tk * H; g.ldc = din; g.accumulate = (k == 1);
             g.naive = !persistent; g.operand_dtype = d->operand_dtype;
-            g.small_footprint = mode == kShare;
+            g.small_footprint = mode == kShare && pc > 0;   // the first piece's product runs while the chain waits for it
             ProfScope ps(sb, 3, l, 1, 0, gemm_flop(g));
             RLSTM_TRY(gemm(sb, g));
           }

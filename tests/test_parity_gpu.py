@@ -461,10 +461,20 @@ def test_bounded_waits_turn_a_silent_workgroup_into_an_error_flag():
 def test_stack_results_do_not_depend_on_how_the_passes_are_cut(first):
     """Two streams + persistent engine: the recurrent passes are cut into pieces (first, first, 2*first, ...)
     that the feeding matrix products run ahead of.  Every cut must give the oracle's results, and the
-    same bits as the uncut passes except for the order of the bias gradient's sums."""
+    same bits as the uncut passes except for the order of the bias gradient's sums.  (The bits are compared with
+    one product kernel for every piece: by default the first piece's product, which runs while the chain waits
+    for it, uses the pipelined kernel and the others the plain one, and the two add in different orders.)"""
     wl = synth.small_blstm(seed=21, L=3, B=9, D=11, H=36, len_lo=0, len_hi=61, T=61)
     ref = gh.oracle_stack(wl)
     try:
+        rl.rlstm_set_first_piece(first)
+        dflt = gh.StackRun(wl, engine=rl.RLSTM_ENGINE_PERSISTENT)
+        dflt.step()
+        rd = dflt.results()
+        assert gh.rel_err(rd["y"], ref["y"]) < TOL_FWD and gh.rel_err(rd["dx"], ref["dx"]) < TOL_GRAD
+        for i, (g, r) in enumerate(zip(rd["grads"], ref["grads"])):
+            assert gh.rel_err(g, r) < TOL_GRAD, (i, gh.rel_err(g, r))
+        rl.rlstm_set_gemm_variant(2)
         rl.rlstm_set_first_piece(0)
         base = gh.StackRun(wl, engine=rl.RLSTM_ENGINE_PERSISTENT)
         base.step()
@@ -477,6 +487,7 @@ def test_stack_results_do_not_depend_on_how_the_passes_are_cut(first):
         again = run.results()
     finally:
         rl.rlstm_set_first_piece(128)
+        rl.rlstm_set_gemm_variant(0)
     assert gh.rel_err(got["y"], ref["y"]) < TOL_FWD
     assert gh.rel_err(got["dx"], ref["dx"]) < TOL_GRAD
     for i, (g, r) in enumerate(zip(got["grads"], ref["grads"])):
