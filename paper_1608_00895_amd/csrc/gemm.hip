@@ -692,18 +692,21 @@ hipError_t splitk_reduce(hipStream_t stream, const float* partial, int slices, i
 // Tall and skinny: C[M,N] = sum_k A[k,m] B[k,n] with M <= 80, N <= 160 and K in the hundreds of thousands (the
 // weight gradients of a layer with few units summed over every pixel of a batch of images).  The 128 x 128
 // tiles of the kernels above would be half empty, and this product is bound by the matrix cores, not by HBM
-// (24 FLOP per byte in fp32).  Here the whole of C is one tile of 5 x 10 MFMA blocks: a workgroup of five
-// wavefronts takes a slice of K, wavefront w the two block columns 2w, 2w + 1 of all five block rows (10
-// accumulators, 7 LDS reads per 10 MFMAs).  Both operands are row-contiguous in k, so a chunk of 32 rows is a
-// flat copy: HBM -> registers one chunk ahead -> LDS (row pitches 80 and 176 floats: the four k of an MFMA
-// operand fall into different banks).  Partial sums [slices][M][N] are added by the split-K reduction above.
+// (24 FLOP per byte in fp32).  Here the whole of C is one tile of 5 x 10 MFMA blocks: a workgroup of ten
+// wavefronts takes a slice of K, wavefront w block column w of all five block rows (5 accumulators, 6 LDS reads
+// per 5 MFMAs); two workgroups a CU put five wavefronts on every SIMD, which keeps its matrix core fed (five
+// wavefronts with two block columns each left the SIMDs with 3, 3, 2, 2 wavefronts and were 4 % slower).  Both
+// operands are row-contiguous in k, so a chunk of 32 rows is a flat copy: HBM -> registers one chunk ahead ->
+// LDS (row pitches 80 and 176 floats: the four k of an MFMA operand fall into different banks).  Partial sums
+// [slices][M][N] are added by the split-K reduction above.
 // ---------------------------------------------------------------------------
 constexpr int TS_KC = 32;                  // rows of a chunk
-constexpr int TS_MB = 5, TS_NW = 5;        // block rows; wavefronts (two block columns each)
+constexpr int TS_MB = 5, TS_NW = 10;       // block rows; wavefronts (one block column each)
+constexpr int TS_NBW = 1;                  // block columns per wavefront
 constexpr int TS_PA = 16 * TS_MB;          // 80: = 16 mod 32
-constexpr int TS_PB = 32 * TS_NW + 16;     // 176: = 16 mod 32
+constexpr int TS_PB = 16 * TS_NBW * TS_NW + 16;   // 176: = 16 mod 32
 constexpr int TS_THREADS = 64 * TS_NW;
-constexpr int TS_NLD = (TS_KC * (TS_PA / 4 + 32 * TS_NW / 4) + TS_THREADS - 1) / TS_THREADS;   // float4 per thread and chunk
+constexpr int TS_NLD = (TS_KC * (TS_PA / 4 + 16 * TS_NBW * TS_NW / 4) + TS_THREADS - 1) / TS_THREADS;   // float4 per thread and chunk
 struct TsP { const float* A; const float* B; float* partial; int M, N, K, lda, ldb, kchunk; };
 
 __global__ __launch_bounds__(TS_THREADS) void tsmm_tn_f32_kernel(TsP p) {
@@ -748,9 +751,11 @@ __global__ __launch_bounds__(TS_THREADS) void tsmm_tn_f32_kernel(TsP p) {
       if (srow[i] < TS_KC) *reinterpret_cast<floatx4*>((sa[i] ? As : Bs) + slds[i]) = st[i];
   };
 
-  floatx4 acc[TS_MB][2];
+  floatx4 acc[TS_MB][TS_NBW];
 #pragma unroll
-  for (int mb = 0; mb < TS_MB; ++mb) { acc[mb][0] = floatx4{0.f, 0.f, 0.f, 0.f}; acc[mb][1] = acc[mb][0]; }
+  for (int mb = 0; mb < TS_MB; ++mb)
+#pragma unroll
+    for (int nb = 0; nb < TS_NBW; ++nb) acc[mb][nb] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   fetch(k_begin);
   for (int k0 = k_begin; k0 < k_end; k0 += TS_KC) {
@@ -759,18 +764,20 @@ __global__ __launch_bounds__(TS_THREADS) void tsmm_tn_f32_kernel(TsP p) {
     __syncthreads();
     if (k0 + TS_KC < k_end) fetch(k0 + TS_KC);
     const float* a = As + lq * TS_PA + l16;
-    const float* b = Bs + lq * TS_PB + 32 * wave + l16;
+    const float* b = Bs + lq * TS_PB + 16 * TS_NBW * wave + l16;
 #pragma unroll
     for (int j = 0; j < TS_KC / 4; ++j) {
       float av[TS_MB];
 #pragma unroll
       for (int mb = 0; mb < TS_MB; ++mb) av[mb] = a[4 * j * TS_PA + 16 * mb];
-      const float b0 = b[4 * j * TS_PB], b1 = b[4 * j * TS_PB + 16];
+      float bv[TS_NBW];
 #pragma unroll
-      for (int mb = 0; mb < TS_MB; ++mb) {
-        acc[mb][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[mb], b0, acc[mb][0], 0, 0, 0);
-        acc[mb][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[mb], b1, acc[mb][1], 0, 0, 0);
-      }
+      for (int nb = 0; nb < TS_NBW; ++nb) bv[nb] = b[4 * j * TS_PB + 16 * nb];
+#pragma unroll
+      for (int mb = 0; mb < TS_MB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < TS_NBW; ++nb)
+          acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[mb], bv[nb], acc[mb][nb], 0, 0, 0);
     }
   }
 
@@ -778,10 +785,10 @@ __global__ __launch_bounds__(TS_THREADS) void tsmm_tn_f32_kernel(TsP p) {
 #pragma unroll
   for (int mb = 0; mb < TS_MB; ++mb)
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
+    for (int nb = 0; nb < TS_NBW; ++nb)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const int m = 16 * mb + 4 * lq + i, n = 32 * wave + 16 * nb + l16;
+        const int m = 16 * mb + 4 * lq + i, n = 16 * TS_NBW * wave + 16 * nb + l16;
         if (m < p.M && n < p.N) out[(size_t)m * p.N + n] = acc[mb][nb][i];
       }
 }
@@ -1074,7 +1081,7 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
   }
 
   // few columns on both sides and a long sum: the kernel with one tile for the whole of C
-  if (!bf16 && g.transA && !g.transB && g.M <= 16 * TS_MB && g.N <= 32 * TS_NW && g.K >= 16 * 1024 && g.splitk_ws &&
+  if (!bf16 && g.transA && !g.transB && g.M <= 16 * TS_MB && g.N <= 16 * TS_NBW * TS_NW && g.K >= 16 * 1024 && g.splitk_ws &&
       !g.small_footprint && g.M % 4 == 0 && g.N % 4 == 0 && g.lda % 4 == 0 && g.ldb % 4 == 0 && aligned16(g.A) &&
       aligned16(g.B) && g_gemm_variant != 2) {
     const size_t per = (size_t)g.M * g.N;
