@@ -338,6 +338,8 @@ int stack_backward(const rblstm_desc* d, const float* x, const float* const* par
             g.C = dxl + f0 * B * din + (size_t)tk * H; g.ldc = din; g.accumulate = (k == 1);
             g.naive = !persistent; g.operand_dtype = d->operand_dtype;
             g.small_footprint = mode == kShare && pc > 0;   // the first piece's product runs while the chain waits for it
+            // ... and has too few tiles for the chip (128 at 128 steps x 32 sequences x 500 units): K is split as well
+            if (pc == 0) { g.splitk_ws = skws; g.splitk_floats = skfloats; }
             ProfScope ps(sb, 3, l, 1, 0, gemm_flop(g));
             RLSTM_TRY(gemm(sb, g));
           }

@@ -1108,7 +1108,9 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
   const int tiles_m = (g.M + tile_m - 1) / tile_m;
   const int tiles = tiles_m * p.tiles_n;
   int slices = 1;
-  if (g.splitk_ws && g.K >= 4 * 1024 && tiles < 512) {
+  // K is split when the tiles alone leave CUs idle: always for long sums, and for sums of a few thousand when the
+  // tiles do not even fill half the chip
+  if (g.splitk_ws && tiles < 512 && (g.K >= 4 * 1024 || (g.K >= 1536 && tiles <= 160))) {
     slices = (1024 + tiles - 1) / tiles;
     const int max_by_k = g.K / 512;
     if (slices > max_by_k) slices = max_by_k;
