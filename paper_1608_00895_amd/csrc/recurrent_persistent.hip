@@ -43,8 +43,10 @@ typedef int intx4 __attribute__((ext_vector_type(4)));
 namespace {
 
 constexpr unsigned long long kDefaultWaitTicks = 400000000ull;   // 4 s of the 100 MHz wall clock
-// 16-byte loads in flight per lane: a multiple of the batch tiles MT, so that a group of loads starts at a whole k-step
-template <int MT> constexpr int load_group() { return MT == 3 ? 12 : 16; }
+// 16-byte loads in flight per lane: a multiple of the batch tiles MT, so that a group of loads starts at a whole k-step.
+// Three row tiles (the 48-row kernels, which run with nothing beside them and can afford the registers) fetch all 24
+// chunks of a 512-unit layer at once: a second group of loads would add a second load latency to every step.
+template <int MT> constexpr int load_group() { return MT == 3 ? 24 : 16; }
 constexpr int kAuxSc1 = 16;             // buffer-load cache policy: device scope
 
 // ---- bounded spinning --------------------------------------------------------
