@@ -119,8 +119,9 @@ __device__ __forceinline__ bool md_wait_word(const unsigned long long* q, unsign
 }
 
 // VEC: H is a multiple of 4, so every group of four units starts 16-byte aligned in all tensors.
-// Workgroup = (band, direction, image); 2 row tiles x HT unit halves, one wavefront each.
-// Forward scan.  One wavefront per (gate, 16 units): 5 * HT wavefronts.  A step's product
+// Workgroup = (band of 16 rows, direction, image).
+// Forward scan.  One wavefront per (gate, 16 units): 5 * HT wavefronts, and one more that takes the rows handed from
+// the band above.  A step's product
 // a^T = [R_u ; R_v]^T [h_up | h_left]^T is then 16 MFMAs per wavefront instead of 80, and a lane applies one
 // nonlinearity to its four units instead of five; the wavefronts of the output gate pick up the other four
 // activated gates from LDS (same lane, one 16-byte read each) and do the cell update.  The lane's 16 matrix
@@ -128,6 +129,8 @@ __device__ __forceinline__ bool md_wait_word(const unsigned long long* q, unsign
 // XIN: the input has one value per pixel (grayscale images): the input part b + x W of the pre-activation is formed
 // here from x and this lane's weights and biases instead of being read from zg, and x is written next to
 // [h_up | h_left] for the weight-gradient product.
+// The gate wavefronts store (gates, c, y, [h_up | h_left]) and therefore never load inside the loop: a wavefront's
+// memory counter retires in order, so waiting for a load would mean waiting for the stores issued before it.
 template <int HT, bool VEC, int XM>
 __global__ __launch_bounds__(64 * (5 * HT + 1)) void mdlstm_fwd_kernel(MdParams p) {
   constexpr bool XIN = XM != 0;        // XM: 0 input part read from zg, 1 x read from HBM, 2 the band's x staged in LDS
