@@ -23,6 +23,7 @@
 // lane per (row, unit).  d a overwrites the gates in place; [h_up | h_left] of every pixel is kept from
 // the forward pass so that d R_u and d R_v are one whole-image product each afterwards.
 #include "rlstm_internal.h"
+#include <algorithm>
 #include <type_traits>
 
 namespace rlstm {
@@ -397,6 +398,24 @@ __global__ __launch_bounds__(64 * (5 * HT + 3)) void mdlstm_bwd_kernel(MdParams 
   float* dcv = dcu + 2 * (kBand + 1) * LDH;          // same with f_v
   int* gaveup = reinterpret_cast<int*>(dcv + 2 * (kBand + 1) * LDH);   // raised when a bounded wait expired
 
+  // Workgroups beyond the scan's own (they land on the CUs the scan leaves idle, and come last in the grid) clear
+  // d a of the pixel slots beyond the images' widths, which the products over all pixel slots read.
+  const int nscan = 4 * p.B * p.NB;
+  if ((int)blockIdx.x >= nscan) {
+    const int cols = 5 * p.H;
+    for (int pair = (int)blockIdx.x - nscan; pair < p.Hh * p.B; pair += (int)gridDim.x - nscan) {
+      const int nn = pair % p.B, u = pair / p.B;
+      const int wn = min(max(p.widths[nn], 0), p.Ww);
+      const int total = (p.Ww - wn) * cols;
+      for (int idx = threadIdx.x; idx < total; idx += NTH) {
+        const int v = wn + idx / cols, col = idx % cols;
+        const size_t o = (((size_t)u * p.Ww + v) * p.B + nn) * cols + col;
+#pragma unroll
+        for (int dd = 0; dd < 4; ++dd) p.zg[dd][o] = 0.f;
+      }
+    }
+    return;
+  }
   // bands below come first in the grid
   const int dn = blockIdx.x % (4 * p.B), band = p.NB - 1 - blockIdx.x / (4 * p.B);
   const int d = dn & 3, n = dn >> 2;
@@ -656,21 +675,6 @@ __global__ __launch_bounds__(64 * (5 * HT + 3)) void mdlstm_bwd_kernel(MdParams 
   }
 }
 
-// zeros in the pixel slots beyond every image's width of four [P, cols] tensors: a launch of its own over the whole
-// chip (a scan's workgroup would spend longer on the slots of a narrow image than on the image)
-struct MdZeroParams { float* a[4]; const int32_t* widths; int Hh, Ww, B, cols; };
-__global__ __launch_bounds__(256) void mdlstm_zero_pad_kernel(MdZeroParams p) {
-  const int n = blockIdx.x % p.B, u = blockIdx.x / p.B;
-  const int wn = min(max(p.widths[n], 0), p.Ww);
-  const int total = (p.Ww - wn) * p.cols;
-  for (int idx = threadIdx.x; idx < total; idx += 256) {
-    const int v = wn + idx / p.cols, col = idx % p.cols;
-    const size_t o = (((size_t)u * p.Ww + v) * p.B + n) * p.cols + col;
-#pragma unroll
-    for (int d = 0; d < 4; ++d) p.a[d][o] = 0.f;
-  }
-}
-
 // db[d][col] = sum over the images and their bands, in that order
 struct MdDbParams { float* db[4]; const float* dbpart; int B, NB, n; };
 __global__ __launch_bounds__(64) void mdlstm_db_sum_kernel(MdDbParams p) {
@@ -846,16 +850,9 @@ hipError_t mdlstm_backward(hipStream_t stream, const MdShape& s, const MdDir* di
   hipError_t e = md_clear(stream, s, halo, err, 192);
   if (e != hipSuccess) return e;
   const bool vec = md_vec(s, dirs, dy);
-  const int grid = 4 * s.B * p.NB;
-  {
-    // d a = 0 beyond the images' widths (the products over all pixel slots read it)
-    MdZeroParams z{};
-    for (int d = 0; d < 4; ++d) z.a[d] = dirs[d].zg;
-    z.widths = widths; z.Hh = s.Hh; z.Ww = s.Ww; z.B = s.B; z.cols = 5 * s.H;
-    hipLaunchKernelGGL(mdlstm_zero_pad_kernel, dim3((unsigned)(s.Hh * s.B)), dim3(256), 0, stream, z);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
+  // the scan's workgroups, then as many again (at most 128) that clear the padding
+  const int nscan = 4 * s.B * p.NB;
+  const int grid = nscan + std::min(128, std::max(1, s.Hh * s.B));
   if (s.H <= 16) e = vec ? md_launch(mdlstm_bwd_kernel<1, true>, grid, 64 * 8, md_lds_bwd(1), stream, p)
                          : md_launch(mdlstm_bwd_kernel<1, false>, grid, 64 * 8, md_lds_bwd(1), stream, p);
   else e = vec ? md_launch(mdlstm_bwd_kernel<2, true>, grid, 64 * 13, md_lds_bwd(2), stream, p)
