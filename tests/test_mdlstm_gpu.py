@@ -80,6 +80,8 @@ def check(got, ref, what, ref32=None):
     dict(Hh=6, B=2, D=40, H=12, w_lo=4, w_hi=11, wscale=0.2),   # wide input: dW as a product of its own
     dict(Hh=33, B=3, D=2, H=16, w_lo=2, w_hi=12, wscale=0.2),   # two bands of rows, one row in the second
     dict(Hh=100, B=2, D=1, H=24, w_lo=5, w_hi=30, wscale=0.12), # four bands handing rows to each other
+    dict(Hh=256, B=1, D=1, H=8, w_lo=3, w_hi=6, wscale=0.1),    # the largest height: a chain of 16 bands
+    dict(Hh=250, B=2, D=3, H=28, w_lo=2, w_hi=5, wscale=0.08),  # 16 bands, the last one partly filled, input part from the product
 ])
 def test_mdlstm_shapes_against_oracle(shape):
     wl = synth.make_image_workload("t", bias_scale=0.2, seed=50 + shape["Hh"] + shape["H"], **shape)
