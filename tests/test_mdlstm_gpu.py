@@ -82,6 +82,8 @@ def check(got, ref, what, ref32=None):
     dict(Hh=100, B=2, D=1, H=24, w_lo=5, w_hi=30, wscale=0.12), # four bands handing rows to each other
     dict(Hh=256, B=1, D=1, H=8, w_lo=3, w_hi=6, wscale=0.1),    # the largest height: a chain of 16 bands
     dict(Hh=250, B=2, D=3, H=28, w_lo=2, w_hi=5, wscale=0.08),  # 16 bands, the last one partly filled, input part from the product
+    dict(Hh=3, B=1, D=1, H=8, w_lo=1380, w_hi=1400, wscale=0.05),   # one value per pixel, too wide for the band's x to be staged in LDS
+    dict(Hh=20, B=1, D=1, H=20, w_lo=1350, w_hi=1360, wscale=0.05), # the same with two bands and 32 padded units
 ])
 def test_mdlstm_shapes_against_oracle(shape):
     wl = synth.make_image_workload("t", bias_scale=0.2, seed=50 + shape["Hh"] + shape["H"], **shape)
