@@ -289,8 +289,10 @@ def bench_stream(args):
         kernels.append(e)
         log(e)
     dom = max(kernels, key=lambda e: e["ms_per_step"])
+    # bytes per launch from the rocprofv3 FETCH_SIZE + WRITE_SIZE runs (profiles/lstm_stream_paper_stream_hbm_counters.md)
+    measured_traffic = {"recurrent_forward": 0.397e9 + 0.393e9, "recurrent_backward": 1.088e9 + 0.655e9}
     roofline = {"kernel": dom["kernel"], "bound": "mfma", "achieved": dom["tflops"], "peak": PEAK_FP32_MFMA_TFLOPS,
-                "unit": "TFLOP/s", "frac": dom["tflops"] / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                "unit": "TFLOP/s", "frac": dom["tflops"] / PEAK_FP32_MFMA_TFLOPS, "traffic": measured_traffic.get(dom["kernel"]),
                 "avg_launch_ms": dom["avg_ms"], "steps_per_launch": dom.get("steps_per_launch"), "step_us": dom.get("step_us"),
                 "note": "the recurrent kernels are bound by the serial chain of dependent steps (see step_us); priced "
                         "against the fp32 MFMA peak with 2*B*H*4H FLOP per step"}
@@ -493,11 +495,14 @@ def main():
     measured_traffic = {"recurrent_forward": 0.391e9 + 0.481e9, "recurrent_backward": 1.074e9 + 0.713e9,
                         "input_projection": 0.135e9 + 0.070e9, "input_gradient": 0.112e9 + 0.017e9,
                         "weight_gradient": 0.572e9 + 0.062e9, "recurrent_weight_gradient": 0.572e9 + 0.062e9}
+    # the same for the paper's batch shape (profiles/train_step_paper_shape_hbm_counters.md)
+    paper_shape_traffic = {"recurrent_forward": 0.948e9 + 0.913e9, "recurrent_backward": 2.764e9 + 2.257e9}
     default_knobs = args.first_piece is None and args.batch_groups is None and not args.one_stream and args.engine == 0
     peak = PEAK_FP32_MFMA_TFLOPS if wl.operand_dtype == 0 else PEAK_BF16_MFMA_TFLOPS
     roofline = {"kernel": dom["kernel"], "bound": "mfma", "achieved": dom["tflops"], "peak": peak,
                 "unit": "TFLOP/s", "frac": dom["tflops"] / peak,
-                "traffic": measured_traffic.get(dom["kernel"]) if args.workload == "config3" and default_knobs else None,
+                "traffic": (measured_traffic if args.workload == "config3" else paper_shape_traffic).get(dom["kernel"])
+                if args.workload in ("config3", "paper_chunks", "paper_train") and default_knobs else None,
                 "avg_launch_ms": dom["avg_ms"],
                 "steps_per_launch": dom.get("steps_per_launch"),
                 "note": "the recurrent kernels are bound by the serial chain of T dependent steps "
