@@ -121,8 +121,9 @@ __device__ __forceinline__ bool md_wait_word(const unsigned long long* q, unsign
 
 // VEC: H is a multiple of 4, so every group of four units starts 16-byte aligned in all tensors.
 // Workgroup = (band of 16 rows, direction, image).
-// Forward scan.  One wavefront per (gate, 16 units): 5 * HT wavefronts, and one more that takes the rows handed from
-// the band above.  A step's product
+// Forward scan.  One wavefront per (gate, 16 units): 5 * HT wavefronts, one more that takes the rows handed from
+// the band above and one that hands this band's last row to the band below (so that no gate wavefront, which the
+// next step waits for, spends time on it).  A step's product
 // a^T = [R_u ; R_v]^T [h_up | h_left]^T is then 16 MFMAs per wavefront instead of 80, and a lane applies one
 // nonlinearity to its four units instead of five; the wavefronts of the output gate pick up the other four
 // activated gates from LDS (same lane, one 16-byte read each) and do the cell update.  The lane's 16 matrix
@@ -133,10 +134,10 @@ __device__ __forceinline__ bool md_wait_word(const unsigned long long* q, unsign
 // The gate wavefronts store (gates, c, y, [h_up | h_left]) and therefore never load inside the loop: a wavefront's
 // memory counter retires in order, so waiting for a load would mean waiting for the stores issued before it.
 template <int HT, bool VEC, int XM>
-__global__ __launch_bounds__(64 * (5 * HT + 1)) void mdlstm_fwd_kernel(MdParams p) {
+__global__ __launch_bounds__(64 * (5 * HT + 2)) void mdlstm_fwd_kernel(MdParams p) {
   constexpr bool XIN = XM != 0;        // XM: 0 input part read from zg, 1 x read from HBM, 2 the band's x staged in LDS
   static_assert(kTiles == 1, "one 16-row tile per band");
-  constexpr int NTH = 64 * (5 * HT + 1);   // one more wavefront takes the rows handed from the band above
+  constexpr int NTH = 64 * (5 * HT + 2);   // two more wavefronts: one takes the rows handed from the band above, one hands this band's last row on
   constexpr int HP = 16 * HT;          // padded units
   constexpr int KS = 2 * HP / 4;       // MFMA k-steps
   constexpr int LDH = HP + 1;
@@ -157,13 +158,13 @@ __global__ __launch_bounds__(64 * (5 * HT + 1)) void mdlstm_fwd_kernel(MdParams 
   // Wavefront 5 HT only moves the handed rows in: it issues the only global loads of the scan.  A wavefront's memory
   // counter retires in order, so a wavefront that waits for a load waits for every store it issued before, and
   // a store to HBM takes about as long as a step; the gate wavefronts, which store, therefore never load.
-  const bool is_halo = wave == 5 * HT;
-  const int g = is_halo ? 5 : wave / HT, ht = wave % HT;     // gate (i, f_u, f_v, o, g) and group of 16 units of this wavefront
+  const bool is_halo = wave == 5 * HT, is_sender = wave == 5 * HT + 1;
+  const int g = (is_halo || is_sender) ? 5 : wave / HT, ht = wave % HT;     // gate (i, f_u, f_v, o, g) and group of 16 units of this wavefront
   const int lr = l16;                          // row inside the band
   const int r = kBand * band + lr;             // row of this lane
   const int jm = 16 * ht + l16;                // unit whose column this lane feeds to the MFMA (A operand row)
   const int j0 = 16 * ht + 4 * lq;             // first of the four units this lane holds (accumulator rows)
-  const int nv = is_halo ? 0 : min(max(H - j0, 0), 4);       // how many of them exist
+  const int nv = (is_halo || is_sender) ? 0 : min(max(H - j0, 0), 4);       // how many of them exist
   const int wn = min(max(p.widths[n], 0), p.Ww);
   const int rows_here = min(Hh - kBand * band, kBand);
   const int slot = g < 3 ? g : 3;              // where this gate's activations go in gact (the output gate has none)
@@ -175,7 +176,7 @@ __global__ __launch_bounds__(64 * (5 * HT + 1)) void mdlstm_fwd_kernel(MdParams 
   for (int ks = 0; ks < KS; ++ks) {
     const int k = 4 * ks + lq, kk = k % HP;
     const float* R = k < HP ? p.Ru[d] : p.Rv[d];
-    ra[ks] = (!is_halo && kk < H && jm < H) ? R[(size_t)kk * 5 * H + g * H + jm] : 0.f;
+    ra[ks] = (!is_halo && !is_sender && kk < H && jm < H) ? R[(size_t)kk * 5 * H + g * H + jm] : 0.f;
   }
   for (int idx = tid; idx < 2 * (kBand + 1) * LDH; idx += NTH) { hb[idx] = 0.f; cb[idx] = 0.f; }
   if (tid == 0) *gaveup = 0;
@@ -202,7 +203,7 @@ __global__ __launch_bounds__(64 * (5 * HT + 1)) void mdlstm_fwd_kernel(MdParams 
   const unsigned long long* halo_in = takes ? p.halo + ((size_t)dn * (p.NB - 1) + (band - 1)) * ndiag * 64 : p.halo;
   unsigned long long* halo_out = gives ? p.halo + ((size_t)dn * (p.NB - 1) + band) * ndiag * 64 : p.halo;
   const bool hands = is_halo && lane < HW;     // the lanes that move the handed row in
-  const bool sends = wave == 1 && lane < HW;   // the lanes that hand this band's last row on (a wavefront that never loads)
+  const bool sends = is_sender && lane < HW;   // the lanes that hand this band's last row on (a wavefront that never loads)
 
   // h, c of the row above on diagonal sd -> entry 0 of the given buffers; returns false when a wait expired
   unsigned long long hw = 0;
@@ -265,6 +266,17 @@ __global__ __launch_bounds__(64 * (5 * HT + 1)) void mdlstm_fwd_kernel(MdParams 
       if (!halo_take(s, hb + (s & 1) * (kBand + 1) * LDH, cb + (s & 1) * (kBand + 1) * LDH)) *gaveup = 1;
       __syncthreads();
       if (*gaveup) return;
+    }
+  } else if (is_sender) {
+    for (int s = s_lo; s <= s_hi; ++s) {
+      __syncthreads();
+      __syncthreads();
+      if (*gaveup) return;
+      if (gives && sends) {            // last row of the band to the band below
+        const float* hcur = hb + (s & 1) * (kBand + 1) * LDH;
+        const float* ccur = cb + (s & 1) * (kBand + 1) * LDH;
+        md_st_word(halo_out + (size_t)s * 64 + lane, lane < HP ? hcur[kBand * LDH + lane] : ccur[kBand * LDH + lane - HP], s);
+      }
     }
   } else
   for (int s = s_lo; s <= s_hi; ++s) {
@@ -335,8 +347,6 @@ __global__ __launch_bounds__(64 * (5 * HT + 1)) void mdlstm_fwd_kernel(MdParams 
       if (tid == 0) __hip_atomic_store(p.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       return;
     }
-    if (gives && sends)                // last row of the band to the band below
-      md_st_word(halo_out + (size_t)s * 64 + lane, lane < HP ? hcur[kBand * LDH + lane] : ccur[kBand * LDH + lane - HP], s);
     if (ok) {
       st4<VEC>(zgd + pix * 5 * H + g * H + j0, act, nv);
       if (g == 3) {
@@ -809,9 +819,9 @@ hipError_t mdlstm_forward(hipStream_t stream, const MdShape& s, const MdDir* dir
   const bool xstage = xin && md_lds_fwd(2) + md_lds_xstage(s.Ww) <= (size_t)96 * 1024;
   const size_t xlds = xstage ? md_lds_xstage(s.Ww) : 0;
 #define RLSTM_MD_FWD(HT_, VEC_, XIN_) \
-  (!(XIN_) ? md_launch(mdlstm_fwd_kernel<HT_, VEC_, 0>, grid, 64 * (5 * HT_ + 1), md_lds_fwd(HT_), stream, p)                \
-   : !xstage ? md_launch(mdlstm_fwd_kernel<HT_, VEC_, 1>, grid, 64 * (5 * HT_ + 1), md_lds_fwd(HT_), stream, p)              \
-             : md_launch(mdlstm_fwd_kernel<HT_, VEC_, 2>, grid, 64 * (5 * HT_ + 1), md_lds_fwd(HT_) + xlds, stream, p))
+  (!(XIN_) ? md_launch(mdlstm_fwd_kernel<HT_, VEC_, 0>, grid, 64 * (5 * HT_ + 2), md_lds_fwd(HT_), stream, p)                \
+   : !xstage ? md_launch(mdlstm_fwd_kernel<HT_, VEC_, 1>, grid, 64 * (5 * HT_ + 2), md_lds_fwd(HT_), stream, p)              \
+             : md_launch(mdlstm_fwd_kernel<HT_, VEC_, 2>, grid, 64 * (5 * HT_ + 2), md_lds_fwd(HT_) + xlds, stream, p))
   if (s.H <= 16) {
     if (xin) return vec ? RLSTM_MD_FWD(1, true, true) : RLSTM_MD_FWD(1, false, true);
     return vec ? RLSTM_MD_FWD(1, true, false) : RLSTM_MD_FWD(1, false, false);
