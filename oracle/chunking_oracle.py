@@ -2,9 +2,9 @@
 
 THIS IS TEST INFRASTRUCTURE (see lstm_oracle.py); plain Python loops, no code shared with the HIP path.
 
-What the paper fixes (RETURNN, arXiv 1608.00895): Sec. 3 — sequences can be cut into possibly overlapping
+What the paper fixes (RETURNN, arXiv 1608.00895): Sec. 4 — sequences can be cut into possibly overlapping
 segments of constant length so that batches carry little zero padding; Sec. 6 — the experiments use segments
-of 250 frames, "padding zero-frames if required", 81 segments per batch.
+of 250 frames, with zero frames appended where a sequence ends inside a segment, 81 segments per batch.
 Reading where the paper is silent: a sequence of n frames yields the segments starting at frames
 0, step, 2*step, ... as long as the start lies inside the sequence; a segment holds ``size`` frames or, at
 the end of the sequence, the frames that are left (the rest of its slot in the batch is zero padding);

@@ -15,8 +15,8 @@ What the paper fixes (RETURNN, arXiv 1608.00895)
   Schmidhuber); the paper prints no cell equations.
 * Sec. 4.2: the pre-activation has a non-recurrent part (input times a weight
   matrix, computable for all frames of the minibatch at once) and a recurrent
-  part (previous output times a recurrent matrix), followed by a "gating
-  mechanism"; the backward pass first runs back through time, then forms the
+  part (previous output times a recurrent matrix), followed by the gating
+  step; the backward pass first runs back through time, then forms the
   gradients with respect to weights and inputs.
 * Sec. 5: tensors are [time, batch, feature]; an index tensor says for each
   (time, batch) whether the frame belongs to the sequence, so that zero

@@ -3,7 +3,7 @@ turn the stack's forward + backward pass into a training step.
 
 THIS IS TEST INFRASTRUCTURE (see lstm_oracle.py); numpy float64, no code shared with the HIP path.
 
-What the paper fixes (RETURNN, arXiv 1608.00895): Sec. 4.1 — output layers with the cross-entropy loss
+What the paper fixes (RETURNN, arXiv 1608.00895): Sec. 3.2 — output layers with the cross-entropy loss
 exist; Sec. 6 — the experiments classify every frame into one of 1501 classes and report the share of
 misclassified frames; Sec. 4.3 — updates by stochastic gradient descent with a classical momentum term or
 with Adam (cited), gradients of a batch are sums (not scaled by the batch size); Sec. 5 — frames

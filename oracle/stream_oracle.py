@@ -4,8 +4,8 @@ back-propagation through time truncated at the segment boundaries.
 
 THIS IS TEST INFRASTRUCTURE (see lstm_oracle.py); numpy float64, no code shared with the HIP path.
 
-What the paper fixes (RETURNN, arXiv 1608.00895): Sec. 4.1 — recurrent layers can be connected by passing
-the final state of one on to another; Sec. 3 — cutting sequences into segments of constant length gives
+What the paper fixes (RETURNN, arXiv 1608.00895): Sec. 3.2 — recurrent layers can be connected by passing
+the final state of one on to another; Sec. 4 — cutting sequences into segments of constant length gives
 up the context that the end states of the segments hold.  This mode keeps that context: it is the
 composition "final state of segment s = initial state of segment s + 1" of the layer of Sec. 4.2, so the
 oracle is that composition written out with the layer oracle (lstm_forward / lstm_backward), nothing else.

@@ -1,4 +1,4 @@
-// Chunking (Sec. 3 of the RETURNN paper): sequences of very different lengths are cut into
+// Chunking (Sec. 4 of the RETURNN paper): sequences of very different lengths are cut into
 // segments of constant length, possibly overlapping, so that a minibatch of segments carries
 // little zero padding; the experiments (Sec. 6) use segments of 250 frames, zero-padded where
 // a sequence ends, 81 segments per batch.

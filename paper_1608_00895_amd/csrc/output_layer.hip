@@ -1,5 +1,5 @@
 // Frame-wise softmax / cross-entropy output layer on top of the stack and the parameter updates
-// (Secs. 4.1, 4.3 and 6 of the RETURNN paper: cross-entropy output layer, 1501 classes per frame,
+// (Secs. 3.2, 4.3 and 6 of the RETURNN paper: cross-entropy output layer, 1501 classes per frame,
 // frame error rate; SGD with momentum or Adam; batch gradients are sums; padded frames have no
 // influence).  The affine map and its gradients are the MFMA products of gemm.hip; here are the
 // row-wise softmax / loss / error kernel, the deterministic reductions and the update kernels.

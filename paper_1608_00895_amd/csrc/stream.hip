@@ -1,6 +1,6 @@
 // Helpers of the streaming mode: a unidirectional LSTM stack reads its sequences segment by segment, every
-// segment starting from the final state of the one before (Sec. 4.1: final states passed on from one
-// recurrent layer to another; Sec. 3: cutting into segments otherwise gives up the context in the end
+// segment starting from the final state of the one before (Sec. 3.2: final states passed on from one
+// recurrent layer to another; Sec. 4: cutting into segments otherwise gives up the context in the end
 // states).  The layer kernels are those of the one-segment path; here are only the per-segment length
 // table, the accumulation of the bias gradients over the segments and a fill.
 #include "rlstm_internal.h"

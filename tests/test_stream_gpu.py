@@ -135,7 +135,7 @@ def test_stream_bad_arguments():
 
 @pytest.mark.parametrize("engine", ENGINES)
 def test_encoder_decoder_hand_off(engine):
-    """Two layers connected by the final state (Sec. 4.1): the decoder starts from the encoder's (hT, cT); in the
+    """Two layers connected by the final state (Sec. 3.2): the decoder starts from the encoder's (hT, cT); in the
     backward pass the decoder's (dh0, dc0) arrive at the encoder as (dhT, dcT).  Existing entry points lstm_fwd /
     lstm_bwd; the oracle is the same composition of the layer oracle."""
     rng = _rng(9300)
