@@ -27,9 +27,11 @@
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers (HIP, fp32 unless said otherwise,
  *     16-byte aligned recommended) owned by the caller.  Descriptors are HOST
- *     structs.  The library allocates and frees no device memory, never
- *     synchronises the device and only enqueues work on the streams passed in
- *     (a null stream handle is HIP's default stream).
+ *     structs.  The library allocates and frees no device memory and only
+ *     enqueues work on the streams passed in (a null stream handle is HIP's
+ *     default stream).  It never synchronises the device, with two exceptions
+ *     that say so: rlstm_last_timeout() and the measurement aid
+ *     rlstm_exchange_floor().
  *   - Inputs are read-only.  Outputs are overwritten, never accumulated into.
  *   - workspace must hold rlstm_workspace_bytes() (resp. rblstm_workspace_bytes())
  *     bytes; its contents need no initialisation and are undefined afterwards.
@@ -40,8 +42,14 @@
  *   - The recurrent kernels are persistent: all of their workgroups must be
  *     resident at once, so the call fails with RLSTM_ERESIDENT when the device
  *     cannot hold them.  Their waits on each other are bounded; if one ever
- *     expires the kernel stops stepping and sets a flag that
- *     rlstm_last_timeout() reports.
+ *     expires the kernel stops stepping and raises a flag in the first word of
+ *     the workspace that rlstm_last_timeout() reports.  The flag is cleared by
+ *     the entry points that start a pass (lstm_fwd, blstm_stack_fwd,
+ *     blstm_stack_fwd_bwd, lstm_stream_fwd_bwd, mdlstm_fwd) and by nothing else:
+ *     the backward entry points (lstm_bwd, blstm_stack_bwd, mdlstm_bwd) leave it,
+ *     and their recurrent kernels do nothing while it is raised, so one read
+ *     after the backward call tells about both passes.  The backward entry
+ *     points must therefore be given the workspace of the forward call.
  */
 #ifndef RLSTM_H
 #define RLSTM_H
@@ -128,6 +136,7 @@ RLSTM_API int lstm_fwd(const rlstm_desc* desc, const float* x, const float* W, c
  *   x, W, R, seq_lens, h0, c0  as given to lstm_fwd
  *   y, c                       as written by lstm_fwd
  *   reserve                    in/out: consumed (holds d loss / d a afterwards)
+ *   workspace                  the one given to lstm_fwd (its first word carries the timeout flag)
  *   dy  [T,B,ldy]  in, gradient w.r.t. y (rows beyond a sequence's length are ignored)
  *   dhT, dcT [B,H] in, may be null (= zeros): gradient w.r.t. hT, cT
  *   dx  [T,B,ldx]  out, may be null (skipped); 0 at invalid frames
@@ -182,7 +191,7 @@ RLSTM_API int blstm_stack_fwd(const rblstm_desc* desc, const float* x, const flo
 
 /*
  * rlstm_gemm_f32 - the whole-minibatch matrix product the layer is built on
- * (Sec. 4.2: "a single matrix multiplication for the whole mini-batch"), exposed
+ * (Sec. 4.2: the non-recurrent part of all frames of a minibatch is one product), exposed
  * for measurement and testing:  C[M,N] = op(A) op(B) (+ bias[n] on every row).
  *   trans_a == 0: A is [M,K] with row stride lda;  != 0: A is stored [K,M]
  *   trans_b == 0: B is [K,N] with row stride ldb;  != 0: B is stored [N,K]
@@ -233,9 +242,13 @@ RLSTM_API int rlstm_copy_f32(float* dst, const float* src, size_t n, void* hip_s
 
 /* Reads (with a blocking device-to-host copy) the timeout flag that the
  * persistent kernels keep at the start of `workspace`: 0 = no bounded wait
- * expired since the last call that used this workspace, 1 = one did and the
- * results are invalid, negative = RLSTM_E* code.  Synchronises the device. */
+ * expired since the last forward entry point that used this workspace, 1 = one
+ * did and the results are invalid, negative = RLSTM_E* code.  The flag is not
+ * changed.  rlstm_last_timeout synchronises the DEVICE first;
+ * rlstm_last_timeout_on waits only for `hip_stream` (the stream the calls in
+ * question were enqueued on: for the stack entry points stream a). */
 RLSTM_API int rlstm_last_timeout(const void* workspace);
+RLSTM_API int rlstm_last_timeout_on(const void* workspace, void* hip_stream);
 
 /*
  * Tuning knob of blstm_stack_fwd_bwd with two streams and the persistent engine.  Each layer's
@@ -268,7 +281,7 @@ RLSTM_API int rlstm_set_first_piece(int steps);
  * gates, cell states and predecessor outputs from mdlstm_fwd to mdlstm_bwd, which overwrites it;
  * workspace (rmdlstm_workspace_bytes) is scratch.  The caller owns all buffers; nothing is
  * allocated and the device is not synchronised.
- * The rows of a scan are dealt out to workgroups in bands of 32 that hand one row per
+ * The rows of a scan are dealt out to workgroups in bands of 16 that hand one row per
  * anti-diagonal to their neighbour through the workspace; all such waits are bounded (2 s) and
  * rlstm_last_timeout(workspace) tells whether one expired (the results are then invalid).
  * Limits of the kernels: Hh <= 256, H <= 32, operand_dtype 0; other shapes return RLSTM_ERESIDENT
@@ -287,7 +300,7 @@ RLSTM_API int mdlstm_bwd(const rmdlstm_desc* d, const float* x, const float* con
                          void* hip_stream);
 
 /*
- * Chunking (Sec. 3: sequences whose lengths differ a lot are cut into segments of constant
+ * Chunking (Sec. 4: sequences whose lengths differ a lot are cut into segments of constant
  * length, possibly overlapping, so that a minibatch carries little zero padding, at the price of
  * the context across segment borders; Sec. 6 trains on segments of 250 frames, zero-padded where a
  * sequence ends, 81 per batch).
@@ -313,9 +326,9 @@ RLSTM_API int rlstm_chunk_gather(const float* x, int T, int B, int D, int ldx, c
 /*
  * Streaming mode: a unidirectional (direction +1) stack of L LSTM layers reads its sequences in S
  * consecutive segments of Tc frames; every layer starts a segment from the final state it reached
- * in the segment before (Sec. 4.1: final states handed on from one recurrent layer to another),
+ * in the segment before (Sec. 3.2: final states handed on from one recurrent layer to another),
  * so the forward result is that of the uncut sequences and the context that plain cutting into
- * segments gives up (Sec. 3) is kept.  Back-propagation through time is truncated at the segment
+ * segments gives up (Sec. 4) is kept.  Back-propagation through time is truncated at the segment
  * boundaries: the backward pass of a segment takes the segment's initial state as a constant,
  * no gradient arrives at its final state, and the gradients of the segments are summed.  Memory:
  * one segment of activations, whatever S is.  Calling with S = 1 once per segment, passing the
@@ -347,7 +360,8 @@ RLSTM_API int lstm_stream_fwd_bwd(const rlstm_stream_desc* desc, const float* x,
 /*
  * softmax_ce_fwd_bwd - the frame-wise output layer of the acoustic model (Sec. 6: a softmax
  * output layer over the tied-state classes on top of the BLSTM stack, trained with the
- * cross-entropy criterion; the frame error rate is what Table 3 reports) and its gradients:
+ * cross-entropy criterion, one of the loss layers of Sec. 3.2; the frame error rate is what Table 1
+ * reports) and its gradients:
  *   z = y Wo + bo;  p = softmax(z) per frame;  loss = sum over valid frames of -log p[label];
  *   errors = number of valid frames whose largest p (lowest index on ties) is not the label;
  *   dz = p - onehot(label) on valid frames, 0 elsewhere;  dy = dz Wo^T;  dWo = y^T dz;

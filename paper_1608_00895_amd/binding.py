@@ -23,7 +23,8 @@ RLSTM_ENGINE_STEPWISE = 2
 
 EXPORTS = [
     "rlstm_reserve_bytes", "rlstm_workspace_bytes", "rblstm_reserve_bytes", "rblstm_workspace_bytes",
-    "lstm_fwd", "lstm_bwd", "blstm_stack_fwd_bwd", "blstm_stack_fwd", "blstm_stack_bwd",
+    "lstm_fwd", "lstm_bwd", "rlstm_last_timeout_on",
+    "blstm_stack_fwd_bwd", "blstm_stack_fwd", "blstm_stack_bwd",
     "rlstm_ce_workspace_bytes", "softmax_ce_fwd_bwd", "rlstm_sgd_momentum_step", "rlstm_adam_step",
     "rlstm_stream_reserve_bytes", "rlstm_stream_workspace_bytes", "lstm_stream_fwd_bwd",
     "rlstm_gemm_f32", "rlstm_gemm_bf16", "rlstm_copy_f32", "rlstm_profile_enable", "rlstm_profile_read", "rlstm_last_timeout", "rlstm_test_hook", "rlstm_set_first_piece", "rlstm_set_batch_groups", "rlstm_set_gemm_variant", "rlstm_set_overlap_mode", "rmdlstm_reserve_bytes", "rmdlstm_workspace_bytes", "mdlstm_fwd", "mdlstm_bwd", "rlstm_chunk_plan", "rlstm_chunk_gather", "rblstm_plan", "rlstm_exchange_floor_bytes", "rlstm_exchange_floor", "rlstm_resolve_engine", "rlstm_strerror", "rlstm_version",
@@ -87,6 +88,8 @@ def lib() -> ctypes.CDLL:
         L.lstm_fwd.argtypes = [ctypes.POINTER(rlstm_desc)] + [vp] * 14
         L.lstm_bwd.restype = ip
         L.lstm_bwd.argtypes = [ctypes.POINTER(rlstm_desc)] + [vp] * 20
+        L.rlstm_last_timeout_on.restype = ip
+        L.rlstm_last_timeout_on.argtypes = [vp, vp]
         L.blstm_stack_fwd_bwd.restype = ip
         L.blstm_stack_fwd_bwd.argtypes = [ctypes.POINTER(rblstm_desc), vp, ctypes.POINTER(vp), vp, vp, vp,
                                           ctypes.POINTER(vp), vp, vp, vp, vp, vp]
@@ -214,6 +217,10 @@ def rlstm_resolve_engine(desc: rlstm_desc) -> int:
 
 def rlstm_last_timeout(workspace: torch.Tensor) -> int:
     return int(lib().rlstm_last_timeout(_ptr(workspace)))
+
+
+def rlstm_last_timeout_on(workspace: torch.Tensor, stream=None) -> int:
+    return int(lib().rlstm_last_timeout_on(_ptr(workspace), _stream(stream)))
 
 
 def lstm_fwd(desc, x, W, R, b, h0, c0, seq_lens, y, c, hT, cT, reserve, workspace, stream=None, check=True) -> int:

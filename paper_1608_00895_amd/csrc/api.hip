@@ -65,7 +65,8 @@ hipEvent_t prof_event() {
 struct ProfScope {
   hipStream_t st; hipEvent_t b = nullptr; bool on;
   // steps: recurrent steps covered (0 for a matrix product); flop: algorithmic FLOP of the group
-  ProfScope(hipStream_t s, int kind, int layer, int ndir, int steps, double flop) : st(s), on(g_prof_on) {
+  ProfScope(hipStream_t s, int kind, int layer, int ndir, int steps, double flop, bool enabled = true)
+      : st(s), on(g_prof_on && enabled) {
     if (!on) return;
     hipEvent_t a = prof_event(); b = prof_event();
     if (!a || !b) { on = false; return; }
@@ -432,6 +433,15 @@ int rlstm_last_timeout(const void* workspace) {
   if (hipDeviceSynchronize() != hipSuccess) { (void)hipGetLastError(); return RLSTM_EHIP; }
   unsigned v = 0;
   if (hipMemcpy(&v, workspace, sizeof(v), hipMemcpyDeviceToHost) != hipSuccess) { (void)hipGetLastError(); return RLSTM_EHIP; }
+  return v != 0 ? 1 : 0;
+}
+
+int rlstm_last_timeout_on(const void* workspace, void* hip_stream) {
+  if (!workspace) return RLSTM_ENULL;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  unsigned v = 0;
+  if (hipMemcpyAsync(&v, workspace, sizeof(v), hipMemcpyDeviceToHost, st) != hipSuccess ||
+      hipStreamSynchronize(st) != hipSuccess) { (void)hipGetLastError(); return RLSTM_EHIP; }
   return v != 0 ? 1 : 0;
 }
 
@@ -950,14 +960,17 @@ int rlstm_gemm_bf16(int trans_a, int trans_b, int M, int N, int K,
   return gemm_entry(1, trans_a, trans_b, M, N, K, A, lda, B, ldb, C, ldc, bias, splitk_ws, splitk_ws_bytes, hip_stream);
 }
 
-int lstm_fwd(const rlstm_desc* d, const float* x, const float* W, const float* R, const float* b,
-             const float* h0, const float* c0, const int32_t* seq_lens,
-             float* y, float* c, float* hT, float* cT, void* reserve, void* workspace, void* hip_stream) {
+// timed = false: no timing events are created, whatever rlstm_profile_enable() says
+static int lstm_fwd_impl(const rlstm_desc* d, const float* x, const float* W, const float* R, const float* b,
+                         const float* h0, const float* c0, const int32_t* seq_lens,
+                         float* y, float* c, float* hT, float* cT, void* reserve, void* workspace, size_t workspace_bytes,
+                         void* hip_stream, bool timed) {
   int rc = check_desc(d);
   if (rc != RLSTM_OK) return rc;
   if (!x || !W || !R || !b || !seq_lens || !y || !c || !reserve || !workspace) return RLSTM_ENULL;
   const int ldx = d->ldx ? d->ldx : d->D, ldy = d->ldy ? d->ldy : d->H;
   RecShape s{d->T, d->B, d->H, ldy, 1, d->operand_dtype};
+  if (workspace_bytes < kFlagBytes + rec_workspace_bytes(s)) return RLSTM_ESIZE;
   const int eng = resolve_engine(d->engine, s);
   if (eng < 0) return eng;
   const bool persistent = eng == RLSTM_ENGINE_PERSISTENT;
@@ -973,15 +986,21 @@ int lstm_fwd(const rlstm_desc* d, const float* x, const float* W, const float* R
   g.A = x; g.lda = ldx; g.B = W; g.ldb = 4 * d->H; g.C = zg; g.ldc = 4 * d->H; g.bias = b;
   g.naive = !persistent; g.operand_dtype = d->operand_dtype;
   {
-    ProfScope ps(st, 0, 0, 1, 0, gemm_flop(g));
+    ProfScope ps(st, 0, 0, 1, 0, gemm_flop(g), timed);
     RLSTM_TRY(gemm(st, g));
   }
   RecFwdDir dir{zg, R, h0, c0, y, c, hT, cT, d->direction};
   {
-    ProfScope ps(st, 1, 0, 1, d->T, rec_flop(s, d->T));
+    ProfScope ps(st, 1, 0, 1, d->T, rec_flop(s, d->T), timed);
     RLSTM_TRY(rec_forward(st, s, &dir, seq_lens, ws + kFlagBytes, flag, persistent, &resident_err, 0, d->T));
   }
   return RLSTM_OK;
+}
+
+int lstm_fwd(const rlstm_desc* d, const float* x, const float* W, const float* R, const float* b,
+             const float* h0, const float* c0, const int32_t* seq_lens,
+             float* y, float* c, float* hT, float* cT, void* reserve, void* workspace, void* hip_stream) {
+  return lstm_fwd_impl(d, x, W, R, b, h0, c0, seq_lens, y, c, hT, cT, reserve, workspace, (size_t)-1, hip_stream, true);
 }
 
 int lstm_bwd(const rlstm_desc* d, const float* x, const float* W, const float* R,
@@ -1008,7 +1027,8 @@ int lstm_bwd(const rlstm_desc* d, const float* x, const float* W, const float* R
   float* skws = reinterpret_cast<float*>(recws + align_up(rec_workspace_bytes(s), 256));
   const size_t skfloats = splitk_floats(D > H ? D : H, H);
 
-  RLSTM_TRY(clear_flag(st, flag));
+  // the timeout flag is left as lstm_fwd left it: a forward pass that gave up keeps the backward kernels from
+  // running, and one read of the flag after this call tells about both passes
   RecBwdDir dir{zg, R, c, c0, dy, dhT, dcT, dh0, dc0, db, d->direction};
   {
     ProfScope ps(st, 2, 0, 1, T, rec_flop(s, T));

@@ -696,11 +696,12 @@ __global__ __launch_bounds__(64) void mdlstm_db_sum_kernel(MdDbParams p) {
   p.db[d][i] = sum;
 }
 
-// clears the handed-row words and the timeout flag before a pass
+// clears the handed-row words before a pass; the forward pass (err != null) also clears the timeout flag, the
+// backward pass leaves it: a timeout of the forward pass stays visible after the backward call
 __global__ __launch_bounds__(256) void mdlstm_clear_kernel(unsigned long long* words, size_t n, unsigned* err) {
   const size_t gsz = (size_t)gridDim.x * 256;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += gsz) words[i] = 0ull;
-  if (blockIdx.x == 0 && threadIdx.x == 0) *err = 0u;
+  if (err && blockIdx.x == 0 && threadIdx.x == 0) *err = 0u;
 }
 
 // x [P, D] into columns [2H, 2H + D) of the four [P, S] predecessor-output arrays, so that
@@ -857,7 +858,7 @@ hipError_t mdlstm_backward(hipStream_t stream, const MdShape& s, const MdDir* di
   if (!mdlstm_supported(s)) return hipErrorInvalidValue;
   MdParams p = md_params(s, dirs, widths);
   p.dy = dy; p.dbpart = dbpart; p.halo = halo; p.err = err;
-  hipError_t e = md_clear(stream, s, halo, err, 192);
+  hipError_t e = md_clear(stream, s, halo, nullptr, 192);
   if (e != hipSuccess) return e;
   const bool vec = md_vec(s, dirs, dy);
   // the scan's workgroups, then as many again (at most 128) that clear the padding
