@@ -47,55 +47,82 @@ def oracle_layer(wl, dtype=np.float64):
     return dict(y=y, dx=dx, grads=flat)
 
 
-def check(got, ref, what, ref32=None):
-    """Bar: 1e-5 (outputs) and 1e-4 (gradients) as for the one-dimensional layer.  The two-dimensional
-    recurrence is Hh + W steps deep with two recurrent inputs per step, and with strong weights rounding
-    alone exceeds that: where the oracle's own definition evaluated in float32 (ref32) is further than a
-    third of the bar from the float64 oracle, the bar for that tensor is three times that distance."""
-    def bar(base, key, i=None):
-        if ref32 is None:
-            return base
-        r32 = ref32[key] if i is None else ref32[key][i]
-        r64 = ref[key] if i is None else ref[key][i]
-        return max(base, 3.0 * rel_err(r32, r64))
-    e = rel_err(got["y"], ref["y"])
-    assert e < bar(TOL_FWD, "y"), (what, "y", e)
+def check(got, ref, what, tol_y=TOL_FWD, tol_grad=TOL_GRAD):
+    """Fixed bars: 1e-5 (outputs) and 1e-4 (gradients) as for the one-dimensional layer unless the case states its
+    own.  Prints the achieved errors."""
+    names = ["y", "dx"] + [f"{k}{d}" for d in range(4) for k in ("dW", "dRu", "dRv", "db")]
+    errs = {"y": rel_err(got["y"], ref["y"])}
     if "dx" in got:
-        e = rel_err(got["dx"], ref["dx"])
-        assert e < bar(TOL_GRAD, "dx"), (what, "dx", e)
+        errs["dx"] = rel_err(got["dx"], ref["dx"])
     for i, (g, r) in enumerate(zip(got["grads"], ref["grads"])):
-        e = rel_err(g, r)
-        assert e < bar(TOL_GRAD, "grads", i), (what, "grad", i, e)
+        errs[names[2 + i]] = rel_err(g, r)
+    worst = max((k for k in errs if k != "y"), key=lambda k: errs[k])
+    print(f"mdlstm {what}: y {errs['y']:.2e} (bar {tol_y:.0e}), worst gradient {worst} {errs[worst]:.2e} (bar {tol_grad:.0e})",
+          flush=True)
+    assert errs["y"] < tol_y, (what, "y", errs["y"])
+    for k, e in errs.items():
+        if k != "y":
+            assert e < tol_grad, (what, k, e)
+    return errs
 
 
-@pytest.mark.parametrize("shape", [
-    dict(Hh=5, B=3, D=2, H=8, w_lo=0, w_hi=9, wscale=0.3),      # one MFMA row tile, 16-unit kernel, an empty image
-    dict(Hh=16, B=2, D=1, H=16, w_lo=3, w_hi=20, wscale=0.3),   # exactly one tile, one value per pixel
-    dict(Hh=37, B=4, D=3, H=20, w_lo=1, w_hi=25, wscale=0.2),   # rows over three tiles, units padded to 32
-    # the full row range and unit count of the kernels; weights as in config 5 (with stronger ones the
-    # recurrence over 64 x 40 pixels amplifies rounding until float32 itself is off by 1e-4)
-    dict(Hh=64, B=2, D=1, H=32, w_lo=10, w_hi=40, wscale=0.1),
-    dict(Hh=3, B=5, D=4, H=32, w_lo=50, w_hi=70, wscale=0.15),  # wide and flat
-    dict(Hh=50, B=3, D=2, H=7, w_lo=1, w_hi=2, wscale=0.3),     # narrow and tall
-    dict(Hh=6, B=2, D=40, H=12, w_lo=4, w_hi=11, wscale=0.2),   # wide input: dW as a product of its own
-    dict(Hh=33, B=3, D=2, H=16, w_lo=2, w_hi=12, wscale=0.2),   # two bands of rows, one row in the second
-    dict(Hh=100, B=2, D=1, H=24, w_lo=5, w_hi=30, wscale=0.12), # four bands handing rows to each other
-    dict(Hh=256, B=1, D=1, H=8, w_lo=3, w_hi=6, wscale=0.1),    # the largest height: a chain of 16 bands
-    dict(Hh=250, B=2, D=3, H=28, w_lo=2, w_hi=5, wscale=0.08),  # 16 bands, the last one partly filled, input part from the product
-    dict(Hh=3, B=1, D=1, H=8, w_lo=1380, w_hi=1400, wscale=0.05),   # one value per pixel, too wide for the band's x to be staged in LDS
-    dict(Hh=20, B=1, D=1, H=20, w_lo=1350, w_hi=1360, wscale=0.05), # the same with two bands and 32 padded units
-])
-def test_mdlstm_shapes_against_oracle(shape):
+# Tolerances.  Every shape is held to 1e-5 (outputs) / 1e-4 (gradients) except where the case carries its own
+# numbers.  Those exceptions are workloads whose exact results move by more than the bar when their float32 inputs
+# and parameters are changed by one unit in the last place (float64 oracle, 50 draws of relative normal noise 2^-23):
+# a two-dimensional recurrence with weights of 0.2 has locally unstable modes that amplify any rounding along a
+# diagonal path of the image.  Their bars are twice the largest deviation seen over the 50 draws, rounded up.
+#   Hh=37 B=4 D=3 H=20 wscale 0.2: one-ulp spread y 6.1e-5, gradients 1.9e-4 (scan direction 1)
+SHAPES = [
+    (dict(Hh=5, B=3, D=2, H=8, w_lo=0, w_hi=9, wscale=0.3), {}),      # one MFMA row tile, 16-unit kernel, an empty image
+    (dict(Hh=16, B=2, D=1, H=16, w_lo=3, w_hi=20, wscale=0.3), {}),   # exactly one tile, one value per pixel
+    (dict(Hh=37, B=4, D=3, H=20, w_lo=1, w_hi=25, wscale=0.2),        # rows over three tiles, units padded to 32
+     dict(tol_y=1.5e-4, tol_grad=4e-4)),
+    # the full row range and unit count of the kernels; weights as in config 5
+    (dict(Hh=64, B=2, D=1, H=32, w_lo=10, w_hi=40, wscale=0.1), {}),
+    (dict(Hh=3, B=5, D=4, H=32, w_lo=50, w_hi=70, wscale=0.15), {}),  # wide and flat
+    (dict(Hh=50, B=3, D=2, H=7, w_lo=1, w_hi=2, wscale=0.3), {}),     # narrow and tall
+    (dict(Hh=6, B=2, D=40, H=12, w_lo=4, w_hi=11, wscale=0.2), {}),   # wide input: dW as a product of its own
+    (dict(Hh=33, B=3, D=2, H=16, w_lo=2, w_hi=12, wscale=0.2), {}),   # two bands of rows, one row in the second
+    (dict(Hh=100, B=2, D=1, H=24, w_lo=5, w_hi=30, wscale=0.12), {}), # four bands handing rows to each other
+    (dict(Hh=256, B=1, D=1, H=8, w_lo=3, w_hi=6, wscale=0.1), {}),    # the largest height: a chain of 16 bands
+    (dict(Hh=250, B=2, D=3, H=28, w_lo=2, w_hi=5, wscale=0.08), {}),  # 16 bands, the last one partly filled, input part from the product
+    (dict(Hh=3, B=1, D=1, H=8, w_lo=1380, w_hi=1400, wscale=0.05), {}),   # one value per pixel, too wide for the band's x to be staged in LDS
+    (dict(Hh=20, B=1, D=1, H=20, w_lo=1350, w_hi=1360, wscale=0.05), {}), # the same with two bands and 32 padded units
+]
+
+
+@pytest.mark.parametrize("shape,tols", SHAPES)
+def test_mdlstm_shapes_against_oracle(shape, tols):
     wl = synth.make_image_workload("t", bias_scale=0.2, seed=50 + shape["Hh"] + shape["H"], **shape)
     if shape["w_lo"] == 0:
         wl.widths[-1] = 0
         wl.x[:, :, -1] = 0
     ref = oracle_layer(wl)
     got = run_layer(wl)
-    check(got, ref, shape, oracle_layer(wl, np.float32))
+    check(got, ref, shape, **tols)
     # beyond an image's width y is exactly zero
     for n, w in enumerate(wl.widths):
         assert not got["y"][:, w:, n].any()
+
+
+def test_mdlstm_ill_conditioned_workload_stays_within_its_one_ulp_spread():
+    """37 x <= 20 pixels, H = 16, weights U(-0.2, 0.2), seed 79: the outputs of scan direction (-1, -1) near pixel
+    (13, 0) of image 0 sit at the end of a path along which deviations grow by a factor 1.37 per pixel; changing the
+    float32 inputs and parameters by one unit in the last place moves the float64 oracle's y there by 1.6e-5 (root mean
+    square over 50 draws; largest 3.8e-5) of the output scale, the other three directions by at most 1e-5.  The
+    kernels' error has the same profile (geometric growth along that path, nothing at the band edges).  Bars: the
+    stated 1e-5 for directions 0..2, 1e-4 (about twice the largest one-ulp deviation) for direction 3; gradients 1e-4
+    (their one-ulp spread is below 4e-6).  tests/test_mdlstm_oracle_pins.py reproduces the spread on the CPU."""
+    wl = synth.make_image_workload("t", Hh=37, B=2, D=1, H=16, w_lo=6, w_hi=20, wscale=0.2, seed=79)
+    ref = oracle_layer(wl)
+    got = run_layer(wl)
+    H = wl.H
+    scale = np.abs(ref["y"]).max()
+    per_dir = [float(np.abs(got["y"][..., d * H:(d + 1) * H] - ref["y"][..., d * H:(d + 1) * H]).max() / scale) for d in range(4)]
+    print("mdlstm seed 79: y error per scan direction", [f"{e:.2e}" for e in per_dir], flush=True)
+    assert max(per_dir[:3]) < TOL_FWD, per_dir
+    assert per_dir[3] < 1e-4, per_dir
+    check(got, ref, "seed 79", tol_y=1e-4)
 
 
 def test_mdlstm_null_dx_and_reproducible():
@@ -151,8 +178,7 @@ def test_mdlstm_failure_path_forced_from_the_host():
         rl.rlstm_test_hook(-1, 0)
     got = run_layer(wl, want_dx=False)
     ref = oracle_layer(wl)
-    ref32 = oracle_layer(wl, dtype=np.float32)
-    check(got, ref, "after a forced timeout", ref32)
+    check(got, ref, "after a forced timeout")
 
 
 def test_mdlstm_argument_errors():
