@@ -151,6 +151,27 @@ RLSTM_API int lstm_bwd(const rlstm_desc* desc, const float* x, const float* W, c
              void* workspace, void* hip_stream);
 
 /*
+ * lstm_fwd_noalloc - lstm_fwd for callers that cannot allocate device memory or pass a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments and results as lstm_fwd (the same kernels run) without `workspace`: the scratch of the
+ * recurrent pass (timeout flag, step flags, exchange arrays, carried state) lives in a device array
+ * of RLSTM_NOALLOC_SCRATCH_LIMIT bytes inside the library, one copy per GPU, held until the process
+ * ends.  The call allocates nothing (no hipMalloc / hipFree, no events: the timing hooks of
+ * rlstm_profile_enable() are skipped) and clears what must start at zero with kernels, not memsets.
+ *   rlstm_noalloc_scratch_bytes(desc): scratch this shape needs (0: invalid descriptor);
+ *   shapes that need more than RLSTM_NOALLOC_SCRATCH_LIMIT are refused with RLSTM_ESIZE
+ *   (H = 512, B = 64 needs about 10 MiB).
+ * All calls on one GPU share that GPU's array, which keeps the last call's contents: calls that
+ * overlap in time on one GPU (different streams or threads) race and must be serialised by the
+ * caller.  The timeout flag is read with rlstm_last_timeout_on(NULL, stream).
+ */
+#define RLSTM_NOALLOC_SCRATCH_LIMIT ((size_t)16 << 20)
+RLSTM_API size_t rlstm_noalloc_scratch_bytes(const rlstm_desc* desc);
+RLSTM_API int lstm_fwd_noalloc(const rlstm_desc* desc, const float* x, const float* W, const float* R, const float* b,
+             const float* h0, const float* c0, const int32_t* seq_lens,
+             float* y, float* c, float* hT, float* cT, void* reserve, void* hip_stream);
+
+/*
  * blstm_stack_fwd_bwd - one training pass (forward, then backward) of an
  * L-layer bidirectional LSTM stack with zero initial states (Fig. 1 stacking,
  * Sec. 4.2 kernels).  The two directions of a layer run concurrently.
@@ -246,7 +267,8 @@ RLSTM_API int rlstm_copy_f32(float* dst, const float* src, size_t n, void* hip_s
  * did and the results are invalid, negative = RLSTM_E* code.  The flag is not
  * changed.  rlstm_last_timeout synchronises the DEVICE first;
  * rlstm_last_timeout_on waits only for `hip_stream` (the stream the calls in
- * question were enqueued on: for the stack entry points stream a). */
+ * question were enqueued on: for the stack entry points stream a) and, given a
+ * null workspace, reads the flag of lstm_fwd_noalloc on the current device. */
 RLSTM_API int rlstm_last_timeout(const void* workspace);
 RLSTM_API int rlstm_last_timeout_on(const void* workspace, void* hip_stream);
 

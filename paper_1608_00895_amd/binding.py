@@ -23,7 +23,7 @@ RLSTM_ENGINE_STEPWISE = 2
 
 EXPORTS = [
     "rlstm_reserve_bytes", "rlstm_workspace_bytes", "rblstm_reserve_bytes", "rblstm_workspace_bytes",
-    "lstm_fwd", "lstm_bwd", "rlstm_last_timeout_on",
+    "lstm_fwd", "lstm_bwd", "lstm_fwd_noalloc", "rlstm_noalloc_scratch_bytes", "rlstm_last_timeout_on",
     "blstm_stack_fwd_bwd", "blstm_stack_fwd", "blstm_stack_bwd",
     "rlstm_ce_workspace_bytes", "softmax_ce_fwd_bwd", "rlstm_sgd_momentum_step", "rlstm_adam_step",
     "rlstm_stream_reserve_bytes", "rlstm_stream_workspace_bytes", "lstm_stream_fwd_bwd",
@@ -88,6 +88,10 @@ def lib() -> ctypes.CDLL:
         L.lstm_fwd.argtypes = [ctypes.POINTER(rlstm_desc)] + [vp] * 14
         L.lstm_bwd.restype = ip
         L.lstm_bwd.argtypes = [ctypes.POINTER(rlstm_desc)] + [vp] * 20
+        L.lstm_fwd_noalloc.restype = ip
+        L.lstm_fwd_noalloc.argtypes = [ctypes.POINTER(rlstm_desc)] + [vp] * 13
+        L.rlstm_noalloc_scratch_bytes.restype = ctypes.c_size_t
+        L.rlstm_noalloc_scratch_bytes.argtypes = [ctypes.POINTER(rlstm_desc)]
         L.rlstm_last_timeout_on.restype = ip
         L.rlstm_last_timeout_on.argtypes = [vp, vp]
         L.blstm_stack_fwd_bwd.restype = ip
@@ -219,8 +223,24 @@ def rlstm_last_timeout(workspace: torch.Tensor) -> int:
     return int(lib().rlstm_last_timeout(_ptr(workspace)))
 
 
-def rlstm_last_timeout_on(workspace: torch.Tensor, stream=None) -> int:
+RLSTM_NOALLOC_SCRATCH_LIMIT = 16 << 20
+
+
+def rlstm_last_timeout_on(workspace: Optional[torch.Tensor], stream=None) -> int:
+    """workspace None: the flag of lstm_fwd_noalloc on the current device."""
     return int(lib().rlstm_last_timeout_on(_ptr(workspace), _stream(stream)))
+
+
+def rlstm_noalloc_scratch_bytes(desc: rlstm_desc) -> int:
+    return int(lib().rlstm_noalloc_scratch_bytes(ctypes.byref(desc)))
+
+
+def lstm_fwd_noalloc(desc, x, W, R, b, h0, c0, seq_lens, y, c, hT, cT, reserve, stream=None, check=True) -> int:
+    rc = lib().lstm_fwd_noalloc(ctypes.byref(desc), _ptr(x), _ptr(W), _ptr(R), _ptr(b), _ptr(h0), _ptr(c0),
+                                _ptr(seq_lens), _ptr(y), _ptr(c), _ptr(hT), _ptr(cT), _ptr(reserve), _stream(stream))
+    if check and rc != 0:
+        raise RlstmError(rc, "lstm_fwd_noalloc")
+    return rc
 
 
 def lstm_fwd(desc, x, W, R, b, h0, c0, seq_lens, y, c, hT, cT, reserve, workspace, stream=None, check=True) -> int:

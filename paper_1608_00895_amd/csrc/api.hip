@@ -6,6 +6,7 @@
 #include "rlstm_internal.h"
 
 #include <cmath>
+#include <mutex>
 #include <vector>
 
 using namespace rlstm;
@@ -436,8 +437,15 @@ int rlstm_last_timeout(const void* workspace) {
   return v != 0 ? 1 : 0;
 }
 
+static int static_scratch_address(void** out);
+
 int rlstm_last_timeout_on(const void* workspace, void* hip_stream) {
-  if (!workspace) return RLSTM_ENULL;
+  if (!workspace) {                               // the scratch of lstm_fwd_noalloc on the current device
+    void* ptr = nullptr;
+    const int rc = static_scratch_address(&ptr);
+    if (rc != RLSTM_OK) return rc;
+    workspace = ptr;
+  }
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   unsigned v = 0;
   if (hipMemcpyAsync(&v, workspace, sizeof(v), hipMemcpyDeviceToHost, st) != hipSuccess ||
@@ -960,7 +968,8 @@ int rlstm_gemm_bf16(int trans_a, int trans_b, int M, int N, int K,
   return gemm_entry(1, trans_a, trans_b, M, N, K, A, lda, B, ldb, C, ldc, bias, splitk_ws, splitk_ws_bytes, hip_stream);
 }
 
-// timed = false: no timing events are created, whatever rlstm_profile_enable() says
+// timed = false: no timing events are created, whatever rlstm_profile_enable() says (events are
+// allocations of the runtime, which the caller of lstm_fwd_noalloc must not trigger)
 static int lstm_fwd_impl(const rlstm_desc* d, const float* x, const float* W, const float* R, const float* b,
                          const float* h0, const float* c0, const int32_t* seq_lens,
                          float* y, float* c, float* hT, float* cT, void* reserve, void* workspace, size_t workspace_bytes,
@@ -1001,6 +1010,51 @@ int lstm_fwd(const rlstm_desc* d, const float* x, const float* W, const float* R
              const float* h0, const float* c0, const int32_t* seq_lens,
              float* y, float* c, float* hT, float* cT, void* reserve, void* workspace, void* hip_stream) {
   return lstm_fwd_impl(d, x, W, R, b, h0, c0, seq_lens, y, c, hT, cT, reserve, workspace, (size_t)-1, hip_stream, true);
+}
+
+// ---- lstm_fwd for callers that cannot allocate ------------------------------------------------
+// The scratch of the recurrent pass (timeout flag, step flags, exchange arrays, carried state) lives in a
+// file-scope device array instead of a caller-provided workspace.  Every device the library runs on holds its own
+// copy of the array at its own address, until the process ends; the address is looked up once per device.  The
+// array's name is only a host-side handle: everything below works with the looked-up device address.
+constexpr size_t kStaticScratchBytes = RLSTM_NOALLOC_SCRATCH_LIMIT;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static void* g_static_scratch[kMaxDevices] = {};
+static std::mutex g_static_scratch_mutex;
+
+// device address of `scratch` on the current device (RLSTM_EHIP if the runtime cannot tell)
+static int static_scratch_address(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return RLSTM_EHIP; }
+  std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+  if (!g_static_scratch[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) { (void)hipGetLastError(); return RLSTM_EHIP; }
+    g_static_scratch[dev] = ptr;
+  }
+  *out = g_static_scratch[dev];
+  return RLSTM_OK;
+}
+
+size_t rlstm_noalloc_scratch_bytes(const rlstm_desc* d) {
+  if (check_desc(d) != RLSTM_OK) return 0;
+  RecShape s{d->T, d->B, d->H, d->ldy ? d->ldy : d->H, 1, d->operand_dtype};
+  return kFlagBytes + rec_workspace_bytes(s);
+}
+
+int lstm_fwd_noalloc(const rlstm_desc* d, const float* x, const float* W, const float* R, const float* b,
+                     const float* h0, const float* c0, const int32_t* seq_lens,
+                     float* y, float* c, float* hT, float* cT, void* reserve, void* hip_stream) {
+  int rc = check_desc(d);
+  if (rc != RLSTM_OK) return rc;
+  if (!x || !W || !R || !b || !seq_lens || !y || !c || !reserve) return RLSTM_ENULL;
+  if (rlstm_noalloc_scratch_bytes(d) > kStaticScratchBytes) return RLSTM_ESIZE;
+  void* ptr = nullptr;
+  rc = static_scratch_address(&ptr);
+  if (rc != RLSTM_OK) return rc;
+  return lstm_fwd_impl(d, x, W, R, b, h0, c0, seq_lens, y, c, hT, cT, reserve, ptr, kStaticScratchBytes, hip_stream, false);
 }
 
 int lstm_bwd(const rlstm_desc* d, const float* x, const float* W, const float* R,
