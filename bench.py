@@ -31,6 +31,41 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def clock_state():
+    """Clock and power state as rocm-smi reports it (a short string; None where the tool is not usable)."""
+    import re
+    import subprocess
+    try:
+        r = subprocess.run(["rocm-smi", "--showclocks", "--showpower", "--showperflevel"], capture_output=True, text=True,
+                           timeout=20)
+        keep = [re.sub(r"\s+", " ", ln.strip()) for ln in r.stdout.splitlines()
+                if any(k in ln for k in ("sclk", "mclk", "fclk", "Power", "Performance Level"))]
+        return "; ".join(keep) if keep else None
+    except Exception as ex:          # measurement aid only
+        return f"unavailable ({type(ex).__name__})"
+
+
+def recorded_traffic(workload, kernel, version, plan=None):
+    """HBM bytes per launch of `kernel` from the rocprofv3 counter runs recorded in profiles/hbm_traffic.json, or
+    (None, why) when the record was made with other kernels than the ones this run launched (another library
+    version or another layout of the recurrent passes): a stale figure is worse than none."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as fh:
+            rec = json.load(fh)["workloads"].get(workload)
+    except (OSError, ValueError, KeyError) as ex:
+        return None, f"no usable traffic record ({type(ex).__name__})"
+    if rec is None:
+        return None, "no counter run recorded for this workload"
+    if rec.get("library_version") != version:
+        return None, (f"counter run was made with library version {rec.get('library_version')} (commit {rec.get('commit')}), "
+                      f"this is {version}: not reported")
+    if plan is not None and rec.get("plan") is not None and rec["plan"] != plan:
+        return None, "counter run was made with another layout of the recurrent passes: not reported"
+    v = rec["bytes_per_launch"].get(kernel)
+    return v, f"{rec['source']} (commit {rec.get('commit')}, {rec.get('date')})"
+
+
 def rec_bytes(kind, wl, steps):
     """Algorithmic HBM bytes of `steps` recurrent steps (both directions), fp32: forward reads Z and writes
     gates, y, c; backward reads gates, c (twice), dy and writes dz; the recurrent matrix is read once per launch."""
@@ -47,7 +82,8 @@ def cpu_baseline(wl_full, seconds_budget=20.0, output_layer=None):
     from oracle import blstm_stack_backward, blstm_stack_forward
     from paper_1608_00895_amd import synth
 
-    Ts = 512 if wl_full.H >= 400 else 500
+    # frames of the slice: sized so that the oracle runs for some tens of seconds (config 4: 6 x 1000 units, B = 64)
+    Ts = 64 if wl_full.H >= 1000 else (512 if wl_full.H >= 400 else 500)
     Ts = min(Ts, wl_full.T)
     lens = np.minimum(wl_full.seq_lens, Ts).astype(np.int32)
     params = [[tuple(a.astype(np.float64) for a in p) for p in layer] for layer in wl_full.params]
@@ -142,9 +178,10 @@ def bench_config5(args):
         log(e)
     dom = max(kernels, key=lambda e: e["ms_per_step"])
     # HBM bytes per launch from the rocprofv3 FETCH_SIZE + WRITE_SIZE runs at this workload, scaled by a copy kernel
-    measured_traffic = {"mdlstm_forward_scan": 0.046e9 + 1.669e9, "mdlstm_backward_scan": 1.134e9 + 1.135e9}
+    traffic, traffic_source = recorded_traffic("config5", dom["kernel"], rl.version())
     roofline = {"kernel": dom["kernel"], "bound": "mfma", "achieved": dom["tflops"], "peak": PEAK_FP32_MFMA_TFLOPS,
-                "unit": "TFLOP/s", "frac": dom["tflops"] / PEAK_FP32_MFMA_TFLOPS, "traffic": measured_traffic.get(dom["kernel"]),
+                "unit": "TFLOP/s", "frac": dom["tflops"] / PEAK_FP32_MFMA_TFLOPS, "traffic": traffic,
+                "traffic_source": traffic_source,
                 "avg_launch_ms": dom["avg_ms"],
                 "note": "one workgroup per (scan direction, image, band of 16 rows): 128 of the 256 CUs work, and the chain of "
                         "anti-diagonals is serial (a step's MFMAs alone take a CU 0.53 us of the measured step); priced against "
@@ -202,17 +239,15 @@ def bench_gemm(args):
         lda, ldb = (M if ta else K), (K if tb else N)
         res = {}
         for variant, tag in ((0, "picked"), (2, "plain")):
-            rl.rlstm_set_gemm_variant(variant)
             for _ in range(args.warmup):
-                rl.rlstm_gemm_f32(ta, tb, M, N, K, A, lda, B, ldb, C, N, None, sk)
+                rl.rlstm_gemm_f32(ta, tb, M, N, K, A, lda, B, ldb, C, N, None, sk, variant=variant)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for _ in range(args.steps):
-                rl.rlstm_gemm_f32(ta, tb, M, N, K, A, lda, B, ldb, C, N, None, sk)
+                rl.rlstm_gemm_f32(ta, tb, M, N, K, A, lda, B, ldb, C, N, None, sk, variant=variant)
             e1.record()
             torch.cuda.synchronize()
             res[tag] = e0.elapsed_time(e1) / args.steps
-        rl.rlstm_set_gemm_variant(0)
         flop = 2.0 * M * N * K
         kernels.append({"kernel": name, "M": M, "N": N, "K": K, "avg_ms": res["picked"], "tflops": flop / res["picked"] / 1e9,
                         "plain_kernel_ms": res["plain"], "plain_kernel_tflops": flop / res["plain"] / 1e9})
@@ -241,7 +276,8 @@ def bench_stream(args):
     dev = "cuda:0"
     wl = synth.paper_stream()
     log(f"workload {wl.name}: L={wl.L} S={wl.S} Tc={wl.Tc} B={wl.B} D={wl.D} H={wl.H} frames={wl.frames}")
-    desc = rl.rlstm_stream_desc(L=wl.L, S=wl.S, Tc=wl.Tc, B=wl.B, D=wl.D, H=wl.H, operand_dtype=0, engine=args.engine)
+    desc = rl.rlstm_stream_desc(L=wl.L, S=wl.S, Tc=wl.Tc, B=wl.B, D=wl.D, H=wl.H, operand_dtype=0, engine=args.engine,
+                                batch_groups=args.batch_groups or 0, bwd_exchange=args.bwd_exchange or 0)
     x = torch.from_numpy(wl.x).to(dev)
     sl = torch.from_numpy(wl.seq_lens).to(dev)
     params = [torch.from_numpy(a).to(dev) for p in wl.params for a in p]
@@ -251,8 +287,6 @@ def bench_stream(args):
     state = torch.zeros((wl.L, 2, wl.B, wl.H), device=dev)
     reserve = torch.empty(rl.rlstm_stream_reserve_bytes(desc), dtype=torch.uint8, device=dev)
     ws = torch.empty(rl.rlstm_stream_workspace_bytes(desc), dtype=torch.uint8, device=dev)
-    if args.batch_groups is not None:
-        rl.rlstm_set_batch_groups(args.batch_groups)
 
     def step():
         state.zero_()
@@ -290,9 +324,12 @@ def bench_stream(args):
         log(e)
     dom = max(kernels, key=lambda e: e["ms_per_step"])
     # bytes per launch from the rocprofv3 FETCH_SIZE + WRITE_SIZE runs (profiles/lstm_stream_paper_stream_hbm_counters.md)
-    measured_traffic = {"recurrent_forward": 0.397e9 + 0.393e9, "recurrent_backward": 1.088e9 + 0.655e9}
+    traffic, traffic_source = recorded_traffic("paper_stream", dom["kernel"], rl.version())
+    if args.batch_groups is not None or args.bwd_exchange is not None or args.engine != 0:
+        traffic, traffic_source = None, "not reported with non-default settings"
     roofline = {"kernel": dom["kernel"], "bound": "mfma", "achieved": dom["tflops"], "peak": PEAK_FP32_MFMA_TFLOPS,
-                "unit": "TFLOP/s", "frac": dom["tflops"] / PEAK_FP32_MFMA_TFLOPS, "traffic": measured_traffic.get(dom["kernel"]),
+                "unit": "TFLOP/s", "frac": dom["tflops"] / PEAK_FP32_MFMA_TFLOPS, "traffic": traffic,
+                "traffic_source": traffic_source,
                 "avg_launch_ms": dom["avg_ms"], "steps_per_launch": dom.get("steps_per_launch"), "step_us": dom.get("step_us"),
                 "note": "the recurrent kernels are bound by the serial chain of dependent steps (see step_us); priced "
                         "against the fp32 MFMA peak with 2*B*H*4H FLOP per step"}
@@ -336,11 +373,13 @@ def main():
     ap.add_argument("--engine", type=int, default=0)
     ap.add_argument("--one-stream", action="store_true")
     ap.add_argument("--first-piece", type=int, default=None,
-                    help="steps of the first piece the recurrent passes are cut into (library default if omitted; 0 = uncut)")
+                    help="steps of the first piece the recurrent passes are cut into (library default if omitted; -1 = uncut)")
     ap.add_argument("--batch-groups", type=int, default=None,
                     help="groups the sequences are dealt out to per direction (library default if omitted)")
     ap.add_argument("--overlap-mode", type=int, default=None,
-                    help="-1 per shape (library default), 0 serial, 1 products share CUs with the recurrent kernels")
+                    help="1 serial, 2 products share CUs with the recurrent kernels (chosen per shape if omitted)")
+    ap.add_argument("--bwd-exchange", type=int, default=None,
+                    help="exchanges per step of the backward recurrent kernel: 1 two, 2 one where it applies (library default if omitted)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed region, run one plain 1 GiB copy kernel (known HBM traffic) "
@@ -365,31 +404,33 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
-    wl = {"config2": synth.config2, "config3": synth.config3, "config4": synth.config4,
-          "paper_chunks": synth.paper_chunks, "paper_train": synth.paper_chunks}[args.workload]()
-    log(f"workload {wl.name}: L={wl.L} T={wl.T} B={wl.B} D={wl.D} H={wl.H} frames={wl.frames} slots={wl.T * wl.B}")
-
-    desc = rl.rblstm_desc(L=wl.L, T=wl.T, B=wl.B, D=wl.D, H=wl.H, operand_dtype=wl.operand_dtype, engine=args.engine)
-    x = torch.from_numpy(wl.x).to(dev)
-    sl = torch.from_numpy(wl.seq_lens).to(dev)
     chunking = None
     if args.workload in ("paper_chunks", "paper_train"):
-        # the batch is cut from the corpus on the device: segment table on the host, gather kernel
+        # the batch is cut from the corpus by the library: segment table on the host, gather kernel on the device
         cx, clens = synth.paper_corpus()
-        cseq, cstart, clen = rl.rlstm_chunk_plan(clens, wl.T, wl.T)
+        size, nb = synth.PAPER_SEGMENT_FRAMES, synth.PAPER_BATCH_SEGMENTS
+        cseq, cstart, clen = rl.rlstm_chunk_plan(clens, size, size)
         cxd = torch.from_numpy(cx).to(dev)
-        tab = [torch.from_numpy(a[:wl.B].copy()).to(dev) for a in (cseq, cstart, clen)]
-        x = torch.empty((wl.T, wl.B, wl.D), device=dev)
+        tab = [torch.from_numpy(a[:nb].copy()).to(dev) for a in (cseq, cstart, clen)]
+        x = torch.empty((size, nb, cx.shape[2]), device=dev)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        rl.rlstm_chunk_gather(cxd, tab[0], tab[1], tab[2], wl.T, x)
+        rl.rlstm_chunk_gather(cxd, tab[0], tab[1], tab[2], size, x)
         e0.record()
-        rl.rlstm_chunk_gather(cxd, tab[0], tab[1], tab[2], wl.T, x)
+        rl.rlstm_chunk_gather(cxd, tab[0], tab[1], tab[2], size, x)
         e1.record()
         torch.cuda.synchronize()
-        assert np.array_equal(x.cpu().numpy(), wl.x) and np.array_equal(clen[:wl.B], wl.seq_lens)
+        wl = synth.paper_workload(x.cpu().numpy(), clen[:nb])
         sl = tab[2]
         chunking = {"corpus_sequences": int(len(clens)), "corpus_frames": int(clens.sum()), "segments": int(len(cseq)),
-                    "segment_frames": wl.T, "gather_ms": e0.elapsed_time(e1)}
+                    "segment_frames": size, "gather_ms": e0.elapsed_time(e1)}
+    else:
+        wl = {"config2": synth.config2, "config3": synth.config3, "config4": synth.config4}[args.workload]()
+        x = torch.from_numpy(wl.x).to(dev)
+        sl = torch.from_numpy(wl.seq_lens).to(dev)
+    log(f"workload {wl.name}: L={wl.L} T={wl.T} B={wl.B} D={wl.D} H={wl.H} frames={wl.frames} slots={wl.T * wl.B}")
+    tuning = dict(first_piece=args.first_piece or 0, batch_groups=args.batch_groups or 0, overlap_mode=args.overlap_mode or 0,
+                  bwd_exchange=args.bwd_exchange or 0)
+    desc = rl.rblstm_desc(L=wl.L, T=wl.T, B=wl.B, D=wl.D, H=wl.H, operand_dtype=wl.operand_dtype, engine=args.engine, **tuning)
     train = None
     host_params = [a for layer in wl.params for p in layer for a in p]
     if args.workload == "paper_train":
@@ -423,14 +464,8 @@ def main():
     ws = torch.empty(rl.rblstm_workspace_bytes(desc), dtype=torch.uint8, device=dev)
     sa = torch.cuda.current_stream()
     sb = None if args.one_stream else torch.cuda.Stream()
-    if args.overlap_mode is not None:
-        rl.rlstm_set_overlap_mode(args.overlap_mode)
-    if args.first_piece is not None:
-        rl.rlstm_set_first_piece(args.first_piece)
-    if args.batch_groups is not None:
-        rl.rlstm_set_batch_groups(args.batch_groups)
 
-    def step():
+    def step(desc=desc):
         # the bottom layer's input gradient is not needed for training and is skipped (dx = null)
         if train is None:
             rl.blstm_stack_fwd_bwd(desc, x, params, sl, G, y_top, grads, None, reserve, ws, sa, sb)
@@ -448,17 +483,36 @@ def main():
         step()
     torch.cuda.synchronize()
     assert rl.rlstm_last_timeout(ws) == 0
+    rl.rlstm_profile_enable(False)
     rl.rlstm_profile_read()
-    rl.rlstm_profile_enable(True)
+    # Timed region: exactly K steps between device synchronisations, the library's timing hooks off.  Every step is
+    # also bracketed by a pair of events on stream a (a call returns with stream a waiting for stream b), which
+    # gives the per-step times behind the median and the minimum.
+    step_events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    clocks_before = clock_state()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for e0, e1 in step_events:
+        e0.record()
         step()
+        e1.record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    assert rl.rlstm_last_timeout(ws) == 0
+    step_ms = sorted(e0.elapsed_time(e1) for e0, e1 in step_events)
+    # A loop of its own with the hooks on: every kernel group bracketed by events on its launch stream.
+    hook_steps = max(1, min(args.steps, 5))
+    rl.rlstm_profile_enable(True)
+    torch.cuda.synchronize()
+    th0 = time.perf_counter()
+    for _ in range(hook_steps):
+        step()
+    torch.cuda.synchronize()
+    th1 = time.perf_counter()
     rl.rlstm_profile_enable(False)
     prof = rl.rlstm_profile_read(1 << 16)
     assert rl.rlstm_last_timeout(ws) == 0
+    ms_per_step_hooks = (th1 - th0) * 1e3 / hook_steps
     if args.calibration_copy:
         n = 1 << 28
         src = torch.ones(n, device=dev)
@@ -478,8 +532,8 @@ def main():
         d["rsteps"] += nsteps
     kernels = []
     for kind, d in sorted(by_kind.items()):
-        e = {"kernel": rl.PROFILE_KINDS[kind], "launches_per_step": d["launches"] / args.steps,
-             "avg_ms": d["ms"] / d["launches"], "ms_per_step": d["ms"] / args.steps,
+        e = {"kernel": rl.PROFILE_KINDS[kind], "launches_per_step": d["launches"] / hook_steps,
+             "avg_ms": d["ms"] / d["launches"], "ms_per_step": d["ms"] / hook_steps,
              "tflops": d["flop"] / (d["ms"] * 1e-3) / 1e12}
         if kind in (1, 2):
             # a pass over the T steps may be cut into several launches
@@ -489,37 +543,40 @@ def main():
         kernels.append(e)
         log(e)
     dom = max(kernels, key=lambda e: e["ms_per_step"])
-    # bytes per launch at the L2-to-fabric interface, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-    # summarised in profiles/blstm_stack_config3_hbm_counters.md (config 3 with the library's default cut of
-    # the passes and groups of sequences only; scaled by the copy kernel)
-    measured_traffic = {"recurrent_forward": 0.391e9 + 0.481e9, "recurrent_backward": 1.074e9 + 0.713e9,
-                        "input_projection": 0.135e9 + 0.070e9, "input_gradient": 0.112e9 + 0.017e9,
-                        "weight_gradient": 0.572e9 + 0.062e9, "recurrent_weight_gradient": 0.572e9 + 0.062e9}
-    # the same for the paper's batch shape (profiles/train_step_paper_shape_hbm_counters.md)
-    paper_shape_traffic = {"recurrent_forward": 0.948e9 + 0.913e9, "recurrent_backward": 2.764e9 + 2.257e9}
-    default_knobs = args.first_piece is None and args.batch_groups is None and not args.one_stream and args.engine == 0
+    # bytes per launch at the L2-to-fabric interface, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs recorded in
+    # profiles/hbm_traffic.json (default settings only; scaled by the copy kernel)
+    default_knobs = (args.first_piece is None and args.batch_groups is None and not args.one_stream and args.engine == 0
+                     and args.overlap_mode is None and args.bwd_exchange is None)
+    try:
+        plan_now = rl.rblstm_plan(desc) if args.engine in (0, 1) else None
+    except rl.RlstmError:
+        plan_now = None
+    if default_knobs:
+        traffic, traffic_source = recorded_traffic(args.workload, dom["kernel"], rl.version(), plan_now)
+    else:
+        traffic, traffic_source = None, "not reported with non-default settings"
     peak = PEAK_FP32_MFMA_TFLOPS if wl.operand_dtype == 0 else PEAK_BF16_MFMA_TFLOPS
     roofline = {"kernel": dom["kernel"], "bound": "mfma", "achieved": dom["tflops"], "peak": peak,
                 "unit": "TFLOP/s", "frac": dom["tflops"] / peak,
-                "traffic": (measured_traffic if args.workload == "config3" else paper_shape_traffic).get(dom["kernel"])
-                if args.workload in ("config3", "paper_chunks", "paper_train") and default_knobs else None,
+                "traffic": traffic, "traffic_source": traffic_source,
                 "avg_launch_ms": dom["avg_ms"],
                 "steps_per_launch": dom.get("steps_per_launch"),
                 "note": "the recurrent kernels are bound by the serial chain of T dependent steps "
-                        "(see step_us), not by MFMA or HBM throughput; priced here against the fp32 MFMA "
-                        "peak with 2*B*H*4H FLOP per step and direction; a pass over the T steps is cut "
-                        "into several launches (steps_per_launch)"}
+                        "(see step_us), not by MFMA or HBM throughput; priced here against the MFMA "
+                        "peak of the operand type with 2*B*H*4H FLOP per step and direction; a pass over the T steps "
+                        "is cut into several launches (steps_per_launch)"}
 
     # The same recurrent kernels with nothing beside them: two calls with the products in serial order on one
     # stream (outside the timed region), for the step time the kernels reach alone.
     if args.engine in (0, 1) and train is None and not args.one_stream and args.overlap_mode is None:
-        rl.rlstm_set_overlap_mode(0)
-        try:
-            step()
+        serial = rl.rblstm_desc(L=wl.L, T=wl.T, B=wl.B, D=wl.D, H=wl.H, operand_dtype=wl.operand_dtype, engine=args.engine,
+                                **dict(tuning, overlap_mode=1))
+        if True:
+            step(serial)
             torch.cuda.synchronize()
             rl.rlstm_profile_read()
             rl.rlstm_profile_enable(True)
-            step()
+            step(serial)
             torch.cuda.synchronize()
             rl.rlstm_profile_enable(False)
             alone = {}
@@ -533,8 +590,6 @@ def main():
                         e["step_us_alone"] = 1e3 * alone[kind][0] / alone[kind][1]
             if "step_us_alone" in dom:
                 roofline["step_us_alone"] = dom["step_us_alone"]
-        finally:
-            rl.rlstm_set_overlap_mode(-1)
 
     # Floor of the step chain: the bare exchange of one hop (store, acknowledge, flag, poll, load; no
     # arithmetic) timed live at the same group shape.  Forward: one hop per step (h_t); backward: two
@@ -548,13 +603,17 @@ def main():
                 wsf = torch.empty(rl.rlstm_exchange_floor_bytes(ng, members, tile), dtype=torch.uint8, device=dev)
                 return rl.rlstm_exchange_floor(ng, members, tile, read, 2000, wsf)
             f_fwd = floor(plan["members_fwd"], bp * u * es, plan["members_fwd"] * bp * u * es)
-            f_dz = floor(plan["members_bwd"], bp * u * 4 * es, plan["members_bwd"] * bp * u * es)
-            f_part = floor(plan["members_bwd"], bp * 4 * u * 8, 4 * bp * u * 8)
+            if plan["bwd_exchanges_per_step"] == 1:
+                # one exchange: every workgroup writes a [16 x padded H] tile and reads its piece of every producer's
+                f_bwd = floor(plan["members_bwd"], 16 * plan["Hq"] * 4, plan["members_bwd"] * 16 * u * 4)
+            else:
+                f_dz = floor(plan["members_bwd"], bp * u * 4 * es, plan["members_bwd"] * bp * u * es)
+                f_bwd = f_dz + floor(plan["members_bwd"], bp * 4 * u * 8, 4 * bp * u * 8)
             for e in kernels:
                 if e["kernel"] == "recurrent_forward":
                     e["exchange_floor_us"] = f_fwd
                 if e["kernel"] == "recurrent_backward":
-                    e["exchange_floor_us"] = f_dz + f_part
+                    e["exchange_floor_us"] = f_bwd
             roofline["plan"] = plan
             if dom["kernel"] in ("recurrent_forward", "recurrent_backward"):
                 roofline["step_us"] = dom["step_us"]
@@ -565,6 +624,12 @@ def main():
     out = {
         "metric": "BLSTM train frames/sec (fwd+bwd)", "value": frames_per_s, "unit": "frames/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "ms_per_step_median": step_ms[len(step_ms) // 2], "ms_per_step_min": step_ms[0],
+        "ms_per_step_with_timing_hooks": ms_per_step_hooks,
+        "timing": "value and ms_per_step: K steps between device synchronisations, the library's event hooks off; median / min: "
+                  "per-step event pairs on stream a in that same loop; the per-kernel figures come from a separate loop of "
+                  f"{hook_steps} steps with the hooks on (ms_per_step_with_timing_hooks)",
+        "clock_state": clocks_before,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if wl.operand_dtype == 0 else "bf16 operands, f32 accumulate", "data": "synthetic",
         "config": {"workload": wl.name, "layers": wl.L, "units_per_direction": wl.H, "batch": wl.B,
@@ -582,7 +647,7 @@ def main():
         out["config"].update(classes=train["C"], update="adam", parameters=int(n_all),
                              loss_per_frame=float(train["loss"].item()) / wl.frames,
                              frame_error_rate=int(train["errors"].item()) / wl.frames)
-    if not args.no_cpu_baseline and args.workload != "config4":
+    if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, output_layer=(train["Wo"], train["bo"], train["labels"]) if train else None)
     print(json.dumps(out), flush=True)
 

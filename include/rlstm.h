@@ -91,7 +91,38 @@ typedef struct rlstm_desc {
   int32_t ldx;            /* row stride (floats) of x and dx, >= D; 0 means D         */
   int32_t ldy;            /* row stride (floats) of y and dy, >= H; 0 means H         */
   int32_t engine;         /* RLSTM_ENGINE_*                                           */
+  /* Tuning (see "Tuning fields" below); 0 = library default for every field.              */
+  int32_t batch_groups;   /* groups the sequences are dealt out to per direction      */
+  int32_t bwd_exchange;   /* exchanges per step of the backward recurrent kernel      */
+  int32_t gemm_variant;   /* which fp32 matrix-product kernel                         */
 } rlstm_desc;
+
+/*
+ * Tuning fields of the descriptors.  They select among implementations of the same computation: results never
+ * differ beyond the order of floating-point sums.  0 always means "library default"; a value outside the ranges
+ * below is RLSTM_EMODE.  They travel with the descriptor, so that callers with different shapes (or threads) in one
+ * process tune independently; the library keeps no tuning state.
+ *   batch_groups  0, 1, 2, 4 or 8.  The sequences of a minibatch are independent; the persistent engine deals them
+ *                 out to this many groups of workgroups per direction, each with its own copy of the recurrent
+ *                 matrix, which exchange h_t / d a_t only among themselves (directions * groups <= 8; a value the
+ *                 shape cannot use makes the persistent engine unavailable for it).  Default: chosen per shape.
+ *   bwd_exchange  1: two exchanges between workgroups per step of the pass back through time (Sec. 4.2) - workgroups
+ *                 fetch a quarter of d a_t each, multiply it with their rows of R^T and hand partial tiles to the
+ *                 owners of the units;  2: one exchange per step where it applies (groups of at most 16 sequences,
+ *                 fp32, H <= 512) - every workgroup multiplies its own columns of d a_t with its rows of R^T and
+ *                 hands a piece of the result to every other workgroup of its group, which adds the pieces in a
+ *                 fixed order.  Default: 1.
+ *   gemm_variant  1: the pipelined kernel wherever its operand conditions hold (both operands made of whole, 16-byte
+ *                 aligned float4s);  2: the plain kernel.  Default: the pipelined kernel where its conditions hold
+ *                 and the product does not run beside the recurrent kernels on the same CUs.
+ *   first_piece   (stack descriptors) with two streams and the persistent engine each layer's recurrent pass is cut
+ *                 into pieces of first_piece, first_piece, 2 first_piece, 4 first_piece, ... steps, and the matrix
+ *                 product that feeds a piece runs on stream b while stream a is inside the piece before it.
+ *                 -1: passes are not cut.  Default: 128.
+ *   overlap_mode  (stack descriptors) 1: matrix products and recurrent passes one after the other;  2: products
+ *                 and recurrent workgroups share CUs and the passes are cut into pieces (falls back to 1 where the
+ *                 two LDS footprints do not fit one CU).  Default: chosen per shape.
+ */
 
 /* Deep bidirectional stack: L layers, each a forward and a backward LSTM of H
  * units on the same input; layer 0 reads D features, layers >= 1 read 2H. */
@@ -99,6 +130,7 @@ typedef struct rblstm_desc {
   int32_t L, T, B, D, H;
   int32_t operand_dtype;  /* as in rlstm_desc */
   int32_t engine;         /* RLSTM_ENGINE_* */
+  int32_t first_piece, batch_groups, overlap_mode, gemm_variant, bwd_exchange;   /* tuning, 0 = default */
 } rblstm_desc;
 
 /* Bytes of the opaque forward-to-backward buffer of lstm_fwd / lstm_bwd (it
@@ -217,17 +249,18 @@ RLSTM_API int blstm_stack_fwd(const rblstm_desc* desc, const float* x, const flo
  *   trans_a == 0: A is [M,K] with row stride lda;  != 0: A is stored [K,M]
  *   trans_b == 0: B is [K,N] with row stride ldb;  != 0: B is stored [N,K]
  *   C [M,N] out, row stride ldc; bias [N] or null
+ *   variant: the gemm_variant tuning value (0 = default)
  *   splitk_ws: scratch of splitk_ws_bytes (may be null / 0): lets products with
  *   K much larger than M, N split K into slices that are summed in a fixed order.
  */
 RLSTM_API int rlstm_gemm_f32(int trans_a, int trans_b, int M, int N, int K,
                    const float* A, int lda, const float* B, int ldb, float* C, int ldc,
-                   const float* bias, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream);
+                   const float* bias, int variant, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream);
 /* Same product with both operands rounded to bf16 (round to nearest even) and fp32
  * accumulation; A, B, C and bias stay fp32 in memory (the operand_dtype = 1 variant). */
 RLSTM_API int rlstm_gemm_bf16(int trans_a, int trans_b, int M, int N, int K,
                     const float* A, int lda, const float* B, int ldb, float* C, int ldc,
-                    const float* bias, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream);
+                    const float* bias, int variant, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream);
 
 /*
  * Optional per-kernel timing for measurement (not part of the method).  While
@@ -272,15 +305,6 @@ RLSTM_API int rlstm_copy_f32(float* dst, const float* src, size_t n, void* hip_s
 RLSTM_API int rlstm_last_timeout(const void* workspace);
 RLSTM_API int rlstm_last_timeout_on(const void* workspace, void* hip_stream);
 
-/*
- * Tuning knob of blstm_stack_fwd_bwd with two streams and the persistent engine.  Each layer's
- * recurrent pass is cut into pieces of `steps`, `steps`, 2*`steps`, 4*`steps`, ... steps, and the
- * matrix product that feeds a piece (input projection in the forward pass, gradient w.r.t. the
- * layer input in the backward pass) runs on stream b while stream a is inside the piece before it.
- * 0 = passes are not cut.  Default 128.  Process-wide; results do not depend on it beyond the
- * order of floating-point sums in the bias gradient.  Returns RLSTM_EDIM for a negative value.
- */
-RLSTM_API int rlstm_set_first_piece(int steps);
 
 /*
  * Two-dimensional (multidimensional) LSTM layer with four scan directions (Sec. 4.2: the state of
@@ -303,15 +327,17 @@ RLSTM_API int rlstm_set_first_piece(int steps);
  * gates, cell states and predecessor outputs from mdlstm_fwd to mdlstm_bwd, which overwrites it;
  * workspace (rmdlstm_workspace_bytes) is scratch.  The caller owns all buffers; nothing is
  * allocated and the device is not synchronised.
- * The rows of a scan are dealt out to workgroups in bands of 16 that hand one row per
- * anti-diagonal to their neighbour through the workspace; all such waits are bounded (2 s) and
- * rlstm_last_timeout(workspace) tells whether one expired (the results are then invalid).
- * Limits of the kernels: Hh <= 256, H <= 32, operand_dtype 0; other shapes return RLSTM_ERESIDENT
- * (the size queries then return 0).  Other errors as for lstm_fwd.
+ * Engines (the `engine` field, RLSTM_ENGINE_* as for the one-dimensional layer).  PERSISTENT: one launch per pass;
+ * the rows of a scan are dealt out to workgroups in bands of 16 that hand one row per anti-diagonal to their
+ * neighbour through the workspace; all such waits are bounded (2 s) and rlstm_last_timeout(workspace) tells
+ * whether one expired (the results are then invalid); limits Hh <= 256, H <= 32 (RLSTM_ERESIDENT beyond them, and
+ * the size queries return 0).  STEPWISE: one launch per anti-diagonal with plain kernels, any shape.  AUTO:
+ * PERSISTENT where the shape fits, else STEPWISE.  operand_dtype must be 0.  Other errors as for lstm_fwd.
  */
 typedef struct rmdlstm_desc {
   int32_t Hh, Ww, B, D, H;
   int32_t operand_dtype;      /* 0 (fp32) */
+  int32_t engine;             /* RLSTM_ENGINE_* */
 } rmdlstm_desc;
 RLSTM_API size_t rmdlstm_reserve_bytes(const rmdlstm_desc* d);
 RLSTM_API size_t rmdlstm_workspace_bytes(const rmdlstm_desc* d);
@@ -372,6 +398,7 @@ typedef struct rlstm_stream_desc {
   int32_t L, S, Tc, B, D, H;
   int32_t operand_dtype;  /* as in rlstm_desc */
   int32_t engine;         /* RLSTM_ENGINE_* */
+  int32_t batch_groups, bwd_exchange, gemm_variant;   /* tuning, 0 = default */
 } rlstm_stream_desc;
 RLSTM_API size_t rlstm_stream_reserve_bytes(const rlstm_stream_desc* desc);
 RLSTM_API size_t rlstm_stream_workspace_bytes(const rlstm_stream_desc* desc);
@@ -417,10 +444,12 @@ RLSTM_API int rlstm_adam_step(float* param, const float* grad, float* m, float* 
 
 /*
  * How the persistent engine lays a stack's recurrent passes out on this device (for reports).
- * out[8] (host): {groups of workgroups (directions * groups of sequences), sequences per group,
+ * out[10] (host): {groups of workgroups (directions * groups of sequences), sequences per group,
  * rows a group's tiles hold, units per workgroup, workgroups per group in the forward kernel,
  * workgroups per group in the backward kernel, padded H of the forward product, units per K
- * quarter of the backward product}.  RLSTM_ERESIDENT if the persistent engine cannot hold the shape.
+ * quarter of the backward product (two exchanges per step) or its padded H (one exchange), exchanges
+ * per step of the backward pass (the bwd_exchange tuning field), 0}.  RLSTM_ERESIDENT if the persistent
+ * engine cannot hold the shape.
  */
 RLSTM_API int rblstm_plan(const rblstm_desc* d, int32_t* out);
 
@@ -441,34 +470,7 @@ RLSTM_API size_t rlstm_exchange_floor_bytes(int groups, int members, int tile_by
 RLSTM_API int rlstm_exchange_floor(int groups, int members, int tile_bytes, int read_bytes, int steps,
                                    void* workspace, size_t workspace_bytes, float* us_per_step, void* hip_stream);
 
-/*
- * Tuning knob of the persistent engine.  The sequences of a minibatch are independent; the
- * engine deals them out to `groups` groups of workgroups per direction, each with its own copy of
- * the recurrent matrix, which exchange h_t / d a_t only among themselves.  0 (default) = chosen
- * per shape; otherwise 1, 2, 4 or 8 with directions * groups <= 8 (a value the shape cannot use
- * makes the persistent engine unavailable for it).  Process-wide.  Results do not depend on it
- * beyond the order of floating-point sums in the bias gradient.
- */
-RLSTM_API int rlstm_set_batch_groups(int groups);
 
-/*
- * How blstm_stack_fwd_bwd / blstm_stack_bwd with two streams run the matrix products beside the recurrent
- * passes (testing and measurement; process-wide, not thread-safe):
- * -1 (default) chosen per shape;  0 one after the other;  1 products and recurrent workgroups share CUs and
- * the passes are cut into pieces (falls back to 0 where the two LDS footprints do not fit one CU).
- * RLSTM_EDIM for any other value.  The choice changes the order
- * of floating-point sums (kernel shapes), never which frames or parameters are computed.
- */
-RLSTM_API int rlstm_set_overlap_mode(int mode);
-
-/*
- * Choice among the fp32 matrix-product kernels (testing and measurement; process-wide, not thread-safe):
- * 0 (default) the library decides per call: the pipelined kernel where both operands consist of whole,
- *   16-byte aligned float4s and the product does not run beside the recurrent kernels on the same CUs,
- *   the plain kernel otherwise;  1: the pipelined kernel wherever its operand conditions hold;
- * 2: the plain kernel.  RLSTM_EDIM for any other value.
- */
-RLSTM_API int rlstm_set_gemm_variant(int variant);
 
 /*
  * Test hook for the failure path of the persistent kernels (not part of the method).  From the

@@ -27,26 +27,29 @@ EXPORTS = [
     "blstm_stack_fwd_bwd", "blstm_stack_fwd", "blstm_stack_bwd",
     "rlstm_ce_workspace_bytes", "softmax_ce_fwd_bwd", "rlstm_sgd_momentum_step", "rlstm_adam_step",
     "rlstm_stream_reserve_bytes", "rlstm_stream_workspace_bytes", "lstm_stream_fwd_bwd",
-    "rlstm_gemm_f32", "rlstm_gemm_bf16", "rlstm_copy_f32", "rlstm_profile_enable", "rlstm_profile_read", "rlstm_last_timeout", "rlstm_test_hook", "rlstm_set_first_piece", "rlstm_set_batch_groups", "rlstm_set_gemm_variant", "rlstm_set_overlap_mode", "rmdlstm_reserve_bytes", "rmdlstm_workspace_bytes", "mdlstm_fwd", "mdlstm_bwd", "rlstm_chunk_plan", "rlstm_chunk_gather", "rblstm_plan", "rlstm_exchange_floor_bytes", "rlstm_exchange_floor", "rlstm_resolve_engine", "rlstm_strerror", "rlstm_version",
+    "rlstm_gemm_f32", "rlstm_gemm_bf16", "rlstm_copy_f32", "rlstm_profile_enable", "rlstm_profile_read", "rlstm_last_timeout", "rlstm_test_hook", "rmdlstm_reserve_bytes", "rmdlstm_workspace_bytes", "mdlstm_fwd", "mdlstm_bwd", "rlstm_chunk_plan", "rlstm_chunk_gather", "rblstm_plan", "rlstm_exchange_floor_bytes", "rlstm_exchange_floor", "rlstm_resolve_engine", "rlstm_strerror", "rlstm_version",
 ]
 
 
 class rlstm_desc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
-                ("T", "B", "D", "H", "direction", "operand_dtype", "ldx", "ldy", "engine")]
+                ("T", "B", "D", "H", "direction", "operand_dtype", "ldx", "ldy", "engine",
+                 "batch_groups", "bwd_exchange", "gemm_variant")]
 
 
 class rblstm_desc(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("L", "T", "B", "D", "H", "operand_dtype", "engine")]
+    _fields_ = [(n, ctypes.c_int32) for n in ("L", "T", "B", "D", "H", "operand_dtype", "engine",
+                                              "first_piece", "batch_groups", "overlap_mode", "gemm_variant", "bwd_exchange")]
 
 
 class rlstm_stream_desc(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("L", "S", "Tc", "B", "D", "H", "operand_dtype", "engine")]
+    _fields_ = [(n, ctypes.c_int32) for n in ("L", "S", "Tc", "B", "D", "H", "operand_dtype", "engine",
+                                              "batch_groups", "bwd_exchange", "gemm_variant")]
 
 
 class rmdlstm_desc(ctypes.Structure):
     _fields_ = [("Hh", ctypes.c_int32), ("Ww", ctypes.c_int32), ("B", ctypes.c_int32), ("D", ctypes.c_int32),
-                ("H", ctypes.c_int32), ("operand_dtype", ctypes.c_int32)]
+                ("H", ctypes.c_int32), ("operand_dtype", ctypes.c_int32), ("engine", ctypes.c_int32)]
 
 
 class rlstm_profile_entry(ctypes.Structure):
@@ -118,7 +121,7 @@ def lib() -> ctypes.CDLL:
         L.blstm_stack_fwd.restype = ip
         L.blstm_stack_fwd.argtypes = [ctypes.POINTER(rblstm_desc), vp, ctypes.POINTER(vp), vp, vp, vp, vp, vp]
         L.rlstm_gemm_f32.restype = ip
-        L.rlstm_gemm_f32.argtypes = [ip, ip, ip, ip, ip, vp, ip, vp, ip, vp, ip, vp, vp, ctypes.c_size_t, vp]
+        L.rlstm_gemm_f32.argtypes = [ip, ip, ip, ip, ip, vp, ip, vp, ip, vp, ip, vp, ip, vp, ctypes.c_size_t, vp]
         L.rlstm_gemm_bf16.restype = ip
         L.rlstm_gemm_bf16.argtypes = L.rlstm_gemm_f32.argtypes
         L.rlstm_copy_f32.restype = ip
@@ -148,14 +151,6 @@ def lib() -> ctypes.CDLL:
         L.rlstm_exchange_floor_bytes.argtypes = [ip, ip, ip]
         L.rlstm_exchange_floor.restype = ip
         L.rlstm_exchange_floor.argtypes = [ip, ip, ip, ip, ip, vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_float), vp]
-        L.rlstm_set_batch_groups.restype = ip
-        L.rlstm_set_batch_groups.argtypes = [ip]
-        L.rlstm_set_overlap_mode.restype = ip
-        L.rlstm_set_overlap_mode.argtypes = [ip]
-        L.rlstm_set_gemm_variant.restype = ip
-        L.rlstm_set_gemm_variant.argtypes = [ip]
-        L.rlstm_set_first_piece.restype = ip
-        L.rlstm_set_first_piece.argtypes = [ip]
         L.rlstm_test_hook.restype = ip
         L.rlstm_test_hook.argtypes = [ip, ctypes.c_uint64]
         L.rlstm_resolve_engine.restype = ip
@@ -346,10 +341,10 @@ def blstm_stack_fwd(desc, x, params, seq_lens, y_top, reserve, workspace, stream
 
 
 def rlstm_gemm_f32(trans_a, trans_b, M, N, K, A, lda, B, ldb, C, ldc, bias=None, splitk_ws=None,
-                   stream=None, check=True) -> int:
+                   stream=None, check=True, variant=0) -> int:
     nbytes = 0 if splitk_ws is None else splitk_ws.numel() * splitk_ws.element_size()
     rc = lib().rlstm_gemm_f32(int(trans_a), int(trans_b), M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc,
-                              _ptr(bias), _ptr(splitk_ws), nbytes, _stream(stream))
+                              _ptr(bias), int(variant), _ptr(splitk_ws), nbytes, _stream(stream))
     if check and rc != 0:
         raise RlstmError(rc, "rlstm_gemm_f32")
     return rc
@@ -377,10 +372,10 @@ def rlstm_copy_f32(dst, src, n, stream=None, check=True) -> int:
 
 
 def rlstm_gemm_bf16(trans_a, trans_b, M, N, K, A, lda, B, ldb, C, ldc, bias=None, splitk_ws=None,
-                    stream=None, check=True) -> int:
+                    stream=None, check=True, variant=0) -> int:
     nbytes = 0 if splitk_ws is None else splitk_ws.numel() * splitk_ws.element_size()
     rc = lib().rlstm_gemm_bf16(int(trans_a), int(trans_b), M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc,
-                               _ptr(bias), _ptr(splitk_ws), nbytes, _stream(stream))
+                               _ptr(bias), int(variant), _ptr(splitk_ws), nbytes, _stream(stream))
     if check and rc != 0:
         raise RlstmError(rc, "rlstm_gemm_bf16")
     return rc
@@ -388,34 +383,6 @@ def rlstm_gemm_bf16(trans_a, trans_b, M, N, K, A, lda, B, ldb, C, ldc, bias=None
 
 def rlstm_test_hook(mute_workgroup: int = -1, wait_ticks: int = 0) -> int:
     return int(lib().rlstm_test_hook(int(mute_workgroup), int(wait_ticks)))
-
-
-def rlstm_set_first_piece(steps: int) -> int:
-    rc = int(lib().rlstm_set_first_piece(int(steps)))
-    if rc != 0:
-        raise RlstmError(rc, "rlstm_set_first_piece")
-    return rc
-
-
-def rlstm_set_batch_groups(groups: int) -> int:
-    rc = int(lib().rlstm_set_batch_groups(int(groups)))
-    if rc != 0:
-        raise RlstmError(rc, "rlstm_set_batch_groups")
-    return rc
-
-
-def rlstm_set_overlap_mode(mode: int) -> int:
-    rc = lib().rlstm_set_overlap_mode(int(mode))
-    if rc != 0:
-        raise RlstmError(rc, "rlstm_set_overlap_mode")
-    return rc
-
-
-def rlstm_set_gemm_variant(variant: int) -> int:
-    rc = lib().rlstm_set_gemm_variant(int(variant))
-    if rc != 0:
-        raise RlstmError(rc, "rlstm_set_gemm_variant")
-    return rc
 
 
 def rlstm_exchange_floor_bytes(groups: int, members: int, tile_bytes: int) -> int:
@@ -434,11 +401,12 @@ def rlstm_exchange_floor(groups, members, tile_bytes, read_bytes, steps, workspa
 
 
 def rblstm_plan(desc) -> dict:
-    out = (ctypes.c_int32 * 8)()
+    out = (ctypes.c_int32 * 10)()
     rc = int(lib().rblstm_plan(ctypes.byref(desc), out))
     if rc != 0:
         raise RlstmError(rc, "rblstm_plan")
-    keys = ("groups", "sequences_per_group", "rows", "units_per_workgroup", "members_fwd", "members_bwd", "Hp", "Hq")
+    keys = ("groups", "sequences_per_group", "rows", "units_per_workgroup", "members_fwd", "members_bwd", "Hp", "Hq",
+            "bwd_exchanges_per_step")
     return dict(zip(keys, [int(v) for v in out]))
 
 

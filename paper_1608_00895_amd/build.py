@@ -17,7 +17,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "librlstm.so")
 SOURCES = ["gemm.hip", "recurrent.hip", "recurrent_persistent.hip", "recurrent_stepwise.hip", "exchange_probe.hip",
-           "mdlstm.hip", "chunking.hip", "output_layer.hip", "stream.hip", "api.hip"]
+           "mdlstm.hip", "mdlstm_stepwise.hip", "chunking.hip", "output_layer.hip", "stream.hip", "api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -16,6 +16,11 @@ namespace {
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 constexpr size_t kFlagBytes = 256;
 
+// tuning fields shared by the descriptors: 0 = library default
+bool tuning_ok(int batch_groups, int bwd_exchange, int gemm_variant) {
+  return batch_groups >= 0 && batch_groups <= 8 && bwd_exchange >= 0 && bwd_exchange <= 2 && gemm_variant >= 0 && gemm_variant <= 2;
+}
+
 int check_desc(const rlstm_desc* d) {
   if (!d) return RLSTM_ENULL;
   if (d->T <= 0 || d->B <= 0 || d->D <= 0 || d->H <= 0) return RLSTM_EDIM;
@@ -25,6 +30,7 @@ int check_desc(const rlstm_desc* d) {
   if (d->direction != 1 && d->direction != -1) return RLSTM_EMODE;
   if (d->operand_dtype != 0 && d->operand_dtype != 1) return RLSTM_EMODE;
   if (d->engine < RLSTM_ENGINE_AUTO || d->engine > RLSTM_ENGINE_STEPWISE) return RLSTM_EMODE;
+  if (!tuning_ok(d->batch_groups, d->bwd_exchange, d->gemm_variant)) return RLSTM_EMODE;
   return RLSTM_OK;
 }
 int check_stack_desc(const rblstm_desc* d) {
@@ -33,7 +39,16 @@ int check_stack_desc(const rblstm_desc* d) {
   if ((long long)d->T * d->B > (1ll << 30) || (long long)d->H * 4 > (1ll << 24)) return RLSTM_EDIM;
   if (d->operand_dtype != 0 && d->operand_dtype != 1) return RLSTM_EMODE;
   if (d->engine < RLSTM_ENGINE_AUTO || d->engine > RLSTM_ENGINE_STEPWISE) return RLSTM_EMODE;
+  if (!tuning_ok(d->batch_groups, d->bwd_exchange, d->gemm_variant)) return RLSTM_EMODE;
+  if (d->first_piece < -1 || d->overlap_mode < 0 || d->overlap_mode > 2) return RLSTM_EMODE;
   return RLSTM_OK;
+}
+
+// recurrent shape of one layer in one direction
+RecShape layer_rec_shape(const rlstm_desc* d) {
+  RecShape s{d->T, d->B, d->H, d->ldy ? d->ldy : d->H, 1, d->operand_dtype};
+  s.batch_groups = d->batch_groups; s.bwd_exchange = d->bwd_exchange;
+  return s;
 }
 
 size_t splitk_floats(int max_m, int H) {
@@ -97,14 +112,14 @@ int hip_to_code(hipError_t e, int resident_err) {
 int weight_grads(hipStream_t st, int layer, int T, int B, int Din, int H, int direction,
                  const float* x, int ldx, const float* y, int ldy, const float* dz,
                  float* dW, float* dR, float* skws, size_t skfloats, bool naive, int operand_dtype,
-                 bool small_footprint, bool accumulate = false) {
+                 bool small_footprint, int variant, bool accumulate = false) {
   int resident_err = 0;
   GemmCall g;
   g.transA = true; g.transB = false;
   g.M = Din; g.N = 4 * H; g.K = T * B;
   g.A = x; g.lda = ldx; g.B = dz; g.ldb = 4 * H; g.C = dW; g.ldc = 4 * H;
   g.splitk_ws = skws; g.splitk_floats = skfloats; g.naive = naive; g.operand_dtype = operand_dtype;
-  g.small_footprint = small_footprint; g.accumulate = accumulate;
+  g.small_footprint = small_footprint; g.accumulate = accumulate; g.variant = variant;
   {
     ProfScope ps(st, 4, layer, 1, 0, gemm_flop(g));
     RLSTM_TRY(gemm(st, g));
@@ -139,6 +154,7 @@ StackLayout stack_layout(const rblstm_desc* d) {
 RecShape stack_rec_shape(const rblstm_desc* d) {
   RecShape s;
   s.T = d->T; s.B = d->B; s.H = d->H; s.ldy = 2 * d->H; s.ndir = 2; s.operand_dtype = d->operand_dtype;
+  s.batch_groups = d->batch_groups; s.bwd_exchange = d->bwd_exchange;
   return s;
 }
 
@@ -147,7 +163,7 @@ RecShape stack_rec_shape(const rblstm_desc* d) {
 // second stream while the first stream is inside piece k.  Only the product of piece 0 is exposed,
 // so the pieces start small and double (the products run two to three times faster per frame than
 // the recurrence, so a piece of twice the size is ready in time).
-int g_first_piece = 128;         // steps of piece 0; 0 = do not cut
+constexpr int kDefaultFirstPiece = 128;   // steps of piece 0 unless the descriptor says otherwise
 
 // Cutting the passes pays only if a matrix-product workgroup fits on a CU next to a workgroup of
 // the persistent kernels (LDS); otherwise the products just queue behind the recurrent launches.
@@ -163,24 +179,27 @@ int g_first_piece = 128;         // steps of piece 0; 0 = do not cut
 // asking for more than half of a CU's LDS): 67.6 ms on the 4 x 500 stack; the products at half rate become the
 // critical path and the recurrent steps still slow down (5.9 / 8.3 us) through the shared memory system.
 enum OverlapMode { kSerial = 0, kShare = 1 };
-int g_overlap_mode = -1;         // -1: chosen per shape; otherwise forced (kShare falls back to kSerial where the LDS does not fit)
 
-OverlapMode overlap_mode(const RecShape& rs, int operand_dtype, bool persistent, bool two_streams) {
-  if (!persistent || !two_streams || g_overlap_mode == kSerial) return kSerial;
+// requested: the descriptor's overlap_mode (0 chosen per shape, 1 serial, 2 shared; shared falls back to serial where the
+// two LDS footprints do not fit one CU)
+OverlapMode overlap_mode(const RecShape& rs, int operand_dtype, bool persistent, bool two_streams, int requested) {
+  if (!persistent || !two_streams || requested == 1) return kSerial;
   DeviceInfo di;
   if (device_info(&di) != hipSuccess) { (void)hipGetLastError(); return kSerial; }
-  int plan[8];
+  int plan[10];
   const size_t rec = persistent_lds_bytes(rs, di.num_cus, di.max_lds);
   const bool fits = rec != 0 && rec + gemm_small_lds_bytes(operand_dtype) <= di.max_lds;
   const bool idle_cores = persistent_plan_info(rs, di.num_cus, di.max_lds, plan) && ((plan[2] + 15) / 16) * (plan[3] / 4) <= 2;
-  return (fits && (idle_cores || g_overlap_mode == kShare)) ? kShare : kSerial;
+  return (fits && (idle_cores || requested == 2)) ? kShare : kSerial;
 }
 
-std::vector<int> piece_bounds(int T, bool pipelined) {
+// first_piece: the descriptor's field (0 = default, -1 = passes not cut, otherwise the steps of piece 0)
+std::vector<int> piece_bounds(int T, bool pipelined, int first_piece) {
   std::vector<int> b{0};
-  if (pipelined && g_first_piece > 0) {
-    for (long long e = g_first_piece; e < T; e *= 2) b.push_back((int)e);
-    if (b.size() > 1 && T - b.back() < g_first_piece) b.pop_back();
+  const int first = first_piece == 0 ? kDefaultFirstPiece : first_piece;
+  if (pipelined && first > 0) {
+    for (long long e = first; e < T; e *= 2) b.push_back((int)e);
+    if (b.size() > 1 && T - b.back() < first) b.pop_back();
   }
   b.push_back(T);
   return b;
@@ -213,10 +232,10 @@ int stack_forward(const rblstm_desc* d, const float* x, const float* const* para
   unsigned* flag = reinterpret_cast<unsigned*>(ws);
   void* recws = ws + kFlagBytes;
   const int T = d->T, B = d->B, H = d->H;
-  const OverlapMode mode = overlap_mode(rs, d->operand_dtype, persistent, sb != sa);
+  const OverlapMode mode = overlap_mode(rs, d->operand_dtype, persistent, sb != sa, d->overlap_mode);
   if (mode == kSerial) sb = sa;
   const bool pipelined = mode != kSerial;
-  const std::vector<int> pb = piece_bounds(T, pipelined);
+  const std::vector<int> pb = piece_bounds(T, pipelined, d->first_piece);
   const int np = (int)pb.size() - 1;
   EventList evs;
   RLSTM_TRY(clear_flag(sa, flag));
@@ -240,7 +259,7 @@ int stack_forward(const rblstm_desc* d, const float* x, const float* const* para
         g.M = (s1 - s0) * B; g.N = 4 * H; g.K = din;
         g.A = in + f0 * B * din; g.lda = din; g.B = params[6 * l + 3 * k + 0]; g.ldb = 4 * H;
         g.C = base + lay.zg[k] + f0 * B * 4 * H; g.ldc = 4 * H; g.bias = params[6 * l + 3 * k + 2];
-        g.naive = !persistent; g.operand_dtype = d->operand_dtype;
+        g.naive = !persistent; g.operand_dtype = d->operand_dtype; g.variant = d->gemm_variant;
         g.small_footprint = mode == kShare && pc > 0;   // the first piece's product runs while the chain waits for it
         ProfScope ps(sb, 0, l, 1, 0, gemm_flop(g));
         RLSTM_TRY(gemm(sb, g));
@@ -258,7 +277,7 @@ int stack_forward(const rblstm_desc* d, const float* x, const float* const* para
 // dR += h0^T dz(first processed valid frame of each sequence).  Direction +1 starts every sequence at frame 0
 // (a sequence without frames has dz = 0 there), so the term is one small product accumulated into dR; direction -1
 // starts each sequence at its own last frame and keeps the gathering kernel.
-int h0_term(hipStream_t st, bool persistent, int operand_dtype, int T, int B, int H, int direction, const float* h0,
+int h0_term(hipStream_t st, bool persistent, int operand_dtype, int variant, int T, int B, int H, int direction, const float* h0,
             const float* dz, const int32_t* seq_lens, float* dR) {
   int resident_err = 0;
   if (persistent && direction > 0) {
@@ -266,7 +285,7 @@ int h0_term(hipStream_t st, bool persistent, int operand_dtype, int T, int B, in
     g.transA = true;
     g.M = H; g.N = 4 * H; g.K = B;
     g.A = h0; g.lda = H; g.B = dz; g.ldb = 4 * H; g.C = dR; g.ldc = 4 * H; g.accumulate = true;
-    g.operand_dtype = operand_dtype;
+    g.operand_dtype = operand_dtype; g.variant = variant;
     RLSTM_TRY(gemm(st, g));
     return RLSTM_OK;
   }
@@ -279,7 +298,7 @@ int stack_backward(const rblstm_desc* d, const float* x, const float* const* par
                    const float* dy_top, const float* y_top, float* const* grads, float* dx, float* res, char* ws,
                    hipStream_t sa, hipStream_t sb, bool persistent) {
   const RecShape rs = stack_rec_shape(d);
-  const OverlapMode mode = overlap_mode(rs, d->operand_dtype, persistent, sb != sa);
+  const OverlapMode mode = overlap_mode(rs, d->operand_dtype, persistent, sb != sa, d->overlap_mode);
   if (mode == kSerial) sb = sa;
   int rc = RLSTM_OK;
   int resident_err = 0;
@@ -298,7 +317,7 @@ int stack_backward(const rblstm_desc* d, const float* x, const float* const* par
   // and in the frame order, in which that layer's pass back through time consumes it, one piece
   // ahead; the weight gradients follow on stream b and overlap the rest of that pass.
   const bool pipelined = mode != kSerial;
-  const std::vector<int> pb = piece_bounds(T, pipelined);
+  const std::vector<int> pb = piece_bounds(T, pipelined, d->first_piece);
   const int np = (int)pb.size() - 1;
   EventList evs;
   std::vector<hipEvent_t> ready;       // ready[pc]: dy of piece pc of the layer about to run is complete
@@ -338,7 +357,7 @@ int stack_backward(const rblstm_desc* d, const float* x, const float* const* par
             g.A = base + lay.zg[k] + f0 * B * 4 * H; g.lda = 4 * H;
             g.B = params[6 * l + 3 * k + 0] + (size_t)tk * H * 4 * H; g.ldb = 4 * H;
             g.C = dxl + f0 * B * din + (size_t)tk * H; g.ldc = din; g.accumulate = (k == 1);
-            g.naive = !persistent; g.operand_dtype = d->operand_dtype;
+            g.naive = !persistent; g.operand_dtype = d->operand_dtype; g.variant = d->gemm_variant;
             g.small_footprint = mode == kShare && pc > 0;   // the first piece's product runs while the chain waits for it
             // ... and has too few tiles for the chip (128 at 128 steps x 32 sequences x 500 units): K is split as well
             if (pc == 0) { g.splitk_ws = skws; g.splitk_floats = skfloats; }
@@ -359,7 +378,7 @@ int stack_backward(const rblstm_desc* d, const float* x, const float* const* par
         g.M = T * B; g.N = din; g.K = 4 * H;
         g.A = base + lay.zg[k]; g.lda = 4 * H; g.B = params[6 * l + 3 * k + 0]; g.ldb = 4 * H;
         g.C = dxl; g.ldc = din; g.accumulate = (k == 1);
-        g.naive = !persistent; g.operand_dtype = d->operand_dtype;
+        g.naive = !persistent; g.operand_dtype = d->operand_dtype; g.variant = d->gemm_variant;
         ProfScope ps(sb, 3, l, 1, 0, gemm_flop(g));
         RLSTM_TRY(gemm(sb, g));
       }
@@ -368,7 +387,8 @@ int stack_backward(const rblstm_desc* d, const float* x, const float* const* par
     for (int k = 0; k < 2; ++k) {
       rc = weight_grads(sb, l, T, B, din, H, k == 0 ? 1 : -1, xin, din, yl + (size_t)k * H, 2 * H,
                         base + lay.zg[k], grads[6 * l + 3 * k + 0], grads[6 * l + 3 * k + 1], skws, skfloats,
-                        !persistent, d->operand_dtype, mode == kShare && l > 0);   // layer 0's run after the last recurrent piece: nothing beside them
+                        !persistent, d->operand_dtype, mode == kShare && l > 0,     // layer 0's run after the last recurrent piece: nothing beside them
+                        d->gemm_variant);
       if (rc != RLSTM_OK) return rc;
     }
     dy = dxl;
@@ -382,7 +402,7 @@ int stack_backward(const rblstm_desc* d, const float* x, const float* const* par
 
 extern "C" {
 
-const char* rlstm_version(void) { return "0.1"; }
+const char* rlstm_version(void) { return "0.2"; }
 
 const char* rlstm_strerror(int code) {
   switch (code) {
@@ -404,7 +424,7 @@ size_t rlstm_reserve_bytes(const rlstm_desc* d) {
 
 size_t rlstm_workspace_bytes(const rlstm_desc* d) {
   if (check_desc(d) != RLSTM_OK) return 0;
-  RecShape s{d->T, d->B, d->H, d->ldy ? d->ldy : d->H, 1, d->operand_dtype};
+  const RecShape s = layer_rec_shape(d);
   const int mm = d->D > d->H ? d->D : d->H;
   return kFlagBytes + align_up(rec_workspace_bytes(s), 256) + splitk_floats(mm, d->H) * sizeof(float);
 }
@@ -425,8 +445,7 @@ size_t rblstm_workspace_bytes(const rblstm_desc* d) {
 int rlstm_resolve_engine(const rlstm_desc* d) {
   int rc = check_desc(d);
   if (rc != RLSTM_OK) return rc;
-  RecShape s{d->T, d->B, d->H, d->ldy ? d->ldy : d->H, 1, d->operand_dtype};
-  return resolve_engine(d->engine, s);
+  return resolve_engine(d->engine, layer_rec_shape(d));
 }
 
 int rlstm_last_timeout(const void* workspace) {
@@ -453,21 +472,15 @@ int rlstm_last_timeout_on(const void* workspace, void* hip_stream) {
   return v != 0 ? 1 : 0;
 }
 
-int rlstm_set_first_piece(int steps) {
-  if (steps < 0) return RLSTM_EDIM;
-  g_first_piece = steps;
-  return RLSTM_OK;
-}
-
 int rblstm_plan(const rblstm_desc* d, int32_t* out) {
   int rc = check_stack_desc(d);
   if (rc != RLSTM_OK) return rc;
   if (!out) return RLSTM_ENULL;
   DeviceInfo di;
   if (device_info(&di) != hipSuccess) { (void)hipGetLastError(); return RLSTM_EHIP; }
-  int v[8];
+  int v[10];
   if (!persistent_plan_info(stack_rec_shape(d), di.num_cus, di.max_lds, v)) return RLSTM_ERESIDENT;
-  for (int i = 0; i < 8; ++i) out[i] = v[i];
+  for (int i = 0; i < 10; ++i) out[i] = v[i];
   return RLSTM_OK;
 }
 
@@ -488,24 +501,6 @@ int rlstm_exchange_floor(int groups, int members, int tile_bytes, int read_bytes
   return timed_out ? RLSTM_EHIP : RLSTM_OK;
 }
 
-int rlstm_set_overlap_mode(int mode) {
-  if (mode < -1 || mode > 1) return RLSTM_EDIM;
-  g_overlap_mode = mode;
-  return RLSTM_OK;
-}
-
-int rlstm_set_gemm_variant(int variant) {
-  if (variant < 0 || variant > 2) return RLSTM_EDIM;
-  gemm_set_variant(variant);
-  return RLSTM_OK;
-}
-
-int rlstm_set_batch_groups(int groups) {
-  if (groups < 0 || groups > 8) return RLSTM_EDIM;
-  persistent_set_batch_groups(groups);
-  return RLSTM_OK;
-}
-
 int rlstm_test_hook(int mute_workgroup, uint64_t wait_ticks) {
   persistent_test_hook(mute_workgroup, wait_ticks);
   mdlstm_test_hook(mute_workgroup, wait_ticks);
@@ -518,9 +513,15 @@ static int check_md_desc(const rmdlstm_desc* d) {
   if (d->Hh <= 0 || d->Ww <= 0 || d->B <= 0 || d->D <= 0 || d->H <= 0) return RLSTM_EDIM;
   if ((long long)d->Hh * d->Ww * d->B > (1ll << 28)) return RLSTM_EDIM;
   if (d->operand_dtype != 0) return RLSTM_EMODE;
+  if (d->engine < RLSTM_ENGINE_AUTO || d->engine > RLSTM_ENGINE_STEPWISE) return RLSTM_EMODE;
   MdShape s{d->Hh, d->Ww, d->B, d->H};
-  if (!mdlstm_supported(s)) return RLSTM_ERESIDENT;
+  if (d->engine == RLSTM_ENGINE_PERSISTENT && !mdlstm_supported(s)) return RLSTM_ERESIDENT;
   return RLSTM_OK;
+}
+// the scan kernels (one launch, bands of rows handing rows on) where the shape fits them, else one launch per anti-diagonal
+static bool md_stepwise(const rmdlstm_desc* d) {
+  MdShape s{d->Hh, d->Ww, d->B, d->H};
+  return d->engine == RLSTM_ENGINE_STEPWISE || (d->engine == RLSTM_ENGINE_AUTO && !mdlstm_supported(s));
 }
 static size_t md_pixels(const rmdlstm_desc* d) { return (size_t)d->Hh * d->Ww * d->B; }
 // For a narrow input x is kept next to [h_up | h_left] so that one product yields dR_u, dR_v and dW.
@@ -533,11 +534,13 @@ static size_t md_splitk_floats(const rmdlstm_desc* d) {
   return align_up((size_t)512 * md_grad_rows(d) * 5 * d->H, 64);
 }
 static size_t md_stacked_floats(const rmdlstm_desc* d) { return align_up((size_t)4 * md_stride(d) * 5 * d->H, 64); }
+// behind the split-K partials: the scan kernels' per-band bias gradients, or the stepwise engine's [P, H] scratch arrays
 static size_t md_dbpart_floats(const rmdlstm_desc* d) {
   MdShape s{d->Hh, d->Ww, d->B, d->H, 0};
-  return align_up(mdlstm_dbpart_floats(s), 64);
+  return align_up(md_stepwise(d) ? mdlstm_stepwise_scratch_floats(s) : mdlstm_dbpart_floats(s), 64);
 }
 static size_t md_halo_bytes(const rmdlstm_desc* d) {
+  if (md_stepwise(d)) return 0;
   MdShape s{d->Hh, d->Ww, d->B, d->H, 0};
   return align_up(mdlstm_halo_words(s) * sizeof(unsigned long long), 256);
 }
@@ -573,17 +576,25 @@ int mdlstm_fwd(const rmdlstm_desc* d, const float* x, const float* const* params
   md_dirs(d, static_cast<float*>(reserve), params, dirs);
   // One input value per pixel (grayscale images): b + x W is an outer product, formed inside the scan kernel
   // instead of being written to and read back from HBM; the kernel also leaves x next to [h_up | h_left].
-  const bool xin = d->D == 1;
+  const bool stepwise = md_stepwise(d);
+  const bool xin = d->D == 1 && !stepwise;
   for (int k = 0; k < 4 && !xin; ++k) {
     GemmCall g;
     g.M = P; g.N = 5 * H; g.K = d->D;
     g.A = x; g.lda = d->D; g.B = params[4 * k + 0]; g.ldb = 5 * H; g.C = dirs[k].zg; g.ldc = 5 * H;
     g.bias = params[4 * k + 3];
+    g.naive = stepwise;
     ProfScope ps(st, 0, 0, 1, 0, gemm_flop(g));
     RLSTM_TRY(gemm(st, g));
   }
   MdShape s{d->Hh, d->Ww, d->B, H, md_stride(d)};
   if (md_fused(d) && !xin) RLSTM_TRY(mdlstm_copy_x(st, s, dirs, x, d->D));
+  if (stepwise) {
+    RLSTM_TRY(clear_flag(st, reinterpret_cast<unsigned*>(workspace)));     // this engine has no waits; the flag only says so
+    ProfScope ps(st, 1, 0, 4, d->Hh + d->Ww - 1, 2.0 * P * 2 * H * 5 * H * 4);
+    RLSTM_TRY(mdlstm_stepwise_forward(st, s, dirs, widths, y));
+    return RLSTM_OK;
+  }
   const float* W1[4]; const float* b1[4];
   for (int k = 0; k < 4; ++k) { W1[k] = params[4 * k + 0]; b1[k] = params[4 * k + 3]; }
   const int diag = d->Hh + d->Ww - 1;
@@ -614,7 +625,8 @@ int mdlstm_bwd(const rmdlstm_desc* d, const float* x, const float* const* params
   {
     float* db[4] = {grads[3], grads[7], grads[11], grads[15]};
     ProfScope ps(st, 2, 0, 4, d->Hh + d->Ww - 1, 2.0 * P * 2 * H * 5 * H * 4);
-    RLSTM_TRY(mdlstm_backward(st, s, dirs, widths, dy, skws + skfloats, db, halo, reinterpret_cast<unsigned*>(ws)));
+    if (md_stepwise(d)) RLSTM_TRY(mdlstm_stepwise_backward(st, s, dirs, widths, dy, skws + skfloats, db));
+    else RLSTM_TRY(mdlstm_backward(st, s, dirs, widths, dy, skws + skfloats, db, halo, reinterpret_cast<unsigned*>(ws)));
   }
   float* stacked = skws + skfloats + md_dbpart_floats(d);
   const size_t stacked_one = (size_t)s.S * 5 * H;
@@ -777,7 +789,13 @@ static int check_stream_desc(const rlstm_stream_desc* d) {
   if (d->L > 64 || (long long)d->S * d->Tc * d->B > (1ll << 30) || (long long)d->H * 4 > (1ll << 24)) return RLSTM_EDIM;
   if (d->operand_dtype != 0 && d->operand_dtype != 1) return RLSTM_EMODE;
   if (d->engine < RLSTM_ENGINE_AUTO || d->engine > RLSTM_ENGINE_STEPWISE) return RLSTM_EMODE;
+  if (!tuning_ok(d->batch_groups, d->bwd_exchange, d->gemm_variant)) return RLSTM_EMODE;
   return RLSTM_OK;
+}
+static RecShape stream_rec_shape(const rlstm_stream_desc* d) {
+  RecShape s{d->Tc, d->B, d->H, d->H, 1, d->operand_dtype};
+  s.batch_groups = d->batch_groups; s.bwd_exchange = d->bwd_exchange;
+  return s;
 }
 struct StreamLayout {
   size_t zg, c, y, per_layer;                       // reserve, floats, one segment per layer
@@ -788,7 +806,7 @@ static StreamLayout stream_layout(const rlstm_stream_desc* d) {
   const size_t tb = (size_t)d->Tc * d->B;
   l.zg = 0; l.c = align_up(tb * 4 * d->H, 64); l.y = l.c + align_up(tb * d->H, 64);
   l.per_layer = l.y + align_up(tb * d->H, 64);
-  const RecShape rs{d->Tc, d->B, d->H, d->H, 1, d->operand_dtype};
+  const RecShape rs = stream_rec_shape(d);
   size_t o = kFlagBytes;
   l.rec = o;     o += align_up(rec_workspace_bytes(rs), 256);
   l.splitk_floats = splitk_floats(d->D > d->H ? d->D : d->H, d->H);
@@ -819,7 +837,7 @@ int lstm_stream_fwd_bwd(const rlstm_stream_desc* d, const float* x, const float*
   if (!x || !params || !seq_lens || !dy_top || !y_top || !grads || !reserve || !workspace) return RLSTM_ENULL;
   for (int i = 0; i < 3 * d->L; ++i) if (!params[i] || !grads[i]) return RLSTM_ENULL;
   const int L = d->L, S = d->S, Tc = d->Tc, B = d->B, D = d->D, H = d->H;
-  const RecShape rs{Tc, B, H, H, 1, d->operand_dtype};
+  const RecShape rs = stream_rec_shape(d);
   const int eng = resolve_engine(d->engine, rs);
   if (eng < 0) return eng;
   const bool persistent = eng == RLSTM_ENGINE_PERSISTENT;
@@ -855,7 +873,7 @@ int lstm_stream_fwd_bwd(const rlstm_stream_desc* d, const float* x, const float*
       GemmCall g;
       g.M = Tc * B; g.N = 4 * H; g.K = din;
       g.A = in; g.lda = din; g.B = params[3 * l + 0]; g.ldb = 4 * H; g.C = base + lay.zg; g.ldc = 4 * H;
-      g.bias = params[3 * l + 2]; g.naive = !persistent; g.operand_dtype = d->operand_dtype;
+      g.bias = params[3 * l + 2]; g.naive = !persistent; g.operand_dtype = d->operand_dtype; g.variant = d->gemm_variant;
       {
         ProfScope ps(st, 0, l, 1, 0, gemm_flop(g));
         RLSTM_TRY(gemm(st, g));
@@ -884,9 +902,9 @@ int lstm_stream_fwd_bwd(const rlstm_stream_desc* d, const float* x, const float*
       }
       RLSTM_TRY(accumulate(st, grads[3 * l + 2], dbtmp, (size_t)4 * H, s == 0));
       rc = weight_grads(st, l, Tc, B, dl, H, 1, xin, dl, yl, H, base + lay.zg, grads[3 * l + 0], grads[3 * l + 1], skws,
-                        lay.splitk_floats, !persistent, d->operand_dtype, false, s > 0);
+                        lay.splitk_floats, !persistent, d->operand_dtype, false, d->gemm_variant, s > 0);
       if (rc != RLSTM_OK) return rc;
-      rc = h0_term(st, persistent, d->operand_dtype, Tc, B, H, 1, h0, base + lay.zg, slens, grads[3 * l + 1]);
+      rc = h0_term(st, persistent, d->operand_dtype, d->gemm_variant, Tc, B, H, 1, h0, base + lay.zg, slens, grads[3 * l + 1]);
       if (rc != RLSTM_OK) return rc;
       float* dxl = (l == 0) ? (dx ? dx + (size_t)s * tb * D : nullptr) : dybuf[l & 1];
       if (dxl) {
@@ -894,7 +912,7 @@ int lstm_stream_fwd_bwd(const rlstm_stream_desc* d, const float* x, const float*
         g.transB = true;
         g.M = Tc * B; g.N = dl; g.K = 4 * H;
         g.A = base + lay.zg; g.lda = 4 * H; g.B = params[3 * l + 0]; g.ldb = 4 * H; g.C = dxl; g.ldc = dl;
-        g.naive = !persistent; g.operand_dtype = d->operand_dtype;
+        g.naive = !persistent; g.operand_dtype = d->operand_dtype; g.variant = d->gemm_variant;
         ProfScope ps(st, 3, l, 1, 0, gemm_flop(g));
         RLSTM_TRY(gemm(st, g));
       }
@@ -942,30 +960,31 @@ int rlstm_profile_read(rlstm_profile_entry* out, int max_entries) {
 
 static int gemm_entry(int operand_dtype, int trans_a, int trans_b, int M, int N, int K,
                       const float* A, int lda, const float* B, int ldb, float* C, int ldc,
-                      const float* bias, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream) {
+                      const float* bias, int variant, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream) {
   if (!A || !B || !C) return RLSTM_ENULL;
   if (M <= 0 || N <= 0 || K < 0) return RLSTM_EDIM;
+  if (variant < 0 || variant > 2) return RLSTM_EMODE;
   if (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N) || ldc < N) return RLSTM_EDIM;
   int resident_err = 0;
   GemmCall g;
   g.transA = trans_a != 0; g.transB = trans_b != 0;
   g.M = M; g.N = N; g.K = K; g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.bias = bias;
   g.splitk_ws = static_cast<float*>(splitk_ws); g.splitk_floats = splitk_ws ? splitk_ws_bytes / sizeof(float) : 0;
-  g.operand_dtype = operand_dtype;
+  g.operand_dtype = operand_dtype; g.variant = variant;
   RLSTM_TRY(gemm(static_cast<hipStream_t>(hip_stream), g));
   return RLSTM_OK;
 }
 
 int rlstm_gemm_f32(int trans_a, int trans_b, int M, int N, int K,
                    const float* A, int lda, const float* B, int ldb, float* C, int ldc,
-                   const float* bias, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream) {
-  return gemm_entry(0, trans_a, trans_b, M, N, K, A, lda, B, ldb, C, ldc, bias, splitk_ws, splitk_ws_bytes, hip_stream);
+                   const float* bias, int variant, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream) {
+  return gemm_entry(0, trans_a, trans_b, M, N, K, A, lda, B, ldb, C, ldc, bias, variant, splitk_ws, splitk_ws_bytes, hip_stream);
 }
 
 int rlstm_gemm_bf16(int trans_a, int trans_b, int M, int N, int K,
                     const float* A, int lda, const float* B, int ldb, float* C, int ldc,
-                    const float* bias, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream) {
-  return gemm_entry(1, trans_a, trans_b, M, N, K, A, lda, B, ldb, C, ldc, bias, splitk_ws, splitk_ws_bytes, hip_stream);
+                    const float* bias, int variant, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream) {
+  return gemm_entry(1, trans_a, trans_b, M, N, K, A, lda, B, ldb, C, ldc, bias, variant, splitk_ws, splitk_ws_bytes, hip_stream);
 }
 
 // timed = false: no timing events are created, whatever rlstm_profile_enable() says (events are
@@ -977,9 +996,9 @@ static int lstm_fwd_impl(const rlstm_desc* d, const float* x, const float* W, co
   int rc = check_desc(d);
   if (rc != RLSTM_OK) return rc;
   if (!x || !W || !R || !b || !seq_lens || !y || !c || !reserve || !workspace) return RLSTM_ENULL;
-  const int ldx = d->ldx ? d->ldx : d->D, ldy = d->ldy ? d->ldy : d->H;
-  RecShape s{d->T, d->B, d->H, ldy, 1, d->operand_dtype};
-  if (workspace_bytes < kFlagBytes + rec_workspace_bytes(s)) return RLSTM_ESIZE;
+  const int ldx = d->ldx ? d->ldx : d->D;
+  const RecShape s = layer_rec_shape(d);
+  if (workspace_bytes < kFlagBytes + rec_workspace_bytes_fwd(s)) return RLSTM_ESIZE;
   const int eng = resolve_engine(d->engine, s);
   if (eng < 0) return eng;
   const bool persistent = eng == RLSTM_ENGINE_PERSISTENT;
@@ -993,7 +1012,7 @@ static int lstm_fwd_impl(const rlstm_desc* d, const float* x, const float* W, co
   GemmCall g;
   g.M = d->T * d->B; g.N = 4 * d->H; g.K = d->D;
   g.A = x; g.lda = ldx; g.B = W; g.ldb = 4 * d->H; g.C = zg; g.ldc = 4 * d->H; g.bias = b;
-  g.naive = !persistent; g.operand_dtype = d->operand_dtype;
+  g.naive = !persistent; g.operand_dtype = d->operand_dtype; g.variant = d->gemm_variant;
   {
     ProfScope ps(st, 0, 0, 1, 0, gemm_flop(g), timed);
     RLSTM_TRY(gemm(st, g));
@@ -1040,8 +1059,7 @@ static int static_scratch_address(void** out) {
 
 size_t rlstm_noalloc_scratch_bytes(const rlstm_desc* d) {
   if (check_desc(d) != RLSTM_OK) return 0;
-  RecShape s{d->T, d->B, d->H, d->ldy ? d->ldy : d->H, 1, d->operand_dtype};
-  return kFlagBytes + rec_workspace_bytes(s);
+  return kFlagBytes + rec_workspace_bytes_fwd(layer_rec_shape(d));
 }
 
 int lstm_fwd_noalloc(const rlstm_desc* d, const float* x, const float* W, const float* R, const float* b,
@@ -1068,7 +1086,7 @@ int lstm_bwd(const rlstm_desc* d, const float* x, const float* W, const float* R
   if (!x || !W || !R || !seq_lens || !y || !c || !reserve || !dy || !dW || !dR || !db || !workspace) return RLSTM_ENULL;
   const int ldx = d->ldx ? d->ldx : d->D, ldy = d->ldy ? d->ldy : d->H;
   const int T = d->T, B = d->B, D = d->D, H = d->H;
-  RecShape s{T, B, H, ldy, 1, d->operand_dtype};
+  const RecShape s = layer_rec_shape(d);
   const int eng = resolve_engine(d->engine, s);
   if (eng < 0) return eng;
   const bool persistent = eng == RLSTM_ENGINE_PERSISTENT;
@@ -1089,10 +1107,10 @@ int lstm_bwd(const rlstm_desc* d, const float* x, const float* W, const float* R
     RLSTM_TRY(rec_backward(st, s, &dir, seq_lens, recws, flag, persistent, &resident_err, 0, T));
   }
   rc = weight_grads(st, 0, T, B, D, H, d->direction, x, ldx, y, ldy, zg, dW, dR, skws, skfloats, !persistent, d->operand_dtype,
-                    false);
+                    false, d->gemm_variant);
   if (rc != RLSTM_OK) return rc;
   if (h0) {
-    rc = h0_term(st, persistent, d->operand_dtype, T, B, H, d->direction, h0, zg, seq_lens, dR);
+    rc = h0_term(st, persistent, d->operand_dtype, d->gemm_variant, T, B, H, d->direction, h0, zg, seq_lens, dR);
     if (rc != RLSTM_OK) return rc;
   }
   if (dx) {
@@ -1100,7 +1118,7 @@ int lstm_bwd(const rlstm_desc* d, const float* x, const float* W, const float* R
     g.transB = true;
     g.M = T * B; g.N = D; g.K = 4 * H;
     g.A = zg; g.lda = 4 * H; g.B = W; g.ldb = 4 * H; g.C = dx; g.ldc = ldx;
-    g.naive = !persistent; g.operand_dtype = d->operand_dtype;
+    g.naive = !persistent; g.operand_dtype = d->operand_dtype; g.variant = d->gemm_variant;
     ProfScope ps(st, 3, 0, 1, 0, gemm_flop(g));
     RLSTM_TRY(gemm(st, g));
   }

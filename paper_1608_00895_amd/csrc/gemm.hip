@@ -1054,8 +1054,6 @@ hipError_t launch_bf16(hipStream_t stream, const GemmP& p, dim3 grid, bool vec, 
 
 }  // namespace
 
-namespace { int g_gemm_variant = 0; }
-void gemm_set_variant(int v) { g_gemm_variant = v; }
 
 hipError_t gemm(hipStream_t stream, const GemmCall& g) {
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
@@ -1083,7 +1081,7 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
   // few columns on both sides and a long sum: the kernel with one tile for the whole of C
   if (!bf16 && g.transA && !g.transB && g.M <= 16 * TS_MB && g.N <= 16 * TS_NBW * TS_NW && g.K >= 16 * 1024 && g.splitk_ws &&
       !g.small_footprint && g.M % 4 == 0 && g.N % 4 == 0 && g.lda % 4 == 0 && g.ldb % 4 == 0 && aligned16(g.A) &&
-      aligned16(g.B) && g_gemm_variant != 2) {
+      aligned16(g.B) && g.variant != 2) {
     const size_t per = (size_t)g.M * g.N;
     int slices = (int)std::min<size_t>(512, std::min<size_t>(g.splitk_floats / per, (size_t)g.K / (4 * TS_KC)));
     if (slices >= 2) {
@@ -1137,7 +1135,7 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
   p.per_xcd = (p.work + 7) / 8;
   dim3 grid((unsigned)(8 * p.per_xcd), 1, 1);
   hipError_t e;
-  const bool pipelined = vec && pipelined_ok && (g_gemm_variant == 1 || (g_gemm_variant == 0 && !g.small_footprint));
+  const bool pipelined = vec && pipelined_ok && (g.variant == 1 || (g.variant == 0 && !g.small_footprint));
   if (bf16) {
     if (!g.transA && !g.transB)      e = launch_bf16<false, false>(stream, p, grid, vec, big, pipelined);
     else if (!g.transA && g.transB)  e = launch_bf16<false, true>(stream, p, grid, vec, big, pipelined);

@@ -15,6 +15,11 @@ size_t rec_workspace_bytes(const RecShape& s) {
   return align_up(a > b ? a : b, 256);
 }
 
+size_t rec_workspace_bytes_fwd(const RecShape& s) {
+  const size_t a = persistent_scratch_bytes_fwd(s), b = 2 * stepwise_dir_bytes(s);
+  return align_up(a > b ? a : b, 256);
+}
+
 bool rec_persistent_supported(const RecShape& s, int num_cus, size_t max_lds) {
   return persistent_supported(s, num_cus, max_lds);
 }

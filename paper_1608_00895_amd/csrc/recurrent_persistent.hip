@@ -849,6 +849,333 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
 }
 
 // ---------------------------------------------------------------------------
+// backward, one exchange per step (groups of at most 16 sequences, fp32)
+// ---------------------------------------------------------------------------
+// The kernel above needs two exchanges per step (d a_t to the multipliers, partial tiles back to the owners), and
+// an exchange between CUs costs 2.7 us whatever its size up to a few tens of KB.  Here the sum over k of
+// d h_{t-1}[b, j] = sum_k d a_t[b, k] R[j, k] is split by the OWNERS of k instead: the workgroup that owns U units
+// multiplies its own d a_t[16 x 4U] (never leaves the CU) with its [4U x Hp] rows of R^T (the slice the forward
+// kernel keeps, transposed) and hands every other workgroup c the [16 x U] piece that belongs to c's units; the
+// owners add the pieces of all producers in a fixed order.  One exchange per step; in return every workgroup
+// writes 16 x Hp floats per step (32 KiB at H = 500) instead of 2 + 4 KiB and reads as much (bare exchange at
+// 4 groups of 64 workgroups: 3.4 us against 2.75 + 2.8 us for the two hops).
+//
+// Exchange array of a group: [step parity][consumer c][producer w][q = 4][n = U][i = 4] floats, element
+// (sequence 4q + i, unit c*U + n): a lane's four accumulator values of an MFMA tile (rows 4q..4q+3 of one column)
+// are one 16-byte store, and a consumer's pieces of all producers are contiguous.
+struct PBwd1Params {
+  PBwdDir d[2];
+  float* px[kMaxGroups];           // per group: 2 x [Gm][Gm][16 U] floats
+  unsigned* flags[kMaxGroups];     // per group: [flag copies][Gm]
+  int ndir, NG, Bg;
+  const int32_t* seq_lens;
+  unsigned* err;
+  unsigned long long wait_ticks;
+  int mute_wg;
+  int T, B, H, ldy, Gm;
+  int s_begin, s_end;
+};
+
+// NT: U = 4 NT units per workgroup; TN: the product's 64 TN columns (>= H) are dealt out to the 4 wavefronts, TN
+// MFMA column tiles each.
+template <int NT, int TN>
+__global__ __launch_bounds__(kBlockThreads) void lstm_bwd_onehop_kernel(PBwd1Params p) {
+  constexpr int U = 4 * NT, KZ = 16 * NT;        // units; rows of the resident slice = (gate, unit) pairs
+  constexpr int HP = 64 * TN;                    // columns of the resident slice (units of the layer, padded)
+  constexpr int NE = 16 * U;                     // (sequence, unit) pairs owned by this workgroup
+  constexpr int EPL = NE / 64;                   // pairs per I/O lane
+  constexpr int VEC = 4 * U;                     // 16-byte vectors of one producer's piece
+  constexpr int SUB = 64 / VEC;                  // producers a wavefront loads side by side (VEC <= 64)
+  constexpr int LD = U;                          // loads per lane: 16 producers per wavefront / SUB
+  constexpr int NPART = 4 * SUB;                 // partial sums per vector
+  static_assert(VEC <= 64 && 16 % SUB == 0, "piece must fit a wavefront");
+  extern __shared__ __align__(16) float lds[];
+  const int grp = blockIdx.x % p.NG, wg = blockIdx.x / p.NG;
+  const int dir = grp % p.ndir, bgi = grp / p.ndir, b0 = bgi * p.Bg;
+  const PBwdDir& D = p.d[dir];
+  const int T = p.T, H = p.H, Gm = p.Gm;
+  const int B = min(p.Bg, p.B - b0);
+  if (B <= 0) return;
+  const int s_begin = p.s_begin, s_end = p.s_end;
+  if (ld_dev(p.err) != 0u) return;               // an earlier launch of this pass gave up waiting
+  __builtin_amdgcn_s_setprio(3);
+  const int u0 = wg * U;
+  float* RTs = lds;                              // [KZ][HP], columns rotated per row
+  float* Red = RTs + (size_t)KZ * HP;            // [NPART][VEC][4] partial sums of the pieces
+  float* Az = Red + NPART * VEC * 4;             // [KZ][16]   d a of the frame, MFMA operand order
+  float* bin = Az + KZ * 16;                     // [2][7][NE] gates i,f,o,g, c, c_prev, dy of the frame
+  float* dzo = bin + 2 * 7 * NE;                 // [2][4][NE] d a of the frame (for the I/O wavefront)
+  int* failed = reinterpret_cast<int*>(dzo + 2 * 4 * NE);
+
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const bool is_io = wave == 4;
+  const int lane = tid & 63;
+
+  // resident slice: row k = g*U + uu (gate g of owned unit uu), column j (unit of the layer):  R[j][g*H + u0 + uu]
+  for (int idx = tid; idx < KZ * HP; idx += kBlockThreads) {
+    const int k = idx / HP, j = idx % HP;
+    const int g = k / U, u = u0 + k % U;
+    const float v = (j < H && u < H) ? D.R[(size_t)j * 4 * H + g * H + u] : 0.f;
+    RTs[k * HP + ((j + 16 * (k & 3)) & (HP - 1))] = v;
+  }
+
+  const size_t piece = (size_t)16 * U;                         // floats of one (consumer, producer) piece
+  const size_t pxsz = (size_t)Gm * Gm * piece;                 // floats of one step buffer
+  float* const pxbase = p.px[grp];
+  unsigned* const gflags = p.flags[grp];
+
+  // the pair (sequence, unit) a compute thread owns (threads NE.. of the compute wavefronts own none)
+  const int eb = tid / U, eu = u0 + tid % U;
+  const bool ev = !is_io && tid < NE && eb < B && eu < H;
+  float Dh = 0.f, Dc = 0.f, dbacc[4] = {0.f, 0.f, 0.f, 0.f};
+  int elen = 0;
+  bool vprev = false;
+  if (ev) {
+    const size_t bu = (size_t)(b0 + eb) * H + eu;
+    elen = min(max(p.seq_lens[b0 + eb], 0), T);
+    if (s_begin > 0) {
+      Dh = D.dhstate[bu]; Dc = D.dcstate[bu];
+      const int tlast = D.direction > 0 ? T - s_begin : s_begin - 1;   // frame of step s_begin - 1
+      vprev = tlast < elen;
+    } else {
+      if (D.dhT) Dh = D.dhT[bu];
+      if (D.dcT) Dc = D.dcT[bu];
+    }
+  }
+
+  // I/O lanes (as in the kernel above)
+  int ib[EPL], iu[EPL];
+  bool iv[EPL];
+  float lr[EPL][6];
+  float cnext[EPL];
+#pragma unroll
+  for (int i = 0; i < EPL; ++i) {
+    const int j = lane + i * 64;
+    ib[i] = j / U; iu[i] = u0 + j % U;
+    iv[i] = is_io && ib[i] < B && iu[i] < H;
+    cnext[i] = 0.f;
+  }
+  auto frame_of = [&](int step) { return D.direction > 0 ? T - 1 - step : step; };
+  auto io_load = [&](int step) {
+    const int t = frame_of(step);
+    const int tprev = D.direction > 0 ? t - 1 : t + 1;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+      if (!iv[i]) continue;
+      const size_t row = (size_t)t * p.B + b0 + ib[i];
+      const float* zrow = D.zg + row * 4 * H + iu[i];
+      lr[i][0] = zrow[0]; lr[i][1] = zrow[H]; lr[i][2] = zrow[2 * H]; lr[i][3] = zrow[3 * H];
+      if (tprev >= 0 && tprev < T) lr[i][4] = D.c[((size_t)tprev * p.B + b0 + ib[i]) * H + iu[i]];
+      else lr[i][4] = D.c0 ? D.c0[(size_t)(b0 + ib[i]) * H + iu[i]] : 0.f;
+      lr[i][5] = D.dy[row * p.ldy + iu[i]];
+    }
+  };
+  auto io_stage = [&](int step) {
+    float* dst = bin + (step & 1) * 7 * NE;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+      const int j = lane + i * 64;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) dst[g * NE + j] = iv[i] ? lr[i][g] : 0.f;
+      dst[4 * NE + j] = cnext[i];
+      dst[5 * NE + j] = iv[i] ? lr[i][4] : 0.f;
+      dst[6 * NE + j] = iv[i] ? lr[i][5] : 0.f;
+      cnext[i] = iv[i] ? lr[i][4] : 0.f;
+    }
+  };
+  auto io_store = [&](int step) {
+    const int t = frame_of(step);
+    const float* src = dzo + (step & 1) * 4 * NE;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+      if (!iv[i]) continue;
+      const int j = lane + i * 64;
+      float* zrow = D.zg + ((size_t)t * p.B + b0 + ib[i]) * 4 * H + iu[i];
+      zrow[0] = src[0 * NE + j]; zrow[H] = src[1 * NE + j]; zrow[2 * H] = src[2 * NE + j]; zrow[3 * H] = src[3 * NE + j];
+    }
+  };
+  if (is_io) {
+    const int t0 = frame_of(s_begin);
+#pragma unroll
+    for (int i = 0; i < EPL; ++i)
+      if (iv[i]) cnext[i] = D.c[((size_t)t0 * p.B + b0 + ib[i]) * H + iu[i]];
+    io_load(s_begin);
+    io_stage(s_begin);
+    if (s_begin + 1 < s_end) io_load(s_begin + 1);
+  }
+  if (tid < 2) failed[tid] = 0;
+  __syncthreads();
+
+  // wavefront `wave` takes the pieces of producers [16 wave, 16 wave + 16): lane = (sub, vector)
+  const int sub = lane / VEC, vec = lane % VEC;
+  const unsigned* myflags = gflags + (wg % kFlagCopies) * kFlagCopyStride;
+
+  // pieces of step `step` for this workgroup's units -> Red[NPART][VEC] (each a fixed-order sum over LD producers)
+  auto collect = [&](int step) -> int {
+    int fail = 0;
+    if (!wave_wait_flags(myflags, wave * 16, 16, Gm, (unsigned)(step + 1), p.err, p.wait_ticks)) fail = 1;
+    const float* mine = pxbase + (size_t)(step & 1) * pxsz + (size_t)wg * Gm * piece;
+    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(mine), 0, (int)(Gm * piece * 4), 0x00020000);
+    floatx4 v[LD];
+#pragma unroll
+    for (int k = 0; k < LD; ++k) {
+      const int w = wave * 16 + k * SUB + sub;                  // producers past Gm read beyond the resource: zeros
+      v[k] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)((w * piece + vec * 4) * 4), 0, kAuxSc1));
+    }
+    floatx4 sum = v[0];
+#pragma unroll
+    for (int k = 1; k < LD; ++k) sum += v[k];
+    *reinterpret_cast<floatx4*>(Red + ((wave * SUB + sub) * VEC + vec) * 4) = sum;
+    return fail;
+  };
+  // the owned pair's sum over the NPART partial sums, in order
+  auto gathered = [&]() -> float {
+    const int v = (eb >> 2) * U + (eu - u0), i = eb & 3;
+    float sum = 0.f;
+#pragma unroll
+    for (int k = 0; k < NPART; ++k) sum += Red[(k * VEC + v) * 4 + i];
+    return sum;
+  };
+
+  for (int s = s_begin; s < s_end; ++s) {
+    const int t = frame_of(s);
+    int fail = 0;
+    if (!is_io) {
+      if (s > 0) fail = collect(s - 1);
+    } else {
+      if (s + 1 < s_end) io_stage(s + 1);
+      if (s > s_begin) io_store(s - 1);
+      if (s + 2 < s_end) io_load(s + 2);
+    }
+    if (barrier_any_failed(fail, failed)) {
+      if (tid == 0) st_dev(p.err, 1u);
+      return;
+    }
+    // gate derivatives of the owned pairs; d a of the frame in MFMA operand order and for the I/O wavefront
+    if (!is_io && tid < NE) {
+      float dz[4] = {0.f, 0.f, 0.f, 0.f};
+      if (ev) {
+        if (s > 0) { const float g = gathered(); Dh = vprev ? g : g + Dh; }
+        const float* in = bin + (s & 1) * 7 * NE;
+        const bool m = t < elen;
+        vprev = m;
+        if (m) {
+          const float gi = in[0 * NE + tid], gf = in[1 * NE + tid], go = in[2 * NE + tid], gg = in[3 * NE + tid];
+          const float tc = ftanh(in[4 * NE + tid]);
+          const float dh = in[6 * NE + tid] + Dh;
+          const float d_o = dh * tc;
+          const float dc = Dc + dh * go * (1.0f - tc * tc);
+          dz[0] = dc * gg * gi * (1.0f - gi);
+          dz[1] = dc * in[5 * NE + tid] * gf * (1.0f - gf);
+          dz[2] = d_o * go * (1.0f - go);
+          dz[3] = dc * gi * (1.0f - gg * gg);
+          Dc = dc * gf;
+        }
+      }
+      float* out = dzo + (s & 1) * 4 * NE;
+      const int uu = tid % U;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        Az[(g * U + uu) * 16 + eb] = dz[g];
+        out[g * NE + tid] = dz[g];
+        dbacc[g] += dz[g];
+      }
+    }
+    __syncthreads();
+    // this workgroup's d a_t times its rows of R^T: the wavefront's 16 TN columns of the [16 x HP] result
+    if (!is_io) {
+      const int l16 = lane & 15, lq = lane >> 4;
+      floatx4 acc[TN];
+#pragma unroll
+      for (int nt = 0; nt < TN; ++nt) acc[nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+      // the rotation of a row's columns, 16 (k % 4) = 16 lq, is the same for every row this lane reads: one LDS
+      // address per column tile, and k-step ks at a constant distance 4 ks HP from k-step 0
+      const float* brow[TN];
+#pragma unroll
+      for (int nt = 0; nt < TN; ++nt)
+        brow[nt] = RTs + (size_t)lq * HP + (((wave * TN + nt) * 16 + l16 + 16 * lq) & (HP - 1));
+      // operands of k-step ks + 1 are fetched from LDS while the MFMAs of k-step ks run; the scheduling barriers keep
+      // the compiler from fetching all k-steps at once (which costs 50 registers more and, beside the matrix-product
+      // kernels that share the CU, one of their two workgroups)
+      float a_cur = Az[lq * 16 + l16], b_cur[TN];
+#pragma unroll
+      for (int nt = 0; nt < TN; ++nt) b_cur[nt] = brow[nt][0];
+#pragma unroll
+      for (int ks = 0; ks < KZ / 4; ++ks) {
+        float a_next = 0.f, b_next[TN];
+        if (ks + 1 < KZ / 4) {
+          a_next = Az[((ks + 1) * 4 + lq) * 16 + l16];
+#pragma unroll
+          for (int nt = 0; nt < TN; ++nt) b_next[nt] = brow[nt][(size_t)(ks + 1) * 4 * HP];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int nt = 0; nt < TN; ++nt) acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur, b_cur[nt], acc[nt], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (ks + 1 < KZ / 4) {
+          a_cur = a_next;
+#pragma unroll
+          for (int nt = 0; nt < TN; ++nt) b_cur[nt] = b_next[nt];
+        }
+      }
+      // lane (lq, l16) of tile nt holds rows 4 lq .. 4 lq + 3 of column j: one 16-byte store into the piece of j's owner
+      float* cur = pxbase + (size_t)(s & 1) * pxsz;
+      __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(cur, 0, (int)(pxsz * 4), 0x00020000);
+#pragma unroll
+      for (int nt = 0; nt < TN; ++nt) {
+        const int j = (wave * TN + nt) * 16 + l16;
+        const int c = j / U, n = j % U;
+        if (c < Gm) {
+          const size_t off = ((size_t)c * Gm + wg) * piece + (size_t)(lq * U + n) * 4;
+          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(intx4, acc[nt]), wr, (int)(off * 4), 0, kAuxSc1);
+        }
+      }
+      wait_stores_acked();
+    }
+    __syncthreads();
+    if ((int)blockIdx.x != p.mute_wg) publish_flag(gflags, wg, (unsigned)(s + 1));
+  }
+
+  int fail = 0;
+  if (is_io) {
+    io_store(s_end - 1);
+  } else if (s_end == T) {
+    fail = collect(T - 1);
+  }
+  if (barrier_any_failed(fail, failed + 1)) {
+    if (tid == 0) st_dev(p.err, 1u);
+    return;
+  }
+  if (ev && s_end == T) { const float g = gathered(); Dh = vprev ? g : g + Dh; }
+  __syncthreads();                               // Red is reused as the bias gradient's stage below
+  float* stage = Red;                            // [16][4U]
+  if (!is_io && tid < NE) {
+    const int uu = tid % U;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) stage[eb * 4 * U + g * U + uu] = ev ? dbacc[g] : 0.f;
+    if (ev) {
+      const size_t bu = (size_t)(b0 + eb) * H + eu;
+      if (s_end < T) { D.dhstate[bu] = Dh; D.dcstate[bu] = Dc; }
+      else {
+        if (D.dh0) D.dh0[bu] = Dh;
+        if (D.dc0) D.dc0[bu] = Dc;
+      }
+    }
+  }
+  __syncthreads();
+  if (tid < 4 * U) {
+    const int g = tid / U, u = u0 + tid % U;
+    if (u < H) {
+      float sum = 0.f;
+      for (int b = 0; b < B; ++b) sum += stage[b * 4 * U + tid];
+      float* dst = (p.NG > p.ndir ? D.dbpart + (size_t)bgi * 4 * H : D.db) + g * H + u;
+      *dst = s_begin > 0 ? *dst + sum : sum;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // set-up kernels: clear flags, exchange arrays and tags; seed h0 in operand order;
 // add up the bias gradients of the groups of sequences
 // ---------------------------------------------------------------------------
@@ -901,7 +1228,6 @@ __global__ __launch_bounds__(256) void db_sum_kernel(DbSumParams p) {
 // ---- host side ----------------------------------------------------------------
 unsigned long long g_wait_ticks = kDefaultWaitTicks;
 int g_mute_wg = -1;
-int g_batch_groups = 0;                          // 0: chosen by make_plan
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 constexpr size_t kFlagBytes = (size_t)kFlagCopies * kFlagCopyStride * sizeof(unsigned);
 
@@ -912,6 +1238,9 @@ struct Plan {
   int Gf, Hp, nchF;
   int PG, Gb, Hq, nchB;
   size_t ldsF, ldsB;
+  bool onehop;                                   // backward pass with one exchange per step (lstm_bwd_onehop_kernel)
+  int TN;                                        // its column tiles per wavefront (64 TN >= H)
+  size_t ldsB1, px_bytes;                        // its LDS request; bytes of its exchange array per group
 };
 
 // kernels exist for these (ROWS, NT)
@@ -932,7 +1261,11 @@ Plan plan_for(const RecShape& s, int num_cus, size_t max_lds, int nb) {
   const int Bg = (s.B + nb - 1) / nb;
   if (Bg > 64) return pl;
   const int per_group = num_cus / NG;
+  // the backward kernel with one exchange per step needs at most 64 workgroups per group: when it is asked for, the
+  // first round only takes slice widths that allow it
+  for (int round = (s.bwd_exchange == 2 && !bf && Bg <= 16 && s.H <= 512) ? 0 : 1; round < 2; ++round)
   for (int NT = 1; NT <= 4; NT *= 2) {
+    if (round == 0 && (s.H + 4 * NT - 1) / (4 * NT) > 64) continue;
     const int rows = Bg <= 8 && have_kernel(8, NT) ? 8 : (Bg <= 16 ? 16 : (Bg <= 32 ? 32 : (Bg <= 48 && have_kernel(48, NT) ? 48 : 64)));
     if (!have_kernel(rows, NT)) continue;
     const int MT = rows <= 16 ? 1 : rows / 16;
@@ -960,6 +1293,19 @@ Plan plan_for(const RecShape& s, int num_cus, size_t max_lds, int nb) {
     pl.Gf = Gf; pl.Hp = Hp; pl.nchF = bf ? (Hp / 4 / 32) * MT : (Hp / 16) * MT / 4;
     pl.PG = PG; pl.Gb = Gb; pl.Hq = Hq; pl.nchB = bf ? (Hq / 32) * MT : (Hq / 4) * MT / 4;
     pl.ldsF = lf > exclusive ? lf : exclusive; pl.ldsB = lb > exclusive ? lb : exclusive;
+    // One exchange per step in the backward pass: groups of at most 16 sequences (one MFMA row tile), fp32, the
+    // forward kernel's deal of the units (Gf <= 64 workgroups), at most 512 units.
+    pl.onehop = false; pl.TN = 0; pl.ldsB1 = 0; pl.px_bytes = 0;
+    if (!bf && rows <= 16 && Gf <= 64 && s.H <= 512 && s.bwd_exchange == 2) {
+      int TN = 1;
+      while (64 * TN < s.H) TN *= 2;
+      const size_t l1 = ((size_t)16 * NT * 64 * TN + 1024 + (size_t)16 * NT * 16 + (2 * 7 + 2 * 4) * 16 * U) * sizeof(float) + 16;
+      if (l1 <= max_lds) {
+        pl.onehop = true; pl.TN = TN;
+        pl.ldsB1 = l1 > exclusive ? l1 : exclusive;
+        pl.px_bytes = align_up((size_t)2 * Gf * Gf * 16 * U * sizeof(float), 256);
+      }
+    }
     return pl;
   }
   return pl;
@@ -976,7 +1322,7 @@ Plan make_plan(const RecShape& s, int num_cus, size_t max_lds) {
   none.ok = false;
   if (s.operand_dtype != 0 && s.operand_dtype != 1) return none;
   if (s.B < 1 || s.H < 1 || s.ndir < 1 || s.ndir > 2) return none;
-  if (g_batch_groups > 0) return plan_for(s, num_cus, max_lds, g_batch_groups);
+  if (s.batch_groups > 0) return plan_for(s, num_cus, max_lds, s.batch_groups);
   int first = 1;
   while (first * 2 * s.ndir <= kMaxGroups && (s.B + first * 2 - 1) / (first * 2) >= 16) first *= 2;
   for (int nb = first; nb >= 1; nb /= 2) {
@@ -1034,6 +1380,22 @@ size_t groups_bytes_max(const RecShape& s) {
   }
   return m;
 }
+// Upper bound of the one-exchange backward kernel's arrays over all plans a device may get (they sit behind the
+// other scratch and are not needed by the forward pass): NG groups of 2 x Gm x Gm pieces of 16 U floats, Gm = ceil(H / U).
+size_t onehop_bytes_max(const RecShape& s) {
+  if (s.operand_dtype != 0 || s.H > 512) return 0;
+  size_t m = 0;
+  for (int nb = 1; nb * s.ndir <= kMaxGroups; nb *= 2) {
+    if (((size_t)s.B + nb - 1) / nb > 16) continue;
+    for (int U = 4; U <= 16; U *= 2) {
+      const size_t Gm = ((size_t)s.H + U - 1) / U;
+      if (Gm > 64) continue;
+      const size_t v = (size_t)nb * s.ndir * align_up(2 * Gm * Gm * 16 * U * sizeof(float), 256);
+      if (v > m) m = v;
+    }
+  }
+  return m;
+}
 size_t state_bytes(const RecShape& s) { return align_up((size_t)s.B * s.H * sizeof(float), 256); }
 size_t dbpart_bytes(const RecShape& s) { return align_up((size_t)kMaxGroups * 4 * s.H * sizeof(float), 256); }
 // per-direction arrays behind the groups: which = 0, 1 state arrays, 2 per-group bias gradients
@@ -1048,7 +1410,6 @@ void persistent_test_hook(int mute_workgroup, unsigned long long wait_ticks) {
   g_mute_wg = mute_workgroup;
   g_wait_ticks = wait_ticks ? wait_ticks : kDefaultWaitTicks;
 }
-void persistent_set_batch_groups(int nb) { g_batch_groups = nb; }
 
 bool persistent_supported(const RecShape& s, int num_cus, size_t max_lds) {
   return make_plan(s, num_cus, max_lds).ok;
@@ -1057,20 +1418,23 @@ bool persistent_supported(const RecShape& s, int num_cus, size_t max_lds) {
 size_t persistent_lds_bytes(const RecShape& s, int num_cus, size_t max_lds) {
   const Plan pl = make_plan(s, num_cus, max_lds);
   if (!pl.ok) return 0;
-  return pl.ldsF > pl.ldsB ? pl.ldsF : pl.ldsB;
+  const size_t b = pl.onehop ? pl.ldsB1 : pl.ldsB;
+  return pl.ldsF > b ? pl.ldsF : b;
 }
 
-bool persistent_plan_info(const RecShape& s, int num_cus, size_t max_lds, int out[8]) {
+bool persistent_plan_info(const RecShape& s, int num_cus, size_t max_lds, int out[10]) {
   const Plan pl = make_plan(s, num_cus, max_lds);
   if (!pl.ok) return false;
   out[0] = pl.NG; out[1] = pl.Bg; out[2] = pl.ROWS; out[3] = pl.U;
-  out[4] = pl.Gf; out[5] = pl.Gb; out[6] = pl.Hp; out[7] = pl.Hq;
+  out[4] = pl.Gf; out[5] = pl.onehop ? pl.Gf : pl.Gb; out[6] = pl.Hp; out[7] = pl.onehop ? 64 * pl.TN : pl.Hq;
+  out[8] = pl.onehop ? 1 : 2; out[9] = 0;
   return true;
 }
 
-size_t persistent_scratch_bytes(const RecShape& s) {
+size_t persistent_scratch_bytes_fwd(const RecShape& s) {
   return groups_bytes_max(s) + (size_t)s.ndir * (2 * state_bytes(s) + dbpart_bytes(s));
 }
+size_t persistent_scratch_bytes(const RecShape& s) { return persistent_scratch_bytes_fwd(s) + onehop_bytes_max(s); }
 
 hipError_t persistent_forward(hipStream_t stream, const RecShape& s, const RecFwdDir* dirs, const int32_t* seq_lens,
                               char* scratch, unsigned* err, int* resident_err, int s_begin, int s_end) {
@@ -1130,6 +1494,58 @@ hipError_t persistent_forward(hipStream_t stream, const RecShape& s, const RecFw
   return hipErrorInvalidValue;
 }
 
+namespace {
+// the backward pass with one exchange per step (see lstm_bwd_onehop_kernel)
+hipError_t onehop_backward(hipStream_t stream, const RecShape& s, const Plan& pl, const DeviceInfo& di, const RecBwdDir* dirs,
+                           const int32_t* seq_lens, char* scratch, unsigned* err, int* resident_err, int s_begin, int s_end) {
+  const GroupBytes gb = group_bytes(s, pl.nb);
+  if ((size_t)pl.NG * pl.px_bytes > onehop_bytes_max(s)) return hipErrorInvalidValue;
+  char* pxbase = scratch + persistent_scratch_bytes_fwd(s);
+  PrepParams pp{};
+  PBwd1Params kp{};
+  for (int g = 0; g < pl.NG; ++g) {
+    kp.flags[g] = reinterpret_cast<unsigned*>(scratch + (size_t)g * gb.total);
+    kp.px[g] = reinterpret_cast<float*>(pxbase + (size_t)g * pl.px_bytes);
+  }
+  DbSumParams ds{};
+  for (int d = 0; d < s.ndir; ++d) {
+    PBwdDir& k = kp.d[d];
+    k.zg = dirs[d].zg; k.R = dirs[d].R; k.c = dirs[d].c; k.c0 = dirs[d].c0; k.dy = dirs[d].dy;
+    k.dhT = dirs[d].dhT; k.dcT = dirs[d].dcT; k.dh0 = dirs[d].dh0; k.dc0 = dirs[d].dc0; k.db = dirs[d].db;
+    k.dhstate = dir_array(scratch, s, d, 0); k.dcstate = dir_array(scratch, s, d, 1);
+    k.dbpart = dir_array(scratch, s, d, 2);
+    k.direction = dirs[d].direction;
+    ds.db[d] = dirs[d].db; ds.dbpart[d] = k.dbpart;
+  }
+  // only the flags have to start at zero: every read of the exchange array is gated by them
+  pp.zero_words = reinterpret_cast<unsigned*>(scratch); pp.nzero = (size_t)pl.NG * gb.total / 4;
+  kp.ndir = s.ndir; kp.NG = pl.NG; kp.Bg = pl.Bg;
+  kp.seq_lens = seq_lens; kp.err = err; kp.wait_ticks = g_wait_ticks; kp.mute_wg = g_mute_wg;
+  kp.T = s.T; kp.B = s.B; kp.H = s.H; kp.ldy = s.ldy; kp.Gm = pl.Gf;
+  kp.s_begin = s_begin; kp.s_end = s_end;
+  if (s_begin == 0) hipLaunchKernelGGL(prep_kernel, dim3(256), dim3(256), 0, stream, pp);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int grid = pl.Gf * pl.NG;
+  e = hipErrorInvalidValue;
+#define RLSTM_BWD1_CASE(NT_, TN_)                                                                              \
+  if (pl.NT == NT_ && pl.TN == TN_)                                                                            \
+    e = resident_launch(lstm_bwd_onehop_kernel<NT_, TN_>, grid, kBlockThreads, pl.ldsB1, di.num_cus, stream,   \
+                        &kp, resident_err);
+  RLSTM_BWD1_CASE(1, 1) RLSTM_BWD1_CASE(1, 2) RLSTM_BWD1_CASE(1, 4)
+  RLSTM_BWD1_CASE(2, 1) RLSTM_BWD1_CASE(2, 2) RLSTM_BWD1_CASE(2, 4) RLSTM_BWD1_CASE(2, 8)
+  RLSTM_BWD1_CASE(4, 1) RLSTM_BWD1_CASE(4, 2) RLSTM_BWD1_CASE(4, 4) RLSTM_BWD1_CASE(4, 8)
+#undef RLSTM_BWD1_CASE
+  if (e != hipSuccess) return e;
+  if (pl.nb > 1 && s_end == s.T) {
+    ds.ndir = s.ndir; ds.nb = (s.B + pl.Bg - 1) / pl.Bg; ds.n = 4 * s.H;
+    hipLaunchKernelGGL(db_sum_kernel, dim3((unsigned)((ds.n + 255) / 256)), dim3(256), 0, stream, ds);
+    e = hipGetLastError();
+  }
+  return e;
+}
+}  // namespace
+
 hipError_t persistent_backward(hipStream_t stream, const RecShape& s, const RecBwdDir* dirs, const int32_t* seq_lens,
                                char* scratch, unsigned* err, int* resident_err, int s_begin, int s_end) {
   if (s_begin < 0 || s_end > s.T || s_begin >= s_end) return hipErrorInvalidValue;
@@ -1138,6 +1554,7 @@ hipError_t persistent_backward(hipStream_t stream, const RecShape& s, const RecB
   if (e != hipSuccess) return e;
   const Plan pl = make_plan(s, di.num_cus, di.max_lds);
   if (!pl.ok) { *resident_err = 1; return hipErrorInvalidValue; }
+  if (pl.onehop) return onehop_backward(stream, s, pl, di, dirs, seq_lens, scratch, err, resident_err, s_begin, s_end);
   const size_t wbytes = (size_t)pl.nchB * 1024;
   const size_t exch_bytes = 2 * 16 * wbytes;
   const size_t part_words = (size_t)2 * pl.PG * 4 * pl.Bp * pl.UG;

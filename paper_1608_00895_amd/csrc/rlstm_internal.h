@@ -31,10 +31,9 @@ struct GemmCall {
   int operand_dtype = 0;
   bool naive = false;
   bool small_footprint = false;   // runs beside the recurrent kernels on shared CUs: keep to the plain 128 x 128 kernel
+  int variant = 0;                // fp32 kernel choice: 0 by call, 1 the pipelined kernel wherever it applies, 2 the plain kernel
 };
 hipError_t gemm(hipStream_t stream, const GemmCall& g);
-// fp32 kernel choice: 0 by call (default), 1 the pipelined kernel wherever it applies, 2 the plain kernel
-void gemm_set_variant(int v);
 
 // ---------------------------------------------------------------------------
 // Recurrent passes.  One call handles ndir (1 or 2) independent directions of
@@ -66,10 +65,15 @@ struct RecBwdDir {
 };
 struct RecShape {
   int T, B, H, ldy, ndir, operand_dtype;
+  // tuning of the persistent engine (0 = chosen per shape)
+  int batch_groups = 0;   // groups the sequences are dealt out to per direction
+  int bwd_exchange = 0;   // exchanges per step of the backward pass: 1 two (d a_t out, partial tiles back), 2 one where it applies
 };
 
 // Scratch bytes the recurrent passes need (max over both engines, fwd and bwd).
 size_t rec_workspace_bytes(const RecShape& s);
+// the part of it that the forward pass uses (a prefix of the same layout)
+size_t rec_workspace_bytes_fwd(const RecShape& s);
 // true if the persistent kernels can hold this shape (LDS, grid <= CUs).
 bool rec_persistent_supported(const RecShape& s, int num_cus, size_t max_lds);
 
@@ -90,10 +94,11 @@ size_t persistent_scratch_bytes(const RecShape& s);
 size_t persistent_lds_bytes(const RecShape& s, int num_cus, size_t max_lds);
 // LDS of the matrix-product kernel that can share a CU with other work (128 x 128 tiles)
 size_t gemm_small_lds_bytes(int operand_dtype);
-// {groups, sequences per group, rows a group can hold, units per workgroup, forward members, backward members, Hp, Hq}
-bool persistent_plan_info(const RecShape& s, int num_cus, size_t max_lds, int out[8]);
-// number of groups the sequences of a minibatch are dealt out to per direction (0: chosen per shape)
-void persistent_set_batch_groups(int nb);
+// {groups, sequences per group, rows a group can hold, units per workgroup, forward members, backward members, Hp,
+//  Hq (two exchanges) or padded H of the backward product (one), exchanges per backward step, 0}
+bool persistent_plan_info(const RecShape& s, int num_cus, size_t max_lds, int out[10]);
+// scratch of the forward pass alone (the backward pass may need more)
+size_t persistent_scratch_bytes_fwd(const RecShape& s);
 // test hook: workgroup `mute_workgroup` (-1: none) withholds its step flags; wait bound in 100 MHz ticks (0: default)
 void persistent_test_hook(int mute_workgroup, unsigned long long wait_ticks);
 hipError_t persistent_forward(hipStream_t stream, const RecShape& s, const RecFwdDir* dirs, const int32_t* seq_lens,
@@ -148,6 +153,13 @@ hipError_t mdlstm_scatter_grads(hipStream_t stream, int D, int H, const float* c
 size_t mdlstm_dbpart_floats(const MdShape& s);
 hipError_t mdlstm_backward(hipStream_t stream, const MdShape& s, const MdDir* dirs, const int32_t* widths, const float* dy,
                            float* dbpart, float* const* db, unsigned long long* halo, unsigned* err);
+
+// the stepwise engine of the two-dimensional layer (mdlstm_stepwise.hip): one launch per anti-diagonal, any shape;
+// zg must hold b + x W (there is no in-kernel input path); scratch: mdlstm_stepwise_scratch_floats() floats
+size_t mdlstm_stepwise_scratch_floats(const MdShape& s);
+hipError_t mdlstm_stepwise_forward(hipStream_t stream, const MdShape& s, const MdDir* dirs, const int32_t* widths, float* y);
+hipError_t mdlstm_stepwise_backward(hipStream_t stream, const MdShape& s, const MdDir* dirs, const int32_t* widths,
+                                    const float* dy, float* scratch, float* const* db);
 
 // output layer and updates (output_layer.hip).  z: [T*B, ld], logits in columns [0, C) in, d loss / d logits out with
 // columns [C, ld) zeroed; scratch: ce_scratch_floats(); loss, errors: one value each; dbo: [C] column sums of the result

@@ -179,6 +179,14 @@ def config5() -> ImageWorkload:
                                wscale=0.1, seed=5, forget_bias=-1.0)
 
 
+def config5_plain() -> ImageWorkload:
+    """The shape of config 5 with the plain recipe: every bias zero, the forget gates' too (same draws as config 5).  Its results
+    depend on their inputs much more strongly than config 5's (the cell state is not contractive), so it is a parity
+    case with a tolerance of its own, not a benchmark workload."""
+    return make_image_workload("config5_plain_mdlstm_h64_B8_H32", Hh=64, B=8, D=1, H=32, w_lo=200, w_hi=800,
+                               wscale=0.1, seed=5, forget_bias=0.0)
+
+
 def paper_corpus(n_seq: int = 40, seed: int = 6) -> Tuple[np.ndarray, np.ndarray]:
     """A corpus shaped like the one the paper's experiments use (Sec. 6): 45 values per frame, segment
     lengths around 738 frames with a spread of 291 (drawn normal, clipped to [100, 1600]).  Returns
@@ -192,23 +200,19 @@ def paper_corpus(n_seq: int = 40, seed: int = 6) -> Tuple[np.ndarray, np.ndarray
     return x, lens
 
 
-def paper_chunks() -> Workload:
-    """The batch shape the paper times (Sec. 6): the corpus above cut into segments of 250 frames without
-    overlap, the first 81 segments as one minibatch, three bidirectional layers of 512 units, fp32.
-    The segmentation here is plain slicing of the corpus arrays (no LSTM arithmetic)."""
-    cx, clens = paper_corpus()
-    size, nb = 250, 81
-    cols, lens = [], []
-    for b in range(len(clens)):
-        for t0 in range(0, int(clens[b]), size):
-            n = min(size, int(clens[b]) - t0)
-            seg = np.zeros((size, cx.shape[2]), np.float32)
-            seg[:n] = cx[t0:t0 + n, b]
-            cols.append(seg)
-            lens.append(n)
-    assert len(cols) >= nb
-    x = np.ascontiguousarray(np.stack(cols[:nb], axis=1))
-    seq_lens = np.array(lens[:nb], np.int32)
+PAPER_SEGMENT_FRAMES = 250     # Sec. 6: segments of 250 frames ...
+PAPER_BATCH_SEGMENTS = 81      # ... 81 of them per batch
+
+
+def paper_workload(x: np.ndarray, seq_lens: np.ndarray) -> Workload:
+    """The network the paper times (Sec. 6: three bidirectional layers of 512 units, fp32) on a minibatch of
+    segments that the caller has cut from paper_corpus(): x [250, 81, 45] with zeros past each segment's length,
+    seq_lens [81].  Cutting the corpus is part of the method and is not done here: the oracle side calls
+    oracle.chunk_batch, the HIP side rlstm_chunk_plan / rlstm_chunk_gather.  Draws the weights U(-0.05, 0.05) and the
+    loss weights G ~ N(0,1) (zero past each segment's length)."""
+    size, nb = x.shape[0], x.shape[1]
+    seq_lens = np.asarray(seq_lens, np.int32)
+    assert x.shape[2] == 45 and seq_lens.shape == (nb,)
     rng = np.random.Generator(np.random.Philox(66))
     L, D, H = 3, 45, 512
     params = []
@@ -223,7 +227,8 @@ def paper_chunks() -> Workload:
     G = rng.standard_normal((size, nb, 2 * H)).astype(np.float32)
     for b in range(nb):
         G[seq_lens[b]:, b, :] = 0.0
-    return Workload("paper_3x512_81_segments_of_250", L, size, nb, D, H, True, 0, seq_lens, x, params, G)
+    return Workload("paper_3x512_81_segments_of_250", L, size, nb, D, H, True, 0, seq_lens,
+                    np.ascontiguousarray(x, dtype=np.float32), params, G)
 
 
 def output_layer(T: int, B: int, F: int, C: int, seed: int, wscale: float = 0.1):

@@ -17,7 +17,7 @@ import numpy as np
 ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
 sys.path.insert(0, ROOT)
 
-from oracle import adam_step, blstm_stack_backward, blstm_stack_forward, softmax_ce_backward, softmax_ce_forward  # noqa: E402
+from oracle import adam_step, blstm_stack_backward, blstm_stack_forward, chunk_batch, softmax_ce_backward, softmax_ce_forward  # noqa: E402
 from paper_1608_00895_amd import synth  # noqa: E402
 
 CLASSES, LABEL_SEED, WSCALE = 1501, 67, 0.05
@@ -25,7 +25,10 @@ ADAM = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8)
 
 
 def main():
-    wl = synth.paper_chunks()
+    cx, clens = synth.paper_corpus()
+    xc, (_, _, clen) = chunk_batch(cx, clens, synth.PAPER_SEGMENT_FRAMES, synth.PAPER_SEGMENT_FRAMES)
+    nb = synth.PAPER_BATCH_SEGMENTS
+    wl = synth.paper_workload(xc[:, :nb], clen[:nb])      # the first 81 segments of the corpus, cut by the oracle
     Wo, bo, labels = synth.output_layer(wl.T, wl.B, 2 * wl.H, CLASSES, seed=LABEL_SEED, wscale=WSCALE)
     params = [[tuple(a.astype(np.float64) for a in p) for p in layer] for layer in wl.params]
     t0 = time.time()

@@ -27,13 +27,13 @@ def rel_err(got, ref) -> float:
 
 
 def run_lstm_layer(x, W, R, b, seq_lens, direction, h0=None, c0=None, dy=None, dhT=None, dcT=None,
-                   engine=rl.RLSTM_ENGINE_AUTO, ldx=0, ldy=0, want_dx=True, fill=float("nan"), operand_dtype=0):
+                   engine=rl.RLSTM_ENGINE_AUTO, ldx=0, ldy=0, want_dx=True, fill=float("nan"), operand_dtype=0, **tuning):
     """lstm_fwd then lstm_bwd on the GPU.  x/y/dy may use padded row strides ldx/ldy
     (padding is filled with `fill` to show that it is neither read into results nor written)."""
     T, B, D = x.shape
     H = R.shape[0]
     desc = rl.rlstm_desc(T=T, B=B, D=D, H=H, direction=direction, operand_dtype=operand_dtype, ldx=ldx, ldy=ldy,
-                         engine=engine)
+                         engine=engine, **tuning)        # tuning: batch_groups, bwd_exchange, gemm_variant
     lx = ldx or D
     ly = ldy or H
     xd = torch.full((T, B, lx), fill, device=DEV)
@@ -73,11 +73,12 @@ def run_lstm_layer(x, W, R, b, seq_lens, direction, h0=None, c0=None, dy=None, d
 class StackRun:
     """Device buffers for blstm_stack_fwd_bwd on one workload."""
 
-    def __init__(self, wl, engine=rl.RLSTM_ENGINE_AUTO, want_dx=True, two_streams=True):
+    def __init__(self, wl, engine=rl.RLSTM_ENGINE_AUTO, want_dx=True, two_streams=True, **tuning):
+        """tuning: the descriptor's tuning fields (first_piece, batch_groups, overlap_mode, gemm_variant, bwd_exchange)."""
         assert wl.bidirectional
         self.wl = wl
         self.desc = rl.rblstm_desc(L=wl.L, T=wl.T, B=wl.B, D=wl.D, H=wl.H, operand_dtype=wl.operand_dtype,
-                                   engine=engine)
+                                   engine=engine, **tuning)
         self.x = dev(wl.x)
         self.seq_lens = dev(wl.seq_lens, torch.int32)
         self.params = [dev(a) for layer in wl.params for p in layer for a in p]
@@ -115,3 +116,68 @@ def oracle_stack(wl):
         for d in range(2):
             flat += [grads[l][d]["dW"], grads[l][d]["dR"], grads[l][d]["db"]]
     return dict(y=y, dx=dx, grads=flat)
+
+
+def paper_batch_from_corpus():
+    """The paper-shaped minibatch (81 segments of 250 frames) cut from the synthetic corpus BY THE LIBRARY: segment
+    table on the host (rlstm_chunk_plan), gather on the device (rlstm_chunk_gather).  Returns the Workload."""
+    from paper_1608_00895_amd import synth
+    cx, clens = synth.paper_corpus()
+    size, nb = synth.PAPER_SEGMENT_FRAMES, synth.PAPER_BATCH_SEGMENTS
+    seq, start, length = rl.rlstm_chunk_plan(clens, size, size)
+    xc = torch.empty((size, nb, cx.shape[2]), device=DEV)
+    rl.rlstm_chunk_gather(dev(cx), dev(seq[:nb], torch.int32), dev(start[:nb], torch.int32), dev(length[:nb], torch.int32),
+                          size, xc)
+    torch.cuda.synchronize()
+    return synth.paper_workload(xc.cpu().numpy(), length[:nb])
+
+
+def check_structured_samples(g, prefix, y, dx, grads, seq_lens, L, tol_y, tol_grad, what):
+    """Compares the places a golden file stores beyond its random samples: whole frames of y_top / dx (`frames`,
+    `y_slab`, `dx_slab`), every sequence's last valid and first padded frame (`y_end`, `dx_end`), the last rows and
+    the last units' columns of every dW / dR, every db whole.  y, dx: device tensors [T,B,.]; grads: list of device
+    tensors (dW, dR, db per layer and direction).  Errors are relative to the tensors' largest absolute values as
+    stored with the random samples (`<name>_max`).  Returns the worst errors (forward, gradients)."""
+    T, B = y.shape[0], y.shape[1]
+    frames = [int(t) for t in g[prefix + "frames"]]
+    worst_y = worst_g = 0.0
+
+    def upd(got, ref, scale):
+        return float(np.abs(np.asarray(got, np.float64) - np.asarray(ref, np.float64)).max() / scale)
+
+    ymax, dxmax = float(g[prefix + "y_max"]), float(g[prefix + "dx_max"])
+    worst_y = max(worst_y, upd(y[frames].cpu().numpy(), g[prefix + "y_slab"], ymax))
+    if dx is not None:
+        worst_g = max(worst_g, upd(dx[frames].cpu().numpy(), g[prefix + "dx_slab"], dxmax))
+    lens = np.asarray(seq_lens, np.int64)
+    nidx = torch.arange(B, device=y.device)
+    last = torch.from_numpy(lens - 1).to(y.device)
+    worst_y = max(worst_y, upd(y[last, nidx].cpu().numpy(), g[prefix + "y_end"][:, 0], ymax))
+    if dx is not None:
+        worst_g = max(worst_g, upd(dx[last, nidx].cpu().numpy(), g[prefix + "dx_end"][:, 0], dxmax))
+    short = np.nonzero(lens < T)[0]
+    if len(short):
+        first_pad = torch.from_numpy(lens[short]).to(y.device)
+        sidx = torch.from_numpy(short).to(y.device)
+        assert not bool(y[first_pad, sidx].any()), what + ": y is not zero at a sequence's first padded frame"
+        assert not g[prefix + "y_end"][short, 1].any()
+        if dx is not None:
+            assert not bool(dx[first_pad, sidx].any()), what + ": dx is not zero at a sequence's first padded frame"
+    cols = torch.from_numpy(np.asarray(g[prefix + "cols"], np.int64)).to(y.device)
+    k = 0
+    for l in range(L):
+        for d in range(2):
+            for nm in ("dW", "dR"):
+                t = grads[k]
+                scale = float(g[f"{prefix}{nm}_{l}_{d}_max"])
+                worst_g = max(worst_g, upd(t[-4:, :].cpu().numpy(), g[f"{prefix}{nm}_{l}_{d}_lastrows"], scale))
+                worst_g = max(worst_g, upd(t[:, cols].cpu().numpy(), g[f"{prefix}{nm}_{l}_{d}_lastcols"], scale))
+                k += 1
+            ref = g[f"{prefix}db_{l}_{d}_whole"] if f"{prefix}db_{l}_{d}_whole" in g.files else g[f"{prefix}db_{l}_{d}"]
+            worst_g = max(worst_g, upd(grads[k].cpu().numpy(), ref, max(float(np.abs(ref).max()), 1e-30)))
+            k += 1
+    print(f"{what}: structured samples (frames {frames}, sequence ends, last rows / columns, bias gradients): "
+          f"forward {worst_y:.2e}, gradients {worst_g:.2e}", flush=True)
+    assert worst_y < tol_y, (what, "forward", worst_y)
+    assert worst_g < tol_grad, (what, "gradients", worst_g)
+    return worst_y, worst_g

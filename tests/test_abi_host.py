@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_version_and_error_strings():
-    assert rl.version() == "0.1"
+    assert rl.version() == "0.2"
     for code in range(0, -7, -1):
         assert "unknown" not in rl.strerror(code)
     assert "unknown" in rl.strerror(-99)
@@ -62,7 +62,7 @@ def test_argument_errors_are_returned_before_any_device_work():
     assert L.blstm_stack_fwd_bwd(ctypes.byref(s), None, None, None, None, None, None, None, None, None, None, None) == -1
     assert L.blstm_stack_fwd_bwd(ctypes.byref(rl.rblstm_desc(L=1, T=4, B=0, D=3, H=4)),
                                  None, None, None, None, None, None, None, None, None, None, None) == -2
-    assert L.rlstm_gemm_f32(0, 0, 4, 4, 4, None, 4, None, 4, None, 4, None, None, 0, None) == -1
+    assert L.rlstm_gemm_f32(0, 0, 4, 4, 4, None, 4, None, 4, None, 4, None, 0, None, 0, None) == -1
     assert L.rlstm_last_timeout(None) == -1
 
 

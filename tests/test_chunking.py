@@ -58,12 +58,14 @@ def test_library_segment_table_equals_the_oracle(size, step):
 
 
 def test_paper_shaped_workload_is_a_batch_of_81_segments():
-    wl = synth.paper_chunks()
+    """The oracle cuts the corpus; the shared generator only draws the network for the batch it is handed."""
+    corpus_x, corpus_lens = synth.paper_corpus()
+    xc, (seq, start, length) = chunk_batch(corpus_x, corpus_lens, synth.PAPER_SEGMENT_FRAMES, synth.PAPER_SEGMENT_FRAMES)
+    assert len(seq) >= synth.PAPER_BATCH_SEGMENTS
+    wl = synth.paper_workload(xc[:, :81], length[:81])
     assert (wl.T, wl.B, wl.D, wl.L, wl.H) == (250, 81, 45, 3, 512)
     assert wl.seq_lens.max() == 250 and wl.seq_lens.min() >= 1
-    corpus_x, corpus_lens = synth.paper_corpus()
-    xc, (seq, start, length) = chunk_batch(corpus_x, corpus_lens, 250, 250)
-    assert np.array_equal(wl.x, xc[:, :81]) and np.array_equal(wl.seq_lens, length[:81])
+    assert np.array_equal(wl.x, xc[:, :81]) and not wl.G[wl.seq_lens[5]:, 5].any()
 
 
 @pytest.mark.gpu
@@ -104,17 +106,11 @@ def test_paper_shaped_batch_against_oracle_samples():
     sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
     import gpu_harness as gh
     g = np.load(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_chunks_oracle_samples.npz"))
-    wl = synth.paper_chunks()
+    # the batch is built by the library from the corpus (segment table + device gather)
+    wl = gh.paper_batch_from_corpus()
     assert np.array_equal(g["seq_lens"], wl.seq_lens)
-    # the same batch, built by the library from the corpus
-    cx, clens = synth.paper_corpus()
-    seq, start, length = rl.rlstm_chunk_plan(clens, 250, 250)
-    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
-    xc = torch.empty((250, 81, 45), device="cuda:0")
-    rl.rlstm_chunk_gather(dev(cx), dev(seq[:81]), dev(start[:81]), dev(length[:81]), 250, xc)
-    torch.cuda.synchronize()
-    assert np.array_equal(xc.cpu().numpy(), wl.x) and np.array_equal(length[:81], wl.seq_lens)
-    wl.x = xc.cpu().numpy()
+    ref_x, (_, _, ref_len) = chunk_batch(*synth.paper_corpus(), synth.PAPER_SEGMENT_FRAMES, synth.PAPER_SEGMENT_FRAMES)
+    assert np.array_equal(wl.x, ref_x[:, :wl.B]) and np.array_equal(wl.seq_lens, ref_len[:wl.B])   # the oracle's cut, bit for bit
     run = gh.StackRun(wl, engine=rl.RLSTM_ENGINE_PERSISTENT, want_dx=True, two_streams=True)
     run.step()
     got = run.results()
@@ -131,3 +127,4 @@ def test_paper_shaped_batch_against_oracle_samples():
             for nm in ("dW", "dR", "db"):
                 check(f"{nm}_{l}_{d}", got["grads"][k], 1e-4)
                 k += 1
+    gh.check_structured_samples(g, "", run.y_top, run.dx, run.grads, wl.seq_lens, wl.L, 1e-5, 1e-4, "paper batch")

@@ -278,7 +278,7 @@ def test_paper_train_step_full_size_against_oracle_samples():
     (tests/golden/make_paper_train_golden.py)."""
     import os
     g = np.load(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_train_oracle_samples.npz"))
-    wl = synth.paper_chunks()
+    wl = gh.paper_batch_from_corpus()      # cut from the corpus by the library
     assert np.array_equal(g["seq_lens"], wl.seq_lens)
     C, lr = 1501, 1e-3
     T, B, F = wl.T, wl.B, 2 * wl.H

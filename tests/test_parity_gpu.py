@@ -132,27 +132,25 @@ def test_stack_one_stream_and_no_dx_match_two_streams():
     assert np.array_equal(c.results()["y"], rb["y"])
 
 
-@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("mode", [1, 2])
 def test_overlap_modes_against_oracle(mode):
-    """Products one after the other on one stream (0) or beside the recurrent kernels with the passes cut into
-    pieces (1): the same results, up to the order of sums."""
+    """Products one after the other on one stream (overlap_mode 1) or beside the recurrent kernels with the passes cut
+    into pieces (2): the same results, up to the order of sums."""
     wl = synth.make_workload("overlap", L=3, B=20, D=16, H=72, len_lo=10, len_hi=300, wscale=0.1, seed=41)
     ref = gh.oracle_stack(wl)
-    rl.rlstm_set_overlap_mode(mode)
-    rl.rlstm_set_first_piece(64)
-    try:
-        run = gh.StackRun(wl, engine=rl.RLSTM_ENGINE_PERSISTENT, two_streams=True)
-        run.step()
-        got = run.results()
-    finally:
-        rl.rlstm_set_overlap_mode(-1)
-        rl.rlstm_set_first_piece(128)
+    run = gh.StackRun(wl, engine=rl.RLSTM_ENGINE_PERSISTENT, two_streams=True, overlap_mode=mode, first_piece=64)
+    run.step()
+    got = run.results()
     assert gh.rel_err(got["y"], ref["y"]) < TOL_FWD
     assert gh.rel_err(got["dx"], ref["dx"]) < TOL_GRAD
     for g1, g2 in zip(got["grads"], ref["grads"]):
         assert gh.rel_err(g1, g2) < TOL_GRAD
-    L = rl.lib()
-    assert L.rlstm_set_overlap_mode(2) == -2 and L.rlstm_set_overlap_mode(-2) == -2
+    # tuning values outside their ranges are refused before anything is enqueued
+    for bad in (dict(overlap_mode=3), dict(overlap_mode=-1), dict(first_piece=-2), dict(batch_groups=9), dict(bwd_exchange=3),
+                dict(gemm_variant=-1)):
+        d = rl.rblstm_desc(L=wl.L, T=wl.T, B=wl.B, D=wl.D, H=wl.H, operand_dtype=0, engine=0, **bad)
+        assert rl.rblstm_workspace_bytes(d) == 0, bad
+        assert rl.blstm_stack_fwd(d, run.x, run.params, run.seq_lens, run.y_top, run.reserve, run.ws, None, check=False) == -3, bad
 
 
 def test_config2_blstm():
@@ -213,12 +211,8 @@ def test_gemm_against_numpy(case, variant):
     Ad, Bd, biasd = gh.dev(A), gh.dev(Bm), gh.dev(bias)
     C = torch.full((M, N), float("nan"), device=gh.DEV)
     ws = torch.empty(16 * M * N * 4, dtype=torch.uint8, device=gh.DEV)
-    rl.rlstm_set_gemm_variant(variant)
-    try:
-        rl.rlstm_gemm_f32(ta, tb, M, N, K, Ad, A.shape[1], Bd, Bm.shape[1], C, N, biasd, ws)
-        torch.cuda.synchronize()
-    finally:
-        rl.rlstm_set_gemm_variant(0)
+    rl.rlstm_gemm_f32(ta, tb, M, N, K, Ad, A.shape[1], Bd, Bm.shape[1], C, N, biasd, ws, variant=variant)
+    torch.cuda.synchronize()
     assert gh.rel_err(C.cpu().numpy(), ref) < 1e-5, (case, variant)
 
 
@@ -281,6 +275,9 @@ def test_config3_full_size_against_oracle_samples():
             for nm in ("dW", "dR", "db"):
                 check(f"{nm}_{l}_{d}", got["grads"][k], TOL_GRAD)
                 k += 1
+    # whole frames on either side of the places the passes are cut, both ends of the time axis, every sequence's last
+    # valid and first padded frame, units 496..499 next to the padding of H, every bias gradient whole
+    gh.check_structured_samples(g, "", run.y_top, run.dx, run.grads, wl.seq_lens, wl.L, TOL_FWD, TOL_GRAD, "config3")
     for n, ln in enumerate(wl.seq_lens):
         assert np.all(got["y"][ln:, n] == 0.0) and np.all(got["dx"][ln:, n] == 0.0)
     assert all(np.isfinite(a).all() for a in got["grads"])
@@ -457,37 +454,31 @@ def test_bounded_waits_turn_a_silent_workgroup_into_an_error_flag():
     assert gh.rel_err(got["y"], ref["y"]) < TOL_FWD
 
 
-@pytest.mark.parametrize("first", [0, 3, 7, 64])
-def test_stack_results_do_not_depend_on_how_the_passes_are_cut(first):
-    """Two streams + persistent engine: the recurrent passes are cut into pieces (first, first, 2*first, ...)
-    that the feeding matrix products run ahead of.  Every cut must give the oracle's results, and the
+@pytest.mark.parametrize("bwd_exchange", [1, 2])
+@pytest.mark.parametrize("first", [-1, 3, 7, 64])
+def test_stack_results_do_not_depend_on_how_the_passes_are_cut(first, bwd_exchange):
+    """Two streams + persistent engine: the recurrent passes are cut into pieces (first, first, 2*first, ...; -1: not
+    cut) that the feeding matrix products run ahead of.  Every cut must give the oracle's results, and the
     same bits as the uncut passes except for the order of the bias gradient's sums.  (The bits are compared with
     one product kernel for every piece: by default the first piece's product, which runs while the chain waits
-    for it, uses the pipelined kernel and the others the plain one, and the two add in different orders.)"""
+    for it, uses the pipelined kernel and the others the plain one, and the two add in different orders.)  With
+    one and with two exchanges per step in the backward kernel."""
     wl = synth.small_blstm(seed=21, L=3, B=9, D=11, H=36, len_lo=0, len_hi=61, T=61)
     ref = gh.oracle_stack(wl)
-    try:
-        rl.rlstm_set_first_piece(first)
-        dflt = gh.StackRun(wl, engine=rl.RLSTM_ENGINE_PERSISTENT)
-        dflt.step()
-        rd = dflt.results()
-        assert gh.rel_err(rd["y"], ref["y"]) < TOL_FWD and gh.rel_err(rd["dx"], ref["dx"]) < TOL_GRAD
-        for i, (g, r) in enumerate(zip(rd["grads"], ref["grads"])):
-            assert gh.rel_err(g, r) < TOL_GRAD, (i, gh.rel_err(g, r))
-        rl.rlstm_set_gemm_variant(2)
-        rl.rlstm_set_first_piece(0)
-        base = gh.StackRun(wl, engine=rl.RLSTM_ENGINE_PERSISTENT)
-        base.step()
-        rb = base.results()
-        rl.rlstm_set_first_piece(first)
-        run = gh.StackRun(wl, engine=rl.RLSTM_ENGINE_PERSISTENT)
-        run.step()
-        got = run.results()
-        run.step()                      # a second step reuses the scratch the first one left behind
-        again = run.results()
-    finally:
-        rl.rlstm_set_first_piece(128)
-        rl.rlstm_set_gemm_variant(0)
+    dflt = gh.StackRun(wl, engine=rl.RLSTM_ENGINE_PERSISTENT, first_piece=first, overlap_mode=2, bwd_exchange=bwd_exchange)
+    dflt.step()
+    rd = dflt.results()
+    assert gh.rel_err(rd["y"], ref["y"]) < TOL_FWD and gh.rel_err(rd["dx"], ref["dx"]) < TOL_GRAD
+    for i, (g, r) in enumerate(zip(rd["grads"], ref["grads"])):
+        assert gh.rel_err(g, r) < TOL_GRAD, (i, gh.rel_err(g, r))
+    base = gh.StackRun(wl, engine=rl.RLSTM_ENGINE_PERSISTENT, first_piece=-1, overlap_mode=2, gemm_variant=2, bwd_exchange=bwd_exchange)
+    base.step()
+    rb = base.results()
+    run = gh.StackRun(wl, engine=rl.RLSTM_ENGINE_PERSISTENT, first_piece=first, overlap_mode=2, gemm_variant=2, bwd_exchange=bwd_exchange)
+    run.step()
+    got = run.results()
+    run.step()                      # a second step reuses the scratch the first one left behind
+    again = run.results()
     assert gh.rel_err(got["y"], ref["y"]) < TOL_FWD
     assert gh.rel_err(got["dx"], ref["dx"]) < TOL_GRAD
     for i, (g, r) in enumerate(zip(got["grads"], ref["grads"])):
@@ -508,26 +499,60 @@ def test_stack_results_do_not_depend_on_how_the_passes_are_cut(first):
     dict(B=24, D=10, H=72, len_lo=0, len_hi=45, T=45),      # groups of 24 / 12 / 6 sequences
     dict(B=9, D=7, H=130, len_lo=3, len_hi=33),             # 4 groups: 3, 3, 3, 0 sequences
 ])
-def test_stack_results_do_not_depend_on_the_groups_of_sequences(groups, shape):
-    """The persistent engine deals the sequences out to groups of workgroups that run independently."""
+@pytest.mark.parametrize("bwd_exchange", [1, 2])
+def test_stack_results_do_not_depend_on_the_groups_of_sequences(groups, shape, bwd_exchange):
+    """The persistent engine deals the sequences out to groups of workgroups that run independently; the backward
+    kernel with two exchanges per step and (where the groups hold at most 16 sequences) with one."""
     wl = synth.small_blstm(seed=23, L=2, **shape)
     ref = gh.oracle_stack(wl)
-    try:
-        rl.rlstm_set_batch_groups(groups)
-        run = gh.StackRun(wl, engine=rl.RLSTM_ENGINE_PERSISTENT)
-        run.step()
-        got = run.results()
-    finally:
-        rl.rlstm_set_batch_groups(0)
+    run = gh.StackRun(wl, engine=rl.RLSTM_ENGINE_PERSISTENT, batch_groups=groups, bwd_exchange=bwd_exchange)
+    run.step()
+    got = run.results()
+    plan = rl.rblstm_plan(run.desc)
+    assert plan["bwd_exchanges_per_step"] == (1 if bwd_exchange == 2 and plan["sequences_per_group"] <= 16 else 2)
     assert gh.rel_err(got["y"], ref["y"]) < TOL_FWD
     assert gh.rel_err(got["dx"], ref["dx"]) < TOL_GRAD
     for i, (g, r) in enumerate(zip(got["grads"], ref["grads"])):
         assert gh.rel_err(g, r) < TOL_GRAD, (i, gh.rel_err(g, r))
 
 
+@pytest.mark.parametrize("direction", [1, -1])
+@pytest.mark.parametrize("shape", [
+    # T, B, D, H: unit counts that take every slice width (4, 8, 16 units per workgroup) and padded product width
+    (13, 5, 12, 20), (9, 16, 7, 130), (11, 7, 16, 256), (7, 12, 5, 300), (6, 3, 5, 500), (5, 10, 8, 600), (4, 2, 3, 1024),
+])
+def test_single_layer_backward_with_one_exchange_per_step(direction, shape):
+    """bwd_exchange = 2 (applies up to H = 512): every workgroup multiplies its own columns of d a_t with its rows of R^T and hands pieces of
+    the result to the owners of the units, one exchange between workgroups per step instead of two; ragged lengths with
+    an empty sequence, initial and final states and their gradients."""
+    T, B, D, H = shape
+    rng = _rng(2500 + T + B + H + (direction > 0))
+    x = rng.standard_normal((T, B, D)).astype(np.float32)
+    s = 0.3 if H < 200 else 0.08
+    W = rng.uniform(-s, s, (D, 4 * H)).astype(np.float32)
+    R = rng.uniform(-s, s, (H, 4 * H)).astype(np.float32)
+    b = rng.uniform(-0.3, 0.3, (4 * H,)).astype(np.float32)
+    h0 = rng.uniform(-0.5, 0.5, (B, H)).astype(np.float32)
+    c0 = rng.uniform(-0.5, 0.5, (B, H)).astype(np.float32)
+    lens = rng.integers(0, T + 1, B).astype(np.int32)
+    lens[0], lens[-1] = T, 0
+    dy = rng.standard_normal((T, B, H)).astype(np.float32)
+    dhT = rng.standard_normal((B, H)).astype(np.float32)
+    dcT = rng.standard_normal((B, H)).astype(np.float32)
+    fwd = lstm_forward(x, W, R, b, lens, direction, h0, c0)
+    grad = lstm_backward(fwd, dy, dhT, dcT)
+    got = gh.run_lstm_layer(x, W, R, b, lens, direction, h0, c0, dy, dhT, dcT, engine=rl.RLSTM_ENGINE_PERSISTENT, bwd_exchange=2)
+    _check_layer(got, fwd, grad, lens, f"one exchange per step, shape={shape} dir={direction}")
+    two = gh.run_lstm_layer(x, W, R, b, lens, direction, h0, c0, dy, dhT, dcT, engine=rl.RLSTM_ENGINE_PERSISTENT, bwd_exchange=1)
+    assert np.array_equal(got["y"], two["y"])                       # the same forward kernel
+    # H <= 512 runs the other kernel (another order of sums); above that the request falls back to two exchanges
+    assert gh.rel_err(got["dW"], two["dW"]) < 1e-5 and np.array_equal(got["dR"], two["dR"]) == (H > 512)
+
+
 @pytest.mark.parametrize("groups", [2, 8])
 @pytest.mark.parametrize("direction", [1, -1])
-def test_single_layer_initial_and_final_state_with_groups_of_sequences(groups, direction):
+@pytest.mark.parametrize("bwd_exchange", [1, 2])
+def test_single_layer_initial_and_final_state_with_groups_of_sequences(groups, direction, bwd_exchange):
     T, B, D, H = 28, 19, 6, 44
     rng = _rng(2400 + groups + (direction > 0))
     x = rng.standard_normal((T, B, D)).astype(np.float32)
@@ -542,12 +567,9 @@ def test_single_layer_initial_and_final_state_with_groups_of_sequences(groups, d
     dcT = rng.standard_normal((B, H)).astype(np.float32)
     fwd = lstm_forward(x, W, R, b, lens, direction, h0, c0)
     grad = lstm_backward(fwd, dy, dhT, dcT)
-    try:
-        rl.rlstm_set_batch_groups(groups)
-        got = gh.run_lstm_layer(x, W, R, b, lens, direction, h0, c0, dy, dhT, dcT, engine=rl.RLSTM_ENGINE_PERSISTENT)
-    finally:
-        rl.rlstm_set_batch_groups(0)
-    _check_layer(got, fwd, grad, lens, f"groups={groups} dir={direction}")
+    got = gh.run_lstm_layer(x, W, R, b, lens, direction, h0, c0, dy, dhT, dcT, engine=rl.RLSTM_ENGINE_PERSISTENT,
+                            batch_groups=groups, bwd_exchange=bwd_exchange)
+    _check_layer(got, fwd, grad, lens, f"groups={groups} dir={direction} bwd_exchange={bwd_exchange}")
 
 
 def test_plan_query_and_exchange_floor_probe():
