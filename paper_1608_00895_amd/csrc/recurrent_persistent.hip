@@ -664,35 +664,43 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
   const int prod_first = (qq * Hq + wave * UW) / U, prod_count = UW / U;
   const unsigned* myflags = gflags + (wg % kFlagCopies) * kFlagCopyStride;
 
-  // sums the partial tiles of step `step` for the owned pairs (tag = step + 1)
+  // sums the partial tiles of step `step` for the owned pairs (tag = step + 1).  The words of all owned pairs are
+  // requested together and checked together: one round trip through the memory side per poll, however many pairs a
+  // thread owns.
   auto collect = [&](int step, float (&out)[EPT]) -> int {
     int fail = 0;
     const unsigned long long* pbuf = gpart + (size_t)(step & 1) * psz;
+    const unsigned long long* src[EPT];
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
-      out[e] = 0.f;
-      if (!ev[e]) continue;
       const int n = qq * U + (eu[e] - u0);
-      const unsigned long long* src = pbuf + ((size_t)(pg * 4) * Bp + eb[e]) * UG + n;
-      unsigned long long v[4];
-      Spin sp(p.wait_ticks);
-      for (;;) {
-        bool ok = true;
+      src[e] = pbuf + ((size_t)(pg * 4) * Bp + (ev[e] ? eb[e] : 0)) * UG + (ev[e] ? n : 0);
+    }
+    unsigned long long v[EPT][4];
+    Spin sp(p.wait_ticks);
+    for (;;) {
+#pragma unroll
+      for (int e = 0; e < EPT; ++e)
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-          v[k] = 0ull;
-          if (k < nq) {
-            v[k] = __hip_atomic_load(src + (size_t)k * Bp * UG, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            ok = ok && (unsigned)(v[k] >> 32) == (unsigned)(step + 1);
-          }
+          v[e][k] = 0ull;
+          if (ev[e] && k < nq) v[e][k] = __hip_atomic_load(src[e] + (size_t)k * Bp * UG, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        if (ok) break;
-        if (sp.expired(p.err)) { fail = 1; break; }
-      }
+      bool ok = true;
+#pragma unroll
+      for (int e = 0; e < EPT; ++e)
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+          if (ev[e] && k < nq) ok = ok && (unsigned)(v[e][k] >> 32) == (unsigned)(step + 1);
+      if (ok) break;
+      if (sp.expired(p.err)) { fail = 1; break; }
+    }
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
       float sum = 0.f;
 #pragma unroll
-      for (int k = 0; k < 4; ++k) sum += __uint_as_float((unsigned)v[k]);
-      out[e] = sum;
+      for (int k = 0; k < 4; ++k) sum += __uint_as_float((unsigned)v[e][k]);
+      out[e] = ev[e] ? sum : 0.f;
     }
     return fail;
   };
