@@ -263,6 +263,28 @@ RLSTM_API int rlstm_gemm_bf16(int trans_a, int trans_b, int M, int N, int K,
                     const float* bias, int variant, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream);
 
 /*
+ * The bf16-operand products of the stack entry points read their operands from bf16 COPIES (half the bytes, no
+ * rounding inside the product), each stored so that the product walks along its rows: x, every layer's output and
+ * d a both as stored and transposed, W as stored and transposed.  The copies live in the stack's workspace when
+ * operand_dtype is 1.  The three calls below expose that path for measurement and testing.
+ *   rlstm_to_bf16: dst[i] = bf16(src[i]), round to nearest even; n a multiple of 8, both arrays 16-byte aligned
+ *   (RLSTM_EDIM otherwise).
+ *   rlstm_to_bf16_2d: src [R, C] fp32 with row stride ld -> dst [R, C] bf16 (may be null) and dst_t [C, R] bf16, its
+ *   transpose (may be null), both dense; R, C multiples of 8, ld a multiple of 4, all arrays 16-byte aligned
+ *   (RLSTM_EDIM otherwise).
+ *   rlstm_gemm_bf16_mem: C[M,N] = op(A16) op(B16) (+ bias), fp32 accumulation, operands bf16 in memory with the
+ *   trans_a / trans_b / lda / ldb meaning of rlstm_gemm_f32 (strides in bf16 elements).  The result has the bits of
+ *   rlstm_gemm_bf16 on fp32 operands that round to these bf16 values.  RLSTM_EMODE when the shape does not take the
+ *   kernel that reads bf16 from memory (it needs 256 x 256 tiles to fill the chip, whole 16-byte aligned groups of 8
+ *   values along the operands' contiguous dimensions and K a multiple of 8).
+ */
+RLSTM_API int rlstm_to_bf16(uint16_t* dst, const float* src, size_t n, void* hip_stream);
+RLSTM_API int rlstm_to_bf16_2d(uint16_t* dst, uint16_t* dst_t, const float* src, int R, int C, int ld, void* hip_stream);
+RLSTM_API int rlstm_gemm_bf16_mem(int trans_a, int trans_b, int M, int N, int K,
+                        const uint16_t* A16, int lda, const uint16_t* B16, int ldb,
+                        float* C, int ldc, const float* bias, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream);
+
+/*
  * Optional per-kernel timing for measurement (not part of the method).  While
  * enabled, every kernel group the library enqueues is bracketed by a pair of
  * HIP events on the stream it is launched on.  rlstm_profile_read() waits for

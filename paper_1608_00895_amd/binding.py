@@ -27,7 +27,7 @@ EXPORTS = [
     "blstm_stack_fwd_bwd", "blstm_stack_fwd", "blstm_stack_bwd",
     "rlstm_ce_workspace_bytes", "softmax_ce_fwd_bwd", "rlstm_sgd_momentum_step", "rlstm_adam_step",
     "rlstm_stream_reserve_bytes", "rlstm_stream_workspace_bytes", "lstm_stream_fwd_bwd",
-    "rlstm_gemm_f32", "rlstm_gemm_bf16", "rlstm_copy_f32", "rlstm_profile_enable", "rlstm_profile_read", "rlstm_last_timeout", "rlstm_test_hook", "rmdlstm_reserve_bytes", "rmdlstm_workspace_bytes", "mdlstm_fwd", "mdlstm_bwd", "rlstm_chunk_plan", "rlstm_chunk_gather", "rblstm_plan", "rlstm_exchange_floor_bytes", "rlstm_exchange_floor", "rlstm_resolve_engine", "rlstm_strerror", "rlstm_version",
+    "rlstm_gemm_f32", "rlstm_gemm_bf16", "rlstm_to_bf16", "rlstm_to_bf16_2d", "rlstm_gemm_bf16_mem", "rlstm_copy_f32", "rlstm_profile_enable", "rlstm_profile_read", "rlstm_last_timeout", "rlstm_test_hook", "rmdlstm_reserve_bytes", "rmdlstm_workspace_bytes", "mdlstm_fwd", "mdlstm_bwd", "rlstm_chunk_plan", "rlstm_chunk_gather", "rblstm_plan", "rlstm_exchange_floor_bytes", "rlstm_exchange_floor", "rlstm_resolve_engine", "rlstm_strerror", "rlstm_version",
 ]
 
 
@@ -124,6 +124,12 @@ def lib() -> ctypes.CDLL:
         L.rlstm_gemm_f32.argtypes = [ip, ip, ip, ip, ip, vp, ip, vp, ip, vp, ip, vp, ip, vp, ctypes.c_size_t, vp]
         L.rlstm_gemm_bf16.restype = ip
         L.rlstm_gemm_bf16.argtypes = L.rlstm_gemm_f32.argtypes
+        L.rlstm_to_bf16.restype = ip
+        L.rlstm_to_bf16.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        L.rlstm_gemm_bf16_mem.restype = ip
+        L.rlstm_gemm_bf16_mem.argtypes = [ip, ip, ip, ip, ip, vp, ip, vp, ip, vp, ip, vp, vp, ctypes.c_size_t, vp]
+        L.rlstm_to_bf16_2d.restype = ip
+        L.rlstm_to_bf16_2d.argtypes = [vp, vp, vp, ip, ip, ip, vp]
         L.rlstm_copy_f32.restype = ip
         L.rlstm_copy_f32.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.rlstm_profile_enable.restype = ip
@@ -378,6 +384,31 @@ def rlstm_gemm_bf16(trans_a, trans_b, M, N, K, A, lda, B, ldb, C, ldc, bias=None
                                _ptr(bias), int(variant), _ptr(splitk_ws), nbytes, _stream(stream))
     if check and rc != 0:
         raise RlstmError(rc, "rlstm_gemm_bf16")
+    return rc
+
+
+def rlstm_to_bf16(dst, src, stream=None, check=True) -> int:
+    """dst: int16 / uint16 tensor of src.numel() elements."""
+    rc = lib().rlstm_to_bf16(_ptr(dst), _ptr(src), src.numel(), _stream(stream))
+    if check and rc != 0:
+        raise RlstmError(rc, "rlstm_to_bf16")
+    return rc
+
+
+def rlstm_to_bf16_2d(dst, dst_t, src, R, C, ld, stream=None, check=True) -> int:
+    rc = lib().rlstm_to_bf16_2d(_ptr(dst), _ptr(dst_t), _ptr(src), R, C, ld, _stream(stream))
+    if check and rc != 0:
+        raise RlstmError(rc, "rlstm_to_bf16_2d")
+    return rc
+
+
+def rlstm_gemm_bf16_mem(trans_a, trans_b, M, N, K, A16, lda, B16, ldb, C, ldc, bias=None, splitk_ws=None,
+                        stream=None, check=True) -> int:
+    nbytes = 0 if splitk_ws is None else splitk_ws.numel() * splitk_ws.element_size()
+    rc = lib().rlstm_gemm_bf16_mem(int(trans_a), int(trans_b), M, N, K, _ptr(A16), lda, _ptr(B16), ldb,
+                                   _ptr(C), ldc, _ptr(bias), _ptr(splitk_ws), nbytes, _stream(stream))
+    if check and rc != 0:
+        raise RlstmError(rc, "rlstm_gemm_bf16_mem")
     return rc
 
 

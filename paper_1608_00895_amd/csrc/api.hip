@@ -112,7 +112,10 @@ int hip_to_code(hipError_t e, int resident_err) {
 int weight_grads(hipStream_t st, int layer, int T, int B, int Din, int H, int direction,
                  const float* x, int ldx, const float* y, int ldy, const float* dz,
                  float* dW, float* dR, float* skws, size_t skfloats, bool naive, int operand_dtype,
-                 bool small_footprint, int variant, bool accumulate = false) {
+                 bool small_footprint, int variant, bool accumulate = false,
+                 const unsigned short* xt16 = nullptr, const unsigned short* yt16 = nullptr, const unsigned short* dzt16 = nullptr) {
+  // xt16 [Din, T*B], yt16 [H, T*B] (this direction's rows), dzt16 [4H, T*B]: TRANSPOSED bf16 copies of x, y, dz (frames
+  // contiguous, so that both operands of these products over the frames are read along their rows), or null
   int resident_err = 0;
   GemmCall g;
   g.transA = true; g.transB = false;
@@ -120,6 +123,7 @@ int weight_grads(hipStream_t st, int layer, int T, int B, int Din, int H, int di
   g.A = x; g.lda = ldx; g.B = dz; g.ldb = 4 * H; g.C = dW; g.ldc = 4 * H;
   g.splitk_ws = skws; g.splitk_floats = skfloats; g.naive = naive; g.operand_dtype = operand_dtype;
   g.small_footprint = small_footprint; g.accumulate = accumulate; g.variant = variant;
+  if (xt16 && dzt16) { g.A16 = xt16; g.lda16 = T * B; g.transA16 = false; g.B16 = dzt16; g.ldb16 = T * B; g.transB16 = true; }
   {
     ProfScope ps(st, 4, layer, 1, 0, gemm_flop(g));
     RLSTM_TRY(gemm(st, g));
@@ -127,8 +131,15 @@ int weight_grads(hipStream_t st, int layer, int T, int B, int Din, int H, int di
   GemmCall r = g;
   r.M = H; r.K = (T - 1) * B;
   r.lda = ldy; r.C = dR;
+  r.A16 = nullptr; r.B16 = nullptr;
   if (direction > 0) { r.A = y; r.B = dz + (size_t)B * 4 * H; }
   else               { r.A = y + (size_t)B * ldy; r.B = dz; }
+  if (yt16 && dzt16) {
+    // a shift by one frame is a shift by B columns of the transposed copies
+    r.lda16 = r.ldb16 = T * B; r.transA16 = false; r.transB16 = true;
+    if (direction > 0) { r.A16 = yt16; r.B16 = dzt16 + B; }
+    else               { r.A16 = yt16 + B; r.B16 = dzt16; }
+  }
   {
     ProfScope ps(st, 5, layer, 1, 0, gemm_flop(r));
     RLSTM_TRY(gemm(st, r));
@@ -151,11 +162,57 @@ StackLayout stack_layout(const rblstm_desc* d) {
   return s;
 }
 
+// bf16 copies of the operands of the stack's matrix products (operand_dtype 1), each in the layout in which the
+// product that reads it walks along its rows (the k index contiguous: the product kernel then takes whole 16-byte
+// groups of 8 values from memory straight into LDS):
+//   xn [T*B, D], yn [T*B, 2H] per layer                  as stored          projection (A)
+//   xt [D, T*B], yt [2H, T*B] per layer, dzt [4H, T*B]   transposed         weight gradients (both operands)
+//   wt [4H, din] per direction                          transposed         projection (B)
+//   dzn [T*B, 8H] = [d a forward | d a backward], wn [din, 8H] = [W forward | W backward]     input gradient
+// The last two hold both directions side by side: the gradient w.r.t. the layer's input, the sum of the two
+// directions' products over 4H, is then ONE product over 8H (the sum happens in the accumulators; the output is
+// written once instead of written, read and written again).
+// One conversion kernel writes both copies of an array from one read of it.  They live behind everything else in the
+// workspace; offsets in bf16 elements.
+struct MirrorLayout { size_t xn, xt, yn, yt, ystride, wn, wt[2], dzn, dzt[2], total; };
+bool stack_mirrors(const rblstm_desc* d) {
+  // whole 16-byte groups of 8 values along every contiguous dimension, also after a shift by one frame; and enough
+  // frames and units that the products take the kernel that reads the copies (256 x 256 tiles over the whole chip)
+  return d->operand_dtype == 1 && d->D % 8 == 0 && d->H % 4 == 0 && d->B % 8 == 0 && (long long)d->T * d->B >= 16384 && d->H >= 256;
+}
+MirrorLayout mirror_layout(const rblstm_desc* d) {
+  MirrorLayout m{};
+  if (!stack_mirrors(d)) return m;
+  const size_t tb = (size_t)d->T * d->B;
+  const size_t dmax = d->D > 2 * d->H ? d->D : 2 * d->H;
+  size_t o = 0;
+  m.xn = o; o += align_up(tb * d->D, 64);
+  m.xt = o; o += align_up(tb * d->D, 64);
+  m.ystride = align_up(tb * 2 * d->H, 64);
+  m.yn = o; o += (size_t)d->L * m.ystride;
+  m.yt = o; o += (size_t)d->L * m.ystride;
+  m.wn = o; o += align_up(dmax * 8 * d->H, 64);
+  for (int k = 0; k < 2; ++k) { m.wt[k] = o; o += align_up(dmax * 4 * d->H, 64); }
+  m.dzn = o; o += align_up(tb * 8 * d->H, 64);
+  for (int k = 0; k < 2; ++k) { m.dzt[k] = o; o += align_up(tb * 4 * d->H, 64); }
+  m.total = o;
+  return m;
+}
+size_t stack_mirror_offset(const rblstm_desc* d);
+
 RecShape stack_rec_shape(const rblstm_desc* d) {
   RecShape s;
   s.T = d->T; s.B = d->B; s.H = d->H; s.ldy = 2 * d->H; s.ndir = 2; s.operand_dtype = d->operand_dtype;
   s.batch_groups = d->batch_groups; s.bwd_exchange = d->bwd_exchange;
   return s;
+}
+
+// bytes of the workspace in front of the bf16 copies: [flag][recurrent scratch][split-K partials][two dy buffers]
+size_t stack_mirror_offset(const rblstm_desc* d) {
+  const RecShape s = stack_rec_shape(d);
+  const int mm = d->D > 2 * d->H ? d->D : 2 * d->H;
+  const size_t dy = align_up((size_t)d->T * d->B * 2 * d->H, 64);
+  return align_up(kFlagBytes + align_up(rec_workspace_bytes(s), 256) + (splitk_floats(mm, d->H) + 2 * dy) * sizeof(float), 256);
 }
 
 // Pipelining of a layer's recurrent pass with the matrix product that feeds it.  The pass over the
@@ -239,11 +296,20 @@ int stack_forward(const rblstm_desc* d, const float* x, const float* const* para
   const int np = (int)pb.size() - 1;
   EventList evs;
   RLSTM_TRY(clear_flag(sa, flag));
+  // bf16 copies of the products' operands: with uncut passes only (everything in order on one stream)
+  const bool mirrors = stack_mirrors(d) && persistent && !pipelined;
+  const MirrorLayout ml = mirror_layout(d);
+  unsigned short* mir = reinterpret_cast<unsigned short*>(ws + stack_mirror_offset(d));
+  const size_t tb = (size_t)T * B;
+  if (mirrors) RLSTM_TRY(to_bf16_2d(sa, x, (int)tb, d->D, d->D, mir + ml.xn, 0, mir + ml.xt));
+  const unsigned short* in16 = mir + ml.xn;
   const float* in = x;
   int din = d->D;
   for (int l = 0; l < d->L; ++l) {
     float* base = res + (size_t)l * lay.per_layer;
     float* yl = (l == d->L - 1) ? y_top : base + lay.y;
+    if (mirrors)
+      for (int k = 0; k < 2; ++k) RLSTM_TRY(to_bf16_2d(sa, params[6 * l + 3 * k + 0], din, 4 * H, 4 * H, nullptr, 0, mir + ml.wt[k]));
     RecFwdDir dirs[2];
     for (int k = 0; k < 2; ++k)
       dirs[k] = RecFwdDir{base + lay.zg[k], params[6 * l + 3 * k + 1], nullptr, nullptr, yl + (size_t)k * H,
@@ -261,12 +327,19 @@ int stack_forward(const rblstm_desc* d, const float* x, const float* const* para
         g.C = base + lay.zg[k] + f0 * B * 4 * H; g.ldc = 4 * H; g.bias = params[6 * l + 3 * k + 2];
         g.naive = !persistent; g.operand_dtype = d->operand_dtype; g.variant = d->gemm_variant;
         g.small_footprint = mode == kShare && pc > 0;   // the first piece's product runs while the chain waits for it
+        if (mirrors) { g.A16 = in16; g.lda16 = din; g.transA16 = false; g.B16 = mir + ml.wt[k]; g.ldb16 = din; g.transB16 = true; }
         ProfScope ps(sb, 0, l, 1, 0, gemm_flop(g));
         RLSTM_TRY(gemm(sb, g));
       }
       RLSTM_TRY(evs.order(sb, sa));
       ProfScope ps(sa, 1, l, 2, s1 - s0, rec_flop(rs, s1 - s0));
       RLSTM_TRY(rec_forward(sa, rs, dirs, seq_lens, recws, flag, persistent, &resident_err, s0, s1));
+    }
+    if (mirrors) {
+      // the layer's output as bf16: the next layer's projection and, in the backward pass, two weight gradients read it
+      unsigned short* yn = mir + ml.yn + (size_t)l * ml.ystride;
+      RLSTM_TRY(to_bf16_2d(sa, yl, (int)tb, 2 * H, 2 * H, l + 1 < d->L ? yn : nullptr, 0, mir + ml.yt + (size_t)l * ml.ystride));
+      in16 = yn;
     }
     in = yl;
     din = 2 * H;
@@ -321,6 +394,11 @@ int stack_backward(const rblstm_desc* d, const float* x, const float* const* par
   const int np = (int)pb.size() - 1;
   EventList evs;
   std::vector<hipEvent_t> ready;       // ready[pc]: dy of piece pc of the layer about to run is complete
+  // bf16 copies of the products' operands (see stack_forward, which left x and every layer's y)
+  const bool mirrors = stack_mirrors(d) && persistent && !pipelined;
+  const MirrorLayout ml = mirror_layout(d);
+  unsigned short* mir = reinterpret_cast<unsigned short*>(ws + stack_mirror_offset(d));
+  const size_t tb = (size_t)T * B;
 
   const float* dy = dy_top;
   for (int l = L - 1; l >= 0; --l) {
@@ -341,8 +419,19 @@ int stack_backward(const rblstm_desc* d, const float* x, const float* const* par
     }
     ready.clear();
     RLSTM_TRY(evs.order(sa, sb));
-
     float* dxl = (l == 0) ? dx : dybuf[l & 1];
+    const unsigned short* yt16 = nullptr; const unsigned short* xt16 = nullptr;
+    if (mirrors) {
+      // d a of both directions (as stored for the input gradient, transposed for the weight gradients) and W as bf16
+      for (int k = 0; k < 2; ++k) {
+        RLSTM_TRY(to_bf16_2d(sb, base + lay.zg[k], (int)tb, 4 * H, 4 * H, dxl ? mir + ml.dzn + (size_t)k * 4 * H : nullptr, 8 * H,
+                             mir + ml.dzt[k]));
+        if (dxl) RLSTM_TRY(to_bf16_2d(sb, params[6 * l + 3 * k + 0], din, 4 * H, 4 * H, mir + ml.wn + (size_t)k * 4 * H, 8 * H, nullptr));
+      }
+      yt16 = mir + ml.yt + (size_t)l * ml.ystride;
+      xt16 = l == 0 ? mir + ml.xt : mir + ml.yt + (size_t)(l - 1) * ml.ystride;
+    }
+
     if (dxl && l > 0 && sb != sa) {
       // columns [0,H) feed direction +1 of the layer below, which visits frames T-1 .. 0;
       // columns [H,2H) feed direction -1, which visits frames 0 .. T-1
@@ -371,6 +460,33 @@ int stack_backward(const rblstm_desc* d, const float* x, const float* const* par
         RLSTM_TRY(hipEventRecord(ev, sb));
         ready.push_back(ev);
       }
+    } else if (dxl && mirrors) {
+      // both directions in one product over 8H (see MirrorLayout); A and B name direction +1's fp32 arrays only for
+      // the fallback test inside gemm(), which the copies' shapes pass whenever mirrors is set
+      GemmCall g;
+      g.transB = true;
+      g.M = T * B; g.N = din; g.K = 8 * H;
+      g.C = dxl; g.ldc = din;
+      g.operand_dtype = d->operand_dtype; g.variant = d->gemm_variant;
+      g.A16 = mir + ml.dzn; g.lda16 = 8 * H; g.transA16 = false; g.B16 = mir + ml.wn; g.ldb16 = 8 * H; g.transB16 = true;
+      g.require_mem16 = true;
+      ProfScope ps(sb, 3, l, 1, 0, gemm_flop(g));
+      const hipError_t e = gemm(sb, g);
+      if (e == hipErrorInvalidValue) {
+        // too few tiles for the kernel that reads the copies (tiny T*B): the two products on the fp32 arrays
+        (void)hipGetLastError();
+        for (int k = 0; k < 2; ++k) {
+          GemmCall f;
+          f.transB = true;
+          f.M = T * B; f.N = din; f.K = 4 * H;
+          f.A = base + lay.zg[k]; f.lda = 4 * H; f.B = params[6 * l + 3 * k + 0]; f.ldb = 4 * H;
+          f.C = dxl; f.ldc = din; f.accumulate = (k == 1);
+          f.operand_dtype = d->operand_dtype; f.variant = d->gemm_variant;
+          RLSTM_TRY(gemm(sb, f));
+        }
+      } else {
+        RLSTM_TRY(e);
+      }
     } else if (dxl) {
       for (int k = 0; k < 2; ++k) {
         GemmCall g;
@@ -388,7 +504,7 @@ int stack_backward(const rblstm_desc* d, const float* x, const float* const* par
       rc = weight_grads(sb, l, T, B, din, H, k == 0 ? 1 : -1, xin, din, yl + (size_t)k * H, 2 * H,
                         base + lay.zg[k], grads[6 * l + 3 * k + 0], grads[6 * l + 3 * k + 1], skws, skfloats,
                         !persistent, d->operand_dtype, mode == kShare && l > 0,     // layer 0's run after the last recurrent piece: nothing beside them
-                        d->gemm_variant);
+                        d->gemm_variant, false, xt16, yt16 ? yt16 + (size_t)k * H * tb : nullptr, mirrors ? mir + ml.dzt[k] : nullptr);
       if (rc != RLSTM_OK) return rc;
     }
     dy = dxl;
@@ -436,10 +552,7 @@ size_t rblstm_reserve_bytes(const rblstm_desc* d) {
 
 size_t rblstm_workspace_bytes(const rblstm_desc* d) {
   if (check_stack_desc(d) != RLSTM_OK) return 0;
-  const RecShape s = stack_rec_shape(d);
-  const int mm = d->D > 2 * d->H ? d->D : 2 * d->H;
-  const size_t dy = align_up((size_t)d->T * d->B * 2 * d->H, 64);
-  return kFlagBytes + align_up(rec_workspace_bytes(s), 256) + (splitk_floats(mm, d->H) + 2 * dy) * sizeof(float);
+  return stack_mirror_offset(d) + mirror_layout(d).total * sizeof(unsigned short);
 }
 
 int rlstm_resolve_engine(const rlstm_desc* d) {
@@ -1022,6 +1135,43 @@ static int lstm_fwd_impl(const rlstm_desc* d, const float* x, const float* W, co
     ProfScope ps(st, 1, 0, 1, d->T, rec_flop(s, d->T), timed);
     RLSTM_TRY(rec_forward(st, s, &dir, seq_lens, ws + kFlagBytes, flag, persistent, &resident_err, 0, d->T));
   }
+  return RLSTM_OK;
+}
+
+int rlstm_to_bf16(uint16_t* dst, const float* src, size_t n, void* hip_stream) {
+  if (!dst || !src) return RLSTM_ENULL;
+  if (n % 8 != 0 || (reinterpret_cast<uintptr_t>(dst) & 15u) || (reinterpret_cast<uintptr_t>(src) & 15u)) return RLSTM_EDIM;
+  int resident_err = 0;
+  RLSTM_TRY(to_bf16(static_cast<hipStream_t>(hip_stream), src, dst, n));
+  return RLSTM_OK;
+}
+
+int rlstm_to_bf16_2d(uint16_t* dst, uint16_t* dst_t, const float* src, int R, int C, int ld, void* hip_stream) {
+  if (!src || (!dst && !dst_t)) return RLSTM_ENULL;
+  if (R < 0 || C < 0 || ld < C) return RLSTM_EDIM;
+  int resident_err = 0;
+  const hipError_t e = to_bf16_2d(static_cast<hipStream_t>(hip_stream), src, R, C, ld, dst, 0, dst_t);
+  if (e == hipErrorInvalidValue) { (void)hipGetLastError(); return RLSTM_EDIM; }
+  RLSTM_TRY(e);
+  return RLSTM_OK;
+}
+
+int rlstm_gemm_bf16_mem(int trans_a, int trans_b, int M, int N, int K,
+                        const uint16_t* A16, int lda, const uint16_t* B16, int ldb,
+                        float* C, int ldc, const float* bias, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream) {
+  if (!A16 || !B16 || !C) return RLSTM_ENULL;
+  if (M <= 0 || N <= 0 || K < 0) return RLSTM_EDIM;
+  if (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N) || ldc < N) return RLSTM_EDIM;
+  int resident_err = 0;
+  GemmCall g;
+  g.transA = g.transA16 = trans_a != 0; g.transB = g.transB16 = trans_b != 0;
+  g.M = M; g.N = N; g.K = K; g.C = C; g.ldc = ldc; g.bias = bias;
+  g.A16 = A16; g.lda16 = lda; g.B16 = B16; g.ldb16 = ldb; g.require_mem16 = true;
+  g.splitk_ws = static_cast<float*>(splitk_ws); g.splitk_floats = splitk_ws ? splitk_ws_bytes / sizeof(float) : 0;
+  g.operand_dtype = 1;
+  const hipError_t e = gemm(static_cast<hipStream_t>(hip_stream), g);
+  if (e == hipErrorInvalidValue) { (void)hipGetLastError(); return RLSTM_EMODE; }
+  RLSTM_TRY(e);
   return RLSTM_OK;
 }
 

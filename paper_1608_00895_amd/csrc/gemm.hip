@@ -17,6 +17,8 @@
 // writes per-slice partial tiles to scratch and sums them in slice order in a
 // second kernel, so results are bit-reproducible run to run.
 #include "rlstm_internal.h"
+
+#include <type_traits>
 #include <algorithm>
 
 namespace rlstm {
@@ -43,6 +45,9 @@ struct GemmP {
   int per_xcd;         // ceil(work / 8); the grid is 8 * per_xcd workgroups
   int kchunk;          // K range per split-K slice (multiple of BK)
   float* partial;      // split-K scratch [slices][M][N] or null
+  // bf16 copies of A and B (same shapes and row strides, in elements), for the kernel that takes its operands
+  // as bf16 from memory; null otherwise
+  const unsigned short* A16; const unsigned short* B16;
 };
 
 // Work item of a workgroup.  The dispatcher deals consecutive workgroups out to the 8 XCDs in
@@ -913,7 +918,93 @@ struct SlabFeederBf {
   }
 };
 
-template <int WM, int WN, bool TA, bool TB>
+// The same for an operand that is already bf16 in memory (a copy written once, read by several products): half the
+// bytes, no rounding in the loop.  KC: a unit is one 16-byte load of 8 consecutive k of a row and one 16-byte LDS
+// store.  !KC: a unit is rows k and k + 1 of 8 columns (two 16-byte loads); each column's pair of k is one 32-bit
+// LDS store, put together with a byte permute.  k and the contiguous dimension are multiples of 8 here.
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uintx4 buffer_load_u4(__amdgpu_buffer_rsrc_t rsrc, unsigned off) {
+  return __builtin_bit_cast(uintx4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0));
+}
+template <int ROWS, bool KC>
+struct SlabFeederB16 {
+  // !KC: a pair of rows is loaded by one op and stored by two (columns 0..3, then 4..7), so that the LDS stores
+  // spread over as many MFMA slots as those of the fp32 feeder
+  static constexpr int kUnits = ROWS / 64;
+  static constexpr int kLoads = KC ? ROWS / 64 : ROWS / 128;
+  __amdgpu_buffer_rsrc_t rsrc;
+  unsigned voff[kLoads][2];
+  unsigned step;
+  int lds_off[kLoads];
+  int kq[kLoads];
+  int klen;
+  uintx4 r[kLoads][2];
+
+  __device__ __forceinline__ void init(const unsigned short* ptr, int ld, int mn0, int MN, int kbeg, int kend) {
+    const int tid = threadIdx.x;
+    klen = kend - kbeg;
+    if (KC) {
+      const int rows = min(ROWS, MN - mn0);
+      const unsigned short* base = ptr + (size_t)mn0 * ld + kbeg;
+      rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned short*>(base), 0, (int)((size_t)rows * ld * 2 - (size_t)kbeg * 2), 0x00020000);
+      step = BKH * 2;
+#pragma unroll
+      for (int u = 0; u < kLoads; ++u) {
+        const int idx = tid + u * 256;
+        const int row = idx >> 2, q = (idx & 3) * 8;
+        voff[u][0] = (unsigned)row * (unsigned)ld * 2u + q * 2u;     // rows past the tile's last: beyond num_records
+        voff[u][1] = 0;
+        kq[u] = q;
+        lds_off[u] = row * LDK + q;
+      }
+    } else {
+      const unsigned short* base = ptr + (size_t)kbeg * ld + mn0;
+      rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned short*>(base), 0, (int)((size_t)klen * ld * 2), 0x00020000);
+      step = (unsigned)BKH * (unsigned)ld * 2u;
+#pragma unroll
+      for (int u = 0; u < kLoads; ++u) {
+        const int idx = tid + u * 256;
+        const int mn = (idx >> 4) * 8, k = (idx & 15) * 2;
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+          voff[u][h] = (mn0 + mn < MN) ? (unsigned)(k + h) * (unsigned)ld * 2u + mn * 2u : kOutOfRange;
+        kq[u] = 0;
+        lds_off[u] = mn * LDK + k;
+      }
+    }
+  }
+  __device__ __forceinline__ void load(int u, int s) {
+    if (KC) {
+      const unsigned off = (s * BKH + kq[u] < klen) ? voff[u][0] + (unsigned)s * step : kOutOfRange;
+      r[u][0] = buffer_load_u4(rsrc, off);
+    } else if ((u & 1) == 0) {
+      const int v = u >> 1;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const unsigned off = (s * BKH < klen) ? voff[v][h] + (unsigned)s * step : kOutOfRange;
+        r[v][h] = buffer_load_u4(rsrc, off);
+      }
+    }
+  }
+  __device__ __forceinline__ void store(int u, unsigned short* slab) const {
+    if (KC) {
+      *reinterpret_cast<uintx4*>(slab + lds_off[u]) = r[u][0];
+    } else {
+      const int v = u >> 1, c0 = (u & 1) * 4;
+      unsigned short* q = slab + lds_off[v];
+#pragma unroll
+      for (int c = c0; c < c0 + 4; ++c) {
+        // column c of rows k (low half) and k + 1 (high half)
+        const unsigned lo = r[v][0][c >> 1], hi = r[v][1][c >> 1];
+        const unsigned w = (c & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+        *reinterpret_cast<unsigned*>(q + c * LDK) = w;
+      }
+    }
+  }
+};
+
+// M16: both operands are read as bf16 from memory (GemmP::A16, B16) instead of fp32 rounded on the way into LDS
+template <int WM, int WN, bool TA, bool TB, bool M16>
 __global__ __launch_bounds__(256) void gemm_mfma_bf16_v2_kernel(GemmP p) {
   constexpr int TMB = 64 * WM, TNB = 64 * WN;
   constexpr bool AKC = !TA, BKC = TB;
@@ -941,11 +1032,18 @@ __global__ __launch_bounds__(256) void gemm_mfma_bf16_v2_kernel(GemmP p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  SlabFeederBf<TMB, AKC> fa;
-  SlabFeederBf<TNB, BKC> fb;
-  fa.init(p.A, p.lda, m0, p.M, kbeg, kend);
-  fb.init(p.B, p.ldb, n0, p.N, kbeg, kend);
-  constexpr int UA = SlabFeederBf<TMB, AKC>::kUnits, UB = SlabFeederBf<TNB, BKC>::kUnits;
+  using FeedA = typename std::conditional<M16, SlabFeederB16<TMB, AKC>, SlabFeederBf<TMB, AKC>>::type;
+  using FeedB = typename std::conditional<M16, SlabFeederB16<TNB, BKC>, SlabFeederBf<TNB, BKC>>::type;
+  FeedA fa;
+  FeedB fb;
+  if constexpr (M16) {
+    fa.init(p.A16, p.lda, m0, p.M, kbeg, kend);
+    fb.init(p.B16, p.ldb, n0, p.N, kbeg, kend);
+  } else {
+    fa.init(p.A, p.lda, m0, p.M, kbeg, kend);
+    fb.init(p.B, p.ldb, n0, p.N, kbeg, kend);
+  }
+  constexpr int UA = FeedA::kUnits, UB = FeedB::kUnits;
   constexpr int NOPS = 2 * (UA + UB);            // stores of slab s+1 (A then B), then loads of slab s+2 (A then B)
   constexpr int NMFMA = 2 * WM * WN;             // per slab and wavefront
   constexpr int OPM = (NOPS + NMFMA - 1) / NMFMA;
@@ -1021,15 +1119,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_bf16_v2_kernel(GemmP p) {
   }
 }
 
-template <int WM, int WN, bool TA, bool TB>
+template <int WM, int WN, bool TA, bool TB, bool M16>
 hipError_t launch_bf16_v2(hipStream_t stream, const GemmP& p, dim3 grid) {
   const size_t lds = (size_t)2 * 64 * (WM + WN) * LDK * sizeof(unsigned short);
-  const void* fn = reinterpret_cast<const void*>(gemm_mfma_bf16_v2_kernel<WM, WN, TA, TB>);
+  const void* fn = reinterpret_cast<const void*>(gemm_mfma_bf16_v2_kernel<WM, WN, TA, TB, M16>);
   if (lds > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((gemm_mfma_bf16_v2_kernel<WM, WN, TA, TB>), grid, dim3(256), lds, stream, p);
+  hipLaunchKernelGGL((gemm_mfma_bf16_v2_kernel<WM, WN, TA, TB, M16>), grid, dim3(256), lds, stream, p);
   return hipGetLastError();
 }
 
@@ -1045,9 +1143,10 @@ hipError_t launch_bf16_v(hipStream_t stream, const GemmP& p, dim3 grid) {
   return hipGetLastError();
 }
 template <bool TA, bool TB>
-hipError_t launch_bf16(hipStream_t stream, const GemmP& p, dim3 grid, bool vec, bool big, bool pipelined) {
+hipError_t launch_bf16(hipStream_t stream, const GemmP& p, dim3 grid, bool vec, bool big, bool pipelined, bool mem16) {
   // the pipelined form pays with 256 x 256 tiles only (128 x 128: 204 against 294 TFLOP/s at 1000 x 4000 x 96000)
-  if (pipelined && big) return launch_bf16_v2<4, 4, TA, TB>(stream, p, grid);
+  if (pipelined && big && mem16) return launch_bf16_v2<4, 4, TA, TB, true>(stream, p, grid);
+  if (pipelined && big) return launch_bf16_v2<4, 4, TA, TB, false>(stream, p, grid);
   if (big) return vec ? launch_bf16_v<4, 4, TA, TB, true>(stream, p, grid) : launch_bf16_v<4, 4, TA, TB, false>(stream, p, grid);
   return vec ? launch_bf16_v<2, 2, TA, TB, true>(stream, p, grid) : launch_bf16_v<2, 2, TA, TB, false>(stream, p, grid);
 }
@@ -1061,6 +1160,7 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
   p.M = g.M; p.N = g.N; p.K = g.K;
   p.A = g.A; p.lda = g.lda; p.B = g.B; p.ldb = g.ldb; p.C = g.C; p.ldc = g.ldc;
   p.bias = g.bias; p.accumulate = g.accumulate ? 1 : 0;
+  p.A16 = g.A16; p.B16 = g.B16;
   const bool bf16 = g.operand_dtype == 1;
   // bf16 operands: 256 x 256 tiles once those alone give every CU work
   // (or, where K is split into slices that multiply the work items, half as many such tiles)
@@ -1137,10 +1237,21 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
   hipError_t e;
   const bool pipelined = vec && pipelined_ok && (g.variant == 1 || (g.variant == 0 && !g.small_footprint));
   if (bf16) {
-    if (!g.transA && !g.transB)      e = launch_bf16<false, false>(stream, p, grid, vec, big, pipelined);
-    else if (!g.transA && g.transB)  e = launch_bf16<false, true>(stream, p, grid, vec, big, pipelined);
-    else if (g.transA && !g.transB)  e = launch_bf16<true, false>(stream, p, grid, vec, big, pipelined);
-    else                             e = launch_bf16<true, true>(stream, p, grid, vec, big, pipelined);
+    // bf16 copies of both operands are used where the kernel that takes them runs (256 x 256 tiles, pipelined) and
+    // the copies consist of whole, 16-byte aligned groups of 8 values along their contiguous dimension
+    const size_t a16_panel = g.transA16 ? kspan * g.lda16 * 2 : (size_t)tile_m * g.lda16 * 2;
+    const size_t b16_panel = g.transB16 ? (size_t)tile_n * g.ldb16 * 2 : kspan * g.ldb16 * 2;
+    const bool mem16 = g.A16 && g.B16 && big && (g.variant != 2) && aligned16(g.A16) && aligned16(g.B16) &&
+                       g.lda16 % 8 == 0 && g.ldb16 % 8 == 0 && g.K % 8 == 0 && (g.transA16 ? g.M : g.K) % 8 == 0 &&
+                       (g.transB16 ? g.K : g.N) % 8 == 0 && p.kchunk % 8 == 0 && a16_panel < (1ull << 31) && b16_panel < (1ull << 31);
+    if (g.require_mem16 && !mem16) return hipErrorInvalidValue;
+    bool tA = g.transA, tB = g.transB;
+    if (mem16) { tA = g.transA16; tB = g.transB16; p.lda = g.lda16; p.ldb = g.ldb16; }
+    const bool pl = mem16 || pipelined;
+    if (!tA && !tB)      e = launch_bf16<false, false>(stream, p, grid, vec, big, pl, mem16);
+    else if (!tA && tB)  e = launch_bf16<false, true>(stream, p, grid, vec, big, pl, mem16);
+    else if (tA && !tB)  e = launch_bf16<true, false>(stream, p, grid, vec, big, pl, mem16);
+    else                 e = launch_bf16<true, true>(stream, p, grid, vec, big, pl, mem16);
   } else if (pipelined) {
     // A product that shares its CUs with the recurrent kernels keeps to the plain kernel: measured on the
     // 4 x 500 stack, the pipelined kernel beside them finishes its products sooner but slows every recurrent
@@ -1160,6 +1271,78 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
     e = splitk_reduce(stream, g.splitk_ws, slices, g.M, g.N, g.C, g.ldc, g.bias, g.accumulate);
   }
   return e;
+}
+
+namespace {
+// fp32 -> bf16 (round to nearest even), 8 values per thread; n is a multiple of 8, both arrays 16-byte aligned
+__global__ __launch_bounds__(256) void to_bf16_kernel(const float* __restrict__ src, unsigned short* __restrict__ dst, size_t n8) {
+  const size_t gsz = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += gsz) {
+    const float4 a = reinterpret_cast<const float4*>(src)[2 * i], b = reinterpret_cast<const float4*>(src)[2 * i + 1];
+    uint4 w;
+    w.x = pack_bf16(a.x, a.y); w.y = pack_bf16(a.z, a.w); w.z = pack_bf16(b.x, b.y); w.w = pack_bf16(b.z, b.w);
+    reinterpret_cast<uint4*>(dst)[i] = w;
+  }
+}
+}  // namespace
+
+namespace {
+// src [R, C] fp32 (row stride ld) -> dst [R, C] bf16 (row stride ldd; may be null) and dstT [C, R] bf16 (row stride R;
+// may be null).  One workgroup per 64 x 64 tile; the transposed copy goes through LDS so that both are written in
+// 16-byte (dstT) or 8-byte (dst) pieces.  R and C are multiples of 8.
+__global__ __launch_bounds__(256) void to_bf16_2d_kernel(const float* __restrict__ src, int R, int C, int ld,
+                                                          unsigned short* __restrict__ dst, int ldd, unsigned short* __restrict__ dstT) {
+  __shared__ float tile[64][65];
+  const int tiles_c = (C + 63) / 64;
+  const int r0 = (int)(blockIdx.x / tiles_c) * 64, c0 = (int)(blockIdx.x % tiles_c) * 64;
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int idx = tid + i * 256;
+    const int r = idx >> 4, c = (idx & 15) * 4;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (r0 + r < R && c0 + c < C) v = *reinterpret_cast<const float4*>(src + (size_t)(r0 + r) * ld + c0 + c);
+    tile[r][c] = v.x; tile[r][c + 1] = v.y; tile[r][c + 2] = v.z; tile[r][c + 3] = v.w;
+    if (dst && r0 + r < R && c0 + c < C) {
+      uint2 w;
+      w.x = pack_bf16(v.x, v.y); w.y = pack_bf16(v.z, v.w);
+      *reinterpret_cast<uint2*>(dst + (size_t)(r0 + r) * ldd + c0 + c) = w;
+    }
+  }
+  if (!dstT) return;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int idx = tid + i * 256;
+    const int c = idx >> 3, r = (idx & 7) * 8;
+    if (c0 + c < C && r0 + r < R) {
+      uint4 w;
+      w.x = pack_bf16(tile[r][c], tile[r + 1][c]); w.y = pack_bf16(tile[r + 2][c], tile[r + 3][c]);
+      w.z = pack_bf16(tile[r + 4][c], tile[r + 5][c]); w.w = pack_bf16(tile[r + 6][c], tile[r + 7][c]);
+      *reinterpret_cast<uint4*>(dstT + (size_t)(c0 + c) * R + r0 + r) = w;
+    }
+  }
+}
+}  // namespace
+
+hipError_t to_bf16_2d(hipStream_t stream, const float* src, int R, int C, int ld, unsigned short* dst, int ldd, unsigned short* dstT) {
+  if (ldd == 0) ldd = C;
+  if (R % 8 != 0 || C % 8 != 0 || ld % 4 != 0 || ldd % 8 != 0 || ldd < C || !aligned16(src) || (dst && !aligned16(dst)) ||
+      (dstT && !aligned16(dstT)))
+    return hipErrorInvalidValue;
+  if (R == 0 || C == 0) return hipSuccess;
+  const size_t tiles = (size_t)((R + 63) / 64) * ((C + 63) / 64);
+  hipLaunchKernelGGL(to_bf16_2d_kernel, dim3((unsigned)tiles), dim3(256), 0, stream, src, R, C, ld, dst, ldd, dstT);
+  return hipGetLastError();
+}
+
+hipError_t to_bf16(hipStream_t stream, const float* src, unsigned short* dst, size_t n) {
+  if (n % 8 != 0 || !aligned16(src) || !aligned16(dst)) return hipErrorInvalidValue;
+  if (n == 0) return hipSuccess;
+  const size_t n8 = n / 8;
+  const unsigned grid = (unsigned)std::min<size_t>((n8 + 255) / 256, 16384);
+  hipLaunchKernelGGL(to_bf16_kernel, dim3(grid), dim3(256), 0, stream, src, dst, n8);
+  return hipGetLastError();
 }
 
 size_t gemm_small_lds_bytes(int operand_dtype) {

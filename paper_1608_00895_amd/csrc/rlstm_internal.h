@@ -32,8 +32,22 @@ struct GemmCall {
   bool naive = false;
   bool small_footprint = false;   // runs beside the recurrent kernels on shared CUs: keep to the plain 128 x 128 kernel
   int variant = 0;                // fp32 kernel choice: 0 by call, 1 the pipelined kernel wherever it applies, 2 the plain kernel
+  // operand_dtype 1 only: bf16 copies of op(A) and op(B) (written by to_bf16 / to_bf16_2d), in a layout of their own:
+  // transA16 == false: A16 is [M,K] with row stride lda16 (k contiguous); true: stored [K,M]; B16 likewise (transB16
+  // == false: [K,N]; true: stored [N,K]).  They are used instead of A and B where the kernel that takes bf16 from
+  // memory runs; A and B stay valid (other kernels read them).  require_mem16: fail with hipErrorInvalidValue
+  // instead of falling back.
+  const unsigned short* A16 = nullptr; const unsigned short* B16 = nullptr;
+  int lda16 = 0, ldb16 = 0;
+  bool transA16 = false, transB16 = false;
+  bool require_mem16 = false;
 };
 hipError_t gemm(hipStream_t stream, const GemmCall& g);
+// dst[i] = bf16(src[i]) (round to nearest even); n a multiple of 8, both arrays 16-byte aligned
+hipError_t to_bf16(hipStream_t stream, const float* src, unsigned short* dst, size_t n);
+// src [R, C] fp32 (row stride ld, a multiple of 4) -> dst [R, C] bf16 with row stride ldd (0: C; a multiple of 8; dst
+// may be null) and its transpose dstT [C, R] bf16, dense (or null); R, C multiples of 8, all arrays 16-byte aligned
+hipError_t to_bf16_2d(hipStream_t stream, const float* src, int R, int C, int ld, unsigned short* dst, int ldd, unsigned short* dstT);
 
 // ---------------------------------------------------------------------------
 // Recurrent passes.  One call handles ndir (1 or 2) independent directions of

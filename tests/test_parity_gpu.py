@@ -321,6 +321,57 @@ def test_gemm_bf16_against_numpy(case):
     assert gh.rel_err(got, ref) < 2e-2, case
 
 
+@pytest.mark.parametrize("case", [
+    # every operand layout; ragged tiles in m and n; K tails inside a slab of 32; split-K
+    (0, 0, 3000, 2904, 104), (0, 1, 2832, 3104, 72), (1, 0, 2904, 2952, 4104), (1, 1, 2824, 2904, 40), (1, 0, 1000, 4000, 16384),
+])
+def test_gemm_bf16_operands_read_as_bf16_from_memory(case):
+    """The product kernel that takes bf16 copies of its operands from memory: the bits of the kernel that reads fp32 and
+    rounds on the way into LDS (the same rounding, the same order of sums), and the fp64 product of the rounded operands
+    up to fp32 accumulation.  The copy itself against the definition of the format."""
+    ta, tb, M, N, K = case
+    rng = _rng(sum(case) + 7)
+    A = rng.standard_normal((K, M) if ta else (M, K)).astype(np.float32)
+    Bm = rng.standard_normal((N, K) if tb else (K, N)).astype(np.float32)
+    bias = rng.standard_normal(N).astype(np.float32)
+    Ad, Bd, biasd = gh.dev(A), gh.dev(Bm), gh.dev(bias)
+    A16 = torch.zeros(A.shape, dtype=torch.int16, device=gh.DEV)
+    B16 = torch.zeros(Bm.shape, dtype=torch.int16, device=gh.DEV)
+    A16t = torch.zeros(A.shape[::-1], dtype=torch.int16, device=gh.DEV)
+    B16t = torch.zeros(Bm.shape[::-1], dtype=torch.int16, device=gh.DEV)
+    rl.rlstm_to_bf16(A16, Ad)
+    rl.rlstm_to_bf16_2d(B16, B16t, Bd, Bm.shape[0], Bm.shape[1], Bm.shape[1])
+    rl.rlstm_to_bf16_2d(None, A16t, Ad, A.shape[0], A.shape[1], A.shape[1])
+    torch.cuda.synchronize()
+    bits = lambda a: (_round_bf16(a).view(np.uint32) >> 16).astype(np.uint16)
+    assert np.array_equal(A16.cpu().numpy().view(np.uint16), bits(A))
+    assert np.array_equal(B16.cpu().numpy().view(np.uint16), bits(Bm))
+    assert np.array_equal(A16t.cpu().numpy().view(np.uint16), bits(A).T)
+    assert np.array_equal(B16t.cpu().numpy().view(np.uint16), bits(Bm).T)
+    ws = torch.empty(16 * M * N * 4, dtype=torch.uint8, device=gh.DEV)
+    Cref = torch.full((M, N), float("nan"), device=gh.DEV)
+    rl.rlstm_gemm_bf16(ta, tb, M, N, K, Ad, A.shape[1], Bd, Bm.shape[1], Cref, N, biasd, ws)
+    torch.cuda.synchronize()
+    ref = Cref.cpu().numpy()
+    Ar, Br = _round_bf16(A).astype(np.float64), _round_bf16(Bm).astype(np.float64)
+    assert gh.rel_err(ref, (Ar.T if ta else Ar) @ (Br.T if tb else Br) + bias) < 1e-5, case
+    # the same product from the copies as stored, and from the transposed copies with the transposition flags flipped
+    # (every combination of layouts goes through a different pair of loaders)
+    for fa in (0, 1):
+        for fb in (0, 1):
+            a16, b16 = (A16t if fa else A16), (B16t if fb else B16)
+            C = torch.full((M, N), float("nan"), device=gh.DEV)
+            rl.rlstm_gemm_bf16_mem(ta ^ fa, tb ^ fb, M, N, K, a16, a16.shape[1], b16, b16.shape[1], C, N, biasd, ws)
+            torch.cuda.synchronize()
+            assert np.array_equal(C.cpu().numpy(), ref), (case, fa, fb)
+    # a shape without the tiles for that kernel, or a K that is no multiple of 8, is refused, not silently rerouted
+    assert rl.rlstm_gemm_bf16_mem(0, 0, 64, 64, 64, A16, 64, B16, 64, C, N, None, None, check=False) == -3
+    if not ta and not tb:
+        assert rl.rlstm_gemm_bf16_mem(0, 0, M, N, K - 4, A16, A.shape[1], B16, Bm.shape[1], C, N, None, None, check=False) == -3
+    # the converter refuses what it cannot write in whole aligned groups
+    assert rl.rlstm_to_bf16_2d(B16, B16t, Bd, Bm.shape[0] - 4, Bm.shape[1], Bm.shape[1], check=False) == -2
+
+
 TOL_BF16 = 2e-2
 
 
