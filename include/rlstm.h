@@ -276,13 +276,14 @@ RLSTM_API int rlstm_gemm_bf16(int trans_a, int trans_b, int M, int N, int K,
  *   trans_a / trans_b / lda / ldb meaning of rlstm_gemm_f32 (strides in bf16 elements).  The result has the bits of
  *   rlstm_gemm_bf16 on fp32 operands that round to these bf16 values.  RLSTM_EMODE when the shape does not take the
  *   kernel that reads bf16 from memory (it needs 256 x 256 tiles to fill the chip, whole 16-byte aligned groups of 8
- *   values along the operands' contiguous dimensions and K a multiple of 8).
+ *   values along the operands' contiguous dimensions and K a multiple of 8).  variant 0: one workgroup per CU that
+ *   walks through its share of the tiles; 3: one workgroup per tile (for measurement).
  */
 RLSTM_API int rlstm_to_bf16(uint16_t* dst, const float* src, size_t n, void* hip_stream);
 RLSTM_API int rlstm_to_bf16_2d(uint16_t* dst, uint16_t* dst_t, const float* src, int R, int C, int ld, void* hip_stream);
 RLSTM_API int rlstm_gemm_bf16_mem(int trans_a, int trans_b, int M, int N, int K,
                         const uint16_t* A16, int lda, const uint16_t* B16, int ldb,
-                        float* C, int ldc, const float* bias, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream);
+                        float* C, int ldc, const float* bias, int variant, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream);
 
 /*
  * Optional per-kernel timing for measurement (not part of the method).  While

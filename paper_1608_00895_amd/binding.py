@@ -127,7 +127,7 @@ def lib() -> ctypes.CDLL:
         L.rlstm_to_bf16.restype = ip
         L.rlstm_to_bf16.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.rlstm_gemm_bf16_mem.restype = ip
-        L.rlstm_gemm_bf16_mem.argtypes = [ip, ip, ip, ip, ip, vp, ip, vp, ip, vp, ip, vp, vp, ctypes.c_size_t, vp]
+        L.rlstm_gemm_bf16_mem.argtypes = [ip, ip, ip, ip, ip, vp, ip, vp, ip, vp, ip, vp, ip, vp, ctypes.c_size_t, vp]
         L.rlstm_to_bf16_2d.restype = ip
         L.rlstm_to_bf16_2d.argtypes = [vp, vp, vp, ip, ip, ip, vp]
         L.rlstm_copy_f32.restype = ip
@@ -403,10 +403,10 @@ def rlstm_to_bf16_2d(dst, dst_t, src, R, C, ld, stream=None, check=True) -> int:
 
 
 def rlstm_gemm_bf16_mem(trans_a, trans_b, M, N, K, A16, lda, B16, ldb, C, ldc, bias=None, splitk_ws=None,
-                        stream=None, check=True) -> int:
+                        stream=None, check=True, variant=0) -> int:
     nbytes = 0 if splitk_ws is None else splitk_ws.numel() * splitk_ws.element_size()
     rc = lib().rlstm_gemm_bf16_mem(int(trans_a), int(trans_b), M, N, K, _ptr(A16), lda, _ptr(B16), ldb,
-                                   _ptr(C), ldc, _ptr(bias), _ptr(splitk_ws), nbytes, _stream(stream))
+                                   _ptr(C), ldc, _ptr(bias), int(variant), _ptr(splitk_ws), nbytes, _stream(stream))
     if check and rc != 0:
         raise RlstmError(rc, "rlstm_gemm_bf16_mem")
     return rc

@@ -1158,15 +1158,16 @@ int rlstm_to_bf16_2d(uint16_t* dst, uint16_t* dst_t, const float* src, int R, in
 
 int rlstm_gemm_bf16_mem(int trans_a, int trans_b, int M, int N, int K,
                         const uint16_t* A16, int lda, const uint16_t* B16, int ldb,
-                        float* C, int ldc, const float* bias, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream) {
+                        float* C, int ldc, const float* bias, int variant, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream) {
   if (!A16 || !B16 || !C) return RLSTM_ENULL;
+  if (variant != 0 && variant != 3) return RLSTM_EMODE;
   if (M <= 0 || N <= 0 || K < 0) return RLSTM_EDIM;
   if (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N) || ldc < N) return RLSTM_EDIM;
   int resident_err = 0;
   GemmCall g;
   g.transA = g.transA16 = trans_a != 0; g.transB = g.transB16 = trans_b != 0;
   g.M = M; g.N = N; g.K = K; g.C = C; g.ldc = ldc; g.bias = bias;
-  g.A16 = A16; g.lda16 = lda; g.B16 = B16; g.ldb16 = ldb; g.require_mem16 = true;
+  g.A16 = A16; g.lda16 = lda; g.B16 = B16; g.ldb16 = ldb; g.require_mem16 = true; g.variant = variant;
   g.splitk_ws = static_cast<float*>(splitk_ws); g.splitk_floats = splitk_ws ? splitk_ws_bytes / sizeof(float) : 0;
   g.operand_dtype = 1;
   const hipError_t e = gemm(static_cast<hipStream_t>(hip_stream), g);

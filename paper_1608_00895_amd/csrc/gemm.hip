@@ -63,6 +63,43 @@ __device__ __forceinline__ bool work_item(const GemmP& p, int* tile, int* kz) {
   return true;
 }
 
+// Epilogue of the MFMA kernels with 32 x 32 accumulator tiles: register r of lane l holds
+// C[(r/4)*8 + (l/32)*4 + r%4][l%32] of its tile.  A wavefront owns WM x WN such tiles starting at (row0, col0).
+// The stores go ROW BY ROW: those of one row's 32 * WN columns are issued back to back, so that memory sees runs of
+// 128 * WN bytes instead of single 128-byte pieces 4 * ldc bytes apart (measured on 96000 x 4000 outputs of the
+// 256 x 256 tile kernel: 4.3 against 1.9 TB/s of stores, 817 against 654 TFLOP/s at K = 2000).
+template <int WM, int WN>
+__device__ __forceinline__ void store_tiles(const GemmP& p, int kz, const floatx16 (&acc)[WM][WN], int row0, int col0) {
+  const int lane = threadIdx.x & 63, l32 = lane & 31, lh = lane >> 5;
+  float* Cout = p.C;
+  int ldc = p.ldc;
+  const bool partial = p.partial != nullptr;
+  if (partial) { Cout = p.partial + (size_t)kz * p.M * p.N; ldc = p.N; }
+  float bv[WN];
+#pragma unroll
+  for (int j = 0; j < WN; ++j) {
+    const int col = col0 + j * 32 + l32;
+    bv[j] = (!partial && p.bias && col < p.N) ? p.bias[col] : 0.f;
+  }
+#pragma unroll
+  for (int i = 0; i < WM; ++i) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int row = row0 + i * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
+      if (row >= p.M) continue;
+      float* drow = Cout + (size_t)row * ldc + col0 + l32;
+#pragma unroll
+      for (int j = 0; j < WN; ++j) {
+        if (col0 + j * 32 + l32 < p.N) {
+          float v = acc[i][j][r] + bv[j];
+          if (!partial && p.accumulate) v += drow[j * 32];
+          drow[j * 32] = v;
+        }
+      }
+    }
+  }
+}
+
 // ---- slab loaders: global -> registers -> LDS ------------------------------
 
 // "natural": element (k, mn) at ptr[k*ld + mn]; slab is BK rows of 128 floats.
@@ -216,31 +253,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_f32_kernel(GemmP p) {
     __syncthreads();
   }
 
-  // Epilogue.  Accumulator register r of lane l holds
-  // C[(r/4)*8 + (l/32)*4 + r%4][l%32] of its 32 x 32 tile.
-  float* Cout = p.C;
-  int ldc = p.ldc;
-  const bool partial = p.partial != nullptr;
-  if (partial) { Cout = p.partial + (size_t)kz * p.M * p.N; ldc = p.N; }
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int col = n0 + wn * 64 + j * 32 + l32;
-      if (col >= p.N) continue;
-      const float bv = (!partial && p.bias) ? p.bias[col] : 0.f;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm * 64 + i * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
-        if (row < p.M) {
-          float* dst = Cout + (size_t)row * ldc + col;
-          float v = acc[i][j][r] + bv;
-          if (!partial && p.accumulate) v += *dst;
-          *dst = v;
-        }
-      }
-    }
-  }
+  store_tiles<2, 2>(p, kz, acc, m0 + wm * 64, n0 + wn * 64);
 }
 
 // ---------------------------------------------------------------------------
@@ -414,29 +427,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_f32_v2_kernel(GemmP p) {
     __syncthreads();
   }
 
-  float* Cout = p.C;
-  int ldc = p.ldc;
-  const bool partial = p.partial != nullptr;
-  if (partial) { Cout = p.partial + (size_t)kz * p.M * p.N; ldc = p.N; }
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int col = n0 + wn * 64 + j * 32 + l32;
-      if (col >= p.N) continue;
-      const float bv = (!partial && p.bias) ? p.bias[col] : 0.f;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm * 64 + i * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
-        if (row < p.M) {
-          float* dst = Cout + (size_t)row * ldc + col;
-          float v = acc[i][j][r] + bv;
-          if (!partial && p.accumulate) v += *dst;
-          *dst = v;
-        }
-      }
-    }
-  }
+  store_tiles<2, 2>(p, kz, acc, m0 + wm * 64, n0 + wn * 64);
 }
 
 // ---------------------------------------------------------------------------
@@ -607,29 +598,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_bf16_kernel(GemmP p) {
     __syncthreads();
   }
 
-  float* Cout = p.C;
-  int ldc = p.ldc;
-  const bool partial = p.partial != nullptr;
-  if (partial) { Cout = p.partial + (size_t)kz * p.M * p.N; ldc = p.N; }
-#pragma unroll
-  for (int i = 0; i < WM; ++i) {
-#pragma unroll
-    for (int j = 0; j < WN; ++j) {
-      const int col = n0 + (wn * WN + j) * 32 + l32;
-      if (col >= p.N) continue;
-      const float bv = (!partial && p.bias) ? p.bias[col] : 0.f;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + (wm * WM + i) * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
-        if (row < p.M) {
-          float* dst = Cout + (size_t)row * ldc + col;
-          float v = acc[i][j][r] + bv;
-          if (!partial && p.accumulate) v += *dst;
-          *dst = v;
-        }
-      }
-    }
-  }
+  store_tiles<WM, WN>(p, kz, acc, m0 + wm * WM * 32, n0 + wn * WN * 32);
 }
 
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int slices,
@@ -1012,17 +981,24 @@ __global__ __launch_bounds__(256) void gemm_mfma_bf16_v2_kernel(GemmP p) {
   unsigned short* As = reinterpret_cast<unsigned short*>(smem);     // [2][TMB][LDK]
   unsigned short* Bs = As + 2 * TMB * LDK;                          // [2][TNB][LDK]
 
-  int tile, kz;
-  if (!work_item(p, &tile, &kz)) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, lh = lane >> 5;
+
+  // A workgroup takes the items j = slot, slot + slots, ... of its XCD's range (see work_item): with a grid of
+  // 8 * per_xcd workgroups that is one item each; with a grid of one workgroup per CU the workgroups stay and walk
+  // through the items, and the stores of one tile drain while the next tile's slabs are already being fetched.
+  const int slots = (int)(gridDim.x >> 3);
+  for (int j = (int)(blockIdx.x >> 3); j < p.per_xcd; j += slots) {
+  const int item = (int)(blockIdx.x & 7) * p.per_xcd + j;
+  if (item >= p.work) break;
+  const int kz = item / p.tiles;
+  const int tile = item - kz * p.tiles;
   const int tn = tile % p.tiles_n, tm = tile / p.tiles_n;
   const int m0 = tm * TMB, n0 = tn * TNB;
   const int kbeg = kz * p.kchunk;
   const int kend = min(p.K, kbeg + p.kchunk);
   const int nslab = (kend - kbeg + BKH - 1) / BKH;
-
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int l32 = lane & 31, lh = lane >> 5;
 
   floatx16 acc[WM][WN];
 #pragma unroll
@@ -1094,29 +1070,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_bf16_v2_kernel(GemmP p) {
     __syncthreads();
   }
 
-  float* Cout = p.C;
-  int ldc = p.ldc;
-  const bool partial = p.partial != nullptr;
-  if (partial) { Cout = p.partial + (size_t)kz * p.M * p.N; ldc = p.N; }
-#pragma unroll
-  for (int i = 0; i < WM; ++i) {
-#pragma unroll
-    for (int j = 0; j < WN; ++j) {
-      const int col = n0 + (wn * WN + j) * 32 + l32;
-      if (col >= p.N) continue;
-      const float bv = (!partial && p.bias) ? p.bias[col] : 0.f;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + (wm * WM + i) * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
-        if (row < p.M) {
-          float* dst = Cout + (size_t)row * ldc + col;
-          float v = acc[i][j][r] + bv;
-          if (!partial && p.accumulate) v += *dst;
-          *dst = v;
-        }
-      }
-    }
-  }
+  store_tiles<WM, WN>(p, kz, acc, m0 + wm * WM * 32, n0 + wn * WN * 32);
+  }  // items of this workgroup
 }
 
 template <int WM, int WN, bool TA, bool TB, bool M16>
@@ -1153,6 +1108,14 @@ hipError_t launch_bf16(hipStream_t stream, const GemmP& p, dim3 grid, bool vec, 
 
 }  // namespace
 
+
+namespace {
+int current_device() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); dev = 0; }
+  return dev;
+}
+}  // namespace
 
 hipError_t gemm(hipStream_t stream, const GemmCall& g) {
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
@@ -1248,6 +1211,13 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
     bool tA = g.transA, tB = g.transB;
     if (mem16) { tA = g.transA16; tB = g.transB16; p.lda = g.lda16; p.ldb = g.ldb16; }
     const bool pl = mem16 || pipelined;
+    if (mem16 && g.variant != 3) {
+      // one workgroup per CU (the kernel's LDS and registers allow no more), each walking through its XCD's items
+      int cus = 0;
+      if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, current_device()) != hipSuccess) { (void)hipGetLastError(); cus = 0; }
+      const int slots = cus / 8;
+      if (slots > 0 && slots < p.per_xcd) grid = dim3((unsigned)(8 * slots), 1, 1);
+    }
     if (!tA && !tB)      e = launch_bf16<false, false>(stream, p, grid, vec, big, pl, mem16);
     else if (!tA && tB)  e = launch_bf16<false, true>(stream, p, grid, vec, big, pl, mem16);
     else if (tA && !tB)  e = launch_bf16<true, false>(stream, p, grid, vec, big, pl, mem16);
