@@ -380,6 +380,8 @@ def main():
                     help="1 serial, 2 products share CUs with the recurrent kernels (chosen per shape if omitted)")
     ap.add_argument("--bwd-exchange", type=int, default=None,
                     help="exchanges per step of the backward recurrent kernel: 1 two, 2 one where it applies (library default if omitted)")
+    ap.add_argument("--gemm-variant", type=int, default=None,
+                    help="matrix-product kernel choice (the descriptors' gemm_variant; library default if omitted)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed region, run one plain 1 GiB copy kernel (known HBM traffic) "
@@ -429,7 +431,7 @@ def main():
         sl = torch.from_numpy(wl.seq_lens).to(dev)
     log(f"workload {wl.name}: L={wl.L} T={wl.T} B={wl.B} D={wl.D} H={wl.H} frames={wl.frames} slots={wl.T * wl.B}")
     tuning = dict(first_piece=args.first_piece or 0, batch_groups=args.batch_groups or 0, overlap_mode=args.overlap_mode or 0,
-                  bwd_exchange=args.bwd_exchange or 0)
+                  bwd_exchange=args.bwd_exchange or 0, gemm_variant=args.gemm_variant or 0)
     desc = rl.rblstm_desc(L=wl.L, T=wl.T, B=wl.B, D=wl.D, H=wl.H, operand_dtype=wl.operand_dtype, engine=args.engine, **tuning)
     train = None
     host_params = [a for layer in wl.params for p in layer for a in p]
@@ -546,7 +548,7 @@ def main():
     # bytes per launch at the L2-to-fabric interface, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs recorded in
     # profiles/hbm_traffic.json (default settings only; scaled by the copy kernel)
     default_knobs = (args.first_piece is None and args.batch_groups is None and not args.one_stream and args.engine == 0
-                     and args.overlap_mode is None and args.bwd_exchange is None)
+                     and args.overlap_mode is None and args.bwd_exchange is None and args.gemm_variant is None)
     try:
         plan_now = rl.rblstm_plan(desc) if args.engine in (0, 1) else None
     except rl.RlstmError:

@@ -257,6 +257,119 @@ __global__ __launch_bounds__(256) void gemm_mfma_f32_kernel(GemmP p) {
 }
 
 // ---------------------------------------------------------------------------
+// The same kernel on the SHORT matrix instruction (v_mfma_f32_16x16x4_f32, 32 cycles, against the 64 cycles of
+// v_mfma_f32_32x32x2_f32; the same flops per cycle), for the products that share their CUs with the persistent
+// recurrent kernels.  The idea was that a recurrent wavefront, however high its priority, cannot issue its own short,
+// dependent matrix instructions while one of the product's is in the pipeline.  Measured on the 4 x 500 stack the
+// recurrent steps beside the products do NOT get faster (5.66 / 8.23 us against 5.62 / 8.30 us; alone 4.57 / 5.48):
+// the matrix pipeline is not where the two kernels collide.  The products themselves run 4 to 10 % faster beside the
+// chain (weight gradients 83 against 80 TFLOP/s, 59.2 against 60.0 ms per training pass), which is why it is kept.
+// Requesting enough LDS that only one product workgroup fits beside a recurrent one changed nothing either.
+// Same tiles, same LDS layout and loaders; a wavefront's 64 x 64 is 4 x 4 tiles of 16 x 16 (64 accumulator registers
+// as before); per step of 4 k it reads 4 + 4 operand words from LDS for 16 instructions, the same words per k as the
+// kernel above.
+typedef float floatx4s __attribute__((ext_vector_type(4)));
+template <int BK, bool TA, bool TB, bool VEC>
+__global__ __launch_bounds__(256) void gemm_mfma_f32_short_kernel(GemmP p) {
+  extern __shared__ __align__(16) float smem[];
+  float* As = smem;                       // [2][BK][LDT]
+  float* Bs = smem + 2 * BK * LDT;        // [2][BK][LDT]
+
+  int tile, kz;
+  if (!work_item(p, &tile, &kz)) return;
+  const int tn = tile % p.tiles_n, tm = tile / p.tiles_n;
+  const int m0 = tm * TM, n0 = tn * TN;
+  const int kbeg = kz * p.kchunk;
+  const int kend = min(p.K, kbeg + p.kchunk);
+  const int nslab = (kend - kbeg + BK - 1) / BK;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l16 = lane & 15, lq = lane >> 4;
+
+  floatx4s acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = floatx4s{0.f, 0.f, 0.f, 0.f};
+
+  float4 ra[BK / 8], rb[BK / 8];
+  auto loadA = [&](int k0) {
+    if (TA) load_natural<BK, VEC>(p.A, p.lda, k0, kend, m0, p.M, ra);
+    else    load_transposing<BK, VEC>(p.A, p.lda, k0, kend, m0, p.M, ra);
+  };
+  auto loadB = [&](int k0) {
+    if (TB) load_transposing<BK, VEC>(p.B, p.ldb, k0, kend, n0, p.N, rb);
+    else    load_natural<BK, VEC>(p.B, p.ldb, k0, kend, n0, p.N, rb);
+  };
+  auto storeAB = [&](int buf) {
+    if (TA) store_natural<BK>(As + buf * BK * LDT, ra); else store_transposing<BK>(As + buf * BK * LDT, ra);
+    if (TB) store_transposing<BK>(Bs + buf * BK * LDT, rb); else store_natural<BK>(Bs + buf * BK * LDT, rb);
+  };
+
+  if (nslab > 0) {
+    loadA(kbeg); loadB(kbeg);
+    storeAB(0);
+  }
+  __syncthreads();
+
+  for (int s = 0; s < nslab; ++s) {
+    const int buf = s & 1;
+    if (s + 1 < nslab) { loadA(kbeg + (s + 1) * BK); loadB(kbeg + (s + 1) * BK); }
+    // lane (l16, lq) holds A[row l16][k + lq] and B[k + lq][column l16] of each 16 x 16 tile
+    const float* as = As + buf * BK * LDT + lq * LDT + wm * 64 + l16;
+    const float* bs = Bs + buf * BK * LDT + lq * LDT + wn * 64 + l16;
+    float a[4], b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { a[i] = as[i * 16]; b[i] = bs[i * 16]; }
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 4) {
+      float na[4] = {0.f, 0.f, 0.f, 0.f}, nb[4] = {0.f, 0.f, 0.f, 0.f};
+      if (kk + 4 < BK) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { na[i] = as[(kk + 4) * LDT + i * 16]; nb[i] = bs[(kk + 4) * LDT + i * 16]; }
+      }
+      __builtin_amdgcn_sched_barrier(0);   // keep the LDS reads above ahead of this step's MFMAs
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[i], b[j], acc[i][j], 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { a[i] = na[i]; b[i] = nb[i]; }
+    }
+    if (s + 1 < nslab) storeAB(buf ^ 1);
+    __syncthreads();
+  }
+
+  // Register r of lane (l16, lq) holds C[4 * lq + r][l16] of its 16 x 16 tile.  Row by row, as in store_tiles.
+  float* Cout = p.C;
+  int ldc = p.ldc;
+  const bool partial = p.partial != nullptr;
+  if (partial) { Cout = p.partial + (size_t)kz * p.M * p.N; ldc = p.N; }
+  const int col0 = n0 + wn * 64 + l16;
+  float bv[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) bv[j] = (!partial && p.bias && col0 + j * 16 < p.N) ? p.bias[col0 + j * 16] : 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int row = m0 + wm * 64 + i * 16 + lq * 4 + r;
+      if (row >= p.M) continue;
+      float* drow = Cout + (size_t)row * ldc + col0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (col0 + j * 16 < p.N) {
+          float v = acc[i][j][r] + bv[j];
+          if (!partial && p.accumulate) v += drow[j * 16];
+          drow[j * 16] = v;
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // Pipelined fp32 kernel for operands whose rows are whole, 16-byte aligned float4s (the usual case).
 // Same tile shape as above; what differs is how a slab gets from memory into LDS:
 //  * buffer loads with a byte range instead of branches: a lane outside the matrix (row or column tail,
@@ -788,9 +901,12 @@ __global__ __launch_bounds__(256) void gemm_naive_kernel(GemmP p, int transA, in
 inline bool aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
 
 template <int BK, bool TA, bool TB>
-hipError_t launch_mfma(hipStream_t stream, const GemmP& p, dim3 grid, bool vec) {
+hipError_t launch_mfma(hipStream_t stream, const GemmP& p, dim3 grid, bool vec, bool short_mfma) {
   const size_t lds = (size_t)4 * BK * LDT * sizeof(float);
-  if (vec) {
+  if (short_mfma) {
+    if (vec) hipLaunchKernelGGL((gemm_mfma_f32_short_kernel<BK, TA, TB, true>), grid, dim3(256), lds, stream, p);
+    else     hipLaunchKernelGGL((gemm_mfma_f32_short_kernel<BK, TA, TB, false>), grid, dim3(256), lds, stream, p);
+  } else if (vec) {
     hipLaunchKernelGGL((gemm_mfma_f32_kernel<BK, TA, TB, true>), grid, dim3(256), lds, stream, p);
   } else {
     hipLaunchKernelGGL((gemm_mfma_f32_kernel<BK, TA, TB, false>), grid, dim3(256), lds, stream, p);
@@ -1231,10 +1347,12 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
     else if (g.transA && !g.transB)  e = launch_mfma_v2<true, false>(stream, p, grid);
     else                             e = launch_mfma_v2<true, true>(stream, p, grid);
   } else {
-    if (!g.transA && !g.transB)      e = launch_mfma<16, false, false>(stream, p, grid, vec);
-    else if (!g.transA && g.transB)  e = launch_mfma<16, false, true>(stream, p, grid, vec);
-    else if (g.transA && !g.transB)  e = launch_mfma<16, true, false>(stream, p, grid, vec);
-    else                             e = launch_mfma<16, true, true>(stream, p, grid, vec);
+    // beside the recurrent kernels: the short matrix instruction (see gemm_mfma_f32_short_kernel); variant 2 keeps the long one
+    const bool sh = g.small_footprint && g.variant != 2;
+    if (!g.transA && !g.transB)      e = launch_mfma<16, false, false>(stream, p, grid, vec, sh);
+    else if (!g.transA && g.transB)  e = launch_mfma<16, false, true>(stream, p, grid, vec, sh);
+    else if (g.transA && !g.transB)  e = launch_mfma<16, true, false>(stream, p, grid, vec, sh);
+    else                             e = launch_mfma<16, true, true>(stream, p, grid, vec, sh);
   }
   if (e != hipSuccess) return e;
   if (slices > 1) {
