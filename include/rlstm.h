@@ -507,6 +507,17 @@ RLSTM_API int rlstm_exchange_floor(int groups, int members, int tile_bytes, int 
  */
 RLSTM_API int rlstm_test_hook(int mute_workgroup, uint64_t wait_ticks);
 
+/*
+ * Test hook against races in the exchange between the workgroups of the persistent kernels (not part of the method).
+ * From the next call on, workgroup `slow_workgroup` of every persistent launch holds back what it publishes (its part
+ * of h_t or d a_t, then its step flag) for `ticks` ticks of the 100 MHz wall clock, every step (-1: none does; ticks
+ * at most 100000 = 1 ms, RLSTM_EDIM beyond).  A consumer that did not wait for its producer would read the values of
+ * two steps ago: the outputs must have the bits of an undisturbed call, only later.  rlstm_test_delay(-1, 0) restores
+ * normal operation.  The hook is process-wide and not synchronised with running calls: set it while no call is in
+ * flight.
+ */
+RLSTM_API int rlstm_test_delay(int slow_workgroup, uint32_t ticks);
+
 /* Which engine RLSTM_ENGINE_AUTO resolves to for this shape on the current
  * device: RLSTM_ENGINE_PERSISTENT or RLSTM_ENGINE_STEPWISE (negative: error). */
 RLSTM_API int rlstm_resolve_engine(const rlstm_desc* desc);

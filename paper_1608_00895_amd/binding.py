@@ -27,7 +27,7 @@ EXPORTS = [
     "blstm_stack_fwd_bwd", "blstm_stack_fwd", "blstm_stack_bwd",
     "rlstm_ce_workspace_bytes", "softmax_ce_fwd_bwd", "rlstm_sgd_momentum_step", "rlstm_adam_step",
     "rlstm_stream_reserve_bytes", "rlstm_stream_workspace_bytes", "lstm_stream_fwd_bwd",
-    "rlstm_gemm_f32", "rlstm_gemm_bf16", "rlstm_to_bf16", "rlstm_to_bf16_2d", "rlstm_gemm_bf16_mem", "rlstm_copy_f32", "rlstm_profile_enable", "rlstm_profile_read", "rlstm_last_timeout", "rlstm_test_hook", "rmdlstm_reserve_bytes", "rmdlstm_workspace_bytes", "mdlstm_fwd", "mdlstm_bwd", "rlstm_chunk_plan", "rlstm_chunk_gather", "rblstm_plan", "rlstm_exchange_floor_bytes", "rlstm_exchange_floor", "rlstm_resolve_engine", "rlstm_strerror", "rlstm_version",
+    "rlstm_gemm_f32", "rlstm_gemm_bf16", "rlstm_to_bf16", "rlstm_to_bf16_2d", "rlstm_gemm_bf16_mem", "rlstm_copy_f32", "rlstm_profile_enable", "rlstm_profile_read", "rlstm_last_timeout", "rlstm_test_hook", "rlstm_test_delay", "rmdlstm_reserve_bytes", "rmdlstm_workspace_bytes", "mdlstm_fwd", "mdlstm_bwd", "rlstm_chunk_plan", "rlstm_chunk_gather", "rblstm_plan", "rlstm_exchange_floor_bytes", "rlstm_exchange_floor", "rlstm_resolve_engine", "rlstm_strerror", "rlstm_version",
 ]
 
 
@@ -159,6 +159,8 @@ def lib() -> ctypes.CDLL:
         L.rlstm_exchange_floor.argtypes = [ip, ip, ip, ip, ip, vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_float), vp]
         L.rlstm_test_hook.restype = ip
         L.rlstm_test_hook.argtypes = [ip, ctypes.c_uint64]
+        L.rlstm_test_delay.restype = ip
+        L.rlstm_test_delay.argtypes = [ip, ctypes.c_uint32]
         L.rlstm_resolve_engine.restype = ip
         L.rlstm_resolve_engine.argtypes = [ctypes.POINTER(rlstm_desc)]
         L.rlstm_strerror.restype = ctypes.c_char_p
@@ -410,6 +412,10 @@ def rlstm_gemm_bf16_mem(trans_a, trans_b, M, N, K, A16, lda, B16, ldb, C, ldc, b
     if check and rc != 0:
         raise RlstmError(rc, "rlstm_gemm_bf16_mem")
     return rc
+
+
+def rlstm_test_delay(slow_workgroup: int = -1, ticks: int = 0) -> int:
+    return int(lib().rlstm_test_delay(int(slow_workgroup), int(ticks)))
 
 
 def rlstm_test_hook(mute_workgroup: int = -1, wait_ticks: int = 0) -> int:

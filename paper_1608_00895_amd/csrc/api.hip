@@ -614,6 +614,12 @@ int rlstm_exchange_floor(int groups, int members, int tile_bytes, int read_bytes
   return timed_out ? RLSTM_EHIP : RLSTM_OK;
 }
 
+int rlstm_test_delay(int slow_workgroup, uint32_t ticks) {
+  if (ticks > 100000u) return RLSTM_EDIM;          // at most 1 ms per step
+  persistent_test_delay(slow_workgroup, ticks);
+  return RLSTM_OK;
+}
+
 int rlstm_test_hook(int mute_workgroup, uint64_t wait_ticks) {
   persistent_test_hook(mute_workgroup, wait_ticks);
   mdlstm_test_hook(mute_workgroup, wait_ticks);

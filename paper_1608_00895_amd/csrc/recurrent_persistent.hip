@@ -88,6 +88,16 @@ __device__ __forceinline__ void publish_flag(unsigned* flags, int wg, unsigned v
   if (threadIdx.x < kFlagCopies) st_dev(flags + threadIdx.x * kFlagCopyStride + wg, value);
 }
 
+// Test hook against races in the exchange: workgroup `slow_wg` holds back what it is about to publish (data, then flag)
+// for `ticks` of the 100 MHz wall clock, every step.  A consumer that read an exchange buffer without having waited for
+// its producer would then read the values of two steps ago, and the results would differ from an undisturbed run; a
+// correct kernel gives the same bits, only later.  The wait is bounded by `ticks` (the host limits it to 1 ms).
+__device__ __forceinline__ void test_delay(int slow_wg, unsigned ticks) {
+  if ((int)blockIdx.x != slow_wg || ticks == 0u) return;
+  const unsigned long long t0 = wall_clock64();
+  while (wall_clock64() - t0 < (unsigned long long)ticks) __builtin_amdgcn_s_sleep(4);
+}
+
 // A wavefront waits until flags[first .. first+count) (clipped to limit) have all reached `want`.
 __device__ __forceinline__ bool wave_wait_flags(const unsigned* flags, int first, int count, int limit,
                                                 unsigned want, unsigned* err, unsigned long long wait_ticks) {
@@ -250,6 +260,7 @@ struct PFwdParams {
   unsigned* err;
   unsigned long long wait_ticks;   // bound of every wait, in 100 MHz wall-clock ticks
   int mute_wg;                     // test hook: this workgroup withholds its step flags (-1: none)
+  int slow_wg; unsigned slow_ticks; // test hook: this workgroup publishes every step late (see test_delay)
   int T, B, H, ldy, Gf, Hp, nch;
   int s_begin, s_end;              // steps [s_begin, s_end) of the T steps are done by this launch
 };
@@ -417,6 +428,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
 
     if (!is_io) {
       // gating, cell update, mask; publish the carried h; leave the frame's outputs in LDS
+      test_delay(p.slow_wg, p.slow_ticks);
       const float* zcur = zin + (s & 1) * 4 * NE;
       float* ocur = gout + (s & 1) * 6 * NE;
 #pragma unroll
@@ -500,6 +512,7 @@ struct PBwdParams {
   unsigned* err;
   unsigned long long wait_ticks;
   int mute_wg;
+  int slow_wg; unsigned slow_ticks;
   int T, B, H, ldy, PG, Hq, nch;
   int s_begin, s_end;
 };
@@ -721,6 +734,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
         for (int e = 0; e < EPT; ++e) Dh[e] = vprev[e] ? g[e] : g[e] + Dh[e];
       }
       // gate derivatives; publish d a of this frame
+      test_delay(p.slow_wg, p.slow_ticks);
       const float* in = bin + (s & 1) * 7 * NE;
       float* out = dzo + (s & 1) * 4 * NE;
 #pragma unroll
@@ -880,6 +894,7 @@ struct PBwd1Params {
   unsigned* err;
   unsigned long long wait_ticks;
   int mute_wg;
+  int slow_wg; unsigned slow_ticks;
   int T, B, H, ldy, Gm;
   int s_begin, s_end;
 };
@@ -1060,6 +1075,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_onehop_kernel(PBwd1Par
       if (tid == 0) st_dev(p.err, 1u);
       return;
     }
+    test_delay(p.slow_wg, p.slow_ticks);
     // gate derivatives of the owned pairs; d a of the frame in MFMA operand order and for the I/O wavefront
     if (!is_io && tid < NE) {
       float dz[4] = {0.f, 0.f, 0.f, 0.f};
@@ -1236,6 +1252,8 @@ __global__ __launch_bounds__(256) void db_sum_kernel(DbSumParams p) {
 // ---- host side ----------------------------------------------------------------
 unsigned long long g_wait_ticks = kDefaultWaitTicks;
 int g_mute_wg = -1;
+int g_slow_wg = -1;
+unsigned g_slow_ticks = 0;
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 constexpr size_t kFlagBytes = (size_t)kFlagCopies * kFlagCopyStride * sizeof(unsigned);
 
@@ -1419,6 +1437,11 @@ void persistent_test_hook(int mute_workgroup, unsigned long long wait_ticks) {
   g_wait_ticks = wait_ticks ? wait_ticks : kDefaultWaitTicks;
 }
 
+void persistent_test_delay(int slow_workgroup, unsigned ticks) {
+  g_slow_wg = slow_workgroup;
+  g_slow_ticks = slow_workgroup >= 0 ? ticks : 0u;
+}
+
 bool persistent_supported(const RecShape& s, int num_cus, size_t max_lds) {
   return make_plan(s, num_cus, max_lds).ok;
 }
@@ -1475,6 +1498,7 @@ hipError_t persistent_forward(hipStream_t stream, const RecShape& s, const RecFw
   pp.ndir = s.ndir; pp.B = s.B; pp.Bg = pl.Bg; pp.H = s.H; pp.KW = pl.Hp / 4; pp.wbytes = (int)wbytes; pp.MT = pl.MT; pp.bf = pl.bf;
   kp.ndir = s.ndir; kp.NG = pl.NG; kp.Bg = pl.Bg;
   kp.seq_lens = seq_lens; kp.err = err; kp.wait_ticks = g_wait_ticks; kp.mute_wg = g_mute_wg;
+  kp.slow_wg = g_slow_wg; kp.slow_ticks = g_slow_ticks;
   kp.T = s.T; kp.B = s.B; kp.H = s.H; kp.ldy = s.ldy; kp.Gf = pl.Gf; kp.Hp = pl.Hp; kp.nch = pl.nchF;
   kp.s_begin = s_begin; kp.s_end = s_end;
   if (s_begin == 0) {
@@ -1529,6 +1553,7 @@ hipError_t onehop_backward(hipStream_t stream, const RecShape& s, const Plan& pl
   pp.zero_words = reinterpret_cast<unsigned*>(scratch); pp.nzero = (size_t)pl.NG * gb.total / 4;
   kp.ndir = s.ndir; kp.NG = pl.NG; kp.Bg = pl.Bg;
   kp.seq_lens = seq_lens; kp.err = err; kp.wait_ticks = g_wait_ticks; kp.mute_wg = g_mute_wg;
+  kp.slow_wg = g_slow_wg; kp.slow_ticks = g_slow_ticks;
   kp.T = s.T; kp.B = s.B; kp.H = s.H; kp.ldy = s.ldy; kp.Gm = pl.Gf;
   kp.s_begin = s_begin; kp.s_end = s_end;
   if (s_begin == 0) hipLaunchKernelGGL(prep_kernel, dim3(256), dim3(256), 0, stream, pp);
@@ -1590,6 +1615,7 @@ hipError_t persistent_backward(hipStream_t stream, const RecShape& s, const RecB
   pp.ndir = s.ndir;
   kp.ndir = s.ndir; kp.NG = pl.NG; kp.Bg = pl.Bg;
   kp.seq_lens = seq_lens; kp.err = err; kp.wait_ticks = g_wait_ticks; kp.mute_wg = g_mute_wg;
+  kp.slow_wg = g_slow_wg; kp.slow_ticks = g_slow_ticks;
   kp.T = s.T; kp.B = s.B; kp.H = s.H; kp.ldy = s.ldy; kp.PG = pl.PG; kp.Hq = pl.Hq; kp.nch = pl.nchB;
   kp.s_begin = s_begin; kp.s_end = s_end;
   if (s_begin == 0) hipLaunchKernelGGL(prep_kernel, dim3(256), dim3(256), 0, stream, pp);

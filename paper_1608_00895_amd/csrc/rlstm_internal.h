@@ -115,6 +115,8 @@ bool persistent_plan_info(const RecShape& s, int num_cus, size_t max_lds, int ou
 size_t persistent_scratch_bytes_fwd(const RecShape& s);
 // test hook: workgroup `mute_workgroup` (-1: none) withholds its step flags; wait bound in 100 MHz ticks (0: default)
 void persistent_test_hook(int mute_workgroup, unsigned long long wait_ticks);
+// workgroup `slow_workgroup` of every persistent launch publishes each step `ticks` of the 100 MHz clock late (-1: none)
+void persistent_test_delay(int slow_workgroup, unsigned ticks);
 hipError_t persistent_forward(hipStream_t stream, const RecShape& s, const RecFwdDir* dirs, const int32_t* seq_lens,
                               char* scratch, unsigned* err, int* resident_err, int s_begin, int s_end);
 hipError_t persistent_backward(hipStream_t stream, const RecShape& s, const RecBwdDir* dirs, const int32_t* seq_lens,

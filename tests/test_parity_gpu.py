@@ -506,6 +506,37 @@ def test_bounded_waits_turn_a_silent_workgroup_into_an_error_flag():
 
 
 @pytest.mark.parametrize("bwd_exchange", [1, 2])
+@pytest.mark.parametrize("operand_dtype", [0, 1])
+def test_a_late_workgroup_changes_no_bit(operand_dtype, bwd_exchange):
+    """Race check of the exchange between the workgroups of the persistent kernels, forced from the host: one
+    workgroup publishes every step 3 us late (several times the step itself).  A consumer that read its producers'
+    data without having waited for them would take the values of two steps ago; with correct waits every output has
+    the bits of the undisturbed call.  Every kernel still ends normally and no wait expires."""
+    if operand_dtype == 1 and bwd_exchange == 2:
+        pytest.skip("one exchange per step exists for fp32 operands only")
+    import dataclasses
+    wl = dataclasses.replace(synth.small_blstm(seed=33, L=2, B=11, D=8, H=44, len_lo=3, len_hi=40), operand_dtype=operand_dtype)
+    run = gh.StackRun(wl, engine=rl.RLSTM_ENGINE_PERSISTENT, bwd_exchange=bwd_exchange)
+    run.step()
+    base = run.results()
+    plan = rl.rblstm_plan(run.desc)
+    members = plan["members_fwd"]            # workgroups 0 .. members-1 exist in every launch (index = member * groups + group)
+    assert members >= 4
+    assert rl.rlstm_test_delay(0, 100001) == -2
+    for slow in (0, 3, members - 1):
+        try:
+            rl.rlstm_test_delay(slow, 300)
+            run.step()
+            got = run.results()          # asserts that no wait expired
+        finally:
+            rl.rlstm_test_delay(-1, 0)
+        assert np.array_equal(got["y"], base["y"]), slow
+        assert np.array_equal(got["dx"], base["dx"]), slow
+        for a, b in zip(got["grads"], base["grads"]):
+            assert np.array_equal(a, b), slow
+
+
+@pytest.mark.parametrize("bwd_exchange", [1, 2])
 @pytest.mark.parametrize("first", [-1, 3, 7, 64])
 def test_stack_results_do_not_depend_on_how_the_passes_are_cut(first, bwd_exchange):
     """Two streams + persistent engine: the recurrent passes are cut into pieces (first, first, 2*first, ...; -1: not
