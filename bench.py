@@ -32,17 +32,37 @@ def log(*a):
 
 
 def clock_state():
-    """Clock and power state as rocm-smi reports it (a short string; None where the tool is not usable)."""
-    import re
-    import subprocess
-    try:
-        r = subprocess.run(["rocm-smi", "--showclocks", "--showpower", "--showperflevel"], capture_output=True, text=True,
-                           timeout=20)
-        keep = [re.sub(r"\s+", " ", ln.strip()) for ln in r.stdout.splitlines()
-                if any(k in ln for k in ("sclk", "mclk", "fclk", "Power", "Performance Level"))]
-        return "; ".join(keep) if keep else None
-    except Exception as ex:          # measurement aid only
-        return f"unavailable ({type(ex).__name__})"
+    """Clock and power state of the first GPU as the amdgpu driver's sysfs files report it (a short string; None
+    where they cannot be read).  Files are read directly: no other program is started from this process."""
+    import glob
+
+    def first_line(path, star_only=False):
+        try:
+            with open(path) as fh:
+                lines = [ln.strip() for ln in fh.read().splitlines() if ln.strip()]
+        except OSError:
+            return None
+        if star_only:
+            lines = [ln for ln in lines if ln.endswith("*")] or lines[:1]
+        return lines[0] if lines else None
+
+    out = []
+    for dev_dir in sorted(glob.glob("/sys/class/drm/card[0-9]*/device")):
+        if first_line(os.path.join(dev_dir, "vendor")) != "0x1002":
+            continue
+        for name, star in (("pp_dpm_sclk", True), ("pp_dpm_mclk", True), ("pp_dpm_fclk", True),
+                           ("power_dpm_force_performance_level", False)):
+            v = first_line(os.path.join(dev_dir, name), star)
+            if v is not None:
+                out.append(f"{name} {v}")
+        for hw in sorted(glob.glob(os.path.join(dev_dir, "hwmon", "hwmon*"))):
+            for name in ("power1_average", "power1_input"):
+                v = first_line(os.path.join(hw, name))
+                if v is not None:
+                    out.append(f"{name} {int(v) / 1e6:.0f} W")
+                    break
+        break
+    return "; ".join(out) if out else None
 
 
 def recorded_traffic(workload, kernel, version, plan=None):

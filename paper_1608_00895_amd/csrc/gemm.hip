@@ -1376,37 +1376,44 @@ __global__ __launch_bounds__(256) void to_bf16_kernel(const float* __restrict__ 
 
 namespace {
 // src [R, C] fp32 (row stride ld) -> dst [R, C] bf16 (row stride ldd; may be null) and dstT [C, R] bf16 (row stride R;
-// may be null).  One workgroup per 64 x 64 tile; the transposed copy goes through LDS so that both are written in
-// 16-byte (dstT) or 8-byte (dst) pieces.  R and C are multiples of 8.
+// may be null).  One workgroup per 128 x 128 tile; the transposed copy goes through LDS (as bf16) so that both are
+// written in runs of 256 bytes per row.  R and C are multiples of 8.
+constexpr int CV_T = 128;            // tile edge
+constexpr int CV_LD = CV_T + 2;      // LDS row stride in bf16: an odd number of words, so a column walks the banks
 __global__ __launch_bounds__(256) void to_bf16_2d_kernel(const float* __restrict__ src, int R, int C, int ld,
                                                           unsigned short* __restrict__ dst, int ldd, unsigned short* __restrict__ dstT) {
-  __shared__ float tile[64][65];
-  const int tiles_c = (C + 63) / 64;
-  const int r0 = (int)(blockIdx.x / tiles_c) * 64, c0 = (int)(blockIdx.x % tiles_c) * 64;
+  __shared__ unsigned short tile[CV_T * CV_LD];
+  const int tiles_c = (C + CV_T - 1) / CV_T;
+  const int r0 = (int)(blockIdx.x / tiles_c) * CV_T, c0 = (int)(blockIdx.x % tiles_c) * CV_T;
   const int tid = threadIdx.x;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < CV_T * CV_T / 4 / 256; ++i) {
     const int idx = tid + i * 256;
-    const int r = idx >> 4, c = (idx & 15) * 4;
+    const int r = idx >> 5, c = (idx & 31) * 4;
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (r0 + r < R && c0 + c < C) v = *reinterpret_cast<const float4*>(src + (size_t)(r0 + r) * ld + c0 + c);
-    tile[r][c] = v.x; tile[r][c + 1] = v.y; tile[r][c + 2] = v.z; tile[r][c + 3] = v.w;
-    if (dst && r0 + r < R && c0 + c < C) {
-      uint2 w;
-      w.x = pack_bf16(v.x, v.y); w.y = pack_bf16(v.z, v.w);
-      *reinterpret_cast<uint2*>(dst + (size_t)(r0 + r) * ldd + c0 + c) = w;
+    const bool in = r0 + r < R && c0 + c < C;
+    if (in) v = *reinterpret_cast<const float4*>(src + (size_t)(r0 + r) * ld + c0 + c);
+    uint2 w;
+    w.x = pack_bf16(v.x, v.y); w.y = pack_bf16(v.z, v.w);
+    if (dst && in) *reinterpret_cast<uint2*>(dst + (size_t)(r0 + r) * ldd + c0 + c) = w;
+    if (dstT) {
+      unsigned* q = reinterpret_cast<unsigned*>(tile + r * CV_LD + c);     // c and CV_LD are even: 4-byte aligned
+      q[0] = w.x; q[1] = w.y;
     }
   }
   if (!dstT) return;
   __syncthreads();
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < CV_T * CV_T / 8 / 256; ++i) {
     const int idx = tid + i * 256;
-    const int c = idx >> 3, r = (idx & 7) * 8;
+    const int c = idx >> 4, r = (idx & 15) * 8;
     if (c0 + c < C && r0 + r < R) {
+      unsigned short h[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) h[k] = tile[(r + k) * CV_LD + c];
       uint4 w;
-      w.x = pack_bf16(tile[r][c], tile[r + 1][c]); w.y = pack_bf16(tile[r + 2][c], tile[r + 3][c]);
-      w.z = pack_bf16(tile[r + 4][c], tile[r + 5][c]); w.w = pack_bf16(tile[r + 6][c], tile[r + 7][c]);
+      w.x = h[0] | ((unsigned)h[1] << 16); w.y = h[2] | ((unsigned)h[3] << 16);
+      w.z = h[4] | ((unsigned)h[5] << 16); w.w = h[6] | ((unsigned)h[7] << 16);
       *reinterpret_cast<uint4*>(dstT + (size_t)(c0 + c) * R + r0 + r) = w;
     }
   }
@@ -1419,7 +1426,7 @@ hipError_t to_bf16_2d(hipStream_t stream, const float* src, int R, int C, int ld
       (dstT && !aligned16(dstT)))
     return hipErrorInvalidValue;
   if (R == 0 || C == 0) return hipSuccess;
-  const size_t tiles = (size_t)((R + 63) / 64) * ((C + 63) / 64);
+  const size_t tiles = (size_t)((R + CV_T - 1) / CV_T) * ((C + CV_T - 1) / CV_T);
   hipLaunchKernelGGL(to_bf16_2d_kernel, dim3((unsigned)tiles), dim3(256), 0, stream, src, R, C, ld, dst, ldd, dstT);
   return hipGetLastError();
 }
