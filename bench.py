@@ -273,6 +273,45 @@ def bench_gemm(args):
                         "plain_kernel_ms": res["plain"], "plain_kernel_tflops": flop / res["plain"] / 1e9})
         log(kernels[-1])
         total_flop += flop; total_ms += res["picked"]
+    # the bf16-operand products at config 4's shapes: operands read as fp32 and rounded on the way into LDS (operands in the
+    # layouts the layer holds them in) against bf16 copies laid out along k (what the stack's large products run on)
+    bf16_kernels = []
+    shapes16 = [("config4 projection X W (NN)", 0, 0, 96000, 4000, 2000), ("config4 input gradient of both directions, K = 8H (NT)", 0, 1, 96000, 2000, 8000),
+                ("config4 weight gradient X^T dZ (TN)", 1, 0, 2000, 4000, 96000), ("config4 recurrent weight gradient (TN)", 1, 0, 1000, 4000, 95936)]
+    sk16 = torch.empty(512 << 20, dtype=torch.uint8, device=dev)
+    for name, ta, tb, M, N, K in shapes16:
+        A = torch.randn((K, M) if ta else (M, K), device=dev)
+        B = torch.randn((N, K) if tb else (K, N), device=dev)
+        C = torch.empty((M, N), device=dev)
+        Ak = torch.empty((M, K), dtype=torch.int16, device=dev)
+        Bk = torch.empty((N, K), dtype=torch.int16, device=dev)
+        if ta:
+            rl.rlstm_to_bf16_2d(None, Ak, A, K, M, M)
+        else:
+            rl.rlstm_to_bf16(Ak, A)
+        if tb:
+            rl.rlstm_to_bf16(Bk, B)
+        else:
+            rl.rlstm_to_bf16_2d(None, Bk, B, K, N, N)
+        lda, ldb = A.shape[1], B.shape[1]
+        res = {}
+        for tag, fn in (("fp32_operands", lambda: rl.rlstm_gemm_bf16(ta, tb, M, N, K, A, lda, B, ldb, C, N, None, sk16)),
+                        ("bf16_copies", lambda: rl.rlstm_gemm_bf16_mem(0, 1, M, N, K, Ak, K, Bk, K, C, N, None, sk16))):
+            for _ in range(args.warmup):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            res[tag] = e0.elapsed_time(e1) / args.steps
+        flop = 2.0 * M * N * K
+        bf16_kernels.append({"kernel": name, "M": M, "N": N, "K": K, "avg_ms": res["bf16_copies"], "tflops": flop / res["bf16_copies"] / 1e9,
+                             "frac_of_bf16_peak": flop / res["bf16_copies"] / 1e9 / PEAK_BF16_MFMA_TFLOPS,
+                             "fp32_operands_ms": res["fp32_operands"], "fp32_operands_tflops": flop / res["fp32_operands"] / 1e9})
+        log(bf16_kernels[-1])
+        del A, B, C, Ak, Bk
     dom = kernels[0]
     out = {"metric": "fp32 matrix products alone, TFLOP/s over all shapes", "value": total_flop / total_ms / 1e9, "unit": "TFLOP/s",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": total_ms, "higher_is_better": True,
@@ -280,7 +319,7 @@ def bench_gemm(args):
            "config": {"workload": "matrix products at the shapes of config 3 and of the paper's batch"},
            "roofline": {"kernel": dom["kernel"], "bound": "mfma", "achieved": dom["tflops"], "peak": PEAK_FP32_MFMA_TFLOPS,
                         "unit": "TFLOP/s", "frac": dom["tflops"] / PEAK_FP32_MFMA_TFLOPS, "traffic": None},
-           "kernels": kernels}
+           "kernels": kernels, "bf16_kernels": bf16_kernels}
     print(json.dumps(out), flush=True)
 
 
