@@ -1166,7 +1166,7 @@ int rlstm_gemm_bf16_mem(int trans_a, int trans_b, int M, int N, int K,
                         const uint16_t* A16, int lda, const uint16_t* B16, int ldb,
                         float* C, int ldc, const float* bias, int variant, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream) {
   if (!A16 || !B16 || !C) return RLSTM_ENULL;
-  if (variant != 0 && variant != 3) return RLSTM_EMODE;
+  if (variant != 0 && variant != 3 && variant != 4) return RLSTM_EMODE;
   if (M <= 0 || N <= 0 || K < 0) return RLSTM_EDIM;
   if (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N) || ldc < N) return RLSTM_EDIM;
   int resident_err = 0;

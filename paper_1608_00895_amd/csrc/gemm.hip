@@ -1190,6 +1190,152 @@ __global__ __launch_bounds__(256) void gemm_mfma_bf16_v2_kernel(GemmP p) {
   }  // items of this workgroup
 }
 
+// ---------------------------------------------------------------------------
+// The bf16-copy kernel for operands that are BOTH laid out along k (A16 [M,K], B16 stored [N,K]: the form every large
+// product of the stack is brought into).  Same 256 x 256 tile, 2 x 2 wavefronts of 4 x 4 MFMA tiles and k slabs of 32
+// as above; what differs is the way into LDS:
+//  * buffer loads that write LDS directly (16 bytes per lane, lane i of a wavefront's load lands at the load's LDS base
+//    + 16 i): no staging registers and no LDS store instructions, so a RING OF FOUR slabs fits (4 x 32 KB) and the
+//    loads of slab s+3 are issued while slab s is multiplied - three slabs (1.3 us of matrix work) of lookahead
+//    against one in the kernel above, whose staging registers hold no more and whose every slab waited for memory
+//    (matrix cores busy 0.45 of the time with LDS only 0.25 busy).
+//  * LDS rows are the slab's 32 k of one row, unpadded (64 bytes); the four 16-byte chunks of a row are permuted by
+//    ring_swizzle(row), applied on the GLOBAL side of the load (the lane that fills chunk position c of a row fetches
+//    chunk c ^ swizzle), so that the operand reads (one chunk of 8 or 16 neighbouring rows per group of lanes) touch
+//    every bank once.
+//  * operand fragments are read half a slab ahead of the MFMAs that use them; one barrier per slab, in its middle:
+//      first half of slab s   MFMAs on f0 (k 0..15); beside them f1 (k 16..31) is read and slab s+3 is requested
+//      wait for this wavefront's loads of slab s+1, barrier (every wavefront's have landed; everybody holds its f1,
+//                             so the slab before s is free to be overwritten)
+//      second half            MFMAs on f1; beside them f0 of slab s+1 is read
+// Out-of-range lanes (rows past M or N, k past the slice) read zeros through the buffer resource's range check, which
+// looks at the lane offset only: the slab's k offset is therefore added to the lane offset, not passed as the scalar
+// offset.
+constexpr int RING = 4;
+__device__ __forceinline__ int ring_swizzle(int row) { return (((row >> 1) ^ (row >> 3)) & 1) | (((row >> 2) & 1) << 1); }
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+__global__ __launch_bounds__(256) void gemm_bf16_ring_kernel(GemmP p) {
+  constexpr int WM = 4, WN = 4, TMB = 256, TNB = 256;
+  constexpr int OPB = TMB * BKH * 2;                                // bytes of one operand's slab (16 KB)
+  extern __shared__ __align__(16) float smem[];
+  unsigned char* ring = reinterpret_cast<unsigned char*>(smem);     // [RING][A slab | B slab]
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, lh = lane >> 5;
+  const int swz = ring_swizzle(l32);                                // the lane's rows are l32 plus multiples of 32
+
+  // this thread's four loads per operand and slab: load u of wavefront w fills LDS chunks [(4 u + w) 64, + 64)
+  unsigned rowoff[4];      // row of the chunk inside the tile
+  int klog[4];             // k offset (elements) of the chunk this lane fetches, inside a slab
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int pc = (u * 4 + wave) * 64 + lane;
+    const int row = pc >> 2;
+    rowoff[u] = (unsigned)row;
+    klog[u] = ((pc & 3) ^ ring_swizzle(row)) * 8;
+  }
+  // LDS byte offsets of the lane's operand fragments inside a slab: row * 64 + permuted chunk * 16
+  int fragoff[2][WM + WN];
+#pragma unroll
+  for (int h = 0; h < 2; ++h)
+#pragma unroll
+    for (int q = 0; q < WM + WN; ++q) {
+      const int row = q < WM ? wm * 32 * WM + q * 32 + l32 : wn * 32 * WN + (q - WM) * 32 + l32;
+      fragoff[h][q] = (q < WM ? 0 : OPB) + row * 64 + (((lh + 2 * h) ^ swz) << 4);
+    }
+
+  const int slots = (int)(gridDim.x >> 3);
+  for (int j = (int)(blockIdx.x >> 3); j < p.per_xcd; j += slots) {
+    const int item = (int)(blockIdx.x & 7) * p.per_xcd + j;
+    if (item >= p.work) break;
+    const int kz = item / p.tiles;
+    const int tile = item - kz * p.tiles;
+    const int tn = tile % p.tiles_n, tm = tile / p.tiles_n;
+    const int m0 = tm * TMB, n0 = tn * TNB;
+    const int kbeg = kz * p.kchunk;
+    const int kend = min(p.K, kbeg + p.kchunk);
+    const int klen = kend - kbeg;
+    const int nslab = (klen + BKH - 1) / BKH;
+
+    // rows past the tile's last valid one lie beyond num_records
+    const int rowsA = min(TMB, p.M - m0), rowsB = min(TNB, p.N - n0);
+    __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<unsigned short*>(p.A16 + (size_t)m0 * p.lda + kbeg), 0, (int)((size_t)rowsA * p.lda * 2 - (size_t)kbeg * 2), 0x00020000);
+    __amdgpu_buffer_rsrc_t rsrcB = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<unsigned short*>(p.B16 + (size_t)n0 * p.ldb + kbeg), 0, (int)((size_t)rowsB * p.ldb * 2 - (size_t)kbeg * 2), 0x00020000);
+    unsigned voffA[4], voffB[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      voffA[u] = rowoff[u] * (unsigned)p.lda * 2u + (unsigned)klog[u] * 2u;
+      voffB[u] = rowoff[u] * (unsigned)p.ldb * 2u + (unsigned)klog[u] * 2u;
+    }
+    // load u (0..3: A, 4..7: B) of slab t into ring stage t % RING
+    auto request = [&](int o, int t) {
+      const int u = o & 3;
+      const bool ink = t * BKH + klog[u] < klen;
+      unsigned char* dst = ring + (t & (RING - 1)) * 2 * OPB + (o < 4 ? 0 : OPB) + (u * 4 + wave) * 1024;
+      const unsigned off = ink ? (o < 4 ? voffA[u] : voffB[u]) + (unsigned)t * (BKH * 2) : kOutOfRange;
+      if (o < 4) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lds_ptr_t)dst, 16, (int)off, 0, 0, 0);
+      else       __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcB, (lds_ptr_t)dst, 16, (int)off, 0, 0, 0);
+    };
+
+    floatx16 acc[WM][WN];
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+      for (int jj = 0; jj < WN; ++jj)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][jj][r] = 0.f;
+
+#pragma unroll
+    for (int t = 0; t < RING - 1; ++t)
+#pragma unroll
+      for (int o = 0; o < 8; ++o) request(o, t);
+    // 24 loads in flight; the oldest 8 are slab 0
+    asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+
+    bf16x8 f0[WM + WN], f1[WM + WN];
+#pragma unroll
+    for (int q = 0; q < WM + WN; ++q) f0[q] = *reinterpret_cast<const bf16x8*>(ring + fragoff[0][q]);
+
+    for (int s = 0; s < nslab; ++s) {
+      const unsigned char* cur = ring + (s & (RING - 1)) * 2 * OPB;
+      const unsigned char* nxt = ring + ((s + 1) & (RING - 1)) * 2 * OPB;
+      // first half: f1 is read, then slab s + 3 is requested (its ring stage held slab s - 1, which nobody reads any more)
+#pragma unroll
+      for (int m = 0; m < WM * WN; ++m) {
+        if (m < WM + WN) f1[m] = *reinterpret_cast<const bf16x8*>(cur + fragoff[1][m]);
+        else request(m - (WM + WN), s + RING - 1);
+        __builtin_amdgcn_sched_barrier(0);
+        acc[m / WN][m % WN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0[m / WN], f0[WM + m % WN], acc[m / WN][m % WN], 0, 0, 0);
+      }
+      // slabs s+1, s+2, s+3 are in flight (8 loads each): at most 16 left means that slab s+1 has landed
+      asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+      // (after the last slab this reads a stage that holds zeros or the next tile's first slab in the making: the
+      // values are not used, the next tile reads its own f0 after its own barrier)
+#pragma unroll
+      for (int m = 0; m < WM * WN; ++m) {
+        if (m < WM + WN) f0[m] = *reinterpret_cast<const bf16x8*>(nxt + fragoff[0][m]);
+        __builtin_amdgcn_sched_barrier(0);
+        acc[m / WN][m % WN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1[m / WN], f1[WM + m % WN], acc[m / WN][m % WN], 0, 0, 0);
+      }
+    }
+
+    store_tiles<WM, WN>(p, kz, acc, m0 + wm * WM * 32, n0 + wn * WN * 32);
+    // The next tile counts its own loads: nothing of this tile may be in flight (the requests past the last slab
+    // returned zeros into ring stages; the stores above).  No barrier is needed: after the last slab's barrier no
+    // wavefront reads LDS, and a wavefront's loads fill its own parts of the ring only.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  }
+}
+
 template <int WM, int WN, bool TA, bool TB, bool M16>
 hipError_t launch_bf16_v2(hipStream_t stream, const GemmP& p, dim3 grid) {
   const size_t lds = (size_t)2 * 64 * (WM + WN) * LDK * sizeof(unsigned short);
@@ -1214,8 +1360,16 @@ hipError_t launch_bf16_v(hipStream_t stream, const GemmP& p, dim3 grid) {
   return hipGetLastError();
 }
 template <bool TA, bool TB>
-hipError_t launch_bf16(hipStream_t stream, const GemmP& p, dim3 grid, bool vec, bool big, bool pipelined, bool mem16) {
+hipError_t launch_bf16(hipStream_t stream, const GemmP& p, dim3 grid, bool vec, bool big, bool pipelined, bool mem16, bool ring) {
   // the pipelined form pays with 256 x 256 tiles only (128 x 128: 204 against 294 TFLOP/s at 1000 x 4000 x 96000)
+  if (pipelined && big && mem16 && !TA && TB && ring) {
+    const size_t lds = (size_t)RING * 2 * 256 * BKH * 2;
+    const void* fn = reinterpret_cast<const void*>(gemm_bf16_ring_kernel);
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(gemm_bf16_ring_kernel, grid, dim3(256), lds, stream, p);
+    return hipGetLastError();
+  }
   if (pipelined && big && mem16) return launch_bf16_v2<4, 4, TA, TB, true>(stream, p, grid);
   if (pipelined && big) return launch_bf16_v2<4, 4, TA, TB, false>(stream, p, grid);
   if (big) return vec ? launch_bf16_v<4, 4, TA, TB, true>(stream, p, grid) : launch_bf16_v<4, 4, TA, TB, false>(stream, p, grid);
@@ -1334,10 +1488,10 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
       const int slots = cus / 8;
       if (slots > 0 && slots < p.per_xcd) grid = dim3((unsigned)(8 * slots), 1, 1);
     }
-    if (!tA && !tB)      e = launch_bf16<false, false>(stream, p, grid, vec, big, pl, mem16);
-    else if (!tA && tB)  e = launch_bf16<false, true>(stream, p, grid, vec, big, pl, mem16);
-    else if (tA && !tB)  e = launch_bf16<true, false>(stream, p, grid, vec, big, pl, mem16);
-    else                 e = launch_bf16<true, true>(stream, p, grid, vec, big, pl, mem16);
+    if (!tA && !tB)      e = launch_bf16<false, false>(stream, p, grid, vec, big, pl, mem16, g.variant != 4);
+    else if (!tA && tB)  e = launch_bf16<false, true>(stream, p, grid, vec, big, pl, mem16, g.variant != 4);
+    else if (tA && !tB)  e = launch_bf16<true, false>(stream, p, grid, vec, big, pl, mem16, g.variant != 4);
+    else                 e = launch_bf16<true, true>(stream, p, grid, vec, big, pl, mem16, g.variant != 4);
   } else if (pipelined) {
     // A product that shares its CUs with the recurrent kernels keeps to the plain kernel: measured on the
     // 4 x 500 stack, the pipelined kernel beside them finishes its products sooner but slows every recurrent

@@ -456,10 +456,12 @@ def test_config4_network_on_short_sequences_against_oracle_samples():
     assert max(errs.values()) < TOL_BF16, errs
 
 
-def test_config4_full_size_single_sequences_against_oracle_samples():
-    """Config 4 at full size (T=1500, B=64, bf16 operands), in the two-stream persistent launch
-    configuration: for two sequences the oracle ran alone through the whole stack, sampled entries
-    of y_top and dx; plus the padding properties for every sequence."""
+def test_config4_full_size_against_oracle_samples():
+    """Config 4 at full size (T=1500, B=64, bf16 operands), in the two-stream persistent launch configuration, against
+    values the oracle wrote (tests/golden/make_config4_golden.py ran the minibatch in groups of 8 sequences and added
+    the groups' weight gradients): random samples of y_top and dx from every sequence, of dW and dR of every layer and
+    direction, every db whole, whole first / last frames, every sequence's last valid and first padded frame, and the
+    rows / columns of the last units; all at the 2e-2 of the bf16-operand variant."""
     g = _golden("config4_oracle_samples.npz")
     wl = synth.config4()
     assert np.array_equal(g["full_seq_lens"], wl.seq_lens)
@@ -467,16 +469,27 @@ def test_config4_full_size_single_sequences_against_oracle_samples():
     run.step()
     torch.cuda.synchronize()
     assert rl.rlstm_last_timeout(run.ws) == 0
-    for n in g["full_picks"]:
-        n = int(n)
-        ln = int(wl.seq_lens[n])
-        y = run.y_top[:ln, n, :].cpu().numpy()
-        dx = run.dx[:ln, n, :].cpu().numpy()
-        for name, arr in (("y", y), ("dx", dx)):
-            key = f"full_{name}_seq{n}"
-            err = np.abs(arr.reshape(-1)[g[key + "_idx"]].astype(np.float64) - g[key + "_val"]).max() / float(g[key + "_max"])
-            print(f"config4 full, sequence {n} (len {ln}): {name} sampled rel err {err:.2e}", flush=True)
-            assert err < TOL_BF16, (name, n, err)
+    errs = {}
+
+    def check(name, t):
+        key = "full_" + name
+        idx = torch.from_numpy(g[key + "_idx"]).to(gh.DEV)
+        got = t.reshape(-1)[idx].cpu().numpy().astype(np.float64)
+        errs[name] = float(np.abs(got - g[key + "_val"]).max() / float(g[key + "_max"]))
+
+    check("y", run.y_top)
+    check("dx", run.dx)
+    k = 0
+    for l in range(wl.L):
+        for d in range(2):
+            for nm in ("dW", "dR"):
+                check(f"{nm}_{l}_{d}", run.grads[k])
+                k += 1
+            k += 1
+    worst = max(errs, key=lambda n: errs[n])
+    print(f"config4 full size: y {errs['y']:.2e}, dx {errs['dx']:.2e}, worst weight gradient {worst} {errs[worst]:.2e}", flush=True)
+    assert max(errs.values()) < TOL_BF16, errs
+    gh.check_structured_samples(g, "full_", run.y_top, run.dx, run.grads, wl.seq_lens, wl.L, TOL_BF16, TOL_BF16, "config4")
     lens = torch.from_numpy(wl.seq_lens.astype(np.int64)).to(gh.DEV)
     pad = torch.arange(wl.T, device=gh.DEV)[:, None] >= lens[None, :]
     assert bool((run.y_top[pad] == 0).all()) and bool((run.dx[pad] == 0).all())
