@@ -1198,7 +1198,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_bf16_v2_kernel(GemmP p) {
 //    + 16 i): no staging registers and no LDS store instructions, so a RING OF FOUR slabs fits (4 x 32 KB) and the
 //    loads of slab s+3 are issued while slab s is multiplied - three slabs (1.3 us of matrix work) of lookahead
 //    against one in the kernel above, whose staging registers hold no more and whose every slab waited for memory
-//    (matrix cores busy 0.45 of the time with LDS only 0.25 busy).
+//    (matrix cores busy 0.45 of the time with LDS only 0.25 busy; here 0.58).
 //  * LDS rows are the slab's 32 k of one row, unpadded (64 bytes); the four 16-byte chunks of a row are permuted by
 //    ring_swizzle(row), applied on the GLOBAL side of the load (the lane that fills chunk position c of a row fetches
 //    chunk c ^ swizzle), so that the operand reads (one chunk of 8 or 16 neighbouring rows per group of lanes) touch
@@ -1211,7 +1211,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_bf16_v2_kernel(GemmP p) {
 // Out-of-range lanes (rows past M or N, k past the slice) read zeros through the buffer resource's range check, which
 // looks at the lane offset only: the slab's k offset is therefore added to the lane offset, not passed as the scalar
 // offset.
-constexpr int RING = 4;
+constexpr int RING = 4;      // slabs in the ring (five, all 160 KB of LDS, measured no faster)
 __device__ __forceinline__ int ring_swizzle(int row) { return (((row >> 1) ^ (row >> 3)) & 1) | (((row >> 2) & 1) << 1); }
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
@@ -1273,10 +1273,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_ring_kernel(GemmP p) {
       voffB[u] = rowoff[u] * (unsigned)p.ldb * 2u + (unsigned)klog[u] * 2u;
     }
     // load u (0..3: A, 4..7: B) of slab t into ring stage t % RING
-    auto request = [&](int o, int t) {
+    auto request = [&](int o, int t, int stage) {
       const int u = o & 3;
       const bool ink = t * BKH + klog[u] < klen;
-      unsigned char* dst = ring + (t & (RING - 1)) * 2 * OPB + (o < 4 ? 0 : OPB) + (u * 4 + wave) * 1024;
+      unsigned char* dst = ring + stage * 2 * OPB + (o < 4 ? 0 : OPB) + (u * 4 + wave) * 1024;
       const unsigned off = ink ? (o < 4 ? voffA[u] : voffB[u]) + (unsigned)t * (BKH * 2) : kOutOfRange;
       if (o < 4) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lds_ptr_t)dst, 16, (int)off, 0, 0, 0);
       else       __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcB, (lds_ptr_t)dst, 16, (int)off, 0, 0, 0);
@@ -1293,9 +1293,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_ring_kernel(GemmP p) {
 #pragma unroll
     for (int t = 0; t < RING - 1; ++t)
 #pragma unroll
-      for (int o = 0; o < 8; ++o) request(o, t);
-    // 24 loads in flight; the oldest 8 are slab 0
-    asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+      for (int o = 0; o < 8; ++o) request(o, t, t);
+    // 8 (RING - 1) loads in flight; the oldest 8 are slab 0
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(8 * (RING - 2)) : "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 
@@ -1303,19 +1303,22 @@ __global__ __launch_bounds__(256) void gemm_bf16_ring_kernel(GemmP p) {
 #pragma unroll
     for (int q = 0; q < WM + WN; ++q) f0[q] = *reinterpret_cast<const bf16x8*>(ring + fragoff[0][q]);
 
+    int st_cur = 0;                                                 // ring stage of slab s
     for (int s = 0; s < nslab; ++s) {
-      const unsigned char* cur = ring + (s & (RING - 1)) * 2 * OPB;
-      const unsigned char* nxt = ring + ((s + 1) & (RING - 1)) * 2 * OPB;
+      const int st_nxt = st_cur + 1 == RING ? 0 : st_cur + 1;
+      const int st_req = st_cur == 0 ? RING - 1 : st_cur - 1;       // stage of slab s - 1 = of slab s + RING - 1
+      const unsigned char* cur = ring + st_cur * 2 * OPB;
+      const unsigned char* nxt = ring + st_nxt * 2 * OPB;
       // first half: f1 is read, then slab s + 3 is requested (its ring stage held slab s - 1, which nobody reads any more)
 #pragma unroll
       for (int m = 0; m < WM * WN; ++m) {
         if (m < WM + WN) f1[m] = *reinterpret_cast<const bf16x8*>(cur + fragoff[1][m]);
-        else request(m - (WM + WN), s + RING - 1);
+        else request(m - (WM + WN), s + RING - 1, st_req);
         __builtin_amdgcn_sched_barrier(0);
         acc[m / WN][m % WN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0[m / WN], f0[WM + m % WN], acc[m / WN][m % WN], 0, 0, 0);
       }
-      // slabs s+1, s+2, s+3 are in flight (8 loads each): at most 16 left means that slab s+1 has landed
-      asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
+      // slabs s+1 .. s+RING-1 are in flight (8 loads each): at most 8 (RING - 2) left means that slab s+1 has landed
+      asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(8 * (RING - 2)) : "memory");
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
       // (after the last slab this reads a stage that holds zeros or the next tile's first slab in the making: the
@@ -1326,6 +1329,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_ring_kernel(GemmP p) {
         __builtin_amdgcn_sched_barrier(0);
         acc[m / WN][m % WN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1[m / WN], f1[WM + m % WN], acc[m / WN][m % WN], 0, 0, 0);
       }
+      st_cur = st_nxt;
     }
 
     store_tiles<WM, WN>(p, kz, acc, m0 + wm * WM * 32, n0 + wn * WN * 32);
