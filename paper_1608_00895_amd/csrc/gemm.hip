@@ -40,6 +40,7 @@ struct GemmP {
   const float* bias;
   int accumulate;
   int tiles_n;
+  int band_m;          // tile rows per band of the tile numbering (see tile_coords)
   int tiles;           // output tiles (tiles_m * tiles_n)
   int work;            // tiles * split-K slices: work items of the launch
   int per_xcd;         // ceil(work / 8); the grid is 8 * per_xcd workgroups
@@ -61,6 +62,21 @@ __device__ __forceinline__ bool work_item(const GemmP& p, int* tile, int* kz) {
   *kz = item / p.tiles;
   *tile = item - *kz * p.tiles;
   return true;
+}
+
+// Tile index -> tile coordinates.  Tiles are numbered in BANDS of band_m tile rows, column by column inside a band, so
+// that the 32 tiles an XCD's CUs work on at a time form a block of band_m x (32 / band_m) tiles: they share band_m
+// panels of A, which stay in the XCD's L2 for the whole band, and each panel of B is fetched once per band.  Numbered
+// row by row, 32 tiles of a wide product span two whole tile rows and all of B is fetched once per two rows: counted
+// at config 3, bands of 4 rows fetch 25 % less for the projections and 28 % less for the weight gradients.  band_m
+// is 4 where there are 8 or more tile columns, otherwise as many rows as make 32 tiles (which is the row-by-row order).
+__device__ __forceinline__ void tile_coords(const GemmP& p, int tile, int tiles_m, int* tm, int* tn) {
+  const int per_band = p.band_m * p.tiles_n;
+  const int band = tile / per_band;
+  const int local = tile - band * per_band;
+  const int hb = min(p.band_m, tiles_m - band * p.band_m);
+  *tn = local / hb;
+  *tm = band * p.band_m + (local - *tn * hb);
 }
 
 // Epilogue of the MFMA kernels with 32 x 32 accumulator tiles: register r of lane l holds
@@ -188,7 +204,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_f32_kernel(GemmP p) {
 
   int tile, kz;
   if (!work_item(p, &tile, &kz)) return;
-  const int tn = tile % p.tiles_n, tm = tile / p.tiles_n;
+  int tm, tn;
+  tile_coords(p, tile, p.tiles / p.tiles_n, &tm, &tn);
   const int m0 = tm * TM, n0 = tn * TN;
   const int kbeg = kz * p.kchunk;
   const int kend = min(p.K, kbeg + p.kchunk);
@@ -277,7 +294,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_f32_short_kernel(GemmP p) {
 
   int tile, kz;
   if (!work_item(p, &tile, &kz)) return;
-  const int tn = tile % p.tiles_n, tm = tile / p.tiles_n;
+  int tm, tn;
+  tile_coords(p, tile, p.tiles / p.tiles_n, &tm, &tn);
   const int m0 = tm * TM, n0 = tn * TN;
   const int kbeg = kz * p.kchunk;
   const int kend = min(p.K, kbeg + p.kchunk);
@@ -473,7 +491,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_f32_v2_kernel(GemmP p) {
 
   int tile, kz;
   if (!work_item(p, &tile, &kz)) return;
-  const int tn = tile % p.tiles_n, tm = tile / p.tiles_n;
+  int tm, tn;
+  tile_coords(p, tile, p.tiles / p.tiles_n, &tm, &tn);
   const int m0 = tm * TM, n0 = tn * TN;
   const int kbeg = kz * p.kchunk;
   const int kend = min(p.K, kbeg + p.kchunk);
@@ -652,7 +671,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_bf16_kernel(GemmP p) {
 
   int tile, kz;
   if (!work_item(p, &tile, &kz)) return;
-  const int tn = tile % p.tiles_n, tm = tile / p.tiles_n;
+  int tm, tn;
+  tile_coords(p, tile, p.tiles / p.tiles_n, &tm, &tn);
   const int m0 = tm * TMB, n0 = tn * TNB;
   const int kbeg = kz * p.kchunk;
   const int kend = min(p.K, kbeg + p.kchunk);
@@ -1110,7 +1130,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_bf16_v2_kernel(GemmP p) {
   if (item >= p.work) break;
   const int kz = item / p.tiles;
   const int tile = item - kz * p.tiles;
-  const int tn = tile % p.tiles_n, tm = tile / p.tiles_n;
+  int tm, tn;
+  tile_coords(p, tile, p.tiles / p.tiles_n, &tm, &tn);
   const int m0 = tm * TMB, n0 = tn * TNB;
   const int kbeg = kz * p.kchunk;
   const int kend = min(p.K, kbeg + p.kchunk);
@@ -1253,7 +1274,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_ring_kernel(GemmP p) {
     if (item >= p.work) break;
     const int kz = item / p.tiles;
     const int tile = item - kz * p.tiles;
-    const int tn = tile % p.tiles_n, tm = tile / p.tiles_n;
+    int tm, tn;
+    tile_coords(p, tile, p.tiles / p.tiles_n, &tm, &tn);
     const int m0 = tm * TMB, n0 = tn * TNB;
     const int kbeg = kz * p.kchunk;
     const int kend = min(p.K, kbeg + p.kchunk);
@@ -1406,6 +1428,7 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
                    (big_tiles >= 128 || (g.splitk_ws && g.K >= 16 * 1024 && big_tiles >= 48));
   const int tile_m = big ? 256 : TM, tile_n = big ? 256 : TN;
   p.tiles_n = (g.N + tile_n - 1) / tile_n;
+  p.band_m = p.tiles_n >= 8 ? 4 : 32 / p.tiles_n;
   p.kchunk = g.K; p.partial = nullptr;
 
   if (g.naive) {
