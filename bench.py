@@ -596,6 +596,8 @@ def main():
         e = {"kernel": rl.PROFILE_KINDS[kind], "launches_per_step": d["launches"] / hook_steps,
              "avg_ms": d["ms"] / d["launches"], "ms_per_step": d["ms"] / hook_steps,
              "tflops": d["flop"] / (d["ms"] * 1e-3) / 1e12}
+        # fraction of the matrix cores' peak for the operand type (the products' MFMA utilisation by throughput)
+        e["frac_of_mfma_peak"] = e["tflops"] / (PEAK_FP32_MFMA_TFLOPS if wl.operand_dtype == 0 else PEAK_BF16_MFMA_TFLOPS)
         if kind in (1, 2):
             # a pass over the T steps may be cut into several launches
             e["steps_per_launch"] = d["rsteps"] / d["launches"]
