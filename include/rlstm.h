@@ -139,7 +139,8 @@ RLSTM_API size_t rlstm_reserve_bytes(const rlstm_desc* desc);
 /* Bytes of scratch for lstm_fwd / lstm_bwd; 0 if the descriptor is invalid. */
 RLSTM_API size_t rlstm_workspace_bytes(const rlstm_desc* desc);
 /* Same for blstm_stack_fwd_bwd (reserve: per layer and direction the gate
- * buffer [T,B,4H] and cell buffer [T,B,H], plus the hidden layers' outputs). */
+ * buffer [T,B,4H] and cell buffer [T,B,H], plus the outputs [T,B,2H] of all layers
+ * but the top one, whose output is the caller's y_top). */
 RLSTM_API size_t rblstm_reserve_bytes(const rblstm_desc* desc);
 RLSTM_API size_t rblstm_workspace_bytes(const rblstm_desc* desc);
 

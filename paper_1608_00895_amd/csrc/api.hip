@@ -547,7 +547,9 @@ size_t rlstm_workspace_bytes(const rlstm_desc* d) {
 
 size_t rblstm_reserve_bytes(const rblstm_desc* d) {
   if (check_stack_desc(d) != RLSTM_OK) return 0;
-  return stack_layout(d).per_layer * (size_t)d->L * sizeof(float);
+  // the top layer's output is the caller's y_top: its block ends before the y slot (the last one of a block)
+  const StackLayout lay = stack_layout(d);
+  return (lay.per_layer * (size_t)(d->L - 1) + lay.y) * sizeof(float);
 }
 
 size_t rblstm_workspace_bytes(const rblstm_desc* d) {
