@@ -278,7 +278,9 @@ RLSTM_API int rlstm_gemm_bf16(int trans_a, int trans_b, int M, int N, int K,
  *   rlstm_gemm_bf16 on fp32 operands that round to these bf16 values.  RLSTM_EMODE when the shape does not take the
  *   kernel that reads bf16 from memory (it needs 256 x 256 tiles to fill the chip, whole 16-byte aligned groups of 8
  *   values along the operands' contiguous dimensions and K a multiple of 8).  variant 0: one workgroup per CU that
- *   walks through its share of the tiles; 3: one workgroup per tile (for measurement).
+ *   walks through its share of the tiles; operands that are both laid out along k (trans_a == 0, trans_b != 0) go
+ *   through a ring of LDS slabs filled by buffer loads that write LDS directly.  For measurement: 3, one workgroup
+ *   per tile; 4, slabs staged through registers for every layout.  Other values: RLSTM_EMODE.
  */
 RLSTM_API int rlstm_to_bf16(uint16_t* dst, const float* src, size_t n, void* hip_stream);
 RLSTM_API int rlstm_to_bf16_2d(uint16_t* dst, uint16_t* dst_t, const float* src, int R, int C, int ld, void* hip_stream);

@@ -364,6 +364,14 @@ def test_gemm_bf16_operands_read_as_bf16_from_memory(case):
             rl.rlstm_gemm_bf16_mem(ta ^ fa, tb ^ fb, M, N, K, a16, a16.shape[1], b16, b16.shape[1], C, N, biasd, ws)
             torch.cuda.synchronize()
             assert np.array_equal(C.cpu().numpy(), ref), (case, fa, fb)
+    # the other forms of the kernel give the same bits: one workgroup per tile instead of one per CU walking through
+    # its tiles (3), slabs staged through registers instead of the ring of LDS slabs filled by direct loads (4)
+    for variant in (3, 4):
+        C = torch.full((M, N), float("nan"), device=gh.DEV)
+        rl.rlstm_gemm_bf16_mem(ta ^ 1, tb ^ 1, M, N, K, A16t, A16t.shape[1], B16t, B16t.shape[1], C, N, biasd, ws, variant=variant)
+        torch.cuda.synchronize()
+        assert np.array_equal(C.cpu().numpy(), ref), (case, variant)
+    assert rl.rlstm_gemm_bf16_mem(0, 0, M, N, K, A16, A.shape[1], B16, Bm.shape[1], C, N, None, None, check=False, variant=1) == -3
     # a shape without the tiles for that kernel, or a K that is no multiple of 8, is refused, not silently rerouted
     assert rl.rlstm_gemm_bf16_mem(0, 0, 64, 64, 64, A16, 64, B16, 64, C, N, None, None, check=False) == -3
     if not ta and not tb:
