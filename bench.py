@@ -86,6 +86,41 @@ def recorded_traffic(workload, kernel, version, plan=None):
     return v, f"{rec['source']} (commit {rec.get('commit')}, {rec.get('date')})"
 
 
+def time_steps(step, steps, rl, torch):
+    """The timing protocol of every workload: `steps` calls between device synchronisations with the library's event
+    hooks off, each call also bracketed by a pair of events on the current stream (median / minimum); then a loop of at
+    most 5 calls with the hooks on, from which the per-kernel figures come.  Returns a dict."""
+    rl.rlstm_profile_enable(False)
+    rl.rlstm_profile_read()
+    step_events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    clocks = clock_state()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for e0, e1 in step_events:
+        e0.record()
+        step()
+        e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    step_ms = sorted(e0.elapsed_time(e1) for e0, e1 in step_events)
+    hook_steps = max(1, min(steps, 5))
+    rl.rlstm_profile_enable(True)
+    torch.cuda.synchronize()
+    th0 = time.perf_counter()
+    for _ in range(hook_steps):
+        step()
+    torch.cuda.synchronize()
+    th1 = time.perf_counter()
+    rl.rlstm_profile_enable(False)
+    prof = rl.rlstm_profile_read(1 << 16)
+    return {"ms_per_step": (t1 - t0) * 1e3 / steps, "ms_per_step_median": step_ms[len(step_ms) // 2],
+            "ms_per_step_min": step_ms[0], "ms_per_step_with_timing_hooks": (th1 - th0) * 1e3 / hook_steps,
+            "hook_steps": hook_steps, "prof": prof, "clock_state": clocks,
+            "timing": "value and ms_per_step: K steps between device synchronisations, the library's event hooks off; "
+                      "median / min: per-step event pairs in that same loop; the per-kernel figures come from a separate "
+                      f"loop of {hook_steps} steps with the hooks on (ms_per_step_with_timing_hooks)"}
+
+
 def rec_bytes(kind, wl, steps):
     """Algorithmic HBM bytes of `steps` recurrent steps (both directions), fp32: forward reads Z and writes
     gates, y, c; backward reads gates, c (twice), dy and writes dz; the recurrent matrix is read once per launch."""
@@ -161,23 +196,15 @@ def bench_config5(args):
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    rl.rlstm_profile_read()
-    rl.rlstm_profile_enable(True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    rl.rlstm_profile_enable(False)
-    prof = rl.rlstm_profile_read(1 << 16)
+    tm = time_steps(step, args.steps, rl, torch)
+    prof, hook_steps = tm["prof"], tm["hook_steps"]
     if args.calibration_copy:
         n = 1 << 28
         src = torch.ones(n, device=dev)
         dst = torch.empty(n, device=dev)
         rl.rlstm_copy_f32(dst, src, n)
         torch.cuda.synchronize()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = tm["ms_per_step"]
     by_kind = {}
     for kind, layer, ndir, ms, nsteps, flop in prof:
         d = by_kind.setdefault(kind, {"ms": 0.0, "launches": 0, "flop": 0.0, "rsteps": 0})
@@ -189,8 +216,8 @@ def bench_config5(args):
     valid_frac = wl.pixels / float(wl.Hh * wl.Ww * wl.B)
     for kind, d in sorted(by_kind.items()):
         flop = d["flop"] * (valid_frac if kind in (1, 2) else 1.0)
-        e = {"kernel": names[kind], "launches_per_step": d["launches"] / args.steps, "avg_ms": d["ms"] / d["launches"],
-             "ms_per_step": d["ms"] / args.steps, "tflops": flop / (d["ms"] * 1e-3) / 1e12}
+        e = {"kernel": names[kind], "launches_per_step": d["launches"] / hook_steps, "avg_ms": d["ms"] / d["launches"],
+             "ms_per_step": d["ms"] / hook_steps, "tflops": flop / (d["ms"] * 1e-3) / 1e12}
         if kind in (1, 2):
             e["diagonals_per_launch"] = d["rsteps"] / d["launches"]
             e["diagonal_us"] = 1e3 * d["ms"] / d["rsteps"]
@@ -208,6 +235,9 @@ def bench_config5(args):
                         "the whole chip's fp32 MFMA peak with 2 * 2H * 5H FLOP per valid pixel and direction"}
     out = {"metric": "MDLSTM train pixels/sec (fwd+bwd), 4 scan directions", "value": wl.pixels / (ms_per_step * 1e-3),
            "unit": "pixels/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+           "ms_per_step_median": tm["ms_per_step_median"], "ms_per_step_min": tm["ms_per_step_min"],
+           "ms_per_step_with_timing_hooks": tm["ms_per_step_with_timing_hooks"], "timing": tm["timing"],
+           "clock_state": tm["clock_state"],
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": wl.name, "height": wl.Hh, "padded_width": wl.Ww, "images": wl.B,
                       "units_per_direction": wl.H, "valid_pixels": wl.pixels,
@@ -355,27 +385,26 @@ def bench_stream(args):
         step()
     torch.cuda.synchronize()
     assert rl.rlstm_last_timeout(ws) == 0
-    rl.rlstm_profile_read()
-    rl.rlstm_profile_enable(True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    rl.rlstm_profile_enable(False)
-    prof = rl.rlstm_profile_read(1 << 16)
+    tm = time_steps(step, args.steps, rl, torch)
+    prof, hook_steps = tm["prof"], tm["hook_steps"]
     assert rl.rlstm_last_timeout(ws) == 0
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    if args.calibration_copy:
+        n = 1 << 28
+        src = torch.ones(n, device=dev)
+        dst = torch.empty(n, device=dev)
+        rl.rlstm_copy_f32(dst, src, n)
+        torch.cuda.synchronize()
+    ms_per_step = tm["ms_per_step"]
     by_kind = {}
     for kind, layer, ndir, ms, nsteps, flop in prof:
         d = by_kind.setdefault(kind, {"ms": 0.0, "launches": 0, "flop": 0.0, "rsteps": 0})
         d["ms"] += ms; d["launches"] += 1; d["flop"] += flop; d["rsteps"] += nsteps
     kernels = []
     for kind, d in sorted(by_kind.items()):
-        e = {"kernel": rl.PROFILE_KINDS[kind], "launches_per_step": d["launches"] / args.steps,
-             "avg_ms": d["ms"] / d["launches"], "ms_per_step": d["ms"] / args.steps,
+        e = {"kernel": rl.PROFILE_KINDS[kind], "launches_per_step": d["launches"] / hook_steps,
+             "avg_ms": d["ms"] / d["launches"], "ms_per_step": d["ms"] / hook_steps,
              "tflops": d["flop"] / (d["ms"] * 1e-3) / 1e12}
+        e["frac_of_mfma_peak"] = e["tflops"] / PEAK_FP32_MFMA_TFLOPS
         if kind in (1, 2):
             e["steps_per_launch"] = d["rsteps"] / d["launches"]
             e["step_us"] = 1e3 * d["ms"] / d["rsteps"]
@@ -395,7 +424,10 @@ def bench_stream(args):
     slots = wl.S * wl.Tc * wl.B
     out = {"metric": "LSTM streaming train frames/sec (segments chained by final states, truncated BPTT)",
            "value": wl.frames / (ms_per_step * 1e-3), "unit": "frames/s", "n_gpus": 1, "steps": args.steps,
-           "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+           "warmup": args.warmup, "ms_per_step": ms_per_step,
+           "ms_per_step_median": tm["ms_per_step_median"], "ms_per_step_min": tm["ms_per_step_min"],
+           "ms_per_step_with_timing_hooks": tm["ms_per_step_with_timing_hooks"], "timing": tm["timing"],
+           "clock_state": tm["clock_state"], "higher_is_better": True, "scaling": "weak",
            "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": wl.name, "layers": wl.L, "units": wl.H, "sequences": wl.B, "segments": wl.S,
                       "segment_frames": wl.Tc, "valid_frames": wl.frames, "padded_slots": slots,
