@@ -246,7 +246,7 @@ def bench_config5(args):
     if not args.no_cpu_baseline:
         from threadpoolctl import threadpool_info
         from oracle import mdlstm4_backward, mdlstm4_forward
-        wc = 24                                    # the oracle on the first 24 columns of every image
+        wc = 400                                   # the oracle on the first 400 columns of every image (about 10 s)
         p64 = [tuple(a.astype(np.float64) for a in p) for p in wl.params]
         wcrop = np.minimum(wl.widths, wc)
         t0 = time.perf_counter()
@@ -442,7 +442,7 @@ def bench_stream(args):
     if not args.no_cpu_baseline:
         from threadpoolctl import threadpool_info
         from oracle import lstm_stream_forward_backward
-        Tc, S2 = 100, 2                            # the oracle on the first 2 segments of 100 frames
+        Tc, S2 = wl.Tc, 4                          # the oracle on the first 4 of the 6 segments (about 10 s)
         p64 = [tuple(a.astype(np.float64) for a in p) for p in wl.params]
         lens = np.minimum(wl.seq_lens, Tc * S2)
         t0 = time.perf_counter()
