@@ -376,10 +376,11 @@ def bench_stream(args):
     state = torch.zeros((wl.L, 2, wl.B, wl.H), device=dev)
     reserve = torch.empty(rl.rlstm_stream_reserve_bytes(desc), dtype=torch.uint8, device=dev)
     ws = torch.empty(rl.rlstm_stream_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+    stream_b = None if args.one_stream else torch.cuda.Stream()      # takes the weight gradients
 
     def step():
         state.zero_()
-        rl.lstm_stream_fwd_bwd(desc, x, params, sl, G, y, grads, None, state, reserve, ws)
+        rl.lstm_stream_fwd_bwd(desc, x, params, sl, G, y, grads, None, state, reserve, ws, stream_b=stream_b)
 
     for _ in range(args.warmup):
         step()

@@ -418,6 +418,11 @@ RLSTM_API int rlstm_chunk_gather(const float* x, int T, int B, int D, int ldx, c
  *   state [L,2,B,H] in/out, may be null: per layer h then c; in: state before the first segment
  *         (null: zeros); out: state after the last segment
  *   reserve: rlstm_stream_reserve_bytes(); workspace: rlstm_stream_workspace_bytes(); all DEVICE.
+ *   hip_stream carries the dependent chain; hip_stream_b, if not null and different, takes the weight gradients
+ *   of every (segment, layer), which then run beside the layers below (ordering by events created and destroyed
+ *   inside the call; when the call returns hip_stream waits for everything placed on hip_stream_b).  The results
+ *   do not depend on it up to the order of sums inside the products (another product kernel runs beside the
+ *   recurrent kernels).
  * Engines and errors as for lstm_fwd / lstm_bwd (the shape seen by the engine is T = Tc).
  */
 typedef struct rlstm_stream_desc {
@@ -430,7 +435,8 @@ RLSTM_API size_t rlstm_stream_reserve_bytes(const rlstm_stream_desc* desc);
 RLSTM_API size_t rlstm_stream_workspace_bytes(const rlstm_stream_desc* desc);
 RLSTM_API int lstm_stream_fwd_bwd(const rlstm_stream_desc* desc, const float* x, const float* const* params,
                                   const int32_t* seq_lens, const float* dy_top, float* y_top, float* const* grads,
-                                  float* dx, float* state, void* reserve, void* workspace, void* hip_stream);
+                                  float* dx, float* state, void* reserve, void* workspace, void* hip_stream,
+                                  void* hip_stream_b);
 
 /*
  * softmax_ce_fwd_bwd - the frame-wise output layer of the acoustic model (Sec. 6: a softmax

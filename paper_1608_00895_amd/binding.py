@@ -108,7 +108,7 @@ def lib() -> ctypes.CDLL:
             getattr(L, name).argtypes = [ctypes.POINTER(rlstm_stream_desc)]
         L.lstm_stream_fwd_bwd.restype = ip
         L.lstm_stream_fwd_bwd.argtypes = [ctypes.POINTER(rlstm_stream_desc), vp, ctypes.POINTER(vp), vp, vp, vp,
-                                          ctypes.POINTER(vp), vp, vp, vp, vp, vp]
+                                          ctypes.POINTER(vp), vp, vp, vp, vp, vp, vp]
         L.rlstm_ce_workspace_bytes.restype = ctypes.c_size_t
         L.rlstm_ce_workspace_bytes.argtypes = [ip, ip, ip, ip]
         L.softmax_ce_fwd_bwd.restype = ip
@@ -298,11 +298,12 @@ def rlstm_stream_workspace_bytes(desc) -> int:
 
 
 def lstm_stream_fwd_bwd(desc, x, params, seq_lens, dy_top, y_top, grads, dx, state, reserve, workspace, stream=None,
-                        check=True) -> int:
+                        check=True, stream_b=None) -> int:
     """params / grads: flat sequences of 3*L tensors (W, R, b per layer); state: [L,2,B,H] tensor or None."""
     pa, ga = _ptr_array(params), _ptr_array(grads)
     rc = lib().lstm_stream_fwd_bwd(ctypes.byref(desc), _ptr(x), pa, _ptr(seq_lens), _ptr(dy_top), _ptr(y_top), ga,
-                                   _ptr(dx), _ptr(state), _ptr(reserve), _ptr(workspace), _stream(stream))
+                                   _ptr(dx), _ptr(state), _ptr(reserve), _ptr(workspace), _stream(stream),
+                                   _stream(stream_b) if stream_b is not None else None)
     if check and rc != 0:
         raise RlstmError(rc, "lstm_stream_fwd_bwd")
     return rc

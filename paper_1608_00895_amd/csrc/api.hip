@@ -952,7 +952,7 @@ size_t rlstm_stream_workspace_bytes(const rlstm_stream_desc* d) {
 
 int lstm_stream_fwd_bwd(const rlstm_stream_desc* d, const float* x, const float* const* params, const int32_t* seq_lens,
                         const float* dy_top, float* y_top, float* const* grads, float* dx, float* state,
-                        void* reserve, void* workspace, void* hip_stream) {
+                        void* reserve, void* workspace, void* hip_stream, void* hip_stream_b) {
   int rc = check_stream_desc(d);
   if (rc != RLSTM_OK) return rc;
   if (!x || !params || !seq_lens || !dy_top || !y_top || !grads || !reserve || !workspace) return RLSTM_ENULL;
@@ -963,6 +963,15 @@ int lstm_stream_fwd_bwd(const rlstm_stream_desc* d, const float* x, const float*
   if (eng < 0) return eng;
   const bool persistent = eng == RLSTM_ENGINE_PERSISTENT;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  // Stream b, if given and different, takes the weight gradients of a (segment, layer): nothing of the segment waits
+  // for them, so they run beside the passes back through time of the layers below; the next segment's forward pass
+  // of a layer waits for them before it overwrites what they read.  Only where a product workgroup fits on a CU
+  // beside a workgroup of the persistent kernels (overlap_mode, as for the bidirectional stack).
+  hipStream_t sw = hip_stream_b ? static_cast<hipStream_t>(hip_stream_b) : st;
+  if (sw != st && overlap_mode(rs, d->operand_dtype, persistent, true, 2) != kShare) sw = st;
+  const bool two = sw != st;
+  EventList evs;
+  std::vector<hipEvent_t> wdone(L, nullptr);   // weight gradients of the previous segment's layer l are done
   const StreamLayout lay = stream_layout(d);
   float* res = static_cast<float*>(reserve);
   char* ws = static_cast<char*>(workspace);
@@ -991,6 +1000,12 @@ int lstm_stream_fwd_bwd(const rlstm_stream_desc* d, const float* x, const float*
     for (int l = 0; l < L; ++l) {
       float* base = res + (size_t)l * lay.per_layer;
       float* yl = (l == L - 1) ? y_top + (size_t)s * tb * H : base + lay.y;
+      if (two) {
+        // this layer's gates and output are about to be overwritten: the previous segment's weight gradients of this
+        // layer read them (d a, y), those of the layer above read y as their input
+        if (wdone[l]) RLSTM_TRY(hipStreamWaitEvent(st, wdone[l], 0));
+        if (l + 1 < L && wdone[l + 1]) RLSTM_TRY(hipStreamWaitEvent(st, wdone[l + 1], 0));
+      }
       GemmCall g;
       g.M = Tc * B; g.N = 4 * H; g.K = din;
       g.A = in; g.lda = din; g.B = params[3 * l + 0]; g.ldb = 4 * H; g.C = base + lay.zg; g.ldc = 4 * H;
@@ -1022,11 +1037,19 @@ int lstm_stream_fwd_bwd(const rlstm_stream_desc* d, const float* x, const float*
         RLSTM_TRY(rec_backward(st, rs, &dir, slens, recws, flag, persistent, &resident_err, 0, Tc));
       }
       RLSTM_TRY(accumulate(st, grads[3 * l + 2], dbtmp, (size_t)4 * H, s == 0));
-      rc = weight_grads(st, l, Tc, B, dl, H, 1, xin, dl, yl, H, base + lay.zg, grads[3 * l + 0], grads[3 * l + 1], skws,
-                        lay.splitk_floats, !persistent, d->operand_dtype, false, d->gemm_variant, s > 0);
+      RLSTM_TRY(evs.order(st, sw));                 // d a of this layer is complete
+      rc = weight_grads(sw, l, Tc, B, dl, H, 1, xin, dl, yl, H, base + lay.zg, grads[3 * l + 0], grads[3 * l + 1], skws,
+                        lay.splitk_floats, !persistent, d->operand_dtype, two && l > 0, d->gemm_variant, s > 0);
       if (rc != RLSTM_OK) return rc;
-      rc = h0_term(st, persistent, d->operand_dtype, d->gemm_variant, Tc, B, H, 1, h0, base + lay.zg, slens, grads[3 * l + 1]);
+      rc = h0_term(sw, persistent, d->operand_dtype, d->gemm_variant, Tc, B, H, 1, h0, base + lay.zg, slens, grads[3 * l + 1]);
       if (rc != RLSTM_OK) return rc;
+      if (two) {
+        hipEvent_t ev;
+        RLSTM_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+        evs.evs.push_back(ev);
+        RLSTM_TRY(hipEventRecord(ev, sw));
+        wdone[l] = ev;
+      }
       float* dxl = (l == 0) ? (dx ? dx + (size_t)s * tb * D : nullptr) : dybuf[l & 1];
       if (dxl) {
         GemmCall g;
@@ -1041,6 +1064,7 @@ int lstm_stream_fwd_bwd(const rlstm_stream_desc* d, const float* x, const float*
     }
   }
   if (state) RLSTM_TRY(accumulate(st, state, sbuf[S & 1], nstate, true));
+  RLSTM_TRY(evs.order(sw, st));                     // the caller's stream sees the end of everything
   return RLSTM_OK;
 }
 

@@ -38,7 +38,8 @@ def _stream_case(seed, L, S, Tc, B, D, H, lens=None, wscale=0.3):
 
 
 class StreamRun:
-    def __init__(self, L, S, Tc, B, D, H, engine, want_dx=True, operand_dtype=0):
+    def __init__(self, L, S, Tc, B, D, H, engine, want_dx=True, operand_dtype=0, two_streams=False):
+        self.stream_b = torch.cuda.Stream() if two_streams else None      # takes the weight gradients
         self.desc = rl.rlstm_stream_desc(L=L, S=S, Tc=Tc, B=B, D=D, H=H, operand_dtype=operand_dtype, engine=engine)
         self.y = torch.full((S * Tc, B, H), float("nan"), device=gh.DEV)
         self.dx = torch.full((S * Tc, B, D), float("nan"), device=gh.DEV) if want_dx else None
@@ -50,7 +51,7 @@ class StreamRun:
         grads = [torch.full_like(a, float("nan")) for a in dp]
         state = gh.dev(state0) if state0 is not None else None
         rl.lstm_stream_fwd_bwd(self.desc, gh.dev(x), dp, gh.dev(lens, torch.int32), gh.dev(G), self.y, grads, self.dx, state,
-                               self.reserve, self.ws)
+                               self.reserve, self.ws, stream_b=self.stream_b)
         torch.cuda.synchronize()
         assert rl.rlstm_last_timeout(self.ws) == 0
         return dict(y=self.y.cpu().numpy(), grads=[g.cpu().numpy() for g in grads],
@@ -92,6 +93,12 @@ def test_stream_against_oracle(engine, shape):
     x, params, lens, G, state0 = _stream_case(9000 + L + S * 3 + Tc * 5 + B + H, L, S, Tc, B, D, H, lens)
     got = StreamRun(L, S, Tc, B, D, H, engine).run(x, params, lens, G, state0)
     _check_stream(got, x, params, lens, G, Tc, state0, f"stream shape={shape} engine={engine}")
+    # the weight gradients on a second stream, beside the layers below and the next segment: the oracle's results
+    # again, and the very same y, state and dx (the chain's kernels and their inputs do not change)
+    two = StreamRun(L, S, Tc, B, D, H, engine, two_streams=True).run(x, params, lens, G, state0)
+    _check_stream(two, x, params, lens, G, Tc, state0, f"stream shape={shape} engine={engine}, two streams")
+    assert np.array_equal(two["y"], got["y"]) and np.array_equal(two["state"], got["state"])
+    assert np.array_equal(two["dx"], got["dx"])
 
 
 def test_stream_without_state_array_and_without_dx_starts_from_zero():
@@ -126,11 +133,11 @@ def test_stream_bad_arguments():
     import ctypes
     d = rl.rlstm_stream_desc(L=1, S=2, Tc=3, B=2, D=3, H=4, operand_dtype=0, engine=0)
     assert rl.rlstm_stream_reserve_bytes(d) > 0 and rl.rlstm_stream_workspace_bytes(d) > 0
-    assert L.lstm_stream_fwd_bwd(ctypes.byref(d), *([None] * 11)) == -1
+    assert L.lstm_stream_fwd_bwd(ctypes.byref(d), *([None] * 12)) == -1
     bad = rl.rlstm_stream_desc(L=1, S=0, Tc=3, B=2, D=3, H=4, operand_dtype=0, engine=0)
-    assert rl.rlstm_stream_reserve_bytes(bad) == 0 and L.lstm_stream_fwd_bwd(ctypes.byref(bad), *([None] * 11)) == -2
+    assert rl.rlstm_stream_reserve_bytes(bad) == 0 and L.lstm_stream_fwd_bwd(ctypes.byref(bad), *([None] * 12)) == -2
     bad = rl.rlstm_stream_desc(L=1, S=1, Tc=3, B=2, D=3, H=4, operand_dtype=3, engine=0)
-    assert L.lstm_stream_fwd_bwd(ctypes.byref(bad), *([None] * 11)) == -3
+    assert L.lstm_stream_fwd_bwd(ctypes.byref(bad), *([None] * 12)) == -3
 
 
 @pytest.mark.parametrize("engine", ENGINES)
@@ -177,7 +184,7 @@ def test_paper_stream_full_size_against_oracle_samples():
     g = np.load(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_stream_oracle_samples.npz"))
     wl = synth.paper_stream()
     assert np.array_equal(g["seq_lens"], wl.seq_lens)
-    run = StreamRun(wl.L, wl.S, wl.Tc, wl.B, wl.D, wl.H, rl.RLSTM_ENGINE_PERSISTENT)
+    run = StreamRun(wl.L, wl.S, wl.Tc, wl.B, wl.D, wl.H, rl.RLSTM_ENGINE_PERSISTENT, two_streams=True)
     got = run.run(wl.x, wl.params, wl.seq_lens, wl.G, np.zeros((wl.L, 2, wl.B, wl.H), np.float32))
 
     def check(name, arr, tol):
