@@ -380,6 +380,25 @@ def test_gemm_bf16_operands_read_as_bf16_from_memory(case):
     assert rl.rlstm_to_bf16_2d(B16, B16t, Bd, Bm.shape[0] - 4, Bm.shape[1], Bm.shape[1], check=False) == -2
 
 
+def test_gemm_bf16_copies_with_row_strides_and_offsets():
+    """The bf16-copy product on operands that are windows of larger arrays, as the stack's weight gradients use them
+    (rows of T*B values of which a product takes (T-1)*B, starting B values in): row strides beyond K, starts that are
+    16-byte but not row aligned, K with a tail inside a slab, split K.  Against the fp64 product of the same bf16 values."""
+    rng = _rng(77)
+    bits = lambda a: torch.from_numpy((a.view(np.uint32) >> 16).astype(np.uint16).view(np.int16)).to(gh.DEV)
+    for M, N, K, ld in ((2904, 3000, 8 * 130, 8 * 140), (1000, 4000, 16384 + 24, 16384 + 96)):
+        A = _round_bf16(rng.standard_normal((M, ld)).astype(np.float32))
+        Bm = _round_bf16(rng.standard_normal((N, ld)).astype(np.float32))
+        A16, B16 = bits(A), bits(Bm)
+        ws = torch.empty(16 * M * N * 4, dtype=torch.uint8, device=gh.DEV)
+        for oa, ob in ((64, 0), (0, 64), (8, 24)):
+            C = torch.full((M, N), float("nan"), device=gh.DEV)
+            rl.rlstm_gemm_bf16_mem(0, 1, M, N, K, A16.reshape(-1)[oa:], ld, B16.reshape(-1)[ob:], ld, C, N, None, ws)
+            torch.cuda.synchronize()
+            ref = A[:, oa:oa + K].astype(np.float64) @ Bm[:, ob:ob + K].astype(np.float64).T
+            assert gh.rel_err(C.cpu().numpy(), ref) < 1e-5, (M, N, K, oa, ob)
+
+
 TOL_BF16 = 2e-2
 
 
