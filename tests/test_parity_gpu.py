@@ -451,6 +451,31 @@ def test_small_stack_bf16_operands(engine):
     assert max(errs) < TOL_BF16
 
 
+def test_stack_bf16_operands_with_bf16_copies():
+    """A bf16-operand stack large enough that the library keeps bf16 copies of the products' operands (T*B >= 16384,
+    H >= 256): a conversion pass writes them, as stored and transposed, and the projections and input gradients
+    read them (the weight gradients of this shape have too few tiles for that kernel and read fp32).  Every output against the oracle, the padding zero, and
+    the same call twice bit for bit."""
+    wl = synth.make_workload("bf16_copies", L=2, B=64, D=40, H=256, len_lo=40, len_hi=264, wscale=0.06, seed=17,
+                             operand_dtype=1, bias_scale=0.1)
+    assert wl.T * wl.B >= 16384
+    ref = gh.oracle_stack(wl)
+    run = gh.StackRun(wl, engine=rl.RLSTM_ENGINE_PERSISTENT)
+    run.step()
+    got = run.results()
+    errs = [gh.rel_err(got["y"], ref["y"]), gh.rel_err(got["dx"], ref["dx"])] + \
+           [gh.rel_err(g, r) for g, r in zip(got["grads"], ref["grads"])]
+    print("bf16 stack with copies", [f"{e:.1e}" for e in errs], flush=True)
+    assert max(errs) < TOL_BF16
+    for n, ln in enumerate(wl.seq_lens):
+        assert np.all(got["y"][ln:, n] == 0.0) and np.all(got["dx"][ln:, n] == 0.0)
+    run.step()
+    again = run.results()
+    assert np.array_equal(again["y"], got["y"]) and np.array_equal(again["dx"], got["dx"])
+    for a, b in zip(again["grads"], got["grads"]):
+        assert np.array_equal(a, b)
+
+
 def _golden(name):
     import os
     return np.load(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", name))
