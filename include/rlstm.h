@@ -112,9 +112,15 @@ typedef struct rlstm_desc {
  *                 fp32, H <= 512) - every workgroup multiplies its own columns of d a_t with its rows of R^T and
  *                 hands a piece of the result to every other workgroup of its group, which adds the pieces in a
  *                 fixed order.  Default: 1.
- *   gemm_variant  1: the pipelined kernel wherever its operand conditions hold (both operands made of whole, 16-byte
- *                 aligned float4s);  2: the plain kernel.  Default: the pipelined kernel where its conditions hold
- *                 and the product does not run beside the recurrent kernels on the same CUs.
+ *   gemm_variant  which kernel multiplies fp32 operands (Sec. 4.2's products over the whole minibatch).  Default (0):
+ *                 each operand value is cut, exactly, into three bf16 parts (8 + 8 + 8 of its 24 significant bits) on
+ *                 its way into LDS, and the six largest of the nine part products are summed in fp32 by the bf16 matrix
+ *                 instructions; what is left out is below 2^-21 of each term, and against an fp64 product the result is
+ *                 as close as that of the fp32 matrix instructions (an infinity among the operands gives NaN).
+ *                 1, 2, 3: the fp32 matrix instructions - 1 the pipelined kernel wherever its operand conditions hold
+ *                 (both operands made of whole, 16-byte aligned float4s), 2 the plain kernel, 3 the pipelined kernel
+ *                 where its conditions hold and the product does not run beside the recurrent kernels on the same CUs.
+ *                 Products of bf16 operands (operand_dtype 1) ignore 3.
  *   first_piece   (stack descriptors) with two streams and the persistent engine each layer's recurrent pass is cut
  *                 into pieces of first_piece, first_piece, 2 first_piece, 4 first_piece, ... steps, and the matrix
  *                 product that feeds a piece runs on stream b while stream a is inside the piece before it.

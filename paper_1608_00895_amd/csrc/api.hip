@@ -18,7 +18,7 @@ constexpr size_t kFlagBytes = 256;
 
 // tuning fields shared by the descriptors: 0 = library default
 bool tuning_ok(int batch_groups, int bwd_exchange, int gemm_variant) {
-  return batch_groups >= 0 && batch_groups <= 8 && bwd_exchange >= 0 && bwd_exchange <= 2 && gemm_variant >= 0 && gemm_variant <= 2;
+  return batch_groups >= 0 && batch_groups <= 8 && bwd_exchange >= 0 && bwd_exchange <= 2 && gemm_variant >= 0 && gemm_variant <= 3;
 }
 
 int check_desc(const rlstm_desc* d) {
@@ -1108,7 +1108,7 @@ static int gemm_entry(int operand_dtype, int trans_a, int trans_b, int M, int N,
                       const float* bias, int variant, void* splitk_ws, size_t splitk_ws_bytes, void* hip_stream) {
   if (!A || !B || !C) return RLSTM_ENULL;
   if (M <= 0 || N <= 0 || K < 0) return RLSTM_EDIM;
-  if (variant < 0 || variant > 2) return RLSTM_EMODE;
+  if (variant < 0 || variant > 3) return RLSTM_EMODE;
   if (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N) || ldc < N) return RLSTM_EDIM;
   int resident_err = 0;
   GemmCall g;
@@ -1199,7 +1199,8 @@ int rlstm_gemm_bf16_mem(int trans_a, int trans_b, int M, int N, int K,
   GemmCall g;
   g.transA = g.transA16 = trans_a != 0; g.transB = g.transB16 = trans_b != 0;
   g.M = M; g.N = N; g.K = K; g.C = C; g.ldc = ldc; g.bias = bias;
-  g.A16 = A16; g.lda16 = lda; g.B16 = B16; g.ldb16 = ldb; g.require_mem16 = true; g.variant = variant;
+  g.A16 = A16; g.lda16 = lda; g.B16 = B16; g.ldb16 = ldb; g.require_mem16 = true;
+  g.variant = variant == 3 ? kVariantNoWalk : (variant == 4 ? kVariantNoRing : 0);
   g.splitk_ws = static_cast<float*>(splitk_ws); g.splitk_floats = splitk_ws ? splitk_ws_bytes / sizeof(float) : 0;
   g.operand_dtype = 1;
   const hipError_t e = gemm(static_cast<hipStream_t>(hip_stream), g);

@@ -16,6 +16,7 @@
 // Split-K (for the weight gradients, whose K = T*B is 32x larger than M or N)
 // writes per-slice partial tiles to scratch and sums them in slice order in a
 // second kernel, so results are bit-reproducible run to run.
+#include <cstdlib>
 #include "rlstm_internal.h"
 
 #include <type_traits>
@@ -734,6 +735,193 @@ __global__ __launch_bounds__(256) void gemm_mfma_bf16_kernel(GemmP p) {
   store_tiles<WM, WN>(p, kz, acc, m0 + wm * WM * 32, n0 + wn * WN * 32);
 }
 
+// ---------------------------------------------------------------------------
+// fp32 product on the bf16 matrix cores.  An fp32 number is exactly the sum of three bf16 numbers (its 24
+// significant bits cut into 8 + 8 + 8: x = x1 + x2 + x3, each part the leading bits of what the parts before it
+// left over, |x2| < 2^-7 |x|, |x3| < 2^-15 |x|).  On their way into LDS both operands are cut this way into three
+// planes; the product of two fp32 numbers is then the sum of nine bf16 products, each exact in the fp32
+// accumulator's format, of which the six largest are formed (1,1) (1,2) (2,1) (2,2) (1,3) (3,1): what is left out,
+// (2,3) (3,2) (3,3), is below 2^-21 |x y| per term, the size of fp32's own rounding of a sum of such terms.  Six
+// v_mfma_f32_32x32x16_bf16 do the work of eight v_mfma_f32_32x32x2_f32 in 3/8 of the matrix cores' time.
+// 128 x 128 tile, 2 x 2 wavefronts, K slabs of 16, LDS [2 stages][3 planes][128 rows][16 (+8)] bf16 per operand.
+// Infinities turn into NaN (inf - inf in the cut), as they do in most sums of products anyway.
+// ---------------------------------------------------------------------------
+constexpr int BK3 = 16;         // K slab of the three-part kernel: one matrix instruction deep
+constexpr int LDK3 = BK3 + 8;   // LDS row stride in bf16 (12 words: 16-byte reads of 16 consecutive rows cover all banks)
+constexpr size_t gemm_3xbf16_lds_bytes() { return (size_t)2 * 3 * (128 + 128) * LDK3 * sizeof(unsigned short); }
+
+// the three parts of two neighbouring values (a at the lower k), packed as bf16 pairs
+__device__ __forceinline__ void cut3(float a, float b, unsigned& w1, unsigned& w2, unsigned& w3) {
+  const unsigned a1 = __float_as_uint(a) & 0xffff0000u, b1 = __float_as_uint(b) & 0xffff0000u;
+  const float ra = a - __uint_as_float(a1), rb = b - __uint_as_float(b1);             // exact
+  const unsigned a2 = __float_as_uint(ra) & 0xffff0000u, b2 = __float_as_uint(rb) & 0xffff0000u;
+  const float sa = ra - __uint_as_float(a2), sb = rb - __uint_as_float(b2);           // exact, at most 8 significant bits
+  w1 = __builtin_amdgcn_perm(b1, a1, 0x07060302u);
+  w2 = __builtin_amdgcn_perm(b2, a2, 0x07060302u);
+  w3 = __builtin_amdgcn_perm(__float_as_uint(sb), __float_as_uint(sa), 0x07060302u);
+}
+
+// k-contiguous source: element (mn, k) at ptr[mn*ld + k]; a slab is ROWS rows of 16 floats, a work item 4 of them
+template <int ROWS, bool VEC>
+__device__ __forceinline__ void load_kc3(const float* __restrict__ ptr, int ld, int k0, int kend, int mn0, int MN,
+                                         float4 (&r)[ROWS / 64]) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < ROWS / 64; ++i) {
+    const int idx = tid + i * 256;
+    const int mn = mn0 + (idx >> 2), k = k0 + (idx & 3) * 4;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (mn < MN) {
+      const float* q = ptr + (size_t)mn * ld + k;
+      if (VEC) {
+        if (k < kend) v = *reinterpret_cast<const float4*>(q);
+      } else {
+        if (k + 0 < kend) v.x = q[0];
+        if (k + 1 < kend) v.y = q[1];
+        if (k + 2 < kend) v.z = q[2];
+        if (k + 3 < kend) v.w = q[3];
+      }
+    }
+    r[i] = v;
+  }
+}
+template <int ROWS>
+__device__ __forceinline__ void store_kc3(unsigned short* __restrict__ s, const float4 (&r)[ROWS / 64]) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < ROWS / 64; ++i) {
+    const int idx = tid + i * 256;
+    const int mn = idx >> 2, kq = (idx & 3) * 4;
+    uint2 w1, w2, w3;
+    cut3(r[i].x, r[i].y, w1.x, w2.x, w3.x);
+    cut3(r[i].z, r[i].w, w1.y, w2.y, w3.y);
+    unsigned short* q = s + mn * LDK3 + kq;
+    *reinterpret_cast<uint2*>(q) = w1;
+    *reinterpret_cast<uint2*>(q + ROWS * LDK3) = w2;
+    *reinterpret_cast<uint2*>(q + 2 * ROWS * LDK3) = w3;
+  }
+}
+// mn-contiguous source: element (k, mn) at ptr[k*ld + mn]; a work item is 2 k rows x 4 columns
+template <int ROWS, bool VEC>
+__device__ __forceinline__ void load_mc3(const float* __restrict__ ptr, int ld, int k0, int kend, int mn0, int MN,
+                                         float4 (&r)[ROWS / 64]) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < ROWS / 128; ++i) {
+    const int idx = tid + i * 256;
+    const int mn = mn0 + (idx >> 3) * 4, k = k0 + (idx & 7) * 2;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (k + h < kend) {
+        const float* q = ptr + (size_t)(k + h) * ld + mn;
+        if (VEC) {
+          if (mn < MN) v = *reinterpret_cast<const float4*>(q);
+        } else {
+          if (mn + 0 < MN) v.x = q[0];
+          if (mn + 1 < MN) v.y = q[1];
+          if (mn + 2 < MN) v.z = q[2];
+          if (mn + 3 < MN) v.w = q[3];
+        }
+      }
+      r[i * 2 + h] = v;
+    }
+  }
+}
+template <int ROWS>
+__device__ __forceinline__ void store_mc3(unsigned short* __restrict__ s, const float4 (&r)[ROWS / 64]) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < ROWS / 128; ++i) {
+    const int idx = tid + i * 256;
+    const int mn = (idx >> 3) * 4, k = (idx & 7) * 2;
+    const float4 a = r[i * 2], b = r[i * 2 + 1];
+    const float av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      unsigned w1, w2, w3;
+      cut3(av[c], bv[c], w1, w2, w3);
+      unsigned short* q = s + (mn + c) * LDK3 + k;
+      *reinterpret_cast<unsigned*>(q) = w1;
+      *reinterpret_cast<unsigned*>(q + ROWS * LDK3) = w2;
+      *reinterpret_cast<unsigned*>(q + 2 * ROWS * LDK3) = w3;
+    }
+  }
+}
+
+template <bool TA, bool TB, bool VEC>
+__global__ __launch_bounds__(256) void gemm_f32_3xbf16_kernel(GemmP p) {
+  constexpr int TMB = 128, TNB = 128;
+  constexpr int PLANE = TMB * LDK3;                                  // one part of one operand's slab
+  extern __shared__ __align__(16) float smem[];
+  unsigned short* As = reinterpret_cast<unsigned short*>(smem);     // [2][3][TMB][LDK3]
+  unsigned short* Bs = As + 2 * 3 * PLANE;                          // [2][3][TNB][LDK3]
+
+  int tile, kz;
+  if (!work_item(p, &tile, &kz)) return;
+  int tm, tn;
+  tile_coords(p, tile, p.tiles / p.tiles_n, &tm, &tn);
+  const int m0 = tm * TMB, n0 = tn * TNB;
+  const int kbeg = kz * p.kchunk;
+  const int kend = min(p.K, kbeg + p.kchunk);
+  const int nslab = (kend - kbeg + BK3 - 1) / BK3;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, lh = lane >> 5;
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  float4 ra[TMB / 64], rb[TNB / 64];
+  auto load = [&](int slab) {
+    const int k0 = kbeg + slab * BK3;
+    if (TA) load_mc3<TMB, VEC>(p.A, p.lda, k0, kend, m0, p.M, ra); else load_kc3<TMB, VEC>(p.A, p.lda, k0, kend, m0, p.M, ra);
+    if (TB) load_kc3<TNB, VEC>(p.B, p.ldb, k0, kend, n0, p.N, rb); else load_mc3<TNB, VEC>(p.B, p.ldb, k0, kend, n0, p.N, rb);
+  };
+  auto store = [&](int buf) {
+    if (TA) store_mc3<TMB>(As + buf * 3 * PLANE, ra); else store_kc3<TMB>(As + buf * 3 * PLANE, ra);
+    if (TB) store_kc3<TNB>(Bs + buf * 3 * PLANE, rb); else store_mc3<TNB>(Bs + buf * 3 * PLANE, rb);
+  };
+
+  if (nslab > 0) { load(0); store(0); }
+  __syncthreads();
+
+  for (int s = 0; s < nslab; ++s) {
+    const int buf = s & 1;
+    if (s + 1 < nslab) load(s + 1);
+    // lane l supplies row l%32, k = 8*(l/32) .. +7
+    const unsigned short* as = As + buf * 3 * PLANE + (wm * 64 + l32) * LDK3 + lh * 8;
+    const unsigned short* bs = Bs + buf * 3 * PLANE + (wn * 64 + l32) * LDK3 + lh * 8;
+    bf16x8 af[3][2], bfr[3][2];
+#pragma unroll
+    for (int q = 0; q < 3; ++q)
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        af[q][i] = *reinterpret_cast<const bf16x8*>(as + q * PLANE + i * 32 * LDK3);
+        bfr[q][i] = *reinterpret_cast<const bf16x8*>(bs + q * PLANE + i * 32 * LDK3);
+      }
+    // small terms first; the four tiles alternate so that no instruction waits for the one before it
+    constexpr int QA[6] = {2, 0, 1, 1, 0, 0}, QB[6] = {0, 2, 1, 0, 1, 0};
+#pragma unroll
+    for (int t = 0; t < 6; ++t)
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[QA[t]][i], bfr[QB[t]][j], acc[i][j], 0, 0, 0);
+    if (s + 1 < nslab) store(buf ^ 1);
+    __syncthreads();
+  }
+
+  store_tiles<2, 2>(p, kz, acc, m0 + wm * 64, n0 + wn * 64);
+}
+
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int slices,
                                                              int M, int N, float* __restrict__ C, int ldc,
                                                              const float* __restrict__ bias, int accumulate) {
@@ -1022,6 +1210,180 @@ struct SlabFeederBf {
     }
   }
 };
+
+// ---------------------------------------------------------------------------
+// Pipelined form of the three-part kernel (gemm_f32_3xbf16_kernel): range-checked buffer loads without branches, so
+// that the wait before a slab's way into LDS counts only that slab's loads; D slabs on their way from memory at any
+// time (slab s waits in register stage s % D); the cutting and the LDS stores of slab s+1 and the loads of slab
+// s+1+D are dealt out between the matrix instructions of slab s.  One such workgroup per CU, as beside the recurrent
+// kernels, then keeps its matrix cores fed by itself.
+// ---------------------------------------------------------------------------
+template <bool KC, int D>
+struct SlabFeeder3 {
+  __amdgpu_buffer_rsrc_t rsrc;
+  unsigned voff[2];
+  unsigned step;
+  int lds_off[2];              // KC: bf16 offset of each float4's 4 values; !KC: [0] = offset of (first column, k)
+  int kq[2];                   // KC: first k of each float4 inside the slab
+  int klen;
+  floatx4 r[D][2];
+
+  __device__ __forceinline__ void init(const float* ptr, int ld, int mn0, int MN, int kbeg, int kend) {
+    const int tid = threadIdx.x;
+    klen = kend - kbeg;
+    if (KC) {
+      const int rows = min(128, MN - mn0);
+      const float* base = ptr + (size_t)mn0 * ld + kbeg;
+      rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(base), 0, (int)((size_t)rows * ld * 4 - (size_t)kbeg * 4), 0x00020000);
+      step = BK3 * 4;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int idx = tid + h * 256;
+        const int row = idx >> 2, q = (idx & 3) * 4;
+        voff[h] = (unsigned)row * (unsigned)ld * 4u + q * 4u;       // rows beyond the matrix fall outside num_records
+        kq[h] = q;
+        lds_off[h] = row * LDK3 + q;
+      }
+    } else {
+      const float* base = ptr + (size_t)kbeg * ld + mn0;
+      rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(base), 0, (int)((size_t)klen * ld * 4), 0x00020000);
+      step = (unsigned)BK3 * (unsigned)ld * 4u;
+      const int mn = (tid >> 3) * 4, k = (tid & 7) * 2;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        voff[h] = (mn0 + mn < MN) ? (unsigned)(k + h) * (unsigned)ld * 4u + mn * 4u : kOutOfRange;   // k tail: num_records
+        kq[h] = 0;
+      }
+      lds_off[0] = mn * LDK3 + k;
+      lds_off[1] = 0;
+    }
+  }
+  // issue the loads of slab s into a stage (any s >= 0; slabs beyond the last read zeros)
+  __device__ __forceinline__ void load(int stage, int s) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      unsigned off = voff[h] + (unsigned)s * step;
+      if (KC) off = (s * BK3 + kq[h] < klen) ? off : kOutOfRange;
+      else    off = (s * BK3 < klen) ? off : kOutOfRange;          // keeps s * step from wrapping around
+      r[stage][h] = buffer_load_x4(rsrc, off);
+    }
+  }
+  // cut a stage into its three parts and write them to the three planes of a slab buffer
+  __device__ __forceinline__ void store(int stage, unsigned short* slab) const {
+    constexpr int PLANE = 128 * LDK3;
+    if (KC) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        uint2 w1, w2, w3;
+        cut3(r[stage][h][0], r[stage][h][1], w1.x, w2.x, w3.x);
+        cut3(r[stage][h][2], r[stage][h][3], w1.y, w2.y, w3.y);
+        unsigned short* q = slab + lds_off[h];
+        *reinterpret_cast<uint2*>(q) = w1;
+        *reinterpret_cast<uint2*>(q + PLANE) = w2;
+        *reinterpret_cast<uint2*>(q + 2 * PLANE) = w3;
+      }
+    } else {
+      // rows k and k+1 of four columns: each column's pair of k is one 32-bit store per plane
+      unsigned short* q = slab + lds_off[0];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        unsigned w1, w2, w3;
+        cut3(r[stage][0][c], r[stage][1][c], w1, w2, w3);
+        *reinterpret_cast<unsigned*>(q + c * LDK3) = w1;
+        *reinterpret_cast<unsigned*>(q + c * LDK3 + PLANE) = w2;
+        *reinterpret_cast<unsigned*>(q + c * LDK3 + 2 * PLANE) = w3;
+      }
+    }
+  }
+};
+
+template <bool TA, bool TB, int D>
+__global__ __launch_bounds__(256) void gemm_f32_3xbf16_v2_kernel(GemmP p) {
+  constexpr int PLANE = 128 * LDK3;
+  constexpr bool AKC = !TA, BKC = TB;
+  extern __shared__ __align__(16) float smem[];
+  unsigned short* As = reinterpret_cast<unsigned short*>(smem);     // [2][3][128][LDK3]
+  unsigned short* Bs = As + 2 * 3 * PLANE;                          // [2][3][128][LDK3]
+
+  int tile, kz;
+  if (!work_item(p, &tile, &kz)) return;
+  int tm, tn;
+  tile_coords(p, tile, p.tiles / p.tiles_n, &tm, &tn);
+  const int m0 = tm * 128, n0 = tn * 128;
+  const int kbeg = kz * p.kchunk;
+  const int kend = min(p.K, kbeg + p.kchunk);
+  const int nslab = (kend - kbeg + BK3 - 1) / BK3;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, lh = lane >> 5;
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  SlabFeeder3<AKC, D> fa;
+  SlabFeeder3<BKC, D> fb;
+  fa.init(p.A, p.lda, m0, p.M, kbeg, kend);
+  fb.init(p.B, p.ldb, n0, p.N, kbeg, kend);
+#pragma unroll
+  for (int d = 0; d < D; ++d) { fa.load(d, d); fb.load(d, d); }
+  fa.store(0, As); fb.store(0, Bs);
+  fa.load(0, D); fb.load(0, D);
+  __syncthreads();
+
+  // lane l supplies row l%32, k = 8*(l/32) .. +7
+  const int a_frag = (wm * 64 + l32) * LDK3 + lh * 8, b_frag = (wn * 64 + l32) * LDK3 + lh * 8;
+  auto slab = [&](int s, int d) {
+    const int buf = s & 1;
+    const int next = (d + 1) % D;          // the stage slab s+1 waits in (a constant once the loops are unrolled)
+    const unsigned short* as = As + buf * 3 * PLANE + a_frag;
+    const unsigned short* bs = Bs + buf * 3 * PLANE + b_frag;
+    unsigned short* as_next = As + (buf ^ 1) * 3 * PLANE;
+    unsigned short* bs_next = Bs + (buf ^ 1) * 3 * PLANE;
+    bf16x8 af[3][2], bfr[3][2];
+#pragma unroll
+    for (int q = 0; q < 3; ++q)
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        af[q][i] = *reinterpret_cast<const bf16x8*>(as + q * PLANE + i * 32 * LDK3);
+        bfr[q][i] = *reinterpret_cast<const bf16x8*>(bs + q * PLANE + i * 32 * LDK3);
+      }
+    // small terms first; the four tiles alternate so that no instruction waits for the one before it
+    constexpr int QA[6] = {2, 0, 1, 1, 0, 0}, QB[6] = {0, 2, 1, 0, 1, 0};
+#pragma unroll
+    for (int t = 0; t < 6; ++t) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[QA[t]][i], bfr[QB[t]][j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      // the next slab's way into LDS and the loads of the slab D after it, between the matrix instructions
+      if (t == 0) fa.store(next, as_next);
+      if (t == 1) fb.store(next, bs_next);
+      if (t == 2) { fa.load(next, s + 1 + D); fb.load(next, s + 1 + D); }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    __syncthreads();
+  };
+  // whole rounds of D slabs without a branch inside (a branch would make the wait before a stage's way into LDS
+  // count every load in flight), then the rest
+  int s0 = 0;
+  for (; s0 + D <= nslab; s0 += D) {
+#pragma unroll
+    for (int d = 0; d < D; ++d) slab(s0 + d, d);
+  }
+#pragma unroll
+  for (int d = 0; d < D - 1; ++d)
+    if (s0 + d < nslab) slab(s0 + d, d);       // uniform over the workgroup
+
+  store_tiles<2, 2>(p, kz, acc, m0 + wm * 64, n0 + wn * 64);
+}
 
 // The same for an operand that is already bf16 in memory (a copy written once, read by several products): half the
 // bytes, no rounding in the loop.  KC: a unit is one 16-byte load of 8 consecutive k of a row and one 16-byte LDS
@@ -1374,6 +1736,26 @@ hipError_t launch_bf16_v2(hipStream_t stream, const GemmP& p, dim3 grid) {
   return hipGetLastError();
 }
 
+template <typename K>
+hipError_t launch_3xbf16_k(K kernel, hipStream_t stream, const GemmP& p, dim3 grid) {
+  const size_t lds = gemm_3xbf16_lds_bytes();
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(kernel, grid, dim3(256), lds, stream, p);
+  return hipGetLastError();
+}
+// buffer_loads: both operands made of whole, 16-byte aligned float4s and panels within 31-bit byte offsets.
+// beside: the product shares its CUs with the recurrent kernels.  One slab in flight then: measured on the 4 x 500
+// stack, two slabs in flight make the products a fifth faster and every recurrent step slower (54.1 against 52.8 ms
+// per call), and the kernel keeps to 152 registers, which fit beside two wavefronts of any of the recurrent kernels.
+template <bool TA, bool TB>
+hipError_t launch_3xbf16(hipStream_t stream, const GemmP& p, dim3 grid, bool vec, bool buffer_loads, bool beside) {
+  if (buffer_loads && beside) return launch_3xbf16_k(gemm_f32_3xbf16_v2_kernel<TA, TB, 1>, stream, p, grid);
+  if (buffer_loads) return launch_3xbf16_k(gemm_f32_3xbf16_v2_kernel<TA, TB, 2>, stream, p, grid);
+  if (vec) return launch_3xbf16_k(gemm_f32_3xbf16_kernel<TA, TB, true>, stream, p, grid);
+  return launch_3xbf16_k(gemm_f32_3xbf16_kernel<TA, TB, false>, stream, p, grid);
+}
+
 template <int WM, int WN, bool TA, bool TB, bool VEC>
 hipError_t launch_bf16_v(hipStream_t stream, const GemmP& p, dim3 grid) {
   const size_t lds = (size_t)2 * 64 * (WM + WN) * LDK * sizeof(unsigned short);
@@ -1495,30 +1877,39 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
   p.per_xcd = (p.work + 7) / 8;
   dim3 grid((unsigned)(8 * p.per_xcd), 1, 1);
   hipError_t e;
-  const bool pipelined = vec && pipelined_ok && (g.variant == 1 || (g.variant == 0 && !g.small_footprint));
+  // variant 3 asks for the fp32 matrix instructions, chosen as variant 0 chose them before the three-part kernel;
+  // it means nothing to bf16 operands
+  const int variant = g.variant == 3 ? 0 : g.variant;
+  const bool pipelined = vec && pipelined_ok && (variant == 1 || (variant == 0 && !g.small_footprint));
   if (bf16) {
     // bf16 copies of both operands are used where the kernel that takes them runs (256 x 256 tiles, pipelined) and
     // the copies consist of whole, 16-byte aligned groups of 8 values along their contiguous dimension
     const size_t a16_panel = g.transA16 ? kspan * g.lda16 * 2 : (size_t)tile_m * g.lda16 * 2;
     const size_t b16_panel = g.transB16 ? (size_t)tile_n * g.ldb16 * 2 : kspan * g.ldb16 * 2;
-    const bool mem16 = g.A16 && g.B16 && big && (g.variant != 2) && aligned16(g.A16) && aligned16(g.B16) &&
+    const bool mem16 = g.A16 && g.B16 && big && (variant != 2) && aligned16(g.A16) && aligned16(g.B16) &&
                        g.lda16 % 8 == 0 && g.ldb16 % 8 == 0 && g.K % 8 == 0 && (g.transA16 ? g.M : g.K) % 8 == 0 &&
                        (g.transB16 ? g.K : g.N) % 8 == 0 && p.kchunk % 8 == 0 && a16_panel < (1ull << 31) && b16_panel < (1ull << 31);
     if (g.require_mem16 && !mem16) return hipErrorInvalidValue;
     bool tA = g.transA, tB = g.transB;
     if (mem16) { tA = g.transA16; tB = g.transB16; p.lda = g.lda16; p.ldb = g.ldb16; }
     const bool pl = mem16 || pipelined;
-    if (mem16 && g.variant != 3) {
+    if (mem16 && g.variant != kVariantNoWalk) {
       // one workgroup per CU (the kernel's LDS and registers allow no more), each walking through its XCD's items
       int cus = 0;
       if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, current_device()) != hipSuccess) { (void)hipGetLastError(); cus = 0; }
       const int slots = cus / 8;
       if (slots > 0 && slots < p.per_xcd) grid = dim3((unsigned)(8 * slots), 1, 1);
     }
-    if (!tA && !tB)      e = launch_bf16<false, false>(stream, p, grid, vec, big, pl, mem16, g.variant != 4);
-    else if (!tA && tB)  e = launch_bf16<false, true>(stream, p, grid, vec, big, pl, mem16, g.variant != 4);
-    else if (tA && !tB)  e = launch_bf16<true, false>(stream, p, grid, vec, big, pl, mem16, g.variant != 4);
-    else                 e = launch_bf16<true, true>(stream, p, grid, vec, big, pl, mem16, g.variant != 4);
+    if (!tA && !tB)      e = launch_bf16<false, false>(stream, p, grid, vec, big, pl, mem16, g.variant != kVariantNoRing);
+    else if (!tA && tB)  e = launch_bf16<false, true>(stream, p, grid, vec, big, pl, mem16, g.variant != kVariantNoRing);
+    else if (tA && !tB)  e = launch_bf16<true, false>(stream, p, grid, vec, big, pl, mem16, g.variant != kVariantNoRing);
+    else                 e = launch_bf16<true, true>(stream, p, grid, vec, big, pl, mem16, g.variant != kVariantNoRing);
+  } else if (g.variant == 0) {
+    // fp32 operands by default: the six-product form on the bf16 matrix cores (see gemm_f32_3xbf16_kernel)
+    if (!g.transA && !g.transB)      e = launch_3xbf16<false, false>(stream, p, grid, vec, vec && pipelined_ok, g.small_footprint);
+    else if (!g.transA && g.transB)  e = launch_3xbf16<false, true>(stream, p, grid, vec, vec && pipelined_ok, g.small_footprint);
+    else if (g.transA && !g.transB)  e = launch_3xbf16<true, false>(stream, p, grid, vec, vec && pipelined_ok, g.small_footprint);
+    else                             e = launch_3xbf16<true, true>(stream, p, grid, vec, vec && pipelined_ok, g.small_footprint);
   } else if (pipelined) {
     // A product that shares its CUs with the recurrent kernels keeps to the plain kernel: measured on the
     // 4 x 500 stack, the pipelined kernel beside them finishes its products sooner but slows every recurrent
@@ -1529,7 +1920,7 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
     else                             e = launch_mfma_v2<true, true>(stream, p, grid);
   } else {
     // beside the recurrent kernels: the short matrix instruction (see gemm_mfma_f32_short_kernel); variant 2 keeps the long one
-    const bool sh = g.small_footprint && g.variant != 2;
+    const bool sh = g.small_footprint && variant != 2;
     if (!g.transA && !g.transB)      e = launch_mfma<16, false, false>(stream, p, grid, vec, sh);
     else if (!g.transA && g.transB)  e = launch_mfma<16, false, true>(stream, p, grid, vec, sh);
     else if (g.transA && !g.transB)  e = launch_mfma<16, true, false>(stream, p, grid, vec, sh);
@@ -1622,7 +2013,7 @@ hipError_t to_bf16(hipStream_t stream, const float* src, unsigned short* dst, si
 }
 
 size_t gemm_small_lds_bytes(int operand_dtype) {
-  return operand_dtype == 1 ? (size_t)2 * (TM + TN) * LDK * sizeof(unsigned short) : (size_t)4 * 16 * LDT * sizeof(float);
+  return operand_dtype == 1 ? (size_t)2 * (TM + TN) * LDK * sizeof(unsigned short) : gemm_3xbf16_lds_bytes();
 }
 
 }  // namespace rlstm

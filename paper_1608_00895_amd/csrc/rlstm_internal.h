@@ -19,6 +19,7 @@ namespace rlstm {
 // (may be null: no split).  naive selects the plain one-thread-per-output
 // kernel of the stepwise engine.
 // ---------------------------------------------------------------------------
+constexpr int kVariantNoWalk = 13, kVariantNoRing = 14;
 struct GemmCall {
   bool transA = false, transB = false;
   int M = 0, N = 0, K = 0;
@@ -31,7 +32,10 @@ struct GemmCall {
   int operand_dtype = 0;
   bool naive = false;
   bool small_footprint = false;   // runs beside the recurrent kernels on shared CUs: keep to the plain 128 x 128 kernel
-  int variant = 0;                // fp32 kernel choice: 0 by call, 1 the pipelined kernel wherever it applies, 2 the plain kernel
+  // fp32 operands: 0 the product from three bf16 parts per operand, 1 the pipelined fp32-instruction kernel wherever it
+  // applies, 2 the plain fp32-instruction kernel, 3 the fp32-instruction kernels chosen by call (pipelined alone, the
+  // short instruction beside the recurrent kernels); bf16 copies: kVariantNoWalk, kVariantNoRing (measurement)
+  int variant = 0;
   // operand_dtype 1 only: bf16 copies of op(A) and op(B) (written by to_bf16 / to_bf16_2d), in a layout of their own:
   // transA16 == false: A16 is [M,K] with row stride lda16 (k contiguous); true: stored [K,M]; B16 likewise (transB16
   // == false: [K,N]; true: stored [N,K]).  They are used instead of A and B where the kernel that takes bf16 from

@@ -199,9 +199,10 @@ def test_engines_agree_on_medium_stack():
     # no multiple of the 32-row chunk
     (1, 0, 68, 160, 40000), (1, 0, 80, 160, 16500), (1, 0, 36, 84, 20001), (1, 0, 4, 4, 16384),
 ])
-@pytest.mark.parametrize("variant", [0, 2])
+@pytest.mark.parametrize("variant", [0, 2, 3])
 def test_gemm_against_numpy(case, variant):
-    """variant 0: the kernel the library picks (the pipelined one where the operands allow); 2: the plain kernel."""
+    """variant 0: the product from three bf16 parts per operand (its pipelined form where the operands allow); 2: the
+    plain kernel on the fp32 matrix instructions; 3: those instructions, the pipelined kernel where the operands allow."""
     ta, tb, M, N, K = case
     rng = _rng(sum(case))
     A = rng.standard_normal((K, M) if ta else (M, K)).astype(np.float32)
@@ -214,6 +215,70 @@ def test_gemm_against_numpy(case, variant):
     rl.rlstm_gemm_f32(ta, tb, M, N, K, Ad, A.shape[1], Bd, Bm.shape[1], C, N, biasd, ws, variant=variant)
     torch.cuda.synchronize()
     assert gh.rel_err(C.cpu().numpy(), ref) < 1e-5, (case, variant)
+
+
+@pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("side", ["a", "b"])
+def test_gemm_three_part_product_keeps_all_24_bits(ta, tb, side):
+    """The default fp32 product cuts every operand value into three bf16 parts.  One operand holds numbers that use all
+    24 significant bits over a range of exponents, the other picks and scales them (one entry +-2^e per column or row):
+    every output is then a single product that fp32 holds exactly, so the result must equal it bit for bit - a lost or
+    misplaced part would show.  Both operand sides, all four storage orders, shapes with tile tails (the kernel with
+    range-checked loads) and without whole float4s (the plain-load kernel)."""
+    for (M, N, K) in [(260, 132, 72), (131, 67, 45)]:
+        rng = _rng(1000 * ta + 100 * tb + M)
+        full_shape = (M, K) if side == "a" else (K, N)
+        mant = rng.integers(2 ** 23, 2 ** 24, size=full_shape).astype(np.float64)          # 24 significant bits
+        full = (mant * np.exp2(rng.integers(-40, 17, size=full_shape)) * rng.choice([-1.0, 1.0], size=full_shape))
+        if side == "a":
+            pick = np.zeros((K, N))
+            rows = rng.integers(0, K, size=N)
+            pick[rows, np.arange(N)] = np.exp2(rng.integers(-6, 7, size=N)) * rng.choice([-1.0, 1.0], size=N)
+            A, Bm = full, pick
+        else:
+            pick = np.zeros((M, K))
+            cols = rng.integers(0, K, size=M)
+            pick[np.arange(M), cols] = np.exp2(rng.integers(-6, 7, size=M)) * rng.choice([-1.0, 1.0], size=M)
+            A, Bm = pick, full
+        ref = (A @ Bm).astype(np.float32)
+        assert np.array_equal(ref.astype(np.float64), A @ Bm)                                # exact in fp32
+        As = np.ascontiguousarray(A.T if ta else A).astype(np.float32)
+        Bs = np.ascontiguousarray(Bm.T if tb else Bm).astype(np.float32)
+        C = torch.full((M, N), float("nan"), device=gh.DEV)
+        rl.rlstm_gemm_f32(ta, tb, M, N, K, gh.dev(As), As.shape[1], gh.dev(Bs), Bs.shape[1], C, N, None, None, variant=0)
+        torch.cuda.synchronize()
+        assert np.array_equal(C.cpu().numpy(), ref), (ta, tb, side, M, N, K)
+
+
+@pytest.mark.parametrize("case", [(0, 0, 1024, 768, 1000), (0, 1, 1000, 500, 2000), (1, 0, 500, 1000, 32000), (1, 1, 260, 132, 516)])
+def test_gemm_three_part_product_is_as_close_to_fp64_as_the_fp32_instructions(case):
+    """Against the fp64 product, entry by entry in units of sum_k |a||b| (the scale rounding errors of a sum of products
+    are measured in), the default fp32 product (three bf16 parts per operand, six of the nine part products) must be as
+    close as the kernels on the fp32 matrix instructions (largest error at most 1.5 times, root mean square at most 1.25
+    times theirs),
+    on normal operands and on operands whose rows carry scales from 2^-30 to 2^30."""
+    ta, tb, M, N, K = case
+    for spread in (0, 30):
+        rng = _rng(sum(case) + spread)
+        A = rng.standard_normal((M, K)) * np.exp2(rng.integers(-spread, spread + 1, size=(M, 1)))
+        Bm = rng.standard_normal((K, N)) * np.exp2(rng.integers(-spread, spread + 1, size=(1, N)))
+        A, Bm = A.astype(np.float32), Bm.astype(np.float32)
+        ref = A.astype(np.float64) @ Bm.astype(np.float64)
+        scale = np.abs(A).astype(np.float64) @ np.abs(Bm).astype(np.float64)
+        As = np.ascontiguousarray(A.T) if ta else A
+        Bs = np.ascontiguousarray(Bm.T) if tb else Bm
+        Ad, Bd = gh.dev(As), gh.dev(Bs)
+        ws = torch.empty(64 * M * N * 4, dtype=torch.uint8, device=gh.DEV)
+        err = {}
+        for variant in (0, 3):
+            C = torch.full((M, N), float("nan"), device=gh.DEV)
+            rl.rlstm_gemm_f32(ta, tb, M, N, K, Ad, As.shape[1], Bd, Bs.shape[1], C, N, None, ws, variant=variant)
+            torch.cuda.synchronize()
+            e = np.abs(C.cpu().numpy().astype(np.float64) - ref) / scale
+            err[variant] = (e.max(), np.sqrt(np.mean(e * e)))
+        print("three-part vs fp32 instructions", case, "spread", spread, err, flush=True)
+        assert err[0][0] <= 1.5 * err[3][0] and err[0][1] <= 1.25 * err[3][1], (case, spread, err)
+        assert err[0][0] < 5e-6
 
 
 def test_gemm_tall_skinny_many_slices():
