@@ -25,6 +25,30 @@ if ROOT not in sys.path:
 PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X dense fp32 matrix peak
 PEAK_BF16_MFMA_TFLOPS = 2500.0    # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
+# fp32 operands multiplied as three bf16 parts each (the library's default): six bf16 matrix instructions do the work
+# of one fp32 product, so a counted TFLOP/s of such a product is priced against a sixth of the bf16 peak
+PEAK_F32_AS_3XBF16_TFLOPS = PEAK_BF16_MFMA_TFLOPS / 6.0
+PRODUCT_KERNELS = ("input_projection", "input_gradient", "weight_gradient", "recurrent_weight_gradient", "output_layer_product")
+
+
+def products_note(operand_dtype, gemm_variant):
+    """How the whole-minibatch matrix products of a run were computed (the recurrent steps: matrix instructions of the
+    operand type, fp32 accumulation)."""
+    if operand_dtype == 1:
+        return "operands rounded to bf16, bf16 matrix instructions, fp32 accumulation"
+    if not gemm_variant:
+        return ("fp32 operands, each cut exactly into three bf16 parts; six bf16 matrix instructions per product, fp32 "
+                "accumulation; as close to an fp64 product as the fp32 matrix instructions (gemm_variant 3 selects those)")
+    return "fp32 operands, fp32 matrix instructions"
+
+
+def mfma_peak(kernel, operand_dtype, gemm_variant):
+    """(peak TFLOP/s, what it is) for the counted FLOP of one of the library's kernel groups."""
+    if operand_dtype == 1:
+        return PEAK_BF16_MFMA_TFLOPS, "bf16 matrix instructions"
+    if kernel in PRODUCT_KERNELS and not gemm_variant:
+        return PEAK_F32_AS_3XBF16_TFLOPS, "bf16 matrix instructions, six per fp32 product (operands cut into three bf16 parts)"
+    return PEAK_FP32_MFMA_TFLOPS, "fp32 matrix instructions"
 
 
 def log(*a):
@@ -263,8 +287,9 @@ def bench_config5(args):
 
 def bench_gemm(args):
     """The whole-minibatch matrix products alone, at the shapes of config 3 and of the paper's batch: one step = one
-    launch of every shape; reports TFLOP/s per shape (fp32 MFMA roofline) for the kernel variant the library picks
-    and for the plain kernel."""
+    launch of every shape; reports TFLOP/s per shape for the kernel the library picks for fp32 operands (three bf16
+    parts per operand, six bf16 matrix instructions per product: priced against a sixth of the bf16 peak) and for the
+    kernels on the fp32 matrix instructions (pipelined where the operands allow, and plain)."""
     import torch
     from paper_1608_00895_amd import binding as rl
 
@@ -288,7 +313,7 @@ def bench_gemm(args):
         C = torch.empty((M, N), device=dev)
         lda, ldb = (M if ta else K), (K if tb else N)
         res = {}
-        for variant, tag in ((0, "picked"), (2, "plain")):
+        for variant, tag in ((0, "picked"), (3, "fp32_instructions"), (2, "plain")):
             for _ in range(args.warmup):
                 rl.rlstm_gemm_f32(ta, tb, M, N, K, A, lda, B, ldb, C, N, None, sk, variant=variant)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -300,6 +325,9 @@ def bench_gemm(args):
             res[tag] = e0.elapsed_time(e1) / args.steps
         flop = 2.0 * M * N * K
         kernels.append({"kernel": name, "M": M, "N": N, "K": K, "avg_ms": res["picked"], "tflops": flop / res["picked"] / 1e9,
+                        "frac_of_mfma_peak": flop / res["picked"] / 1e9 / PEAK_F32_AS_3XBF16_TFLOPS,
+                        "fp32_instruction_kernel_ms": res["fp32_instructions"],
+                        "fp32_instruction_kernel_tflops": flop / res["fp32_instructions"] / 1e9,
                         "plain_kernel_ms": res["plain"], "plain_kernel_tflops": flop / res["plain"] / 1e9})
         log(kernels[-1])
         total_flop += flop; total_ms += res["picked"]
@@ -347,8 +375,10 @@ def bench_gemm(args):
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": total_ms, "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": "matrix products at the shapes of config 3 and of the paper's batch"},
-           "roofline": {"kernel": dom["kernel"], "bound": "mfma", "achieved": dom["tflops"], "peak": PEAK_FP32_MFMA_TFLOPS,
-                        "unit": "TFLOP/s", "frac": dom["tflops"] / PEAK_FP32_MFMA_TFLOPS, "traffic": None},
+           "roofline": {"kernel": dom["kernel"], "bound": "mfma", "achieved": dom["tflops"], "peak": PEAK_F32_AS_3XBF16_TFLOPS,
+                        "unit": "TFLOP/s", "frac": dom["tflops"] / PEAK_F32_AS_3XBF16_TFLOPS, "traffic": None,
+                        "note": "fp32 operands cut into three bf16 parts, six bf16 matrix instructions per product: "
+                                "the peak is a sixth of the bf16 matrix peak"},
            "kernels": kernels, "bf16_kernels": bf16_kernels}
     print(json.dumps(out), flush=True)
 
@@ -405,7 +435,8 @@ def bench_stream(args):
         e = {"kernel": rl.PROFILE_KINDS[kind], "launches_per_step": d["launches"] / hook_steps,
              "avg_ms": d["ms"] / d["launches"], "ms_per_step": d["ms"] / hook_steps,
              "tflops": d["flop"] / (d["ms"] * 1e-3) / 1e12}
-        e["frac_of_mfma_peak"] = e["tflops"] / PEAK_FP32_MFMA_TFLOPS
+        e["mfma_peak_tflops"], e["mfma_path"] = mfma_peak(e["kernel"], 0, args.gemm_variant)
+        e["frac_of_mfma_peak"] = e["tflops"] / e["mfma_peak_tflops"]
         if kind in (1, 2):
             e["steps_per_launch"] = d["rsteps"] / d["launches"]
             e["step_us"] = 1e3 * d["ms"] / d["rsteps"]
@@ -432,7 +463,8 @@ def bench_stream(args):
            "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": wl.name, "layers": wl.L, "units": wl.H, "sequences": wl.B, "segments": wl.S,
                       "segment_frames": wl.Tc, "valid_frames": wl.frames, "padded_slots": slots,
-                      "engine": "persistent" if args.engine in (0, 1) else "stepwise"},
+                      "engine": "persistent" if args.engine in (0, 1) else "stepwise",
+                      "products": products_note(0, args.gemm_variant)},
            "roofline": roofline, "kernels": kernels}
     try:
         out["config"]["plan"] = rl.rblstm_plan(rl.rblstm_desc(L=wl.L, T=wl.Tc, B=wl.B, D=wl.D, H=wl.H, operand_dtype=0,
@@ -629,8 +661,9 @@ def main():
         e = {"kernel": rl.PROFILE_KINDS[kind], "launches_per_step": d["launches"] / hook_steps,
              "avg_ms": d["ms"] / d["launches"], "ms_per_step": d["ms"] / hook_steps,
              "tflops": d["flop"] / (d["ms"] * 1e-3) / 1e12}
-        # fraction of the matrix cores' peak for the operand type (the products' MFMA utilisation by throughput)
-        e["frac_of_mfma_peak"] = e["tflops"] / (PEAK_FP32_MFMA_TFLOPS if wl.operand_dtype == 0 else PEAK_BF16_MFMA_TFLOPS)
+        # fraction of the matrix cores' peak for the instructions the kernel runs on (MFMA utilisation by throughput)
+        e["mfma_peak_tflops"], e["mfma_path"] = mfma_peak(e["kernel"], wl.operand_dtype, args.gemm_variant)
+        e["frac_of_mfma_peak"] = e["tflops"] / e["mfma_peak_tflops"]
         if kind in (1, 2):
             # a pass over the T steps may be cut into several launches
             e["steps_per_launch"] = d["rsteps"] / d["launches"]
@@ -732,7 +765,8 @@ def main():
                    "T_padded": wl.T, "valid_frames": wl.frames, "padded_slots": wl.T * wl.B,
                    "padded_slots_per_s": wl.T * wl.B / (ms_per_step * 1e-3),
                    "engine": "persistent" if args.engine in (0, 1) else "stepwise",
-                   "streams": 1 if args.one_stream else 2},
+                   "streams": 1 if args.one_stream else 2,
+                   "products": products_note(wl.operand_dtype, args.gemm_variant)},
         "roofline": roofline,
         "kernels": kernels,
     }
