@@ -239,15 +239,22 @@ enum OverlapMode { kSerial = 0, kShare = 1 };
 
 // requested: the descriptor's overlap_mode (0 chosen per shape, 1 serial, 2 shared; shared falls back to serial where the
 // two LDS footprints do not fit one CU)
-OverlapMode overlap_mode(const RecShape& rs, int operand_dtype, bool persistent, bool two_streams, int requested) {
+// *variant: in, the descriptor's gemm_variant; out, the one the call's products use - where the default product kernel
+// for fp32 operands (three bf16 parts, 72 KB of LDS) does not fit beside the recurrent workgroups and the kernels on the
+// fp32 matrix instructions (33 KB) do, a shared call keeps to those.
+OverlapMode overlap_mode(const RecShape& rs, int operand_dtype, bool persistent, bool two_streams, int requested, int* variant) {
   if (!persistent || !two_streams || requested == 1) return kSerial;
   DeviceInfo di;
   if (device_info(&di) != hipSuccess) { (void)hipGetLastError(); return kSerial; }
   int plan[10];
   const size_t rec = persistent_lds_bytes(rs, di.num_cus, di.max_lds);
-  const bool fits = rec != 0 && rec + gemm_small_lds_bytes(operand_dtype) <= di.max_lds;
+  bool fits = rec != 0 && rec + gemm_small_lds_bytes(operand_dtype, *variant) <= di.max_lds;
+  int v = *variant;
+  if (!fits && rec != 0 && operand_dtype == 0 && v == 0 && rec + gemm_small_lds_bytes(0, 3) <= di.max_lds) { fits = true; v = 3; }
   const bool idle_cores = persistent_plan_info(rs, di.num_cus, di.max_lds, plan) && ((plan[2] + 15) / 16) * (plan[3] / 4) <= 2;
-  return (fits && (idle_cores || requested == 2)) ? kShare : kSerial;
+  if (!(fits && (idle_cores || requested == 2))) return kSerial;
+  *variant = v;
+  return kShare;
 }
 
 // first_piece: the descriptor's field (0 = default, -1 = passes not cut, otherwise the steps of piece 0)
@@ -289,7 +296,8 @@ int stack_forward(const rblstm_desc* d, const float* x, const float* const* para
   unsigned* flag = reinterpret_cast<unsigned*>(ws);
   void* recws = ws + kFlagBytes;
   const int T = d->T, B = d->B, H = d->H;
-  const OverlapMode mode = overlap_mode(rs, d->operand_dtype, persistent, sb != sa, d->overlap_mode);
+  int gv = d->gemm_variant;                      // the product kernels of this call (see overlap_mode)
+  const OverlapMode mode = overlap_mode(rs, d->operand_dtype, persistent, sb != sa, d->overlap_mode, &gv);
   if (mode == kSerial) sb = sa;
   const bool pipelined = mode != kSerial;
   const std::vector<int> pb = piece_bounds(T, pipelined, d->first_piece);
@@ -325,7 +333,7 @@ int stack_forward(const rblstm_desc* d, const float* x, const float* const* para
         g.M = (s1 - s0) * B; g.N = 4 * H; g.K = din;
         g.A = in + f0 * B * din; g.lda = din; g.B = params[6 * l + 3 * k + 0]; g.ldb = 4 * H;
         g.C = base + lay.zg[k] + f0 * B * 4 * H; g.ldc = 4 * H; g.bias = params[6 * l + 3 * k + 2];
-        g.naive = !persistent; g.operand_dtype = d->operand_dtype; g.variant = d->gemm_variant;
+        g.naive = !persistent; g.operand_dtype = d->operand_dtype; g.variant = gv;
         g.small_footprint = mode == kShare && pc > 0;   // the first piece's product runs while the chain waits for it
         if (mirrors) { g.A16 = in16; g.lda16 = din; g.transA16 = false; g.B16 = mir + ml.wt[k]; g.ldb16 = din; g.transB16 = true; }
         ProfScope ps(sb, 0, l, 1, 0, gemm_flop(g));
@@ -371,7 +379,8 @@ int stack_backward(const rblstm_desc* d, const float* x, const float* const* par
                    const float* dy_top, const float* y_top, float* const* grads, float* dx, float* res, char* ws,
                    hipStream_t sa, hipStream_t sb, bool persistent) {
   const RecShape rs = stack_rec_shape(d);
-  const OverlapMode mode = overlap_mode(rs, d->operand_dtype, persistent, sb != sa, d->overlap_mode);
+  int gv = d->gemm_variant;                      // the product kernels of this call (see overlap_mode)
+  const OverlapMode mode = overlap_mode(rs, d->operand_dtype, persistent, sb != sa, d->overlap_mode, &gv);
   if (mode == kSerial) sb = sa;
   int rc = RLSTM_OK;
   int resident_err = 0;
@@ -446,7 +455,7 @@ int stack_backward(const rblstm_desc* d, const float* x, const float* const* par
             g.A = base + lay.zg[k] + f0 * B * 4 * H; g.lda = 4 * H;
             g.B = params[6 * l + 3 * k + 0] + (size_t)tk * H * 4 * H; g.ldb = 4 * H;
             g.C = dxl + f0 * B * din + (size_t)tk * H; g.ldc = din; g.accumulate = (k == 1);
-            g.naive = !persistent; g.operand_dtype = d->operand_dtype; g.variant = d->gemm_variant;
+            g.naive = !persistent; g.operand_dtype = d->operand_dtype; g.variant = gv;
             g.small_footprint = mode == kShare && pc > 0;   // the first piece's product runs while the chain waits for it
             // ... and has too few tiles for the chip (128 at 128 steps x 32 sequences x 500 units): K is split as well
             if (pc == 0) { g.splitk_ws = skws; g.splitk_floats = skfloats; }
@@ -467,7 +476,7 @@ int stack_backward(const rblstm_desc* d, const float* x, const float* const* par
       g.transB = true;
       g.M = T * B; g.N = din; g.K = 8 * H;
       g.C = dxl; g.ldc = din;
-      g.operand_dtype = d->operand_dtype; g.variant = d->gemm_variant;
+      g.operand_dtype = d->operand_dtype; g.variant = gv;
       g.A16 = mir + ml.dzn; g.lda16 = 8 * H; g.transA16 = false; g.B16 = mir + ml.wn; g.ldb16 = 8 * H; g.transB16 = true;
       g.require_mem16 = true;
       ProfScope ps(sb, 3, l, 1, 0, gemm_flop(g));
@@ -481,7 +490,7 @@ int stack_backward(const rblstm_desc* d, const float* x, const float* const* par
           f.M = T * B; f.N = din; f.K = 4 * H;
           f.A = base + lay.zg[k]; f.lda = 4 * H; f.B = params[6 * l + 3 * k + 0]; f.ldb = 4 * H;
           f.C = dxl; f.ldc = din; f.accumulate = (k == 1);
-          f.operand_dtype = d->operand_dtype; f.variant = d->gemm_variant;
+          f.operand_dtype = d->operand_dtype; f.variant = gv;
           RLSTM_TRY(gemm(sb, f));
         }
       } else {
@@ -494,7 +503,7 @@ int stack_backward(const rblstm_desc* d, const float* x, const float* const* par
         g.M = T * B; g.N = din; g.K = 4 * H;
         g.A = base + lay.zg[k]; g.lda = 4 * H; g.B = params[6 * l + 3 * k + 0]; g.ldb = 4 * H;
         g.C = dxl; g.ldc = din; g.accumulate = (k == 1);
-        g.naive = !persistent; g.operand_dtype = d->operand_dtype; g.variant = d->gemm_variant;
+        g.naive = !persistent; g.operand_dtype = d->operand_dtype; g.variant = gv;
         ProfScope ps(sb, 3, l, 1, 0, gemm_flop(g));
         RLSTM_TRY(gemm(sb, g));
       }
@@ -504,7 +513,7 @@ int stack_backward(const rblstm_desc* d, const float* x, const float* const* par
       rc = weight_grads(sb, l, T, B, din, H, k == 0 ? 1 : -1, xin, din, yl + (size_t)k * H, 2 * H,
                         base + lay.zg[k], grads[6 * l + 3 * k + 0], grads[6 * l + 3 * k + 1], skws, skfloats,
                         !persistent, d->operand_dtype, mode == kShare && l > 0,     // layer 0's run after the last recurrent piece: nothing beside them
-                        d->gemm_variant, false, xt16, yt16 ? yt16 + (size_t)k * H * tb : nullptr, mirrors ? mir + ml.dzt[k] : nullptr);
+                        gv, false, xt16, yt16 ? yt16 + (size_t)k * H * tb : nullptr, mirrors ? mir + ml.dzt[k] : nullptr);
       if (rc != RLSTM_OK) return rc;
     }
     dy = dxl;
@@ -967,8 +976,9 @@ int lstm_stream_fwd_bwd(const rlstm_stream_desc* d, const float* x, const float*
   // for them, so they run beside the passes back through time of the layers below; the next segment's forward pass
   // of a layer waits for them before it overwrites what they read.  Only where a product workgroup fits on a CU
   // beside a workgroup of the persistent kernels (overlap_mode, as for the bidirectional stack).
+  int gv = d->gemm_variant;                      // the product kernels of this call (see overlap_mode)
   hipStream_t sw = hip_stream_b ? static_cast<hipStream_t>(hip_stream_b) : st;
-  if (sw != st && overlap_mode(rs, d->operand_dtype, persistent, true, 2) != kShare) sw = st;
+  if (sw != st && overlap_mode(rs, d->operand_dtype, persistent, true, 2, &gv) != kShare) sw = st;
   const bool two = sw != st;
   EventList evs;
   std::vector<hipEvent_t> wdone(L, nullptr);   // weight gradients of the previous segment's layer l are done
@@ -1009,7 +1019,7 @@ int lstm_stream_fwd_bwd(const rlstm_stream_desc* d, const float* x, const float*
       GemmCall g;
       g.M = Tc * B; g.N = 4 * H; g.K = din;
       g.A = in; g.lda = din; g.B = params[3 * l + 0]; g.ldb = 4 * H; g.C = base + lay.zg; g.ldc = 4 * H;
-      g.bias = params[3 * l + 2]; g.naive = !persistent; g.operand_dtype = d->operand_dtype; g.variant = d->gemm_variant;
+      g.bias = params[3 * l + 2]; g.naive = !persistent; g.operand_dtype = d->operand_dtype; g.variant = gv;
       {
         ProfScope ps(st, 0, l, 1, 0, gemm_flop(g));
         RLSTM_TRY(gemm(st, g));
@@ -1039,9 +1049,9 @@ int lstm_stream_fwd_bwd(const rlstm_stream_desc* d, const float* x, const float*
       RLSTM_TRY(accumulate(st, grads[3 * l + 2], dbtmp, (size_t)4 * H, s == 0));
       RLSTM_TRY(evs.order(st, sw));                 // d a of this layer is complete
       rc = weight_grads(sw, l, Tc, B, dl, H, 1, xin, dl, yl, H, base + lay.zg, grads[3 * l + 0], grads[3 * l + 1], skws,
-                        lay.splitk_floats, !persistent, d->operand_dtype, two && l > 0, d->gemm_variant, s > 0);
+                        lay.splitk_floats, !persistent, d->operand_dtype, two && l > 0, gv, s > 0);
       if (rc != RLSTM_OK) return rc;
-      rc = h0_term(sw, persistent, d->operand_dtype, d->gemm_variant, Tc, B, H, 1, h0, base + lay.zg, slens, grads[3 * l + 1]);
+      rc = h0_term(sw, persistent, d->operand_dtype, gv, Tc, B, H, 1, h0, base + lay.zg, slens, grads[3 * l + 1]);
       if (rc != RLSTM_OK) return rc;
       if (two) {
         hipEvent_t ev;
@@ -1056,7 +1066,7 @@ int lstm_stream_fwd_bwd(const rlstm_stream_desc* d, const float* x, const float*
         g.transB = true;
         g.M = Tc * B; g.N = dl; g.K = 4 * H;
         g.A = base + lay.zg; g.lda = 4 * H; g.B = params[3 * l + 0]; g.ldb = 4 * H; g.C = dxl; g.ldc = dl;
-        g.naive = !persistent; g.operand_dtype = d->operand_dtype; g.variant = d->gemm_variant;
+        g.naive = !persistent; g.operand_dtype = d->operand_dtype; g.variant = gv;
         ProfScope ps(st, 3, l, 1, 0, gemm_flop(g));
         RLSTM_TRY(gemm(st, g));
       }

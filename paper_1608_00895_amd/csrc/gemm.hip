@@ -2012,8 +2012,9 @@ hipError_t to_bf16(hipStream_t stream, const float* src, unsigned short* dst, si
   return hipGetLastError();
 }
 
-size_t gemm_small_lds_bytes(int operand_dtype) {
-  return operand_dtype == 1 ? (size_t)2 * (TM + TN) * LDK * sizeof(unsigned short) : gemm_3xbf16_lds_bytes();
+size_t gemm_small_lds_bytes(int operand_dtype, int variant) {
+  if (operand_dtype == 1) return (size_t)2 * (TM + TN) * LDK * sizeof(unsigned short);
+  return variant == 0 ? gemm_3xbf16_lds_bytes() : (size_t)4 * 16 * LDT * sizeof(float);
 }
 
 }  // namespace rlstm

@@ -111,7 +111,7 @@ size_t persistent_scratch_bytes(const RecShape& s);
 // LDS a workgroup of the persistent kernels requests (larger of forward / backward); 0: shape not supported
 size_t persistent_lds_bytes(const RecShape& s, int num_cus, size_t max_lds);
 // LDS of the matrix-product kernel that can share a CU with other work (128 x 128 tiles)
-size_t gemm_small_lds_bytes(int operand_dtype);
+size_t gemm_small_lds_bytes(int operand_dtype, int variant);
 // {groups, sequences per group, rows a group can hold, units per workgroup, forward members, backward members, Hp,
 //  Hq (two exchanges) or padded H of the backward product (one), exchanges per backward step, 0}
 bool persistent_plan_info(const RecShape& s, int num_cus, size_t max_lds, int out[10]);

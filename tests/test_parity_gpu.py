@@ -114,8 +114,8 @@ def test_small_stack(engine):
 
 def test_stack_one_stream_and_no_dx_match_two_streams():
     """The schedule changes no result beyond rounding: with two streams the products run beside the recurrent
-    kernels and use the plain matrix-product kernel, with one stream the pipelined one (another summation order
-    over k), and the two-stream pass adds the bias gradient piece by piece."""
+    kernels with one slab in flight, with one stream with two (the same sums in the same order), and the two-stream
+    pass adds the bias gradient piece by piece."""
     wl = synth.small_blstm(seed=12, L=2, B=7, D=9, H=24, len_lo=2, len_hi=30)
     a = gh.StackRun(wl, two_streams=True)
     a.step()
@@ -147,10 +147,32 @@ def test_overlap_modes_against_oracle(mode):
         assert gh.rel_err(g1, g2) < TOL_GRAD
     # tuning values outside their ranges are refused before anything is enqueued
     for bad in (dict(overlap_mode=3), dict(overlap_mode=-1), dict(first_piece=-2), dict(batch_groups=9), dict(bwd_exchange=3),
-                dict(gemm_variant=-1)):
+                dict(gemm_variant=-1), dict(gemm_variant=4)):
         d = rl.rblstm_desc(L=wl.L, T=wl.T, B=wl.B, D=wl.D, H=wl.H, operand_dtype=0, engine=0, **bad)
         assert rl.rblstm_workspace_bytes(d) == 0, bad
         assert rl.blstm_stack_fwd(d, run.x, run.params, run.seq_lens, run.y_top, run.reserve, run.ws, None, check=False) == -3, bad
+
+
+def test_shared_call_where_only_the_fp32_instruction_products_fit_beside_the_recurrent_kernels():
+    """640 units per direction: the recurrent workgroups hold 100 KB of LDS, so the default product kernel for fp32
+    operands (three bf16 parts, 72 KB) does not fit on a CU beside them; a two-stream call then shares the CUs with the
+    kernels on the fp32 matrix instructions (33 KB) instead of falling back to the serial schedule.  Against the
+    oracle, and bit-equal to the same call with those kernels asked for by gemm_variant 3."""
+    wl = synth.make_workload("wide_shared", L=2, B=16, D=24, H=640, len_lo=40, len_hi=200, wscale=0.05, seed=43)
+    ref = gh.oracle_stack(wl)
+    run = gh.StackRun(wl, engine=rl.RLSTM_ENGINE_PERSISTENT, two_streams=True, overlap_mode=2, first_piece=64)
+    run.step()
+    got = run.results()
+    assert gh.rel_err(got["y"], ref["y"]) < TOL_FWD
+    assert gh.rel_err(got["dx"], ref["dx"]) < TOL_GRAD
+    for g1, g2 in zip(got["grads"], ref["grads"]):
+        assert gh.rel_err(g1, g2) < TOL_GRAD
+    same = gh.StackRun(wl, engine=rl.RLSTM_ENGINE_PERSISTENT, two_streams=True, overlap_mode=2, first_piece=64, gemm_variant=3)
+    same.step()
+    again = same.results()
+    assert np.array_equal(again["y"], got["y"]) and np.array_equal(again["dx"], got["dx"])
+    for g1, g2 in zip(again["grads"], got["grads"]):
+        assert np.array_equal(g1, g2)
 
 
 def test_config2_blstm():
