@@ -1215,7 +1215,7 @@ struct SlabFeederBf {
 // Pipelined form of the three-part kernel (gemm_f32_3xbf16_kernel): range-checked buffer loads without branches, so
 // that the wait before a slab's way into LDS counts only that slab's loads; D slabs on their way from memory at any
 // time (slab s waits in register stage s % D); the cutting and the LDS stores of slab s+1 and the loads of slab
-// s+1+D are dealt out between the matrix instructions of slab s.  One such workgroup per CU, as beside the recurrent
+// s+1+D are dealt out between the 24 matrix instructions of slab s, a few behind each (sched_group_barrier).  One such workgroup per CU, as beside the recurrent
 // kernels, then keeps its matrix cores fed by itself.
 // ---------------------------------------------------------------------------
 template <bool KC, int D>
@@ -1355,20 +1355,28 @@ __global__ __launch_bounds__(256) void gemm_f32_3xbf16_v2_kernel(GemmP p) {
       }
     // small terms first; the four tiles alternate so that no instruction waits for the one before it
     constexpr int QA[6] = {2, 0, 1, 1, 0, 0}, QB[6] = {0, 2, 1, 0, 1, 0};
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int t = 0; t < 6; ++t) {
+    for (int t = 0; t < 6; ++t)
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[QA[t]][i], bfr[QB[t]][j], acc[i][j], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-      // the next slab's way into LDS and the loads of the slab D after it, between the matrix instructions
-      if (t == 0) fa.store(next, as_next);
-      if (t == 1) fb.store(next, bs_next);
-      if (t == 2) { fa.load(next, s + 1 + D); fb.load(next, s + 1 + D); }
-      __builtin_amdgcn_sched_barrier(0);
+    // the next slab's way into LDS and the loads of the slab D after it
+    fa.store(next, as_next);
+    fb.store(next, bs_next);
+    fa.load(next, s + 1 + D); fb.load(next, s + 1 + D);
+    // order of issue: one matrix instruction, then in its shadow a share of the cutting (5 vector instructions) and
+    // one LDS store; the four loads behind the last four matrix instructions
+#pragma unroll
+    for (int g = 0; g < 24; ++g) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+      __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+      if (g >= 20) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
     }
+    __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
   };
   // whole rounds of D slabs without a branch inside (a branch would make the wait before a stage's way into LDS
@@ -1747,7 +1755,7 @@ hipError_t launch_3xbf16_k(K kernel, hipStream_t stream, const GemmP& p, dim3 gr
 // buffer_loads: both operands made of whole, 16-byte aligned float4s and panels within 31-bit byte offsets.
 // beside: the product shares its CUs with the recurrent kernels.  One slab in flight then: measured on the 4 x 500
 // stack, two slabs in flight make the products a fifth faster and every recurrent step slower (54.1 against 52.8 ms
-// per call), and the kernel keeps to 152 registers, which fit beside two wavefronts of any of the recurrent kernels.
+// per call), and the kernel keeps to 160 registers, which fit beside two wavefronts of any of the recurrent kernels that share CUs.
 template <bool TA, bool TB>
 hipError_t launch_3xbf16(hipStream_t stream, const GemmP& p, dim3 grid, bool vec, bool buffer_loads, bool beside) {
   if (buffer_loads && beside) return launch_3xbf16_k(gemm_f32_3xbf16_v2_kernel<TA, TB, 1>, stream, p, grid);
