@@ -42,10 +42,13 @@ def products_note(operand_dtype, gemm_variant):
     return "fp32 operands, fp32 matrix instructions"
 
 
-def mfma_peak(kernel, operand_dtype, gemm_variant):
-    """(peak TFLOP/s, what it is) for the counted FLOP of one of the library's kernel groups."""
+def mfma_peak(kernel, operand_dtype, gemm_variant, recurrent_form=0):
+    """(peak TFLOP/s, what it is) for the counted FLOP of one of the library's kernel groups.  recurrent_form: the plan's
+    form of the recurrent product's operands (2: three bf16 parts)."""
     if operand_dtype == 1:
         return PEAK_BF16_MFMA_TFLOPS, "bf16 matrix instructions"
+    if kernel in ("recurrent_forward", "recurrent_backward") and recurrent_form == 2:
+        return PEAK_F32_AS_3XBF16_TFLOPS, "bf16 matrix instructions, six per fp32 product (operands exchanged and kept as three bf16 parts)"
     if kernel in PRODUCT_KERNELS and not gemm_variant:
         return PEAK_F32_AS_3XBF16_TFLOPS, "bf16 matrix instructions, six per fp32 product (operands cut into three bf16 parts)"
     return PEAK_FP32_MFMA_TFLOPS, "fp32 matrix instructions"
@@ -656,13 +659,18 @@ def main():
         d["launches"] += 1
         d["flop"] += flop
         d["rsteps"] += nsteps
+    try:
+        plan_now = rl.rblstm_plan(desc) if args.engine in (0, 1) else None
+    except rl.RlstmError:
+        plan_now = None
+    rec_form = plan_now["recurrent_operand_form"] if plan_now else 0
     kernels = []
     for kind, d in sorted(by_kind.items()):
         e = {"kernel": rl.PROFILE_KINDS[kind], "launches_per_step": d["launches"] / hook_steps,
              "avg_ms": d["ms"] / d["launches"], "ms_per_step": d["ms"] / hook_steps,
              "tflops": d["flop"] / (d["ms"] * 1e-3) / 1e12}
         # fraction of the matrix cores' peak for the instructions the kernel runs on (MFMA utilisation by throughput)
-        e["mfma_peak_tflops"], e["mfma_path"] = mfma_peak(e["kernel"], wl.operand_dtype, args.gemm_variant)
+        e["mfma_peak_tflops"], e["mfma_path"] = mfma_peak(e["kernel"], wl.operand_dtype, args.gemm_variant, rec_form)
         e["frac_of_mfma_peak"] = e["tflops"] / e["mfma_peak_tflops"]
         if kind in (1, 2):
             # a pass over the T steps may be cut into several launches
@@ -676,16 +684,12 @@ def main():
     # profiles/hbm_traffic.json (default settings only; scaled by the copy kernel)
     default_knobs = (args.first_piece is None and args.batch_groups is None and not args.one_stream and args.engine == 0
                      and args.overlap_mode is None and args.bwd_exchange is None and args.gemm_variant is None)
-    try:
-        plan_now = rl.rblstm_plan(desc) if args.engine in (0, 1) else None
-    except rl.RlstmError:
-        plan_now = None
     if default_knobs:
         traffic, traffic_source = recorded_traffic(args.workload, dom["kernel"], rl.version(), plan_now)
     else:
         traffic, traffic_source = None, "not reported with non-default settings"
-    peak = PEAK_FP32_MFMA_TFLOPS if wl.operand_dtype == 0 else PEAK_BF16_MFMA_TFLOPS
-    roofline = {"kernel": dom["kernel"], "bound": "mfma", "achieved": dom["tflops"], "peak": peak,
+    peak = dom["mfma_peak_tflops"]
+    roofline = {"kernel": dom["kernel"], "bound": "mfma", "achieved": dom["tflops"], "peak": peak, "mfma_path": dom["mfma_path"],
                 "unit": "TFLOP/s", "frac": dom["tflops"] / peak,
                 "traffic": traffic, "traffic_source": traffic_source,
                 "avg_launch_ms": dom["avg_ms"],
@@ -726,7 +730,7 @@ def main():
     if args.engine in (0, 1):
         try:
             plan = rl.rblstm_plan(desc)
-            es = 2 if wl.operand_dtype == 1 else 4
+            es = 2 if wl.operand_dtype == 1 else (6 if plan["recurrent_operand_form"] == 2 else 4)
             ng, bp, u = plan["groups"], max(16, plan["rows"]), plan["units_per_workgroup"]
             def floor(members, tile, read):
                 wsf = torch.empty(rl.rlstm_exchange_floor_bytes(ng, members, tile), dtype=torch.uint8, device=dev)

@@ -121,6 +121,10 @@ typedef struct rlstm_desc {
  *                 (both operands made of whole, 16-byte aligned float4s), 2 the plain kernel, 3 the pipelined kernel
  *                 where its conditions hold and the product does not run beside the recurrent kernels on the same CUs.
  *                 Products of bf16 operands (operand_dtype 1) ignore 3.
+ *                 The recurrent kernels follow: with fp32 operands and groups of more than 16 sequences (two or
+ *                 more 16-row tiles per workgroup, H <= 512) they exchange h_t / d a_t and keep R as three bf16
+ *                 parts each and form the recurrent product the same way; 3 keeps them on the fp32 matrix
+ *                 instructions.  Groups of up to 16 sequences always use those.
  *   first_piece   (stack descriptors) with two streams and the persistent engine each layer's recurrent pass is cut
  *                 into pieces of first_piece, first_piece, 2 first_piece, 4 first_piece, ... steps, and the matrix
  *                 product that feeds a piece runs on stream b while stream a is inside the piece before it.
@@ -486,8 +490,9 @@ RLSTM_API int rlstm_adam_step(float* param, const float* grad, float* m, float* 
  * rows a group's tiles hold, units per workgroup, workgroups per group in the forward kernel,
  * workgroups per group in the backward kernel, padded H of the forward product, units per K
  * quarter of the backward product (two exchanges per step) or its padded H (one exchange), exchanges
- * per step of the backward pass (the bwd_exchange tuning field), 0}.  RLSTM_ERESIDENT if the persistent
- * engine cannot hold the shape.
+ * per step of the backward pass (the bwd_exchange tuning field), form of the recurrent product's operands:
+ * 0 fp32 values on the fp32 matrix instructions, 1 values rounded to bf16, 2 fp32 values as three bf16
+ * parts each}.  RLSTM_ERESIDENT if the persistent engine cannot hold the shape.
  */
 RLSTM_API int rblstm_plan(const rblstm_desc* d, int32_t* out);
 

@@ -444,7 +444,7 @@ def rblstm_plan(desc) -> dict:
     if rc != 0:
         raise RlstmError(rc, "rblstm_plan")
     keys = ("groups", "sequences_per_group", "rows", "units_per_workgroup", "members_fwd", "members_bwd", "Hp", "Hq",
-            "bwd_exchanges_per_step")
+            "bwd_exchanges_per_step", "recurrent_operand_form")
     return dict(zip(keys, [int(v) for v in out]))
 
 

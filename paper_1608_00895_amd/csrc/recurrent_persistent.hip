@@ -272,6 +272,73 @@ __device__ __forceinline__ void wave_product_bf(const void* xblock, int xblock_b
   }
 }
 
+// ---- three-part variant (fp32 operands, groups of more than 16 sequences): the exchanged h_t / d a_t and the
+// resident R / R^T are each kept as THREE bf16 parts that add up to the fp32 value exactly (its 24 significant bits
+// cut 8 + 8 + 8), and the product is the sum of the six largest of the nine part products, as in the large matrix
+// products (gemm_f32_3xbf16_kernel): 6 v_mfma_f32_16x16x32_bf16 do the work of 8 v_mfma_f32_16x16x4_f32 in 3/8 of
+// the matrix cores' time; what is left out is below 2^-21 of each term.  With two or three 16-row tiles per workgroup
+// the matrix instructions are a third of the step, which is where this pays; with one tile the 1.5 x larger
+// exchange costs what the shorter instructions save, and the fp32 kernels stay.
+// Layouts: as the bf16 variant, once per part - a wavefront's exchange block is [part][chunk][lane][16 bytes], the
+// resident matrix [part][k/8][columns][8].
+__device__ __forceinline__ void cut3_bits(float x, unsigned& b1, unsigned& b2, unsigned& b3) {
+  const unsigned a1 = __float_as_uint(x) & 0xffff0000u;
+  const float r = x - __uint_as_float(a1);                    // exact
+  const unsigned a2 = __float_as_uint(r) & 0xffff0000u;
+  const float r2 = r - __uint_as_float(a2);                   // exact, at most 8 significant bits
+  b1 = a1 >> 16; b2 = a2 >> 16; b3 = __float_as_uint(r2) >> 16;
+}
+
+// nchp: chunks per part; bplane: bf16 elements between the parts of the resident matrix.  All chunks of a K range of
+// up to 4 k-steps (a quarter of 512 units) are requested at once, 3 * 4 * MT of them.
+template <int MT, int NT>
+__device__ __forceinline__ void wave_product_3(const void* xblock, int xblock_bytes, int nchp, const unsigned short* bs,
+                                               int bplane, floatx4 (&acc)[MT][NT]) {
+  constexpr int ldn = 16 * NT;
+  constexpr int KG = 4;                            // k-steps per group of loads
+  const int lane = threadIdx.x & 63, l16 = lane & 15, lq = lane >> 4;
+  __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(xblock), 0, xblock_bytes, 0x00020000);
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+  const int nks = nchp / MT;
+  for (int k0 = 0; k0 < nks; k0 += KG) {
+    intx4 v[3][KG * MT];
+#pragma unroll
+    for (int part = 0; part < 3; ++part)
+#pragma unroll
+      for (int q = 0; q < KG * MT; ++q) {
+        // a chunk past the part's last one is given an offset beyond the block and reads zeros
+        const int c = k0 * MT + q;
+        const unsigned off = c < nchp ? (unsigned)(((part * nchp + c) * 64 + lane) * 16) : 0x80000000u;
+        v[part][q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, kAuxSc1);
+      }
+#pragma unroll
+    for (int kk = 0; kk < KG; ++kk) {
+      const int ks = k0 + kk;
+      if (ks < nks) {
+        bf16x8 bfrag[3][NT];
+#pragma unroll
+        for (int part = 0; part < 3; ++part)
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+            bfrag[part][nt] = *reinterpret_cast<const bf16x8*>(bs + (size_t)part * bplane + ((size_t)(ks * 4 + lq) * ldn + nt * 16 + l16) * 8);
+        // small terms first; the tiles alternate so that no instruction waits for the one before it
+        constexpr int QA[6] = {2, 0, 1, 1, 0, 0}, QB[6] = {0, 2, 1, 0, 1, 0};
+#pragma unroll
+        for (int t = 0; t < 6; ++t)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+              acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v[QA[t]][kk * MT + mt]), bfrag[QB[t]][nt],
+                                                                   acc[mt][nt], 0, 0, 0);
+      }
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------
 // forward
 // ---------------------------------------------------------------------------
@@ -308,8 +375,10 @@ struct PFwdParams {
 constexpr int kBlockThreads = 320;
 
 // ROWS: sequences a group can hold (8, 16, 32, 48 or 64); 8 uses half of one 16-row MFMA tile.
-template <int ROWS, int NT, bool BF>
+// PREC: 0 fp32 matrix instructions, 1 operands rounded to bf16, 2 fp32 operands as three bf16 parts
+template <int ROWS, int NT, int PREC>
 __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwdParams p) {
+  constexpr bool BF = PREC == 1, P3 = PREC == 2;
   constexpr int MT = ROWS <= 16 ? 1 : ROWS / 16;
   constexpr bool HALF = ROWS == 8;
   constexpr int U = 4 * NT, NC = 16 * NT;
@@ -330,9 +399,9 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
   // the step chain is latency-bound: its wavefronts go before those of any kernel sharing the CU
   __builtin_amdgcn_s_setprio(3);
   const int u0 = wg * U;
-  float* Rs = lds;                               // fp32: [Hp][NC]; bf16: [Hp/8][NC][8] (half the size)
+  float* Rs = lds;                               // fp32: [Hp][NC]; bf16: [Hp/8][NC][8] (half the size); three parts: 3 of those
   unsigned short* Rsb = reinterpret_cast<unsigned short*>(lds);
-  float* Red = Rs + (size_t)Hp * NC / (BF ? 2 : 1);   // [4][MT][NT][256]
+  float* Red = Rs + (size_t)Hp * NC * (P3 ? 3 : (BF ? 1 : 2)) / 2;   // [4][MT][NT][256]
   float* zin = Red + 4 * MT * NT * 256;          // [2][4][NE]  input part of the frame, per gate
   float* gout = zin + 2 * 4 * NE;                // [2][6][NE]  gates i,f,o,g, y, c of the frame
   int* failed = reinterpret_cast<int*>(gout + 2 * 6 * NE);   // raised when a bounded wait expired
@@ -347,11 +416,17 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
     const int k = idx / NC, col = idx % NC;
     const int g = col / U, u = u0 + col % U;
     const float v = (k < H && u < H) ? D.R[(size_t)k * 4 * H + g * H + u] : 0.f;
-    if (BF) Rsb[((size_t)(k >> 3) * NC + col) * 8 + (k & 7)] = bf16_bits(v);
+    if (P3) {
+      unsigned b1, b2, b3;
+      cut3_bits(v, b1, b2, b3);
+      unsigned short* q = Rsb + ((size_t)(k >> 3) * NC + col) * 8 + (k & 7);
+      q[0] = (unsigned short)b1; q[(size_t)Hp * NC] = (unsigned short)b2; q[(size_t)2 * Hp * NC] = (unsigned short)b3;
+    } else if (BF) Rsb[((size_t)(k >> 3) * NC + col) * 8 + (k & 7)] = bf16_bits(v);
     else Rs[k * NC + rotated_col<NT>(k, col)] = v;
   }
 
   const int KW = Hp / 4;                         // rows of h per wavefront
+  const int nchp = nch / 3;                      // three parts: chunks per part
   const int wbytes = nch * 1024;                 // bytes of one wavefront's operand block (64 lanes x 16 bytes per chunk)
   const size_t hxsz = (size_t)4 * wbytes;        // bytes of one step buffer
   char* const hxbase = static_cast<char*>(p.hx[grp]);
@@ -375,8 +450,8 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
         if (D.c0) creg[e] = D.c0[bu];
       }
       elen[e] = min(max(p.seq_lens[b0 + eb[e]], 0), T);
-      eslot[e] = BF ? (eu[e] / KW) * (wbytes / 2) + operand_slot_bf<MT>(eu[e] % KW, eb[e])
-                    : (eu[e] / KW) * (wbytes / 4) + operand_slot<MT>(eu[e] % KW, eb[e]);
+      eslot[e] = (BF || P3) ? (eu[e] / KW) * (wbytes / 2) + operand_slot_bf<MT>(eu[e] % KW, eb[e])
+                            : (eu[e] / KW) * (wbytes / 4) + operand_slot<MT>(eu[e] % KW, eb[e]);
     }
   }
   // I/O lanes: the pairs they move
@@ -441,7 +516,8 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
       // h of the previous step: wait for the producers of this wavefront's rows, then h_prev * R
       if (s > 0 && !wave_wait_flags(myflags, prod_first, prod_count, p.Gf, (unsigned)s, p.err, p.wait_ticks)) fail = 1;
       floatx4 acc[MT][NT];
-      if (BF) wave_product_bf<MT, NT, HALF, false>(hprev + (size_t)wave * wbytes, wbytes, nch, Rsb + (size_t)wave * KW * NC, acc);
+      if (P3) wave_product_3<MT, NT>(hprev + (size_t)wave * wbytes, wbytes, nchp, Rsb + (size_t)wave * KW * NC, Hp * NC, acc);
+      else if (BF) wave_product_bf<MT, NT, HALF, false>(hprev + (size_t)wave * wbytes, wbytes, nch, Rsb + (size_t)wave * KW * NC, acc);
       else wave_product<MT, NT, HALF>(reinterpret_cast<const float*>(hprev + (size_t)wave * wbytes), wbytes, nch,
                                       Rs + (size_t)wave * KW * NC, acc);
 #pragma unroll
@@ -491,7 +567,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
         const float hn = go * ftanh(cn);
         const bool valid = t < elen[e];
         if (valid) { creg[e] = cn; hreg[e] = hn; }
-        if (!BF) st_dev(reinterpret_cast<float*>(hcur) + eslot[e], hreg[e]);
+        if (!BF && !P3) st_dev(reinterpret_cast<float*>(hcur) + eslot[e], hreg[e]);
         ocur[0 * NE + j] = gi; ocur[1 * NE + j] = gf; ocur[2 * NE + j] = go; ocur[3 * NE + j] = gg;
         ocur[4 * NE + j] = valid ? hn : 0.f;
         ocur[5 * NE + j] = creg[e];
@@ -504,6 +580,21 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_fwd_persistent_kernel(PFwd
           const unsigned other = __shfl_xor(mine, 1);
           if (ev[e] && !(eu[e] & 1))
             st_dev(reinterpret_cast<unsigned*>(hcur) + (eslot[e] >> 1), mine | (other << 16));
+        }
+      }
+      if (P3) {
+        // the same pairs, once per part (a part's chunks are nchp * 1024 bytes on)
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+          unsigned m1 = 0u, m2 = 0u, m3 = 0u;
+          if (ev[e]) cut3_bits(hreg[e], m1, m2, m3);
+          const unsigned o1 = __shfl_xor(m1, 1), o2 = __shfl_xor(m2, 1), o3 = __shfl_xor(m3, 1);
+          if (ev[e] && !(eu[e] & 1)) {
+            unsigned* dst = reinterpret_cast<unsigned*>(hcur) + (eslot[e] >> 1);
+            st_dev(dst, m1 | (o1 << 16));
+            st_dev(dst + nchp * 256, m2 | (o2 << 16));
+            st_dev(dst + 2 * nchp * 256, m3 | (o3 << 16));
+          }
         }
       }
       wait_stores_acked();
@@ -555,8 +646,9 @@ struct PBwdParams {
 // Same workgroup shape as the forward kernel: 4 compute wavefronts + 1 I/O wavefront that stages
 // the frame's gates, cell states and dy from HBM into LDS one step ahead and writes d a back to
 // HBM one step behind.
-template <int ROWS, int NT, bool BF>
+template <int ROWS, int NT, int PREC>
 __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwdParams p) {
+  constexpr bool BF = PREC == 1, P3 = PREC == 2;
   constexpr int MT = ROWS <= 16 ? 1 : ROWS / 16;
   constexpr bool HALF = ROWS == 8;
   constexpr int U = 4 * NT, UG = 16 * NT, Bp = 16 * MT;
@@ -579,7 +671,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
   const int u0 = wg * U;                         // owned units
   float* RTs = lds;                              // fp32: [4*Hq][UG]; bf16: [4*Hq/8][UG][8] (half the size)
   unsigned short* RTb = reinterpret_cast<unsigned short*>(lds);
-  float* Red = RTs + (size_t)4 * Hq * UG / (BF ? 2 : 1);   // [4][MT][NT][256]
+  float* Red = RTs + (size_t)4 * Hq * UG * (P3 ? 3 : (BF ? 1 : 2)) / 2;   // [4][MT][NT][256]
   float* bin = Red + 4 * MT * NT * 256;          // [2][7][NE]  gates i,f,o,g, c, c_prev, dy of the frame
   float* dzo = bin + 2 * 7 * NE;                 // [2][4][NE]  d a of the frame
   int* failed = reinterpret_cast<int*>(dzo + 2 * 4 * NE);   // two words raised when a bounded wait expired
@@ -602,10 +694,16 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
     const int uk = qq * Hq + w * UW + (rr >> 2), g = rr & 3;
     const int un = pg * UG + n;
     const float v = (uk < H && un < H) ? D.R[(size_t)un * 4 * H + g * H + uk] : 0.f;
-    if (BF) RTb[((size_t)(r >> 3) * UG + n) * 8 + (r & 7)] = bf16_bits(v);
+    if (P3) {
+      unsigned b1, b2, b3;
+      cut3_bits(v, b1, b2, b3);
+      unsigned short* q = RTb + ((size_t)(r >> 3) * UG + n) * 8 + (r & 7);
+      q[0] = (unsigned short)b1; q[(size_t)4 * Hq * UG] = (unsigned short)b2; q[(size_t)8 * Hq * UG] = (unsigned short)b3;
+    } else if (BF) RTb[((size_t)(r >> 3) * UG + n) * 8 + (r & 7)] = bf16_bits(v);
     else RTs[r * UG + rotated_col<NT>(r, n)] = v;
   }
 
+  const int nchp = nch / 3;                      // three parts: chunks per part
   const int wbytes = nch * 1024;                 // bytes per (quarter, wavefront) operand block
   const size_t xsz = (size_t)16 * wbytes;        // bytes of one step buffer
   char* const dzbase = static_cast<char*>(p.dzx[grp]);
@@ -638,8 +736,8 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
       }
       // d a of unit u, gate g sits in quarter u/Hq, wavefront (u%Hq)/UW, row ((u%Hq)%UW)*4 + g
       const int ul = eu[e] % Hq;
-      eslot[e] = BF ? ((eu[e] / Hq) * 4 + ul / UW) * (wbytes / 2) + operand_slot_bf<MT>((ul % UW) * 4, eb[e])
-                    : ((eu[e] / Hq) * 4 + ul / UW) * (wbytes / 4) + operand_slot<MT>((ul % UW) * 4, eb[e]);
+      eslot[e] = (BF || P3) ? ((eu[e] / Hq) * 4 + ul / UW) * (wbytes / 2) + operand_slot_bf<MT>((ul % UW) * 4, eb[e])
+                            : ((eu[e] / Hq) * 4 + ul / UW) * (wbytes / 4) + operand_slot<MT>((ul % UW) * 4, eb[e]);
     }
   }
 
@@ -799,10 +897,24 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
           __hip_atomic_store(reinterpret_cast<unsigned long long*>(dzcur) + (eslot[e] >> 2), w, __ATOMIC_RELAXED,
                              __HIP_MEMORY_SCOPE_AGENT);
         }
+        if (P3) {
+          // the same 8-byte word of four gates, once per part (a part's chunks are nchp * 1024 bytes on)
+          unsigned long long w1 = 0ull, w2 = 0ull, w3 = 0ull;
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            unsigned b1, b2, b3;
+            cut3_bits(dz[g], b1, b2, b3);
+            w1 |= (unsigned long long)b1 << (16 * g); w2 |= (unsigned long long)b2 << (16 * g); w3 |= (unsigned long long)b3 << (16 * g);
+          }
+          unsigned long long* dst = reinterpret_cast<unsigned long long*>(dzcur) + (eslot[e] >> 2);
+          __hip_atomic_store(dst, w1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_store(dst + nchp * 128, w2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_store(dst + 2 * nchp * 128, w3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           // fp32: rows (unit, gate 0..3) are 16 lanes apart in operand order
-          if (!BF) st_dev(reinterpret_cast<float*>(dzcur) + eslot[e] + g * 64, dz[g]);
+          if (!BF && !P3) st_dev(reinterpret_cast<float*>(dzcur) + eslot[e] + g * 64, dz[g]);
           out[g * NE + j] = dz[g];
           dbacc[e][g] += dz[g];
         }
@@ -826,7 +938,8 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_persistent_kernel(PBwd
     if (!is_io && qq < nq) {
       if (!wave_wait_flags(myflags, prod_first, prod_count, Gb, (unsigned)(s + 1), p.err, p.wait_ticks)) fail = 1;
       floatx4 acc[MT][NT];
-      if (BF) wave_product_bf<MT, NT, HALF, true>(dzcur + (size_t)(qq * 4 + wave) * wbytes, wbytes, nch, RTb + (size_t)wave * Hq * UG, acc);
+      if (P3) wave_product_3<MT, NT>(dzcur + (size_t)(qq * 4 + wave) * wbytes, wbytes, nchp, RTb + (size_t)wave * Hq * UG, 4 * Hq * UG, acc);
+      else if (BF) wave_product_bf<MT, NT, HALF, true>(dzcur + (size_t)(qq * 4 + wave) * wbytes, wbytes, nch, RTb + (size_t)wave * Hq * UG, acc);
       else wave_product<MT, NT, HALF>(reinterpret_cast<const float*>(dzcur + (size_t)(qq * 4 + wave) * wbytes), wbytes, nch,
                                       RTs + (size_t)wave * Hq * UG, acc);
 #pragma unroll
@@ -1241,7 +1354,7 @@ __global__ __launch_bounds__(kBlockThreads) void lstm_bwd_onehop_kernel(PBwd1Par
 struct PrepParams {
   unsigned* zero_words; size_t nzero;             // flags + exchange (+ partial tiles) of all groups
   void* hx1[kMaxGroups]; const float* h0[2];      // forward only: buffer 1 of each group's h exchange, h0 or null
-  int ndir, B, Bg, H, KW, wbytes, MT, bf;
+  int ndir, B, Bg, H, KW, wbytes, MT, prec;   // prec: 0 fp32, 1 bf16, 2 three bf16 parts (see the kernels)
 };
 __global__ __launch_bounds__(256) void prep_kernel(PrepParams p) {
   const size_t gtid = (size_t)blockIdx.x * 256 + threadIdx.x, gsz = (size_t)gridDim.x * 256;
@@ -1258,12 +1371,19 @@ __global__ __launch_bounds__(256) void seed_h0_kernel(PrepParams p) {
     void* hx1 = p.hx1[bgi * p.ndir + d];
     const int k = u % p.KW;
     int slot;
-    if (p.bf) {
+    if (p.prec != 0) {
       if (p.MT == 1) slot = operand_slot_bf<1>(k, b);
       else if (p.MT == 2) slot = operand_slot_bf<2>(k, b);
       else if (p.MT == 3) slot = operand_slot_bf<3>(k, b);
       else slot = operand_slot_bf<4>(k, b);
-      static_cast<unsigned short*>(hx1)[(size_t)(u / p.KW) * (p.wbytes / 2) + slot] = bf16_bits(p.h0[d][gtid]);
+      unsigned short* dst = static_cast<unsigned short*>(hx1) + (size_t)(u / p.KW) * (p.wbytes / 2) + slot;
+      if (p.prec == 1) *dst = bf16_bits(p.h0[d][gtid]);
+      else {
+        unsigned b1, b2, b3;
+        cut3_bits(p.h0[d][gtid], b1, b2, b3);
+        const size_t part = (size_t)(p.wbytes / 3) / 2;        // bf16 elements of one part of a wavefront's block
+        dst[0] = (unsigned short)b1; dst[part] = (unsigned short)b2; dst[2 * part] = (unsigned short)b3;
+      }
     } else {
       if (p.MT == 1) slot = operand_slot<1>(k, b);
       else if (p.MT == 2) slot = operand_slot<2>(k, b);
@@ -1294,7 +1414,7 @@ constexpr size_t kFlagBytes = (size_t)kFlagCopies * kFlagCopyStride * sizeof(uns
 
 struct Plan {
   bool ok;
-  int ROWS, MT, NT, U, UG, Bp, bf;
+  int ROWS, MT, NT, U, UG, Bp, prec;
   int nb, Bg, NG;                                // groups of sequences per direction, sequences per group, all groups
   int Gf, Hp, nchF;
   int PG, Gb, Hq, nchB;
@@ -1316,7 +1436,6 @@ Plan plan_for(const RecShape& s, int num_cus, size_t max_lds, int nb) {
   Plan pl{};
   pl.ok = false;
   const int bf = s.operand_dtype == 1 ? 1 : 0;
-  const size_t es = bf ? 2 : 4;                  // bytes per element of the resident matrix and the exchanged rows
   const int NG = s.ndir * nb;
   if (NG > kMaxGroups || nb > s.B) return pl;
   const int Bg = (s.B + nb - 1) / nb;
@@ -1335,12 +1454,22 @@ Plan plan_for(const RecShape& s, int num_cus, size_t max_lds, int nb) {
     const int PG = (s.H + UG - 1) / UG;
     const int Gb = 4 * PG;
     if (Gf > per_group || Gb > per_group) continue;
-    const int Hp = (int)align_up((size_t)s.H, bf ? 128 : 64);   // rows of h per wavefront: whole MFMA k-steps
     const int Hq = (int)align_up((size_t)PG * U, 32);
-    // a wavefront polls at most 64 producers
-    if (Hp / 4 / U > 64 || Hq / 4 / U > 64) continue;
     const size_t red = (size_t)4 * MT * NT * 256;
     const size_t ne = (size_t)rows * U;
+    // fp32 operands with two or more 16-row tiles per workgroup: the three-part kernels where their 1.5 x larger
+    // resident matrix fits (at most 4 k-steps per wavefront: 512 units), else the fp32 matrix instructions
+    int prec = bf;
+    int Hp = (int)align_up((size_t)s.H, bf ? 128 : 64);          // rows of h per wavefront: whole MFMA k-steps
+    size_t es = bf ? 2 : 4;                      // bytes per element of the resident matrix and the exchanged rows
+    if (!bf && !s.fp32_instructions && MT >= 2 && s.H <= 512) {
+      const int Hp3 = (int)align_up((size_t)s.H, 128);
+      const size_t lf3 = (size_t)Hp3 * 16 * NT * 6 + (red + (2 * 4 + 2 * 6) * ne) * sizeof(float) + 16;
+      const size_t lb3 = (size_t)4 * Hq * UG * 6 + (red + (2 * 7 + 2 * 4) * ne) * sizeof(float) + 16;
+      if (lf3 <= max_lds && lb3 <= max_lds && Hq % 32 == 0) { prec = 2; Hp = Hp3; es = 6; }
+    }
+    // a wavefront polls at most 64 producers
+    if (Hp / 4 / U > 64 || Hq / 4 / U > 64) continue;
     const size_t lf = (size_t)Hp * 16 * NT * es + (red + (2 * 4 + 2 * 6) * ne) * sizeof(float) + 16;
     const size_t lb = (size_t)4 * Hq * UG * es + (red + (2 * 7 + 2 * 4) * ne) * sizeof(float) + 16;
     if (lf > max_lds || lb > max_lds) continue;
@@ -1348,11 +1477,12 @@ Plan plan_for(const RecShape& s, int num_cus, size_t max_lds, int nb) {
     // stack two of these workgroups on one CU (they would share its matrix cores and every other
     // workgroup would wait for them each step).
     const size_t exclusive = max_lds / 2 + 1024;
-    pl.ok = true; pl.ROWS = rows; pl.MT = MT; pl.NT = NT; pl.U = U; pl.UG = UG; pl.Bp = 16 * MT; pl.bf = bf;
+    pl.ok = true; pl.ROWS = rows; pl.MT = MT; pl.NT = NT; pl.U = U; pl.UG = UG; pl.Bp = 16 * MT; pl.prec = prec;
     pl.nb = nb; pl.Bg = Bg; pl.NG = NG;
     // 16-byte chunks per lane and wavefront: fp32 4 values (4 k-steps x batch tiles / 4), bf16 8 values (1 k-step of 32)
-    pl.Gf = Gf; pl.Hp = Hp; pl.nchF = bf ? (Hp / 4 / 32) * MT : (Hp / 16) * MT / 4;
-    pl.PG = PG; pl.Gb = Gb; pl.Hq = Hq; pl.nchB = bf ? (Hq / 32) * MT : (Hq / 4) * MT / 4;
+    // (three parts: the chunks of all three)
+    pl.Gf = Gf; pl.Hp = Hp; pl.nchF = prec ? (prec == 2 ? 3 : 1) * (Hp / 4 / 32) * MT : (Hp / 16) * MT / 4;
+    pl.PG = PG; pl.Gb = Gb; pl.Hq = Hq; pl.nchB = prec ? (prec == 2 ? 3 : 1) * (Hq / 32) * MT : (Hq / 4) * MT / 4;
     pl.ldsF = lf > exclusive ? lf : exclusive; pl.ldsB = lb > exclusive ? lb : exclusive;
     // One exchange per step in the backward pass: groups of at most 16 sequences (one MFMA row tile), fp32, the
     // forward kernel's deal of the units (Gf <= 64 workgroups), at most 512 units.
@@ -1428,7 +1558,8 @@ GroupBytes group_bytes(const RecShape& s, int nb) {
   const size_t Hp = align_up((size_t)s.H, 128);
   const size_t Hq = align_up((size_t)s.H / 4 + 16, 32);
   GroupBytes g;
-  g.exch = align_up(2 * (Hp > 16 * Hq ? Hp : 16 * Hq) * Bp * sizeof(float), 256);
+  // 4 bytes per exchanged value; 6 where fp32 operands may be exchanged as three bf16 parts
+  g.exch = align_up(2 * (Hp > 16 * Hq ? Hp : 16 * Hq) * Bp * (s.operand_dtype == 0 ? 6 : 4), 256);
   g.part = align_up(2 * 4 * Bp * ((size_t)s.H + 64) * sizeof(unsigned long long), 256);
   g.total = kFlagBytes + g.exch + g.part;
   return g;
@@ -1493,9 +1624,31 @@ bool persistent_plan_info(const RecShape& s, int num_cus, size_t max_lds, int ou
   if (!pl.ok) return false;
   out[0] = pl.NG; out[1] = pl.Bg; out[2] = pl.ROWS; out[3] = pl.U;
   out[4] = pl.Gf; out[5] = pl.onehop ? pl.Gf : pl.Gb; out[6] = pl.Hp; out[7] = pl.onehop ? 64 * pl.TN : pl.Hq;
-  out[8] = pl.onehop ? 1 : 2; out[9] = 0;
+  out[8] = pl.onehop ? 1 : 2; out[9] = pl.prec;
   return true;
 }
+
+namespace {
+// the kernel of a plan's precision; the three-part kernels exist for two and more 16-row tiles only
+template <int ROWS, int NT>
+hipError_t launch_fwd_prec(int prec, int grid, size_t lds, int num_cus, hipStream_t stream, void* kp, int* resident_err) {
+  if (prec == 1) return resident_launch(lstm_fwd_persistent_kernel<ROWS, NT, 1>, grid, kBlockThreads, lds, num_cus, stream, kp, resident_err);
+  if constexpr (ROWS >= 32) {
+    if (prec == 2) return resident_launch(lstm_fwd_persistent_kernel<ROWS, NT, 2>, grid, kBlockThreads, lds, num_cus, stream, kp, resident_err);
+  }
+  if (prec != 0) return hipErrorInvalidValue;
+  return resident_launch(lstm_fwd_persistent_kernel<ROWS, NT, 0>, grid, kBlockThreads, lds, num_cus, stream, kp, resident_err);
+}
+template <int ROWS, int NT>
+hipError_t launch_bwd_prec(int prec, int grid, size_t lds, int num_cus, hipStream_t stream, void* kp, int* resident_err) {
+  if (prec == 1) return resident_launch(lstm_bwd_persistent_kernel<ROWS, NT, 1>, grid, kBlockThreads, lds, num_cus, stream, kp, resident_err);
+  if constexpr (ROWS >= 32) {
+    if (prec == 2) return resident_launch(lstm_bwd_persistent_kernel<ROWS, NT, 2>, grid, kBlockThreads, lds, num_cus, stream, kp, resident_err);
+  }
+  if (prec != 0) return hipErrorInvalidValue;
+  return resident_launch(lstm_bwd_persistent_kernel<ROWS, NT, 0>, grid, kBlockThreads, lds, num_cus, stream, kp, resident_err);
+}
+}  // namespace
 
 size_t persistent_scratch_bytes_fwd(const RecShape& s) {
   return groups_bytes_max(s) + (size_t)s.ndir * (2 * state_bytes(s) + dbpart_bytes(s));
@@ -1530,7 +1683,7 @@ hipError_t persistent_forward(hipStream_t stream, const RecShape& s, const RecFw
     k.direction = dirs[d].direction;
   }
   pp.zero_words = reinterpret_cast<unsigned*>(scratch); pp.nzero = (size_t)pl.NG * gb.total / 4;
-  pp.ndir = s.ndir; pp.B = s.B; pp.Bg = pl.Bg; pp.H = s.H; pp.KW = pl.Hp / 4; pp.wbytes = (int)wbytes; pp.MT = pl.MT; pp.bf = pl.bf;
+  pp.ndir = s.ndir; pp.B = s.B; pp.Bg = pl.Bg; pp.H = s.H; pp.KW = pl.Hp / 4; pp.wbytes = (int)wbytes; pp.MT = pl.MT; pp.prec = pl.prec;
   kp.ndir = s.ndir; kp.NG = pl.NG; kp.Bg = pl.Bg;
   kp.seq_lens = seq_lens; kp.err = err; kp.wait_ticks = g_wait_ticks; kp.mute_wg = g_mute_wg;
   kp.slow_wg = g_slow_wg; kp.slow_ticks = g_slow_ticks;
@@ -1548,11 +1701,7 @@ hipError_t persistent_forward(hipStream_t stream, const RecShape& s, const RecFw
   const int grid = pl.Gf * pl.NG;
 #define RLSTM_FWD_CASE(ROWS_, NT_)                                                                       \
   if (pl.ROWS == ROWS_ && pl.NT == NT_) {                                                                \
-    if (pl.bf)                                                                                           \
-      return resident_launch(lstm_fwd_persistent_kernel<ROWS_, NT_, true>, grid, kBlockThreads, pl.ldsF, \
-                             di.num_cus, stream, &kp, resident_err);                                     \
-    return resident_launch(lstm_fwd_persistent_kernel<ROWS_, NT_, false>, grid, kBlockThreads, pl.ldsF,  \
-                           di.num_cus, stream, &kp, resident_err);                                       \
+    return launch_fwd_prec<ROWS_, NT_>(pl.prec, grid, pl.ldsF, di.num_cus, stream, &kp, resident_err);   \
   }
   RLSTM_FWD_CASE(16, 1) RLSTM_FWD_CASE(32, 1) RLSTM_FWD_CASE(48, 1) RLSTM_FWD_CASE(64, 1)
   RLSTM_FWD_CASE(8, 2) RLSTM_FWD_CASE(16, 2) RLSTM_FWD_CASE(32, 2) RLSTM_FWD_CASE(48, 2) RLSTM_FWD_CASE(64, 2)
@@ -1660,12 +1809,7 @@ hipError_t persistent_backward(hipStream_t stream, const RecShape& s, const RecB
   e = hipErrorInvalidValue;
 #define RLSTM_BWD_CASE(ROWS_, NT_)                                                                       \
   if (pl.ROWS == ROWS_ && pl.NT == NT_) {                                                                \
-    if (pl.bf)                                                                                           \
-      e = resident_launch(lstm_bwd_persistent_kernel<ROWS_, NT_, true>, grid, kBlockThreads, pl.ldsB,    \
-                          di.num_cus, stream, &kp, resident_err);                                        \
-    else                                                                                                 \
-      e = resident_launch(lstm_bwd_persistent_kernel<ROWS_, NT_, false>, grid, kBlockThreads, pl.ldsB,   \
-                          di.num_cus, stream, &kp, resident_err);                                        \
+    e = launch_bwd_prec<ROWS_, NT_>(pl.prec, grid, pl.ldsB, di.num_cus, stream, &kp, resident_err);      \
   }
   RLSTM_BWD_CASE(16, 1) RLSTM_BWD_CASE(32, 1) RLSTM_BWD_CASE(48, 1) RLSTM_BWD_CASE(64, 1)
   RLSTM_BWD_CASE(8, 2) RLSTM_BWD_CASE(16, 2) RLSTM_BWD_CASE(32, 2) RLSTM_BWD_CASE(48, 2) RLSTM_BWD_CASE(64, 2)

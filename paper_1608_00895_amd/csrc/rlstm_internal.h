@@ -86,6 +86,7 @@ struct RecShape {
   // tuning of the persistent engine (0 = chosen per shape)
   int batch_groups = 0;   // groups the sequences are dealt out to per direction
   int bwd_exchange = 0;   // exchanges per step of the backward pass: 1 two (d a_t out, partial tiles back), 2 one where it applies
+  bool fp32_instructions = false;   // fp32 operands: keep to the fp32 matrix instructions (no three-part kernels)
 };
 
 // Scratch bytes the recurrent passes need (max over both engines, fwd and bwd).

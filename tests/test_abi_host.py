@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_version_and_error_strings():
-    assert rl.version() == "0.2"
+    assert rl.version() == "0.3"
     for code in range(0, -7, -1):
         assert "unknown" not in rl.strerror(code)
     assert "unknown" in rl.strerror(-99)

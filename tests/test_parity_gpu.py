@@ -175,6 +175,36 @@ def test_shared_call_where_only_the_fp32_instruction_products_fit_beside_the_rec
         assert np.array_equal(g1, g2)
 
 
+def test_groups_of_more_than_16_sequences_as_three_parts_and_on_the_fp32_instructions():
+    """fp32 operands, 40 sequences = 2 groups of 20 per direction, i.e. two 16-row tiles per workgroup: by default the
+    recurrent kernels exchange h_t / d a_t and keep R as three bf16 parts each (rblstm_plan reports form 2, and the
+    products use the three-part kernel as well); gemm_variant 3 keeps both on the fp32 matrix instructions (form 0).
+    Both against the oracle at the unchanged bars; the default twice, bit for bit; and the two agree with each other
+    more closely than either has to agree with the oracle."""
+    wl = synth.make_workload("two_tiles", L=2, B=40, D=24, H=200, len_lo=30, len_hi=150, wscale=0.08, seed=47)
+    ref = gh.oracle_stack(wl)
+    res = {}
+    for variant in (0, 3):
+        run = gh.StackRun(wl, engine=rl.RLSTM_ENGINE_PERSISTENT, gemm_variant=variant)
+        assert rl.rblstm_plan(run.desc)["recurrent_operand_form"] == (2 if variant == 0 else 0)
+        assert rl.rblstm_plan(run.desc)["rows"] == 32
+        run.step()
+        got = run.results()
+        assert gh.rel_err(got["y"], ref["y"]) < TOL_FWD, variant
+        assert gh.rel_err(got["dx"], ref["dx"]) < TOL_GRAD, variant
+        for g1, g2 in zip(got["grads"], ref["grads"]):
+            assert gh.rel_err(g1, g2) < TOL_GRAD, variant
+        res[variant] = got
+        if variant == 0:
+            run.step()
+            again = run.results()
+            assert np.array_equal(again["y"], got["y"]) and np.array_equal(again["dx"], got["dx"])
+            for g1, g2 in zip(again["grads"], got["grads"]):
+                assert np.array_equal(g1, g2)
+    print("three parts vs fp32 instructions: y", gh.rel_err(res[0]["y"], res[3]["y"]), flush=True)
+    assert gh.rel_err(res[0]["y"], res[3]["y"]) < 2e-6
+
+
 def test_config2_blstm():
     """Config 2: 1-layer BLSTM, D=40, H=256 per direction, B=16, lengths uniform in [100, 500]."""
     wl = synth.config2()
