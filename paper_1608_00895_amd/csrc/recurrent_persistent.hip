@@ -33,6 +33,13 @@
 // There is no device-wide barrier and no cache write-back / invalidate in the
 // step loop.  All waits are bounded: on expiry the kernel raises the timeout
 // flag and every workgroup leaves its loop.
+//
+// Three forms of the recurrent product (template argument PREC of the kernels):
+// 0 fp32 values on the fp32 matrix instructions (as described above); 1 values
+// rounded to bf16 (operand_dtype 1: v_mfma_f32_16x16x32_bf16, R and the
+// exchanged rows at 2 bytes per value); 2 fp32 values as three bf16 parts each
+// (groups of more than 16 sequences: six bf16 instructions per product, see
+// wave_product_3).  Everything outside the product is fp32 in all three.
 #include "rlstm_internal.h"
 
 namespace rlstm {
