@@ -123,7 +123,7 @@ typedef struct rlstm_desc {
  *                 Products of bf16 operands (operand_dtype 1) ignore 3.
  *                 The recurrent kernels follow: with fp32 operands and groups of more than 16 sequences (two or
  *                 more 16-row tiles per workgroup, H <= 512) they exchange h_t / d a_t and keep R as three bf16
- *                 parts each and form the recurrent product the same way; 3 keeps them on the fp32 matrix
+ *                 parts each and form the recurrent product the same way; 1, 2 and 3 keep them on the fp32 matrix
  *                 instructions.  Groups of up to 16 sequences always use those.
  *   first_piece   (stack descriptors) with two streams and the persistent engine each layer's recurrent pass is cut
  *                 into pieces of first_piece, first_piece, 2 first_piece, 4 first_piece, ... steps, and the matrix

@@ -47,7 +47,7 @@ int check_stack_desc(const rblstm_desc* d) {
 // recurrent shape of one layer in one direction
 RecShape layer_rec_shape(const rlstm_desc* d) {
   RecShape s{d->T, d->B, d->H, d->ldy ? d->ldy : d->H, 1, d->operand_dtype};
-  s.batch_groups = d->batch_groups; s.bwd_exchange = d->bwd_exchange; s.fp32_instructions = d->gemm_variant == 3;
+  s.batch_groups = d->batch_groups; s.bwd_exchange = d->bwd_exchange; s.fp32_instructions = d->gemm_variant != 0;
   return s;
 }
 
@@ -203,7 +203,7 @@ size_t stack_mirror_offset(const rblstm_desc* d);
 RecShape stack_rec_shape(const rblstm_desc* d) {
   RecShape s;
   s.T = d->T; s.B = d->B; s.H = d->H; s.ldy = 2 * d->H; s.ndir = 2; s.operand_dtype = d->operand_dtype;
-  s.batch_groups = d->batch_groups; s.bwd_exchange = d->bwd_exchange; s.fp32_instructions = d->gemm_variant == 3;
+  s.batch_groups = d->batch_groups; s.bwd_exchange = d->bwd_exchange; s.fp32_instructions = d->gemm_variant != 0;
   return s;
 }
 
@@ -924,7 +924,7 @@ static int check_stream_desc(const rlstm_stream_desc* d) {
 }
 static RecShape stream_rec_shape(const rlstm_stream_desc* d) {
   RecShape s{d->Tc, d->B, d->H, d->H, 1, d->operand_dtype};
-  s.batch_groups = d->batch_groups; s.bwd_exchange = d->bwd_exchange; s.fp32_instructions = d->gemm_variant == 3;
+  s.batch_groups = d->batch_groups; s.bwd_exchange = d->bwd_exchange; s.fp32_instructions = d->gemm_variant != 0;
   return s;
 }
 struct StreamLayout {
