@@ -16,7 +16,6 @@
 // Split-K (for the weight gradients, whose K = T*B is 32x larger than M or N)
 // writes per-slice partial tiles to scratch and sums them in slice order in a
 // second kernel, so results are bit-reproducible run to run.
-#include <cstdlib>
 #include "rlstm_internal.h"
 
 #include <type_traits>
@@ -1859,7 +1858,17 @@ hipError_t gemm(hipStream_t stream, const GemmCall& g) {
   // K is split when the tiles alone leave CUs idle: always for long sums, and for sums of a few thousand when the
   // tiles do not even fill half the chip
   if (g.splitk_ws && tiles < 512 && (g.K >= 4 * 1024 || (g.K >= 1536 && tiles <= 160))) {
-    slices = (1024 + tiles - 1) / tiles;
+    // Alone: about 1024 work items (two workgroups per CU, two rounds).  Beside the recurrent kernels one workgroup
+    // per CU fits, and every slice more is partial sums written and read through the memory path the recurrent
+    // steps wait on: one work item per CU (the 4 x 500 stack: 52.4 -> 51.8 ms per call, backward steps beside the
+    // weight gradients 7.23 -> 7.10 us; 384 items 52.4 ms, 128 items 55.9 ms).
+    int items = 1024;
+    if (g.small_footprint) {
+      int cus = 0;
+      if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, current_device()) != hipSuccess) { (void)hipGetLastError(); cus = 0; }
+      items = cus > 0 ? cus : 256;
+    }
+    slices = (items + tiles - 1) / tiles;
     const int max_by_k = g.K / 512;
     if (slices > max_by_k) slices = max_by_k;
     const size_t per = (size_t)g.M * g.N;
