@@ -205,6 +205,20 @@ def test_groups_of_more_than_16_sequences_as_three_parts_and_on_the_fp32_instruc
     assert gh.rel_err(res[0]["y"], res[3]["y"]) < 2e-6
 
 
+def test_plan_reports_the_form_of_the_recurrent_product():
+    """rblstm_plan's last field: groups of 16 sequences (the benchmark stack) keep fp32 values on the fp32 matrix
+    instructions (0), groups of 41 (the paper's batch of 81 segments) exchange three bf16 parts (2) unless a gemm_variant
+    asks for the fp32 instructions, bf16 operands are 1; more than 512 units keep the fp32 instructions."""
+    def form(**kw):
+        return rl.rblstm_plan(rl.rblstm_desc(**kw))["recurrent_operand_form"]
+    assert form(L=4, T=1000, B=32, D=40, H=500, operand_dtype=0, engine=0) == 0
+    assert form(L=3, T=250, B=81, D=45, H=512, operand_dtype=0, engine=0) == 2
+    for v in (1, 2, 3):
+        assert form(L=3, T=250, B=81, D=45, H=512, operand_dtype=0, engine=0, gemm_variant=v) == 0
+    assert form(L=3, T=250, B=81, D=45, H=512, operand_dtype=1, engine=0) == 1
+    assert form(L=2, T=100, B=40, D=40, H=640, operand_dtype=0, engine=0) == 0
+
+
 def test_config2_blstm():
     """Config 2: 1-layer BLSTM, D=40, H=256 per direction, B=16, lengths uniform in [100, 500]."""
     wl = synth.config2()
